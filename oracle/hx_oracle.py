@@ -1,0 +1,235 @@
+"""ctypes front of the CPU oracle (``hx_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the
+CPU-baseline leg of the benchmark.  The product path never touches this module.
+
+The wrappers below only marshal numpy arrays; all arithmetic of the method is
+in the C file.  The one piece of logic that lives here is structural: turning
+parent lists into successor lists, so that "incremental append" can be checked
+against its definition (a full recomputation on the grown graph).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hx_oracle.c")
+_LIB = os.path.join(_HERE, "libhx_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C99, -O2, OpenMP over calls)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class _Model(C.Structure):
+    _fields_ = [("kv_bytes_per_token", C.c_double), ("flops_per_token", C.c_double),
+                ("attn_flops_per_token2", C.c_double), ("weight_bytes", C.c_double),
+                ("nominal_batch", C.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.hxo_score_one.restype = C.c_double
+        _lib.hxo_candidate_cost.restype = C.c_double
+        for name in ("hxo_prefill_wait", "hxo_prefill_time", "hxo_transfer_time",
+                     "hxo_decode_step", "hxo_decode_wait", "hxo_decode_token_time"):
+            getattr(_lib, name).restype = C.c_double
+    return _lib
+
+
+def _model(m) -> _Model:
+    return _Model(float(m["kv_bytes_per_token"]), float(m["flops_per_token"]),
+                  float(m["attn_flops_per_token2"]), float(m["weight_bytes"]),
+                  float(m["nominal_batch"]))
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class ScoreResult:
+    best_p: np.ndarray
+    best_d: np.ndarray
+    best_cost: np.ndarray
+    second: np.ndarray
+    cost: np.ndarray | None
+    feas: np.ndarray | None
+
+
+def _tables(pre, dec, links):
+    T = int(links["n_types"])
+    t = dict(
+        pF=_f32(pre["flops"]), pB=_f32(pre["hbm_bw"]), pbl=_i32(pre["backlog_tok"]), pty=_i32(pre["type"]),
+        dF=_f32(dec["flops"]), dB=_f32(dec["hbm_bw"]), dus=_i32(dec["used_tok"]), dcap=_i32(dec["cap_tok"]),
+        dba=_i32(dec["batch"]), dqd=_i32(dec["qd_tok"]), dty=_i32(dec["type"]),
+        bw=_f32(links["bw"]).reshape(-1),
+        lat=None if links.get("latency") is None else _f32(links["latency"]).reshape(-1), T=T)
+    assert t["bw"].size == T * T
+    return t
+
+
+def score(model, L_in, L_out, pre, dec, links, want_cost=False, want_feas=False, nthreads=0) -> ScoreResult:
+    """R7/R8 over all (call, prefill, decode) candidates."""
+    L_in, L_out = _i32(L_in), _i32(L_out)
+    t = _tables(pre, dec, links)
+    Cn, P, D = L_in.size, t["pF"].size, t["dF"].size
+    cost = np.empty((Cn, P, D), np.float64) if want_cost else None
+    feas = np.empty((Cn, D), np.uint8) if want_feas else None
+    bp = np.empty(Cn, np.int32); bd = np.empty(Cn, np.int32)
+    bc = np.empty(Cn, np.float64); sc = np.empty(Cn, np.float64)
+    m = _model(model)
+    rc = lib().hxo_score(C.byref(m), Cn, _p(L_in), _p(L_out),
+                         P, _p(t["pF"]), _p(t["pB"]), _p(t["pbl"]), _p(t["pty"]),
+                         D, _p(t["dF"]), _p(t["dB"]), _p(t["dus"]), _p(t["dcap"]), _p(t["dba"]),
+                         _p(t["dqd"]), _p(t["dty"]), t["T"], _p(t["bw"]), _p(t["lat"]),
+                         _p(cost), _p(feas), _p(bp), _p(bd), _p(bc), _p(sc), int(nthreads))
+    if rc:
+        raise ValueError(f"hxo_score failed: {rc}")
+    return ScoreResult(bp, bd, bc, sc, cost, feas)
+
+
+def score_one(model, L, O, p, d, pre, dec, links) -> float:
+    """R7 for one candidate, by index."""
+    t = _tables(pre, dec, links)
+    m = _model(model)
+    return float(lib().hxo_score_one(C.byref(m), C.c_int32(int(L)), C.c_int32(int(O)),
+                                     C.c_int32(int(p)), _p(t["pF"]), _p(t["pB"]), _p(t["pbl"]), _p(t["pty"]),
+                                     C.c_int32(int(d)), _p(t["dF"]), _p(t["dB"]), _p(t["dus"]), _p(t["dcap"]),
+                                     _p(t["dba"]), _p(t["dqd"]), _p(t["dty"]),
+                                     t["T"], _p(t["bw"]), _p(t["lat"])))
+
+
+def select(cost):
+    """R8 on an existing [C,P,D] fp64 tensor."""
+    cost = _f64(cost)
+    Cn, P, D = cost.shape
+    bp = np.empty(Cn, np.int32); bd = np.empty(Cn, np.int32); bc = np.empty(Cn, np.float64)
+    rc = lib().hxo_select(Cn, P, D, _p(cost), _p(bp), _p(bd), _p(bc))
+    if rc:
+        raise ValueError(f"hxo_select failed: {rc}")
+    return bp, bd, bc
+
+
+def node_cost(model, L_in, L_out, types, links):
+    """R9: standalone cost of each call on its best class pair."""
+    L_in, L_out = _i32(L_in), _i32(L_out)
+    tF, tB = _f32(types["flops"]), _f32(types["hbm_bw"])
+    T = tF.size
+    bw = _f32(links["bw"]).reshape(-1)
+    lat = None if links.get("latency") is None else _f32(links["latency"]).reshape(-1)
+    out = np.empty(L_in.size, np.float64)
+    m = _model(model)
+    rc = lib().hxo_node_cost(C.byref(m), L_in.size, _p(L_in), _p(L_out), T, _p(tF), _p(tB),
+                             _p(bw), _p(lat), _p(out))
+    if rc:
+        raise ValueError(f"hxo_node_cost failed: {rc}")
+    return out
+
+
+def critical_path(row_ptr, col, cost, wf_ptr, round_f32=True):
+    """R10.  Returns (rem, tail, level, horizon); rem/tail/horizon as fp64
+    holders of (when round_f32) exact fp32 values."""
+    row_ptr, col, wf_ptr = _i32(row_ptr), _i32(col), _i32(wf_ptr)
+    cost = _f64(cost)
+    n, n_wf = row_ptr.size - 1, wf_ptr.size - 1
+    rem = np.zeros(n, np.float64); tail = np.zeros(n, np.float64)
+    level = np.zeros(n, np.int32); hor = np.zeros(max(n_wf, 0), np.float64)
+    rc = lib().hxo_critical_path(n, _p(row_ptr), _p(col), _p(cost), n_wf, _p(wf_ptr),
+                                 1 if round_f32 else 0, _p(rem), _p(tail), _p(level), _p(hor))
+    if rc == -2:
+        raise ValueError("not a DAG")
+    if rc:
+        raise ValueError(f"hxo_critical_path failed: {rc}")
+    return rem, tail, level, hor
+
+
+def successors_from_parents(n, parent_row_ptr, parent_col):
+    """Structure only: transpose child->parents lists into a successor CSR
+    (successors of a node in increasing id)."""
+    parent_row_ptr, parent_col = _i32(parent_row_ptr), _i32(parent_col)
+    child = np.repeat(np.arange(n, dtype=np.int32), np.diff(parent_row_ptr))
+    order = np.lexsort((child, parent_col))
+    col = child[order].astype(np.int32)
+    counts = np.bincount(parent_col, minlength=n) if parent_col.size else np.zeros(n, np.int64)
+    row_ptr = np.zeros(n + 1, np.int32)
+    row_ptr[1:] = np.cumsum(counts)
+    return row_ptr, col
+
+
+def critical_path_by_parents(parent_row_ptr, parent_col, cost, wf_of_node, n_wf, round_f32=True):
+    """R10 on a graph given as parent lists with a per-node workflow id: the
+    definition the incremental append must reproduce after every batch."""
+    n = len(cost)
+    row_ptr, col = successors_from_parents(n, parent_row_ptr, parent_col)
+    rem, tail, level, _ = critical_path(row_ptr, col, cost, np.zeros(1, np.int32), round_f32)
+    hor = np.zeros(n_wf, np.float64)
+    wf = _i32(wf_of_node)
+    rc = lib().hxo_horizon_by_id(n, _p(rem), _p(wf), n_wf, _p(hor))
+    if rc:
+        raise ValueError("workflow id out of range")
+    return rem, tail, level, hor
+
+
+def urgency(elapsed, best_cost, node, wf, tail, horizon):
+    """R11 / Eq. (2)."""
+    elapsed, best_cost, tail, horizon = _f64(elapsed), _f64(best_cost), _f64(tail), _f64(horizon)
+    node, wf = _i32(node), _i32(wf)
+    out = np.empty(elapsed.size, np.float64)
+    with np.errstate(all="ignore"):
+        lib().hxo_urgency(elapsed.size, _p(elapsed), _p(best_cost), _p(node), _p(wf),
+                          _p(tail), _p(horizon), _p(out))
+    return out
+
+
+def commit(L_in, L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
+           drain_prefill, drain_decode_q, release_tok, tokens_per_seq=2048, max_batch=256):
+    """R12.  Returns new (backlog_tok, used_tok, batch, qd_tok) and the status."""
+    L_in, L_out, best_p, best_d = _i32(L_in), _i32(L_out), _i32(best_p), _i32(best_d)
+    bl, us, ba, qd = (_i32(x).copy() for x in (backlog_tok, used_tok, batch, qd_tok))
+    dp, dq, rl = _i32(drain_prefill), _i32(drain_decode_q), _i32(release_tok)
+    rc = lib().hxo_commit(L_in.size, _p(L_in), _p(L_out), _p(best_p), _p(best_d),
+                          bl.size, _p(bl), us.size, _p(us), _p(ba), _p(qd),
+                          _p(dp), _p(dq), _p(rl), int(tokens_per_seq), int(max_batch))
+    return bl, us, ba, qd, rc
+
+
+# scalar term accessors, for the round-number pins
+def term(name, model, *args):
+    m = _model(model)
+    f = getattr(lib(), "hxo_" + name)
+    conv = []
+    for a in args:
+        conv.append(C.c_int32(a) if isinstance(a, (int, np.integer)) else C.c_double(float(a)))
+    return float(f(C.byref(m), *conv))
+
+
+def feasible(L, O, used, cap) -> bool:
+    return bool(lib().hxo_feasible(C.c_int32(L), C.c_int32(O), C.c_int32(used), C.c_int32(cap)))
