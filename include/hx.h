@@ -1,0 +1,276 @@
+/*
+ * hx.h -- C ABI of the GPU placement search (AMD MI355X / gfx950).
+ *
+ * The library evaluates, for one scheduling invocation of a workflow- and
+ * heterogeneity-aware scheduler on a prefill-decode disaggregated pool, the
+ * search the paper's Algorithm 1 runs for every waiting call: enumerate every
+ * (prefill instance, decode instance) pair, estimate the time until decode
+ * finishes there, keep the earliest feasible pair, and turn it into the
+ * call's projected ratio against its workflow horizon.
+ *
+ * Conventions for every entry point
+ * ---------------------------------
+ *  - Returns HX_OK (0) or a negative HX_ERR_* code; never throws; a failed
+ *    call has launched nothing.  hx_last_error(ctx) describes the last
+ *    failure of that context.
+ *  - "device" pointers are device memory of the GPU the context was created
+ *    on, owned by the caller, valid until the work enqueued on `stream` has
+ *    finished.  "host" pointers are ordinary host memory read during the
+ *    call.  The structs hx_model / hx_calls / hx_prefill_tab / hx_decode_tab /
+ *    hx_links themselves live in host memory; their pointer members are
+ *    device pointers.  The library never returns memory the caller must free
+ *    (hx_dag_view returns borrowed pointers into the context).
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Work is enqueued
+ *    on it and the call returns without waiting.  Conditions that only the
+ *    GPU can see (an index out of range inside an array, a graph that is not
+ *    a DAG, a sweep limit reached) never fault: the offending element is
+ *    skipped, a sticky status word is set on the device, and
+ *    hx_stream_status() reports it after synchronising the stream.
+ *  - Indices are int32; -1 means "none".  Costs are fp32 seconds, +infinity
+ *    for an infeasible pair.  Rates are FLOP/s and B/s, lengths and
+ *    capacities are tokens.
+ *  - Calls on one context must not overlap in time on different streams: the
+ *    context owns scratch that consecutive calls reuse.
+ */
+#ifndef HX_H
+#define HX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HX_OK               0
+#define HX_ERR_INVALID_ARG (-1)  /* NULL where a pointer is required, negative size, bad flag      */
+#define HX_ERR_SHAPE       (-2)  /* a size beyond HX_MAX_TYPES / HX_MAX_INSTANCES / int32 indexing */
+#define HX_ERR_NOT_DAG     (-3)  /* successor not later than its node / no fixed point in time      */
+#define HX_ERR_CAPACITY    (-4)  /* reserved store, scratch or sweep limit exceeded                 */
+#define HX_ERR_DEVICE      (-5)  /* a HIP call failed; hx_last_error has its text                   */
+#define HX_ERR_INDEX       (-6)  /* an index held in a device array is out of range                 */
+#define HX_ERR_OVERFLOW    (-7)  /* an int32 instance counter would exceed INT32_MAX                */
+
+#define HX_MAX_TYPES      8      /* GPU classes in a pool                      */
+#define HX_MAX_INSTANCES  1024   /* prefill instances, and decode instances    */
+
+typedef struct hx_ctx hx_ctx;
+
+/* Model descriptor of the estimator (Sec. 4.2 "Scheduler internals": a
+ * roofline-style model over per-call input and output length). */
+typedef struct {
+    float kv_bytes_per_token;      /* kappa: KV-cache bytes one token occupies           */
+    float flops_per_token;         /* phi:   FLOP per token, linear part                 */
+    float attn_flops_per_token2;   /* a:     FLOP per token^2, attention part of prefill */
+    float weight_bytes;            /* omega: bytes read per forward pass                 */
+    float nominal_batch;           /* Bbar:  decode-queue tokens retired per decode step */
+} hx_model;
+
+/* Ready calls, structure of arrays, n entries each (Sec. 7.1: a call is
+ * annotated with input length, output length and workflow identity). */
+typedef struct {
+    int32_t n;
+    const int32_t *L_in;      /* device [n] prompt tokens, >= 0                        */
+    const int32_t *L_out;     /* device [n] predicted output tokens, >= 0              */
+    const int32_t *node;      /* device [n] DAG node of the call; NULL if no ratio     */
+    const int32_t *wf;        /* device [n] workflow of the call;  NULL if no ratio    */
+    const float   *elapsed;   /* device [n] t - a_w of Eq. (2);    NULL if no ratio    */
+} hx_calls;
+
+/* Prefill pool snapshot: single-server instances with a queue (Sec. 4.2
+ * "Heterogeneous resource modelling"). */
+typedef struct {
+    int32_t n;                    /* P, 0..HX_MAX_INSTANCES                            */
+    const float   *flops;         /* device [n] FLOP/s, > 0                            */
+    const float   *hbm_bw;        /* device [n] B/s, > 0                               */
+    const int32_t *backlog_tok;   /* device [n] prompt tokens queued ahead, >= 0       */
+    const int32_t *type;          /* device [n] GPU class, 0..n_types-1                */
+} hx_prefill_tab;
+
+/* Decode pool snapshot: batched decoding under a KV-capacity limit. */
+typedef struct {
+    int32_t n;                    /* D, 0..HX_MAX_INSTANCES                            */
+    const float   *flops;         /* device [n] FLOP/s, > 0                            */
+    const float   *hbm_bw;        /* device [n] B/s, > 0                               */
+    const int32_t *used_tok;      /* device [n] KV tokens resident, >= 0               */
+    const int32_t *cap_tok;       /* device [n] KV capacity in tokens, Cap(d) of Eq. (4) */
+    const int32_t *batch;         /* device [n] sequences in the running batch, >= 0   */
+    const int32_t *qd_tok;        /* device [n] output tokens queued for decode, >= 0  */
+    const int32_t *type;          /* device [n] GPU class, 0..n_types-1                */
+} hx_decode_tab;
+
+/* Effective KV-transfer bandwidth between GPU classes (Sec. 4.2): row =
+ * class of the prefill side, column = class of the decode side. */
+typedef struct {
+    int32_t n_types;              /* T, 1..HX_MAX_TYPES                                */
+    const float *bw;              /* device [T*T] B/s, > 0                             */
+    const float *latency;         /* device [T*T] seconds added per transfer, or NULL  */
+} hx_links;
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Creates a context on HIP device `device` (allocates a few KB of scratch and
+ * a pinned status word).  *out is NULL on failure. */
+int hx_ctx_create(hx_ctx **out, int device);
+
+/* Frees everything the context owns.  The caller has synchronised its streams. */
+int hx_ctx_destroy(hx_ctx *ctx);
+
+/* Text of the last error of this context (static storage, never NULL). */
+const char *hx_last_error(const hx_ctx *ctx);
+
+/* Synchronises `stream`, returns the sticky device status (HX_OK or the first
+ * HX_ERR_* a kernel raised since the last call) and clears it. */
+int hx_stream_status(hx_ctx *ctx, void *stream);
+
+/* ---- (1) critical path: CSR DAGs + per-node cost -> remaining latency ---- */
+
+/*
+ * Standalone cost of each call: its prefill, KV transfer and decode time on
+ * an idle pool, on the best pair of GPU classes.  This is the per-node term
+ * of the workflow horizon H_w(t) of Sec. 5.1 ("served in isolation using the
+ * same serving cluster").
+ *   n, L_in, L_out      device [n] lengths of the nodes
+ *   n_types, type_flops, type_hbm_bw   device [n_types] per-class rates
+ *   links               class-pair bandwidth (same n_types)
+ *   cost                device [n] out, seconds
+ */
+int hx_node_cost(hx_ctx *ctx, const hx_model *model, int32_t n,
+                 const int32_t *L_in, const int32_t *L_out,
+                 int32_t n_types, const float *type_flops, const float *type_hbm_bw,
+                 const hx_links *links, float *cost, void *stream);
+
+/*
+ * Longest remaining path of every node (max-plus pass from the sinks up) and
+ * the horizon of every workflow (Sec. 5.1; Algorithm 1 "update affected
+ * workflow horizons"):
+ *   tail[v]  = max(0, max over successors u of rem[u])
+ *   rem[v]   = node_cost[v] + tail[v]          (one fp32 addition)
+ *   level[v] = 0 without successors, else 1 + max level[u]
+ *   horizon[w] = max rem[v] over the nodes of w
+ * Inputs (device): successor lists in CSR form, succ_row_ptr [n_nodes+1]
+ * non-decreasing with succ_row_ptr[0] = 0 and succ_row_ptr[n_nodes] =
+ * n_edges, succ_col_idx [n_edges]; node_cost [n_nodes] >= 0; wf_ptr [n_wf+1]:
+ * workflow w owns the contiguous nodes wf_ptr[w] .. wf_ptr[w+1]-1.
+ * Outputs (device): rem, tail [n_nodes] fp32; level [n_nodes]; horizon [n_wf].
+ *
+ * max_sweeps == 0: single pass.  Requires what online reveal gives by
+ *   construction: every successor has a larger id than its node and belongs
+ *   to the same workflow.  An edge that breaks this is skipped and raises
+ *   HX_ERR_NOT_DAG in the stream status.
+ * max_sweeps  > 0: level-synchronous relaxation for any numbering; successors
+ *   may be anywhere.  Sweeps until nothing changes, at most max_sweeps times
+ *   (a DAG of depth L needs L+2); still changing then -> HX_ERR_NOT_DAG in the
+ *   stream status (a cycle, or the limit was too small).
+ * Both give bit-identical results on inputs both accept.
+ */
+int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
+                     const int32_t *succ_row_ptr, const int32_t *succ_col_idx,
+                     const float *node_cost, int32_t n_wf, const int32_t *wf_ptr,
+                     int32_t max_sweeps,
+                     float *rem, float *tail, int32_t *level, float *horizon, void *stream);
+
+/*
+ * Incremental form for DAGs revealed at run time (Sec. 4.1 "online reveal";
+ * Sec. 5.1 "recomputes it whenever new calls are revealed").  The graph lives
+ * in the context.  hx_dag_reserve sizes it (allocates; not for the hot loop)
+ * and empties it; max_depth bounds the longest path in edges and with it the
+ * number of propagation sweeps one append runs.
+ */
+int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges, int32_t max_wf,
+                   int32_t max_depth, void *stream);
+
+/*
+ * Appends n_new nodes with ids n_old .. n_old+n_new-1.  New nodes have no
+ * successors yet (rem = cost, level 0); tail, level and rem of their
+ * ancestors and the horizons of their workflows are raised to what a full
+ * recomputation on the grown graph gives, bit for bit.
+ *   parent_row_ptr device [n_new+1], parent_row_ptr[0] = 0,
+ *                  parent_row_ptr[n_new] = n_new_edges
+ *   parent_col_idx device [n_new_edges] parents of each new node; a parent id
+ *                  must be smaller than the child's id (else the edge is
+ *                  skipped and HX_ERR_NOT_DAG raised in the stream status)
+ *   new_cost       device [n_new] >= 0
+ *   new_wf         device [n_new] workflow ids, 0 .. max_wf-1
+ * HX_ERR_CAPACITY if the reserved store would overflow.
+ */
+int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
+                  const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                  const float *new_cost, const int32_t *new_wf, void *stream);
+
+/* Borrowed device pointers into the context's graph (valid until the next
+ * hx_dag_reserve or hx_ctx_destroy) and the number of nodes appended so far.
+ * Any out pointer may be NULL. */
+int hx_dag_view(hx_ctx *ctx, const float **rem, const float **tail, const int32_t **level,
+                const float **horizon, int32_t *n_nodes);
+
+/* ---- (2) scoring: calls x prefill x decode -> cost tensor or best pair ---- */
+
+/*
+ * Evaluates the latency model for every candidate (c, p, d) (Sec. 5.3:
+ * "enumerates candidate prefill instances and candidate decode instances,
+ * estimates the prefill finish time, adds transfer latency, and projects the
+ * earliest decode finish"; feasibility per Sec. 5.4 Eq. (3),(4) against the
+ * KV capacity still free on d):
+ *   cost(c,p,d) = max(wait_p + prefill(c,p) + transfer(c,p,d), avail_d)
+ *                 + L_out * token_time(c,d)      if used_d + L_in + L_out <= cap_d
+ *               = +infinity                      otherwise
+ * Fused outputs (no tensor is written): best_p, best_d [C] = the pair of
+ * minimum cost, ties to the lowest p*D + d, (-1,-1) when no pair is feasible;
+ * best_cost [C]; ratio [C] = (elapsed + best_cost + tail[node]) / horizon[wf]
+ * (Eq. (2) with the downstream tail of the call's node; needs tail [n_nodes],
+ * horizon [n_wf] and the node/wf/elapsed members of `calls`; a node or
+ * workflow index outside those lengths gives NaN and raises HX_ERR_INDEX in
+ * the stream status).  best_p, best_d, best_cost are
+ * all NULL or all non-NULL; ratio may be NULL on its own.
+ * Materialised outputs, each may be NULL: cost [C*P*D] row-major (c,p,d) --
+ * bit-identical to what the fused search compares; feas [C*D] 1/0.
+ * At least one output must be requested.  P or D of 0 gives (-1,-1,+inf).
+ */
+int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                        const hx_prefill_tab *prefill, const hx_decode_tab *decode,
+                        const hx_links *links,
+                        const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                        float *cost, uint8_t *feas,
+                        int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                        void *stream);
+
+/* ---- (3) select: per-call argmin over a materialised tensor --------------- */
+
+/*
+ * best pair of each call from cost [C*P*D] (device, row-major (c,p,d), values
+ * >= 0 or +infinity): minimum cost, ties to the lowest flat index p*D + d
+ * (Sec. 5.3 "the prefill-decode pair with the earliest projected decode
+ * finish").  Outputs as in hx_score_placements; `calls`, tail, horizon and
+ * ratio may all be NULL when no ratio is wanted.
+ */
+int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const float *cost,
+              const hx_calls *calls, const float *tail, const float *horizon,
+              int32_t n_nodes, int32_t n_wf,
+              int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio, void *stream);
+
+/* ---- (4) commit the chosen placements into the snapshots ------------------ */
+
+/*
+ * Algorithm 1 "update simulated state", applied once for the whole round:
+ * every call with best_p >= 0 adds L_in to backlog_tok[best_p], L_out to
+ * qd_tok[best_d] and L_in + L_out to used_tok[best_d]; then each instance
+ * drains: backlog = max(0, backlog - drain_prefill), qd = max(0, qd -
+ * drain_decode_q), used = max(0, used - release_tok), batch =
+ * min(max_batch, ceil(used / tokens_per_seq)).  Integer arithmetic; the
+ * result does not depend on the order of the calls.  backlog_tok [P],
+ * used_tok, batch, qd_tok [D] are device arrays updated in place; the drain
+ * arrays are device inputs or NULL (= 0).  A total above INT32_MAX saturates
+ * and raises HX_ERR_OVERFLOW in the stream status; a placement index outside
+ * the pool is skipped and raises HX_ERR_INDEX.
+ */
+int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
+              int32_t P, int32_t *backlog_tok,
+              int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
+              const int32_t *drain_prefill, const int32_t *drain_decode_q,
+              const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
+              void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HX_H */

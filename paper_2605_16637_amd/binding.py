@@ -1,0 +1,252 @@
+"""Thin ctypes binding of ``libhx.so`` with the names of ``include/hx.h``.
+
+Argument marshalling only: every step of the search runs in the library's HIP
+kernels.  PyTorch is used for device memory and streams.  There is no CPU
+fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhx.so")
+
+HX_OK = 0
+ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4: "HX_ERR_CAPACITY",
+          -5: "HX_ERR_DEVICE", -6: "HX_ERR_INDEX", -7: "HX_ERR_OVERFLOW"}
+
+EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
+           "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_view",
+           "hx_score_placements", "hx_select", "hx_commit")
+
+
+class HxError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"{ERRORS.get(code, code)}: {text}")
+        self.code = code
+
+
+class hx_model(C.Structure):
+    _fields_ = [("kv_bytes_per_token", C.c_float), ("flops_per_token", C.c_float),
+                ("attn_flops_per_token2", C.c_float), ("weight_bytes", C.c_float),
+                ("nominal_batch", C.c_float)]
+
+
+class hx_calls(C.Structure):
+    _fields_ = [("n", C.c_int32), ("L_in", C.c_void_p), ("L_out", C.c_void_p), ("node", C.c_void_p),
+                ("wf", C.c_void_p), ("elapsed", C.c_void_p)]
+
+
+class hx_prefill_tab(C.Structure):
+    _fields_ = [("n", C.c_int32), ("flops", C.c_void_p), ("hbm_bw", C.c_void_p),
+                ("backlog_tok", C.c_void_p), ("type", C.c_void_p)]
+
+
+class hx_decode_tab(C.Structure):
+    _fields_ = [("n", C.c_int32), ("flops", C.c_void_p), ("hbm_bw", C.c_void_p), ("used_tok", C.c_void_p),
+                ("cap_tok", C.c_void_p), ("batch", C.c_void_p), ("qd_tok", C.c_void_p), ("type", C.c_void_p)]
+
+
+class hx_links(C.Structure):
+    _fields_ = [("n_types", C.c_int32), ("bw", C.c_void_p), ("latency", C.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads the library (built in-tree by ``build.py``); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2605_16637_amd.build` "
+                              "(or __graft_entry__.build()) first")
+        lib = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(lib, name).restype = C.c_int
+        lib.hx_last_error.restype = C.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("the placement search needs a GPU: no HIP device is visible")
+    return torch
+
+
+def _ptr(t, dtype=None, n=None):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL), after checks."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor in device memory")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    if n is not None and t.numel() < n:
+        raise ValueError(f"tensor has {t.numel()} elements, {n} needed")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def make_model(m: dict) -> hx_model:
+    return hx_model(m["kv_bytes_per_token"], m["flops_per_token"], m["attn_flops_per_token2"],
+                    m["weight_bytes"], m["nominal_batch"])
+
+
+def make_calls(c: dict) -> hx_calls:
+    torch = _torch()
+    n = int(c["n"])
+    return hx_calls(n, _ptr(c["L_in"], torch.int32, n), _ptr(c["L_out"], torch.int32, n),
+                    _ptr(c.get("node"), torch.int32, n), _ptr(c.get("wf"), torch.int32, n),
+                    _ptr(c.get("elapsed"), torch.float32, n))
+
+
+def make_prefill(p: dict) -> hx_prefill_tab:
+    torch = _torch()
+    n = int(p["n"])
+    return hx_prefill_tab(n, _ptr(p["flops"], torch.float32, n), _ptr(p["hbm_bw"], torch.float32, n),
+                          _ptr(p["backlog_tok"], torch.int32, n), _ptr(p["type"], torch.int32, n))
+
+
+def make_decode(d: dict) -> hx_decode_tab:
+    torch = _torch()
+    n = int(d["n"])
+    i32 = torch.int32
+    return hx_decode_tab(n, _ptr(d["flops"], torch.float32, n), _ptr(d["hbm_bw"], torch.float32, n),
+                         _ptr(d["used_tok"], i32, n), _ptr(d["cap_tok"], i32, n), _ptr(d["batch"], i32, n),
+                         _ptr(d["qd_tok"], i32, n), _ptr(d["type"], i32, n))
+
+
+def make_links(l: dict) -> hx_links:
+    torch = _torch()
+    T = int(l["n_types"])
+    return hx_links(T, _ptr(l["bw"], torch.float32, T * T), _ptr(l.get("latency"), torch.float32, T * T))
+
+
+class Context:
+    """Owns one ``hx_ctx``.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, device: int = 0):
+        _torch()
+        self.lib = load()
+        self._ctx = C.c_void_p()
+        rc = self.lib.hx_ctx_create(C.byref(self._ctx), int(device))
+        if rc != HX_OK:
+            raise HxError(rc, "hx_ctx_create failed")
+        self.device = device
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self.lib.hx_ctx_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != HX_OK:
+            raise HxError(rc, self.lib.hx_last_error(self._ctx).decode())
+
+    def hx_stream_status(self, stream=None):
+        self._check(self.lib.hx_stream_status(self._ctx, _stream(stream)))
+
+    def hx_node_cost(self, model, L_in, L_out, type_flops, type_hbm_bw, links, cost, stream=None):
+        torch = _torch()
+        n, T = int(L_in.numel()), int(type_flops.numel())
+        m, lk = make_model(model), make_links(links)
+        self._check(self.lib.hx_node_cost(self._ctx, C.byref(m), n, _ptr(L_in, torch.int32), _ptr(L_out, torch.int32, n),
+                                          T, _ptr(type_flops, torch.float32), _ptr(type_hbm_bw, torch.float32, T),
+                                          C.byref(lk), _ptr(cost, torch.float32, n), _stream(stream)))
+
+    def hx_critical_path(self, succ_row_ptr, succ_col_idx, node_cost, wf_ptr, rem, tail, level, horizon,
+                         max_sweeps=0, stream=None):
+        torch = _torch()
+        n, n_wf, n_edges = int(succ_row_ptr.numel()) - 1, int(wf_ptr.numel()) - 1, int(succ_col_idx.numel())
+        self._check(self.lib.hx_critical_path(
+            self._ctx, n, n_edges, _ptr(succ_row_ptr, torch.int32), _ptr(succ_col_idx, torch.int32),
+            _ptr(node_cost, torch.float32, n), n_wf, _ptr(wf_ptr, torch.int32), int(max_sweeps),
+            _ptr(rem, torch.float32, n), _ptr(tail, torch.float32, n), _ptr(level, torch.int32, n),
+            _ptr(horizon, torch.float32, n_wf), _stream(stream)))
+
+    def hx_dag_reserve(self, max_nodes, max_edges, max_wf, max_depth, stream=None):
+        self._check(self.lib.hx_dag_reserve(self._ctx, int(max_nodes), int(max_edges), int(max_wf),
+                                            int(max_depth), _stream(stream)))
+
+    def hx_dag_append(self, parent_row_ptr, parent_col_idx, new_cost, new_wf, stream=None):
+        torch = _torch()
+        n_new, n_e = int(new_cost.numel()), int(parent_col_idx.numel())
+        self._check(self.lib.hx_dag_append(self._ctx, n_new, n_e, _ptr(parent_row_ptr, torch.int32, n_new + 1),
+                                           _ptr(parent_col_idx, torch.int32), _ptr(new_cost, torch.float32),
+                                           _ptr(new_wf, torch.int32, n_new), _stream(stream)))
+
+    def hx_dag_view(self):
+        """Raw device addresses (rem, tail, level, horizon) and the node count."""
+        rem, tail, level, hor = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
+        n = C.c_int32()
+        self._check(self.lib.hx_dag_view(self._ctx, C.byref(rem), C.byref(tail), C.byref(level),
+                                         C.byref(hor), C.byref(n)))
+        return rem.value, tail.value, level.value, hor.value, n.value
+
+    def hx_score_placements(self, model, calls, prefill, decode, links, tail=None, horizon=None,
+                            cost=None, feas=None, best_p=None, best_d=None, best_cost=None, ratio=None,
+                            stream=None):
+        torch = _torch()
+        m, cs, pt, dt, lk = make_model(model), make_calls(calls), make_prefill(prefill), make_decode(decode), make_links(links)
+        Cn, P, D = cs.n, pt.n, dt.n
+        n_nodes = 0 if tail is None else int(tail.numel())
+        n_wf = 0 if horizon is None else int(horizon.numel())
+        self._check(self.lib.hx_score_placements(
+            self._ctx, C.byref(m), C.byref(cs), C.byref(pt), C.byref(dt), C.byref(lk),
+            _ptr(tail, torch.float32), _ptr(horizon, torch.float32), n_nodes, n_wf,
+            _ptr(cost, torch.float32, Cn * P * D), _ptr(feas, torch.uint8, Cn * D),
+            _ptr(best_p, torch.int32, Cn), _ptr(best_d, torch.int32, Cn), _ptr(best_cost, torch.float32, Cn),
+            _ptr(ratio, torch.float32, Cn), _stream(stream)))
+
+    def hx_select(self, C_, P, D, cost, best_p, best_d, best_cost, calls=None, tail=None, horizon=None,
+                  ratio=None, stream=None):
+        torch = _torch()
+        cs = make_calls(calls) if calls is not None else None
+        n_nodes = 0 if tail is None else int(tail.numel())
+        n_wf = 0 if horizon is None else int(horizon.numel())
+        self._check(self.lib.hx_select(
+            self._ctx, int(C_), int(P), int(D), _ptr(cost, torch.float32, C_ * P * D),
+            C.byref(cs) if cs is not None else None, _ptr(tail, torch.float32), _ptr(horizon, torch.float32),
+            n_nodes, n_wf, _ptr(best_p, torch.int32, C_), _ptr(best_d, torch.int32, C_),
+            _ptr(best_cost, torch.float32, C_), _ptr(ratio, torch.float32, C_), _stream(stream)))
+
+    def hx_commit(self, calls, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
+                  drain_prefill=None, drain_decode_q=None, release_tok=None,
+                  tokens_per_seq=2048, max_batch=256, stream=None):
+        torch = _torch()
+        cs = make_calls(calls)
+        P, D = int(backlog_tok.numel()), int(used_tok.numel())
+        i32 = torch.int32
+        self._check(self.lib.hx_commit(
+            self._ctx, C.byref(cs), _ptr(best_p, i32, cs.n), _ptr(best_d, i32, cs.n),
+            P, _ptr(backlog_tok, i32), D, _ptr(used_tok, i32), _ptr(batch, i32, D), _ptr(qd_tok, i32, D),
+            _ptr(drain_prefill, i32, P), _ptr(drain_decode_q, i32, D), _ptr(release_tok, i32, D),
+            int(tokens_per_seq), int(max_batch), _stream(stream)))
+
+
+def to_device(d: dict, device="cuda:0") -> dict:
+    """numpy tables of ``synth`` -> torch tensors in device memory (scalars and None pass through)."""
+    import numpy as np
+    torch = _torch()
+    out = {}
+    for k, v in d.items():
+        if isinstance(v, np.ndarray):
+            out[k] = torch.from_numpy(np.ascontiguousarray(v)).to(device)
+        else:
+            out[k] = v
+    return out

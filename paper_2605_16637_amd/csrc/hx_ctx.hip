@@ -1,0 +1,170 @@
+// Context life cycle, stream status and the commit-and-drain step.
+#include "hx_common.hpp"
+
+void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
+
+namespace {
+
+__global__ void hx_clear_status_kernel(int32_t *status) { *status = 0; }
+
+struct CommitArgs {
+    int C, P, D;
+    const int32_t *L_in, *L_out, *best_p, *best_d;
+    int32_t *backlog, *used, *batch, *qd;
+    const int32_t *drain_p, *drain_q, *release;
+    int tokens_per_seq, max_batch;
+    unsigned long long *acc;    // [P] backlog, [D] used, [D] qd additions of this round
+    int32_t *status;
+};
+
+__global__ __launch_bounds__(256) void hx_commit_clear_kernel(CommitArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.P + 2 * a.D) a.acc[i] = 0ull;
+}
+
+// Algorithm 1 "update simulated state" for all calls of the round at once:
+// integer additions commute, so the result does not depend on call order.
+__global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
+{
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < a.C; c += gridDim.x * blockDim.x) {
+        const int p = a.best_p[c], d = a.best_d[c];
+        if (p < 0 || d < 0) continue;                       // the call stays queued
+        if (p >= a.P || d >= a.D) { hx_raise(a.status, HX_ERR_INDEX); continue; }
+        const int L = a.L_in[c], O = a.L_out[c];
+        if (L < 0 || O < 0) { hx_raise(a.status, HX_ERR_INDEX); continue; }
+        atomicAdd(&a.acc[p], (unsigned long long)L);
+        atomicAdd(&a.acc[a.P + d], (unsigned long long)L + (unsigned long long)O);
+        atomicAdd(&a.acc[a.P + a.D + d], (unsigned long long)O);
+    }
+}
+
+__device__ __forceinline__ int hx_add_sat_drain(int cur, unsigned long long add, int drain, int32_t *status)
+{
+    unsigned long long total = (unsigned long long)(cur < 0 ? 0 : cur) + add;
+    if (total > 2147483647ull) { hx_raise(status, HX_ERR_OVERFLOW); total = 2147483647ull; }
+    long long left = (long long)total - (long long)drain;
+    return left < 0 ? 0 : (left > 2147483647LL ? 2147483647 : (int)left);
+}
+
+__global__ __launch_bounds__(256) void hx_commit_drain_kernel(CommitArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.P)
+        a.backlog[i] = hx_add_sat_drain(a.backlog[i], a.acc[i], a.drain_p ? a.drain_p[i] : 0, a.status);
+    if (i < a.D) {
+        a.qd[i] = hx_add_sat_drain(a.qd[i], a.acc[a.P + a.D + i], a.drain_q ? a.drain_q[i] : 0, a.status);
+        const int used = hx_add_sat_drain(a.used[i], a.acc[a.P + i], a.release ? a.release[i] : 0, a.status);
+        a.used[i] = used;
+        long long b = ((long long)used + a.tokens_per_seq - 1) / a.tokens_per_seq;
+        a.batch[i] = (int)(b > a.max_batch ? a.max_batch : b);
+    }
+}
+
+}  // namespace
+
+extern "C" int hx_ctx_create(hx_ctx **out, int device)
+{
+    if (!out) return HX_ERR_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return HX_ERR_DEVICE;
+    HxDeviceGuard guard(device);
+    if (!guard.ok) return HX_ERR_DEVICE;
+    hx_ctx *ctx = new (std::nothrow) hx_ctx();
+    if (!ctx) return HX_ERR_DEVICE;
+    ctx->device = device;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->num_cu = prop.multiProcessorCount;
+    bool ok = hipMalloc((void **)&ctx->d_status, sizeof(int32_t)) == hipSuccess &&
+              hipHostMalloc((void **)&ctx->h_status, sizeof(int32_t), hipHostMallocDefault) == hipSuccess &&
+              hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)) == hipSuccess &&
+              hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)) == hipSuccess &&
+              hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)) == hipSuccess;
+    if (ok) {
+        hx_clear_status_kernel<<<1, 1, 0, nullptr>>>(ctx->d_status);
+        ok = hipGetLastError() == hipSuccess && hipStreamSynchronize(nullptr) == hipSuccess;
+    }
+    if (!ok) {
+        hx_ctx_destroy(ctx);
+        return HX_ERR_DEVICE;
+    }
+    *out = ctx;
+    return HX_OK;
+}
+
+extern "C" int hx_ctx_destroy(hx_ctx *ctx)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HxDeviceGuard guard(ctx->device);
+    hx_dag_release(ctx);
+    if (ctx->d_status) (void)hipFree(ctx->d_status);
+    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    if (ctx->d_prep) (void)hipFree(ctx->d_prep);
+    if (ctx->d_flags) (void)hipFree(ctx->d_flags);
+    if (ctx->d_acc) (void)hipFree(ctx->d_acc);
+    delete ctx;
+    return HX_OK;
+}
+
+extern "C" const char *hx_last_error(const hx_ctx *ctx)
+{
+    return ctx ? ctx->err : "NULL context";
+}
+
+extern "C" int hx_stream_status(hx_ctx *ctx, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    HX_HIP(ctx, hipMemcpyAsync(ctx->h_status, ctx->d_status, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    hx_clear_status_kernel<<<1, 1, 0, stream>>>(ctx->d_status);
+    HX_HIP(ctx, hipStreamSynchronize(stream));
+    const int code = *ctx->h_status;
+    if (code != HX_OK) {
+        const char *what = code == HX_ERR_NOT_DAG ? "an edge breaks the DAG order, or no fixed point within the sweep limit"
+                         : code == HX_ERR_INDEX ? "an index held in a device array is out of range"
+                         : code == HX_ERR_OVERFLOW ? "an instance counter exceeded INT32_MAX"
+                         : code == HX_ERR_CAPACITY ? "propagation did not finish within max_depth sweeps"
+                                                   : "device status";
+        return hx_fail(ctx, code, "%s", what);
+    }
+    return HX_OK;
+}
+
+extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
+                         int32_t P, int32_t *backlog_tok,
+                         int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
+                         const int32_t *drain_prefill, const int32_t *drain_decode_q,
+                         const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
+                         void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, calls, HX_ERR_INVALID_ARG, "NULL calls");
+    const int C = calls->n;
+    HX_REQUIRE(ctx, C >= 0 && P >= 0 && D >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, P <= HX_MAX_INSTANCES && D <= HX_MAX_INSTANCES, HX_ERR_SHAPE,
+               "pool %d x %d beyond %d instances per side", P, D, HX_MAX_INSTANCES);
+    HX_REQUIRE(ctx, tokens_per_seq > 0 && max_batch >= 0, HX_ERR_INVALID_ARG, "tokens_per_seq must be positive");
+    HX_REQUIRE(ctx, C == 0 || (calls->L_in && calls->L_out && best_p && best_d), HX_ERR_INVALID_ARG, "NULL call array");
+    HX_REQUIRE(ctx, P == 0 || backlog_tok, HX_ERR_INVALID_ARG, "NULL backlog_tok");
+    HX_REQUIRE(ctx, D == 0 || (used_tok && batch && qd_tok), HX_ERR_INVALID_ARG, "NULL decode array");
+    if (P + D == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    CommitArgs a{C, P, D, calls->L_in, calls->L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
+                 drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, ctx->d_acc, ctx->d_status};
+    const int n_acc = P + 2 * D;
+    hx_commit_clear_kernel<<<(n_acc + 255) / 256, 256, 0, stream>>>(a);
+    if (C > 0) {
+        int grid = (C + 255) / 256;
+        grid = grid > ctx->num_cu * 4 ? ctx->num_cu * 4 : grid;
+        hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a);
+    }
+    const int n_inst = P > D ? P : D;
+    hx_commit_drain_kernel<<<(n_inst + 255) / 256, 256, 0, stream>>>(a);
+    return hx_check_launch(ctx, "hx_commit kernels");
+}

@@ -1,0 +1,509 @@
+// Workflow horizons: standalone node cost, the max-plus critical-path pass
+// (single-pass workflow-local form and level-synchronous general form) and the
+// incremental append for DAGs revealed at run time.
+//
+// What is computed: Sec. 5.1 of the paper.  H_w(t) is the completion time of
+// the revealed sub-DAG of workflow w served in isolation; it is recomputed when
+// calls are revealed and can only grow.  Here that is the longest
+// cost-weighted path, with rem[v] = cost[v] + max over successors of rem.
+//
+// rem is one fp32 addition of an exact maximum, so every evaluation order --
+// the single pass, the sweeps, the incremental propagation -- gives the same
+// bits.
+#include "hx_common.hpp"
+#include "hx_terms.hpp"
+
+#include <cmath>
+
+namespace {
+
+constexpr int kT = HX_MAX_TYPES;
+
+// ---- standalone node cost -----------------------------------------------------
+
+struct NodeCostArgs {
+    HxModelF m;
+    int n, T;
+    const int32_t *L_in, *L_out;
+    const float *tF, *tB, *bw, *lat;
+    float *cost;
+};
+
+// cost[v] = min over class pairs of prefill + transfer + decode on an idle pool
+__global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
+{
+    __shared__ float s_invF[kT], s_invB[kT], s_c1[kT], s_kB[kT], s_c2[kT];
+    __shared__ float s_invbw[kT * kT], s_lat[kT * kT];
+    const int tid = threadIdx.x;
+    if (tid < a.T) {
+        float invF = 1.0f / a.tF[tid], invB = 1.0f / a.tB[tid];
+        HxDecF d = hx_decode_terms(a.m, 0, 0, 0, invF, invB);
+        s_invF[tid] = invF; s_invB[tid] = invB; s_c1[tid] = d.c1; s_c2[tid] = d.c2; s_kB[tid] = d.kB;
+    }
+    if (tid < a.T * a.T) {
+        s_invbw[tid] = 1.0f / a.bw[tid];
+        s_lat[tid] = a.lat ? a.lat[tid] : 0.0f;
+    }
+    __syncthreads();
+    for (int v = blockIdx.x * blockDim.x + tid; v < a.n; v += gridDim.x * blockDim.x) {
+        const HxCallF cf = hx_call_terms(a.m, a.L_in[v], a.L_out[v]);
+        float dec[kT];
+        for (int td = 0; td < a.T; ++td) dec[td] = hx_decode_time(cf, s_c1[td], s_c2[td], s_kB[td]);
+        float best = INFINITY;
+        for (int tp = 0; tp < a.T; ++tp) {
+            float done = hx_prefill_done(cf, 0.0f, s_invF[tp], s_invB[tp]);
+            for (int td = 0; td < a.T; ++td) {
+                float x = hx_transfer(cf, s_invbw[tp * a.T + td], s_lat[tp * a.T + td]);
+                best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
+            }
+        }
+        a.cost[v] = best;
+    }
+}
+
+// ---- critical path, single pass ---------------------------------------------------
+
+struct CpArgs {
+    int n_nodes, n_edges, n_wf;
+    const int32_t *row_ptr, *col, *wf_ptr;
+    const float *cost;
+    float *rem, *tail, *horizon;
+    int32_t *level;
+    int32_t *status;
+};
+
+constexpr int CP_THREADS = 128;      // workflows per block, one thread each
+constexpr int CP_NMAX = 4096;        // nodes staged per block
+constexpr int CP_EMAX = 8192;        // edges staged per block
+
+// One block takes CP_THREADS consecutive workflows.  Their node and edge
+// ranges are contiguous, so the CSR slice is staged into LDS with coalesced
+// loads (row offsets and successors as 16-bit offsets relative to the slice),
+// each thread walks one workflow from its last node to its first, and the
+// results leave through coalesced stores.  A slice too large for LDS is
+// walked in global memory by the same threads.
+__global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
+{
+    __shared__ float s_rem[CP_NMAX];          // holds cost, then rem
+    __shared__ float s_tail[CP_NMAX];
+    __shared__ uint16_t s_level[CP_NMAX];
+    __shared__ uint16_t s_row[CP_NMAX + 2];
+    __shared__ uint16_t s_col[CP_EMAX];
+    __shared__ int s_bad;
+
+    const int tid = threadIdx.x;
+    const int w0 = blockIdx.x * CP_THREADS;
+    const int w1 = min(w0 + CP_THREADS, a.n_wf);
+    int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
+    const int w = w0 + tid;
+    int ws = 0, we = 0;
+    if (w < w1) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
+    if (tid == 0) s_bad = 0;
+    // malformed ranges: clamp so that nothing is read out of bounds, and report
+    bool bad = n0 < 0 || n1 > a.n_nodes || n0 > n1 || ws < n0 || we > n1 || ws > we;
+    if (bad) { n0 = n1 = ws = we = 0; }
+    __syncthreads();
+    if (bad) s_bad = 1;
+    __syncthreads();
+    if (s_bad) {
+        if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
+        if (w < w1) a.horizon[w] = 0.0f;
+        return;
+    }
+    const int nn = n1 - n0;
+    int e0 = 0, e1 = 0;
+    if (nn > 0) { e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1]; }
+    if (e0 < 0 || e1 > a.n_edges || e0 > e1) {
+        if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
+        if (w < w1) a.horizon[w] = 0.0f;
+        return;
+    }
+    const int ne = e1 - e0;
+    float hmax = 0.0f;
+    bool not_dag = false;
+
+    if (nn <= CP_NMAX && ne <= CP_EMAX) {
+        for (int i = tid; i < nn; i += CP_THREADS) s_rem[i] = a.cost[n0 + i];
+        for (int i = tid; i <= nn; i += CP_THREADS) {
+            int r = a.row_ptr[n0 + i] - e0;
+            s_row[i] = (uint16_t)min(max(r, 0), ne);     // a non-monotone row_ptr cannot leave the slice
+        }
+        for (int i = tid; i < ne; i += CP_THREADS) {
+            int u = a.col[e0 + i] - n0;
+            s_col[i] = (u >= 0 && u < nn) ? (uint16_t)u : (uint16_t)0xffff;   // 0xffff: outside the slice
+        }
+        __syncthreads();
+        for (int v = we - 1 - n0; v >= ws - n0; --v) {
+            int r0 = s_row[v], r1 = s_row[v + 1];
+            float tl = 0.0f;
+            int lv = 0;
+            for (int e = r0; e < r1; ++e) {
+                int u = s_col[e];
+                if (u <= v || u >= we - n0) { not_dag = true; continue; }   // not a later node of this workflow
+                tl = fmaxf(tl, s_rem[u]);
+                lv = max(lv, (int)s_level[u] + 1);
+            }
+            float r = s_rem[v] + tl;
+            s_rem[v] = r; s_tail[v] = tl; s_level[v] = (uint16_t)lv;
+            hmax = fmaxf(hmax, r);
+        }
+        __syncthreads();
+        for (int i = tid; i < nn; i += CP_THREADS) {
+            a.rem[n0 + i] = s_rem[i];
+            a.tail[n0 + i] = s_tail[i];
+            a.level[n0 + i] = s_level[i];
+        }
+    } else {
+        for (int v = we - 1; v >= ws; --v) {
+            int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
+            r0 = min(max(r0, e0), e1); r1 = min(max(r1, r0), e1);
+            float tl = 0.0f;
+            int lv = 0;
+            for (int e = r0; e < r1; ++e) {
+                int u = a.col[e];
+                if (u <= v || u >= we) { not_dag = true; continue; }
+                tl = fmaxf(tl, a.rem[u]);          // written earlier by this same thread
+                lv = max(lv, a.level[u] + 1);
+            }
+            float r = a.cost[v] + tl;
+            a.rem[v] = r; a.tail[v] = tl; a.level[v] = lv;
+            hmax = fmaxf(hmax, r);
+        }
+    }
+    if (w < w1) a.horizon[w] = hmax;
+    if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
+}
+
+// ---- critical path, level-synchronous sweeps ------------------------------------------
+
+__global__ __launch_bounds__(256) void hx_cp_init_kernel(CpArgs a, int32_t *flags, int n_flags)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.n_nodes) { a.rem[i] = a.cost[i]; a.tail[i] = 0.0f; a.level[i] = 0; }
+    if (i < n_flags) flags[i] = (i == 0) ? 1 : 0;      // flags[s] != 0: sweep s changed something
+}
+
+// Sweep s: every node pulls from its successors.  Values only grow towards the
+// fixed point; a sweep in which nothing changed has read only final values.
+// Runs only if the previous sweep changed something.
+__global__ __launch_bounds__(256) void hx_cp_sweep_kernel(CpArgs a, int32_t *flags, int s)
+{
+    if (__hip_atomic_load(&flags[s - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
+    bool changed = false, bad = false;
+    for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < a.n_nodes; v += gridDim.x * blockDim.x) {
+        int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
+        if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad = true; continue; }
+        float tl = 0.0f;
+        int lv = 0;
+        for (int e = r0; e < r1; ++e) {
+            int u = a.col[e];
+            if (u < 0 || u >= a.n_nodes) { bad = true; continue; }
+            tl = fmaxf(tl, __hip_atomic_load(&a.rem[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            lv = max(lv, __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1);
+        }
+        // a level beyond the node count can only come from a cycle: stop growing
+        lv = min(lv, a.n_nodes);
+        if (tl != a.tail[v] || lv != a.level[v]) {
+            changed = true;
+            a.tail[v] = tl;
+            __hip_atomic_store(&a.level[v], lv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.rem[v], a.cost[v] + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if (changed) flags[s] = 1;
+    if (bad) hx_raise(a.status, HX_ERR_INDEX);
+}
+
+__global__ __launch_bounds__(256) void hx_cp_finish_kernel(CpArgs a, const int32_t *flags, int last)
+{
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w == 0 && flags[last] != 0) hx_raise(a.status, HX_ERR_NOT_DAG);
+    if (w >= a.n_wf) return;
+    int s = a.wf_ptr[w], e = a.wf_ptr[w + 1];
+    if (s < 0 || e > a.n_nodes || s > e) { hx_raise(a.status, HX_ERR_INDEX); a.horizon[w] = 0.0f; return; }
+    float h = 0.0f;
+    for (int v = s; v < e; ++v) h = fmaxf(h, a.rem[v]);
+    a.horizon[w] = h;
+}
+
+// ---- incremental append ------------------------------------------------------------------
+
+struct AppendArgs {
+    int n_old, n_new, e_old, n_new_edges, cap_wf;
+    const int32_t *new_row_ptr, *new_col, *new_wf;
+    const float *new_cost;
+    float *cost, *rem, *tail, *horizon;
+    int32_t *level, *wf, *prow, *pcol, *mark;
+    int32_t *list_in, *list_out;
+    int32_t *counters;      // [0..2] rotating list sizes
+    int cin, cout, czero;   // which counter is read, appended to, cleared
+    uint32_t epoch;
+    int32_t *status;
+};
+
+// non-negative fp32 values order like their bit patterns
+__device__ __forceinline__ bool hx_raise_max_f32(float *addr, float v)
+{
+    unsigned old = atomicMax((unsigned *)addr, __float_as_uint(v));
+    return __float_as_uint(v) > old;
+}
+
+// push the (new) rem and level of node v to its parent u; enqueue u if it grew
+__device__ __forceinline__ void hx_push_parent(const AppendArgs &a, int u, float rem_v, int level_v)
+{
+    bool grew = hx_raise_max_f32(&a.tail[u], rem_v);
+    int old = atomicMax(&a.level[u], level_v + 1);
+    grew = grew || (level_v + 1 > old);
+    if (grew && (uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch) {
+        int slot = atomicAdd(&a.counters[a.cout], 1);
+        a.list_out[slot] = u;        // at most one entry per node and sweep: never beyond cap_nodes
+    }
+}
+
+__global__ void hx_append_reset_kernel(int32_t *counters)
+{
+    if (threadIdx.x < 3) counters[threadIdx.x] = 0;
+}
+
+__global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.counters[a.czero] = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.n_new; i += gridDim.x * blockDim.x) {
+        const int v = a.n_old + i;
+        float c = a.new_cost[i];
+        int w = a.new_wf[i];
+        int r0 = a.new_row_ptr[i], r1 = a.new_row_ptr[i + 1];
+        if (r0 < 0 || r1 > a.n_new_edges || r0 > r1) { hx_raise(a.status, HX_ERR_INDEX); r0 = r1 = min(max(r0, 0), a.n_new_edges); }
+        a.cost[v] = c; a.rem[v] = c; a.tail[v] = 0.0f; a.level[v] = 0; a.mark[v] = 0;
+        a.prow[v + 1] = a.e_old + r1;
+        if (w < 0 || w >= a.cap_wf) { hx_raise(a.status, HX_ERR_INDEX); w = -1; }
+        a.wf[v] = w;
+        if (w >= 0) hx_raise_max_f32(&a.horizon[w], c);
+        for (int e = r0; e < r1; ++e) {
+            int u = a.new_col[e];
+            if (u < 0 || u >= v) { hx_raise(a.status, HX_ERR_NOT_DAG); u = -1; }
+            a.pcol[a.e_old + e] = u;
+        }
+    }
+}
+
+// second phase of an append: parents of the new nodes (a kernel boundary after
+// init, so that a new node whose parent is also new sees that parent initialised)
+__global__ __launch_bounds__(256) void hx_append_push_new_kernel(AppendArgs a)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.n_new; i += gridDim.x * blockDim.x) {
+        const int v = a.n_old + i;
+        const float c = a.cost[v];
+        for (int e = a.prow[v]; e < a.prow[v + 1]; ++e) {
+            int u = a.pcol[e];
+            if (u >= 0) hx_push_parent(a, u, c, 0);
+        }
+    }
+}
+
+// one propagation sweep: nodes whose tail or level grew recompute rem, raise
+// their workflow horizon and push to their own parents
+__global__ __launch_bounds__(256) void hx_append_sweep_kernel(AppendArgs a)
+{
+    const int n = __hip_atomic_load(&a.counters[a.cin], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.counters[a.czero] = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const int u = a.list_in[i];
+        const float tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float r = a.cost[u] + tl;
+        a.rem[u] = r;
+        const int w = a.wf[u];
+        if (w >= 0) hx_raise_max_f32(&a.horizon[w], r);
+        for (int e = a.prow[u]; e < a.prow[u + 1]; ++e) {
+            int q = a.pcol[e];
+            if (q >= 0) hx_push_parent(a, q, r, lv);
+        }
+    }
+}
+
+__global__ void hx_append_finish_kernel(AppendArgs a)
+{
+    if (threadIdx.x == 0 && a.counters[a.cin] != 0) hx_raise(a.status, HX_ERR_CAPACITY);
+}
+
+__global__ __launch_bounds__(256) void hx_fill_i32_kernel(int32_t *p, size_t n, int32_t v)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+template <typename T>
+int dev_alloc(hx_ctx *ctx, T **p, size_t n)
+{
+    *p = nullptr;
+    HX_HIP(ctx, hipMalloc((void **)p, (n ? n : 1) * sizeof(T)));
+    return HX_OK;
+}
+
+void dag_free(HxDagStore &g)
+{
+    void *ptrs[] = {g.cost, g.rem, g.tail, g.horizon, g.level, g.wf, g.parent_row_ptr, g.parent_col,
+                    g.mark, g.list[0], g.list[1], g.counters};
+    for (void *p : ptrs) if (p) (void)hipFree(p);
+    g = HxDagStore{};
+}
+
+}  // namespace
+
+void hx_dag_release(hx_ctx *ctx) { dag_free(ctx->dag); }
+
+extern "C" int hx_node_cost(hx_ctx *ctx, const hx_model *model, int32_t n,
+                            const int32_t *L_in, const int32_t *L_out,
+                            int32_t n_types, const float *type_flops, const float *type_hbm_bw,
+                            const hx_links *links, float *cost, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, model && links && links->bw && type_flops && type_hbm_bw, HX_ERR_INVALID_ARG, "NULL table");
+    HX_REQUIRE(ctx, n >= 0, HX_ERR_INVALID_ARG, "negative n");
+    HX_REQUIRE(ctx, n_types >= 1 && n_types <= HX_MAX_TYPES && links->n_types == n_types, HX_ERR_SHAPE,
+               "n_types %d (links %d) outside 1..%d", n_types, links->n_types, HX_MAX_TYPES);
+    HX_REQUIRE(ctx, n == 0 || (L_in && L_out && cost), HX_ERR_INVALID_ARG, "NULL array");
+    if (n == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    NodeCostArgs a{};
+    a.m = HxModelF{model->kv_bytes_per_token, model->flops_per_token, model->attn_flops_per_token2,
+                   model->weight_bytes, model->nominal_batch};
+    a.n = n; a.T = n_types; a.L_in = L_in; a.L_out = L_out; a.tF = type_flops; a.tB = type_hbm_bw;
+    a.bw = links->bw; a.lat = links->latency; a.cost = cost;
+    int grid = (n + 255) / 256;
+    grid = grid > ctx->num_cu * 8 ? ctx->num_cu * 8 : grid;
+    hx_node_cost_kernel<<<grid, 256, 0, (hipStream_t)stream_>>>(a);
+    return hx_check_launch(ctx, "hx_node_cost_kernel");
+}
+
+extern "C" int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
+                                const int32_t *succ_row_ptr, const int32_t *succ_col_idx,
+                                const float *node_cost, int32_t n_wf, const int32_t *wf_ptr,
+                                int32_t max_sweeps,
+                                float *rem, float *tail, int32_t *level, float *horizon, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, n_nodes >= 0 && n_edges >= 0 && n_wf >= 0 && max_sweeps >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, max_sweeps < HX_MAX_SWEEP_FLAGS, HX_ERR_SHAPE, "max_sweeps beyond %d", HX_MAX_SWEEP_FLAGS - 1);
+    HX_REQUIRE(ctx, succ_row_ptr && wf_ptr, HX_ERR_INVALID_ARG, "NULL row_ptr or wf_ptr");
+    HX_REQUIRE(ctx, n_edges == 0 || succ_col_idx, HX_ERR_INVALID_ARG, "NULL col_idx");
+    HX_REQUIRE(ctx, n_nodes == 0 || (node_cost && rem && tail && level), HX_ERR_INVALID_ARG, "NULL node array");
+    HX_REQUIRE(ctx, n_wf == 0 || horizon, HX_ERR_INVALID_ARG, "NULL horizon");
+    if (n_wf == 0 && (n_nodes == 0 || max_sweeps == 0)) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    CpArgs a{n_nodes, n_edges, n_wf, succ_row_ptr, succ_col_idx, wf_ptr, node_cost, rem, tail, horizon, level,
+             ctx->d_status};
+    if (max_sweeps == 0) {
+        const int grid = (n_wf + CP_THREADS - 1) / CP_THREADS;
+        hx_cp_local_kernel<<<grid, CP_THREADS, 0, stream>>>(a);
+        return hx_check_launch(ctx, "hx_cp_local_kernel");
+    }
+    const int nmax = n_nodes > max_sweeps + 1 ? n_nodes : max_sweeps + 1;
+    hx_cp_init_kernel<<<(nmax + 255) / 256, 256, 0, stream>>>(a, ctx->d_flags, max_sweeps + 1);
+    if (int rc = hx_check_launch(ctx, "hx_cp_init_kernel")) return rc;
+    int grid = (n_nodes + 255) / 256;
+    grid = grid > ctx->num_cu * 8 ? ctx->num_cu * 8 : (grid < 1 ? 1 : grid);
+    for (int s = 1; s <= max_sweeps; ++s) {
+        hx_cp_sweep_kernel<<<grid, 256, 0, stream>>>(a, ctx->d_flags, s);
+        if (int rc = hx_check_launch(ctx, "hx_cp_sweep_kernel")) return rc;
+    }
+    hx_cp_finish_kernel<<<(n_wf + 255) / 256 + 1, 256, 0, stream>>>(a, ctx->d_flags, max_sweeps);
+    return hx_check_launch(ctx, "hx_cp_finish_kernel");
+}
+
+extern "C" int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges, int32_t max_wf,
+                              int32_t max_depth, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, max_nodes >= 0 && max_edges >= 0 && max_wf >= 0 && max_depth >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, max_depth <= 4096, HX_ERR_SHAPE, "max_depth beyond 4096");
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    HX_HIP(ctx, hipStreamSynchronize(stream));
+    HxDagStore &g = ctx->dag;
+    dag_free(g);
+    int rc = HX_OK;
+    const size_t N = (size_t)max_nodes, E = (size_t)max_edges, W = (size_t)max_wf;
+    if ((rc = dev_alloc(ctx, &g.cost, N)) || (rc = dev_alloc(ctx, &g.rem, N)) || (rc = dev_alloc(ctx, &g.tail, N)) ||
+        (rc = dev_alloc(ctx, &g.horizon, W)) || (rc = dev_alloc(ctx, &g.level, N)) || (rc = dev_alloc(ctx, &g.wf, N)) ||
+        (rc = dev_alloc(ctx, &g.parent_row_ptr, N + 1)) || (rc = dev_alloc(ctx, &g.parent_col, E)) ||
+        (rc = dev_alloc(ctx, &g.mark, N)) || (rc = dev_alloc(ctx, &g.list[0], N)) ||
+        (rc = dev_alloc(ctx, &g.list[1], N)) || (rc = dev_alloc(ctx, &g.counters, (size_t)4))) {
+        dag_free(g);
+        return rc;
+    }
+    g.cap_nodes = max_nodes; g.cap_edges = max_edges; g.cap_wf = max_wf; g.max_depth = max_depth;
+    g.n_nodes = 0; g.n_edges = 0; g.epoch = 0;
+    // horizon of every workflow starts at 0; parent_row_ptr[0] = 0 (fill kernels, no memset nodes)
+    hx_fill_i32_kernel<<<256, 256, 0, stream>>>((int32_t *)g.horizon, W, 0);
+    hx_fill_i32_kernel<<<1, 64, 0, stream>>>(g.parent_row_ptr, 1, 0);
+    hx_fill_i32_kernel<<<1, 64, 0, stream>>>(g.counters, 4, 0);
+    return hx_check_launch(ctx, "hx_fill_i32_kernel");
+}
+
+extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
+                             const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                             const float *new_cost, const int32_t *new_wf, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HxDagStore &g = ctx->dag;
+    HX_REQUIRE(ctx, g.cost, HX_ERR_INVALID_ARG, "hx_dag_reserve has not been called");
+    HX_REQUIRE(ctx, n_new >= 0 && n_new_edges >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, n_new == 0 || (parent_row_ptr && new_cost && new_wf), HX_ERR_INVALID_ARG, "NULL array");
+    HX_REQUIRE(ctx, n_new_edges == 0 || parent_col_idx, HX_ERR_INVALID_ARG, "NULL parent_col_idx");
+    HX_REQUIRE(ctx, (long long)g.n_nodes + n_new <= g.cap_nodes, HX_ERR_CAPACITY,
+               "%d + %d nodes beyond the reserved %d", g.n_nodes, n_new, g.cap_nodes);
+    HX_REQUIRE(ctx, (long long)g.n_edges + n_new_edges <= g.cap_edges, HX_ERR_CAPACITY,
+               "%d + %d edges beyond the reserved %d", g.n_edges, n_new_edges, g.cap_edges);
+    if (n_new == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+
+    AppendArgs a{};
+    a.n_old = g.n_nodes; a.n_new = n_new; a.e_old = g.n_edges; a.n_new_edges = n_new_edges; a.cap_wf = g.cap_wf;
+    a.new_row_ptr = parent_row_ptr; a.new_col = parent_col_idx; a.new_wf = new_wf; a.new_cost = new_cost;
+    a.cost = g.cost; a.rem = g.rem; a.tail = g.tail; a.horizon = g.horizon;
+    a.level = g.level; a.wf = g.wf; a.prow = g.parent_row_ptr; a.pcol = g.parent_col; a.mark = g.mark;
+    a.counters = g.counters; a.status = ctx->d_status;
+
+    int grid = (n_new + 255) / 256;
+    grid = grid > ctx->num_cu * 8 ? ctx->num_cu * 8 : grid;
+    hx_append_reset_kernel<<<1, 64, 0, stream>>>(g.counters);
+    a.cin = 0; a.cout = 1; a.czero = 2; a.epoch = ++g.epoch;
+    a.list_in = g.list[1]; a.list_out = g.list[0];
+    hx_append_init_kernel<<<grid, 256, 0, stream>>>(a);
+    hx_append_push_new_kernel<<<grid, 256, 0, stream>>>(a);
+    // sweep k reads the list sweep k-1 wrote; max_depth sweeps reach every ancestor
+    const int sweep_grid = ctx->num_cu * 2;
+    for (int s = 0; s < g.max_depth; ++s) {
+        a.cin = (s + 1) % 3; a.cout = (s + 2) % 3; a.czero = s % 3;
+        a.list_in = g.list[s & 1]; a.list_out = g.list[(s + 1) & 1];
+        a.epoch = ++g.epoch;
+        hx_append_sweep_kernel<<<sweep_grid, 256, 0, stream>>>(a);
+    }
+    a.cin = (g.max_depth + 1) % 3;
+    hx_append_finish_kernel<<<1, 64, 0, stream>>>(a);
+    if (int rc = hx_check_launch(ctx, "hx_dag_append kernels")) return rc;
+    g.n_nodes += n_new;
+    g.n_edges += n_new_edges;
+    return HX_OK;
+}
+
+extern "C" int hx_dag_view(hx_ctx *ctx, const float **rem, const float **tail, const int32_t **level,
+                           const float **horizon, int32_t *n_nodes)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HxDagStore &g = ctx->dag;
+    HX_REQUIRE(ctx, g.cost, HX_ERR_INVALID_ARG, "hx_dag_reserve has not been called");
+    if (rem) *rem = g.rem;
+    if (tail) *tail = g.tail;
+    if (level) *level = g.level;
+    if (horizon) *horizon = g.horizon;
+    if (n_nodes) *n_nodes = g.n_nodes;
+    return HX_OK;
+}

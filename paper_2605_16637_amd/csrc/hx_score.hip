@@ -1,0 +1,521 @@
+// Scoring of placement candidates: prepare (per-round tables), fused search
+// (score + per-call argmin, no tensor written), materialised tensor, select.
+//
+// What is computed: Sec. 5.3 of the paper (enumerate prefill x decode
+// instances, prefill finish + transfer, earliest decode finish, keep the
+// earliest pair), feasibility per Sec. 5.4 Eq. (3),(4), projected ratio per
+// Sec. 5.1 Eq. (2).  How it is laid out is specific to gfx950:
+//
+//  * One wavefront owns one call at a time.  Lanes are prefill instances
+//    (KP per lane), so everything that depends on the decode instance only --
+//    its availability hint and the call's decode time there -- is the same
+//    for all 64 lanes and is read from LDS as a broadcast.
+//  * Transfer time depends on the two GPU classes only, so a lane keeps
+//    ready[class] = prefill finish + transfer for the <= 8 decode classes in
+//    registers, and decode instances are visited grouped by class: inside a
+//    class segment the inner loop is  t = max(ready, avail_d) + dec_d ;
+//    best = min(best, t)  with no index bookkeeping.
+//  * The index is recovered afterwards: the wave minimum fixes the winning
+//    prefill instance (lowest p among lanes that hold the minimum), and one
+//    pass of the wave over that instance's D candidates finds the lowest d
+//    that reproduces the minimum bit for bit.  This gives exactly the
+//    lexicographic minimum of (cost, p*D + d).
+#include "hx_common.hpp"
+#include "hx_terms.hpp"
+
+#include <cfloat>
+#include <cmath>
+
+namespace {
+
+constexpr int kT = HX_MAX_TYPES;
+
+// ---- prepare ------------------------------------------------------------------
+
+struct PrepArgs {
+    HxModelF m;
+    int P, D, T;
+    const float *p_flops, *p_hbm;
+    const int32_t *p_backlog, *p_type;
+    const float *d_flops, *d_hbm;
+    const int32_t *d_used, *d_cap, *d_batch, *d_qd, *d_type;
+    const float *bw, *lat;
+    HxPrepTables *out;
+    int32_t *status;
+};
+
+__global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
+{
+    __shared__ int s_type[HX_MAX_INSTANCES];
+    __shared__ int s_cnt[kT], s_seg[kT + 1];
+    const int tid = threadIdx.x;
+    HxPrepTables *o = a.out;
+
+    if (tid < kT * kT) {
+        int tp = tid / kT, td = tid % kT;
+        bool in = tp < a.T && td < a.T;
+        o->link_invbw[tid] = in ? 1.0f / a.bw[tp * a.T + td] : 0.0f;
+        o->link_lat[tid] = (in && a.lat) ? a.lat[tp * a.T + td] : 0.0f;
+    }
+    for (int p = tid; p < a.P; p += blockDim.x) {
+        int t = a.p_type[p];
+        if (t < 0 || t >= a.T) { hx_raise(a.status, HX_ERR_INDEX); t = 0; }
+        float invF = 1.0f / a.p_flops[p];
+        o->pre_invF[p] = invF;
+        o->pre_invB[p] = 1.0f / a.p_hbm[p];
+        o->pre_wait[p] = hx_prefill_wait(a.m, a.p_backlog[p], invF);
+        o->pre_type[p] = t;
+    }
+    for (int d = tid; d < a.D; d += blockDim.x) {
+        int t = a.d_type[d];
+        if (t < 0 || t >= a.T) { hx_raise(a.status, HX_ERR_INDEX); t = 0; }
+        s_type[d] = t;
+    }
+    __syncthreads();
+    if (tid < kT) {
+        int n = 0;
+        for (int d = 0; d < a.D; ++d) n += (s_type[d] == tid);
+        s_cnt[tid] = n;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int e = 0;
+        for (int t = 0; t < kT; ++t) {
+            s_seg[t] = e;
+            e += (s_cnt[t] + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP;
+        }
+        s_seg[kT] = e;
+        for (int t = 0; t <= kT; ++t) o->seg[t] = s_seg[t];
+        o->n_entries = e;
+    }
+    __syncthreads();
+    const int n_entries = s_seg[kT];
+    // pads first, real entries overwrite them below (disjoint indices)
+    for (int e = tid; e < n_entries; e += blockDim.x) {
+        int t = 0;
+        while (t + 1 < kT && e >= s_seg[t + 1]) ++t;
+        if (e >= s_seg[t] + s_cnt[t]) {
+            o->dec_wait[e] = 0.0f; o->dec_c1[e] = 0.0f; o->dec_c2[e] = 0.0f; o->dec_kB[e] = 0.0f;
+            o->dec_free[e] = -1; o->dec_orig[e] = -1; o->dec_type[e] = t;
+        }
+    }
+    for (int d = tid; d < a.D; d += blockDim.x) {
+        int t = s_type[d];
+        int rank = 0;
+        for (int q = 0; q < d; ++q) rank += (s_type[q] == t);
+        int e = s_seg[t] + rank;
+        HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], a.d_qd[d],
+                                   1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
+        o->dec_wait[e] = x.wait; o->dec_c1[e] = x.c1; o->dec_c2[e] = x.c2; o->dec_kB[e] = x.kB;
+        long long fr = (long long)a.d_cap[d] - (long long)a.d_used[d];
+        o->dec_free[e] = fr < -1 ? -1 : (fr > 2147483647LL ? 2147483647 : (int)fr);
+        o->dec_orig[e] = d; o->dec_type[e] = t; o->dec_pos[d] = e;
+    }
+}
+
+// ---- common argument block of the scoring kernels ------------------------------
+
+struct ScoreArgs {
+    HxModelF m;
+    int C, P, D;
+    const int32_t *L_in, *L_out, *node, *wf;
+    const float *elapsed, *tail, *horizon;
+    int n_nodes, n_wf;
+    const HxPrepTables *prep;
+    int32_t *best_p, *best_d;
+    float *best_cost, *ratio;
+    float *cost;          // materialised tensor or NULL
+    uint8_t *feas;        // materialised mask or NULL
+    int32_t *status;
+};
+
+// projected ratio, Eq. (2), with the downstream tail of the call's node
+__device__ __forceinline__ float hx_ratio(const ScoreArgs &a, int c, float best)
+{
+    int nd = a.node[c], w = a.wf[c];
+    if (nd < 0 || nd >= a.n_nodes || w < 0 || w >= a.n_wf) {
+        hx_raise(a.status, HX_ERR_INDEX);
+        return __uint_as_float(0x7fc00000u);   // quiet NaN
+    }
+    return ((a.elapsed[c] + best) + a.tail[nd]) / a.horizon[w];
+}
+
+// ---- fused search ----------------------------------------------------------------
+
+// LDS carve-up shared by host (size) and device (offsets)
+struct FusedLds {
+    int Dp, Pp;
+    __host__ __device__ FusedLds(int n_entries_bound, int P)
+        : Dp(n_entries_bound), Pp((P + HX_WAVE - 1) / HX_WAVE * HX_WAVE) {}
+    __host__ __device__ size_t block_floats() const { return (size_t)7 * Dp + (size_t)4 * Pp + 2 * kT * kT + 16; }
+    __host__ __device__ size_t wave_floats() const { return (size_t)2 * Dp + kT * kT; }
+    __host__ __device__ size_t bytes(int waves) const { return 4 * (block_floats() + waves * wave_floats()); }
+};
+
+template <int KP>
+__global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, int dp_bound)
+{
+    extern __shared__ __align__(16) float smem[];
+    const HxPrepTables *__restrict__ t = a.prep;
+    const int Dp = t->n_entries;           // <= dp_bound by construction
+    const FusedLds lay(dp_bound, a.P);
+    float *s_wait = smem;                  // 7 decode arrays of dp_bound entries
+    float *s_c1 = s_wait + lay.Dp;
+    float *s_c2 = s_c1 + lay.Dp;
+    float *s_kB = s_c2 + lay.Dp;
+    int *s_free = (int *)(s_kB + lay.Dp);
+    int *s_orig = s_free + lay.Dp;
+    int *s_dtype = s_orig + lay.Dp;
+    float *s_pw = (float *)(s_dtype + lay.Dp);   // 4 prefill arrays of Pp entries
+    float *s_pinvF = s_pw + lay.Pp;
+    float *s_pinvB = s_pinvF + lay.Pp;
+    int *s_ptype = (int *)(s_pinvB + lay.Pp);
+    float *s_invbw = (float *)(s_ptype + lay.Pp);
+    float *s_lat = s_invbw + kT * kT;
+    int *s_seg = (int *)(s_lat + kT * kT);       // kT+1 used, 16 reserved
+    float *s_wave = (float *)(s_seg + 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (HX_WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int waves_per_block = blockDim.x >> 6;
+    float2 *wbuf = (float2 *)(s_wave + (size_t)wave * lay.wave_floats());   // (avail, decode time) per entry
+    float *xbuf = (float *)(wbuf + lay.Dp);                                  // transfer per class pair
+
+    for (int e = tid; e < Dp; e += blockDim.x) {
+        s_wait[e] = t->dec_wait[e]; s_c1[e] = t->dec_c1[e]; s_c2[e] = t->dec_c2[e]; s_kB[e] = t->dec_kB[e];
+        s_free[e] = t->dec_free[e]; s_orig[e] = t->dec_orig[e]; s_dtype[e] = t->dec_type[e];
+    }
+    for (int p = tid; p < lay.Pp; p += blockDim.x) {
+        bool in = p < a.P;
+        s_pw[p] = in ? t->pre_wait[p] : INFINITY;     // lanes beyond P never win
+        s_pinvF[p] = in ? t->pre_invF[p] : 0.0f;
+        s_pinvB[p] = in ? t->pre_invB[p] : 0.0f;
+        s_ptype[p] = in ? t->pre_type[p] : 0;
+    }
+    if (tid < kT * kT) { s_invbw[tid] = t->link_invbw[tid]; s_lat[tid] = t->link_lat[tid]; }
+    if (tid <= kT) s_seg[tid] = t->seg[tid];
+    __syncthreads();
+    for (int e = lane; e < Dp; e += HX_WAVE) wbuf[e].x = s_wait[e];
+
+    int seg[kT + 1];
+#pragma unroll
+    for (int k = 0; k <= kT; ++k) seg[k] = __builtin_amdgcn_readfirstlane(s_seg[k]);
+
+    const int gw = blockIdx.x * waves_per_block + wave;
+    const int nw = gridDim.x * waves_per_block;
+    for (int c = gw; c < a.C; c += nw) {
+        const int L = a.L_in[c], O = a.L_out[c];
+        const HxCallF cf = hx_call_terms(a.m, L, O);
+
+        // decode time of this call on every decode entry (+inf where it does not fit)
+        for (int e = lane; e < Dp; e += HX_WAVE)
+            wbuf[e].y = hx_fits(L, O, s_free[e]) ? hx_decode_time(cf, s_c1[e], s_c2[e], s_kB[e]) : INFINITY;
+        xbuf[lane] = hx_transfer(cf, s_invbw[lane], s_lat[lane]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        float bestv = INFINITY;
+        int bestp = -1;
+        for (int chunk = 0; chunk < a.P; chunk += HX_WAVE * KP) {
+            float R[KP][kT], bj[KP];
+#pragma unroll
+            for (int j = 0; j < KP; ++j) {
+                int p = chunk + j * HX_WAVE + lane;
+                p = p < lay.Pp ? p : lay.Pp - 1;        // stays inside the staged (padded) table
+                bool in = chunk + j * HX_WAVE + lane < a.P;
+                float done = in ? hx_prefill_done(cf, s_pw[p], s_pinvF[p], s_pinvB[p]) : INFINITY;
+                const float *xr = xbuf + s_ptype[p] * kT;
+#pragma unroll
+                for (int k = 0; k < kT; ++k) R[j][k] = done + xr[k];
+                bj[j] = INFINITY;
+            }
+#pragma unroll
+            for (int k = 0; k < kT; ++k) {
+                const float4 *q = (const float4 *)(wbuf + seg[k]);
+                const int ngroups = (seg[k + 1] - seg[k]) / HX_DGROUP;
+                for (int g = 0; g < ngroups; ++g, q += HX_DGROUP / 2) {
+                    float4 q0 = q[0], q1 = q[1], q2 = q[2], q3 = q[3];
+#pragma unroll
+                    for (int j = 0; j < KP; ++j) {
+                        float r = R[j][k];
+                        float t0 = hx_candidate(r, q0.x, q0.y), t1 = hx_candidate(r, q0.z, q0.w);
+                        float t2 = hx_candidate(r, q1.x, q1.y), t3 = hx_candidate(r, q1.z, q1.w);
+                        float t4 = hx_candidate(r, q2.x, q2.y), t5 = hx_candidate(r, q2.z, q2.w);
+                        float t6 = hx_candidate(r, q3.x, q3.y), t7 = hx_candidate(r, q3.z, q3.w);
+                        float m0 = fminf(fminf(bj[j], t0), t1);
+                        float m1 = fminf(fminf(t2, t3), t4);
+                        float m2 = fminf(fminf(t5, t6), t7);
+                        bj[j] = fminf(fminf(m0, m1), m2);
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < KP; ++j) {
+                // p grows with j and with chunk: "<" keeps the lowest p of this lane
+                if (bj[j] < bestv) { bestv = bj[j]; bestp = chunk + j * HX_WAVE + lane; }
+            }
+        }
+        // wave minimum of (cost, p)
+#pragma unroll
+        for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
+            float ov = __shfl_xor(bestv, off);
+            int op = __shfl_xor(bestp, off);
+            bool take = ov < bestv || (ov == bestv && op < bestp);
+            bestv = take ? ov : bestv;
+            bestp = take ? op : bestp;
+        }
+        int dstar = -1, pstar = -1;
+        if (bestv < INFINITY) {
+            pstar = bestp;
+            // lowest d of instance p* that reproduces the minimum exactly
+            const float done = hx_prefill_done(cf, s_pw[pstar], s_pinvF[pstar], s_pinvB[pstar]);
+            const float *xr = xbuf + s_ptype[pstar] * kT;
+            int dmin = 0x7fffffff;
+            for (int e = lane; e < Dp; e += HX_WAVE) {
+                float v = hx_candidate(done + xr[s_dtype[e]], wbuf[e].x, wbuf[e].y);
+                if (v == bestv) dmin = min(dmin, s_orig[e]);
+            }
+#pragma unroll
+            for (int off = HX_WAVE / 2; off > 0; off >>= 1) dmin = min(dmin, __shfl_xor(dmin, off));
+            dstar = dmin;
+        }
+        if (lane == 0) {
+            a.best_p[c] = pstar;
+            a.best_d[c] = dstar;
+            a.best_cost[c] = bestv;
+            if (a.ratio) a.ratio[c] = hx_ratio(a, c, bestv);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- materialised tensor ------------------------------------------------------------
+
+// One block per call.  LDS: prefill finish per instance, decode time and
+// availability per instance (original order), class of each side.
+__global__ __launch_bounds__(256) void hx_materialise_kernel(ScoreArgs a)
+{
+    extern __shared__ __align__(16) float smem[];
+    const HxPrepTables *__restrict__ t = a.prep;
+    float *s_done = smem;                       // [P]
+    float *s_dec = s_done + a.P;                // [D]
+    float *s_wait = s_dec + a.D;                // [D]
+    int *s_ptype = (int *)(s_wait + a.D);       // [P]
+    int *s_dtype = s_ptype + a.P;               // [D]
+    float *s_x = (float *)(s_dtype + a.D);      // [kT*kT]
+    const int tid = threadIdx.x;
+    for (int c = blockIdx.x; c < a.C; c += gridDim.x) {
+        const int L = a.L_in[c], O = a.L_out[c];
+        const HxCallF cf = hx_call_terms(a.m, L, O);
+        __syncthreads();
+        for (int p = tid; p < a.P; p += blockDim.x) {
+            s_done[p] = hx_prefill_done(cf, t->pre_wait[p], t->pre_invF[p], t->pre_invB[p]);
+            s_ptype[p] = t->pre_type[p];
+        }
+        for (int d = tid; d < a.D; d += blockDim.x) {
+            int e = t->dec_pos[d];
+            bool fits = hx_fits(L, O, t->dec_free[e]);
+            s_dec[d] = fits ? hx_decode_time(cf, t->dec_c1[e], t->dec_c2[e], t->dec_kB[e]) : INFINITY;
+            s_wait[d] = t->dec_wait[e];
+            s_dtype[d] = t->dec_type[e];
+            if (a.feas) a.feas[(size_t)c * a.D + d] = fits ? 1 : 0;
+        }
+        if (tid < kT * kT) s_x[tid] = hx_transfer(cf, t->link_invbw[tid], t->link_lat[tid]);
+        __syncthreads();
+        if (a.cost) {
+            float *out = a.cost + (size_t)c * a.P * a.D;
+            const int n = a.P * a.D;
+            for (int i = tid; i < n; i += blockDim.x) {
+                int p = i / a.D, d = i - p * a.D;
+                out[i] = hx_candidate(s_done[p] + s_x[s_ptype[p] * kT + s_dtype[d]], s_wait[d], s_dec[d]);
+            }
+        }
+    }
+}
+
+// ---- select over a materialised tensor -------------------------------------------------
+
+__global__ __launch_bounds__(256) void hx_select_kernel(ScoreArgs a)
+{
+    __shared__ float s_v[4];
+    __shared__ int s_i[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = a.P * a.D;
+    for (int c = blockIdx.x; c < a.C; c += gridDim.x) {
+        const float *row = a.cost + (size_t)c * n;
+        float bv = INFINITY;
+        int bi = 0x7fffffff;
+        for (int i = tid; i < n; i += blockDim.x) {     // i grows: "<" keeps the lowest index of this thread
+            float v = row[i];
+            if (v < bv) { bv = v; bi = i; }
+        }
+#pragma unroll
+        for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
+            float ov = __shfl_xor(bv, off);
+            int oi = __shfl_xor(bi, off);
+            bool take = ov < bv || (ov == bv && oi < bi);
+            bv = take ? ov : bv;
+            bi = take ? oi : bi;
+        }
+        __syncthreads();
+        if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
+                if (s_v[w] < bv || (s_v[w] == bv && s_i[w] < bi)) { bv = s_v[w]; bi = s_i[w]; }
+            bool any = bv < INFINITY;
+            a.best_p[c] = any ? bi / a.D : -1;
+            a.best_d[c] = any ? bi % a.D : -1;
+            a.best_cost[c] = bv;
+            if (a.ratio) a.ratio[c] = hx_ratio(a, c, bv);
+        }
+    }
+}
+
+// fused outputs when the pool is empty: nothing is feasible
+__global__ void hx_no_pool_kernel(ScoreArgs a)
+{
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    a.best_p[c] = -1; a.best_d[c] = -1; a.best_cost[c] = INFINITY;
+    if (a.ratio) a.ratio[c] = hx_ratio(a, c, INFINITY);
+}
+
+HxModelF to_model(const hx_model *m)
+{
+    return HxModelF{m->kv_bytes_per_token, m->flops_per_token, m->attn_flops_per_token2,
+                    m->weight_bytes, m->nominal_batch};
+}
+
+int check_ratio_inputs(hx_ctx *ctx, const hx_calls *calls, const float *tail, const float *horizon,
+                       int32_t n_nodes, int32_t n_wf, const float *ratio)
+{
+    if (!ratio) return HX_OK;
+    HX_REQUIRE(ctx, calls && calls->node && calls->wf && calls->elapsed && tail && horizon,
+               HX_ERR_INVALID_ARG, "ratio needs calls.node, calls.wf, calls.elapsed, tail and horizon");
+    HX_REQUIRE(ctx, n_nodes >= 0 && n_wf >= 0, HX_ERR_INVALID_ARG, "negative n_nodes or n_wf");
+    return HX_OK;
+}
+
+}  // namespace
+
+extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                                   const hx_prefill_tab *pre, const hx_decode_tab *dec,
+                                   const hx_links *links,
+                                   const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                                   float *cost, uint8_t *feas,
+                                   int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                                   void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, model && calls && pre && dec && links, HX_ERR_INVALID_ARG, "NULL table");
+    const int C = calls->n, P = pre->n, D = dec->n, T = links->n_types;
+    HX_REQUIRE(ctx, C >= 0 && P >= 0 && D >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, T >= 1 && T <= HX_MAX_TYPES, HX_ERR_SHAPE, "n_types %d outside 1..%d", T, HX_MAX_TYPES);
+    HX_REQUIRE(ctx, P <= HX_MAX_INSTANCES && D <= HX_MAX_INSTANCES, HX_ERR_SHAPE,
+               "pool %d x %d beyond %d instances per side", P, D, HX_MAX_INSTANCES);
+    const bool fused = best_p || best_d || best_cost;
+    HX_REQUIRE(ctx, !fused || (best_p && best_d && best_cost), HX_ERR_INVALID_ARG,
+               "best_p, best_d, best_cost must be given together");
+    HX_REQUIRE(ctx, fused || cost || feas, HX_ERR_INVALID_ARG, "no output requested");
+    HX_REQUIRE(ctx, !ratio || fused, HX_ERR_INVALID_ARG, "ratio needs the fused outputs");
+    HX_REQUIRE(ctx, C == 0 || (calls->L_in && calls->L_out), HX_ERR_INVALID_ARG, "calls.L_in / L_out is NULL");
+    HX_REQUIRE(ctx, P == 0 || (pre->flops && pre->hbm_bw && pre->backlog_tok && pre->type),
+               HX_ERR_INVALID_ARG, "NULL member in prefill table");
+    HX_REQUIRE(ctx, D == 0 || (dec->flops && dec->hbm_bw && dec->used_tok && dec->cap_tok && dec->batch &&
+                               dec->qd_tok && dec->type), HX_ERR_INVALID_ARG, "NULL member in decode table");
+    HX_REQUIRE(ctx, links->bw, HX_ERR_INVALID_ARG, "links.bw is NULL");
+    HX_REQUIRE(ctx, !cost || (double)C * P * D < 9.0e18, HX_ERR_SHAPE, "tensor too large");
+    HX_REQUIRE(ctx, (long long)P * D <= 2147483647LL, HX_ERR_SHAPE, "P*D beyond int32");
+    if (int rc = check_ratio_inputs(ctx, calls, tail, horizon, n_nodes, n_wf, ratio)) return rc;
+    if (C == 0) return HX_OK;
+
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+
+    ScoreArgs a{};
+    a.m = to_model(model);
+    a.C = C; a.P = P; a.D = D;
+    a.L_in = calls->L_in; a.L_out = calls->L_out; a.node = calls->node; a.wf = calls->wf;
+    a.elapsed = calls->elapsed; a.tail = tail; a.horizon = horizon; a.n_nodes = n_nodes; a.n_wf = n_wf;
+    a.prep = ctx->d_prep;
+    a.best_p = best_p; a.best_d = best_d; a.best_cost = best_cost; a.ratio = ratio;
+    a.cost = cost; a.feas = feas; a.status = ctx->d_status;
+
+    if (P == 0 || D == 0) {
+        if (fused) {
+            hx_no_pool_kernel<<<(C + 255) / 256, 256, 0, stream>>>(a);
+            return hx_check_launch(ctx, "hx_no_pool_kernel");
+        }
+        return HX_OK;
+    }
+
+    PrepArgs pa{};
+    pa.m = a.m; pa.P = P; pa.D = D; pa.T = T;
+    pa.p_flops = pre->flops; pa.p_hbm = pre->hbm_bw; pa.p_backlog = pre->backlog_tok; pa.p_type = pre->type;
+    pa.d_flops = dec->flops; pa.d_hbm = dec->hbm_bw; pa.d_used = dec->used_tok; pa.d_cap = dec->cap_tok;
+    pa.d_batch = dec->batch; pa.d_qd = dec->qd_tok; pa.d_type = dec->type;
+    pa.bw = links->bw; pa.lat = links->latency; pa.out = ctx->d_prep; pa.status = ctx->d_status;
+    hx_prepare_kernel<<<1, 1024, 0, stream>>>(pa);
+    if (int rc = hx_check_launch(ctx, "hx_prepare_kernel")) return rc;
+
+    if (fused) {
+        // upper bound of the padded decode entries, known on the host without reading the device
+        const int dp_bound = (D + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP + (T - 1) * HX_DGROUP;
+        const int waves = 4;
+        const FusedLds lay(dp_bound, P);
+        const size_t lds = lay.bytes(waves);
+        HX_REQUIRE(ctx, lds <= 160 * 1024, HX_ERR_SHAPE, "pool needs %zu B of LDS", lds);
+        int blocks_per_cu = (int)((160 * 1024) / lds);
+        blocks_per_cu = blocks_per_cu > 4 ? 4 : (blocks_per_cu < 1 ? 1 : blocks_per_cu);
+        int grid = ctx->num_cu * blocks_per_cu;
+        const int need = (C + waves - 1) / waves;
+        grid = grid > need ? need : grid;
+        auto launch = [&](auto kern) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            kern<<<grid, waves * HX_WAVE, lds, stream>>>(a, dp_bound);
+        };
+        if (P <= 64) launch(hx_fused_search_kernel<1>);
+        else if (P <= 128) launch(hx_fused_search_kernel<2>);
+        else launch(hx_fused_search_kernel<4>);
+        if (int rc = hx_check_launch(ctx, "hx_fused_search_kernel")) return rc;
+    }
+    if (cost || feas) {
+        const size_t lds = 4 * ((size_t)2 * P + 3 * D + kT * kT);
+        const int grid = C < ctx->num_cu * 8 ? C : ctx->num_cu * 8;
+        hx_materialise_kernel<<<grid, 256, lds, stream>>>(a);
+        if (int rc = hx_check_launch(ctx, "hx_materialise_kernel")) return rc;
+    }
+    return HX_OK;
+}
+
+extern "C" int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const float *cost,
+                         const hx_calls *calls, const float *tail, const float *horizon,
+                         int32_t n_nodes, int32_t n_wf,
+                         int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, C >= 0 && P >= 0 && D >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, (long long)P * D <= 2147483647LL, HX_ERR_SHAPE, "P*D beyond int32");
+    HX_REQUIRE(ctx, best_p && best_d && best_cost, HX_ERR_INVALID_ARG, "NULL output");
+    HX_REQUIRE(ctx, cost || (long long)C * P * D == 0, HX_ERR_INVALID_ARG, "cost is NULL");
+    if (int rc = check_ratio_inputs(ctx, calls, tail, horizon, n_nodes, n_wf, ratio)) return rc;
+    HX_REQUIRE(ctx, !calls || calls->n == C, HX_ERR_INVALID_ARG, "calls.n differs from C");
+    if (C == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    ScoreArgs a{};
+    a.C = C; a.P = P; a.D = D; a.cost = const_cast<float *>(cost);
+    if (calls) { a.node = calls->node; a.wf = calls->wf; a.elapsed = calls->elapsed; }
+    a.tail = tail; a.horizon = horizon; a.n_nodes = n_nodes; a.n_wf = n_wf;
+    a.best_p = best_p; a.best_d = best_d; a.best_cost = best_cost; a.ratio = ratio; a.status = ctx->d_status;
+    const int grid = C < ctx->num_cu * 8 ? C : ctx->num_cu * 8;
+    hx_select_kernel<<<grid, 256, 0, stream>>>(a);
+    return hx_check_launch(ctx, "hx_select_kernel");
+}

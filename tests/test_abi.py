@@ -1,0 +1,34 @@
+"""The C-ABI library loads and exports every entry point the header declares
+(no compute calls: runs without a GPU)."""
+import ctypes
+import os
+import re
+
+from paper_2605_16637_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared():
+    text = open(os.path.join(ROOT, "include", "hx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hx_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_list_the_same_entry_points():
+    assert declared() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(binding.LIB_PATH), "build the library first (__graft_entry__.build())"
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared():
+        assert hasattr(lib, name), f"{name} is declared in hx.h but not exported"
+
+
+def test_null_context_is_an_error_not_a_crash():
+    lib = binding.load()
+    assert lib.hx_stream_status(None, None) == -1
+    assert lib.hx_ctx_destroy(None) == -1
+    assert lib.hx_last_error(None) == b"NULL context"
+    assert lib.hx_ctx_create(None, 0) == -1
