@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the placement search on one MI355X.
+
+A step is one scheduling round through the whole hot path, inputs resident in
+HBM: standalone node cost -> critical path -> fused score + argmin + projected
+ratio -> commit.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|mid|stream]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+# non-packed, non-FMA fp32 VALU issue peak: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# VALU issue slots the search needs per candidate: max, add, half a 3-input min
+OPS_PER_CANDIDATE = 2.5
+HBM_PEAK_GBS = 8000.0
+
+
+def dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+
+
+class RoundOnDevice:
+    """One synthetic round with every input and output buffer resident in HBM."""
+
+    def __init__(self, ctx, rnd):
+        import torch
+        from paper_2605_16637_amd import binding
+        self.ctx, self.rnd = ctx, rnd
+        d = rnd.dag
+        self.calls = binding.to_device(rnd.calls)
+        self.pre = binding.to_device(rnd.pre)
+        self.dec = binding.to_device(rnd.dec)
+        self.links = binding.to_device(rnd.links)
+        self.tF, self.tB = dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"])
+        self.L_in, self.L_out = dev(d.L_in), dev(d.L_out)
+        self.row_ptr, self.col, self.wf_ptr = dev(d.succ_row_ptr), dev(d.succ_col), dev(d.wf_ptr)
+        f32 = dict(dtype=torch.float32, device="cuda:0")
+        i32 = dict(dtype=torch.int32, device="cuda:0")
+        self.cost = torch.empty(d.n_nodes, **f32)
+        self.rem = torch.empty(d.n_nodes, **f32); self.tail = torch.empty(d.n_nodes, **f32)
+        self.level = torch.empty(d.n_nodes, **i32); self.hor = torch.empty(d.n_wf, **f32)
+        n = rnd.calls["n"]
+        self.bp = torch.empty(n, **i32); self.bd = torch.empty(n, **i32)
+        self.bc = torch.empty(n, **f32); self.ratio = torch.empty(n, **f32)
+        # per-round drains sized to what a round adds, so the pool stays in its regime
+        P, D = rnd.pre["n"], rnd.dec["n"]
+        Ls, Os = float(rnd.calls["L_in"].sum()), float(rnd.calls["L_out"].sum())
+        self.drain_p = dev(np.full(P, int(Ls / max(P, 1)), np.int32))
+        self.drain_q = dev(np.full(D, int(Os / max(D, 1)), np.int32))
+        self.release = dev(np.full(D, int((Ls + Os) / max(D, 1)), np.int32))
+
+    def horizons(self):
+        r = self.rnd
+        self.ctx.hx_node_cost(r.model, self.L_in, self.L_out, self.tF, self.tB, self.links, self.cost)
+        self.ctx.hx_critical_path(self.row_ptr, self.col, self.cost, self.wf_ptr,
+                                  self.rem, self.tail, self.level, self.hor)
+
+    def score(self):
+        self.ctx.hx_score_placements(self.rnd.model, self.calls, self.pre, self.dec, self.links,
+                                     tail=self.tail, horizon=self.hor,
+                                     best_p=self.bp, best_d=self.bd, best_cost=self.bc, ratio=self.ratio)
+
+    def commit(self):
+        self.ctx.hx_commit(self.calls, self.bp, self.bd, self.pre["backlog_tok"], self.dec["used_tok"],
+                           self.dec["batch"], self.dec["qd_tok"], self.drain_p, self.drain_q, self.release)
+
+    def step(self):
+        self.horizons()
+        self.score()
+        self.commit()
+
+
+def time_steps(torch, fn, steps, warmup, inner=None):
+    """Wall-clock of `steps` calls of fn bracketed by synchronisation; `inner`
+    (start, end) event lists bracket the dominant launch inside every step."""
+    for _ in range(warmup):
+        fn(None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(i)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(rnd, target_s=12.0):
+    """The oracle, as it stands, on a bounded sample of the same round."""
+    from oracle import hx_oracle as o
+    threads = min(os.cpu_count() or 1, 16)
+    L, O = rnd.calls["L_in"], rnd.calls["L_out"]
+    per = rnd.pre["n"] * rnd.dec["n"]
+    n0 = max(1, min(len(L), 2_000_000 // per * threads))
+    t0 = time.perf_counter()
+    o.score(rnd.model, L[:n0], O[:n0], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
+    dt = time.perf_counter() - t0
+    n1 = int(max(n0, min(len(L), n0 * target_s / max(dt, 1e-6))))
+    t0 = time.perf_counter()
+    o.score(rnd.model, L[:n1], O[:n1], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
+    dt = time.perf_counter() - t0
+    return dict(value=n1 * per / dt, unit="candidates/s", cores=threads, kind="oracle",
+                sample="first %d of %d calls x %d x %d candidates, fp64, %.1f s" %
+                       (n1, len(L), rnd.pre["n"], rnd.dec["n"], dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="large", choices=["large", "mid", "stream"])
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the mid-round latency and critical-path legs")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_16637_amd import binding, synth
+    ctx = binding.Context(0)
+    torch.cuda.set_device(0)
+
+    rnd = synth.make_round(args.workload if args.workload != "stream" else "stream", args.seed)
+    rd = RoundOnDevice(ctx, rnd)
+    C, P, D = rnd.calls["n"], rnd.pre["n"], rnd.dec["n"]
+    n_cand = C * P * D
+
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+
+    def step(i):
+        rd.horizons()
+        if i is not None:
+            ev0[i].record()
+        rd.score()
+        if i is not None:
+            ev1[i].record()
+        rd.commit()
+
+    wall = time_steps(torch, step, args.steps, args.warmup)
+    ctx.hx_stream_status()
+    score_ms = np.array([a.elapsed_time(b) for a, b in zip(ev0, ev1)])
+    ms_per_step = wall / args.steps * 1e3
+    value = n_cand * args.steps / wall
+
+    score_s = float(score_ms.mean()) * 1e-3
+    achieved = n_cand * OPS_PER_CANDIDATE / score_s / 1e12
+    out = {
+        "metric": "placement candidates scored/sec",
+        "value": value, "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": {"large": "large scoring sweep: 16384 ready calls x 256 prefill x 256 decode, 8 classes",
+                                "mid": "mid round: 4096 ready calls x 64 prefill x 64 decode, 4 classes",
+                                "stream": "streaming round shape: 32768 ready calls x 512 x 512, 8 classes"}[args.workload],
+                   "calls": C, "prefill": P, "decode": D, "candidates_per_round": n_cand,
+                   "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
+                   "step": "node cost -> critical path -> fused score+argmin+ratio -> commit", "seed": args.seed},
+        "roofline": {"kernel": "hx_fused_search_kernel (+ its table-prepare launch)", "bound": "alu",
+                     "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
+                     "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+                     "ops_per_candidate": OPS_PER_CANDIDATE, "launch_ms": score_s * 1e3,
+                     "candidates_per_s_kernel": n_cand / score_s},
+    }
+
+    if not args.no_extras:
+        # p50 scheduling-round latency on the mid round: host clock from "round handed over" to "indices ready"
+        mid = synth.make_round("mid", args.seed)
+        rm = RoundOnDevice(ctx, mid)
+        lat = []
+        for i in range(320):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rm.step()
+            torch.cuda.synchronize()
+            if i >= 20:
+                lat.append((time.perf_counter() - t0) * 1e6)
+        lat = np.array(lat)
+        out["round_latency"] = {"workload": "mid round: 4096 calls x 64 x 64, 1000 workflows / %d nodes" % mid.dag.n_nodes,
+                                "p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
+                                "rounds": int(lat.size),
+                                "candidates_per_s_at_p50": mid.n_candidates / (np.percentile(lat, 50) * 1e-6)}
+        # critical-path stress: 100 000 workflows, 2.0 M nodes; rotating copies so the
+        # pass does not run out of the 256 MB last-level cache
+        cp = synth.make_round("cp", args.seed)
+        d = cp.dag
+        n_copies = 6
+        sets = []
+        cost_np = np.random.default_rng(args.seed).uniform(0.5, 6.0, d.n_nodes).astype(np.float32)
+        for _ in range(n_copies):
+            sets.append(dict(rp=dev(d.succ_row_ptr), col=dev(d.succ_col), wp=dev(d.wf_ptr), cost=dev(cost_np),
+                             rem=torch.empty(d.n_nodes, device="cuda:0"), tail=torch.empty(d.n_nodes, device="cuda:0"),
+                             level=torch.empty(d.n_nodes, dtype=torch.int32, device="cuda:0"),
+                             hor=torch.empty(d.n_wf, device="cuda:0")))
+        reps = 60
+        e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        for i in range(-6, reps):
+            s = sets[i % n_copies]
+            if i >= 0:
+                e0[i].record()
+            ctx.hx_critical_path(s["rp"], s["col"], s["cost"], s["wp"], s["rem"], s["tail"], s["level"], s["hor"])
+            if i >= 0:
+                e1[i].record()
+        torch.cuda.synchronize()
+        ctx.hx_stream_status()
+        cp_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
+        cp_bytes = 4 * (d.n_nodes + 1) + 4 * d.n_edges + 4 * d.n_nodes + 4 * (d.n_wf + 1) + 12 * d.n_nodes + 4 * d.n_wf
+        gbs = cp_bytes / (cp_ms * 1e-3) / 1e9
+        out["critical_path"] = {"workload": "critical-path stress: %d workflows, %d nodes, %d edges" % (d.n_wf, d.n_nodes, d.n_edges),
+                                "kernel": "hx_cp_local_kernel", "bound": "hbm", "launch_ms": cp_ms,
+                                "algorithmic_bytes": cp_bytes, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                "frac": gbs / HBM_PEAK_GBS, "traffic": None, "rotating_copies": n_copies}
+        del sets
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(rnd)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

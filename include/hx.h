@@ -115,7 +115,8 @@ int hx_ctx_create(hx_ctx **out, int device);
 /* Frees everything the context owns.  The caller has synchronised its streams. */
 int hx_ctx_destroy(hx_ctx *ctx);
 
-/* Text of the last error of this context (static storage, never NULL). */
+/* Text of the last error of this context (static storage, never NULL); with
+ * ctx == NULL, why the last hx_ctx_create of this process failed. */
 const char *hx_last_error(const hx_ctx *ctx);
 
 /* Synchronises `stream`, returns the sticky device status (HX_OK or the first

@@ -62,6 +62,9 @@ def load() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2605_16637_amd.build` "
                               "(or __graft_entry__.build()) first")
+        # PyTorch ships its own copy of the HIP runtime; import it first so the
+        # library binds to that copy and the process holds exactly one runtime
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         for name in EXPORTS:
             getattr(lib, name).restype = C.c_int
@@ -135,12 +138,16 @@ class Context:
     """Owns one ``hx_ctx``.  Methods mirror the C entry points one to one."""
 
     def __init__(self, device: int = 0):
-        _torch()
+        torch = _torch()
+        # the HIP runtime in this process is PyTorch's copy; let PyTorch bring the
+        # device up before the library makes its first HIP call
+        torch.cuda.init()
+        torch.empty(1, device=f"cuda:{int(device)}")
         self.lib = load()
         self._ctx = C.c_void_p()
         rc = self.lib.hx_ctx_create(C.byref(self._ctx), int(device))
         if rc != HX_OK:
-            raise HxError(rc, "hx_ctx_create failed")
+            raise HxError(rc, self.lib.hx_last_error(None).decode())
         self.device = device
 
     def close(self):

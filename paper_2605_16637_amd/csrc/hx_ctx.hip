@@ -5,6 +5,14 @@ void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
 
 namespace {
 
+char g_create_err[256] = "NULL context";   // why the last hx_ctx_create failed
+
+int create_fail(const char *what, hipError_t e)
+{
+    snprintf(g_create_err, sizeof(g_create_err), "hx_ctx_create: %s: %s", what, hipGetErrorString(e));
+    return HX_ERR_DEVICE;
+}
+
 __global__ void hx_clear_status_kernel(int32_t *status) { *status = 0; }
 
 struct CommitArgs {
@@ -68,27 +76,32 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (!out) return HX_ERR_INVALID_ARG;
     *out = nullptr;
     int count = 0;
-    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return HX_ERR_DEVICE;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess) return create_fail("hipGetDeviceCount", e);
+    if (device < 0 || device >= count) return create_fail("no such device", hipErrorInvalidDevice);
     HxDeviceGuard guard(device);
-    if (!guard.ok) return HX_ERR_DEVICE;
+    if (!guard.ok) return create_fail("hipSetDevice", hipErrorInvalidDevice);
     hx_ctx *ctx = new (std::nothrow) hx_ctx();
-    if (!ctx) return HX_ERR_DEVICE;
+    if (!ctx) return create_fail("out of host memory", hipErrorOutOfMemory);
     ctx->device = device;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->num_cu = prop.multiProcessorCount;
-    bool ok = hipMalloc((void **)&ctx->d_status, sizeof(int32_t)) == hipSuccess &&
-              hipHostMalloc((void **)&ctx->h_status, sizeof(int32_t), hipHostMallocDefault) == hipSuccess &&
-              hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)) == hipSuccess &&
-              hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)) == hipSuccess &&
-              hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)) == hipSuccess;
-    if (ok) {
+    const char *what = "hipMalloc(status)";
+    e = hipMalloc((void **)&ctx->d_status, sizeof(int32_t));
+    if (e == hipSuccess) { what = "hipHostMalloc(status)"; e = hipHostMalloc((void **)&ctx->h_status, sizeof(int32_t), hipHostMallocDefault); }
+    if (e == hipSuccess) { what = "hipMalloc(tables)"; e = hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)); }
+    if (e == hipSuccess) { what = "hipMalloc(flags)"; e = hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)); }
+    if (e == hipSuccess) { what = "hipMalloc(accumulators)"; e = hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)); }
+    if (e == hipSuccess) {
+        what = "launch of hx_clear_status_kernel";
         hx_clear_status_kernel<<<1, 1, 0, nullptr>>>(ctx->d_status);
-        ok = hipGetLastError() == hipSuccess && hipStreamSynchronize(nullptr) == hipSuccess;
+        e = hipGetLastError();
     }
-    if (!ok) {
+    if (e == hipSuccess) { what = "hipStreamSynchronize"; e = hipStreamSynchronize(nullptr); }
+    if (e != hipSuccess) {
         hx_ctx_destroy(ctx);
-        return HX_ERR_DEVICE;
+        return create_fail(what, e);
     }
     *out = ctx;
     return HX_OK;
@@ -110,7 +123,7 @@ extern "C" int hx_ctx_destroy(hx_ctx *ctx)
 
 extern "C" const char *hx_last_error(const hx_ctx *ctx)
 {
-    return ctx ? ctx->err : "NULL context";
+    return ctx ? ctx->err : g_create_err;
 }
 
 extern "C" int hx_stream_status(hx_ctx *ctx, void *stream_)

@@ -96,7 +96,7 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
     const int w1 = min(w0 + CP_THREADS, a.n_wf);
     int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
     const int w = w0 + tid;
-    int ws = 0, we = 0;
+    int ws = n0, we = n0;                       // threads past the last workflow own no nodes
     if (w < w1) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
     if (tid == 0) s_bad = 0;
     // malformed ranges: clamp so that nothing is read out of bounds, and report

@@ -199,7 +199,7 @@ def test_append_errors(ctx):
     assert e.value.code == -3
     # a chain deeper than max_depth: propagation is cut and reported, nothing hangs
     ctx.hx_dag_reserve(16, 16, 1, 2)
-    ctx.hx_dag_append(dev(np.array([0, 0, 1, 2, 3, 4], np.int32)), dev(np.arange(5, dtype=np.int32)),
+    ctx.hx_dag_append(dev(np.array([0, 0, 1, 2, 3, 4, 5], np.int32)), dev(np.arange(5, dtype=np.int32)),
                       dev(np.ones(6, np.float32)), dev(np.zeros(6, np.int32)))
     with pytest.raises(binding.HxError) as e:
         ctx.hx_stream_status()
