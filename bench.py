@@ -82,17 +82,38 @@ class RoundOnDevice:
         self.commit()
 
 
-def time_steps(torch, fn, steps, warmup, inner=None):
-    """Wall-clock of `steps` calls of fn bracketed by synchronisation; `inner`
-    (start, end) event lists bracket the dominant launch inside every step."""
+def capture(torch, fn):
+    """Records one call of fn (kernel launches only) into a HIP graph."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    return g
+
+
+def time_steps(torch, fn, steps, warmup):
+    """Wall-clock of exactly `steps` calls of fn, synchronised on both sides."""
     for _ in range(warmup):
-        fn(None)
+        fn()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
-        fn(i)
+    for _ in range(steps):
+        fn()
     torch.cuda.synchronize()
     return time.perf_counter() - t0
+
+
+def time_launches(torch, fn, reps, warmup=5):
+    """Average GPU time of one call of fn from HIP events on the launch stream,
+    over `reps` back-to-back calls."""
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e-3
 
 
 def cpu_baseline(rnd, target_s=12.0):
@@ -121,6 +142,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="large", choices=["large", "mid", "stream"])
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--eager", action="store_true", help="launch every step from the host instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the mid-round latency and critical-path legs")
     args = ap.parse_args()
@@ -138,25 +160,16 @@ def main():
     C, P, D = rnd.calls["n"], rnd.pre["n"], rnd.dec["n"]
     n_cand = C * P * D
 
-    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-
-    def step(i):
-        rd.horizons()
-        if i is not None:
-            ev0[i].record()
-        rd.score()
-        if i is not None:
-            ev1[i].record()
-        rd.commit()
-
-    wall = time_steps(torch, step, args.steps, args.warmup)
+    # the round is launch-bound on the host unless its launches are replayed from a HIP graph
+    rd.step()
+    torch.cuda.synchronize()
+    run = rd.step if args.eager else capture(torch, rd.step).replay
+    wall = time_steps(torch, run, args.steps, args.warmup)
     ctx.hx_stream_status()
-    score_ms = np.array([a.elapsed_time(b) for a, b in zip(ev0, ev1)])
     ms_per_step = wall / args.steps * 1e3
     value = n_cand * args.steps / wall
-
-    score_s = float(score_ms.mean()) * 1e-3
+    # the dominant kernel on its own: table prepare + fused search, HIP events on the launch stream
+    score_s = time_launches(torch, rd.score, max(20, min(args.steps, 200)))
     achieved = n_cand * OPS_PER_CANDIDATE / score_s / 1e12
     out = {
         "metric": "placement candidates scored/sec",
@@ -169,7 +182,8 @@ def main():
                                 "stream": "streaming round shape: 32768 ready calls x 512 x 512, 8 classes"}[args.workload],
                    "calls": C, "prefill": P, "decode": D, "candidates_per_round": n_cand,
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
-                   "step": "node cost -> critical path -> fused score+argmin+ratio -> commit", "seed": args.seed},
+                   "step": "node cost -> critical path -> fused score+argmin+ratio -> commit",
+                   "launch": "eager" if args.eager else "hip graph replay", "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (+ its table-prepare launch)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                      "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
@@ -181,11 +195,14 @@ def main():
         # p50 scheduling-round latency on the mid round: host clock from "round handed over" to "indices ready"
         mid = synth.make_round("mid", args.seed)
         rm = RoundOnDevice(ctx, mid)
+        rm.step()
+        torch.cuda.synchronize()
+        run_mid = rm.step if args.eager else capture(torch, rm.step).replay
         lat = []
-        for i in range(320):
+        for i in range(520):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            rm.step()
+            run_mid()
             torch.cuda.synchronize()
             if i >= 20:
                 lat.append((time.perf_counter() - t0) * 1e6)
@@ -207,18 +224,15 @@ def main():
                              level=torch.empty(d.n_nodes, dtype=torch.int32, device="cuda:0"),
                              hor=torch.empty(d.n_wf, device="cuda:0")))
         reps = 60
-        e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
-        e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
-        for i in range(-6, reps):
-            s = sets[i % n_copies]
-            if i >= 0:
-                e0[i].record()
-            ctx.hx_critical_path(s["rp"], s["col"], s["cost"], s["wp"], s["rem"], s["tail"], s["level"], s["hor"])
-            if i >= 0:
-                e1[i].record()
-        torch.cuda.synchronize()
+        k = [0]
+
+        def cp_once():
+            x = sets[k[0] % n_copies]
+            k[0] += 1
+            ctx.hx_critical_path(x["rp"], x["col"], x["cost"], x["wp"], x["rem"], x["tail"], x["level"], x["hor"])
+
+        cp_ms = time_launches(torch, cp_once, reps, warmup=n_copies) * 1e3
         ctx.hx_stream_status()
-        cp_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
         cp_bytes = 4 * (d.n_nodes + 1) + 4 * d.n_edges + 4 * d.n_nodes + 4 * (d.n_wf + 1) + 12 * d.n_nodes + 4 * d.n_wf
         gbs = cp_bytes / (cp_ms * 1e-3) / 1e9
         out["critical_path"] = {"workload": "critical-path stress: %d workflows, %d nodes, %d edges" % (d.n_wf, d.n_nodes, d.n_edges),

@@ -2,6 +2,7 @@
 #include "hx_common.hpp"
 
 void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
+int hx_score_init();                // hx_score.hip
 
 namespace {
 
@@ -31,20 +32,32 @@ __global__ __launch_bounds__(256) void hx_commit_clear_kernel(CommitArgs a)
     if (i < a.P + 2 * a.D) a.acc[i] = 0ull;
 }
 
-// Algorithm 1 "update simulated state" for all calls of the round at once:
-// integer additions commute, so the result does not depend on call order.
+// The state update of Algorithm 1 for all calls of the round at once: integer
+// additions commute, so the result does not depend on call order.  Chosen
+// placements concentrate on a few instances, so every block first sums into an
+// LDS copy of the counters and only then adds its non-zero sums to the global
+// ones (a handful of global atomics per block instead of three per call).
 __global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
 {
+    __shared__ unsigned long long s_acc[3 * HX_MAX_INSTANCES];
+    const int n_acc = a.P + 2 * a.D;
+    for (int i = threadIdx.x; i < n_acc; i += blockDim.x) s_acc[i] = 0ull;
+    __syncthreads();
+    bool bad = false;
     for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < a.C; c += gridDim.x * blockDim.x) {
         const int p = a.best_p[c], d = a.best_d[c];
         if (p < 0 || d < 0) continue;                       // the call stays queued
-        if (p >= a.P || d >= a.D) { hx_raise(a.status, HX_ERR_INDEX); continue; }
+        if (p >= a.P || d >= a.D) { bad = true; continue; }
         const int L = a.L_in[c], O = a.L_out[c];
-        if (L < 0 || O < 0) { hx_raise(a.status, HX_ERR_INDEX); continue; }
-        atomicAdd(&a.acc[p], (unsigned long long)L);
-        atomicAdd(&a.acc[a.P + d], (unsigned long long)L + (unsigned long long)O);
-        atomicAdd(&a.acc[a.P + a.D + d], (unsigned long long)O);
+        if (L < 0 || O < 0) { bad = true; continue; }
+        atomicAdd(&s_acc[p], (unsigned long long)L);
+        atomicAdd(&s_acc[a.P + d], (unsigned long long)L + (unsigned long long)O);
+        atomicAdd(&s_acc[a.P + a.D + d], (unsigned long long)O);
     }
+    if (bad) hx_raise(a.status, HX_ERR_INDEX);
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_acc; i += blockDim.x)
+        if (s_acc[i]) atomicAdd(&a.acc[i], s_acc[i]);
 }
 
 __device__ __forceinline__ int hx_add_sat_drain(int cur, unsigned long long add, int drain, int32_t *status)
@@ -93,6 +106,7 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (e == hipSuccess) { what = "hipMalloc(tables)"; e = hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)); }
     if (e == hipSuccess) { what = "hipMalloc(flags)"; e = hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)); }
     if (e == hipSuccess) { what = "hipMalloc(accumulators)"; e = hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)); }
+    if (e == hipSuccess && hx_score_init() != HX_OK) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
     if (e == hipSuccess) {
         what = "launch of hx_clear_status_kernel";
         hx_clear_status_kernel<<<1, 1, 0, nullptr>>>(ctx->d_status);
@@ -174,7 +188,7 @@ extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best
     hx_commit_clear_kernel<<<(n_acc + 255) / 256, 256, 0, stream>>>(a);
     if (C > 0) {
         int grid = (C + 255) / 256;
-        grid = grid > ctx->num_cu * 4 ? ctx->num_cu * 4 : grid;
+        grid = grid > ctx->num_cu ? ctx->num_cu : grid;
         hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a);
     }
     const int n_inst = P > D ? P : D;

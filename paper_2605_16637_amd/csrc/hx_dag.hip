@@ -72,17 +72,22 @@ struct CpArgs {
     int32_t *status;
 };
 
-constexpr int CP_THREADS = 128;      // workflows per block, one thread each
-constexpr int CP_NMAX = 4096;        // nodes staged per block
-constexpr int CP_EMAX = 8192;        // edges staged per block
+constexpr int CP_THREADS = 256;      // threads per block (loads and stores use all of them)
+constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking thread each
+constexpr int CP_NMAX = 2048;        // nodes staged per block
+constexpr int CP_EMAX = 4096;        // edges staged per block
+constexpr int CP_NPT = CP_NMAX / CP_THREADS;
+constexpr int CP_EPT = CP_EMAX / CP_THREADS;
 
-// One block takes CP_THREADS consecutive workflows.  Their node and edge
-// ranges are contiguous, so the CSR slice is staged into LDS with coalesced
-// loads (row offsets and successors as 16-bit offsets relative to the slice),
-// each thread walks one workflow from its last node to its first, and the
-// results leave through coalesced stores.  A slice too large for LDS is
-// walked in global memory by the same threads.
-__global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
+// One block takes `wpb` consecutive workflows.  Their node and edge ranges are
+// contiguous, so the CSR slice is staged into LDS with coalesced loads -- all
+// of a thread's loads are issued before the first is used, which is what keeps
+// enough bytes in flight to cover HBM latency -- row offsets and successors
+// are kept as 16-bit offsets relative to the slice, one thread per workflow
+// walks it from its last node to its first, and the results leave through
+// coalesced stores.  A slice too large for LDS is walked in global memory by
+// the same threads.
+__global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a, int wpb)
 {
     __shared__ float s_rem[CP_NMAX];          // holds cost, then rem
     __shared__ float s_tail[CP_NMAX];
@@ -92,8 +97,8 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
     __shared__ int s_bad;
 
     const int tid = threadIdx.x;
-    const int w0 = blockIdx.x * CP_THREADS;
-    const int w1 = min(w0 + CP_THREADS, a.n_wf);
+    const int w0 = blockIdx.x * wpb;
+    const int w1 = min(w0 + wpb, a.n_wf);
     int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
     const int w = w0 + tid;
     int ws = n0, we = n0;                       // threads past the last workflow own no nodes
@@ -111,6 +116,22 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
         return;
     }
     const int nn = n1 - n0;
+    const bool staged_nodes = nn <= CP_NMAX;
+    // node arrays first: they do not depend on the edge range
+    float c[CP_NPT];
+    int r[CP_NPT + 1];
+    if (staged_nodes) {
+#pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            c[k] = i < nn ? a.cost[n0 + i] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k <= CP_NPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            r[k] = i <= nn ? a.row_ptr[n0 + i] : 0;
+        }
+    }
     int e0 = 0, e1 = 0;
     if (nn > 0) { e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1]; }
     if (e0 < 0 || e1 > a.n_edges || e0 > e1) {
@@ -122,36 +143,58 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
     float hmax = 0.0f;
     bool not_dag = false;
 
-    if (nn <= CP_NMAX && ne <= CP_EMAX) {
-        for (int i = tid; i < nn; i += CP_THREADS) s_rem[i] = a.cost[n0 + i];
-        for (int i = tid; i <= nn; i += CP_THREADS) {
-            int r = a.row_ptr[n0 + i] - e0;
-            s_row[i] = (uint16_t)min(max(r, 0), ne);     // a non-monotone row_ptr cannot leave the slice
+    if (staged_nodes && ne <= CP_EMAX) {
+        int ed[CP_EPT];
+#pragma unroll
+        for (int k = 0; k < CP_EPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            ed[k] = i < ne ? a.col[e0 + i] : -1;
         }
-        for (int i = tid; i < ne; i += CP_THREADS) {
-            int u = a.col[e0 + i] - n0;
-            s_col[i] = (u >= 0 && u < nn) ? (uint16_t)u : (uint16_t)0xffff;   // 0xffff: outside the slice
+#pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            if (i < nn) s_rem[i] = c[k];
+        }
+#pragma unroll
+        for (int k = 0; k <= CP_NPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            if (i <= nn) s_row[i] = (uint16_t)min(max(r[k] - e0, 0), ne);   // a non-monotone row_ptr cannot leave the slice
+        }
+#pragma unroll
+        for (int k = 0; k < CP_EPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            int u = ed[k] - n0;
+            if (i < ne) s_col[i] = (u >= 0 && u < nn) ? (uint16_t)u : (uint16_t)0xffff;   // 0xffff: outside the slice
         }
         __syncthreads();
-        for (int v = we - 1 - n0; v >= ws - n0; --v) {
-            int r0 = s_row[v], r1 = s_row[v + 1];
-            float tl = 0.0f;
-            int lv = 0;
-            for (int e = r0; e < r1; ++e) {
-                int u = s_col[e];
-                if (u <= v || u >= we - n0) { not_dag = true; continue; }   // not a later node of this workflow
-                tl = fmaxf(tl, s_rem[u]);
-                lv = max(lv, (int)s_level[u] + 1);
+        if (we > ws) {
+            const int lo = ws - n0, hi = we - n0;
+            int r1 = s_row[hi];
+            for (int v = hi - 1; v >= lo; --v) {
+                const int r0 = s_row[v];
+                float tl = 0.0f;
+                int lv = 0;
+                for (int e = r0; e < r1; ++e) {
+                    int u = s_col[e];
+                    if (u <= v || u >= hi) { not_dag = true; continue; }   // not a later node of this workflow
+                    tl = fmaxf(tl, s_rem[u]);
+                    lv = max(lv, (int)s_level[u] + 1);
+                }
+                float rv = s_rem[v] + tl;
+                s_rem[v] = rv; s_tail[v] = tl; s_level[v] = (uint16_t)lv;
+                hmax = fmaxf(hmax, rv);
+                r1 = r0;
             }
-            float r = s_rem[v] + tl;
-            s_rem[v] = r; s_tail[v] = tl; s_level[v] = (uint16_t)lv;
-            hmax = fmaxf(hmax, r);
         }
         __syncthreads();
-        for (int i = tid; i < nn; i += CP_THREADS) {
-            a.rem[n0 + i] = s_rem[i];
-            a.tail[n0 + i] = s_tail[i];
-            a.level[n0 + i] = s_level[i];
+#pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            int i = k * CP_THREADS + tid;
+            if (i < nn) {
+                a.rem[n0 + i] = s_rem[i];
+                a.tail[n0 + i] = s_tail[i];
+                a.level[n0 + i] = s_level[i];
+            }
         }
     } else {
         for (int v = we - 1; v >= ws; --v) {
@@ -165,9 +208,9 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a)
                 tl = fmaxf(tl, a.rem[u]);          // written earlier by this same thread
                 lv = max(lv, a.level[u] + 1);
             }
-            float r = a.cost[v] + tl;
-            a.rem[v] = r; a.tail[v] = tl; a.level[v] = lv;
-            hmax = fmaxf(hmax, r);
+            float rv = a.cost[v] + tl;
+            a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
+            hmax = fmaxf(hmax, rv);
         }
     }
     if (w < w1) a.horizon[w] = hmax;
@@ -397,8 +440,11 @@ extern "C" int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
     CpArgs a{n_nodes, n_edges, n_wf, succ_row_ptr, succ_col_idx, wf_ptr, node_cost, rem, tail, horizon, level,
              ctx->d_status};
     if (max_sweeps == 0) {
-        const int grid = (n_wf + CP_THREADS - 1) / CP_THREADS;
-        hx_cp_local_kernel<<<grid, CP_THREADS, 0, stream>>>(a);
+        // workflows per block: as many as fit the staged slice at the average workflow size
+        long long fit = n_nodes > 0 ? (long long)(CP_NMAX * 3 / 4) * n_wf / n_nodes : CP_WPB;
+        const int wpb = (int)(fit < 1 ? 1 : (fit > CP_WPB ? CP_WPB : fit));
+        const int grid = (n_wf + wpb - 1) / wpb;
+        hx_cp_local_kernel<<<grid, CP_THREADS, 0, stream>>>(a, wpb);
         return hx_check_launch(ctx, "hx_cp_local_kernel");
     }
     const int nmax = n_nodes > max_sweeps + 1 ? n_nodes : max_sweeps + 1;

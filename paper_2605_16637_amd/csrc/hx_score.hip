@@ -46,7 +46,6 @@ struct PrepArgs {
 
 __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
 {
-    __shared__ int s_type[HX_MAX_INSTANCES];
     __shared__ int s_cnt[kT], s_seg[kT + 1];
     const int tid = threadIdx.x;
     HxPrepTables *o = a.out;
@@ -66,23 +65,30 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
         o->pre_wait[p] = hx_prefill_wait(a.m, a.p_backlog[p], invF);
         o->pre_type[p] = t;
     }
-    for (int d = tid; d < a.D; d += blockDim.x) {
-        int t = a.d_type[d];
-        if (t < 0 || t >= a.T) { hx_raise(a.status, HX_ERR_INDEX); t = 0; }
-        s_type[d] = t;
+    // class of each decode instance, per-wave class counts (ballots), class segments
+    __shared__ int s_wcnt[HX_MAX_INSTANCES / HX_WAVE][kT];
+    const int lane = tid & (HX_WAVE - 1), wv = tid >> 6;
+    int my_t = -1;
+    if (tid < a.D) {
+        my_t = a.d_type[tid];
+        if (my_t < 0 || my_t >= a.T) { hx_raise(a.status, HX_ERR_INDEX); my_t = 0; }
     }
-    __syncthreads();
-    if (tid < kT) {
-        int n = 0;
-        for (int d = 0; d < a.D; ++d) n += (s_type[d] == tid);
-        s_cnt[tid] = n;
+    int my_rank = 0;                     // instances of my class before me in my wave
+#pragma unroll
+    for (int t = 0; t < kT; ++t) {
+        unsigned long long b = __ballot(my_t == t);
+        if (lane == 0) s_wcnt[wv][t] = __popcll(b);
+        if (my_t == t) my_rank = __popcll(b & ((1ull << lane) - 1ull));
     }
     __syncthreads();
     if (tid == 0) {
         int e = 0;
         for (int t = 0; t < kT; ++t) {
+            int n = 0;
+            for (int k = 0; k < (a.D + HX_WAVE - 1) / HX_WAVE; ++k) n += s_wcnt[k][t];
+            s_cnt[t] = n;
             s_seg[t] = e;
-            e += (s_cnt[t] + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP;
+            e += (n + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP;
         }
         s_seg[kT] = e;
         for (int t = 0; t <= kT; ++t) o->seg[t] = s_seg[t];
@@ -99,10 +105,10 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
             o->dec_free[e] = -1; o->dec_orig[e] = -1; o->dec_type[e] = t;
         }
     }
-    for (int d = tid; d < a.D; d += blockDim.x) {
-        int t = s_type[d];
-        int rank = 0;
-        for (int q = 0; q < d; ++q) rank += (s_type[q] == t);
+    if (tid < a.D) {
+        const int d = tid, t = my_t;
+        int rank = my_rank;
+        for (int k = 0; k < wv; ++k) rank += s_wcnt[k][t];
         int e = s_seg[t] + rank;
         HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], a.d_qd[d],
                                    1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
@@ -402,6 +408,21 @@ int check_ratio_inputs(hx_ctx *ctx, const hx_calls *calls, const float *tail, co
 
 }  // namespace
 
+// the fused search may use all 160 KB of LDS; said once per process, outside any stream work
+int hx_score_init()
+{
+    const int lds = 160 * 1024;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_fused_search_kernel<1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_fused_search_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_fused_search_kernel<4>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return e == hipSuccess ? HX_OK : HX_ERR_DEVICE;
+}
+
 extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
                                    const hx_prefill_tab *pre, const hx_decode_tab *dec,
                                    const hx_links *links,
@@ -475,11 +496,7 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         int grid = ctx->num_cu * blocks_per_cu;
         const int need = (C + waves - 1) / waves;
         grid = grid > need ? need : grid;
-        auto launch = [&](auto kern) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            kern<<<grid, waves * HX_WAVE, lds, stream>>>(a, dp_bound);
-        };
+        auto launch = [&](auto kern) { kern<<<grid, waves * HX_WAVE, lds, stream>>>(a, dp_bound); };
         if (P <= 64) launch(hx_fused_search_kernel<1>);
         else if (P <= 128) launch(hx_fused_search_kernel<2>);
         else launch(hx_fused_search_kernel<4>);
