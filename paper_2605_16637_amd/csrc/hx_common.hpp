@@ -90,7 +90,8 @@ inline int hx_fail(hx_ctx *ctx, int code, const char *fmt, ...)
 // Every kernel that can meet a bad element records the first error here.
 __device__ inline void hx_raise(int32_t *status, int32_t code)
 {
-    atomicCAS(status, 0, code);
+    // read first: when many threads meet the same bad input only a few reach the atomic
+    if (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) atomicCAS(status, 0, code);
 }
 
 inline int hx_check_launch(hx_ctx *ctx, const char *what)

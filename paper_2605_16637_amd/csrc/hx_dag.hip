@@ -72,29 +72,34 @@ struct CpArgs {
     int32_t *status;
 };
 
-constexpr int CP_THREADS = 256;      // threads per block (loads and stores use all of them)
-constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking thread each
-constexpr int CP_NMAX = 2048;        // nodes staged per block
-constexpr int CP_EMAX = 4096;        // edges staged per block
-constexpr int CP_NPT = CP_NMAX / CP_THREADS;
-constexpr int CP_EPT = CP_EMAX / CP_THREADS;
+constexpr int CP_THREADS = 128;      // threads per block (loads and stores use all of them)
+constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking lane each
+constexpr int CP_NMAX = 2040;        // nodes staged per block; 10 B of LDS each, so 8 blocks fit a CU
+constexpr int CP_NPT = (CP_NMAX + CP_THREADS - 1) / CP_THREADS;
+static_assert(CP_NPT % 2 == 0, "the staging loop splits a thread's nodes in two halves");
+constexpr int CP_DEG = 4;            // successors held inline per staged node
 
-// One block takes `wpb` consecutive workflows.  Their node and edge ranges are
-// contiguous, so the CSR slice is staged into LDS with coalesced loads -- all
-// of a thread's loads are issued before the first is used, which is what keeps
-// enough bytes in flight to cover HBM latency -- row offsets and successors
-// are kept as 16-bit offsets relative to the slice, one thread per workflow
-// walks it from its last node to its first, and the results leave through
-// coalesced stores.  A slice too large for LDS is walked in global memory by
-// the same threads.
-__global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a, int wpb)
+// One block takes `wpb` consecutive workflows; their nodes are one contiguous
+// slice.  Every thread stages a few nodes: the cost and the node's (at most
+// CP_DEG) successors, as 8-bit distances to the successor's id, go to LDS --
+// all loads of a stage are issued before the first is used, which keeps
+// enough bytes in flight to cover HBM latency.  Then one lane per workflow
+// walks its nodes from the last to the first; a step costs one LDS round trip
+// because the gathers of a node's successors are unconditional (an empty slot
+// reads entry 0) and the next node's successor word is fetched while
+// the current one is combined.  Finally every thread writes its nodes back
+// (tail is re-derived from the final successors), coalesced.  The launch is
+// sized so that every block is resident at once (no second round of blocks).
+// A slice that does not fit -- more than CP_NMAX nodes, a node with more than
+// CP_DEG successors, a successor more than 255 ids away -- is walked in
+// global memory by the same lanes.
+__global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8)))
+void hx_cp_local_kernel(CpArgs a, int wpb)
 {
-    __shared__ float s_rem[CP_NMAX];          // holds cost, then rem
-    __shared__ float s_tail[CP_NMAX];
-    __shared__ uint16_t s_level[CP_NMAX];
-    __shared__ uint16_t s_row[CP_NMAX + 2];
-    __shared__ uint16_t s_col[CP_EMAX];
-    __shared__ int s_bad;
+    __shared__ float s_rem[CP_NMAX];          // cost until the node is final, then rem
+    __shared__ unsigned s_succ[CP_NMAX];      // 4 x 8-bit distance to each successor, 0 = empty slot
+    __shared__ uint16_t s_lvl[CP_NMAX];
+    __shared__ int s_flag;                    // 1: malformed ranges, 2: slice does not fit
 
     const int tid = threadIdx.x;
     const int w0 = blockIdx.x * wpb;
@@ -102,104 +107,138 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a, int w
     int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
     const int w = w0 + tid;
     int ws = n0, we = n0;                       // threads past the last workflow own no nodes
-    if (w < w1) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
-    if (tid == 0) s_bad = 0;
+    if (tid < wpb && w < w1) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
+    if (tid == 0) s_flag = 0;
     // malformed ranges: clamp so that nothing is read out of bounds, and report
     bool bad = n0 < 0 || n1 > a.n_nodes || n0 > n1 || ws < n0 || we > n1 || ws > we;
     if (bad) { n0 = n1 = ws = we = 0; }
     __syncthreads();
-    if (bad) s_bad = 1;
+    if (bad) s_flag = 1;
     __syncthreads();
-    if (s_bad) {
+    if (s_flag == 1) {
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
-        if (w < w1) a.horizon[w] = 0.0f;
+        if (tid < wpb && w < w1) a.horizon[w] = 0.0f;
         return;
     }
     const int nn = n1 - n0;
-    const bool staged_nodes = nn <= CP_NMAX;
-    // node arrays first: they do not depend on the edge range
-    float c[CP_NPT];
-    int r[CP_NPT + 1];
-    if (staged_nodes) {
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            int i = k * CP_THREADS + tid;
-            c[k] = i < nn ? a.cost[n0 + i] : 0.0f;
-        }
-#pragma unroll
-        for (int k = 0; k <= CP_NPT; ++k) {
-            int i = k * CP_THREADS + tid;
-            r[k] = i <= nn ? a.row_ptr[n0 + i] : 0;
-        }
-    }
-    int e0 = 0, e1 = 0;
-    if (nn > 0) { e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1]; }
-    if (e0 < 0 || e1 > a.n_edges || e0 > e1) {
-        if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
-        if (w < w1) a.horizon[w] = 0.0f;
-        return;
-    }
-    const int ne = e1 - e0;
     float hmax = 0.0f;
-    bool not_dag = false;
+    bool not_dag = false, bad_index = false;
 
-    if (staged_nodes && ne <= CP_EMAX) {
-        int ed[CP_EPT];
-#pragma unroll
-        for (int k = 0; k < CP_EPT; ++k) {
-            int i = k * CP_THREADS + tid;
-            ed[k] = i < ne ? a.col[e0 + i] : -1;
-        }
+    if (nn <= CP_NMAX) {
+        float c[CP_NPT];
+        int r0[CP_NPT], r1[CP_NPT];
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
-            int i = k * CP_THREADS + tid;
-            if (i < nn) s_rem[i] = c[k];
+            const int i = k * CP_THREADS + tid;
+            const bool in = i < nn;
+            c[k] = in ? a.cost[n0 + i] : 0.0f;
+            r0[k] = in ? a.row_ptr[n0 + i] : 0;
+            r1[k] = in ? a.row_ptr[n0 + i + 1] : 0;
         }
+        bool wide = false;
+        // successors in two halves, to hold the registers this stage needs at 4 waves per SIMD
 #pragma unroll
-        for (int k = 0; k <= CP_NPT; ++k) {
-            int i = k * CP_THREADS + tid;
-            if (i <= nn) s_row[i] = (uint16_t)min(max(r[k] - e0, 0), ne);   // a non-monotone row_ptr cannot leave the slice
-        }
+        for (int half = 0; half < 2; ++half) {
+            constexpr int H = CP_NPT / 2;
+            int ed[H][CP_DEG];
 #pragma unroll
-        for (int k = 0; k < CP_EPT; ++k) {
-            int i = k * CP_THREADS + tid;
-            int u = ed[k] - n0;
-            if (i < ne) s_col[i] = (u >= 0 && u < nn) ? (uint16_t)u : (uint16_t)0xffff;   // 0xffff: outside the slice
+            for (int kk = 0; kk < H; ++kk) {
+                const int k = half * H + kk;
+                if (r0[k] < 0 || r1[k] > a.n_edges || r0[k] > r1[k]) { bad_index = true; r1[k] = r0[k] = 0; }
+                wide = wide || (r1[k] - r0[k] > CP_DEG);
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j)
+                    ed[kk][j] = (r0[k] + j < r1[k]) ? a.col[r0[k] + j] : -1;
+            }
+#pragma unroll
+            for (int kk = 0; kk < H; ++kk) {
+                const int k = half * H + kk;
+                const int i = k * CP_THREADS + tid;
+                if (i < nn) {
+                    unsigned word = 0;
+#pragma unroll
+                    for (int j = 0; j < CP_DEG; ++j) {
+                        if (r0[k] + j < r1[k]) {
+                            const int dist = ed[kk][j] - (n0 + i);
+                            // a successor must be a later node, inside this slice
+                            if (dist <= 0 || i + dist >= nn) not_dag = true;
+                            else if (dist > 255) wide = true;
+                            else word |= (unsigned)dist << (8 * j);
+                        }
+                    }
+                    s_rem[i] = c[k];
+                    s_succ[i] = word;
+                }
+            }
         }
-        __syncthreads();
-        if (we > ws) {
+        if (wide) s_flag = 2;
+    } else if (tid == 0) {
+        s_flag = 2;
+    }
+    __syncthreads();
+    const bool staged = s_flag == 0;
+
+    if (staged) {
+        if (we > ws) {                        // lanes of the first wave that own a workflow
             const int lo = ws - n0, hi = we - n0;
-            int r1 = s_row[hi];
+            unsigned nxt = s_succ[hi - 1];
+            float cst = s_rem[hi - 1];
             for (int v = hi - 1; v >= lo; --v) {
-                const int r0 = s_row[v];
+                const unsigned cur = nxt;
+                const float cv = cst;
+                const int vp = max(v - 1, lo);
+                nxt = s_succ[vp];             // fetched while v is combined
+                cst = s_rem[vp];
+                int idx[CP_DEG];
+                bool ok[CP_DEG];
+                unsigned clean = cur;
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) {
+                    const int dist = (cur >> (8 * j)) & 0xff;
+                    ok[j] = dist != 0 && v + dist < hi;          // a successor stays inside the workflow
+                    if (dist != 0 && !ok[j]) clean &= ~(0xffu << (8 * j));
+                    idx[j] = ok[j] ? v + dist : 0;               // empty slots all read entry 0: a broadcast, no bank conflict
+                }
+                float rj[CP_DEG];
+                int lj[CP_DEG];
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) { rj[j] = s_rem[idx[j]]; lj[j] = s_lvl[idx[j]]; }
                 float tl = 0.0f;
                 int lv = 0;
-                for (int e = r0; e < r1; ++e) {
-                    int u = s_col[e];
-                    if (u <= v || u >= hi) { not_dag = true; continue; }   // not a later node of this workflow
-                    tl = fmaxf(tl, s_rem[u]);
-                    lv = max(lv, (int)s_level[u] + 1);
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) {
+                    tl = fmaxf(tl, ok[j] ? rj[j] : 0.0f);
+                    lv = max(lv, ok[j] ? lj[j] + 1 : 0);
                 }
-                float rv = s_rem[v] + tl;
-                s_rem[v] = rv; s_tail[v] = tl; s_level[v] = (uint16_t)lv;
+                const float rv = cv + tl;
+                s_rem[v] = rv;
+                s_lvl[v] = (uint16_t)lv;
+                if (clean != cur) { not_dag = true; s_succ[v] = clean; }
                 hmax = fmaxf(hmax, rv);
-                r1 = r0;
             }
         }
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
-            int i = k * CP_THREADS + tid;
+            const int i = k * CP_THREADS + tid;
             if (i < nn) {
+                const unsigned word = s_succ[i];
+                float tl = 0.0f;
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) {
+                    const int dist = (word >> (8 * j)) & 0xff;
+                    const float rs = s_rem[i + dist];            // dist 0 reads the node itself
+                    tl = fmaxf(tl, dist ? rs : 0.0f);
+                }
                 a.rem[n0 + i] = s_rem[i];
-                a.tail[n0 + i] = s_tail[i];
-                a.level[n0 + i] = s_level[i];
+                a.tail[n0 + i] = tl;
+                a.level[n0 + i] = s_lvl[i];
             }
         }
     } else {
         for (int v = we - 1; v >= ws; --v) {
             int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
-            r0 = min(max(r0, e0), e1); r1 = min(max(r1, r0), e1);
+            if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
             float tl = 0.0f;
             int lv = 0;
             for (int e = r0; e < r1; ++e) {
@@ -213,8 +252,9 @@ __global__ __launch_bounds__(CP_THREADS) void hx_cp_local_kernel(CpArgs a, int w
             hmax = fmaxf(hmax, rv);
         }
     }
-    if (w < w1) a.horizon[w] = hmax;
+    if (tid < wpb && w < w1) a.horizon[w] = hmax;
     if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
+    if (bad_index) hx_raise(a.status, HX_ERR_INDEX);
 }
 
 // ---- critical path, level-synchronous sweeps ------------------------------------------
@@ -441,7 +481,7 @@ extern "C" int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
              ctx->d_status};
     if (max_sweeps == 0) {
         // workflows per block: as many as fit the staged slice at the average workflow size
-        long long fit = n_nodes > 0 ? (long long)(CP_NMAX * 3 / 4) * n_wf / n_nodes : CP_WPB;
+        long long fit = n_nodes > 0 ? (long long)(CP_NMAX * 2 / 3) * n_wf / n_nodes : CP_WPB;
         const int wpb = (int)(fit < 1 ? 1 : (fit > CP_WPB ? CP_WPB : fit));
         const int grid = (n_wf + wpb - 1) / wpb;
         hx_cp_local_kernel<<<grid, CP_THREADS, 0, stream>>>(a, wpb);
