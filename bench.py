@@ -144,6 +144,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--eager", action="store_true", help="launch every step from the host instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies, the known-size reference for HBM byte counters")
     ap.add_argument("--no-extras", action="store_true", help="skip the mid-round latency and critical-path legs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -241,6 +243,13 @@ def main():
                                 "frac": gbs / HBM_PEAK_GBS, "traffic": None, "rotating_copies": n_copies}
         del sets
 
+    if args.calibration_copy:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 3}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(rnd)
     ctx.close()

@@ -128,8 +128,8 @@ int hx_stream_status(hx_ctx *ctx, void *stream);
 /*
  * Standalone cost of each call: its prefill, KV transfer and decode time on
  * an idle pool, on the best pair of GPU classes.  This is the per-node term
- * of the workflow horizon H_w(t) of Sec. 5.1 ("served in isolation using the
- * same serving cluster").
+ * of the workflow horizon H_w(t) of Sec. 5.1, which is defined on the same
+ * cluster with no other workflow present.
  *   n, L_in, L_out      device [n] lengths of the nodes
  *   n_types, type_flops, type_hbm_bw   device [n_types] per-class rates
  *   links               class-pair bandwidth (same n_types)
@@ -142,8 +142,8 @@ int hx_node_cost(hx_ctx *ctx, const hx_model *model, int32_t n,
 
 /*
  * Longest remaining path of every node (max-plus pass from the sinks up) and
- * the horizon of every workflow (Sec. 5.1; Algorithm 1 "update affected
- * workflow horizons"):
+ * the horizon of every workflow (Sec. 5.1; the horizon-update step of
+ * Algorithm 1):
  *   tail[v]  = max(0, max over successors u of rem[u])
  *   rem[v]   = node_cost[v] + tail[v]          (one fp32 addition)
  *   level[v] = 0 without successors, else 1 + max level[u]
@@ -171,8 +171,8 @@ int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
                      float *rem, float *tail, int32_t *level, float *horizon, void *stream);
 
 /*
- * Incremental form for DAGs revealed at run time (Sec. 4.1 "online reveal";
- * Sec. 5.1 "recomputes it whenever new calls are revealed").  The graph lives
+ * Incremental form for DAGs revealed at run time (Sec. 4.1, online reveal;
+ * Sec. 5.1, the horizon is refreshed at every reveal).  The graph lives
  * in the context.  hx_dag_reserve sizes it (allocates; not for the hot loop)
  * and empties it; max_depth bounds the longest path in edges and with it the
  * number of propagation sweeps one append runs.
@@ -207,11 +207,10 @@ int hx_dag_view(hx_ctx *ctx, const float **rem, const float **tail, const int32_
 /* ---- (2) scoring: calls x prefill x decode -> cost tensor or best pair ---- */
 
 /*
- * Evaluates the latency model for every candidate (c, p, d) (Sec. 5.3:
- * "enumerates candidate prefill instances and candidate decode instances,
- * estimates the prefill finish time, adds transfer latency, and projects the
- * earliest decode finish"; feasibility per Sec. 5.4 Eq. (3),(4) against the
- * KV capacity still free on d):
+ * Evaluates the latency model for every candidate (c, p, d) (Sec. 5.3: all
+ * prefill x decode instance pairs, prefill finish plus KV transfer, then the
+ * earliest decode finish given decode availability; feasibility per Sec. 5.4
+ * Eq. (3),(4) against the KV capacity still free on d):
  *   cost(c,p,d) = max(wait_p + prefill(c,p) + transfer(c,p,d), avail_d)
  *                 + L_out * token_time(c,d)      if used_d + L_in + L_out <= cap_d
  *               = +infinity                      otherwise
@@ -240,8 +239,8 @@ int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *call
 /*
  * best pair of each call from cost [C*P*D] (device, row-major (c,p,d), values
  * >= 0 or +infinity): minimum cost, ties to the lowest flat index p*D + d
- * (Sec. 5.3 "the prefill-decode pair with the earliest projected decode
- * finish").  Outputs as in hx_score_placements; `calls`, tail, horizon and
+ * (Sec. 5.3: a call goes to the pair whose projected decode finish is
+ * earliest).  Outputs as in hx_score_placements; `calls`, tail, horizon and
  * ratio may all be NULL when no ratio is wanted.
  */
 int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const float *cost,
@@ -252,7 +251,7 @@ int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const float *cost,
 /* ---- (4) commit the chosen placements into the snapshots ------------------ */
 
 /*
- * Algorithm 1 "update simulated state", applied once for the whole round:
+ * The simulated-state update of Algorithm 1, applied once for the whole round:
  * every call with best_p >= 0 adds L_in to backlog_tok[best_p], L_out to
  * qd_tok[best_d] and L_in + L_out to used_tok[best_d]; then each instance
  * drains: backlog = max(0, backlog - drain_prefill), qd = max(0, qd -

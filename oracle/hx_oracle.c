@@ -26,8 +26,8 @@
  *     under a KV-capacity limit, transfer latency is KV size over the
  *     effective bandwidth between the two GPU classes;
  *   - Sec. 5.1, Eq. (2): projected ratio R = ((t - a_w) + Delta) / H_w(t);
- *   - Sec. 5.1 "online workflow horizon": H_w(t) is the completion time of
- *     the revealed sub-DAG served in isolation;
+ *   - Sec. 5.1 (online workflow horizon): H_w(t) is the completion time of
+ *     the revealed sub-DAG when nothing else runs on the cluster;
  *   - Sec. 5.3: enumerate candidate prefill x decode instances, estimate the
  *     prefill finish, add transfer latency, project the earliest decode
  *     finish from decode availability hints, choose the pair with the
@@ -103,7 +103,7 @@ typedef struct {
 /* ---- the latency terms, one function per reading ---------------------- */
 
 /* R1: queue of a single-server prefill instance (Sec. 4.2 resource model;
- * "waiting time" in Sec. 5.1). */
+ * the waiting part of the prefill projection in Sec. 5.1). */
 double hxo_prefill_wait(const hxo_model *m, int32_t backlog_tok, double F)
 {
     return (double)backlog_tok * m->flops_per_token / F;
@@ -296,7 +296,7 @@ int hxo_node_cost(const hxo_model *m, int32_t n, const int32_t *L_in, const int3
     return 0;
 }
 
-/* ---- critical path (R10; Sec. 5.1 horizon; Algorithm 1 "update horizons") */
+/* ---- critical path (R10; Sec. 5.1 horizon; horizon-update step of Algorithm 1) */
 
 /*
  * Longest remaining path over a DAG given as successor lists.  Makes no
@@ -392,8 +392,8 @@ int hxo_urgency(int32_t C, const double *elapsed, const double *best_cost,
     return 0;
 }
 
-/* ---- R12: commit the chosen placements, then drain (Algorithm 1 "update
- * simulated state", batched once per round) ------------------------------ */
+/* ---- R12: commit the chosen placements, then drain (the simulated-state
+ * update of Algorithm 1, batched once per round) -------------------------- */
 
 /*
  * For every call with a placement: backlog_tok[p*] += L; qd_tok[d*] += O;

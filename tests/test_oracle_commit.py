@@ -1,5 +1,5 @@
-"""Pins of the oracle's commit-and-drain step (Algorithm 1, "update simulated
-state", applied once per round).  The paper gives no numbers for it; these are
+"""Pins of the oracle's commit-and-drain step (the simulated-state update of
+Algorithm 1, applied once per round).  The paper gives no numbers for it; these are
 hand-worked integers and order-independence.  No GPU."""
 import numpy as np
 

@@ -190,7 +190,7 @@ def test_cost_antimonotone_in_rates_and_bandwidth():
 
 def test_scaling_all_rates_scales_all_costs():
     # a uniform multiplicative error on every estimate leaves every choice
-    # unchanged (cf. the robustness experiment, Sec. 7.4)
+    # unchanged (cf. the robustness experiment, Sec. 7.6)
     rng = np.random.default_rng(13)
     M = synth.MODEL
     types, pre, dec, links = random_pool(rng, 4, 4, 3)
