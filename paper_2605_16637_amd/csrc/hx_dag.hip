@@ -72,33 +72,55 @@ struct CpArgs {
     int32_t *status;
 };
 
-constexpr int CP_THREADS = 128;      // threads per block (loads and stores use all of them)
-constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking lane each
-constexpr int CP_NMAX = 2040;        // nodes staged per block; 10 B of LDS each, so 8 blocks fit a CU
+constexpr int CP_THREADS = 256;      // threads per block
+constexpr int CP_WPB = 64;           // at most this many workflows per block: 16 per wave, 4 lanes each
+constexpr int CP_NMAX = 2000;        // nodes staged per block; 10 B of LDS each
 constexpr int CP_NPT = (CP_NMAX + CP_THREADS - 1) / CP_THREADS;
-static_assert(CP_NPT % 2 == 0, "the staging loop splits a thread's nodes in two halves");
-constexpr int CP_DEG = 4;            // successors held inline per staged node
+constexpr int CP_DEG = 4;            // successors held inline per staged node, one per lane of a quad
+constexpr int CP_EMAX = 2 * CP_NMAX;  // edges staged per block (16-bit each, in the space of s_rem)
+constexpr int CP_EPT = (CP_EMAX + CP_THREADS - 1) / CP_THREADS;
+
+// max over the 4 lanes of a quad, by two DPP lane swaps (no LDS traffic)
+__device__ __forceinline__ float hx_quad_max(float x)
+{
+    int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+    x = fmaxf(x, __int_as_float(y));
+    y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false);       // quad_perm [2,3,0,1]
+    return fmaxf(x, __int_as_float(y));
+}
+
+__device__ __forceinline__ int hx_quad_max(int x)
+{
+    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, false));
+    return max(x, __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, false));
+}
 
 // One block takes `wpb` consecutive workflows; their nodes are one contiguous
-// slice.  Every thread stages a few nodes: the cost and the node's (at most
-// CP_DEG) successors, as 8-bit distances to the successor's id, go to LDS --
-// all loads of a stage are issued before the first is used, which keeps
-// enough bytes in flight to cover HBM latency.  Then one lane per workflow
-// walks its nodes from the last to the first; a step costs one LDS round trip
-// because the gathers of a node's successors are unconditional (an empty slot
-// reads entry 0) and the next node's successor word is fetched while
-// the current one is combined.  Finally every thread writes its nodes back
-// (tail is re-derived from the final successors), coalesced.  The launch is
-// sized so that every block is resident at once (no second round of blocks).
-// A slice that does not fit -- more than CP_NMAX nodes, a node with more than
-// CP_DEG successors, a successor more than 255 ids away -- is walked in
-// global memory by the same lanes.
-__global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(4, 8)))
+// slice.
+//  stage  The slice's cost, row offsets and successor ids are read flat and
+//         coalesced, all loads of a step issued before the first is used
+//         (enough bytes in flight to cover HBM latency).  Successor ids are
+//         parked in LDS as 16-bit offsets; every thread then packs, for a few
+//         nodes, the (at most CP_DEG) successors as 8-bit distances to the
+//         successor's id.  Edges are checked here (successor later than the
+//         node, inside the node's own workflow), so the walk needs no checks.
+//  walk   Four lanes per workflow walk its nodes from the last to the first;
+//         lane j of the quad gathers successor slot j, two DPP swaps combine
+//         the quad.  A step costs one LDS round trip: empty slots read a zero
+//         entry, and the next node's successor word and cost are fetched
+//         while the current node is combined.
+//  store  Every thread writes its nodes back (tail is re-derived from the
+//         final successors), coalesced.
+// A slice that does not fit -- more than CP_NMAX nodes or CP_EMAX edges, a
+// node with more than CP_DEG successors, a successor more than 255 ids away --
+// is walked in global memory, one lane per workflow.
+__global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
 void hx_cp_local_kernel(CpArgs a, int wpb)
 {
-    __shared__ float s_rem[CP_NMAX];          // cost until the node is final, then rem
+    __shared__ float s_rem[CP_NMAX + 1];      // cost until the node is final, then rem; [CP_NMAX] = 0
     __shared__ unsigned s_succ[CP_NMAX];      // 4 x 8-bit distance to each successor, 0 = empty slot
-    __shared__ uint16_t s_lvl[CP_NMAX];
+    __shared__ uint16_t s_lvl[CP_NMAX + 2];   // workflow end while staging, then level + 1; [CP_NMAX] = 0
+    __shared__ uint16_t s_wlo[CP_WPB], s_whi[CP_WPB];
     __shared__ int s_flag;                    // 1: malformed ranges, 2: slice does not fit
 
     const int tid = threadIdx.x;
@@ -106,9 +128,10 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
     const int w1 = min(w0 + wpb, a.n_wf);
     int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
     const int w = w0 + tid;
-    int ws = n0, we = n0;                       // threads past the last workflow own no nodes
-    if (tid < wpb && w < w1) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
-    if (tid == 0) s_flag = 0;
+    const bool owner = tid < wpb && w < w1;     // this thread loads workflow w's range
+    int ws = n0, we = n0;
+    if (owner) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
+    if (tid == 0) { s_flag = 0; s_rem[CP_NMAX] = 0.0f; s_lvl[CP_NMAX] = 0; }
     // malformed ranges: clamp so that nothing is read out of bounds, and report
     bool bad = n0 < 0 || n1 > a.n_nodes || n0 > n1 || ws < n0 || we > n1 || ws > we;
     if (bad) { n0 = n1 = ws = we = 0; }
@@ -117,14 +140,14 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
     __syncthreads();
     if (s_flag == 1) {
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
-        if (tid < wpb && w < w1) a.horizon[w] = 0.0f;
+        if (owner) a.horizon[w] = 0.0f;
         return;
     }
     const int nn = n1 - n0;
-    float hmax = 0.0f;
     bool not_dag = false, bad_index = false;
 
     if (nn <= CP_NMAX) {
+        // step 1: cost and row offsets of this thread's nodes, and the edge range of the slice
         float c[CP_NPT];
         int r0[CP_NPT], r1[CP_NPT];
 #pragma unroll
@@ -135,87 +158,94 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
             r0[k] = in ? a.row_ptr[n0 + i] : 0;
             r1[k] = in ? a.row_ptr[n0 + i + 1] : 0;
         }
-        bool wide = false;
-        // successors in two halves, to hold the registers this stage needs at 4 waves per SIMD
+        int e0 = 0, e1 = 0;
+        if (nn > 0) { e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1]; }
+        if (e0 < 0 || e1 > a.n_edges || e0 > e1) { bad_index = true; e0 = e1 = 0; }
+        const int ne = e1 - e0;
+        // while those loads fly: every workflow marks its nodes with its end
+        if (tid < wpb) {
+            s_wlo[tid] = (uint16_t)(ws - n0);
+            s_whi[tid] = (uint16_t)(we - n0);
+            for (int v = ws - n0; v < we - n0; ++v) s_lvl[v] = (uint16_t)(we - n0);
+        }
+        // step 2: the slice's successor ids, flat and coalesced, parked in LDS as
+        // 16-bit offsets into the slice (in the space s_rem takes over afterwards)
+        uint16_t *s_col = reinterpret_cast<uint16_t *>(s_rem);
+        const bool fits = ne <= CP_EMAX;
+        int ed[CP_EPT];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            constexpr int H = CP_NPT / 2;
-            int ed[H][CP_DEG];
+        for (int k = 0; k < CP_EPT; ++k) {
+            const int i = k * CP_THREADS + tid;
+            ed[k] = (fits && i < ne) ? a.col[e0 + i] : -1;
+        }
 #pragma unroll
-            for (int kk = 0; kk < H; ++kk) {
-                const int k = half * H + kk;
-                if (r0[k] < 0 || r1[k] > a.n_edges || r0[k] > r1[k]) { bad_index = true; r1[k] = r0[k] = 0; }
-                wide = wide || (r1[k] - r0[k] > CP_DEG);
+        for (int k = 0; k < CP_EPT; ++k) {
+            const int i = k * CP_THREADS + tid;
+            const int rel = ed[k] - n0;
+            if (fits && i < ne) s_col[i] = (rel >= 0 && rel < nn) ? (uint16_t)rel : (uint16_t)0xffff;
+        }
+        __syncthreads();
+        // step 3: per node, its successors as 8-bit distances, checked
+        bool wide = !fits;
+        unsigned word[CP_NPT];
 #pragma unroll
-                for (int j = 0; j < CP_DEG; ++j)
-                    ed[kk][j] = (r0[k] + j < r1[k]) ? a.col[r0[k] + j] : -1;
-            }
+        for (int k = 0; k < CP_NPT; ++k) {
+            const int i = k * CP_THREADS + tid;
+            word[k] = 0;
+            if (i < nn && fits) {
+                int b = r0[k] - e0, d = r1[k] - r0[k];
+                if (b < 0 || d < 0 || b + d > ne) { bad_index = true; d = 0; }
+                wide = wide || d > CP_DEG;
+                const int end = s_lvl[i];         // end of node i's workflow
 #pragma unroll
-            for (int kk = 0; kk < H; ++kk) {
-                const int k = half * H + kk;
-                const int i = k * CP_THREADS + tid;
-                if (i < nn) {
-                    unsigned word = 0;
-#pragma unroll
-                    for (int j = 0; j < CP_DEG; ++j) {
-                        if (r0[k] + j < r1[k]) {
-                            const int dist = ed[kk][j] - (n0 + i);
-                            // a successor must be a later node, inside this slice
-                            if (dist <= 0 || i + dist >= nn) not_dag = true;
-                            else if (dist > 255) wide = true;
-                            else word |= (unsigned)dist << (8 * j);
-                        }
+                for (int j = 0; j < CP_DEG; ++j) {
+                    if (j < d) {
+                        const int dist = (int)s_col[b + j] - i;
+                        // a successor must be a later node of the same workflow
+                        if (dist <= 0 || i + dist >= end) not_dag = true;
+                        else if (dist > 255) wide = true;
+                        else word[k] |= (unsigned)dist << (8 * j);
                     }
-                    s_rem[i] = c[k];
-                    s_succ[i] = word;
                 }
             }
+        }
+        __syncthreads();                      // every read of s_col is done: s_rem takes its place
+#pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            const int i = k * CP_THREADS + tid;
+            if (i < nn) { s_rem[i] = c[k]; s_succ[i] = word[k]; }
         }
         if (wide) s_flag = 2;
     } else if (tid == 0) {
         s_flag = 2;
     }
     __syncthreads();
-    const bool staged = s_flag == 0;
 
-    if (staged) {
-        if (we > ws) {                        // lanes of the first wave that own a workflow
-            const int lo = ws - n0, hi = we - n0;
-            unsigned nxt = s_succ[hi - 1];
-            float cst = s_rem[hi - 1];
-            for (int v = hi - 1; v >= lo; --v) {
-                const unsigned cur = nxt;
-                const float cv = cst;
-                const int vp = max(v - 1, lo);
-                nxt = s_succ[vp];             // fetched while v is combined
-                cst = s_rem[vp];
-                int idx[CP_DEG];
-                bool ok[CP_DEG];
-                unsigned clean = cur;
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) {
-                    const int dist = (cur >> (8 * j)) & 0xff;
-                    ok[j] = dist != 0 && v + dist < hi;          // a successor stays inside the workflow
-                    if (dist != 0 && !ok[j]) clean &= ~(0xffu << (8 * j));
-                    idx[j] = ok[j] ? v + dist : 0;               // empty slots all read entry 0: a broadcast, no bank conflict
+    if (s_flag == 0) {
+        const int q = tid >> 2, j = tid & 3;          // workflow of this quad, successor slot of this lane
+        if (q < wpb) {
+            const int lo = s_wlo[q], hi = s_whi[q];
+            float hmax = 0.0f;
+            if (hi > lo) {
+                const int shift = 8 * j;
+                unsigned nxt = s_succ[hi - 1];
+                float cst = s_rem[hi - 1];
+                for (int v = hi - 1; v >= lo; --v) {
+                    const unsigned cur = nxt;
+                    const float cv = cst;
+                    const int vp = max(v - 1, lo);
+                    nxt = s_succ[vp];                 // fetched while v is combined
+                    cst = s_rem[vp];
+                    const int dist = (cur >> shift) & 0xff;
+                    const int idx = dist ? v + dist : CP_NMAX;     // empty slot: the zero entry
+                    const float tl = hx_quad_max(s_rem[idx]);
+                    const int lv = hx_quad_max((int)s_lvl[idx]);    // successors hold level + 1
+                    const float rv = cv + tl;
+                    if (j == 0) { s_rem[v] = rv; s_lvl[v] = (uint16_t)(lv + 1); }
+                    hmax = fmaxf(hmax, rv);
                 }
-                float rj[CP_DEG];
-                int lj[CP_DEG];
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) { rj[j] = s_rem[idx[j]]; lj[j] = s_lvl[idx[j]]; }
-                float tl = 0.0f;
-                int lv = 0;
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) {
-                    tl = fmaxf(tl, ok[j] ? rj[j] : 0.0f);
-                    lv = max(lv, ok[j] ? lj[j] + 1 : 0);
-                }
-                const float rv = cv + tl;
-                s_rem[v] = rv;
-                s_lvl[v] = (uint16_t)lv;
-                if (clean != cur) { not_dag = true; s_succ[v] = clean; }
-                hmax = fmaxf(hmax, rv);
             }
+            if (j == 0 && w0 + q < w1) a.horizon[w0 + q] = hmax;
         }
         __syncthreads();
 #pragma unroll
@@ -225,17 +255,17 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
                 const unsigned word = s_succ[i];
                 float tl = 0.0f;
 #pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) {
-                    const int dist = (word >> (8 * j)) & 0xff;
-                    const float rs = s_rem[i + dist];            // dist 0 reads the node itself
-                    tl = fmaxf(tl, dist ? rs : 0.0f);
+                for (int jj = 0; jj < CP_DEG; ++jj) {
+                    const int dist = (word >> (8 * jj)) & 0xff;
+                    tl = fmaxf(tl, s_rem[dist ? i + dist : CP_NMAX]);
                 }
                 a.rem[n0 + i] = s_rem[i];
                 a.tail[n0 + i] = tl;
-                a.level[n0 + i] = s_lvl[i];
+                a.level[n0 + i] = (int)s_lvl[i] - 1;
             }
         }
     } else {
+        float hmax = 0.0f;
         for (int v = we - 1; v >= ws; --v) {
             int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
             if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
@@ -251,8 +281,8 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
             a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
             hmax = fmaxf(hmax, rv);
         }
+        if (owner) a.horizon[w] = hmax;
     }
-    if (tid < wpb && w < w1) a.horizon[w] = hmax;
     if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
     if (bad_index) hx_raise(a.status, HX_ERR_INDEX);
 }
