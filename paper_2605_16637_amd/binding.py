@@ -80,10 +80,26 @@ def _torch():
     return torch
 
 
+class RawArray:
+    """A device array known only by address (e.g. one returned by hx_dag_view)."""
+
+    def __init__(self, addr: int, numel: int, dtype):
+        self.addr, self._n, self.dtype = int(addr), int(numel), dtype
+
+    def numel(self):
+        return self._n
+
+
 def _ptr(t, dtype=None, n=None):
     """Device pointer of a contiguous CUDA tensor (None -> NULL), after checks."""
     if t is None:
         return None
+    if isinstance(t, RawArray):
+        if dtype is not None and t.dtype != dtype:
+            raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+        if n is not None and t.numel() < n:
+            raise ValueError(f"array has {t.numel()} elements, {n} needed")
+        return C.c_void_p(t.addr)
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous tensor in device memory")
     if dtype is not None and t.dtype != dtype:
@@ -197,13 +213,17 @@ class Context:
                                            _ptr(parent_col_idx, torch.int32), _ptr(new_cost, torch.float32),
                                            _ptr(new_wf, torch.int32, n_new), _stream(stream)))
 
-    def hx_dag_view(self):
-        """Raw device addresses (rem, tail, level, horizon) and the node count."""
+    def hx_dag_view(self, n_wf: int):
+        """(rem, tail, level, horizon) of the context's graph as borrowed RawArray
+        views (rem/tail/level over the nodes appended so far, horizon over the
+        first n_wf workflows) and the node count."""
+        torch = _torch()
         rem, tail, level, hor = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
         n = C.c_int32()
         self._check(self.lib.hx_dag_view(self._ctx, C.byref(rem), C.byref(tail), C.byref(level),
                                          C.byref(hor), C.byref(n)))
-        return rem.value, tail.value, level.value, hor.value, n.value
+        return (RawArray(rem.value, n.value, torch.float32), RawArray(tail.value, n.value, torch.float32),
+                RawArray(level.value, n.value, torch.int32), RawArray(hor.value, n_wf, torch.float32), n.value)
 
     def hx_score_placements(self, model, calls, prefill, decode, links, tail=None, horizon=None,
                             cost=None, feas=None, best_p=None, best_d=None, best_cost=None, ratio=None,

@@ -137,24 +137,23 @@ def test_sweeps_accept_any_numbering_and_report_cycles(ctx):
         ctx.hx_stream_status()
 
 
-def view(ctx, n, n_wf):
-    """Copy the context's graph arrays to the host (ctypes pointers -> torch via a device copy)."""
+def fetch(raw):
+    """Copy a borrowed device array of the context to the host (device-to-device copy into a tensor first)."""
     import ctypes
     import torch
-    rem_p, tail_p, level_p, hor_p, n_nodes = ctx.hx_dag_view()
+    out = torch.empty(raw.numel(), dtype=raw.dtype, device="cuda:0")
+    if raw.numel():
+        torch.cuda.synchronize()
+        hip = ctypes.CDLL("libamdhip64.so")
+        rc = hip.hipMemcpy(ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(raw.addr), ctypes.c_size_t(raw.numel() * 4), 3)
+        assert rc == 0
+    return out.cpu().numpy()
+
+
+def view(ctx, n, n_wf):
+    rem, tail, level, hor, n_nodes = ctx.hx_dag_view(n_wf)
     assert n_nodes == n
-
-    def fetch(ptr, count, dtype):
-        out = torch.empty(count, dtype=dtype, device="cuda:0")
-        if count:
-            torch.cuda.synchronize()
-            hip = ctypes.CDLL("libamdhip64.so")
-            rc = hip.hipMemcpy(ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(ptr), ctypes.c_size_t(count * 4), 3)
-            assert rc == 0
-        return out.cpu().numpy()
-
-    return (fetch(rem_p, n, torch.float32), fetch(tail_p, n, torch.float32),
-            fetch(level_p, n, torch.int32), fetch(hor_p, n_wf, torch.float32))
+    return fetch(rem), fetch(tail), fetch(level), fetch(hor)
 
 
 @pytest.mark.parametrize("seed,n_live,rounds", [(1, 40, 12), (2, 700, 8)])

@@ -1,0 +1,155 @@
+"""GPU parity of whole scheduling rounds, and of rounds replayed from a HIP graph.
+
+Streaming: every round reveals new calls (hx_node_cost -> hx_dag_append), scores
+them against the current pool snapshot (hx_score_placements with the projected
+ratio) and commits the chosen placements (hx_commit).  The oracle runs the same
+rounds on its own state; it adopts the GPU's pair for a call only after checking
+that the oracle's cost of that pair is within tolerance of the oracle's best."""
+import numpy as np
+import pytest
+
+from oracle import hx_oracle as o
+from paper_2605_16637_amd import synth
+from gpu_helpers import REL, assert_costs_close, assert_search_matches, dev, dev_tables
+from test_gpu_dag import fetch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2605_16637_amd import binding
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("seed,n_live,rounds,P,D", [(1, 300, 25, 64, 64), (2, 60, 40, 20, 33)])
+def test_streaming_rounds(ctx, seed, n_live, rounds, P, D):
+    import torch
+    from paper_2605_16637_amd import binding
+    model = synth.MODEL
+    gen = synth.StreamGen(seed, n_live, final_lo=6, final_hi=20)
+    rng = np.random.default_rng(100 + seed)
+    L0, O0 = synth.gen_lengths(rng, 4000)
+    types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
+    d_links = binding.to_device(links)
+    d_pre, d_dec = binding.to_device(pre), binding.to_device(dec)
+    tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
+    ctx.hx_dag_reserve(400000, 600000, 100000, 24)
+    # oracle-side state
+    o_pre = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in pre.items()}
+    o_dec = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in dec.items()}
+    prow = np.zeros(1, np.int32); pcol = np.zeros(0, np.int32)
+    cost_all = np.zeros(0, np.float64); wf_all = np.zeros(0, np.int32)
+    n_diff = n_calls = 0
+    for r in range(rounds):
+        b = gen.next_batch()
+        n_new, n_wf = b["n_new"], b["n_wf_total"]
+        # reveal: node cost of the new calls, append
+        g_cost = torch.empty(n_new, device="cuda:0")
+        ctx.hx_node_cost(model, dev(b["L_in"]), dev(b["L_out"]), tF, tB, d_links, g_cost)
+        ctx.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), g_cost, dev(b["wf"]))
+        g_rem, g_tail, g_level, g_hor, n_nodes = ctx.hx_dag_view(n_wf)
+        # the ready calls of the round are the calls just revealed
+        elapsed = rng.uniform(0, 30, n_new).astype(np.float32)
+        calls = dict(n=n_new, L_in=dev(b["L_in"]), L_out=dev(b["L_out"]), node=dev(b["ids"]), wf=dev(b["wf"]),
+                     elapsed=dev(elapsed))
+        bp = torch.empty(n_new, dtype=torch.int32, device="cuda:0"); bd = torch.empty_like(bp)
+        bc = torch.empty(n_new, device="cuda:0"); ratio = torch.empty(n_new, device="cuda:0")
+        ctx.hx_score_placements(model, calls, d_pre, d_dec, d_links, tail=g_tail, horizon=g_hor,
+                                best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+        # drains sized to what the round adds, so the pool stays in its regime
+        Ls, Os = int(b["L_in"].sum()), int(b["L_out"].sum())
+        dp = np.full(P, Ls // P, np.int32); dq = np.full(D, Os // D, np.int32); rl = np.full(D, (Ls + Os) // D, np.int32)
+        ctx.hx_commit(calls, bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"],
+                      dev(dp), dev(dq), dev(rl))
+        ctx.hx_stream_status()
+
+        # the same round on the oracle's own state
+        o_cost = o.node_cost(model, b["L_in"], b["L_out"], types, links)
+        prow = np.concatenate([prow, prow[-1] + b["parent_row_ptr"][1:]]).astype(np.int32)
+        pcol = np.concatenate([pcol, b["parent_col"]]); cost_all = np.concatenate([cost_all, o_cost])
+        wf_all = np.concatenate([wf_all, b["wf"]])
+        rem, tail, level, hor = o.critical_path_by_parents(prow, pcol, cost_all, wf_all, n_wf, round_f32=False)
+        assert n_nodes == cost_all.size
+        assert np.array_equal(fetch(g_level), level)
+        assert_costs_close(fetch(g_rem), rem, "rem"); assert_costs_close(fetch(g_hor), hor, "horizon")
+        ores = o.score(model, b["L_in"], b["L_out"], o_pre, o_dec, links)
+        gp, gd, gc = bp.cpu().numpy(), bd.cpu().numpy(), bc.cpu().numpy()
+        n_diff += assert_search_matches(model, b["L_in"], b["L_out"], o_pre, o_dec, links, ores, gp, gd, gc)
+        n_calls += n_new
+        want_ratio = o.urgency(elapsed, ores.best_cost, b["ids"], b["wf"], tail, hor)
+        assert_costs_close(ratio.cpu().numpy(), want_ratio, "ratio")
+        # commit on the oracle's state with the (validated) pairs; integer state must agree exactly
+        bl, us, ba, qd, rc = o.commit(b["L_in"], b["L_out"], gp, gd, o_pre["backlog_tok"], o_dec["used_tok"],
+                                      o_dec["batch"], o_dec["qd_tok"], dp, dq, rl)
+        assert rc == 0
+        o_pre["backlog_tok"], o_dec["used_tok"], o_dec["batch"], o_dec["qd_tok"] = bl, us, ba, qd
+        assert np.array_equal(d_pre["backlog_tok"].cpu().numpy(), bl)
+        assert np.array_equal(d_dec["used_tok"].cpu().numpy(), us)
+        assert np.array_equal(d_dec["batch"].cpu().numpy(), ba)
+        assert np.array_equal(d_dec["qd_tok"].cpu().numpy(), qd)
+    assert n_diff <= max(3, n_calls // 200)
+    assert (ores.best_p < 0).mean() < 0.9       # the pool did not drift into "nothing fits"
+
+
+def test_round_replayed_from_a_hip_graph(ctx):
+    # the benchmark replays a captured round; every replay must equal the eager
+    # result, with eager work and synchronisation between replays
+    import torch
+    rnd = synth.make_round("mid", 5)
+    d = rnd.dag
+    calls, pre, dec, links = dev_tables(rnd)
+    from paper_2605_16637_amd import binding
+    tF, tB = dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"])
+    L_in, L_out = dev(d.L_in), dev(d.L_out)
+    rp, col, wp = dev(d.succ_row_ptr), dev(d.succ_col), dev(d.wf_ptr)
+    f32 = dict(dtype=torch.float32, device="cuda:0"); i32 = dict(dtype=torch.int32, device="cuda:0")
+    cost = torch.empty(d.n_nodes, **f32); rem = torch.empty(d.n_nodes, **f32); tail = torch.empty(d.n_nodes, **f32)
+    level = torch.empty(d.n_nodes, **i32); hor = torch.empty(d.n_wf, **f32)
+    n = rnd.calls["n"]
+    bp = torch.empty(n, **i32); bd = torch.empty(n, **i32); bc = torch.empty(n, **f32); ratio = torch.empty(n, **f32)
+    state0 = [pre["backlog_tok"].clone(), dec["used_tok"].clone(), dec["batch"].clone(), dec["qd_tok"].clone()]
+    drain_p = torch.full((rnd.pre["n"],), 70000, **i32); drain_q = torch.full((rnd.dec["n"],), 15000, **i32)
+    release = torch.full((rnd.dec["n"],), 90000, **i32)
+
+    def reset():
+        for t, s in zip((pre["backlog_tok"], dec["used_tok"], dec["batch"], dec["qd_tok"]), state0):
+            t.copy_(s)
+        for t in (cost, rem, tail, hor, bc, ratio):
+            t.fill_(-1.0)
+        for t in (level, bp, bd):
+            t.fill_(-1)
+
+    def one_round():
+        ctx.hx_node_cost(rnd.model, L_in, L_out, tF, tB, links, cost)
+        ctx.hx_critical_path(rp, col, cost, wp, rem, tail, level, hor)
+        ctx.hx_score_placements(rnd.model, calls, pre, dec, links, tail=tail, horizon=hor,
+                                best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+        ctx.hx_commit(calls, bp, bd, pre["backlog_tok"], dec["used_tok"], dec["batch"], dec["qd_tok"],
+                      drain_p, drain_q, release)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.cpu().numpy().copy() for t in (cost, rem, tail, level, hor, bp, bd, bc, ratio,
+                                                 pre["backlog_tok"], dec["used_tok"], dec["batch"], dec["qd_tok"])]
+
+    reset(); one_round(); one_round()                 # two eager rounds: the second sees the committed state
+    want = snapshot()
+    ctx.hx_stream_status()
+    g = torch.cuda.CUDAGraph()
+    reset()
+    with torch.cuda.graph(g):
+        one_round()
+    for rep in range(3):
+        reset()
+        torch.cuda.synchronize()
+        g.replay(); g.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b), f"replay {rep} differs from the eager rounds"
+        ctx.hx_stream_status()
+        # eager work of the program between replays
+        one_round()
+        torch.cuda.synchronize()
