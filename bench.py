@@ -116,6 +116,66 @@ def time_launches(torch, fn, reps, warmup=5):
     return e0.elapsed_time(e1) / reps * 1e-3
 
 
+def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=32768, P=512, D=512):
+    """Rounds of a live system: reveal (node cost + append), score the ready calls
+    with their projected ratio, commit.  Every batch is resident before the clock starts."""
+    rng = np.random.default_rng(seed)
+    gen = synth.StreamGen(seed, n_live)
+    L0, O0 = synth.gen_lengths(rng, 50000)
+    types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
+    d_links, d_pre, d_dec = binding.to_device(links), binding.to_device(pre), binding.to_device(dec)
+    tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
+    warm = 3
+    batches, n_nodes, n_edges = [], 0, 0
+    for _ in range(rounds + warm):
+        b = gen.next_batch()
+        n = b["n_new"]
+        pick = np.sort(rng.choice(n, min(C, n), replace=False)).astype(np.int32)
+        Ls, Os = int(b["L_in"][pick].sum()), int(b["L_out"][pick].sum())
+        batches.append(dict(
+            n_new=n, n_wf=b["n_wf_total"], prow=dev(b["parent_row_ptr"]), pcol=dev(b["parent_col"]), wf=dev(b["wf"]),
+            L_in=dev(b["L_in"]), L_out=dev(b["L_out"]), cost=torch.empty(n, device="cuda:0"),
+            calls=dict(n=int(pick.size), L_in=dev(b["L_in"][pick]), L_out=dev(b["L_out"][pick]), node=dev(b["ids"][pick]),
+                       wf=dev(b["wf"][pick]), elapsed=dev(rng.uniform(0, 30, pick.size).astype(np.float32))),
+            drain_p=dev(np.full(P, Ls // P, np.int32)), drain_q=dev(np.full(D, Os // D, np.int32)),
+            release=dev(np.full(D, (Ls + Os) // D, np.int32))))
+        n_nodes += n; n_edges += int(b["parent_col"].size)
+    ctx.hx_dag_reserve(n_nodes + 16, n_edges + 16, gen.n_wf + 16, 32)
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    bp, bd = torch.empty(C, **i32), torch.empty(C, **i32)
+    bc, ratio = torch.empty(C, device="cuda:0"), torch.empty(C, device="cuda:0")
+
+    def one(b):
+        ctx.hx_node_cost(synth.MODEL, b["L_in"], b["L_out"], tF, tB, d_links, b["cost"])
+        ctx.hx_dag_append(b["prow"], b["pcol"], b["cost"], b["wf"])
+        _, tail, _, hor, _ = ctx.hx_dag_view(b["n_wf"])
+        ctx.hx_score_placements(synth.MODEL, b["calls"], d_pre, d_dec, d_links, tail=tail, horizon=hor,
+                                best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+        ctx.hx_commit(b["calls"], bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"],
+                      b["drain_p"], b["drain_q"], b["release"])
+
+    for b in batches[:warm]:
+        one(b)
+    torch.cuda.synchronize()
+    lat, cand = [], 0
+    t_all = time.perf_counter()
+    for b in batches[warm:]:
+        t0 = time.perf_counter()
+        one(b)
+        torch.cuda.synchronize()
+        lat.append((time.perf_counter() - t0) * 1e6)
+        cand += b["calls"]["n"] * P * D
+    wall = time.perf_counter() - t_all
+    ctx.hx_stream_status()
+    placed = float((bp >= 0).float().mean().item())
+    lat = np.array(lat)
+    return {"workload": "streaming rounds: %d live workflows, +0..8 calls per workflow per round, %d ready calls x %d x %d, 8 classes"
+                        % (n_live, C, P, D),
+            "rounds": rounds, "candidates_per_round": C * P * D, "new_nodes_per_round": n_nodes / (rounds + warm),
+            "p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
+            "candidates_per_s": cand / wall, "placed_fraction_last_round": placed, "launch": "eager, synchronised every round"}
+
+
 def cpu_baseline(rnd, target_s=12.0):
     """The oracle, as it stands, on a bounded sample of the same round."""
     from oracle import hx_oracle as o
@@ -243,6 +303,8 @@ def main():
                                 "frac": gbs / HBM_PEAK_GBS, "traffic": None, "rotating_copies": n_copies}
         del sets
 
+    if not args.no_extras:
+        out["streaming"] = streaming_leg(torch, ctx, synth, binding, args.seed, rounds=30)
     if args.calibration_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").fill_(1.0)
         dst = torch.empty_like(src)
