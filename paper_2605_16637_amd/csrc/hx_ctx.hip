@@ -32,11 +32,40 @@ __global__ __launch_bounds__(256) void hx_commit_clear_kernel(CommitArgs a)
     if (i < a.P + 2 * a.D) a.acc[i] = 0ull;
 }
 
+// sum of x over the lanes of `members` (all lanes of the wave take part)
+__device__ __forceinline__ unsigned long long hx_wave_sum(unsigned long long x)
+{
+#pragma unroll
+    for (int off = HX_WAVE / 2; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+// Adds, per distinct key among the lanes of the wave, the lanes' values into
+// acc[key] with one LDS atomic per key (chosen placements concentrate on a few
+// instances: 64 atomics on one address would serialise).
+__device__ __forceinline__ void hx_add_by_key(unsigned long long *acc, bool valid, int key,
+                                              unsigned long long v0, unsigned long long *acc1, unsigned long long v1)
+{
+    unsigned long long todo = __ballot(valid);
+    const int lane = threadIdx.x & (HX_WAVE - 1);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int k = __shfl(key, leader);
+        const bool mine = valid && key == k;
+        const unsigned long long s0 = hx_wave_sum(mine ? v0 : 0ull);
+        const unsigned long long s1 = acc1 ? hx_wave_sum(mine ? v1 : 0ull) : 0ull;
+        if (lane == leader) {
+            atomicAdd(&acc[k], s0);
+            if (acc1) atomicAdd(&acc1[k], s1);
+        }
+        todo &= ~__ballot(mine);
+    }
+}
+
 // The state update of Algorithm 1 for all calls of the round at once: integer
-// additions commute, so the result does not depend on call order.  Chosen
-// placements concentrate on a few instances, so every block first sums into an
-// LDS copy of the counters and only then adds its non-zero sums to the global
-// ones (a handful of global atomics per block instead of three per call).
+// additions commute, so the result does not depend on call order.  Every wave
+// first combines its calls per instance, every block sums into an LDS copy of
+// the counters, and only the non-zero sums reach the global accumulators.
 __global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
 {
     __shared__ unsigned long long s_acc[3 * HX_MAX_INSTANCES];
@@ -44,15 +73,17 @@ __global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
     for (int i = threadIdx.x; i < n_acc; i += blockDim.x) s_acc[i] = 0ull;
     __syncthreads();
     bool bad = false;
-    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < a.C; c += gridDim.x * blockDim.x) {
-        const int p = a.best_p[c], d = a.best_d[c];
-        if (p < 0 || d < 0) continue;                       // the call stays queued
-        if (p >= a.P || d >= a.D) { bad = true; continue; }
-        const int L = a.L_in[c], O = a.L_out[c];
-        if (L < 0 || O < 0) { bad = true; continue; }
-        atomicAdd(&s_acc[p], (unsigned long long)L);
-        atomicAdd(&s_acc[a.P + d], (unsigned long long)L + (unsigned long long)O);
-        atomicAdd(&s_acc[a.P + a.D + d], (unsigned long long)O);
+    const int stride = gridDim.x * blockDim.x;
+    const int rounds = (a.C + stride - 1) / stride;          // the same trip count for every lane of a wave
+    for (int it = 0; it < rounds; ++it) {
+        const int c = it * stride + blockIdx.x * blockDim.x + threadIdx.x;
+        int p = -1, d = -1, L = 0, O = 0;
+        if (c < a.C) { p = a.best_p[c]; d = a.best_d[c]; L = a.L_in[c]; O = a.L_out[c]; }
+        bool valid = p >= 0 && d >= 0;                      // otherwise the call stays queued
+        if (valid && (p >= a.P || d >= a.D || L < 0 || O < 0)) { bad = true; valid = false; }
+        hx_add_by_key(s_acc, valid, p, (unsigned long long)L, nullptr, 0ull);
+        hx_add_by_key(s_acc + a.P, valid, d, (unsigned long long)L + (unsigned long long)O,
+                      s_acc + a.P + a.D, (unsigned long long)O);
     }
     if (bad) hx_raise(a.status, HX_ERR_INDEX);
     __syncthreads();
@@ -70,13 +101,18 @@ __device__ __forceinline__ int hx_add_sat_drain(int cur, unsigned long long add,
 
 __global__ __launch_bounds__(256) void hx_commit_drain_kernel(CommitArgs a)
 {
+    // the accumulators are left at zero for the next round
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < a.P)
+    if (i < a.P) {
         a.backlog[i] = hx_add_sat_drain(a.backlog[i], a.acc[i], a.drain_p ? a.drain_p[i] : 0, a.status);
+        a.acc[i] = 0ull;
+    }
     if (i < a.D) {
         a.qd[i] = hx_add_sat_drain(a.qd[i], a.acc[a.P + a.D + i], a.drain_q ? a.drain_q[i] : 0, a.status);
         const int used = hx_add_sat_drain(a.used[i], a.acc[a.P + i], a.release ? a.release[i] : 0, a.status);
         a.used[i] = used;
+        a.acc[a.P + i] = 0ull;
+        a.acc[a.P + a.D + i] = 0ull;
         long long b = ((long long)used + a.tokens_per_seq - 1) / a.tokens_per_seq;
         a.batch[i] = (int)(b > a.max_batch ? a.max_batch : b);
     }
@@ -109,6 +145,9 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (e == hipSuccess && hx_score_init() != HX_OK) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
     if (e == hipSuccess) {
         what = "launch of hx_clear_status_kernel";
+        CommitArgs z{};
+        z.P = HX_MAX_INSTANCES; z.D = HX_MAX_INSTANCES; z.acc = ctx->d_acc;
+        hx_commit_clear_kernel<<<(3 * HX_MAX_INSTANCES + 255) / 256, 256, 0, nullptr>>>(z);
         hx_clear_status_kernel<<<1, 1, 0, nullptr>>>(ctx->d_status);
         e = hipGetLastError();
     }
@@ -184,8 +223,6 @@ extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best
     hipStream_t stream = (hipStream_t)stream_;
     CommitArgs a{C, P, D, calls->L_in, calls->L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
                  drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, ctx->d_acc, ctx->d_status};
-    const int n_acc = P + 2 * D;
-    hx_commit_clear_kernel<<<(n_acc + 255) / 256, 256, 0, stream>>>(a);
     if (C > 0) {
         int grid = (C + 255) / 256;
         grid = grid > ctx->num_cu ? ctx->num_cu : grid;

@@ -73,105 +73,78 @@ struct CpArgs {
 };
 
 constexpr int CP_THREADS = 256;      // threads per block
-constexpr int CP_WPB = 64;           // at most this many workflows per block: 16 per wave, 4 lanes each
-constexpr int CP_NMAX = 2000;        // nodes staged per block; 10 B of LDS each
-constexpr int CP_NPT = (CP_NMAX + CP_THREADS - 1) / CP_THREADS;
-constexpr int CP_DEG = 4;            // successors held inline per staged node, one per lane of a quad
-constexpr int CP_EMAX = 2 * CP_NMAX;  // edges staged per block (16-bit each, in the space of s_rem)
+constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking lane each
+constexpr int CP_NMAX = 1700;        // nodes staged per block
+constexpr int CP_EMAX = 3000;        // edges staged per block
+constexpr int CP_NPT = (CP_NMAX + 1 + CP_THREADS - 1) / CP_THREADS;
 constexpr int CP_EPT = (CP_EMAX + CP_THREADS - 1) / CP_THREADS;
+constexpr int CP_DEG = 4;            // successors a walking lane combines per step
+constexpr int CP_NONE = 0xffff;
 
-// max over the 4 lanes of a quad, by two DPP lane swaps (no LDS traffic)
-__device__ __forceinline__ float hx_quad_max(float x)
-{
-    int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
-    x = fmaxf(x, __int_as_float(y));
-    y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false);       // quad_perm [2,3,0,1]
-    return fmaxf(x, __int_as_float(y));
-}
+struct __align__(8) CpRec { float rem; int lvl; };   // (cost, -) until the node is final, then (rem, level)
 
-__device__ __forceinline__ int hx_quad_max(int x)
-{
-    x = max(x, __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, false));
-    return max(x, __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, false));
-}
-
-// One block takes `wpb` consecutive workflows; their nodes are one contiguous
-// slice.
-//  stage  The slice's cost, row offsets and successor ids are read flat and
-//         coalesced, all loads of a step issued before the first is used
-//         (enough bytes in flight to cover HBM latency).  Successor ids are
-//         parked in LDS as 16-bit offsets; every thread then packs, for a few
-//         nodes, the (at most CP_DEG) successors as 8-bit distances to the
-//         successor's id.  Edges are checked here (successor later than the
-//         node, inside the node's own workflow), so the walk needs no checks.
-//  walk   Four lanes per workflow walk its nodes from the last to the first;
-//         lane j of the quad gathers successor slot j, two DPP swaps combine
-//         the quad.  A step costs one LDS round trip: empty slots read a zero
-//         entry, and the next node's successor word and cost are fetched
-//         while the current node is combined.
-//  store  Every thread writes its nodes back (tail is re-derived from the
-//         final successors), coalesced.
+// One block takes `wpb` consecutive workflows; their nodes and edges are two
+// contiguous slices of the CSR arrays.
+//  stage  cost, row offsets and successor ids are read flat and coalesced, all
+//         loads issued before the first is used (enough bytes in flight to
+//         cover HBM latency), and parked in LDS: row offsets and successor ids
+//         as 16-bit offsets into the slices (10 B + 2 B per edge for a node).
+//  walk   one lane per workflow (the lanes of one wave, a different wave in
+//         consecutive blocks so that the walkers of a CU spread over its
+//         SIMDs) walks the nodes from the last to the first.  A step costs one
+//         LDS round trip: the successor ids of the next node and the row
+//         offset of the one after are fetched in the same batch as the
+//         gathers of the current node.  Edges are checked here (successor
+//         later than the node, inside the workflow).  tail goes straight to
+//         global memory from the walking lane.
+//  store  every thread writes rem and level of a few nodes, coalesced.
 // A slice that does not fit -- more than CP_NMAX nodes or CP_EMAX edges, a
-// node with more than CP_DEG successors, a successor more than 255 ids away --
-// is walked in global memory, one lane per workflow.
+// node with more than CP_DEG successors -- is walked in global memory, one
+// lane per workflow.
 __global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
 void hx_cp_local_kernel(CpArgs a, int wpb)
 {
-    __shared__ float s_rem[CP_NMAX + 1];      // cost until the node is final, then rem; [CP_NMAX] = 0
-    __shared__ unsigned s_succ[CP_NMAX];      // 4 x 8-bit distance to each successor, 0 = empty slot
-    __shared__ uint16_t s_lvl[CP_NMAX + 2];   // workflow end while staging, then level + 1; [CP_NMAX] = 0
-    __shared__ uint16_t s_wlo[CP_WPB], s_whi[CP_WPB];
-    __shared__ int s_flag;                    // 1: malformed ranges, 2: slice does not fit
+    __shared__ CpRec s_rec[CP_NMAX + 1];      // [CP_NMAX] = (0, -1): what an empty successor slot reads
+    __shared__ uint16_t s_row[CP_NMAX + 2];   // first edge of each node, relative to the slice
+    __shared__ uint16_t s_col[CP_EMAX + CP_DEG];
+    __shared__ int s_flag;                    // 2: slice does not fit
 
     const int tid = threadIdx.x;
     const int w0 = blockIdx.x * wpb;
     const int w1 = min(w0 + wpb, a.n_wf);
     int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
-    const int w = w0 + tid;
-    const bool owner = tid < wpb && w < w1;     // this thread loads workflow w's range
-    int ws = n0, we = n0;
-    if (owner) { ws = a.wf_ptr[w]; we = a.wf_ptr[w + 1]; }
-    if (tid == 0) { s_flag = 0; s_rem[CP_NMAX] = 0.0f; s_lvl[CP_NMAX] = 0; }
-    // malformed ranges: clamp so that nothing is read out of bounds, and report
-    bool bad = n0 < 0 || n1 > a.n_nodes || n0 > n1 || ws < n0 || we > n1 || ws > we;
-    if (bad) { n0 = n1 = ws = we = 0; }
-    __syncthreads();
-    if (bad) s_flag = 1;
-    __syncthreads();
-    if (s_flag == 1) {
+    if (tid == 0) { s_flag = 0; s_rec[CP_NMAX] = CpRec{0.0f, -1}; }
+    // the slice of the block: malformed -> nothing is read, the error is reported
+    if (n0 < 0 || n1 > a.n_nodes || n0 > n1) {
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
-        if (owner) a.horizon[w] = 0.0f;
+        if (tid < wpb && w0 + tid < w1) a.horizon[w0 + tid] = 0.0f;
         return;
     }
     const int nn = n1 - n0;
+    // the walking lanes: wave (blockIdx mod 4), lane = workflow within the block
+    const int wl = tid - ((int)(blockIdx.x & 3) << 6);
+    const bool walker = wl >= 0 && wl < wpb && w0 + wl < w1;
+    int ws = n0, we = n0;
+    if (walker) { ws = a.wf_ptr[w0 + wl]; we = a.wf_ptr[w0 + wl + 1]; }
     bool not_dag = false, bad_index = false;
+    if (ws < n0 || we > n1 || ws > we) { bad_index = true; ws = we = n0; }   // this workflow is skipped
+    float hmax = 0.0f;
 
-    if (nn <= CP_NMAX) {
-        // step 1: cost and row offsets of this thread's nodes, and the edge range of the slice
+    bool fits = nn <= CP_NMAX;
+    int e0 = 0, e1 = 0;
+    if (fits) {
         float c[CP_NPT];
-        int r0[CP_NPT], r1[CP_NPT];
+        int r[CP_NPT];
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
             const int i = k * CP_THREADS + tid;
-            const bool in = i < nn;
-            c[k] = in ? a.cost[n0 + i] : 0.0f;
-            r0[k] = in ? a.row_ptr[n0 + i] : 0;
-            r1[k] = in ? a.row_ptr[n0 + i + 1] : 0;
+            c[k] = i < nn ? a.cost[n0 + i] : 0.0f;
+            r[k] = i <= nn ? a.row_ptr[n0 + i] : 0;
         }
-        int e0 = 0, e1 = 0;
-        if (nn > 0) { e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1]; }
+        e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1];
         if (e0 < 0 || e1 > a.n_edges || e0 > e1) { bad_index = true; e0 = e1 = 0; }
         const int ne = e1 - e0;
-        // while those loads fly: every workflow marks its nodes with its end
-        if (tid < wpb) {
-            s_wlo[tid] = (uint16_t)(ws - n0);
-            s_whi[tid] = (uint16_t)(we - n0);
-            for (int v = ws - n0; v < we - n0; ++v) s_lvl[v] = (uint16_t)(we - n0);
-        }
-        // step 2: the slice's successor ids, flat and coalesced, parked in LDS as
-        // 16-bit offsets into the slice (in the space s_rem takes over afterwards)
-        uint16_t *s_col = reinterpret_cast<uint16_t *>(s_rem);
-        const bool fits = ne <= CP_EMAX;
+        fits = ne <= CP_EMAX;
         int ed[CP_EPT];
 #pragma unroll
         for (int k = 0; k < CP_EPT; ++k) {
@@ -179,93 +152,89 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
             ed[k] = (fits && i < ne) ? a.col[e0 + i] : -1;
         }
 #pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            const int i = k * CP_THREADS + tid;
+            if (i < nn) s_rec[i] = CpRec{c[k], 0};
+            if (i <= nn) s_row[i] = (uint16_t)min(max(r[k] - e0, 0), ne);   // a non-monotone row_ptr cannot leave the slice
+        }
+#pragma unroll
         for (int k = 0; k < CP_EPT; ++k) {
             const int i = k * CP_THREADS + tid;
             const int rel = ed[k] - n0;
-            if (fits && i < ne) s_col[i] = (rel >= 0 && rel < nn) ? (uint16_t)rel : (uint16_t)0xffff;
+            if (fits && i < ne) s_col[i] = (rel >= 0 && rel < nn) ? (uint16_t)rel : (uint16_t)CP_NONE;
         }
-        __syncthreads();
-        // step 3: per node, its successors as 8-bit distances, checked
-        bool wide = !fits;
-        unsigned word[CP_NPT];
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            word[k] = 0;
-            if (i < nn && fits) {
-                int b = r0[k] - e0, d = r1[k] - r0[k];
-                if (b < 0 || d < 0 || b + d > ne) { bad_index = true; d = 0; }
-                wide = wide || d > CP_DEG;
-                const int end = s_lvl[i];         // end of node i's workflow
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) {
-                    if (j < d) {
-                        const int dist = (int)s_col[b + j] - i;
-                        // a successor must be a later node of the same workflow
-                        if (dist <= 0 || i + dist >= end) not_dag = true;
-                        else if (dist > 255) wide = true;
-                        else word[k] |= (unsigned)dist << (8 * j);
-                    }
-                }
-            }
-        }
-        __syncthreads();                      // every read of s_col is done: s_rem takes its place
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            if (i < nn) { s_rem[i] = c[k]; s_succ[i] = word[k]; }
-        }
-        if (wide) s_flag = 2;
+        if (!fits) s_flag = 2;
     } else if (tid == 0) {
         s_flag = 2;
     }
     __syncthreads();
 
     if (s_flag == 0) {
-        const int q = tid >> 2, j = tid & 3;          // workflow of this quad, successor slot of this lane
-        if (q < wpb) {
-            const int lo = s_wlo[q], hi = s_whi[q];
-            float hmax = 0.0f;
-            if (hi > lo) {
-                const int shift = 8 * j;
-                unsigned nxt = s_succ[hi - 1];
-                float cst = s_rem[hi - 1];
-                for (int v = hi - 1; v >= lo; --v) {
-                    const unsigned cur = nxt;
-                    const float cv = cst;
-                    const int vp = max(v - 1, lo);
-                    nxt = s_succ[vp];                 // fetched while v is combined
-                    cst = s_rem[vp];
-                    const int dist = (cur >> shift) & 0xff;
-                    const int idx = dist ? v + dist : CP_NMAX;     // empty slot: the zero entry
-                    const float tl = hx_quad_max(s_rem[idx]);
-                    const int lv = hx_quad_max((int)s_lvl[idx]);    // successors hold level + 1
-                    const float rv = cv + tl;
-                    if (j == 0) { s_rem[v] = rv; s_lvl[v] = (uint16_t)(lv + 1); }
-                    hmax = fmaxf(hmax, rv);
+        if (we > ws) {                                  // a walking lane with a non-empty workflow
+            const int lo = ws - n0, hi = we - n0;
+            // software pipeline: at the step of node v the lane holds the successors of v and the
+            // first edge of v-1, and fetches the successors of v-1 and the first edge of v-2
+            int r1 = s_row[hi];
+            int r0 = s_row[hi - 1];
+            int rp = s_row[max(hi - 2, lo)];            // first edge of v-1
+            int u[CP_DEG];
+#pragma unroll
+            for (int j = 0; j < CP_DEG; ++j) u[j] = s_col[r0 + j];
+            bool wide = false;
+            int n_ok = 0, n_edges_seen = 0;
+            float *tail_out = a.tail + n0;
+            for (int v = hi - 1; v >= lo; --v) {
+                const int deg = r1 - r0;
+                wide = wide || deg > CP_DEG;
+                // fetches for the next two steps
+                const int rpp = s_row[max(v - 2, lo)];
+                int un[CP_DEG];
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) un[j] = s_col[rp + j];
+                const float cv = s_rec[v].rem;
+                // gathers of this step; a slot that is empty or breaks the order reads the (0, -1) entry
+                CpRec g[CP_DEG];
+                const unsigned span = (unsigned)(hi - v - 1);      // ids v+1 .. hi-1 are the legal successors
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) {
+                    const bool ok = j < deg && (unsigned)(u[j] - v - 1) < span;
+                    n_ok += ok;
+                    g[j] = s_rec[ok ? u[j] : CP_NMAX];
                 }
+                n_edges_seen += min(deg, CP_DEG);
+                float tl = 0.0f;
+                int lv = -1;
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) {
+                    tl = fmaxf(tl, g[j].rem);
+                    lv = max(lv, g[j].lvl);
+                }
+                const float rv = cv + tl;
+                s_rec[v] = CpRec{rv, lv + 1};
+                tail_out[v] = tl;
+                hmax = fmaxf(hmax, rv);
+                r1 = r0; r0 = rp; rp = rpp;
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) u[j] = un[j];
             }
-            if (j == 0 && w0 + q < w1) a.horizon[w0 + q] = hmax;
+            not_dag = not_dag || n_ok != n_edges_seen;     // an edge left its workflow or pointed backwards
+            if (wide) s_flag = 3;                       // a node with more successors than a step combines
         }
         __syncthreads();
+    }
+    if (s_flag == 0) {
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
             const int i = k * CP_THREADS + tid;
             if (i < nn) {
-                const unsigned word = s_succ[i];
-                float tl = 0.0f;
-#pragma unroll
-                for (int jj = 0; jj < CP_DEG; ++jj) {
-                    const int dist = (word >> (8 * jj)) & 0xff;
-                    tl = fmaxf(tl, s_rem[dist ? i + dist : CP_NMAX]);
-                }
-                a.rem[n0 + i] = s_rem[i];
-                a.tail[n0 + i] = tl;
-                a.level[n0 + i] = (int)s_lvl[i] - 1;
+                const CpRec me = s_rec[i];
+                a.rem[n0 + i] = me.rem;
+                a.level[n0 + i] = me.lvl;
             }
         }
     } else {
-        float hmax = 0.0f;
+        // walked in global memory (also after a staged walk met a node that is too wide: everything is redone)
+        hmax = 0.0f;
         for (int v = we - 1; v >= ws; --v) {
             int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
             if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
@@ -281,8 +250,8 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
             a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
             hmax = fmaxf(hmax, rv);
         }
-        if (owner) a.horizon[w] = hmax;
     }
+    if (walker) a.horizon[w0 + wl] = hmax;
     if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
     if (bad_index) hx_raise(a.status, HX_ERR_INDEX);
 }

@@ -205,18 +205,19 @@ def test_append_errors(ctx):
     assert e.value.code == -4
 
 
-def test_commit_matches_oracle(ctx):
+@pytest.mark.parametrize("C", [5000, 200000])       # one-block and multi-block paths
+def test_commit_matches_oracle(ctx, C):
     import torch
     from paper_2605_16637_amd import binding
     rng = np.random.default_rng(6)
-    C, P, D = 5000, 37, 53
+    P, D = 37, 53
     L, O = synth.gen_lengths(rng, C)
     bp = rng.integers(-1, P, C).astype(np.int32)
     bd = np.where(bp < 0, -1, rng.integers(0, D, C)).astype(np.int32)
     st = [rng.integers(0, 20000, P).astype(np.int32), rng.integers(0, 300000, D).astype(np.int32),
           rng.integers(0, 200, D).astype(np.int32), rng.integers(0, 20000, D).astype(np.int32)]
-    dr = [rng.integers(0, 400000, P).astype(np.int32), rng.integers(0, 30000, D).astype(np.int32),
-          rng.integers(0, 200000, D).astype(np.int32)]
+    dr = [rng.integers(0, 80 * C, P).astype(np.int32), rng.integers(0, 6 * C, D).astype(np.int32),
+          rng.integers(0, 40 * C, D).astype(np.int32)]
     want = o.commit(L, O, bp, bd, *st, *dr)
     assert want[4] == 0
     g = [dev(x.copy()) for x in st]
