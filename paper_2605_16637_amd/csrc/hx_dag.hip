@@ -29,31 +29,42 @@ struct NodeCostArgs {
     float *cost;
 };
 
-// cost[v] = min over class pairs of prefill + transfer + decode on an idle pool
+// cost[v] = min over class pairs of prefill + transfer + decode on an idle pool.
+// The class tables are padded to kT x kT in LDS (a pair with a class that does
+// not exist has infinite transfer latency), so the pair loop unrolls completely
+// and its table reads are LDS broadcasts.
 __global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
 {
     __shared__ float s_invF[kT], s_invB[kT], s_c1[kT], s_kB[kT], s_c2[kT];
-    __shared__ float s_invbw[kT * kT], s_lat[kT * kT];
+    __shared__ __align__(16) float s_invbw[kT * kT], s_lat[kT * kT];
     const int tid = threadIdx.x;
-    if (tid < a.T) {
-        float invF = 1.0f / a.tF[tid], invB = 1.0f / a.tB[tid];
+    if (tid < kT) {
+        const bool in = tid < a.T;
+        float invF = in ? 1.0f / a.tF[tid] : 0.0f, invB = in ? 1.0f / a.tB[tid] : 0.0f;
         HxDecF d = hx_decode_terms(a.m, 0, 0, 0, invF, invB);
-        s_invF[tid] = invF; s_invB[tid] = invB; s_c1[tid] = d.c1; s_c2[tid] = d.c2; s_kB[tid] = d.kB;
+        s_invF[tid] = invF; s_invB[tid] = invB;
+        // a padded class is excluded by an infinite link latency below; its own terms stay finite (0)
+        s_c1[tid] = in ? d.c1 : 0.0f; s_c2[tid] = in ? d.c2 : 0.0f; s_kB[tid] = in ? d.kB : 0.0f;
     }
-    if (tid < a.T * a.T) {
-        s_invbw[tid] = 1.0f / a.bw[tid];
-        s_lat[tid] = a.lat ? a.lat[tid] : 0.0f;
+    if (tid < kT * kT) {
+        const int tp = tid / kT, td = tid % kT;
+        const bool in = tp < a.T && td < a.T;
+        s_invbw[tid] = in ? 1.0f / a.bw[tp * a.T + td] : 0.0f;
+        s_lat[tid] = in ? (a.lat ? a.lat[tp * a.T + td] : 0.0f) : INFINITY;
     }
     __syncthreads();
     for (int v = blockIdx.x * blockDim.x + tid; v < a.n; v += gridDim.x * blockDim.x) {
         const HxCallF cf = hx_call_terms(a.m, a.L_in[v], a.L_out[v]);
         float dec[kT];
-        for (int td = 0; td < a.T; ++td) dec[td] = hx_decode_time(cf, s_c1[td], s_c2[td], s_kB[td]);
+#pragma unroll
+        for (int td = 0; td < kT; ++td) dec[td] = hx_decode_time(cf, s_c1[td], s_c2[td], s_kB[td]);
         float best = INFINITY;
-        for (int tp = 0; tp < a.T; ++tp) {
-            float done = hx_prefill_done(cf, 0.0f, s_invF[tp], s_invB[tp]);
-            for (int td = 0; td < a.T; ++td) {
-                float x = hx_transfer(cf, s_invbw[tp * a.T + td], s_lat[tp * a.T + td]);
+#pragma unroll
+        for (int tp = 0; tp < kT; ++tp) {
+            const float done = hx_prefill_done(cf, 0.0f, s_invF[tp], s_invB[tp]);
+#pragma unroll
+            for (int td = 0; td < kT; ++td) {
+                const float x = hx_transfer(cf, s_invbw[tp * kT + td], s_lat[tp * kT + td]);
                 best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
             }
         }
