@@ -208,6 +208,16 @@ def test_scaling_all_rates_scales_all_costs():
     assert np.array_equal(sc.best_p, base.best_p) and np.array_equal(sc.best_d, base.best_d)
 
 
+def test_node_cost_round():
+    links = dict(n_types=1, bw=np.array([[1e9]], np.float32), latency=None)
+    types = dict(flops=np.array([1e13], np.float32), hbm_bw=np.array([1e12], np.float32))
+    nc = o.node_cost(ROUND_MODEL, [1000], [100], types, links)
+    assert nc[0] == pytest.approx(G["node_cost_memory_bound_decode"], rel=1e-6)
+    types = dict(flops=np.array([1e10], np.float32), hbm_bw=np.array([1e12], np.float32))
+    nc = o.node_cost(ROUND_MODEL, [1000], [100], types, links)
+    assert nc[0] == pytest.approx(G["node_cost_compute_bound_decode"], rel=1e-6)
+
+
 def test_node_cost_is_best_pair_on_idle_pool():
     # R9 = min over class pairs of R7 on an idle pool holding one instance per class
     rng = np.random.default_rng(14)
