@@ -193,3 +193,52 @@ def test_errors_are_reported_not_faulted(ctx):
         ctx.hx_stream_status()
     assert e.value.code == -6
     ctx.hx_stream_status()                                        # sticky status was cleared
+
+
+@pytest.mark.parametrize("C,P,D,T", [(7, 65, 9, 3), (3, 5, 130, 8), (11, 33, 33, 1)])
+def test_materialised_tensor_ragged_and_select_with_ratio(ctx, C, P, D, T):
+    import torch
+    from paper_2605_16637_amd import binding
+    rng = np.random.default_rng(2000 + P + D)
+    types, pre, dec, links = random_pool(rng, P, D, T)
+    L, O = synth.gen_lengths(rng, C)
+    L[0], O[0] = 0, 0                       # degenerate lengths: no prefill work, nothing to decode
+    if C > 3:
+        L[2], O[2] = 0, 77
+        L[3], O[3] = 500, 0
+    model = synth.MODEL
+    ores = o.score(model, L, O, pre, dec, links, want_cost=True, want_feas=True)
+    pre["n"], dec["n"] = P, D
+    n_nodes, n_wf = 40, 6
+    node = rng.integers(0, n_nodes, C).astype(np.int32); wf = rng.integers(0, n_wf, C).astype(np.int32)
+    elapsed = rng.uniform(0, 9, C).astype(np.float32)
+    tail = rng.uniform(0, 5, n_nodes).astype(np.float32); hor = rng.uniform(1, 50, n_wf).astype(np.float32)
+    calls = binding.to_device(dict(n=C, L_in=L, L_out=O, node=node, wf=wf, elapsed=elapsed))
+    dp, dd, dl = binding.to_device(pre), binding.to_device(dec), binding.to_device(links)
+    cost = torch.empty(C * P * D, dtype=torch.float32, device="cuda:0")
+    feas = torch.empty(C * D, dtype=torch.uint8, device="cuda:0")
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    fp, fd = torch.empty(C, **i32), torch.empty(C, **i32)
+    fc, fr = torch.empty(C, device="cuda:0"), torch.empty(C, device="cuda:0")
+    # tensor, mask and fused outputs from one call
+    ctx.hx_score_placements(model, calls, dp, dd, dl, tail=dev(tail), horizon=dev(hor), cost=cost, feas=feas,
+                            best_p=fp, best_d=fd, best_cost=fc, ratio=fr)
+    ctx.hx_stream_status()
+    gcost = cost.cpu().numpy().reshape(C, P, D)
+    assert_costs_close(gcost, ores.cost, "cost tensor")
+    assert np.array_equal(feas.cpu().numpy().reshape(C, D), ores.feas)
+    assert_search_matches(model, L, O, pre, dec, links, ores, fp.cpu().numpy(), fd.cpu().numpy(), fc.cpu().numpy())
+    sp, sd = torch.empty(C, **i32), torch.empty(C, **i32)
+    sc, sr = torch.empty(C, device="cuda:0"), torch.empty(C, device="cuda:0")
+    ctx.hx_select(C, P, D, cost, sp, sd, sc, calls=calls, tail=dev(tail), horizon=dev(hor), ratio=sr)
+    ctx.hx_stream_status()
+    for a, b in ((sp, fp), (sd, fd), (sc, fc), (sr, fr)):            # select == fused, bit for bit
+        assert np.array_equal(a.cpu().numpy(), b.cpu().numpy(), equal_nan=True)
+    want = o.urgency(elapsed, ores.best_cost, node, wf, tail, hor)
+    assert_costs_close(sr.cpu().numpy(), want, "ratio")
+    # a node index beyond the tail array is reported, not read
+    bad = dict(calls, node=dev(np.full(C, n_nodes, np.int32)))
+    ctx.hx_select(C, P, D, cost, sp, sd, sc, calls=bad, tail=dev(tail), horizon=dev(hor), ratio=sr)
+    with pytest.raises(binding.HxError) as e:
+        ctx.hx_stream_status()
+    assert e.value.code == -6
