@@ -71,6 +71,17 @@
  *                        revealed DAG (tail = 0)
  *  R12 commit and drain  integer bookkeeping of chosen placements, see
  *                        hxo_commit
+ *  R13 recomputing greedy (Algorithm 1 main loop; Sec. 5.3, small queues):
+ *                        repeat: score every remaining call on the simulated
+ *                        state (R7, R8, R11); take the call of largest R,
+ *                        equal R by lowest call index; record its pair, cost,
+ *                        R and its rank (0 = first); add it to the state
+ *                        (backlog[p*] += L, qd[d*] += O, used[d*] += L + O,
+ *                        batch[d*] = R12's rule; no drain).  A call with no
+ *                        feasible pair has R = +infinity: it is ranked at
+ *                        once, keeps (-1,-1) and changes nothing.
+ *  R14 one-pass ordering (Sec. 5.3, larger queues): rank = position by
+ *                        decreasing R, equal R by increasing call index
  *
  * The choice of these formulas cannot be checked against printed values of
  * the paper (it prints none): parity with "the paper's estimator" is
@@ -447,5 +458,77 @@ int hxo_commit(int32_t C, const int32_t *L_in, const int32_t *L_out,
         }
     }
     free(bl); free(us); free(qd);
+    return rc;
+}
+
+/* ---- R14: one-pass ordering by the risk score (Sec. 5.3) ----------------- */
+
+int hxo_rank(int32_t C, const double *ratio, int32_t *rank)
+{
+    if (C < 0) return -1;
+    for (int32_t c = 0; c < C; ++c) {
+        int32_t ahead = 0;
+        for (int32_t k = 0; k < C; ++k)
+            if (ratio[k] > ratio[c] || (ratio[k] == ratio[c] && k < c)) ++ahead;
+        rank[c] = ahead;
+    }
+    return 0;
+}
+
+/* ---- R13: the recomputing greedy loop of Algorithm 1 (Sec. 5.3) ---------- */
+
+/*
+ * p_backlog [P], d_used, d_batch, d_qd [D] are the simulated state: read, and
+ * left as the plan leaves them.  Outputs per call, as of the moment the call
+ * was picked: best_p, best_d, best_cost, ratio, rank.
+ * Returns 0; -1 bad argument; -3 out of memory; -4 an int32 counter overflowed.
+ */
+int hxo_plan_greedy(const hxo_model *m,
+                    int32_t C, const int32_t *L_in, const int32_t *L_out,
+                    const double *elapsed, const int32_t *node, const int32_t *wf,
+                    const double *tail, const double *horizon,
+                    int32_t P, const float *pF, const float *pB, int32_t *p_backlog, const int32_t *p_type,
+                    int32_t D, const float *dF, const float *dB, int32_t *d_used, const int32_t *d_cap,
+                    int32_t *d_batch, int32_t *d_qd, const int32_t *d_type,
+                    int32_t T, const float *link_bw, const float *link_lat,
+                    int32_t tokens_per_seq, int32_t max_batch,
+                    int32_t *best_p, int32_t *best_d, double *best_cost, double *ratio, int32_t *rank)
+{
+    if (C < 0 || P < 0 || D < 0 || T <= 0 || tokens_per_seq <= 0) return -1;
+    uint8_t *done = (uint8_t *)calloc((size_t)C + 1, 1);
+    if (!done) return -3;
+    int rc = 0;
+    for (int32_t k = 0; k < C && rc == 0; ++k) {
+        int32_t pick = -1, pick_p = -1, pick_d = -1;
+        double pick_r = 0.0, pick_cost = 0.0;
+        for (int32_t c = 0; c < C; ++c) {
+            if (done[c]) continue;
+            double bc = INFINITY;
+            int32_t bp = -1, bd = -1;
+            for (int32_t p = 0; p < P; ++p)
+                for (int32_t d = 0; d < D; ++d) {
+                    int32_t tp = p_type[p], td = d_type[d];
+                    double lat = link_lat ? (double)link_lat[tp * T + td] : 0.0;
+                    double v = hxo_candidate_cost(m, L_in[c], L_out[c], (double)pF[p], (double)pB[p], p_backlog[p],
+                                                  (double)dF[d], (double)dB[d], d_used[d], d_cap[d], d_batch[d], d_qd[d],
+                                                  (double)link_bw[tp * T + td], lat);
+                    if (v < bc) { bc = v; bp = p; bd = d; }
+                }
+            double r = (elapsed[c] + bc + tail[node[c]]) / horizon[wf[c]];
+            if (pick < 0 || r > pick_r) { pick = c; pick_r = r; pick_cost = bc; pick_p = bp; pick_d = bd; }
+        }
+        done[pick] = 1;
+        best_p[pick] = pick_p; best_d[pick] = pick_d; best_cost[pick] = pick_cost; ratio[pick] = pick_r; rank[pick] = k;
+        if (pick_p >= 0) {
+            int64_t bl = (int64_t)p_backlog[pick_p] + L_in[pick];
+            int64_t qd = (int64_t)d_qd[pick_d] + L_out[pick];
+            int64_t us = (int64_t)d_used[pick_d] + L_in[pick] + L_out[pick];
+            if (bl > 2147483647LL || qd > 2147483647LL || us > 2147483647LL) { rc = -4; break; }
+            p_backlog[pick_p] = (int32_t)bl; d_qd[pick_d] = (int32_t)qd; d_used[pick_d] = (int32_t)us;
+            int64_t b = (us + tokens_per_seq - 1) / tokens_per_seq;
+            d_batch[pick_d] = (int32_t)(b > max_batch ? max_batch : b);
+        }
+    }
+    free(done);
     return rc;
 }

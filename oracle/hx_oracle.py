@@ -221,6 +221,51 @@ def commit(L_in, L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
     return bl, us, ba, qd, rc
 
 
+def rank(ratio):
+    """R14: position of every call by decreasing ratio, equal ratios by increasing index."""
+    ratio = _f64(ratio)
+    out = np.empty(ratio.size, np.int32)
+    rc = lib().hxo_rank(ratio.size, _p(ratio), _p(out))
+    if rc:
+        raise ValueError(f"hxo_rank failed: {rc}")
+    return out
+
+
+@dataclass
+class PlanResult:
+    best_p: np.ndarray
+    best_d: np.ndarray
+    best_cost: np.ndarray
+    ratio: np.ndarray
+    rank: np.ndarray
+    backlog_tok: np.ndarray
+    used_tok: np.ndarray
+    batch: np.ndarray
+    qd_tok: np.ndarray
+
+
+def plan_greedy(model, L_in, L_out, elapsed, node, wf, tail, horizon, pre, dec, links,
+                tokens_per_seq=2048, max_batch=256) -> PlanResult:
+    """R13: the recomputing greedy loop; returns the plan and the simulated state it leaves."""
+    L_in, L_out, node, wf = _i32(L_in), _i32(L_out), _i32(node), _i32(wf)
+    elapsed, tail, horizon = _f64(elapsed), _f64(tail), _f64(horizon)
+    t = _tables(pre, dec, links)
+    bl, us, ba, qd = t["pbl"].copy(), t["dus"].copy(), t["dba"].copy(), t["dqd"].copy()
+    Cn = L_in.size
+    bp = np.empty(Cn, np.int32); bd = np.empty(Cn, np.int32); rk = np.empty(Cn, np.int32)
+    bc = np.empty(Cn, np.float64); rt = np.empty(Cn, np.float64)
+    m = _model(model)
+    with np.errstate(all="ignore"):
+        rc = lib().hxo_plan_greedy(C.byref(m), Cn, _p(L_in), _p(L_out), _p(elapsed), _p(node), _p(wf), _p(tail), _p(horizon),
+                                   t["pF"].size, _p(t["pF"]), _p(t["pB"]), _p(bl), _p(t["pty"]),
+                                   t["dF"].size, _p(t["dF"]), _p(t["dB"]), _p(us), _p(t["dcap"]), _p(ba), _p(qd), _p(t["dty"]),
+                                   t["T"], _p(t["bw"]), _p(t["lat"]), int(tokens_per_seq), int(max_batch),
+                                   _p(bp), _p(bd), _p(bc), _p(rt), _p(rk))
+    if rc:
+        raise ValueError(f"hxo_plan_greedy failed: {rc}")
+    return PlanResult(bp, bd, bc, rt, rk, bl, us, ba, qd)
+
+
 # scalar term accessors, for the round-number pins
 def term(name, model, *args):
     m = _model(model)

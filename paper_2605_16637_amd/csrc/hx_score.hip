@@ -22,6 +22,7 @@
 //    lexicographic minimum of (cost, p*D + d).
 #include "hx_common.hpp"
 #include "hx_terms.hpp"
+#include "hx_search.hpp"
 
 #include <cfloat>
 #include <cmath>
@@ -207,94 +208,21 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, int d
     int seg[kT + 1];
 #pragma unroll
     for (int k = 0; k <= kT; ++k) seg[k] = __builtin_amdgcn_readfirstlane(s_seg[k]);
+    const HxPoolLds pool{s_wait, s_c1, s_c2, s_kB, s_free, s_orig, s_dtype, s_pw, s_pinvF, s_pinvB, s_ptype,
+                         s_invbw, s_lat, Dp, a.P, lay.Pp};
 
     const int gw = blockIdx.x * waves_per_block + wave;
     const int nw = gridDim.x * waves_per_block;
     for (int c = gw; c < a.C; c += nw) {
-        const int L = a.L_in[c], O = a.L_out[c];
-        const HxCallF cf = hx_call_terms(a.m, L, O);
-
-        // decode time of this call on every decode entry (+inf where it does not fit)
-        for (int e = lane; e < Dp; e += HX_WAVE)
-            wbuf[e].y = hx_fits(L, O, s_free[e]) ? hx_decode_time(cf, s_c1[e], s_c2[e], s_kB[e]) : INFINITY;
-        xbuf[lane] = hx_transfer(cf, s_invbw[lane], s_lat[lane]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        float bestv = INFINITY;
-        int bestp = -1;
-        for (int chunk = 0; chunk < a.P; chunk += HX_WAVE * KP) {
-            float R[KP][kT], bj[KP];
-#pragma unroll
-            for (int j = 0; j < KP; ++j) {
-                int p = chunk + j * HX_WAVE + lane;
-                p = p < lay.Pp ? p : lay.Pp - 1;        // stays inside the staged (padded) table
-                bool in = chunk + j * HX_WAVE + lane < a.P;
-                float done = in ? hx_prefill_done(cf, s_pw[p], s_pinvF[p], s_pinvB[p]) : INFINITY;
-                const float *xr = xbuf + s_ptype[p] * kT;
-#pragma unroll
-                for (int k = 0; k < kT; ++k) R[j][k] = done + xr[k];
-                bj[j] = INFINITY;
-            }
-#pragma unroll
-            for (int k = 0; k < kT; ++k) {
-                const float4 *q = (const float4 *)(wbuf + seg[k]);
-                const int ngroups = (seg[k + 1] - seg[k]) / HX_DGROUP;
-                for (int g = 0; g < ngroups; ++g, q += HX_DGROUP / 2) {
-                    float4 q0 = q[0], q1 = q[1], q2 = q[2], q3 = q[3];
-#pragma unroll
-                    for (int j = 0; j < KP; ++j) {
-                        float r = R[j][k];
-                        float t0 = hx_candidate(r, q0.x, q0.y), t1 = hx_candidate(r, q0.z, q0.w);
-                        float t2 = hx_candidate(r, q1.x, q1.y), t3 = hx_candidate(r, q1.z, q1.w);
-                        float t4 = hx_candidate(r, q2.x, q2.y), t5 = hx_candidate(r, q2.z, q2.w);
-                        float t6 = hx_candidate(r, q3.x, q3.y), t7 = hx_candidate(r, q3.z, q3.w);
-                        float m0 = fminf(fminf(bj[j], t0), t1);
-                        float m1 = fminf(fminf(t2, t3), t4);
-                        float m2 = fminf(fminf(t5, t6), t7);
-                        bj[j] = fminf(fminf(m0, m1), m2);
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < KP; ++j) {
-                // p grows with j and with chunk: "<" keeps the lowest p of this lane
-                if (bj[j] < bestv) { bestv = bj[j]; bestp = chunk + j * HX_WAVE + lane; }
-            }
-        }
-        // wave minimum of (cost, p)
-#pragma unroll
-        for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
-            float ov = __shfl_xor(bestv, off);
-            int op = __shfl_xor(bestp, off);
-            bool take = ov < bestv || (ov == bestv && op < bestp);
-            bestv = take ? ov : bestv;
-            bestp = take ? op : bestp;
-        }
-        int dstar = -1, pstar = -1;
-        if (bestv < INFINITY) {
-            pstar = bestp;
-            // lowest d of instance p* that reproduces the minimum exactly
-            const float done = hx_prefill_done(cf, s_pw[pstar], s_pinvF[pstar], s_pinvB[pstar]);
-            const float *xr = xbuf + s_ptype[pstar] * kT;
-            int dmin = 0x7fffffff;
-            for (int e = lane; e < Dp; e += HX_WAVE) {
-                float v = hx_candidate(done + xr[s_dtype[e]], wbuf[e].x, wbuf[e].y);
-                if (v == bestv) dmin = min(dmin, s_orig[e]);
-            }
-#pragma unroll
-            for (int off = HX_WAVE / 2; off > 0; off >>= 1) dmin = min(dmin, __shfl_xor(dmin, off));
-            dstar = dmin;
-        }
+        const HxBest b = hx_search_call<KP, false>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
+        const float bestv = b.cost;
+        const int pstar = b.p, dstar = b.d;
         if (lane == 0) {
             a.best_p[c] = pstar;
             a.best_d[c] = dstar;
             a.best_cost[c] = bestv;
             if (a.ratio) a.ratio[c] = hx_ratio(a, c, bestv);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
     }
 }
 

@@ -1,0 +1,130 @@
+// The search of one call over the whole pool by one wavefront: the inner part
+// of the fused scoring kernel, shared with the recomputing-greedy planner so
+// that both compare exactly the same fp32 costs.
+//
+// Lanes are prefill instances (KP per lane, in chunks of 64*KP beyond that).
+// Everything that depends on the decode instance only -- its availability hint
+// and the call's decode time there (+inf where the call does not fit) -- is
+// written once per call into the wave's LDS buffer and read back as
+// broadcasts; decode entries are grouped by GPU class, so the transfer time
+// leaves the inner loop, which is  t = max(ready, avail_d) + dec_d ;
+// best = min(best, t)  with no index bookkeeping.  The index is recovered
+// afterwards: the wave minimum fixes the winning prefill instance (lowest p
+// among the lanes that hold the minimum), and one pass over that instance's
+// candidates finds the lowest d that reproduces the minimum bit for bit --
+// exactly the lexicographic minimum of (cost, p*D + d).
+#pragma once
+
+#include "hx_common.hpp"
+#include "hx_terms.hpp"
+
+#include <cmath>
+
+// views of the pool tables staged in LDS
+struct HxPoolLds {
+    const float *wait, *c1, *c2, *kB;      // decode entries (grouped by class, padded): availability hint and per-token terms
+    const int *free, *orig, *dtype;        // free KV tokens, instance index (-1 = pad), class
+    const float *pw, *pinvF, *pinvB;       // prefill instances, padded to Pp: wait, 1/F, 1/B
+    const int *ptype;
+    const float *invbw, *lat;              // [kT*kT] class-pair transfer tables
+    int Dp, P, Pp;
+};
+
+struct HxBest {
+    float cost;    // +inf when no pair is feasible
+    int p, d;      // -1, -1 then
+};
+
+// wbuf: the wave's [Dp] (avail, decode time) pairs; with REFRESH_WAIT the avail
+// halves are rewritten from the pool view first (the caller changes the pool
+// between calls), otherwise the caller has filled them once.
+// xbuf: the wave's [kT*kT] transfer times.  seg: class segments, wave-uniform.
+template <int KP, bool REFRESH_WAIT>
+__device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPoolLds &s,
+                                                 const int (&seg)[HX_MAX_TYPES + 1],
+                                                 float2 *wbuf, float *xbuf, int L, int O, int lane)
+{
+    constexpr int kT = HX_MAX_TYPES;
+    const HxCallF cf = hx_call_terms(m, L, O);
+    const int Dp = s.Dp;
+
+    // decode time of this call on every decode entry (+inf where it does not fit)
+    for (int e = lane; e < Dp; e += HX_WAVE) {
+        if (REFRESH_WAIT) wbuf[e].x = s.wait[e];
+        wbuf[e].y = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
+    }
+    xbuf[lane] = hx_transfer(cf, s.invbw[lane], s.lat[lane]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    float bestv = INFINITY;
+    int bestp = -1;
+    for (int chunk = 0; chunk < s.P; chunk += HX_WAVE * KP) {
+        float R[KP][kT], bj[KP];
+#pragma unroll
+        for (int j = 0; j < KP; ++j) {
+            int p = chunk + j * HX_WAVE + lane;
+            p = p < s.Pp ? p : s.Pp - 1;            // stays inside the staged (padded) table
+            const bool in = chunk + j * HX_WAVE + lane < s.P;
+            const float done = in ? hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]) : INFINITY;
+            const float *xr = xbuf + s.ptype[p] * kT;
+#pragma unroll
+            for (int k = 0; k < kT; ++k) R[j][k] = done + xr[k];
+            bj[j] = INFINITY;
+        }
+#pragma unroll
+        for (int k = 0; k < kT; ++k) {
+            const float4 *q = (const float4 *)(wbuf + seg[k]);
+            const int ngroups = (seg[k + 1] - seg[k]) / HX_DGROUP;
+            for (int g = 0; g < ngroups; ++g, q += HX_DGROUP / 2) {
+                const float4 q0 = q[0], q1 = q[1], q2 = q[2], q3 = q[3];
+#pragma unroll
+                for (int j = 0; j < KP; ++j) {
+                    const float r = R[j][k];
+                    const float t0 = hx_candidate(r, q0.x, q0.y), t1 = hx_candidate(r, q0.z, q0.w);
+                    const float t2 = hx_candidate(r, q1.x, q1.y), t3 = hx_candidate(r, q1.z, q1.w);
+                    const float t4 = hx_candidate(r, q2.x, q2.y), t5 = hx_candidate(r, q2.z, q2.w);
+                    const float t6 = hx_candidate(r, q3.x, q3.y), t7 = hx_candidate(r, q3.z, q3.w);
+                    const float m0 = fminf(fminf(bj[j], t0), t1);
+                    const float m1 = fminf(fminf(t2, t3), t4);
+                    const float m2 = fminf(fminf(t5, t6), t7);
+                    bj[j] = fminf(fminf(m0, m1), m2);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KP; ++j) {
+            // p grows with j and with chunk: "<" keeps the lowest p of this lane
+            if (bj[j] < bestv) { bestv = bj[j]; bestp = chunk + j * HX_WAVE + lane; }
+        }
+    }
+    // wave minimum of (cost, p)
+#pragma unroll
+    for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(bestv, off);
+        const int op = __shfl_xor(bestp, off);
+        const bool take = ov < bestv || (ov == bestv && op < bestp);
+        bestv = take ? ov : bestv;
+        bestp = take ? op : bestp;
+    }
+    HxBest out{bestv, -1, -1};
+    if (bestv < INFINITY) {
+        out.p = bestp;
+        // lowest d of instance p* that reproduces the minimum exactly
+        const float done = hx_prefill_done(cf, s.pw[bestp], s.pinvF[bestp], s.pinvB[bestp]);
+        const float *xr = xbuf + s.ptype[bestp] * kT;
+        int dmin = 0x7fffffff;
+        for (int e = lane; e < Dp; e += HX_WAVE) {
+            const float v = hx_candidate(done + xr[s.dtype[e]], wbuf[e].x, wbuf[e].y);
+            if (v == bestv) dmin = min(dmin, s.orig[e]);
+        }
+#pragma unroll
+        for (int off = HX_WAVE / 2; off > 0; off >>= 1) dmin = min(dmin, __shfl_xor(dmin, off));
+        out.d = dmin;
+    }
+    // the next call of this wave rewrites the buffers: order its writes after these reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return out;
+}
