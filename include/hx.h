@@ -52,6 +52,8 @@ extern "C" {
 
 #define HX_MAX_TYPES      8      /* GPU classes in a pool                      */
 #define HX_MAX_INSTANCES  1024   /* prefill instances, and decode instances    */
+#define HX_GREEDY_MAX_CALLS      1024   /* queue length hx_plan_greedy takes            */
+#define HX_GREEDY_MAX_INSTANCES  256    /* instances per side hx_plan_greedy takes      */
 
 typedef struct hx_ctx hx_ctx;
 
@@ -269,6 +271,43 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
               const int32_t *drain_prefill, const int32_t *drain_decode_q,
               const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
               void *stream);
+
+/* ---- (5) the planner around the scoring loop ------------------------------- */
+
+/*
+ * One-pass ordering for larger queues (Sec. 5.3: calls are ordered once by the
+ * same risk score): rank[c] = position of call c when the calls are sorted by
+ * decreasing ratio, equal ratios by increasing call index (0 = most urgent).
+ * ratio [C] device in (as written by hx_score_placements or hx_select; +inf =
+ * nothing feasible, ranked first), rank [C] device out.  Work grows with C^2;
+ * meant for queues up to some 10^5 calls.
+ */
+int hx_rank(hx_ctx *ctx, int32_t C, const float *ratio, int32_t *rank, void *stream);
+
+/*
+ * Recomputing greedy for small queues (the main loop of Algorithm 1; Sec. 5.3):
+ * repeat C times -- score every remaining call on a simulated copy of the pool
+ * state, take the call of largest projected ratio (equal ratios: lowest call
+ * index), record its pair, cost, ratio and rank (0 = first), and add it to the
+ * simulated state: backlog_tok[p] += L_in, qd_tok[d] += L_out, used_tok[d] +=
+ * L_in + L_out, batch[d] = min(max_batch, ceil(used_tok[d] / tokens_per_seq)).
+ * A call with no feasible pair has ratio +inf: it is ranked at once, keeps
+ * (-1, -1) and changes nothing.  Inputs as in hx_score_placements (tail,
+ * horizon and the node/wf/elapsed members of `calls` are required; the pool
+ * tables are read only).  Outputs [C]: best_p, best_d, best_cost, ratio as of
+ * the moment the call was picked, and rank.  backlog_tok_out [P], used_tok_out,
+ * batch_out, qd_tok_out [D] receive the simulated state the plan leaves; each
+ * may be NULL.  At most HX_GREEDY_MAX_CALLS calls and HX_GREEDY_MAX_INSTANCES
+ * instances per side (HX_ERR_SHAPE beyond): the whole loop runs in one
+ * workgroup with no launch between iterations.
+ */
+int hx_plan_greedy(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                   const hx_prefill_tab *prefill, const hx_decode_tab *decode, const hx_links *links,
+                   const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                   int32_t tokens_per_seq, int32_t max_batch,
+                   int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio, int32_t *rank,
+                   int32_t *backlog_tok_out, int32_t *used_tok_out, int32_t *batch_out, int32_t *qd_tok_out,
+                   void *stream);
 
 #ifdef __cplusplus
 }

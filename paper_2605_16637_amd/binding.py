@@ -18,7 +18,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
            "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_view",
-           "hx_score_placements", "hx_select", "hx_commit")
+           "hx_score_placements", "hx_select", "hx_commit", "hx_rank", "hx_plan_greedy")
 
 
 class HxError(RuntimeError):
@@ -264,6 +264,28 @@ class Context:
             P, _ptr(backlog_tok, i32), D, _ptr(used_tok, i32), _ptr(batch, i32, D), _ptr(qd_tok, i32, D),
             _ptr(drain_prefill, i32, P), _ptr(drain_decode_q, i32, D), _ptr(release_tok, i32, D),
             int(tokens_per_seq), int(max_batch), _stream(stream)))
+
+
+    def hx_rank(self, ratio, rank, stream=None):
+        torch = _torch()
+        n = int(ratio.numel())
+        self._check(self.lib.hx_rank(self._ctx, n, _ptr(ratio, torch.float32), _ptr(rank, torch.int32, n), _stream(stream)))
+
+    def hx_plan_greedy(self, model, calls, prefill, decode, links, tail, horizon,
+                       best_p, best_d, best_cost, ratio, rank,
+                       backlog_tok_out=None, used_tok_out=None, batch_out=None, qd_tok_out=None,
+                       tokens_per_seq=2048, max_batch=256, stream=None):
+        torch = _torch()
+        m, cs, pt, dt, lk = make_model(model), make_calls(calls), make_prefill(prefill), make_decode(decode), make_links(links)
+        i32 = torch.int32
+        self._check(self.lib.hx_plan_greedy(
+            self._ctx, C.byref(m), C.byref(cs), C.byref(pt), C.byref(dt), C.byref(lk),
+            _ptr(tail, torch.float32), _ptr(horizon, torch.float32), int(tail.numel()), int(horizon.numel()),
+            int(tokens_per_seq), int(max_batch),
+            _ptr(best_p, i32, cs.n), _ptr(best_d, i32, cs.n), _ptr(best_cost, torch.float32, cs.n),
+            _ptr(ratio, torch.float32, cs.n), _ptr(rank, i32, cs.n),
+            _ptr(backlog_tok_out, i32, pt.n), _ptr(used_tok_out, i32, dt.n), _ptr(batch_out, i32, dt.n),
+            _ptr(qd_tok_out, i32, dt.n), _stream(stream)))
 
 
 def to_device(d: dict, device="cuda:0") -> dict:

@@ -101,6 +101,10 @@ inline int hx_check_launch(hx_ctx *ctx, const char *what)
     return HX_OK;
 }
 
+// hx_score.hip: validate the pool tables and enqueue the per-round table kernel (fills ctx->d_prep)
+int hx_prepare_pool(hx_ctx *ctx, const hx_model *model, const hx_prefill_tab *pre, const hx_decode_tab *dec,
+                    const hx_links *links, hipStream_t stream);
+
 // set the device of the context for the duration of a call
 struct HxDeviceGuard {
     int prev = -1;

@@ -3,6 +3,7 @@
 
 void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
 int hx_score_init();                // hx_score.hip
+int hx_plan_init();                 // hx_plan.hip
 
 namespace {
 
@@ -142,7 +143,7 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (e == hipSuccess) { what = "hipMalloc(tables)"; e = hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)); }
     if (e == hipSuccess) { what = "hipMalloc(flags)"; e = hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)); }
     if (e == hipSuccess) { what = "hipMalloc(accumulators)"; e = hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)); }
-    if (e == hipSuccess && hx_score_init() != HX_OK) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
+    if (e == hipSuccess && (hx_score_init() != HX_OK || hx_plan_init() != HX_OK)) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
     if (e == hipSuccess) {
         what = "launch of hx_clear_status_kernel";
         CommitArgs z{};

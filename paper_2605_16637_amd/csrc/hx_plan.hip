@@ -1,0 +1,347 @@
+// The planner around the scoring loop (Algorithm 1 main loop; Sec. 5.3):
+// one-pass ordering of the calls by their projected ratio, and the recomputing
+// greedy loop for small queues -- pick the most urgent call, give it the pair
+// with the earliest projected decode finish, add it to a simulated copy of the
+// pool state, score again.
+#include "hx_common.hpp"
+#include "hx_terms.hpp"
+#include "hx_search.hpp"
+
+#include <cmath>
+
+namespace {
+
+constexpr int kT = HX_MAX_TYPES;
+
+// ordering key of a ratio: a NaN (raised elsewhere as a bad index) sorts with +inf
+__device__ __forceinline__ float hx_rank_key(float r)
+{
+    return (__float_as_uint(r) & 0x7fffffffu) > 0x7f800000u ? INFINITY : r;
+}
+
+// ---- one-pass ordering -----------------------------------------------------------
+
+constexpr int RANK_TILE = 2048;      // calls compared against per block
+
+__global__ __launch_bounds__(256) void hx_rank_zero_kernel(int32_t *rank, int C)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < C) rank[c] = 0;
+}
+
+// rank[c] = number of calls ahead of c: larger ratio, or equal ratio and lower
+// index.  Block (i, j) counts, for 256 calls, those ahead of them among the
+// calls of tile j; the partial counts are added up with integer atomics.
+__global__ __launch_bounds__(256) void hx_rank_count_kernel(const float *ratio, int32_t *rank, int C)
+{
+    __shared__ float s_r[RANK_TILE];
+    const int k0 = blockIdx.y * RANK_TILE;
+    const int kn = min(RANK_TILE, C - k0);
+    for (int i = threadIdx.x; i < kn; i += blockDim.x) s_r[i] = hx_rank_key(ratio[k0 + i]);
+    __syncthreads();
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    const float r = hx_rank_key(ratio[c]);
+    int ahead = 0;
+    for (int i = 0; i < kn; ++i) {
+        const float x = s_r[i];
+        ahead += (x > r) || (x == r && k0 + i < c);
+    }
+    if (ahead) atomicAdd(&rank[c], ahead);
+}
+
+// ---- recomputing greedy -------------------------------------------------------------
+
+constexpr int GREEDY_THREADS = 1024;
+constexpr int GREEDY_WAVES = GREEDY_THREADS / HX_WAVE;
+
+struct GreedyArgs {
+    HxModelF m;
+    int C, P, D;
+    const int32_t *L_in, *L_out, *node, *wf;
+    const float *elapsed, *tail, *horizon;
+    int n_nodes, n_wf;
+    const HxPrepTables *prep;
+    const float *d_flops, *d_hbm;
+    const int32_t *p_backlog, *d_used, *d_cap, *d_batch, *d_qd;
+    int tokens_per_seq, max_batch;
+    int32_t *best_p, *best_d, *rank;
+    float *best_cost, *ratio;
+    int32_t *backlog_out, *used_out, *batch_out, *qd_out;
+    int32_t *status;
+};
+
+// LDS carve-up shared by host (size) and device (offsets), in 4-byte words
+struct GreedyLds {
+    int Dp, Pp, C, P, D;      // lengths of the LDS arrays (not the problem sizes)
+    __host__ __device__ GreedyLds(int dp_bound, int P_, int D_, int C_)
+        : Dp(dp_bound), Pp((P_ + HX_WAVE - 1) / HX_WAVE * HX_WAVE),
+          C((C_ + 3) & ~3), P((P_ + 3) & ~3), D((D_ + 3) & ~3) {}      // array lengths, kept 16-byte aligned
+    __host__ __device__ size_t words() const
+    {
+        return (size_t)7 * Dp + 4 * Pp + 2 * kT * kT + 16     // pool view, as in the fused search
+             + P + 7 * (size_t)D                               // simulated state and what is needed to re-derive an entry
+             + 5 * (size_t)C                                   // per call: pair, cost, ratio, flags
+             + 4 * GREEDY_WAVES                                // reduction scratch
+             + (size_t)GREEDY_WAVES * (2 * Dp + kT * kT);      // per-wave search buffers
+    }
+};
+
+enum : int { ALIVE = 1, DIRTY = 2 };
+
+// One block plans the whole queue: the pool tables, the simulated state and the
+// per-call results live in LDS, there is no launch between iterations.  A call
+// is scored again only if its current pair touches the instance a commit just
+// changed: additions to the state can only raise costs, so every other call
+// keeps its pair and cost exactly.
+__global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyArgs a, int dp_bound)
+{
+    extern __shared__ __align__(16) float smem[];
+    const HxPrepTables *__restrict__ t = a.prep;
+    const int Dp = t->n_entries;
+    const GreedyLds lay(dp_bound, a.P, a.D, a.C);
+    float *s_wait = smem;
+    float *s_c1 = s_wait + lay.Dp;
+    float *s_c2 = s_c1 + lay.Dp;
+    float *s_kB = s_c2 + lay.Dp;
+    int *s_free = (int *)(s_kB + lay.Dp);
+    int *s_orig = s_free + lay.Dp;
+    int *s_dtype = s_orig + lay.Dp;
+    float *s_pw = (float *)(s_dtype + lay.Dp);
+    float *s_pinvF = s_pw + lay.Pp;
+    float *s_pinvB = s_pinvF + lay.Pp;
+    int *s_ptype = (int *)(s_pinvB + lay.Pp);
+    float *s_invbw = (float *)(s_ptype + lay.Pp);
+    float *s_lat = s_invbw + kT * kT;
+    int *s_seg = (int *)(s_lat + kT * kT);
+    int *s_backlog = s_seg + 16;                       // simulated state
+    int *s_used = s_backlog + lay.P;
+    int *s_batch = s_used + lay.D;
+    int *s_qd = s_batch + lay.D;
+    int *s_cap = s_qd + lay.D;
+    int *s_pos = s_cap + lay.D;                        // entry of decode instance d
+    float *s_dinvF = (float *)(s_pos + lay.D);
+    float *s_dinvB = s_dinvF + lay.D;
+    int *s_bp = (int *)(s_dinvB + lay.D);              // per call
+    int *s_bd = s_bp + lay.C;
+    float *s_bc = (float *)(s_bd + lay.C);
+    float *s_ratio = s_bc + lay.C;
+    int *s_flags = (int *)(s_ratio + lay.C);
+    float *s_redv = (float *)(s_flags + lay.C);        // reduction scratch, then the pick
+    int *s_redi = (int *)(s_redv + GREEDY_WAVES);
+    int *s_pick = s_redi + GREEDY_WAVES;               // [0] call, [1] p, [2] d
+    float *s_wave = (float *)(s_pick + 2 * GREEDY_WAVES);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (HX_WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float2 *wbuf = (float2 *)(s_wave + (size_t)wave * (2 * lay.Dp + kT * kT));
+    float *xbuf = (float *)(wbuf + lay.Dp);
+
+    for (int e = tid; e < Dp; e += GREEDY_THREADS) {
+        s_wait[e] = t->dec_wait[e]; s_c1[e] = t->dec_c1[e]; s_c2[e] = t->dec_c2[e]; s_kB[e] = t->dec_kB[e];
+        s_free[e] = t->dec_free[e]; s_orig[e] = t->dec_orig[e]; s_dtype[e] = t->dec_type[e];
+    }
+    for (int p = tid; p < lay.Pp; p += GREEDY_THREADS) {
+        const bool in = p < a.P;
+        s_pw[p] = in ? t->pre_wait[p] : INFINITY;
+        s_pinvF[p] = in ? t->pre_invF[p] : 0.0f;
+        s_pinvB[p] = in ? t->pre_invB[p] : 0.0f;
+        s_ptype[p] = in ? t->pre_type[p] : 0;
+        if (in) s_backlog[p] = a.p_backlog[p];
+    }
+    for (int d = tid; d < a.D; d += GREEDY_THREADS) {
+        s_used[d] = a.d_used[d]; s_batch[d] = a.d_batch[d]; s_qd[d] = a.d_qd[d]; s_cap[d] = a.d_cap[d];
+        s_pos[d] = t->dec_pos[d];
+        s_dinvF[d] = 1.0f / a.d_flops[d]; s_dinvB[d] = 1.0f / a.d_hbm[d];
+    }
+    if (tid < kT * kT) { s_invbw[tid] = t->link_invbw[tid]; s_lat[tid] = t->link_lat[tid]; }
+    if (tid <= kT) s_seg[tid] = t->seg[tid];
+    for (int c = tid; c < a.C; c += GREEDY_THREADS) s_flags[c] = ALIVE | DIRTY;
+    __syncthreads();
+
+    int seg[kT + 1];
+#pragma unroll
+    for (int k = 0; k <= kT; ++k) seg[k] = __builtin_amdgcn_readfirstlane(s_seg[k]);
+    const HxPoolLds pool{s_wait, s_c1, s_c2, s_kB, s_free, s_orig, s_dtype, s_pw, s_pinvF, s_pinvB, s_ptype,
+                         s_invbw, s_lat, Dp, a.P, lay.Pp};
+
+    for (int k = 0; k < a.C; ++k) {
+        // (1) score the calls whose pair may have changed, on the simulated state
+        for (int c = wave; c < a.C; c += GREEDY_WAVES) {
+            if (s_flags[c] != (ALIVE | DIRTY)) continue;           // wave-uniform: c depends on the wave only
+            const HxBest b = hx_search_call<4, true>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
+            if (lane == 0) {
+                s_bp[c] = b.p; s_bd[c] = b.d; s_bc[c] = b.cost;
+                s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf,
+                                                c, b.cost, a.status);
+                s_flags[c] = ALIVE;
+            }
+        }
+        __syncthreads();
+        // (2) the most urgent remaining call: largest ratio, lowest index among equals
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int c = tid; c < a.C; c += GREEDY_THREADS) {
+            if (s_flags[c] & ALIVE) {
+                const float r = hx_rank_key(s_ratio[c]);
+                if (bi == 0x7fffffff || r > bv) { bv = r; bi = c; }
+            }
+        }
+#pragma unroll
+        for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+            bv = take ? ov : bv;
+            bi = take ? oi : bi;
+        }
+        if (lane == 0) { s_redv[wave] = bv; s_redi[wave] = bi; }
+        __syncthreads();
+        // (3) one thread records the pick and adds it to the simulated state
+        if (tid == 0) {
+            for (int w = 1; w < GREEDY_WAVES; ++w) {
+                const float ov = s_redv[w];
+                const int oi = s_redi[w];
+                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+            }
+            const int c = bi, p = s_bp[c], d = s_bd[c];
+            a.best_p[c] = p; a.best_d[c] = d; a.best_cost[c] = s_bc[c]; a.ratio[c] = s_ratio[c]; a.rank[c] = k;
+            s_flags[c] = 0;
+            s_pick[0] = c; s_pick[1] = p; s_pick[2] = d;
+            if (p >= 0) {
+                const int L = a.L_in[c], O = a.L_out[c];
+                long long bl = (long long)s_backlog[p] + L, qd = (long long)s_qd[d] + O, us = (long long)s_used[d] + L + O;
+                if (L < 0 || O < 0) { hx_raise(a.status, HX_ERR_INDEX); bl = s_backlog[p]; qd = s_qd[d]; us = s_used[d]; }
+                if (bl > 2147483647LL || qd > 2147483647LL || us > 2147483647LL) {
+                    hx_raise(a.status, HX_ERR_OVERFLOW);
+                    bl = min(bl, 2147483647LL); qd = min(qd, 2147483647LL); us = min(us, 2147483647LL);
+                }
+                s_backlog[p] = (int)bl; s_qd[d] = (int)qd; s_used[d] = (int)us;
+                const long long nb = (us + a.tokens_per_seq - 1) / a.tokens_per_seq;
+                s_batch[d] = (int)(nb > a.max_batch ? a.max_batch : nb);
+                // the derived tables of the two instances, by the functions the per-round prepare uses
+                s_pw[p] = hx_prefill_wait(a.m, s_backlog[p], s_pinvF[p]);
+                const HxDecF x = hx_decode_terms(a.m, s_used[d], s_batch[d], s_qd[d], s_dinvF[d], s_dinvB[d]);
+                const int e = s_pos[d];
+                s_wait[e] = x.wait; s_c1[e] = x.c1; s_c2[e] = x.c2; s_kB[e] = x.kB;
+                const long long fr = (long long)s_cap[d] - us;
+                s_free[e] = fr < -1 ? -1 : (int)fr;
+            }
+        }
+        __syncthreads();
+        // (4) calls whose pair touches a changed instance are scored again
+        const int pp = s_pick[1], pd = s_pick[2];
+        if (pp >= 0) {
+            for (int c = tid; c < a.C; c += GREEDY_THREADS)
+                if ((s_flags[c] & ALIVE) && (s_bp[c] == pp || s_bd[c] == pd)) s_flags[c] = ALIVE | DIRTY;
+        }
+        __syncthreads();
+    }
+    // the simulated state the plan leaves
+    for (int p = tid; p < a.P; p += GREEDY_THREADS) if (a.backlog_out) a.backlog_out[p] = s_backlog[p];
+    for (int d = tid; d < a.D; d += GREEDY_THREADS) {
+        if (a.used_out) a.used_out[d] = s_used[d];
+        if (a.batch_out) a.batch_out[d] = s_batch[d];
+        if (a.qd_out) a.qd_out[d] = s_qd[d];
+    }
+}
+
+__global__ __launch_bounds__(256) void hx_plan_no_pool_kernel(GreedyArgs a)
+{
+    // with an empty pool nothing is feasible: every call has infinite ratio and is ranked by index
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    a.best_p[c] = -1; a.best_d[c] = -1; a.best_cost[c] = INFINITY; a.rank[c] = c;
+    a.ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, INFINITY, a.status);
+}
+
+__global__ __launch_bounds__(256) void hx_copy_i32_kernel(const int32_t *src, int32_t *dst, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+}  // namespace
+
+// the planner kernel may use all of a CU's LDS; said once per process
+int hx_plan_init()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
+               ? HX_OK : HX_ERR_DEVICE;
+}
+
+extern "C" int hx_rank(hx_ctx *ctx, int32_t C, const float *ratio, int32_t *rank, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, C >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, C == 0 || (ratio && rank), HX_ERR_INVALID_ARG, "NULL array");
+    if (C == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    const int bx = (C + 255) / 256, by = (C + RANK_TILE - 1) / RANK_TILE;
+    HX_REQUIRE(ctx, by <= 65535, HX_ERR_SHAPE, "more than %d calls to rank", 65535 * RANK_TILE);
+    hx_rank_zero_kernel<<<bx, 256, 0, stream>>>(rank, C);
+    hx_rank_count_kernel<<<dim3(bx, by), 256, 0, stream>>>(ratio, rank, C);
+    return hx_check_launch(ctx, "hx_rank kernels");
+}
+
+extern "C" int hx_plan_greedy(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                              const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
+                              const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                              int32_t tokens_per_seq, int32_t max_batch,
+                              int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio, int32_t *rank,
+                              int32_t *backlog_tok_out, int32_t *used_tok_out, int32_t *batch_out, int32_t *qd_tok_out,
+                              void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, model && calls && pre && dec && links, HX_ERR_INVALID_ARG, "NULL table");
+    const int C = calls->n, P = pre->n, D = dec->n, T = links->n_types;
+    HX_REQUIRE(ctx, C >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, C <= HX_GREEDY_MAX_CALLS, HX_ERR_SHAPE, "%d calls beyond the %d the recomputing planner takes", C,
+               HX_GREEDY_MAX_CALLS);
+    HX_REQUIRE(ctx, P <= HX_GREEDY_MAX_INSTANCES && D <= HX_GREEDY_MAX_INSTANCES, HX_ERR_SHAPE,
+               "pool %d x %d beyond the %d instances per side the recomputing planner takes", P, D, HX_GREEDY_MAX_INSTANCES);
+    HX_REQUIRE(ctx, tokens_per_seq > 0 && max_batch >= 0, HX_ERR_INVALID_ARG, "tokens_per_seq must be positive");
+    HX_REQUIRE(ctx, best_p && best_d && best_cost && ratio && rank, HX_ERR_INVALID_ARG, "NULL output");
+    HX_REQUIRE(ctx, C == 0 || (calls->L_in && calls->L_out && calls->node && calls->wf && calls->elapsed && tail && horizon),
+               HX_ERR_INVALID_ARG, "the planner needs L_in, L_out, node, wf, elapsed, tail and horizon");
+    HX_REQUIRE(ctx, n_nodes >= 0 && n_wf >= 0, HX_ERR_INVALID_ARG, "negative n_nodes or n_wf");
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+
+    GreedyArgs a{};
+    a.m = HxModelF{model->kv_bytes_per_token, model->flops_per_token, model->attn_flops_per_token2,
+                   model->weight_bytes, model->nominal_batch};
+    a.C = C; a.P = P; a.D = D;
+    a.L_in = calls->L_in; a.L_out = calls->L_out; a.node = calls->node; a.wf = calls->wf; a.elapsed = calls->elapsed;
+    a.tail = tail; a.horizon = horizon; a.n_nodes = n_nodes; a.n_wf = n_wf;
+    a.prep = ctx->d_prep; a.d_flops = dec->flops; a.d_hbm = dec->hbm_bw;
+    a.p_backlog = pre->backlog_tok; a.d_used = dec->used_tok; a.d_cap = dec->cap_tok; a.d_batch = dec->batch; a.d_qd = dec->qd_tok;
+    a.tokens_per_seq = tokens_per_seq; a.max_batch = max_batch;
+    a.best_p = best_p; a.best_d = best_d; a.rank = rank; a.best_cost = best_cost; a.ratio = ratio;
+    a.backlog_out = backlog_tok_out; a.used_out = used_tok_out; a.batch_out = batch_out; a.qd_out = qd_tok_out;
+    a.status = ctx->d_status;
+
+    if (P == 0 || D == 0) {
+        // an empty side: nothing is feasible, the state is returned unchanged
+        if (P) HX_REQUIRE(ctx, pre->backlog_tok, HX_ERR_INVALID_ARG, "NULL member in prefill table");
+        if (D) HX_REQUIRE(ctx, dec->used_tok && dec->batch && dec->qd_tok, HX_ERR_INVALID_ARG, "NULL member in decode table");
+        if (C) hx_plan_no_pool_kernel<<<(C + 255) / 256, 256, 0, stream>>>(a);
+        if (P && backlog_tok_out) hx_copy_i32_kernel<<<(P + 255) / 256, 256, 0, stream>>>(pre->backlog_tok, backlog_tok_out, P);
+        if (D && used_tok_out) hx_copy_i32_kernel<<<(D + 255) / 256, 256, 0, stream>>>(dec->used_tok, used_tok_out, D);
+        if (D && batch_out) hx_copy_i32_kernel<<<(D + 255) / 256, 256, 0, stream>>>(dec->batch, batch_out, D);
+        if (D && qd_tok_out) hx_copy_i32_kernel<<<(D + 255) / 256, 256, 0, stream>>>(dec->qd_tok, qd_tok_out, D);
+        return hx_check_launch(ctx, "hx_plan_no_pool_kernel");
+    }
+    if (int rc = hx_prepare_pool(ctx, model, pre, dec, links, stream)) return rc;
+    const int dp_bound = (D + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP + (T - 1) * HX_DGROUP;
+    const GreedyLds lay(dp_bound, P, D, C);
+    const size_t lds = 4 * lay.words();
+    HX_REQUIRE(ctx, lds <= 160 * 1024, HX_ERR_SHAPE, "queue and pool need %zu B of LDS", lds);
+    hx_plan_greedy_kernel<<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
+    return hx_check_launch(ctx, "hx_plan_greedy_kernel");
+}

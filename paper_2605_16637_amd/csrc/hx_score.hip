@@ -139,12 +139,7 @@ struct ScoreArgs {
 // projected ratio, Eq. (2), with the downstream tail of the call's node
 __device__ __forceinline__ float hx_ratio(const ScoreArgs &a, int c, float best)
 {
-    int nd = a.node[c], w = a.wf[c];
-    if (nd < 0 || nd >= a.n_nodes || w < 0 || w >= a.n_wf) {
-        hx_raise(a.status, HX_ERR_INDEX);
-        return __uint_as_float(0x7fc00000u);   // quiet NaN
-    }
-    return ((a.elapsed[c] + best) + a.tail[nd]) / a.horizon[w];
+    return hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, best, a.status);
 }
 
 // ---- fused search ----------------------------------------------------------------
@@ -336,6 +331,32 @@ int check_ratio_inputs(hx_ctx *ctx, const hx_calls *calls, const float *tail, co
 
 }  // namespace
 
+// Validates the pool tables and enqueues the kernel that derives the per-round
+// tables (ctx->d_prep) from them.  Shared by every entry point that scores.
+int hx_prepare_pool(hx_ctx *ctx, const hx_model *model, const hx_prefill_tab *pre, const hx_decode_tab *dec,
+                    const hx_links *links, hipStream_t stream)
+{
+    HX_REQUIRE(ctx, model && pre && dec && links, HX_ERR_INVALID_ARG, "NULL table");
+    const int P = pre->n, D = dec->n, T = links->n_types;
+    HX_REQUIRE(ctx, P >= 0 && D >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, T >= 1 && T <= HX_MAX_TYPES, HX_ERR_SHAPE, "n_types %d outside 1..%d", T, HX_MAX_TYPES);
+    HX_REQUIRE(ctx, P <= HX_MAX_INSTANCES && D <= HX_MAX_INSTANCES, HX_ERR_SHAPE,
+               "pool %d x %d beyond %d instances per side", P, D, HX_MAX_INSTANCES);
+    HX_REQUIRE(ctx, P == 0 || (pre->flops && pre->hbm_bw && pre->backlog_tok && pre->type),
+               HX_ERR_INVALID_ARG, "NULL member in prefill table");
+    HX_REQUIRE(ctx, D == 0 || (dec->flops && dec->hbm_bw && dec->used_tok && dec->cap_tok && dec->batch &&
+                               dec->qd_tok && dec->type), HX_ERR_INVALID_ARG, "NULL member in decode table");
+    HX_REQUIRE(ctx, links->bw, HX_ERR_INVALID_ARG, "links.bw is NULL");
+    PrepArgs pa{};
+    pa.m = to_model(model); pa.P = P; pa.D = D; pa.T = T;
+    pa.p_flops = pre->flops; pa.p_hbm = pre->hbm_bw; pa.p_backlog = pre->backlog_tok; pa.p_type = pre->type;
+    pa.d_flops = dec->flops; pa.d_hbm = dec->hbm_bw; pa.d_used = dec->used_tok; pa.d_cap = dec->cap_tok;
+    pa.d_batch = dec->batch; pa.d_qd = dec->qd_tok; pa.d_type = dec->type;
+    pa.bw = links->bw; pa.lat = links->latency; pa.out = ctx->d_prep; pa.status = ctx->d_status;
+    hx_prepare_kernel<<<1, 1024, 0, stream>>>(pa);
+    return hx_check_launch(ctx, "hx_prepare_kernel");
+}
+
 // the fused search may use all 160 KB of LDS; said once per process, outside any stream work
 int hx_score_init()
 {
@@ -403,14 +424,7 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         return HX_OK;
     }
 
-    PrepArgs pa{};
-    pa.m = a.m; pa.P = P; pa.D = D; pa.T = T;
-    pa.p_flops = pre->flops; pa.p_hbm = pre->hbm_bw; pa.p_backlog = pre->backlog_tok; pa.p_type = pre->type;
-    pa.d_flops = dec->flops; pa.d_hbm = dec->hbm_bw; pa.d_used = dec->used_tok; pa.d_cap = dec->cap_tok;
-    pa.d_batch = dec->batch; pa.d_qd = dec->qd_tok; pa.d_type = dec->type;
-    pa.bw = links->bw; pa.lat = links->latency; pa.out = ctx->d_prep; pa.status = ctx->d_status;
-    hx_prepare_kernel<<<1, 1024, 0, stream>>>(pa);
-    if (int rc = hx_check_launch(ctx, "hx_prepare_kernel")) return rc;
+    if (int rc = hx_prepare_pool(ctx, model, pre, dec, links, stream)) return rc;
 
     if (fused) {
         // upper bound of the padded decode entries, known on the host without reading the device

@@ -128,3 +128,18 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
     __builtin_amdgcn_wave_barrier();
     return out;
 }
+
+// projected ratio of a call, Eq. (2) with the downstream tail of the call's
+// node: (elapsed + best + tail[node]) / horizon[wf].  A node or workflow index
+// outside the arrays gives NaN and raises HX_ERR_INDEX.
+__device__ __forceinline__ float hx_projected_ratio(const int32_t *node, const int32_t *wf, const float *elapsed,
+                                                    const float *tail, const float *horizon, int n_nodes, int n_wf,
+                                                    int c, float best, int32_t *status)
+{
+    const int nd = node[c], w = wf[c];
+    if (nd < 0 || nd >= n_nodes || w < 0 || w >= n_wf) {
+        hx_raise(status, HX_ERR_INDEX);
+        return __uint_as_float(0x7fc00000u);   // quiet NaN
+    }
+    return ((elapsed[c] + best) + tail[nd]) / horizon[w];
+}
