@@ -176,6 +176,42 @@ def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=3276
             "candidates_per_s": cand / wall, "placed_fraction_last_round": placed, "launch": "eager, synchronised every round"}
 
 
+def planner_leg(torch, ctx, synth, binding, seed):
+    """The planner around the scoring loop: the recomputing greedy plan of a small queue on pools of the
+    size the paper serves (8 + 8 instances of 3 classes), and of a larger queue; one-pass ordering."""
+    from oracle import hx_oracle as o
+    out = {}
+    rng = np.random.default_rng(seed)
+    for name, C, P, D, T in (("queue 64 x pool 8+8, 3 classes", 64, 8, 8, 3), ("queue 256 x pool 64+64, 4 classes", 256, 64, 64, 4)):
+        L0, O0 = synth.gen_lengths(rng, C)
+        types, links, pre, dec = synth.gen_pool(rng, P, D, T if T in (2, 4) else 4, L0, O0, near_capacity=False)
+        if T == 3:      # three of the four listed classes
+            pre["type"] %= 3; dec["type"] %= 3
+            pre["flops"], pre["hbm_bw"] = types["flops"][pre["type"]].copy(), types["hbm_bw"][pre["type"]].copy()
+            dec["flops"], dec["hbm_bw"] = types["flops"][dec["type"]].copy(), types["hbm_bw"][dec["type"]].copy()
+        node = np.arange(C, dtype=np.int32); wf = (np.arange(C) % 8).astype(np.int32)
+        tail = rng.uniform(0, 5, C).astype(np.float32); hor = rng.uniform(10, 60, 8).astype(np.float32)
+        elapsed = rng.uniform(0, 30, C).astype(np.float32)
+        calls = binding.to_device(dict(n=C, L_in=L0, L_out=O0, node=node, wf=wf, elapsed=elapsed))
+        dp, dd, dl = binding.to_device(pre), binding.to_device(dec), binding.to_device(links)
+        i32 = dict(dtype=torch.int32, device="cuda:0")
+        bufs = [torch.empty(C, **i32), torch.empty(C, **i32), torch.empty(C, device="cuda:0"), torch.empty(C, device="cuda:0"),
+                torch.empty(C, **i32)]
+        d_tail, d_hor = dev(tail), dev(hor)
+        fn = lambda: ctx.hx_plan_greedy(synth.MODEL, calls, dp, dd, dl, d_tail, d_hor, *bufs)
+        gpu_s = time_launches(torch, fn, 30)
+        t0 = time.perf_counter()
+        o.plan_greedy(synth.MODEL, L0, O0, elapsed, node, wf, tail, hor, pre, dec, links)
+        cpu_s = time.perf_counter() - t0
+        out[name] = {"gpu_us": gpu_s * 1e6, "oracle_1_thread_us": cpu_s * 1e6,
+                     "candidates_if_fully_rescored": C * (C + 1) // 2 * P * D}
+    ctx.hx_stream_status()
+    C = 32768
+    ratio = dev(rng.uniform(0.1, 9.0, C).astype(np.float32)); rank = torch.empty(C, dtype=torch.int32, device="cuda:0")
+    out["one-pass ordering of 32768 calls"] = {"gpu_us": time_launches(torch, lambda: ctx.hx_rank(ratio, rank), 30) * 1e6}
+    return out
+
+
 def cpu_baseline(rnd, target_s=12.0):
     """The oracle, as it stands, on a bounded sample of the same round."""
     from oracle import hx_oracle as o
@@ -305,6 +341,7 @@ def main():
 
     if not args.no_extras:
         out["streaming"] = streaming_leg(torch, ctx, synth, binding, args.seed, rounds=30)
+        out["planner"] = planner_leg(torch, ctx, synth, binding, args.seed)
     if args.calibration_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").fill_(1.0)
         dst = torch.empty_like(src)

@@ -29,24 +29,31 @@ __global__ __launch_bounds__(256) void hx_rank_zero_kernel(int32_t *rank, int C)
     if (c < C) rank[c] = 0;
 }
 
+// (ratio, index) as one unsigned 64-bit key that orders like "larger ratio first,
+// then lower index": the float bits made monotone, then the complemented index
+__device__ __forceinline__ unsigned long long hx_rank_key64(float r, int idx)
+{
+    unsigned b = __float_as_uint(hx_rank_key(r));
+    b ^= (b & 0x80000000u) ? 0xffffffffu : 0x80000000u;
+    return ((unsigned long long)b << 32) | (unsigned)(0xffffffffu - (unsigned)idx);
+}
+
 // rank[c] = number of calls ahead of c: larger ratio, or equal ratio and lower
 // index.  Block (i, j) counts, for 256 calls, those ahead of them among the
 // calls of tile j; the partial counts are added up with integer atomics.
 __global__ __launch_bounds__(256) void hx_rank_count_kernel(const float *ratio, int32_t *rank, int C)
 {
-    __shared__ float s_r[RANK_TILE];
+    __shared__ unsigned long long s_key[RANK_TILE];
     const int k0 = blockIdx.y * RANK_TILE;
     const int kn = min(RANK_TILE, C - k0);
-    for (int i = threadIdx.x; i < kn; i += blockDim.x) s_r[i] = hx_rank_key(ratio[k0 + i]);
+    for (int i = threadIdx.x; i < kn; i += blockDim.x) s_key[i] = hx_rank_key64(ratio[k0 + i], k0 + i);
     __syncthreads();
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
-    const float r = hx_rank_key(ratio[c]);
+    const unsigned long long mine = hx_rank_key64(ratio[c], c);
     int ahead = 0;
-    for (int i = 0; i < kn; ++i) {
-        const float x = s_r[i];
-        ahead += (x > r) || (x == r && k0 + i < c);
-    }
+#pragma unroll 8
+    for (int i = 0; i < kn; ++i) ahead += s_key[i] > mine;
     if (ahead) atomicAdd(&rank[c], ahead);
 }
 
@@ -94,6 +101,7 @@ enum : int { ALIVE = 1, DIRTY = 2 };
 // is scored again only if its current pair touches the instance a commit just
 // changed: additions to the state can only raise costs, so every other call
 // keeps its pair and cost exactly.
+template <int KP>
 __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyArgs a, int dp_bound)
 {
     extern __shared__ __align__(16) float smem[];
@@ -170,7 +178,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         // (1) score the calls whose pair may have changed, on the simulated state
         for (int c = wave; c < a.C; c += GREEDY_WAVES) {
             if (s_flags[c] != (ALIVE | DIRTY)) continue;           // wave-uniform: c depends on the wave only
-            const HxBest b = hx_search_call<4, true>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
+            const HxBest b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
             if (lane == 0) {
                 s_bp[c] = b.p; s_bd[c] = b.d; s_bc[c] = b.cost;
                 s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf,
@@ -267,9 +275,16 @@ __global__ __launch_bounds__(256) void hx_copy_i32_kernel(const int32_t *src, in
 // the planner kernel may use all of a CU's LDS; said once per process
 int hx_plan_init()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
-               ? HX_OK : HX_ERR_DEVICE;
+    const int lds = 160 * 1024;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<4>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return e == hipSuccess ? HX_OK : HX_ERR_DEVICE;
 }
 
 extern "C" int hx_rank(hx_ctx *ctx, int32_t C, const float *ratio, int32_t *rank, void *stream_)
@@ -342,6 +357,8 @@ extern "C" int hx_plan_greedy(hx_ctx *ctx, const hx_model *model, const hx_calls
     const GreedyLds lay(dp_bound, P, D, C);
     const size_t lds = 4 * lay.words();
     HX_REQUIRE(ctx, lds <= 160 * 1024, HX_ERR_SHAPE, "queue and pool need %zu B of LDS", lds);
-    hx_plan_greedy_kernel<<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
+    if (P <= 64) hx_plan_greedy_kernel<1><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
+    else if (P <= 128) hx_plan_greedy_kernel<2><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
+    else hx_plan_greedy_kernel<4><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
     return hx_check_launch(ctx, "hx_plan_greedy_kernel");
 }
