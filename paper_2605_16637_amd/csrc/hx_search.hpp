@@ -20,6 +20,41 @@
 
 #include <cmath>
 
+// Minimum over the 64 lanes of a wavefront with data-parallel-primitive lane
+// moves (no LDS traffic): two quad swaps and two row mirrors leave every row
+// of 16 lanes holding its minimum, two row broadcasts carry it to lane 63,
+// which is read back as a wave-uniform value.
+#define HX_DPP_MIN_STEP(T_, MINF, ctrl, row_mask)                                                        \
+    x = MINF(x, hx_from_bits<T_>(__builtin_amdgcn_update_dpp(hx_to_bits(x), hx_to_bits(x), ctrl, row_mask, 0xf, false)))
+
+template <typename T> __device__ __forceinline__ T hx_from_bits(int b);
+template <> __device__ __forceinline__ float hx_from_bits<float>(int b) { return __int_as_float(b); }
+template <> __device__ __forceinline__ int hx_from_bits<int>(int b) { return b; }
+__device__ __forceinline__ int hx_to_bits(float x) { return __float_as_int(x); }
+__device__ __forceinline__ int hx_to_bits(int x) { return x; }
+
+__device__ __forceinline__ float hx_wave_min(float x)
+{
+    HX_DPP_MIN_STEP(float, fminf, 0xB1, 0xf);     // quad_perm [1,0,3,2]
+    HX_DPP_MIN_STEP(float, fminf, 0x4E, 0xf);     // quad_perm [2,3,0,1]
+    HX_DPP_MIN_STEP(float, fminf, 0x141, 0xf);    // row_half_mirror
+    HX_DPP_MIN_STEP(float, fminf, 0x140, 0xf);    // row_mirror
+    HX_DPP_MIN_STEP(float, fminf, 0x142, 0xa);    // row_bcast15 into rows 1 and 3
+    HX_DPP_MIN_STEP(float, fminf, 0x143, 0xc);    // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+__device__ __forceinline__ int hx_wave_min(int x)
+{
+    HX_DPP_MIN_STEP(int, min, 0xB1, 0xf);
+    HX_DPP_MIN_STEP(int, min, 0x4E, 0xf);
+    HX_DPP_MIN_STEP(int, min, 0x141, 0xf);
+    HX_DPP_MIN_STEP(int, min, 0x140, 0xf);
+    HX_DPP_MIN_STEP(int, min, 0x142, 0xa);
+    HX_DPP_MIN_STEP(int, min, 0x143, 0xc);
+    return __builtin_amdgcn_readlane(x, 63);
+}
+
 // views of the pool tables staged in LDS
 struct HxPoolLds {
     const float *wait, *c1, *c2, *kB;      // decode entries (grouped by class, padded): availability hint and per-token terms
@@ -99,15 +134,10 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
             if (bj[j] < bestv) { bestv = bj[j]; bestp = chunk + j * HX_WAVE + lane; }
         }
     }
-    // wave minimum of (cost, p)
-#pragma unroll
-    for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
-        const float ov = __shfl_xor(bestv, off);
-        const int op = __shfl_xor(bestp, off);
-        const bool take = ov < bestv || (ov == bestv && op < bestp);
-        bestv = take ? ov : bestv;
-        bestp = take ? op : bestp;
-    }
+    // wave minimum of (cost, p): the minimum cost, then the lowest p among the lanes that hold it
+    const float lane_best = bestv;
+    bestv = hx_wave_min(lane_best);
+    bestp = hx_wave_min(lane_best == bestv ? bestp : 0x7fffffff);
     HxBest out{bestv, -1, -1};
     if (bestv < INFINITY) {
         out.p = bestp;
@@ -119,9 +149,7 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
             const float v = hx_candidate(done + xr[s.dtype[e]], wbuf[e].x, wbuf[e].y);
             if (v == bestv) dmin = min(dmin, s.orig[e]);
         }
-#pragma unroll
-        for (int off = HX_WAVE / 2; off > 0; off >>= 1) dmin = min(dmin, __shfl_xor(dmin, off));
-        out.d = dmin;
+        out.d = hx_wave_min(dmin);
     }
     // the next call of this wave rewrites the buffers: order its writes after these reads
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
