@@ -353,6 +353,18 @@ __device__ __forceinline__ void hx_push_parent(const AppendArgs &a, int u, float
     }
 }
 
+// same, for the single-workgroup loop: the list entry is written with a device-scope store
+__device__ __forceinline__ void hx_push_parent_scoped(const AppendArgs &a, int u, float rem_v, int level_v)
+{
+    bool grew = hx_raise_max_f32(&a.tail[u], rem_v);
+    int old = atomicMax(&a.level[u], level_v + 1);
+    grew = grew || (level_v + 1 > old);
+    if (grew && (uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch) {
+        int slot = atomicAdd(&a.counters[a.cout], 1);
+        __hip_atomic_store(&a.list_out[slot], u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 __global__ void hx_append_reset_kernel(int32_t *counters)
 {
     if (threadIdx.x < 3) counters[threadIdx.x] = 0;
@@ -394,6 +406,11 @@ __global__ __launch_bounds__(256) void hx_append_push_new_kernel(AppendArgs a)
     }
 }
 
+__global__ void hx_append_finish_kernel(AppendArgs a)
+{
+    if (threadIdx.x == 0 && a.counters[a.cin] != 0) hx_raise(a.status, HX_ERR_CAPACITY);
+}
+
 // one propagation sweep: nodes whose tail or level grew recompute rem, raise
 // their workflow horizon and push to their own parents
 __global__ __launch_bounds__(256) void hx_append_sweep_kernel(AppendArgs a)
@@ -415,9 +432,49 @@ __global__ __launch_bounds__(256) void hx_append_sweep_kernel(AppendArgs a)
     }
 }
 
-__global__ void hx_append_finish_kernel(AppendArgs a)
+// The remaining sweeps in one workgroup: after a few grid-wide sweeps the lists
+// are short, and what is left is a chain of dependent steps -- one launch loops
+// over them until the list is empty (or `sweeps` steps are done) instead of one
+// launch per step.  Every value another thread may have written is read with a
+// device-scope load.
+__global__ __launch_bounds__(1024) void hx_append_tail_kernel(AppendArgs a, int32_t *list0, int32_t *list1,
+                                                              int first, int sweeps)
 {
-    if (threadIdx.x == 0 && a.counters[a.cin] != 0) hx_raise(a.status, HX_ERR_CAPACITY);
+    __shared__ int s_n;
+    for (int s = first; s < first + sweeps; ++s) {
+        a.cin = (s + 1) % 3; a.cout = (s + 2) % 3; a.czero = s % 3;
+        a.list_in = (s & 1) ? list1 : list0;
+        a.list_out = (s & 1) ? list0 : list1;
+        a.epoch += 1;
+        if (threadIdx.x == 0) {
+            s_n = __hip_atomic_load(&a.counters[a.cin], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.counters[a.czero], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        const int n = s_n;
+        if (n == 0) break;                                   // uniform: nothing left to propagate
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            const int u = __hip_atomic_load(&a.list_in[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float r = a.cost[u] + tl;
+            a.rem[u] = r;
+            const int w = a.wf[u];
+            if (w >= 0) hx_raise_max_f32(&a.horizon[w], r);
+            for (int e = a.prow[u]; e < a.prow[u + 1]; ++e) {
+                int q = a.pcol[e];
+                if (q >= 0) hx_push_parent_scoped(a, q, r, lv);
+            }
+        }
+        __threadfence();
+        __syncthreads();
+    }
+    // the list the last step wrote must be empty, or the depth limit was too small
+    if (threadIdx.x == 0) {
+        const int last = (first + sweeps + 1) % 3;
+        if (__hip_atomic_load(&a.counters[last], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 &&
+            s_n != 0) hx_raise(a.status, HX_ERR_CAPACITY);
+    }
 }
 
 __global__ __launch_bounds__(256) void hx_fill_i32_kernel(int32_t *p, size_t n, int32_t v)
@@ -574,16 +631,24 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
     a.list_in = g.list[1]; a.list_out = g.list[0];
     hx_append_init_kernel<<<grid, 256, 0, stream>>>(a);
     hx_append_push_new_kernel<<<grid, 256, 0, stream>>>(a);
-    // sweep k reads the list sweep k-1 wrote; max_depth sweeps reach every ancestor
+    // sweep k reads the list sweep k-1 wrote; max_depth sweeps reach every ancestor.  The first
+    // few sweeps have long lists and run grid-wide, the rest is one workgroup looping
     const int sweep_grid = ctx->num_cu * 2;
-    for (int s = 0; s < g.max_depth; ++s) {
+    const int wide = g.max_depth < 3 ? g.max_depth : 3;
+    for (int s = 0; s < wide; ++s) {
         a.cin = (s + 1) % 3; a.cout = (s + 2) % 3; a.czero = s % 3;
         a.list_in = g.list[s & 1]; a.list_out = g.list[(s + 1) & 1];
         a.epoch = ++g.epoch;
         hx_append_sweep_kernel<<<sweep_grid, 256, 0, stream>>>(a);
     }
-    a.cin = (g.max_depth + 1) % 3;
-    hx_append_finish_kernel<<<1, 64, 0, stream>>>(a);
+    if (g.max_depth > wide) {
+        a.epoch = g.epoch;                       // the loop advances it once per step
+        hx_append_tail_kernel<<<1, 1024, 0, stream>>>(a, g.list[0], g.list[1], wide, g.max_depth - wide);
+        g.epoch += (uint32_t)(g.max_depth - wide);
+    } else {
+        a.cin = (g.max_depth + 1) % 3;
+        hx_append_finish_kernel<<<1, 64, 0, stream>>>(a);
+    }
     if (int rc = hx_check_launch(ctx, "hx_dag_append kernels")) return rc;
     g.n_nodes += n_new;
     g.n_edges += n_new_edges;
