@@ -24,6 +24,11 @@ ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # VALU issue slots the search needs per candidate: max, add, half a 3-input min
 OPS_PER_CANDIDATE = 2.5
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/
+# (counter x calibration factor of a plain copy); valid for the default workloads only, and to be
+# reset to None whenever the kernel changes until the counters are taken again
+FUSED_TRAFFIC_BYTES = {"large": 4.44e6 + 0.52e6}
+CP_TRAFFIC_BYTES = 31.74e6 + 25.88e6
 
 
 def dev(x):
@@ -284,7 +289,7 @@ def main():
                    "launch": "eager" if args.eager else "hip graph replay", "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (+ its table-prepare launch)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
-                     "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+                     "frac": achieved / ALU_PEAK_TOPS, "traffic": FUSED_TRAFFIC_BYTES.get(args.workload),
                      "ops_per_candidate": OPS_PER_CANDIDATE, "launch_ms": score_s * 1e3,
                      "candidates_per_s_kernel": n_cand / score_s},
     }
@@ -333,10 +338,25 @@ def main():
         ctx.hx_stream_status()
         cp_bytes = 4 * (d.n_nodes + 1) + 4 * d.n_edges + 4 * d.n_nodes + 4 * (d.n_wf + 1) + 12 * d.n_nodes + 4 * d.n_wf
         gbs = cp_bytes / (cp_ms * 1e-3) / 1e9
+        # what a plain device copy moving the same number of bytes takes (half read, half written),
+        # over rotating buffers: the practical floor of a launch this small
+        half = cp_bytes // 8
+        bufs = [(torch.empty(half, dtype=torch.float32, device="cuda:0").fill_(1.0),
+                 torch.empty(half, dtype=torch.float32, device="cuda:0")) for _ in range(n_copies)]
+        j = [0]
+
+        def copy_once():
+            a, b = bufs[j[0] % n_copies]
+            j[0] += 1
+            b.copy_(a)
+
+        copy_ms = time_launches(torch, copy_once, reps, warmup=n_copies) * 1e3
+        del bufs
         out["critical_path"] = {"workload": "critical-path stress: %d workflows, %d nodes, %d edges" % (d.n_wf, d.n_nodes, d.n_edges),
                                 "kernel": "hx_cp_local_kernel", "bound": "hbm", "launch_ms": cp_ms,
                                 "algorithmic_bytes": cp_bytes, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                "frac": gbs / HBM_PEAK_GBS, "traffic": None, "rotating_copies": n_copies}
+                                "frac": gbs / HBM_PEAK_GBS, "traffic": CP_TRAFFIC_BYTES, "rotating_copies": n_copies,
+                                "plain_copy_same_bytes_ms": copy_ms}
         del sets
 
     if not args.no_extras:
