@@ -83,6 +83,35 @@
  *  R14 one-pass ordering (Sec. 5.3, larger queues): rank = position by
  *                        decreasing R, equal R by increasing call index
  *
+ * Decode stage (Sec. 5.4; calls whose KV has arrived and that wait for decode
+ * admission).  Times are seconds from now.
+ *  R22 token-capacity intervals: decode instance d holds intervals
+ *                        j = (s_j, e_j, m_j): m_j tokens of KV occupied on
+ *                        s_j <= tau < e_j (resident sequences have s_j <= 0,
+ *                        planned ones start later);
+ *                        occ_d(tau) = sum of m_j over the intervals holding tau
+ *  R23 capacity-feasible start: t is feasible for call c on d when
+ *                        occ_d(tau) + m(c) <= cap_d for every tau in
+ *                        [t, t + Tdec(c,d)), m(c) = L + O (Eq. 3);
+ *                        S(c,d) = the earliest feasible t >= 0.  Occupancy only
+ *                        drops where an interval ends, so S is 0 or some e_j.
+ *                        m(c) > cap_d (Eq. 4): never feasible, S = +infinity
+ *  R24 decode-stage cost Delta_D(c,d) = S(c,d) + Tdec(c,d): waiting for decode
+ *                        capacity plus decode execution (Sec. 5.1), Tdec by R5
+ *                        on the snapshot (batch_d, used_d)
+ *  R25 legal instances   a call locked to d (Sec. 5.4) may only go to d; a free
+ *                        call to any instance; best = lexicographic minimum of
+ *                        (Delta_D, d); nothing legal and feasible -> (-1, +inf)
+ *  R26 decode greedy     (Sec. 5.4, small queues) repeat: score every remaining
+ *                        call on the simulated intervals; take the call of
+ *                        largest R = (elapsed + Delta_D + tail)/H, equal R by
+ *                        lowest index; record instance, start, finish, R, rank;
+ *                        append (S, S + Tdec, m(c)) to that instance.  Only the
+ *                        intervals are simulated (batch_d, used_d of R5 stay as
+ *                        in the snapshot).  A call with nothing feasible is
+ *                        ranked at once with (-1, +inf) and changes nothing.
+ *                        Larger queues: one scoring pass, then R14.
+ *
  * The choice of these formulas cannot be checked against printed values of
  * the paper (it prints none): parity with "the paper's estimator" is
  * unpinned.  What the tests pin is that this file computes R1..R12 as
@@ -527,6 +556,129 @@ int hxo_plan_greedy(const hxo_model *m,
             p_backlog[pick_p] = (int32_t)bl; d_qd[pick_d] = (int32_t)qd; d_used[pick_d] = (int32_t)us;
             int64_t b = (us + tokens_per_seq - 1) / tokens_per_seq;
             d_batch[pick_d] = (int32_t)(b > max_batch ? max_batch : b);
+        }
+    }
+    free(done);
+    return rc;
+}
+
+/* ---- decode stage (Sec. 5.4): capacity intervals, locks, greedy ------------- */
+
+/* R22: tokens occupied on an instance at time tau. */
+int64_t hxo_occupancy(int32_t K, const double *iv_start, const double *iv_end, const int32_t *iv_tok, double tau)
+{
+    int64_t occ = 0;
+    for (int32_t j = 0; j < K; ++j)
+        if (iv_start[j] <= tau && tau < iv_end[j]) occ += iv_tok[j];
+    return occ;
+}
+
+/* R23: is a start at t capacity-feasible for a call of m_tok tokens decoding
+ * for T seconds?  Occupancy only rises where an interval starts, so the window
+ * [t, t + T) is checked at t and at every interval start inside it. */
+int hxo_start_is_feasible(int32_t m_tok, double T, int32_t cap_tok, double t,
+                          int32_t K, const double *iv_start, const double *iv_end, const int32_t *iv_tok)
+{
+    if (hxo_occupancy(K, iv_start, iv_end, iv_tok, t) + (int64_t)m_tok > (int64_t)cap_tok) return 0;
+    for (int32_t j = 0; j < K; ++j)
+        if (iv_start[j] > t && iv_start[j] < t + T &&
+            hxo_occupancy(K, iv_start, iv_end, iv_tok, iv_start[j]) + (int64_t)m_tok > (int64_t)cap_tok) return 0;
+    return 1;
+}
+
+/* R23: earliest capacity-feasible start, by trying now and every interval end. */
+double hxo_decode_start(int32_t m_tok, double T, int32_t cap_tok,
+                        int32_t K, const double *iv_start, const double *iv_end, const int32_t *iv_tok)
+{
+    if ((int64_t)m_tok > (int64_t)cap_tok) return INFINITY;
+    double best = INFINITY;
+    if (hxo_start_is_feasible(m_tok, T, cap_tok, 0.0, K, iv_start, iv_end, iv_tok)) best = 0.0;
+    for (int32_t j = 0; j < K; ++j) {
+        double t = iv_end[j];
+        if (t > 0.0 && t < best && hxo_start_is_feasible(m_tok, T, cap_tok, t, K, iv_start, iv_end, iv_tok)) best = t;
+    }
+    return best;
+}
+
+/*
+ * R24, R25: decode-stage score of every (call, instance).  Interval lists are
+ * stored with a fixed stride: instance d owns entries d*stride .. d*stride +
+ * iv_count[d] - 1.  t_scale multiplies every decode time (1 for the method
+ * itself; the parity tests use it to bracket fp32 rounding of Tdec).
+ * start, cost: [Q*D] or NULL; best_*: [Q].  Returns -3 on a lock outside
+ * [-1, D).
+ */
+int hxo_decode_score(const hxo_model *m, int32_t Q, const int32_t *L_in, const int32_t *L_out, const int32_t *lock,
+                     int32_t D, const float *dF, const float *dB, const int32_t *d_used, const int32_t *d_cap,
+                     const int32_t *d_batch,
+                     int32_t stride, const int32_t *iv_count, const double *iv_start, const double *iv_end,
+                     const int32_t *iv_tok, double t_scale,
+                     double *start, double *cost, int32_t *best_d, double *best_start, double *best_cost)
+{
+    if (Q < 0 || D < 0 || stride < 0) return -1;
+    for (int32_t c = 0; c < Q; ++c)
+        if (lock && (lock[c] < -1 || lock[c] >= D)) return -3;
+    for (int32_t c = 0; c < Q; ++c) {
+        double bc = INFINITY, bs = INFINITY;
+        int32_t bd = -1;
+        for (int32_t d = 0; d < D; ++d) {
+            double S = INFINITY, v = INFINITY;
+            if (!lock || lock[c] < 0 || lock[c] == d) {
+                double T = t_scale * (double)L_out[c] *
+                           hxo_decode_token_time(m, L_in[c], L_out[c], d_batch[d], d_used[d], (double)dF[d], (double)dB[d]);
+                int64_t need = (int64_t)L_in[c] + (int64_t)L_out[c];
+                int32_t m_tok = need > 2147483647LL ? 2147483647 : (int32_t)need;
+                if (need <= (int64_t)d_cap[d])
+                    S = hxo_decode_start(m_tok, T, d_cap[d], iv_count[d], iv_start + (size_t)d * stride,
+                                         iv_end + (size_t)d * stride, iv_tok + (size_t)d * stride);
+                v = S + T;
+            }
+            if (start) start[(size_t)c * D + d] = S;
+            if (cost) cost[(size_t)c * D + d] = v;
+            if (v < bc) { bc = v; bs = S; bd = d; }
+        }
+        best_d[c] = bd; best_start[c] = bs; best_cost[c] = bc;
+    }
+    return 0;
+}
+
+/*
+ * R26: recomputing greedy of the decode stage.  The interval lists are
+ * extended in place (iv_count grows); -4 when an instance's list is full.
+ */
+int hxo_decode_plan_greedy(const hxo_model *m, int32_t Q, const int32_t *L_in, const int32_t *L_out, const int32_t *lock,
+                           const double *elapsed, const int32_t *node, const int32_t *wf,
+                           const double *tail, const double *horizon,
+                           int32_t D, const float *dF, const float *dB, const int32_t *d_used, const int32_t *d_cap,
+                           const int32_t *d_batch,
+                           int32_t stride, int32_t *iv_count, double *iv_start, double *iv_end, int32_t *iv_tok,
+                           int32_t *best_d, double *best_start, double *best_cost, double *ratio, int32_t *rank)
+{
+    if (Q < 0 || D < 0 || stride < 0) return -1;
+    uint8_t *done = (uint8_t *)calloc((size_t)Q + 1, 1);
+    if (!done) return -3;
+    int rc = 0;
+    for (int32_t k = 0; k < Q && rc == 0; ++k) {
+        int32_t pick = -1, pick_d = -1;
+        double pick_r = 0.0, pick_s = 0.0, pick_cost = 0.0;
+        for (int32_t c = 0; c < Q; ++c) {
+            if (done[c]) continue;
+            int32_t bd;
+            double bs, bc;
+            rc = hxo_decode_score(m, 1, L_in + c, L_out + c, lock ? lock + c : NULL, D, dF, dB, d_used, d_cap, d_batch,
+                                  stride, iv_count, iv_start, iv_end, iv_tok, 1.0, NULL, NULL, &bd, &bs, &bc);
+            if (rc) break;
+            double r = (elapsed[c] + bc + tail[node[c]]) / horizon[wf[c]];
+            if (pick < 0 || r > pick_r) { pick = c; pick_r = r; pick_d = bd; pick_s = bs; pick_cost = bc; }
+        }
+        if (rc) break;
+        done[pick] = 1;
+        best_d[pick] = pick_d; best_start[pick] = pick_s; best_cost[pick] = pick_cost; ratio[pick] = pick_r; rank[pick] = k;
+        if (pick_d >= 0) {
+            if (iv_count[pick_d] >= stride) { rc = -4; break; }
+            size_t at = (size_t)pick_d * stride + iv_count[pick_d];
+            iv_start[at] = pick_s; iv_end[at] = pick_cost; iv_tok[at] = L_in[pick] + L_out[pick];
+            iv_count[pick_d] += 1;
         }
     }
     free(done);

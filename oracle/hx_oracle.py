@@ -47,7 +47,7 @@ def lib():
         _lib.hxo_score_one.restype = C.c_double
         _lib.hxo_candidate_cost.restype = C.c_double
         for name in ("hxo_prefill_wait", "hxo_prefill_time", "hxo_transfer_time",
-                     "hxo_decode_step", "hxo_decode_wait", "hxo_decode_token_time"):
+                     "hxo_decode_step", "hxo_decode_wait", "hxo_decode_token_time", "hxo_decode_start"):
             getattr(_lib, name).restype = C.c_double
     return _lib
 
@@ -264,6 +264,83 @@ def plan_greedy(model, L_in, L_out, elapsed, node, wf, tail, horizon, pre, dec, 
     if rc:
         raise ValueError(f"hxo_plan_greedy failed: {rc}")
     return PlanResult(bp, bd, bc, rt, rk, bl, us, ba, qd)
+
+
+# ---- decode stage (R22-R26) -------------------------------------------------------
+def decode_start(m_tok, T, cap_tok, iv_start, iv_end, iv_tok) -> float:
+    """R23: earliest capacity-feasible start of m_tok tokens for T seconds on one instance."""
+    s, e, k = _f64(iv_start), _f64(iv_end), _i32(iv_tok)
+    return float(lib().hxo_decode_start(C.c_int32(int(m_tok)), C.c_double(float(T)), C.c_int32(int(cap_tok)),
+                                        C.c_int32(s.size), _p(s), _p(e), _p(k)))
+
+
+@dataclass
+class DecodeScore:
+    best_d: np.ndarray
+    best_start: np.ndarray
+    best_cost: np.ndarray
+    start: np.ndarray | None
+    cost: np.ndarray | None
+
+
+def _intervals(iv, D):
+    stride = int(iv["stride"])
+    cnt = _i32(iv["count"]).copy()
+    s, e, k = _f64(iv["start"]).reshape(-1).copy(), _f64(iv["end"]).reshape(-1).copy(), _i32(iv["tok"]).reshape(-1).copy()
+    assert cnt.size == D and s.size == e.size == k.size == D * stride and (cnt <= stride).all() and (cnt >= 0).all()
+    return stride, cnt, s, e, k
+
+
+def decode_score(model, L_in, L_out, lock, dec, iv, t_scale=1.0, want_all=False) -> DecodeScore:
+    """R24/R25 over all (call, decode instance) pairs."""
+    L_in, L_out = _i32(L_in), _i32(L_out)
+    lock = None if lock is None else _i32(lock)
+    dF, dB, dus, dcap, dba = _f32(dec["flops"]), _f32(dec["hbm_bw"]), _i32(dec["used_tok"]), _i32(dec["cap_tok"]), _i32(dec["batch"])
+    Q, D = L_in.size, dF.size
+    stride, cnt, s, e, k = _intervals(iv, D)
+    bd = np.empty(Q, np.int32); bs = np.empty(Q, np.float64); bc = np.empty(Q, np.float64)
+    st = np.empty((Q, D), np.float64) if want_all else None
+    co = np.empty((Q, D), np.float64) if want_all else None
+    m = _model(model)
+    rc = lib().hxo_decode_score(C.byref(m), Q, _p(L_in), _p(L_out), _p(lock), D, _p(dF), _p(dB), _p(dus), _p(dcap), _p(dba),
+                                stride, _p(cnt), _p(s), _p(e), _p(k), C.c_double(float(t_scale)),
+                                _p(st), _p(co), _p(bd), _p(bs), _p(bc))
+    if rc:
+        raise ValueError(f"hxo_decode_score failed: {rc}")
+    return DecodeScore(bd, bs, bc, st, co)
+
+
+@dataclass
+class DecodePlan:
+    best_d: np.ndarray
+    best_start: np.ndarray
+    best_cost: np.ndarray
+    ratio: np.ndarray
+    rank: np.ndarray
+    count: np.ndarray
+    start: np.ndarray
+    end: np.ndarray
+    tok: np.ndarray
+
+
+def decode_plan_greedy(model, L_in, L_out, lock, elapsed, node, wf, tail, horizon, dec, iv) -> DecodePlan:
+    """R26: recomputing greedy of the decode stage; returns the plan and the extended interval lists."""
+    L_in, L_out, node, wf = _i32(L_in), _i32(L_out), _i32(node), _i32(wf)
+    lock = None if lock is None else _i32(lock)
+    elapsed, tail, horizon = _f64(elapsed), _f64(tail), _f64(horizon)
+    dF, dB, dus, dcap, dba = _f32(dec["flops"]), _f32(dec["hbm_bw"]), _i32(dec["used_tok"]), _i32(dec["cap_tok"]), _i32(dec["batch"])
+    Q, D = L_in.size, dF.size
+    stride, cnt, s, e, k = _intervals(iv, D)
+    bd = np.empty(Q, np.int32); rk = np.empty(Q, np.int32)
+    bs = np.empty(Q, np.float64); bc = np.empty(Q, np.float64); rt = np.empty(Q, np.float64)
+    m = _model(model)
+    with np.errstate(all="ignore"):
+        rc = lib().hxo_decode_plan_greedy(C.byref(m), Q, _p(L_in), _p(L_out), _p(lock), _p(elapsed), _p(node), _p(wf),
+                                          _p(tail), _p(horizon), D, _p(dF), _p(dB), _p(dus), _p(dcap), _p(dba),
+                                          stride, _p(cnt), _p(s), _p(e), _p(k), _p(bd), _p(bs), _p(bc), _p(rt), _p(rk))
+    if rc:
+        raise ValueError(f"hxo_decode_plan_greedy failed: {rc}")
+    return DecodePlan(bd, bs, bc, rt, rk, cnt, s.reshape(D, stride), e.reshape(D, stride), k.reshape(D, stride))
 
 
 # scalar term accessors, for the round-number pins

@@ -254,6 +254,71 @@ def make_round(name: str, seed: int = 1, **override) -> Round:
     return Round(name, seed, dict(MODEL), dag, calls, types, links, pre, dec)
 
 
+def gen_intervals(rng: np.random.Generator, cap_tok, demand, stride: int, n_resident: int, n_planned: int):
+    """Decode token-capacity intervals of every decode instance, fixed stride.
+
+    Per instance: ``n_resident`` entries that hold KV now (start in the last
+    20 s, release within the next 30 s; one entry may stand for a group of
+    sequences released together) whose token counts split, with random
+    weights, an occupancy of cap minus a free amount; the free amount is a
+    U(0.2, 1) quantile of the waiting calls' demands, so a good share of the
+    calls does not fit an instance right now and has to wait for releases.
+    Then 0..``n_planned`` planned sequences with demands drawn like calls, that
+    start within the next 10 s and hold their tokens for 1..20 s.  Entries
+    beyond count[d] are filler.  Times are float32 seconds from now."""
+    cap_tok = np.asarray(cap_tok, np.int64)
+    demand = np.sort(np.asarray(demand, np.int64))
+    D = cap_tok.size
+    assert n_resident + n_planned <= stride and n_resident >= 1
+    start = np.zeros((D, stride), np.float32)
+    end = np.zeros((D, stride), np.float32)
+    tok = np.zeros((D, stride), np.int32)
+    count = np.zeros(D, np.int32)
+    for d in range(D):
+        free = demand[min(int(rng.uniform(0.2, 1.0) * demand.size), demand.size - 1)]
+        occ0 = max(int(cap_tok[d] - free), 0)
+        w = rng.random(n_resident) + 0.1
+        share = np.floor(w / w.sum() * occ0).astype(np.int64)
+        share[0] += occ0 - share.sum()
+        k_pl = int(rng.integers(0, n_planned + 1))
+        n = n_resident + k_pl
+        start[d, :n_resident] = -rng.uniform(0.0, 20.0, n_resident)
+        end[d, :n_resident] = rng.uniform(0.05, 30.0, n_resident)
+        tok[d, :n_resident] = share
+        Lp, Op = gen_lengths(rng, max(k_pl, 1))
+        s_pl = rng.uniform(0.0, 10.0, k_pl)
+        start[d, n_resident:n] = s_pl
+        end[d, n_resident:n] = s_pl + rng.uniform(1.0, 20.0, k_pl)
+        tok[d, n_resident:n] = (Lp.astype(np.int64) + Op)[:k_pl]
+        count[d] = n
+    return dict(stride=stride, count=count, start=start.reshape(-1), end=end.reshape(-1), tok=tok.reshape(-1))
+
+
+# decode-stage workloads: (n_wf, size_lo, size_hi, Q, D, T, stride, n_resident, n_planned, lock_fraction)
+DECODE_WORKLOADS = {
+    "decode_tiny": (8, 4, 12, 48, 4, 2, 16, 10, 3, 0.5),
+    "decode_mid": (1000, 10, 30, 4096, 64, 4, 64, 56, 6, 0.5),
+    "decode_large": (4096, 10, 30, 16384, 256, 8, 128, 112, 12, 0.5),
+}
+
+
+def make_decode_round(name: str, seed: int = 1, **override):
+    """One decode-stage round: a queue of calls whose KV has arrived (about
+    half of them locked to an instance), the decode table and its intervals.
+    Returns (Round, lock, intervals); the Round's prefill side is a 1-instance stub."""
+    keys = ("n_wf", "size_lo", "size_hi", "Q", "D", "T", "stride", "n_resident", "n_planned", "lock_fraction")
+    cfg = dict(zip(keys, DECODE_WORKLOADS[name]))
+    cfg.update(override)
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    dag = gen_dag(rng, cfg["n_wf"], cfg["size_lo"], cfg["size_hi"], 4, 12, 0.4, 1.0)
+    calls = gen_calls(rng, dag, cfg["Q"])
+    types, links, pre, dec = gen_pool(rng, 1, cfg["D"], cfg["T"], calls["L_in"], calls["L_out"], False)
+    iv = gen_intervals(rng, dec["cap_tok"], calls["L_in"].astype(np.int64) + calls["L_out"], cfg["stride"],
+                       cfg["n_resident"], cfg["n_planned"])
+    lock = np.where(rng.random(cfg["Q"]) < cfg["lock_fraction"], rng.integers(0, cfg["D"], cfg["Q"]), -1).astype(np.int32)
+    return Round(name, seed, dict(MODEL), dag, calls, types, links, pre, dec), lock, iv
+
+
 class StreamGen:
     """Rounds of a live system: every round reveals 0..8 new calls per live
     workflow (parents among that workflow's recent nodes), a workflow that has

@@ -1,0 +1,214 @@
+"""Pins of the decode-stage oracle (Sec. 5.4: capacity-feasible start on token-capacity
+intervals, instance locks, decode greedy) against things other than itself: a hand-worked
+instance, the closed form when nothing starts in the future, an integer-time simulation,
+numpy's argmin over the materialised costs, and capacity validity of a finished plan."""
+import numpy as np
+import pytest
+
+from oracle import hx_oracle as o
+from paper_2605_16637_amd import synth
+from helpers import ROUND_MODEL, read_rows
+
+
+def test_hand_worked_instance():
+    s, e, k = [-5.0, -2.0, 6.0], [4.0, 7.0, 12.0], [40, 30, 50]
+    rows = [r for r in read_rows("decode_intervals.txt") if r[0] == "case"]
+    assert len(rows) == 9
+    for _, m, T, want in rows:
+        assert o.decode_start(int(m), float(T), 100, s, e, k) == float(want), (m, T)
+
+
+def test_only_resident_sequences_closed_form():
+    """With every start in the past occupancy only falls: the start is the first release
+    after which what is still resident leaves room (a sort and a suffix sum)."""
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        K = int(rng.integers(0, 12))
+        s = -rng.uniform(0, 5, K); e = rng.uniform(-1, 20, K); k = rng.integers(1, 50, K)
+        cap = int(rng.integers(20, 200)); m = int(rng.integers(1, 120)); T = float(rng.uniform(0, 10))
+        got = o.decode_start(m, T, cap, s, e, k)
+        if m > cap:
+            assert got == np.inf
+            continue
+        # candidate times in increasing order; resident after t = tokens of the entries released later
+        want = None
+        for t in np.concatenate([[0.0], np.sort(e[e > 0])]):
+            if k[e > t].sum() + m <= cap:
+                want = float(t)
+                break
+        assert got == want
+
+
+def test_against_integer_time_simulation():
+    """Integer times: a start is feasible iff the occupancy array fits at every integer
+    second of the window; the earliest such second must be what the oracle returns
+    (which also pins that only `now` and interval ends need to be tried)."""
+    rng = np.random.default_rng(6)
+    hits_window = 0
+    for _ in range(400):
+        K = int(rng.integers(1, 9))
+        s = rng.integers(-6, 25, K); e = s + rng.integers(1, 15, K); k = rng.integers(5, 60, K)
+        cap = int(rng.integers(60, 160)); m = int(rng.integers(1, 100)); T = int(rng.integers(1, 12))
+        occ = np.zeros(80, np.int64)                       # occupancy on [t, t+1), t = 0..79
+        for a, b, w in zip(s, e, k):
+            occ[max(a, 0):max(b, 0)] += w
+        want = np.inf
+        if m <= cap:
+            for t in range(0, 60):
+                if (occ[t:t + T] + m <= cap).all():
+                    want = float(t)
+                    break
+        got = o.decode_start(m, float(T), cap, s.astype(float), e.astype(float), k)
+        assert got == want, (s, e, k, cap, m, T)
+        if np.isfinite(want) and want > 0 and (occ[int(want):] + m > cap).any():
+            hits_window += 1
+    assert hits_window > 20            # starts that had to clear a later, planned interval were exercised
+
+
+def test_start_monotone_and_limits():
+    rng = np.random.default_rng(7)
+    for _ in range(100):
+        K = 10
+        s = rng.uniform(-5, 10, K); e = s + rng.uniform(0.5, 10, K); k = rng.integers(5, 60, K)
+        cap = 150
+        last = -1.0
+        for m in range(1, 150, 7):
+            v = o.decode_start(m, 3.0, cap, s, e, k)
+            assert v >= last
+            last = v
+        last = -1.0
+        for T in np.linspace(0, 20, 15):
+            v = o.decode_start(60, float(T), cap, s, e, k)
+            assert v >= last
+            last = v
+        assert o.decode_start(60, 3.0, 10**9, s, e, k) == 0.0              # room for everything: start now
+        assert o.decode_start(150, 1.0, cap, s, e, k) <= e.max()           # after the last release it always fits
+        assert o.decode_start(60, 3.0, cap, [], [], []) == 0.0
+
+
+def _round(name="decode_tiny", seed=1, **kw):
+    r, lock, iv = synth.make_decode_round(name, seed, **kw)
+    return r, lock, iv
+
+
+def test_score_recomposes_and_selects_like_numpy():
+    r, lock, iv = _round()
+    L, O = r.calls["L_in"], r.calls["L_out"]
+    s = o.decode_score(r.model, L, O, lock, r.dec, iv, want_all=True)
+    Q, D = s.cost.shape
+    K = iv["stride"]
+    for c in range(Q):
+        for d in range(D):
+            legal = lock[c] < 0 or lock[c] == d
+            if not legal:
+                assert np.isinf(s.cost[c, d]) and np.isinf(s.start[c, d])
+                continue
+            T = O[c] * o.term("decode_token_time", r.model, int(L[c]), int(O[c]), int(r.dec["batch"][d]),
+                              int(r.dec["used_tok"][d]), float(r.dec["flops"][d]), float(r.dec["hbm_bw"][d]))
+            n = iv["count"][d]
+            S = o.decode_start(int(L[c] + O[c]), T, int(r.dec["cap_tok"][d]), iv["start"][d * K:d * K + n],
+                               iv["end"][d * K:d * K + n], iv["tok"][d * K:d * K + n])
+            assert s.start[c, d] == S and s.cost[c, d] == pytest.approx(S + T, rel=1e-14)
+    want_d = np.where(np.isfinite(s.cost.min(axis=1)), s.cost.argmin(axis=1), -1)
+    assert np.array_equal(s.best_d, want_d)
+    assert np.array_equal(s.best_cost, s.cost.min(axis=1))
+    assert np.array_equal(s.best_start, np.where(want_d >= 0, s.start[np.arange(Q), np.maximum(want_d, 0)], np.inf))
+    # a locked call sits on its instance or nowhere
+    locked = lock >= 0
+    assert ((s.best_d[locked] == lock[locked]) | (s.best_d[locked] == -1)).all()
+    assert (s.best_start > 0).any() and (s.best_start == 0).any()
+
+
+def test_score_lock_is_the_single_column():
+    """Sec. 5.4: a locked call cannot migrate -- its result is the D = 1 problem of that instance."""
+    r, lock, iv = _round(seed=2)
+    L, O = r.calls["L_in"], r.calls["L_out"]
+    free = o.decode_score(r.model, L, O, None, r.dec, iv, want_all=True)
+    K = iv["stride"]
+    for d in range(len(r.dec["flops"])):
+        one = {k: np.asarray(v)[d:d + 1] for k, v in r.dec.items() if k != "n"}
+        iv1 = dict(stride=K, count=iv["count"][d:d + 1], start=iv["start"][d * K:(d + 1) * K],
+                   end=iv["end"][d * K:(d + 1) * K], tok=iv["tok"][d * K:(d + 1) * K])
+        col = o.decode_score(r.model, L, O, None, one, iv1)
+        lk = o.decode_score(r.model, L, O, np.full(L.size, d, np.int32), r.dec, iv)
+        assert np.array_equal(col.best_cost, free.cost[:, d]) and np.array_equal(lk.best_cost, free.cost[:, d])
+        assert np.array_equal(lk.best_d, np.where(np.isfinite(free.cost[:, d]), d, -1))
+    with pytest.raises(ValueError):
+        o.decode_score(r.model, L, O, np.full(L.size, 99, np.int32), r.dec, iv)
+
+
+def test_greedy_plan_is_valid_and_ordered():
+    r, lock, iv = _round(seed=3)
+    Q = 24
+    L, O = r.calls["L_in"][:Q], r.calls["L_out"][:Q]
+    lock = lock[:Q]
+    K0 = iv["stride"]
+    # room for the plan's own entries
+    K = K0 + Q
+    D = len(r.dec["flops"])
+    big = dict(stride=K, count=iv["count"].copy(), start=np.zeros((D, K), np.float32), end=np.zeros((D, K), np.float32),
+               tok=np.zeros((D, K), np.int32))
+    for key in ("start", "end", "tok"):
+        big[key][:, :K0] = iv[key].reshape(D, K0)
+        big[key] = big[key].reshape(-1)
+    # intervals given so that the snapshot alone never exceeds capacity
+    cap = np.asarray(r.dec["cap_tok"])
+    rng = np.random.default_rng(3)
+    elapsed = rng.uniform(0, 20, Q); node = np.arange(Q, dtype=np.int32); wf = rng.integers(0, 3, Q).astype(np.int32)
+    tail = rng.uniform(0, 5, Q); hor = rng.uniform(5, 50, 3)
+    plan = o.decode_plan_greedy(r.model, L, O, lock, elapsed, node, wf, tail, hor, r.dec, big)
+    assert sorted(plan.rank) == list(range(Q))
+    placed = plan.best_d >= 0
+    assert placed.sum() >= Q // 2
+    # every placed call became exactly one appended interval (start, finish, demand) on its instance
+    assert np.array_equal(plan.count - iv["count"], np.bincount(plan.best_d[placed], minlength=D))
+    for c in np.nonzero(placed)[0]:
+        d = plan.best_d[c]
+        j = np.nonzero((plan.start[d] == plan.best_start[c]) & (plan.end[d] == plan.best_cost[c]) & (plan.tok[d] == L[c] + O[c]))[0]
+        assert j.size >= 1 and j.max() >= iv["count"][d]
+        assert lock[c] < 0 or lock[c] == d
+        assert plan.ratio[c] == pytest.approx((elapsed[c] + plan.best_cost[c] + tail[c]) / hor[wf[c]], rel=1e-14)
+    # capacity holds at every instant an appended interval is active
+    for d in range(D):
+        n0, n = iv["count"][d], plan.count[d]
+        s, e, k = plan.start[d, :n], plan.end[d, :n], plan.tok[d, :n]
+        for j in range(n0, n):
+            for tau in np.concatenate([[s[j]], s[(s > s[j]) & (s < e[j])]]):
+                assert k[(s <= tau) & (tau < e)].sum() <= cap[d], (d, j, tau)
+    # the first pick is the most urgent call of the one-pass scores on the untouched snapshot
+    s0 = o.decode_score(r.model, L, O, lock, r.dec, iv)
+    with np.errstate(all="ignore"):
+        R0 = (elapsed + s0.best_cost + tail[node]) / hor[wf]
+    first = int(np.nonzero(plan.rank == 0)[0][0])
+    assert first == int(np.argmax(R0)) and plan.best_d[first] == s0.best_d[first] and plan.best_cost[first] == s0.best_cost[first]
+
+
+def test_greedy_two_calls_one_slot_by_hand():
+    """Two equal calls, one instance with room for one at a time, nothing resident.  Per-token time
+    with the round-number model: compute 1e10*(0+1)/1e13 = 1e-3 s, memory (1e10 + 1e5*(0+1000+50))/1e12
+    = 0.010105 s -> 100 tokens take 1.0105 s.  The more urgent call (larger elapsed) starts now, the
+    other one when the first finishes; one scoring pass would have started both now.
+    (Rates pass through fp32 tables: 1e-6.)"""
+    dec = dict(flops=[1e13], hbm_bw=[1e12], used_tok=[0], cap_tok=[1500], batch=[0], qd_tok=[0], type=[0])
+    iv = dict(stride=4, count=[0], start=np.zeros(4), end=np.zeros(4), tok=np.zeros(4, np.int32))
+    plan = o.decode_plan_greedy(ROUND_MODEL, [1000, 1000], [100, 100], [-1, 0], [1.0, 5.0], [0, 1], [0, 0], [0.0, 0.0], [10.0],
+                                dec, iv)
+    assert list(plan.rank) == [1, 0] and list(plan.best_d) == [0, 0]
+    assert plan.best_start[1] == 0.0 and plan.best_cost[1] == pytest.approx(1.0105, rel=1e-6)
+    assert plan.best_start[0] == pytest.approx(1.0105, rel=1e-6) and plan.best_cost[0] == pytest.approx(2.021, rel=1e-6)
+    assert plan.ratio[1] == pytest.approx((5.0 + 1.0105) / 10, rel=1e-6)
+    assert plan.ratio[0] == pytest.approx((1.0 + 2.021) / 10, rel=1e-6)
+    one = o.decode_score(ROUND_MODEL, [1000, 1000], [100, 100], None, dec, iv)
+    assert list(one.best_start) == [0.0, 0.0]
+
+
+def test_greedy_infeasible_and_full_list():
+    dec = dict(flops=[1e13], hbm_bw=[1e12], used_tok=[0], cap_tok=[1500], batch=[0], qd_tok=[0], type=[0])
+    iv = dict(stride=4, count=[0], start=np.zeros(4), end=np.zeros(4), tok=np.zeros(4, np.int32))
+    plan = o.decode_plan_greedy(ROUND_MODEL, [1000, 2000], [100, 100], None, [1.0, 1.0], [0, 1], [0, 0], [0.0, 0.0], [10.0], dec, iv)
+    # the call that can never fit (Eq. 4) is ranked first with no instance, the other one is unaffected
+    assert list(plan.rank) == [1, 0] and list(plan.best_d) == [0, -1] and np.isinf(plan.best_cost[1]) and plan.best_start[0] == 0.0
+    assert list(plan.count) == [1]
+    iv1 = dict(stride=1, count=[0], start=np.zeros(1), end=np.zeros(1), tok=np.zeros(1, np.int32))
+    with pytest.raises(ValueError):
+        o.decode_plan_greedy(ROUND_MODEL, [100, 100], [10, 10], None, [1.0, 1.0], [0, 1], [0, 0], [0.0, 0.0], [10.0], dec, iv1)
