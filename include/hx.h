@@ -54,6 +54,8 @@ extern "C" {
 #define HX_MAX_INSTANCES  1024   /* prefill instances, and decode instances    */
 #define HX_GREEDY_MAX_CALLS      1024   /* queue length hx_plan_greedy takes            */
 #define HX_GREEDY_MAX_INSTANCES  256    /* instances per side hx_plan_greedy takes      */
+#define HX_MAX_INTERVALS         511    /* entries per decode instance in hx_intervals  */
+#define HX_DECODE_GREEDY_MAX_CALLS 1024 /* queue length hx_decode_plan_greedy takes     */
 
 typedef struct hx_ctx hx_ctx;
 
@@ -308,6 +310,75 @@ int hx_plan_greedy(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
                    int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio, int32_t *rank,
                    int32_t *backlog_tok_out, int32_t *used_tok_out, int32_t *batch_out, int32_t *qd_tok_out,
                    void *stream);
+
+/* ---- (6) the decode stage (Sec. 5.4) ---------------------------------------- */
+
+/*
+ * Decode token-capacity intervals (Sec. 5.4 "simulated decode intervals"; Sec. 6:
+ * the estimator keeps decode token-capacity intervals per instance).  Instance d
+ * owns entries d*stride .. d*stride + count[d] - 1; entry j says that tok[j] KV
+ * tokens are held on start[j] <= t < end[j], seconds from now (resident
+ * sequences have start <= 0, planned ones start later).  An entry with
+ * start >= end or tok <= 0 holds nothing.  All arrays are device memory owned by
+ * the caller; hx_decode_score only reads them, hx_decode_plan_greedy appends.
+ */
+typedef struct {
+    int32_t  stride;   /* entries reserved per instance, 0..HX_MAX_INTERVALS     */
+    int32_t *count;    /* device [D] entries in use, 0..stride                   */
+    float   *start;    /* device [D*stride]                                      */
+    float   *end;      /* device [D*stride]                                      */
+    int32_t *tok;      /* device [D*stride]                                      */
+} hx_intervals;
+
+/*
+ * Decode-stage scoring of a queue of calls whose KV has arrived (Sec. 5.4;
+ * Sec. 5.1: for decode scheduling the projection is waiting for decode capacity
+ * plus decode execution on the candidate instance).  For call c and instance d
+ *   T(c,d)  = L_out * per-token decode time on d's snapshot (batch, used_tok),
+ *   S(c,d)  = the earliest t >= 0 such that the intervals of d leave room for
+ *             L_in + L_out more tokens (Eq. 3) under cap_tok[d] (Eq. 4) at every
+ *             instant of [t, t + T); it is 0 or the end of one of d's entries;
+ *             +inf when L_in + L_out > cap_tok[d],
+ *   cost    = S + T.
+ * lock [Q] device or NULL: lock[c] = d restricts call c to instance d (a call
+ * locked during prefill planning cannot migrate), -1 leaves it free; any other
+ * value raises HX_ERR_INDEX in the status word and the call gets no instance.
+ * Per call the result is the lexicographic minimum of (cost, d) over its legal
+ * instances: best_d (-1 if none), best_start, best_cost (+inf if none) and,
+ * when ratio != NULL, ratio = (elapsed + best_cost + tail[node]) / horizon[wf]
+ * (Eq. 2 at the decode stage; needs the node/wf/elapsed members of `queue`,
+ * tail and horizon).  start, cost: device [Q*D] row-major or NULL, every pair
+ * (+inf for an instance the lock excludes).  decode->qd_tok and decode->type are
+ * not read.  The library keeps 8 bytes of scratch per call; the first call with
+ * a larger Q than any before allocates (and is then not capturable in a graph).
+ */
+int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_calls *queue, const int32_t *lock,
+                    const hx_decode_tab *decode, const hx_intervals *intervals,
+                    const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                    float *start, float *cost,
+                    int32_t *best_d, float *best_start, float *best_cost, float *ratio, void *stream);
+
+/*
+ * Recomputing greedy of the decode stage for small queues (Sec. 5.4 "Adaptive
+ * greedy decode assignment"): repeat Q times -- score every remaining call as
+ * hx_decode_score does, on the simulated intervals; take the call of largest
+ * ratio (equal ratios: lowest index); record its instance, start, finish
+ * (best_cost), ratio and rank (0 = first); append (start, finish, L_in + L_out)
+ * to that instance's entries and count[d] += 1.  A call with no feasible legal
+ * instance has ratio +inf: it is ranked at once with (-1, +inf) and changes
+ * nothing.  If an instance's list is full the status word gets HX_ERR_CAPACITY
+ * and that entry is not appended.  Only the intervals are simulated: the
+ * per-token time keeps the snapshot's batch and used_tok.  At most
+ * HX_DECODE_GREEDY_MAX_CALLS calls, and D * (2*stride + 1) must fit the
+ * workgroup's local memory (HX_ERR_SHAPE otherwise; e.g. 64 instances x 90
+ * entries, 16 x 370): the whole loop is one workgroup with no launch between
+ * iterations.  Larger queues: hx_decode_score once, then hx_rank.
+ */
+int hx_decode_plan_greedy(hx_ctx *ctx, const hx_model *model, const hx_calls *queue, const int32_t *lock,
+                          const hx_decode_tab *decode, const hx_intervals *intervals,
+                          const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                          int32_t *best_d, float *best_start, float *best_cost, float *ratio, int32_t *rank,
+                          void *stream);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,8 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
            "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_view",
-           "hx_score_placements", "hx_select", "hx_commit", "hx_rank", "hx_plan_greedy")
+           "hx_score_placements", "hx_select", "hx_commit", "hx_rank", "hx_plan_greedy",
+           "hx_decode_score", "hx_decode_plan_greedy")
 
 
 class HxError(RuntimeError):
@@ -50,6 +51,11 @@ class hx_decode_tab(C.Structure):
 
 class hx_links(C.Structure):
     _fields_ = [("n_types", C.c_int32), ("bw", C.c_void_p), ("latency", C.c_void_p)]
+
+
+class hx_intervals(C.Structure):
+    _fields_ = [("stride", C.c_int32), ("count", C.c_void_p), ("start", C.c_void_p), ("end", C.c_void_p),
+                ("tok", C.c_void_p)]
 
 
 _lib = None
@@ -148,6 +154,13 @@ def make_links(l: dict) -> hx_links:
     torch = _torch()
     T = int(l["n_types"])
     return hx_links(T, _ptr(l["bw"], torch.float32, T * T), _ptr(l.get("latency"), torch.float32, T * T))
+
+
+def make_intervals(iv: dict, D: int) -> hx_intervals:
+    torch = _torch()
+    k = int(iv["stride"])
+    return hx_intervals(k, _ptr(iv["count"], torch.int32, D), _ptr(iv["start"], torch.float32, D * k),
+                        _ptr(iv["end"], torch.float32, D * k), _ptr(iv["tok"], torch.int32, D * k))
 
 
 class Context:
@@ -286,6 +299,34 @@ class Context:
             _ptr(ratio, torch.float32, cs.n), _ptr(rank, i32, cs.n),
             _ptr(backlog_tok_out, i32, pt.n), _ptr(used_tok_out, i32, dt.n), _ptr(batch_out, i32, dt.n),
             _ptr(qd_tok_out, i32, dt.n), _stream(stream)))
+
+
+    def hx_decode_score(self, model, queue, lock, decode, intervals, best_d, best_start, best_cost,
+                        tail=None, horizon=None, ratio=None, start=None, cost=None, stream=None):
+        torch = _torch()
+        m, cs, dt = make_model(model), make_calls(queue), make_decode(decode)
+        iv = make_intervals(intervals, dt.n)
+        n_nodes = 0 if tail is None else int(tail.numel())
+        n_wf = 0 if horizon is None else int(horizon.numel())
+        f32, i32 = torch.float32, torch.int32
+        self._check(self.lib.hx_decode_score(
+            self._ctx, C.byref(m), C.byref(cs), _ptr(lock, i32, cs.n), C.byref(dt), C.byref(iv),
+            _ptr(tail, f32), _ptr(horizon, f32), n_nodes, n_wf,
+            _ptr(start, f32, cs.n * dt.n), _ptr(cost, f32, cs.n * dt.n),
+            _ptr(best_d, i32, cs.n), _ptr(best_start, f32, cs.n), _ptr(best_cost, f32, cs.n), _ptr(ratio, f32, cs.n),
+            _stream(stream)))
+
+    def hx_decode_plan_greedy(self, model, queue, lock, decode, intervals, tail, horizon,
+                              best_d, best_start, best_cost, ratio, rank, stream=None):
+        torch = _torch()
+        m, cs, dt = make_model(model), make_calls(queue), make_decode(decode)
+        iv = make_intervals(intervals, dt.n)
+        f32, i32 = torch.float32, torch.int32
+        self._check(self.lib.hx_decode_plan_greedy(
+            self._ctx, C.byref(m), C.byref(cs), _ptr(lock, i32, cs.n), C.byref(dt), C.byref(iv),
+            _ptr(tail, f32), _ptr(horizon, f32), int(tail.numel()), int(horizon.numel()),
+            _ptr(best_d, i32, cs.n), _ptr(best_start, f32, cs.n), _ptr(best_cost, f32, cs.n), _ptr(ratio, f32, cs.n),
+            _ptr(rank, i32, cs.n), _stream(stream)))
 
 
 def to_device(d: dict, device="cuda:0") -> dict:

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhx.so")
-SOURCES = ["hx_ctx.hip", "hx_score.hip", "hx_dag.hip", "hx_plan.hip"]
+SOURCES = ["hx_ctx.hip", "hx_score.hip", "hx_dag.hip", "hx_plan.hip", "hx_decode.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                       # every fused multiply-add is an explicit fmaf

@@ -58,6 +58,8 @@ struct hx_ctx {
     HxPrepTables *d_prep = nullptr;
     int32_t *d_flags = nullptr;        // sweep "changed" flags, [HX_MAX_SWEEP_FLAGS]
     unsigned long long *d_acc = nullptr;   // commit accumulators, [3 * HX_MAX_INSTANCES]
+    unsigned long long *d_dkey = nullptr;  // decode-stage selection keys, [dkey_cap]
+    int32_t dkey_cap = 0;
     int num_cu = 256;
     HxDagStore dag;
 };

@@ -4,6 +4,7 @@
 void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
 int hx_score_init();                // hx_score.hip
 int hx_plan_init();                 // hx_plan.hip
+int hx_decode_init();               // hx_decode.hip
 
 namespace {
 
@@ -143,7 +144,7 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (e == hipSuccess) { what = "hipMalloc(tables)"; e = hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)); }
     if (e == hipSuccess) { what = "hipMalloc(flags)"; e = hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)); }
     if (e == hipSuccess) { what = "hipMalloc(accumulators)"; e = hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)); }
-    if (e == hipSuccess && (hx_score_init() != HX_OK || hx_plan_init() != HX_OK)) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
+    if (e == hipSuccess && (hx_score_init() != HX_OK || hx_plan_init() != HX_OK || hx_decode_init() != HX_OK)) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
     if (e == hipSuccess) {
         what = "launch of hx_clear_status_kernel";
         CommitArgs z{};
@@ -171,6 +172,7 @@ extern "C" int hx_ctx_destroy(hx_ctx *ctx)
     if (ctx->d_prep) (void)hipFree(ctx->d_prep);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->d_acc) (void)hipFree(ctx->d_acc);
+    if (ctx->d_dkey) (void)hipFree(ctx->d_dkey);
     delete ctx;
     return HX_OK;
 }
@@ -194,7 +196,7 @@ extern "C" int hx_stream_status(hx_ctx *ctx, void *stream_)
         const char *what = code == HX_ERR_NOT_DAG ? "an edge breaks the DAG order, or no fixed point within the sweep limit"
                          : code == HX_ERR_INDEX ? "an index held in a device array is out of range"
                          : code == HX_ERR_OVERFLOW ? "an instance counter exceeded INT32_MAX"
-                         : code == HX_ERR_CAPACITY ? "propagation did not finish within max_depth sweeps"
+                         : code == HX_ERR_CAPACITY ? "a limit was hit on the device: propagation did not finish within max_depth sweeps, or an interval list is full"
                                                    : "device status";
         return hx_fail(ctx, code, "%s", what);
     }

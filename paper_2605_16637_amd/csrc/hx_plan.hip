@@ -13,12 +13,6 @@ namespace {
 
 constexpr int kT = HX_MAX_TYPES;
 
-// ordering key of a ratio: a NaN (raised elsewhere as a bad index) sorts with +inf
-__device__ __forceinline__ float hx_rank_key(float r)
-{
-    return (__float_as_uint(r) & 0x7fffffffu) > 0x7f800000u ? INFINITY : r;
-}
-
 // ---- one-pass ordering -----------------------------------------------------------
 
 constexpr int RANK_TILE = 2048;      // calls compared against per block

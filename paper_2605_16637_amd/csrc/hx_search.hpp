@@ -171,3 +171,9 @@ __device__ __forceinline__ float hx_projected_ratio(const int32_t *node, const i
     }
     return ((elapsed[c] + best) + tail[nd]) / horizon[w];
 }
+
+// ordering key of a ratio: a NaN (raised elsewhere as a bad index) sorts with +inf
+__device__ __forceinline__ float hx_rank_key(float r)
+{
+    return (__float_as_uint(r) & 0x7fffffffu) > 0x7f800000u ? INFINITY : r;
+}
