@@ -217,6 +217,67 @@ def planner_leg(torch, ctx, synth, binding, seed):
     return out
 
 
+def decode_leg(torch, ctx, synth, binding, seed):
+    """The decode stage: one scoring pass of a large queue (16384 calls x 256 instances, ~118 intervals
+    each, half the calls locked) followed by the one-pass ordering, and the recomputing greedy on pools
+    of the size the paper serves."""
+    from oracle import hx_oracle as o
+    out = {}
+    r, lock, iv = synth.make_decode_round("decode_large", seed)
+    Q, D = r.calls["n"], r.dec["n"]
+    q = binding.to_device(r.calls)
+    dd = binding.to_device(r.dec)
+    div = dict(stride=iv["stride"], count=dev(iv["count"]), start=dev(iv["start"]), end=dev(iv["end"]), tok=dev(iv["tok"]))
+    d_lock = dev(lock)
+    tail = torch.zeros(r.dag.n_nodes, device="cuda:0")
+    hor = torch.full((r.dag.n_wf,), 30.0, device="cuda:0")
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    bd, rk = torch.empty(Q, **i32), torch.empty(Q, **i32)
+    bs, bc, rt = (torch.empty(Q, device="cuda:0") for _ in range(3))
+
+    def one_pass():
+        ctx.hx_decode_score(synth.MODEL, q, d_lock, dd, div, bd, bs, bc, tail=tail, horizon=hor, ratio=rt)
+        ctx.hx_rank(rt, rk)
+
+    score_s = time_launches(torch, lambda: ctx.hx_decode_score(synth.MODEL, q, d_lock, dd, div, bd, bs, bc, tail=tail, horizon=hor, ratio=rt), 30)
+    both_s = time_launches(torch, one_pass, 30)
+    ctx.hx_stream_status()
+    legal = int((lock < 0).sum()) * D + int((lock >= 0).sum())
+    out["one pass"] = {"workload": "%d calls x %d instances, %d..%d intervals each, %d%% of the calls locked"
+                                   % (Q, D, int(iv["count"].min()), int(iv["count"].max()), round(100 * float((lock >= 0).mean()))),
+                       "score_us": score_s * 1e6, "score_and_rank_us": both_s * 1e6,
+                       "legal_pairs": legal, "legal_pairs_per_s": legal / score_s,
+                       "waiting_fraction_of_placed": float(((bs > 0) & (bd >= 0)).float().sum().item() / max(1, int((bd >= 0).sum().item())))}
+    rng = np.random.default_rng(seed)
+    for name, Qg, Dg, T, res, plan in (("queue 64 x 8 instances, 3 classes", 64, 8, 4, 24, 4), ("queue 256 x 32 instances, 4 classes", 256, 32, 4, 24, 4)):
+        r, lock, iv = synth.make_decode_round("decode_tiny", seed + 1, n_wf=64, Q=Qg, D=Dg, T=T, stride=res + plan, n_resident=res, n_planned=plan)
+        K0, K = iv["stride"], min(iv["stride"] + Qg, 140)
+        big = dict(stride=K, count=iv["count"].copy())
+        for key, dt in (("start", np.float32), ("end", np.float32), ("tok", np.int32)):
+            a = np.zeros((Dg, K), dt); a[:, :K0] = iv[key].reshape(Dg, K0); big[key] = a.reshape(-1)
+        node = np.arange(Qg, dtype=np.int32); wf = (np.arange(Qg) % 8).astype(np.int32)
+        tl = rng.uniform(0, 5, Qg).astype(np.float32); hz = rng.uniform(10, 60, 8).astype(np.float32)
+        el = rng.uniform(0, 30, Qg).astype(np.float32)
+        qg = binding.to_device(dict(n=Qg, L_in=r.calls["L_in"], L_out=r.calls["L_out"], node=node, wf=wf, elapsed=el))
+        ddg, d_lk, d_tl, d_hz = binding.to_device(r.dec), dev(lock), dev(tl), dev(hz)
+        cnt0 = dev(big["count"])
+        dbig = dict(stride=K, count=cnt0.clone(), start=dev(big["start"]), end=dev(big["end"]), tok=dev(big["tok"]))
+        outs = [torch.empty(Qg, **i32), torch.empty(Qg, device="cuda:0"), torch.empty(Qg, device="cuda:0"), torch.empty(Qg, device="cuda:0"),
+                torch.empty(Qg, **i32)]
+
+        def plan_once():
+            dbig["count"].copy_(cnt0)         # every plan starts from the same snapshot
+            ctx.hx_decode_plan_greedy(synth.MODEL, qg, d_lk, ddg, dbig, d_tl, d_hz, *outs)
+
+        gpu_s = time_launches(torch, plan_once, 20)
+        ctx.hx_stream_status()
+        t0 = time.perf_counter()
+        o.decode_plan_greedy(synth.MODEL, r.calls["L_in"], r.calls["L_out"], lock, el, node, wf, tl, hz, r.dec, big)
+        cpu_s = time.perf_counter() - t0
+        out[name] = {"gpu_us": gpu_s * 1e6, "oracle_1_thread_us": cpu_s * 1e6, "entries_per_instance": K}
+    return out
+
+
 def cpu_baseline(rnd, target_s=12.0):
     """The oracle, as it stands, on a bounded sample of the same round."""
     from oracle import hx_oracle as o
@@ -362,6 +423,7 @@ def main():
     if not args.no_extras:
         out["streaming"] = streaming_leg(torch, ctx, synth, binding, args.seed, rounds=30)
         out["planner"] = planner_leg(torch, ctx, synth, binding, args.seed)
+        out["decode_stage"] = decode_leg(torch, ctx, synth, binding, args.seed)
     if args.calibration_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").fill_(1.0)
         dst = torch.empty_like(src)

@@ -42,6 +42,10 @@ struct Tl {
 
 __host__ __device__ inline size_t hx_align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
+// The scans read whole groups of entries, one group ahead: a timeline of up to ne entries is
+// stored in ne rounded up to a multiple of eight, plus sixteen, the rest filled with (never, empty).
+__host__ __device__ inline int hx_tl_len(int ne) { return ((ne + 7) & ~7) + 16; }
+
 __device__ inline TlScratch hx_carve_scratch(unsigned char *p, int ne)
 {
     TlScratch w;
@@ -99,7 +103,15 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
     for (int i = tid; i < n_ev; i += nthreads) {
         const u64 ki = w.key[i];
         int r = 0;
-        for (int j = 0; j < n_ev; ++j) r += w.key[j] < ki;
+        int j = 0;
+        for (; j + 8 <= n_ev; j += 8) {                   // eight independent reads in flight
+            u64 kk[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) kk[u] = w.key[j + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r += kk[u] < ki;
+        }
+        for (; j < n_ev; ++j) r += w.key[j] < ki;
         w.ts[r] = __uint_as_float((unsigned)(ki >> 32));
         w.ds[r] = w.delta[i];
         w.ss[r] = w.su[i];
@@ -138,6 +150,8 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
         if (tid == HX_WAVE - 1) *n_out = pos;
     }
     __syncthreads();
+    for (int i = *n_out + tid; i < hx_tl_len(n_ev); i += nthreads) out.e[i] = make_int2(0x7f800000, 0);
+    __syncthreads();
 }
 
 // ---- earliest capacity-feasible start, one lane per (call, instance) ------------------
@@ -148,29 +162,50 @@ struct HxSlot {
 };
 
 // thr = tokens the call may find occupied (capacity - demand), < 0: never fits.  T = decode time.
-// Lanes of a wavefront may scan different timelines; every lane leaves the loop after at most
-// n steps, the loop ends when all lanes have.
+// Lanes of a wavefront may scan different timelines (e 16-byte aligned, padded as hx_tl_len says).
+//
+// Straight-line arithmetic per entry, no flags: rs is the start of the run of entries with room
+// that the scan is in, +inf while it is in none (a run begins at the first entry with room:
+// min(+inf, t_i) = t_i; inside a run t_i > rs leaves rs alone); the run is long enough once the next
+// entry's time reaches rs + T, which cannot happen outside a run (rs + T = +inf, and the entry
+// whose successor is "never" always has room: everything has ended by then).  Run starts only
+// grow along the timeline, so the earliest start is the minimum over all hits.  Four entries per
+// step; the loop ends when every lane has its answer or has passed the end of its timeline.
 __device__ __forceinline__ HxSlot hx_earliest_start(const int2 *e, const short *src, int n, int thr, float T, bool active)
 {
-    HxSlot r{INFINITY, -1};
-    bool open = active && thr >= 0 && n > 0;
-    bool in_run = false;
-    float rs = 0.0f;
-    int rsi = 0;
-    float nxt = open ? __int_as_float(e[0].x) : 0.0f;
-    for (int i = 0; __builtin_amdgcn_ballot_w64(open) != 0; ++i) {
-        if (open) {
-            const float cur = nxt;
-            const int occ = e[i].y;
-            nxt = (i + 1 < n) ? __int_as_float(e[i + 1].x) : INFINITY;
-            const bool room = occ <= thr;
-            if (room && !in_run) { rs = cur; rsi = i; }
-            in_run = room;
-            if (in_run && nxt >= rs + T) { r.S = rs; r.src = rsi; open = false; }
-            if (i + 1 >= n) open = false;
-        }
+    const bool open = active && thr >= 0;
+    float rs = INFINITY, ans = INFINITY;
+#define HX_TL_STEP(cur_, occ_, nxt_)                                              \
+    {                                                                             \
+        rs = (occ_) <= thr ? fminf(rs, __int_as_float(cur_)) : INFINITY;          \
+        ans = fminf(ans, __int_as_float(nxt_) >= rs + T ? rs : INFINITY);         \
     }
-    if (r.src >= 0) r.src = src[r.src];
+    for (int i0 = 0;; i0 += 4) {
+        const bool going = open && i0 < n && !(ans < INFINITY);
+        if (__builtin_amdgcn_ballot_w64(going) == 0) break;
+        const int at = going ? i0 : 0;                     // lanes that are through read a harmless place
+        const int4 a = *reinterpret_cast<const int4 *>(e + at);
+        const int4 b = *reinterpret_cast<const int4 *>(e + at + 2);
+        const int t4 = e[at + 4].x;
+        float keep = ans;
+        HX_TL_STEP(a.x, a.y, a.z)
+        HX_TL_STEP(a.z, a.w, b.x)
+        HX_TL_STEP(b.x, b.y, b.z)
+        HX_TL_STEP(b.z, b.w, t4)
+        ans = going ? ans : keep;
+    }
+#undef HX_TL_STEP
+    HxSlot r{INFINITY, -1};
+    if (open && ans < INFINITY) {
+        // which entry the start is: times are strictly increasing, so a bisection finds it
+        int lo = 0, hi = n - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (__int_as_float(e[mid].x) < ans) lo = mid + 1; else hi = mid;
+        }
+        r.S = ans;
+        r.src = src[lo];
+    }
     return r;
 }
 
@@ -223,18 +258,19 @@ __global__ __launch_bounds__(256) void hx_decode_key_init_kernel(u64 *key, int Q
     if (c < Q) key[c] = ~0ull;
 }
 
-// Workgroup (d, part): the timeline of instance d, then calls part*chunk .. of the queue, one per lane.
-__global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, int splits, int chunk)
+// Workgroup d: the timeline of instance d, built in LDS and written to the library's scratch
+// (nt entries per instance, padded); the workgroups also set the selection keys to "nothing yet".
+__global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, int2 *tl_e, short *tl_src, int *tl_n, int nt)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_n;
     const int tid = threadIdx.x;
-    const int d = blockIdx.x / splits, part = blockIdx.x - d * splits;
+    const int d = blockIdx.x;
     const int ne = 2 * a.stride + 1;
     TlScratch w = hx_carve_scratch(smem, ne);
     Tl tl;
     tl.e = (int2 *)(smem + hx_scratch_bytes(ne));
-    tl.src = (short *)(smem + hx_scratch_bytes(ne) + hx_align16((size_t)ne * 8));
+    tl.src = (short *)(smem + hx_scratch_bytes(ne) + hx_align16((size_t)hx_tl_len(ne) * 8));
     int cnt = a.iv_count[d];
     if (cnt < 0 || cnt > a.stride) {
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
@@ -243,17 +279,88 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, int 
     const size_t at = (size_t)d * a.stride;
     hx_build_timeline<false>(cnt, a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n, a.status);
     const int n = s_n;
+    for (int i = tid; i < hx_tl_len(2 * cnt + 1); i += blockDim.x) tl_e[(size_t)d * nt + i] = tl.e[i];
+    for (int i = tid; i < n; i += blockDim.x) tl_src[(size_t)d * ne + i] = tl.src[i];
+    if (tid == 0) tl_n[d] = n;
+    const int per = (a.Q + a.D - 1) / a.D;
+    for (int c = d * per + tid; c < min(a.Q, (d + 1) * per); c += blockDim.x) a.key[c] = ~0ull;
+}
+
+// The same scan as hx_earliest_start for a timeline every lane of the wavefront shares.  The
+// timeline was written by an earlier kernel and nothing writes it now, so it is read through the
+// constant address space: with wave-uniform addresses the entries arrive as scalars, cost no vector
+// memory or LDS traffic, and feed the vector arithmetic as scalar operands.  Eight entries per
+// step, the next eight already on their way.
+typedef int HxTlGroup __attribute__((ext_vector_type(16)));      // eight (time, occupancy) entries
+typedef __attribute__((address_space(4))) const HxTlGroup *hx_tl_group_cp;
+
+__device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restrict__ e, const short *__restrict__ src, int n,
+                                                           int thr, float T, bool active)
+{
+    const bool open = active && thr >= 0;
+    float rs = INFINITY, ans = INFINITY;
+#define HX_TL_STEP(cur_, occ_, nxt_)                                              \
+    {                                                                             \
+        rs = (occ_) <= thr ? fminf(rs, __int_as_float(cur_)) : INFINITY;          \
+        ans = fminf(ans, __int_as_float(nxt_) >= rs + T ? rs : INFINITY);         \
+    }
+    const hx_tl_group_cp g = (hx_tl_group_cp)(unsigned long long)e;
+    HxTlGroup cur = g[0];
+    for (int i0 = 0; i0 < n; i0 += 8) {
+        if (__builtin_amdgcn_ballot_w64(open && !(ans < INFINITY)) == 0) break;
+        const HxTlGroup nxt = g[(i0 >> 3) + 1];
+        // a lane that already has its answer keeps it: later hits have later starts
+        HX_TL_STEP(cur[0], cur[1], cur[2])
+        HX_TL_STEP(cur[2], cur[3], cur[4])
+        HX_TL_STEP(cur[4], cur[5], cur[6])
+        HX_TL_STEP(cur[6], cur[7], cur[8])
+        HX_TL_STEP(cur[8], cur[9], cur[10])
+        HX_TL_STEP(cur[10], cur[11], cur[12])
+        HX_TL_STEP(cur[12], cur[13], cur[14])
+        HX_TL_STEP(cur[14], cur[15], nxt[0])
+        cur = nxt;
+    }
+#undef HX_TL_STEP
+    HxSlot r{INFINITY, -1};
+    if (open && ans < INFINITY) {
+        int lo = 0, hi = n - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (__int_as_float(e[mid].x) < ans) lo = mid + 1; else hi = mid;
+        }
+        r.S = ans;
+        r.src = src[lo];
+    }
+    return r;
+}
+
+// Workgroup (d, part): calls part*chunk .. of the queue against instance d, one call per lane.
+__global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, const int2 *__restrict__ tl_e,
+                                                              const short *__restrict__ tl_src, const int *__restrict__ tl_n,
+                                                              int nt, int splits, int chunk)
+{
+    const int tid = threadIdx.x;
+    const int d = blockIdx.x / splits, part = blockIdx.x - d * splits;
+    const int ne = 2 * a.stride + 1;
+    const int2 *__restrict__ e = tl_e + (size_t)d * nt;
+    const short *__restrict__ src = tl_src + (size_t)d * ne;
+    const int n = tl_n[d];
     const float invF = 1.0f / a.d_flops[d], invB = 1.0f / a.d_hbm[d];
     const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, invF, invB);
     const int cap = a.d_cap[d];
     const int c_lo = part * chunk, c_hi = min(a.Q, c_lo + chunk);
+    // the lengths and lock of the next pass are fetched while this pass scans
+    int c = c_lo + tid;
+    bool in = c < c_hi;
+    int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
+    int lk = (in && a.lock) ? a.lock[c] : -1;
     for (int base = c_lo; base < c_hi; base += blockDim.x) {
-        const int c = base + tid;
-        const bool in = c < c_hi;
-        const int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
-        const int lk = (in && a.lock) ? a.lock[c] : -1;
+        const int cn = c + blockDim.x;
+        const bool inn = cn < c_hi;
+        const int Ln = inn ? a.L_in[cn] : 0, On = inn ? a.L_out[cn] : 0;
+        const int lkn = (inn && a.lock) ? a.lock[cn] : -1;
         const HxDecodeCand k = hx_decode_candidate(a.m, L, O, lk, d, a.D, x, cap, a.status);
-        const HxSlot s = hx_earliest_start(tl.e, tl.src, n, k.thr, k.T, in && k.legal);
+        const HxSlot s = hx_earliest_start_shared(e, src, n, k.thr, k.T, in && k.legal);
         const float v = s.S + k.T;                         // +inf when there is no start
         if (in) {
             if (a.start) a.start[(size_t)c * a.D + d] = s.S;
@@ -263,6 +370,7 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, int 
                 if (__hip_atomic_load(&a.key[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > mine) atomicMin(&a.key[c], mine);
             }
         }
+        c = cn; in = inn; L = Ln; O = On; lk = lkn;
     }
 }
 
@@ -319,10 +427,11 @@ struct DGreedyArgs {
 
 // LDS carve-up shared by host (size) and device (offsets)
 struct DGreedyLds {
-    int ne, D, Q;
-    __host__ __device__ DGreedyLds(int stride, int D_, int Q_) : ne(2 * stride + 1), D((D_ + 3) & ~3), Q((Q_ + 3) & ~3) {}
+    int ne, nt, D, Q;      // events per instance, stored timeline length, padded sizes
+    __host__ __device__ DGreedyLds(int stride, int D_, int Q_)
+        : ne(2 * stride + 1), nt(hx_tl_len(2 * stride + 1)), D((D_ + 3) & ~3), Q((Q_ + 3) & ~3) {}
     __host__ __device__ size_t off_tl() const { return hx_scratch_bytes(ne); }
-    __host__ __device__ size_t off_src() const { return off_tl() + hx_align16((size_t)D * ne * 8); }
+    __host__ __device__ size_t off_src() const { return off_tl() + hx_align16((size_t)D * nt * 8); }
     __host__ __device__ size_t off_inst() const { return off_src() + hx_align16((size_t)D * ne * 2); }
     __host__ __device__ size_t off_call() const { return off_inst() + (size_t)6 * D * 4; }
     __host__ __device__ size_t off_red() const { return off_call() + (size_t)5 * Q * 4; }
@@ -371,7 +480,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     __syncthreads();
     for (int d = 0; d < a.D; ++d) {
         const size_t at = (size_t)d * a.stride;
-        Tl tl{s_tl + (size_t)d * lay.ne, s_src + (size_t)d * lay.ne};
+        Tl tl{s_tl + (size_t)d * lay.nt, s_src + (size_t)d * lay.ne};
         hx_build_timeline<false>(s_cnt[d], a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n[d], a.status);
     }
 
@@ -390,7 +499,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 HxDecF x;
                 x.wait = 0.0f; x.c1 = s_c1[dd]; x.c2 = s_c2[dd]; x.kB = s_kB[dd];
                 const HxDecodeCand q = hx_decode_candidate(a.m, L, O, lk, dd, a.D, x, s_cap[dd], a.status);
-                const HxSlot s = hx_earliest_start(s_tl + (size_t)dd * lay.ne, s_src + (size_t)dd * lay.ne, s_n[dd],
+                const HxSlot s = hx_earliest_start(s_tl + (size_t)dd * lay.nt, s_src + (size_t)dd * lay.ne, s_n[dd],
                                                    q.thr, q.T, in && q.legal);
                 const float v = s.S + q.T;
                 if (in && s.src >= 0 && v < bv) { bv = v; bS = s.S; bd = d; }
@@ -460,7 +569,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         const int pd = s_pick[0];
         if (pd >= 0) {
             const size_t at = (size_t)pd * a.stride;
-            Tl tl{s_tl + (size_t)pd * lay.ne, s_src + (size_t)pd * lay.ne};
+            Tl tl{s_tl + (size_t)pd * lay.nt, s_src + (size_t)pd * lay.ne};
             hx_build_timeline<true>(s_cnt[pd], a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n[pd], a.status);
             for (int c = tid; c < a.Q; c += DG_THREADS)
                 if ((s_flags[c] & DG_ALIVE) && s_bd[c] == pd) s_flags[c] = DG_ALIVE | DG_DIRTY;
@@ -525,14 +634,27 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
     HxDeviceGuard guard(ctx->device);
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
     hipStream_t stream = (hipStream_t)stream_;
-    if (Q > ctx->dkey_cap) {
-        // grown, never shrunk; work queued on the old block has to finish before it goes
-        if (ctx->d_dkey) { HX_HIP(ctx, hipDeviceSynchronize()); HX_HIP(ctx, hipFree(ctx->d_dkey)); ctx->d_dkey = nullptr; ctx->dkey_cap = 0; }
-        const int want = Q < 4096 ? 4096 : Q;
-        HX_HIP(ctx, hipMalloc((void **)&ctx->d_dkey, (size_t)want * sizeof(u64)));
-        ctx->dkey_cap = want;
+    const int ne = 2 * iv->stride + 1, nt = hx_tl_len(ne);
+    const size_t tl_need = (size_t)(D > 0 ? D : 1) * nt;
+    if (Q > ctx->dkey_cap || tl_need > ctx->dtl_cap) {
+        // grown, never shrunk; work queued on the old blocks has to finish before they go
+        HX_HIP(ctx, hipDeviceSynchronize());
+        if (Q > ctx->dkey_cap) {
+            if (ctx->d_dkey) { HX_HIP(ctx, hipFree(ctx->d_dkey)); ctx->d_dkey = nullptr; ctx->dkey_cap = 0; }
+            const int want = Q < 4096 ? 4096 : Q;
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dkey, (size_t)want * sizeof(u64)));
+            ctx->dkey_cap = want;
+        }
+        if (tl_need > ctx->dtl_cap) {
+            if (ctx->d_dtl) { HX_HIP(ctx, hipFree(ctx->d_dtl)); ctx->d_dtl = nullptr; ctx->dtl_cap = 0; }
+            // per entry: (time, occupancy) 8 bytes + source 2 bytes; per instance one length
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 10 + (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
+            ctx->dtl_cap = tl_need;
+        }
     }
-    hx_decode_key_init_kernel<<<(Q + 255) / 256, 256, 0, stream>>>(ctx->d_dkey, Q);
+    int2 *tl_e = (int2 *)ctx->d_dtl;
+    int *tl_n = (int *)((unsigned char *)ctx->d_dtl + ctx->dtl_cap * 8);
+    short *tl_src = (short *)((unsigned char *)ctx->d_dtl + ctx->dtl_cap * 8 + (size_t)HX_MAX_INSTANCES * sizeof(int));
     if (D > 0) {
         DecodeArgs a{};
         a.m = to_model(model); a.Q = Q; a.D = D; a.stride = iv->stride;
@@ -540,19 +662,19 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         a.d_flops = dec->flops; a.d_hbm = dec->hbm_bw; a.d_used = dec->used_tok; a.d_cap = dec->cap_tok; a.d_batch = dec->batch;
         a.iv_count = iv->count; a.iv_start = iv->start; a.iv_end = iv->end; a.iv_tok = iv->tok;
         a.start = start; a.cost = cost; a.key = ctx->d_dkey; a.status = ctx->d_status;
+        const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)nt * 8) + hx_align16((size_t)ne * 2);
+        hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, tl_e, tl_src, tl_n, nt);
         // enough workgroups to fill the chip, each with at least one full pass of calls
-        int splits = (4 * ctx->num_cu + D - 1) / D;
+        int splits = (8 * ctx->num_cu + D - 1) / D;
         const int max_splits = (Q + 255) / 256;
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;
         int chunk = (Q + splits - 1) / splits;
         chunk = (chunk + 255) / 256 * 256;
         splits = (Q + chunk - 1) / chunk;
-        const int ne = 2 * iv->stride + 1;
-        const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)ne * 8) + hx_align16((size_t)ne * 2);
-        hx_decode_score_kernel<<<D * splits, 256, lds, stream>>>(a, splits, chunk);
-    } else if (start || cost) {
-        // nothing to write: the [Q*0] tensors are empty
+        hx_decode_score_kernel<<<D * splits, 256, 0, stream>>>(a, tl_e, tl_src, tl_n, nt, splits, chunk);
+    } else {
+        hx_decode_key_init_kernel<<<(Q + 255) / 256, 256, 0, stream>>>(ctx->d_dkey, Q);
     }
     DecodeFinishArgs f{};
     f.Q = Q; f.D = D; f.stride = iv->stride; f.key = ctx->d_dkey; f.iv_end = iv->end;
