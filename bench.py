@@ -23,6 +23,7 @@ import numpy as np
 ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # VALU issue slots the search needs per candidate: max, add, half a 3-input min
 OPS_PER_CANDIDATE = 2.5
+DECODE_OPS_PER_STEP = 7.0    # vector ops per (call, instance, timeline entry) of the decode-stage scan
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/
 # (counter x calibration factor of a plain copy); valid for the default workloads only, and to be
@@ -243,10 +244,21 @@ def decode_leg(torch, ctx, synth, binding, seed):
     both_s = time_launches(torch, one_pass, 30)
     ctx.hx_stream_status()
     legal = int((lock < 0).sum()) * D + int((lock >= 0).sum())
+    # timeline entries per instance = distinct event times from now on (the past folds onto now)
+    K = iv["stride"]
+    n_tl = np.array([np.unique(np.maximum(np.concatenate([[0.0], iv["start"][d * K:d * K + iv["count"][d]],
+                                                          iv["end"][d * K:d * K + iv["count"][d]]]), 0.0)).size for d in range(D)])
+    per_inst = np.bincount(lock[lock >= 0], minlength=D) + int((lock < 0).sum())
+    steps = float((per_inst * n_tl).sum())                  # (legal pair, timeline entry) steps
+    ops = DECODE_OPS_PER_STEP * steps
     out["one pass"] = {"workload": "%d calls x %d instances, %d..%d intervals each, %d%% of the calls locked"
                                    % (Q, D, int(iv["count"].min()), int(iv["count"].max()), round(100 * float((lock >= 0).mean()))),
                        "score_us": score_s * 1e6, "score_and_rank_us": both_s * 1e6,
                        "legal_pairs": legal, "legal_pairs_per_s": legal / score_s,
+                       "timeline_entries_mean": float(n_tl.mean()),
+                       "roofline": {"kernel": "hx_decode_score_kernel (+ timeline and finish launches)", "bound": "alu",
+                                    "ops_per_pair_and_entry": DECODE_OPS_PER_STEP, "achieved": ops / score_s / 1e12,
+                                    "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s", "frac": ops / score_s / 1e12 / ALU_PEAK_TOPS},
                        "waiting_fraction_of_placed": float(((bs > 0) & (bd >= 0)).float().sum().item() / max(1, int((bd >= 0).sum().item())))}
     rng = np.random.default_rng(seed)
     for name, Qg, Dg, T, res, plan in (("queue 64 x 8 instances, 3 classes", 64, 8, 4, 24, 4), ("queue 256 x 32 instances, 4 classes", 256, 32, 4, 24, 4)):

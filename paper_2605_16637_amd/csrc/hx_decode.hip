@@ -334,12 +334,19 @@ __device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restric
     return r;
 }
 
-// Workgroup (d, part): calls part*chunk .. of the queue against instance d, one call per lane.
+// Workgroup (d, part): calls part*chunk .. of the queue against instance d.  The calls that may
+// go to d (free ones and those locked to d) are first gathered in LDS, so that the scan runs with
+// full wavefronts however many calls are locked elsewhere; then one call per lane.
+constexpr int DS_CHUNK = 2048;        // calls per workgroup at most
+
 __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, const int2 *__restrict__ tl_e,
                                                               const short *__restrict__ tl_src, const int *__restrict__ tl_n,
                                                               int nt, int splits, int chunk)
 {
+    __shared__ int s_c[DS_CHUNK], s_L[DS_CHUNK], s_O[DS_CHUNK];
+    __shared__ int s_count;
     const int tid = threadIdx.x;
+    const int lane = tid & (HX_WAVE - 1);
     const int d = blockIdx.x / splits, part = blockIdx.x - d * splits;
     const int ne = 2 * a.stride + 1;
     const int2 *__restrict__ e = tl_e + (size_t)d * nt;
@@ -349,18 +356,34 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, cons
     const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, invF, invB);
     const int cap = a.d_cap[d];
     const int c_lo = part * chunk, c_hi = min(a.Q, c_lo + chunk);
-    // the lengths and lock of the next pass are fetched while this pass scans
-    int c = c_lo + tid;
-    bool in = c < c_hi;
-    int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
-    int lk = (in && a.lock) ? a.lock[c] : -1;
+    if (tid == 0) s_count = 0;
+    __syncthreads();
     for (int base = c_lo; base < c_hi; base += blockDim.x) {
-        const int cn = c + blockDim.x;
-        const bool inn = cn < c_hi;
-        const int Ln = inn ? a.L_in[cn] : 0, On = inn ? a.L_out[cn] : 0;
-        const int lkn = (inn && a.lock) ? a.lock[cn] : -1;
-        const HxDecodeCand k = hx_decode_candidate(a.m, L, O, lk, d, a.D, x, cap, a.status);
-        const HxSlot s = hx_earliest_start_shared(e, src, n, k.thr, k.T, in && k.legal);
+        const int c = base + tid;
+        const bool in = c < c_hi;
+        const int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
+        const int lk = (in && a.lock) ? a.lock[c] : -1;
+        const bool ok = L >= 0 && O >= 0 && lk >= -1 && lk < a.D;
+        if (!ok) hx_raise(a.status, HX_ERR_INDEX);
+        const bool legal = in && ok && (lk < 0 || lk == d);
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(legal);
+        int at = 0;
+        if (lane == 0 && m) at = atomicAdd(&s_count, __popcll(m));
+        at = __builtin_amdgcn_readfirstlane(at) + __popcll(m & ((1ull << lane) - 1ull));
+        if (legal) { s_c[at] = c; s_L[at] = L; s_O[at] = O; }
+        if (in && !legal) {
+            if (a.start) a.start[(size_t)c * a.D + d] = INFINITY;
+            if (a.cost) a.cost[(size_t)c * a.D + d] = INFINITY;
+        }
+    }
+    __syncthreads();
+    const int n_legal = s_count;
+    for (int base = 0; base < n_legal; base += blockDim.x) {
+        const int i = base + tid;
+        const bool in = i < n_legal;
+        const int c = in ? s_c[i] : 0, L = in ? s_L[i] : 0, O = in ? s_O[i] : 0;
+        const HxDecodeCand k = hx_decode_candidate(a.m, L, O, -1, d, a.D, x, cap, a.status);
+        const HxSlot s = hx_earliest_start_shared(e, src, n, k.thr, k.T, in);
         const float v = s.S + k.T;                         // +inf when there is no start
         if (in) {
             if (a.start) a.start[(size_t)c * a.D + d] = s.S;
@@ -370,7 +393,6 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, cons
                 if (__hip_atomic_load(&a.key[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > mine) atomicMin(&a.key[c], mine);
             }
         }
-        c = cn; in = inn; L = Ln; O = On; lk = lkn;
     }
 }
 
@@ -666,11 +688,11 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, tl_e, tl_src, tl_n, nt);
         // enough workgroups to fill the chip, each with at least one full pass of calls
         int splits = (8 * ctx->num_cu + D - 1) / D;
-        const int max_splits = (Q + 255) / 256;
+        const int max_splits = (Q + 255) / 256, min_splits = (Q + DS_CHUNK - 1) / DS_CHUNK;
         if (splits > max_splits) splits = max_splits;
-        if (splits < 1) splits = 1;
+        if (splits < min_splits) splits = min_splits;
         int chunk = (Q + splits - 1) / splits;
-        chunk = (chunk + 255) / 256 * 256;
+        chunk = (chunk + 255) / 256 * 256;                // <= DS_CHUNK, a multiple of 256 itself
         splits = (Q + chunk - 1) / chunk;
         hx_decode_score_kernel<<<D * splits, 256, 0, stream>>>(a, tl_e, tl_src, tl_n, nt, splits, chunk);
     } else {
