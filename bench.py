@@ -290,6 +290,41 @@ def decode_leg(torch, ctx, synth, binding, seed):
     return out
 
 
+def robustness_leg(torch, ctx, synth, binding, seed):
+    """Sensitivity of the chosen pairs to estimate error (Sec. 7.6 injects deterministic multiplicative
+    error into the scheduler-visible prefill and decode estimates): every instance's estimates are scaled by
+    1 + e or 1 - e, alternating by instance index (its rates divided by that factor); reported are the
+    fraction of calls whose pair changes and the true cost of the changed choice relative to the true best."""
+    rnd = synth.make_round("mid", seed)
+    C, P, D = rnd.calls["n"], rnd.pre["n"], rnd.dec["n"]
+    calls, links = binding.to_device(rnd.calls), binding.to_device(rnd.links)
+    pre, dec = binding.to_device(rnd.pre), binding.to_device(rnd.dec)
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    cost = torch.empty(C * P * D, device="cuda:0")
+    bp, bd, bc = torch.empty(C, **i32), torch.empty(C, **i32), torch.empty(C, device="cuda:0")
+    ctx.hx_score_placements(synth.MODEL, calls, pre, dec, links, cost=cost, best_p=bp, best_d=bd, best_cost=bc)
+    cost = cost.view(C, P * D)
+    ok = bp >= 0
+    out = {"workload": "mid round: %d calls x %d x %d" % (C, P, D)}
+    for err in (0.1, 0.2, 0.3):
+        fp = torch.where(torch.arange(P, device="cuda:0") % 2 == 0, 1.0 + err, 1.0 - err)
+        fd = torch.where(torch.arange(D, device="cuda:0") % 2 == 0, 1.0 + err, 1.0 - err)
+        npre = dict(pre, flops=pre["flops"] / fp, hbm_bw=pre["hbm_bw"] / fp)
+        ndec = dict(dec, flops=dec["flops"] / fd, hbm_bw=dec["hbm_bw"] / fd)
+        np_, nd_, nc_ = torch.empty(C, **i32), torch.empty(C, **i32), torch.empty(C, device="cuda:0")
+        ctx.hx_score_placements(synth.MODEL, calls, npre, ndec, links, best_p=np_, best_d=nd_, best_cost=nc_)
+        changed = ok & ((np_ != bp) | (nd_ != bd))
+        flat = (np_.long() * D + nd_.long()).clamp(min=0)
+        true_of_choice = cost.gather(1, flat.view(-1, 1)).view(-1)
+        regret = (true_of_choice[ok] / bc[ok] - 1.0)
+        out["%d%%" % round(err * 100)] = {"pairs_changed": float(changed.float().sum().item() / max(1, int(ok.sum().item()))),
+                                         "decode_instance_changed": float((ok & (nd_ != bd)).float().sum().item() / max(1, int(ok.sum().item()))),
+                                         "mean_cost_increase": float(regret.mean().item()),
+                                         "p99_cost_increase": float(regret.quantile(0.99).item())}
+    ctx.hx_stream_status()
+    return out
+
+
 def cpu_baseline(rnd, target_s=12.0):
     """The oracle, as it stands, on a bounded sample of the same round."""
     from oracle import hx_oracle as o
@@ -436,6 +471,7 @@ def main():
         out["streaming"] = streaming_leg(torch, ctx, synth, binding, args.seed, rounds=30)
         out["planner"] = planner_leg(torch, ctx, synth, binding, args.seed)
         out["decode_stage"] = decode_leg(torch, ctx, synth, binding, args.seed)
+        out["estimate_error"] = robustness_leg(torch, ctx, synth, binding, args.seed)
     if args.calibration_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").fill_(1.0)
         dst = torch.empty_like(src)

@@ -157,6 +157,35 @@ def test_large_sweep_sampled(ctx):
     assert ((gp[ok] >= 0) & (gp[ok] < rnd.pre["n"])).all()
 
 
+@pytest.mark.parametrize("name", ["large", "stream"])
+def test_full_size_against_the_class_collapsed_search(ctx, name):
+    """Every call of the full-size rounds, not a sample.  Transfer time depends on the classes only and
+    instances of one class share their rates, so for a fixed decode instance the best prefill instance of a
+    class is the one with the shortest queue: the minimum over P x D pairs equals the minimum over
+    (classes) x D pairs of a pool that keeps one prefill instance per class.  The oracle enumerates that
+    32-times smaller pool for all calls; the GPU enumerates the whole pool."""
+    rnd = synth.make_round(name, 1)
+    calls, pre, dec, links = dev_tables(rnd)
+    gp, gd, gc = fused(ctx, rnd.model, calls, pre, dec, links)
+    T = rnd.links["n_types"]
+    pt, bl = rnd.pre["type"], rnd.pre["backlog_tok"]
+    for t in range(T):      # what the shortcut rests on
+        assert np.unique(rnd.pre["flops"][pt == t]).size == 1 and np.unique(rnd.pre["hbm_bw"][pt == t]).size == 1
+    keep = np.array([np.nonzero(pt == t)[0][np.argmin(bl[pt == t])] for t in range(T)])      # lowest index among equal queues
+    small = {k: (np.asarray(v)[keep] if k != "n" else T) for k, v in rnd.pre.items()}
+    L, O = rnd.calls["L_in"], rnd.calls["L_out"]
+    ores = o.score(rnd.model, L, O, small, rnd.dec, rnd.links)
+    assert_costs_close(gc, ores.best_cost, "best cost, all calls")
+    none = ores.best_p < 0
+    assert np.array_equal(gp < 0, none) and np.array_equal(gd < 0, none)
+    # the pair itself: many pairs share the minimum when the decode instance's availability dominates, and the
+    # lowest flat index among them need not be the shortest queue of its class -- so every call's GPU pair is
+    # priced by the oracle on the full pool and must reach the collapsed search's minimum
+    for c in np.nonzero(~none)[0]:
+        alt = o.score_one(rnd.model, L[c], O[c], gp[c], gd[c], rnd.pre, rnd.dec, rnd.links)
+        assert alt <= ores.best_cost[c] * (1 + REL), c
+
+
 def test_empty_inputs(ctx):
     import torch
     from paper_2605_16637_amd import binding
