@@ -341,28 +341,41 @@ __device__ __forceinline__ bool hx_raise_max_f32(float *addr, float v)
     return __float_as_uint(v) > old;
 }
 
-// push the (new) rem and level of node v to its parent u; enqueue u if it grew
-__device__ __forceinline__ void hx_push_parent(const AppendArgs &a, int u, float rem_v, int level_v)
+// push the (new) rem and level of node v to its parent u; enqueue u if it grew.  The lanes of a
+// wavefront that enqueue at the same moment take their list slots with one atomic between them
+// (the list counter is a single address: one atomic per lane would serialise the whole sweep).
+// SCOPED: the list entry is written with a device-scope store (for the single-workgroup loop,
+// whose later steps read the list back).
+template <bool SCOPED>
+__device__ __forceinline__ void hx_push_parent_t(const AppendArgs &a, int u, float rem_v, int level_v)
 {
     bool grew = hx_raise_max_f32(&a.tail[u], rem_v);
     int old = atomicMax(&a.level[u], level_v + 1);
     grew = grew || (level_v + 1 > old);
-    if (grew && (uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch) {
-        int slot = atomicAdd(&a.counters[a.cout], 1);
-        a.list_out[slot] = u;        // at most one entry per node and sweep: never beyond cap_nodes
+    const bool want = grew && (uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(want);      // of the lanes active here
+    if (m) {
+        const int lane = (int)(threadIdx.x & (HX_WAVE - 1));
+        const int leader = __ffsll((long long)m) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&a.counters[a.cout], __popcll(m));
+        base = __shfl(base, leader);
+        if (want) {
+            const int slot = base + __popcll(m & ((1ull << lane) - 1ull));   // at most one entry per node and sweep:
+            if (SCOPED) __hip_atomic_store(&a.list_out[slot], u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else a.list_out[slot] = u;                                        // never beyond cap_nodes
+        }
     }
 }
 
-// same, for the single-workgroup loop: the list entry is written with a device-scope store
+__device__ __forceinline__ void hx_push_parent(const AppendArgs &a, int u, float rem_v, int level_v)
+{
+    hx_push_parent_t<false>(a, u, rem_v, level_v);
+}
+
 __device__ __forceinline__ void hx_push_parent_scoped(const AppendArgs &a, int u, float rem_v, int level_v)
 {
-    bool grew = hx_raise_max_f32(&a.tail[u], rem_v);
-    int old = atomicMax(&a.level[u], level_v + 1);
-    grew = grew || (level_v + 1 > old);
-    if (grew && (uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch) {
-        int slot = atomicAdd(&a.counters[a.cout], 1);
-        __hip_atomic_store(&a.list_out[slot], u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    hx_push_parent_t<true>(a, u, rem_v, level_v);
 }
 
 __global__ void hx_append_reset_kernel(int32_t *counters)

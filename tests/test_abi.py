@@ -32,3 +32,27 @@ def test_null_context_is_an_error_not_a_crash():
     assert lib.hx_ctx_destroy(None) == -1
     assert lib.hx_last_error(None) == b"NULL context"
     assert lib.hx_ctx_create(None, 0) == -1
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes structures of the binding against what a C compiler makes of hx.h."""
+    import subprocess
+    structs = {"hx_model": binding.hx_model, "hx_calls": binding.hx_calls, "hx_prefill_tab": binding.hx_prefill_tab,
+               "hx_decode_tab": binding.hx_decode_tab, "hx_links": binding.hx_links, "hx_intervals": binding.hx_intervals}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hx.h"', 'int main(void) {']
+    for name, cls in structs.items():
+        lines.append(f'printf("{name} size %zu\\n", sizeof({name}));')
+        for field, _ in cls._fields_:
+            lines.append(f'printf("{name} {field} %zu\\n", offsetof({name}, {field}));')
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = subprocess.check_output([str(exe)], text=True).split("\n")
+    want = []
+    for name, cls in structs.items():
+        want.append(f"{name} size {ctypes.sizeof(cls)}")
+        for field, _ in cls._fields_:
+            want.append(f"{name} {field} {getattr(cls, field).offset}")
+    assert [g for g in got if g] == want
