@@ -82,14 +82,22 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
         if (my_t == t) my_rank = __popcll(b & ((1ull << lane) - 1ull));
     }
     __syncthreads();
+    // class sizes: one thread per class adds up the waves' counts, then one thread lays out the segments
+    if (tid < kT) {
+        int n = 0;
+        for (int k = 0; k < (a.D + HX_WAVE - 1) / HX_WAVE; ++k) {
+            const int here = s_wcnt[k][tid];
+            s_wcnt[k][tid] = n;                      // instances of the class in earlier waves
+            n += here;
+        }
+        s_cnt[tid] = n;
+    }
+    __syncthreads();
     if (tid == 0) {
         int e = 0;
         for (int t = 0; t < kT; ++t) {
-            int n = 0;
-            for (int k = 0; k < (a.D + HX_WAVE - 1) / HX_WAVE; ++k) n += s_wcnt[k][t];
-            s_cnt[t] = n;
             s_seg[t] = e;
-            e += (n + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP;
+            e += (s_cnt[t] + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP;
         }
         s_seg[kT] = e;
         for (int t = 0; t <= kT; ++t) o->seg[t] = s_seg[t];
@@ -108,9 +116,7 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
     }
     if (tid < a.D) {
         const int d = tid, t = my_t;
-        int rank = my_rank;
-        for (int k = 0; k < wv; ++k) rank += s_wcnt[k][t];
-        int e = s_seg[t] + rank;
+        int e = s_seg[t] + s_wcnt[wv][t] + my_rank;
         HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], a.d_qd[d],
                                    1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
         o->dec_wait[e] = x.wait; o->dec_c1[e] = x.c1; o->dec_c2[e] = x.c2; o->dec_kB[e] = x.kB;
