@@ -38,6 +38,9 @@ __global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
     __shared__ float s_invF[kT], s_invB[kT], s_c1[kT], s_kB[kT], s_c2[kT];
     __shared__ __align__(16) float s_invbw[kT * kT], s_lat[kT * kT];
     const int tid = threadIdx.x;
+    // the first node's lengths are on their way while the class tables are set up
+    const int v0 = blockIdx.x * blockDim.x + tid;
+    int L = v0 < a.n ? a.L_in[v0] : 0, O = v0 < a.n ? a.L_out[v0] : 0;
     if (tid < kT) {
         const bool in = tid < a.T;
         float invF = in ? 1.0f / a.tF[tid] : 0.0f, invB = in ? 1.0f / a.tB[tid] : 0.0f;
@@ -53,8 +56,10 @@ __global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
         s_lat[tid] = in ? (a.lat ? a.lat[tp * a.T + td] : 0.0f) : INFINITY;
     }
     __syncthreads();
-    for (int v = blockIdx.x * blockDim.x + tid; v < a.n; v += gridDim.x * blockDim.x) {
-        const HxCallF cf = hx_call_terms(a.m, a.L_in[v], a.L_out[v]);
+    for (int v = v0; v < a.n; v += gridDim.x * blockDim.x) {
+        const HxCallF cf = hx_call_terms(a.m, L, O);
+        const int vn = v + gridDim.x * blockDim.x;
+        if (vn < a.n) { L = a.L_in[vn]; O = a.L_out[vn]; }
         float dec[kT];
 #pragma unroll
         for (int td = 0; td < kT; ++td) dec[td] = hx_decode_time(cf, s_c1[td], s_c2[td], s_kB[td]);
