@@ -294,8 +294,8 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, i
 typedef int HxTlGroup __attribute__((ext_vector_type(16)));      // eight (time, occupancy) entries
 typedef __attribute__((address_space(4))) const HxTlGroup *hx_tl_group_cp;
 
-__device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restrict__ e, const short *__restrict__ src, int n,
-                                                           int thr, float T, bool active)
+__device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restrict__ e, const float *lds_t, const short *lds_src,
+                                                           int n, int thr, float T, bool active)
 {
     const bool open = active && thr >= 0;
     float rs = INFINITY, ans = INFINITY;
@@ -323,13 +323,14 @@ __device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restric
 #undef HX_TL_STEP
     HxSlot r{INFINITY, -1};
     if (open && ans < INFINITY) {
+        // which entry the start is: times are strictly increasing, a bisection over the copy in LDS finds it
         int lo = 0, hi = n - 1;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (__int_as_float(e[mid].x) < ans) lo = mid + 1; else hi = mid;
+            if (lds_t[mid] < ans) lo = mid + 1; else hi = mid;
         }
         r.S = ans;
-        r.src = src[lo];
+        r.src = lds_src[lo];
     }
     return r;
 }
@@ -337,13 +338,15 @@ __device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restric
 // Workgroup (d, part): calls part*chunk .. of the queue against instance d.  The calls that may
 // go to d (free ones and those locked to d) are first gathered in LDS, so that the scan runs with
 // full wavefronts however many calls are locked elsewhere; then one call per lane.
-constexpr int DS_CHUNK = 2048;        // calls per workgroup at most
+constexpr int DS_CHUNK = 1024;        // calls per workgroup at most
 
 __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, const int2 *__restrict__ tl_e,
                                                               const short *__restrict__ tl_src, const int *__restrict__ tl_n,
                                                               int nt, int splits, int chunk)
 {
     __shared__ int s_c[DS_CHUNK], s_L[DS_CHUNK], s_O[DS_CHUNK];
+    __shared__ float s_t[2 * HX_MAX_INTERVALS + 2];        // the timeline's times and sources, for the bisection
+    __shared__ short s_src[2 * HX_MAX_INTERVALS + 2];
     __shared__ int s_count;
     const int tid = threadIdx.x;
     const int lane = tid & (HX_WAVE - 1);
@@ -357,6 +360,7 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, cons
     const int cap = a.d_cap[d];
     const int c_lo = part * chunk, c_hi = min(a.Q, c_lo + chunk);
     if (tid == 0) s_count = 0;
+    for (int i = tid; i < n; i += blockDim.x) { s_t[i] = __int_as_float(e[i].x); s_src[i] = src[i]; }
     __syncthreads();
     for (int base = c_lo; base < c_hi; base += blockDim.x) {
         const int c = base + tid;
@@ -383,14 +387,13 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, cons
         const bool in = i < n_legal;
         const int c = in ? s_c[i] : 0, L = in ? s_L[i] : 0, O = in ? s_O[i] : 0;
         const HxDecodeCand k = hx_decode_candidate(a.m, L, O, -1, d, a.D, x, cap, a.status);
-        const HxSlot s = hx_earliest_start_shared(e, src, n, k.thr, k.T, in);
+        const HxSlot s = hx_earliest_start_shared(e, s_t, s_src, n, k.thr, k.T, in);
         const float v = s.S + k.T;                         // +inf when there is no start
         if (in) {
             if (a.start) a.start[(size_t)c * a.D + d] = s.S;
             if (a.cost) a.cost[(size_t)c * a.D + d] = s.src >= 0 ? v : INFINITY;
             if (s.src >= 0 && v < INFINITY) {
-                const u64 mine = hx_decode_key(v, d, s.src);
-                if (__hip_atomic_load(&a.key[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > mine) atomicMin(&a.key[c], mine);
+                atomicMin(&a.key[c], hx_decode_key(v, d, s.src));      // result unused: nothing waits for it
             }
         }
     }
