@@ -114,9 +114,12 @@
  *
  * The choice of these formulas cannot be checked against printed values of
  * the paper (it prints none): parity with "the paper's estimator" is
- * unpinned.  What the tests pin is that this file computes R1..R12 as
- * written: round-number cases worked by hand, closed forms, brute force,
- * monotonicity and scaling invariants.
+ * unpinned, and so are the tie rules of R8, R13, R14, R25, R26, the
+ * commit/drain rule R12 and the interval layout R22.  What the tests pin is
+ * that this file computes R1..R14 and R22..R26 as written: round-number
+ * cases worked by hand, closed forms, brute force on small inputs, an
+ * integer-time simulation of the intervals, monotonicity and scaling
+ * invariants, validity of finished plans.
  *
  * L = L_in, O = predicted output length, kappa = KV bytes per token,
  * phi = FLOP per token, a = attention FLOP per token^2, omega = weight
