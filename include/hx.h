@@ -178,8 +178,11 @@ int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
  * Incremental form for DAGs revealed at run time (Sec. 4.1, online reveal;
  * Sec. 5.1, the horizon is refreshed at every reveal).  The graph lives
  * in the context.  hx_dag_reserve sizes it (allocates; not for the hot loop)
- * and empties it; max_depth bounds the longest path in edges and with it the
- * number of propagation sweeps one append runs.
+ * and empties it.  An append propagates with one walk per new node, of any
+ * depth; only a walk that is cut short (more than 16 parents waiting at once,
+ * or more than 1024 nodes visited) hands over to level-by-level sweeps, of
+ * which at most max_depth run: if they do not finish, the stream status gets
+ * HX_ERR_CAPACITY.  max_depth = longest path in edges is always enough.
  */
 int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges, int32_t max_wf,
                    int32_t max_depth, void *stream);

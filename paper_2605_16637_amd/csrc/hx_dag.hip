@@ -373,9 +373,13 @@ __device__ __forceinline__ void hx_push_parent_t(const AppendArgs &a, int u, flo
     }
 }
 
-__device__ __forceinline__ void hx_push_parent(const AppendArgs &a, int u, float rem_v, int level_v)
+// node u onto the worklist of the next sweep, once per sweep (rare path: one atomic per entry)
+__device__ __forceinline__ void hx_enqueue(const AppendArgs &a, int u)
 {
-    hx_push_parent_t<false>(a, u, rem_v, level_v);
+    if ((uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch) {
+        const int slot = atomicAdd(&a.counters[a.cout], 1);
+        a.list_out[slot] = u;
+    }
 }
 
 __device__ __forceinline__ void hx_push_parent_scoped(const AppendArgs &a, int u, float rem_v, int level_v)
@@ -410,16 +414,46 @@ __global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a)
     }
 }
 
-// second phase of an append: parents of the new nodes (a kernel boundary after
-// init, so that a new node whose parent is also new sees that parent initialised)
-__global__ __launch_bounds__(256) void hx_append_push_new_kernel(AppendArgs a)
+// Second phase of an append (a kernel boundary after init, so that a new node whose parent is
+// also new finds that parent initialised).  Asynchronous propagation: every new node walks up from itself, one thread per new node.  A visit
+// of node u recomputes rem[u] from the tail u has now, raises its workflow's horizon, and raises the
+// tail and level of u's parents; a parent that grew is visited next (further grown parents wait on a
+// small stack).  Whoever raises a node visits it afterwards and reads the value current by then, so
+// every increase is carried upwards by someone, and a thread whose value did not raise anything
+// stops: the fixed point is the same as that of the level-by-level sweeps, maxima are exact, and no
+// launch or barrier separates the levels.  A walk that outgrows its stack or its step budget hands
+// the remaining nodes to the worklist, which the sweeps after this kernel finish.
+constexpr int RELAX_STACK = 16;
+constexpr int RELAX_STEPS = 1024;
+
+__global__ __launch_bounds__(256) void hx_append_relax_kernel(AppendArgs a)
 {
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.n_new; i += gridDim.x * blockDim.x) {
-        const int v = a.n_old + i;
-        const float c = a.cost[v];
-        for (int e = a.prow[v]; e < a.prow[v + 1]; ++e) {
-            int u = a.pcol[e];
-            if (u >= 0) hx_push_parent(a, u, c, 0);
+        int stack[RELAX_STACK];
+        int sp = 0, steps = 0;
+        int u = a.n_old + i;
+        while (u >= 0) {
+            const float tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float r = a.cost[u] + tl;
+            hx_raise_max_f32(&a.rem[u], r);
+            const int w = a.wf[u];
+            if (w >= 0) hx_raise_max_f32(&a.horizon[w], r);
+            ++steps;
+            int next = -1;
+            for (int e = a.prow[u]; e < a.prow[u + 1]; ++e) {
+                const int q = a.pcol[e];
+                if (q < 0) continue;
+                bool grew = hx_raise_max_f32(&a.tail[q], r);
+                const int old = atomicMax(&a.level[q], lv + 1);
+                grew = grew || (lv + 1 > old);
+                if (!grew) continue;
+                if (steps >= RELAX_STEPS) hx_enqueue(a, q);
+                else if (next < 0) next = q;
+                else if (sp < RELAX_STACK) stack[sp++] = q;
+                else hx_enqueue(a, q);
+            }
+            u = next >= 0 ? next : (sp > 0 ? stack[--sp] : -1);
         }
     }
 }
@@ -427,27 +461,6 @@ __global__ __launch_bounds__(256) void hx_append_push_new_kernel(AppendArgs a)
 __global__ void hx_append_finish_kernel(AppendArgs a)
 {
     if (threadIdx.x == 0 && a.counters[a.cin] != 0) hx_raise(a.status, HX_ERR_CAPACITY);
-}
-
-// one propagation sweep: nodes whose tail or level grew recompute rem, raise
-// their workflow horizon and push to their own parents
-__global__ __launch_bounds__(256) void hx_append_sweep_kernel(AppendArgs a)
-{
-    const int n = __hip_atomic_load(&a.counters[a.cin], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.counters[a.czero] = 0;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        const int u = a.list_in[i];
-        const float tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float r = a.cost[u] + tl;
-        a.rem[u] = r;
-        const int w = a.wf[u];
-        if (w >= 0) hx_raise_max_f32(&a.horizon[w], r);
-        for (int e = a.prow[u]; e < a.prow[u + 1]; ++e) {
-            int q = a.pcol[e];
-            if (q >= 0) hx_push_parent(a, q, r, lv);
-        }
-    }
 }
 
 // The remaining sweeps in one workgroup: after a few grid-wide sweeps the lists
@@ -648,23 +661,15 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
     a.cin = 0; a.cout = 1; a.czero = 2; a.epoch = ++g.epoch;
     a.list_in = g.list[1]; a.list_out = g.list[0];
     hx_append_init_kernel<<<grid, 256, 0, stream>>>(a);
-    hx_append_push_new_kernel<<<grid, 256, 0, stream>>>(a);
-    // sweep k reads the list sweep k-1 wrote; max_depth sweeps reach every ancestor.  The first
-    // few sweeps have long lists and run grid-wide, the rest is one workgroup looping
-    const int sweep_grid = ctx->num_cu * 2;
-    const int wide = g.max_depth < 3 ? g.max_depth : 3;
-    for (int s = 0; s < wide; ++s) {
-        a.cin = (s + 1) % 3; a.cout = (s + 2) % 3; a.czero = s % 3;
-        a.list_in = g.list[s & 1]; a.list_out = g.list[(s + 1) & 1];
-        a.epoch = ++g.epoch;
-        hx_append_sweep_kernel<<<sweep_grid, 256, 0, stream>>>(a);
-    }
-    if (g.max_depth > wide) {
+    hx_append_relax_kernel<<<grid, 256, 0, stream>>>(a);
+    // what the walks handed over (normally nothing) is finished level by level in one workgroup:
+    // sweep k reads the list sweep k-1 wrote, max_depth sweeps reach every ancestor
+    if (g.max_depth > 0) {
         a.epoch = g.epoch;                       // the loop advances it once per step
-        hx_append_tail_kernel<<<1, 1024, 0, stream>>>(a, g.list[0], g.list[1], wide, g.max_depth - wide);
-        g.epoch += (uint32_t)(g.max_depth - wide);
+        hx_append_tail_kernel<<<1, 1024, 0, stream>>>(a, g.list[0], g.list[1], 0, g.max_depth);
+        g.epoch += (uint32_t)g.max_depth;
     } else {
-        a.cin = (g.max_depth + 1) % 3;
+        a.cin = 1;
         hx_append_finish_kernel<<<1, 64, 0, stream>>>(a);
     }
     if (int rc = hx_check_launch(ctx, "hx_dag_append kernels")) return rc;

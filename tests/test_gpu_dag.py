@@ -196,10 +196,46 @@ def test_append_errors(ctx):
     with pytest.raises(binding.HxError) as e:
         ctx.hx_stream_status()
     assert e.value.code == -3
-    # a chain deeper than max_depth: propagation is cut and reported, nothing hangs
+    # a chain deeper than max_depth is no error: the walks do not go level by level
     ctx.hx_dag_reserve(16, 16, 1, 2)
     ctx.hx_dag_append(dev(np.array([0, 0, 1, 2, 3, 4, 5], np.int32)), dev(np.arange(5, dtype=np.int32)),
                       dev(np.ones(6, np.float32)), dev(np.zeros(6, np.int32)))
+    ctx.hx_stream_status()
+    rem, tail, level, hor = view(ctx, 6, 1)
+    assert list(rem) == [6, 5, 4, 3, 2, 1] and list(level) == [5, 4, 3, 2, 1, 0] and list(hor) == [6]
+
+
+def chain_and_fan(n_chain, n_fan):
+    """A chain 0 <- 1 <- ... and then one node whose parents are the last n_fan chain nodes."""
+    rp = np.concatenate([[0], np.arange(n_chain), [n_chain - 1 + n_fan]]).astype(np.int32)       # node 0 has no parent
+    col = np.concatenate([np.arange(n_chain - 1), np.arange(n_chain - n_fan, n_chain)]).astype(np.int32)
+    return rp, col
+
+
+def test_append_walks_that_hand_over_to_the_sweeps(ctx):
+    """A walk is cut short when more than 16 grown parents wait at once, or after 1024 visited nodes; the rest
+    goes level by level.  Both paths must still give the full recomputation, and too few sweeps are reported."""
+    from paper_2605_16637_amd import binding
+    rng = np.random.default_rng(12)
+    for n_chain, n_fan, depth in ((60, 40, 64), (1500, 1, 1500)):
+        n = n_chain + 1
+        rp, col = chain_and_fan(n_chain, n_fan)
+        cost = rng.uniform(0.5, 2.0, n).astype(np.float32)
+        ctx.hx_dag_reserve(n + 4, col.size + 4, 1, depth)
+        # the chain first, then the node with the many parents
+        ctx.hx_dag_append(dev(rp[:n_chain + 1]), dev(col[:n_chain - 1]), dev(cost[:n_chain]), dev(np.zeros(n_chain, np.int32)))
+        ctx.hx_stream_status()
+        ctx.hx_dag_append(dev(np.array([0, n_fan], np.int32)), dev(col[n_chain - 1:]), dev(cost[n_chain:]), dev(np.zeros(1, np.int32)))
+        ctx.hx_stream_status()
+        want = o.critical_path_by_parents(rp, col, cost.astype(np.float64), np.zeros(n, np.int32), 1, round_f32=True)
+        got = view(ctx, n, 1)
+        assert np.array_equal(got[2], want[2])
+        for k in (0, 1, 3):
+            assert np.array_equal(got[k].astype(np.float64), want[k]), k
+    # the 1500-deep chain with room for 3 sweeps only: the cut walk cannot be finished, and says so
+    rp, col = chain_and_fan(1500, 1)
+    ctx.hx_dag_reserve(1600, 1600, 1, 3)
+    ctx.hx_dag_append(dev(rp[:1501]), dev(col[:1499]), dev(np.ones(1500, np.float32)), dev(np.zeros(1500, np.int32)))
     with pytest.raises(binding.HxError) as e:
         ctx.hx_stream_status()
     assert e.value.code == -4
