@@ -284,8 +284,12 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
  * same risk score): rank[c] = position of call c when the calls are sorted by
  * decreasing ratio, equal ratios by increasing call index (0 = most urgent).
  * ratio [C] device in (as written by hx_score_placements or hx_select; +inf =
- * nothing feasible, ranked first), rank [C] device out.  Work grows with C^2;
- * meant for queues up to some 10^5 calls.
+ * nothing feasible, ranked first), rank [C] device out.  Up to 16384 calls every
+ * call is compared with every call (no scratch).  Beyond that the calls are
+ * split into 257 buckets by 256 sampled splitters and compared within their
+ * bucket; the library then keeps 8 bytes of scratch per call, and a call with a
+ * larger C than any before it allocates, after waiting for the device, and is
+ * then not capturable in a graph.
  */
 int hx_rank(hx_ctx *ctx, int32_t C, const float *ratio, int32_t *rank, void *stream);
 

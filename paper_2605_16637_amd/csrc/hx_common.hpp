@@ -60,6 +60,8 @@ struct hx_ctx {
     unsigned long long *d_acc = nullptr;   // commit accumulators, [3 * HX_MAX_INSTANCES]
     unsigned long long *d_dkey = nullptr;  // decode-stage selection keys, [dkey_cap]
     int32_t dkey_cap = 0;
+    unsigned long long *d_rkey = nullptr;  // sorted tiles of ordering keys, [rkey_cap]
+    size_t rkey_cap = 0;
     void *d_dtl = nullptr;                 // decode-stage timelines (entries, lengths, sources), dtl_cap entries
     size_t dtl_cap = 0;
     int num_cu = 256;

@@ -174,6 +174,7 @@ extern "C" int hx_ctx_destroy(hx_ctx *ctx)
     if (ctx->d_acc) (void)hipFree(ctx->d_acc);
     if (ctx->d_dkey) (void)hipFree(ctx->d_dkey);
     if (ctx->d_dtl) (void)hipFree(ctx->d_dtl);
+    if (ctx->d_rkey) (void)hipFree(ctx->d_rkey);
     delete ctx;
     return HX_OK;
 }

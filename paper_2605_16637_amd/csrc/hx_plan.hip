@@ -16,6 +16,7 @@ constexpr int kT = HX_MAX_TYPES;
 // ---- one-pass ordering -----------------------------------------------------------
 
 constexpr int RANK_TILE = 2048;      // calls compared against per block
+constexpr int RANK_SMALL = 16384;    // queues up to this size are ranked by all-pairs counting
 
 __global__ __launch_bounds__(256) void hx_rank_zero_kernel(int32_t *rank, int C)
 {
@@ -49,6 +50,148 @@ __global__ __launch_bounds__(256) void hx_rank_count_kernel(const float *ratio, 
 #pragma unroll 8
     for (int i = 0; i < kn; ++i) ahead += s_key[i] > mine;
     if (ahead) atomicAdd(&rank[c], ahead);
+}
+
+// Larger queues: sample sort.  256 evenly spaced calls are sorted and serve as splitters; every call
+// finds its bucket among them, takes a slot in it, and is moved next to the other members of its
+// bucket; a workgroup per bucket then counts, for every member, the larger keys inside the bucket and
+// adds the sizes of all higher buckets.  Keys are unique (they end in the call index), so buckets stay
+// balanced however many ratios are equal, and the ranks do not depend on the order the slots were
+// taken in.
+constexpr int RANK_SPLIT = 256;                  // splitters; buckets 0 .. RANK_SPLIT
+constexpr int RANK_BUCKETS = RANK_SPLIT + 1;
+constexpr int RANK_CHUNK = 2048;                 // bucket members held in LDS at a time
+
+struct RankScratch {
+    unsigned long long *split;                   // [RANK_SPLIT] ascending
+    unsigned long long *bkey;                    // [C] keys grouped by bucket
+    int *hist;                                   // [RANK_BUCKETS] bucket sizes
+};
+
+__global__ __launch_bounds__(RANK_SPLIT) void hx_rank_splitters_kernel(const float *ratio, int C, RankScratch w)
+{
+    __shared__ unsigned long long s[RANK_SPLIT];
+    const int t = threadIdx.x;
+    const int c = (int)(((long long)t * C) / RANK_SPLIT);
+    s[t] = hx_rank_key64(ratio[c], c);
+    w.hist[t] = 0;
+    if (t == 0) w.hist[RANK_SPLIT] = 0;
+    __syncthreads();
+    for (int k = 2; k <= RANK_SPLIT; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const int l = t ^ j;
+            const unsigned long long x = s[t], y = s[l];
+            __syncthreads();
+            // ascending bitonic network: the lower index of a pair keeps the smaller key when (t & k) == 0
+            const bool keep_small = ((t & k) == 0) == (t < l);
+            s[t] = keep_small ? (x < y ? x : y) : (x < y ? y : x);
+            __syncthreads();
+        }
+    }
+    w.split[t] = s[t];
+}
+
+// bucket of a key: the number of splitters below it
+__device__ __forceinline__ int hx_rank_bucket(const unsigned long long *split, unsigned long long key)
+{
+    int lo = 0, hi = RANK_SPLIT;                  // first splitter that is not below the key
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (split[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// every call takes a slot in its bucket; the slot is parked in rank[c].  The calls of a workgroup first
+// count themselves per bucket in LDS, then the workgroup reserves its share of every bucket with one
+// global atomic per non-empty bucket (one atomic per call would queue up on 257 addresses).
+__global__ __launch_bounds__(1024) void hx_rank_slot_kernel(const float *ratio, int32_t *rank, int C, RankScratch w)
+{
+    __shared__ unsigned long long s_split[RANK_SPLIT];
+    __shared__ int s_cnt[RANK_BUCKETS], s_base[RANK_BUCKETS];
+    const int t = threadIdx.x;
+    if (t < RANK_SPLIT) s_split[t] = w.split[t];
+    if (t < RANK_BUCKETS) s_cnt[t] = 0;
+    __syncthreads();
+    const int c = blockIdx.x * blockDim.x + t;
+    int b = 0, local = 0;
+    if (c < C) {
+        b = hx_rank_bucket(s_split, hx_rank_key64(ratio[c], c));
+        local = atomicAdd(&s_cnt[b], 1);
+    }
+    __syncthreads();
+    if (t < RANK_BUCKETS && s_cnt[t] > 0) s_base[t] = atomicAdd(&w.hist[t], s_cnt[t]);
+    __syncthreads();
+    if (c < C) rank[c] = s_base[b] + local;
+}
+
+// exclusive prefix of the bucket sizes, by every workgroup for itself (257 values)
+__device__ __forceinline__ void hx_rank_starts(const int *hist, int *s_start)
+{
+    __shared__ int s_part[4];
+    const int t = threadIdx.x;                    // the first 256 threads: bucket t (bucket 256 rides with thread 255)
+    const int lane = t & (HX_WAVE - 1), wv = t >> 6;
+    const int h = t < RANK_SPLIT ? hist[t] : 0;
+    int incl = h;
+#pragma unroll
+    for (int off = 1; off < HX_WAVE; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    if (t < RANK_SPLIT && lane == HX_WAVE - 1) s_part[wv] = incl;
+    __syncthreads();
+    if (t < RANK_SPLIT) {
+        int base = 0;
+        for (int k = 0; k < wv; ++k) base += s_part[k];
+        s_start[t] = base + incl - h;
+        if (t == RANK_SPLIT - 1) { s_start[RANK_SPLIT] = base + incl; s_start[RANK_BUCKETS] = base + incl + hist[RANK_SPLIT]; }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void hx_rank_scatter_kernel(const float *ratio, const int32_t *rank, int C, RankScratch w)
+{
+    __shared__ unsigned long long s_split[RANK_SPLIT];
+    __shared__ int s_start[RANK_BUCKETS + 1];
+    s_split[threadIdx.x] = w.split[threadIdx.x];
+    hx_rank_starts(w.hist, s_start);
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    const unsigned long long key = hx_rank_key64(ratio[c], c);
+    w.bkey[s_start[hx_rank_bucket(s_split, key)] + rank[c]] = key;
+}
+
+// workgroup b: rank of every member of bucket b = keys in higher buckets + larger keys in its own
+__global__ __launch_bounds__(1024) void hx_rank_within_kernel(int32_t *rank, int C, RankScratch w)
+{
+    __shared__ unsigned long long s_key[RANK_CHUNK];
+    __shared__ int s_start[RANK_BUCKETS + 1];
+    hx_rank_starts(w.hist, s_start);
+    const int b = blockIdx.x;
+    const int m0 = s_start[b], m1 = s_start[b + 1];
+    const int higher = C - m1;
+    // members in rounds of one per thread, each compared with the whole bucket, which passes through LDS in chunks
+    for (int base = m0; base < m1; base += blockDim.x) {                   // same trip count for all threads
+        const int i = base + threadIdx.x;
+        const unsigned long long mine = i < m1 ? w.bkey[i] : ~0ull;
+        int ahead = 0;
+        for (int k0 = m0; k0 < m1; k0 += RANK_CHUNK) {
+            const int kn = min(RANK_CHUNK, m1 - k0);
+            __syncthreads();
+            for (int k = threadIdx.x; k < kn; k += blockDim.x) s_key[k] = w.bkey[k0 + k];
+            __syncthreads();
+            int k = 0;
+            for (; k + 8 <= kn; k += 8) {                  // eight independent reads in flight
+                unsigned long long kk[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) kk[u] = s_key[k + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) ahead += kk[u] > mine;
+            }
+            for (; k < kn; ++k) ahead += s_key[k] > mine;
+        }
+        if (i < m1) rank[0xffffffffu - (unsigned)(mine & 0xffffffffull)] = higher + ahead;
+    }
 }
 
 // ---- recomputing greedy -------------------------------------------------------------
@@ -291,9 +434,28 @@ extern "C" int hx_rank(hx_ctx *ctx, int32_t C, const float *ratio, int32_t *rank
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
     hipStream_t stream = (hipStream_t)stream_;
     const int bx = (C + 255) / 256, by = (C + RANK_TILE - 1) / RANK_TILE;
-    HX_REQUIRE(ctx, by <= 65535, HX_ERR_SHAPE, "more than %d calls to rank", 65535 * RANK_TILE);
-    hx_rank_zero_kernel<<<bx, 256, 0, stream>>>(rank, C);
-    hx_rank_count_kernel<<<dim3(bx, by), 256, 0, stream>>>(ratio, rank, C);
+    if (C <= RANK_SMALL) {
+        // small queues: every call against every call, no scratch
+        hx_rank_zero_kernel<<<bx, 256, 0, stream>>>(rank, C);
+        hx_rank_count_kernel<<<dim3(bx, by), 256, 0, stream>>>(ratio, rank, C);
+        return hx_check_launch(ctx, "hx_rank kernels");
+    }
+    const size_t need = (size_t)C + RANK_SPLIT + (RANK_BUCKETS + 1) / 2 + 8;      // keys, splitters, bucket sizes (two ints per word)
+    if (need > ctx->rkey_cap) {
+        // grown, never shrunk; work queued on the old block has to finish before it goes
+        HX_HIP(ctx, hipDeviceSynchronize());
+        if (ctx->d_rkey) { HX_HIP(ctx, hipFree(ctx->d_rkey)); ctx->d_rkey = nullptr; ctx->rkey_cap = 0; }
+        HX_HIP(ctx, hipMalloc((void **)&ctx->d_rkey, need * sizeof(unsigned long long)));
+        ctx->rkey_cap = need;
+    }
+    RankScratch w;
+    w.split = ctx->d_rkey;
+    w.bkey = ctx->d_rkey + RANK_SPLIT;
+    w.hist = (int *)(ctx->d_rkey + RANK_SPLIT + C);
+    hx_rank_splitters_kernel<<<1, RANK_SPLIT, 0, stream>>>(ratio, C, w);
+    hx_rank_slot_kernel<<<(C + 1023) / 1024, 1024, 0, stream>>>(ratio, rank, C, w);
+    hx_rank_scatter_kernel<<<bx, 256, 0, stream>>>(ratio, rank, C, w);
+    hx_rank_within_kernel<<<RANK_BUCKETS, 1024, 0, stream>>>(rank, C, w);
     return hx_check_launch(ctx, "hx_rank kernels");
 }
 

@@ -26,7 +26,7 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("C", [1, 7, 2048, 2049, 40000])
+@pytest.mark.parametrize("C", [1, 7, 2048, 2049, 16384, 16385, 40000, 100003])
 def test_rank_matches_oracle(ctx, C):
     import torch
     rng = np.random.default_rng(60 + C)
