@@ -336,12 +336,15 @@ def cpu_baseline(rnd, target_s=12.0):
     o.score(rnd.model, L[:n0], O[:n0], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
     dt = time.perf_counter() - t0
     n1 = int(max(n0, min(len(L), n0 * target_s / max(dt, 1e-6))))
+    # when the whole round takes less than the target, it is scored several times over
+    passes = int(max(1, min(20, round(target_s * n0 / max(dt, 1e-6) / n1)))) if n1 == len(L) else 1
     t0 = time.perf_counter()
-    o.score(rnd.model, L[:n1], O[:n1], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
+    for _ in range(passes):
+        o.score(rnd.model, L[:n1], O[:n1], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
     dt = time.perf_counter() - t0
-    return dict(value=n1 * per / dt, unit="candidates/s", cores=threads, kind="oracle",
-                sample="first %d of %d calls x %d x %d candidates, fp64, %.1f s" %
-                       (n1, len(L), rnd.pre["n"], rnd.dec["n"], dt))
+    return dict(value=passes * n1 * per / dt, unit="candidates/s", cores=threads, kind="oracle",
+                sample="%d pass(es) over the first %d of %d calls x %d x %d candidates, fp64, %.1f s" %
+                       (passes, n1, len(L), rnd.pre["n"], rnd.dec["n"], dt))
 
 
 def main():
