@@ -606,8 +606,9 @@ double hxo_decode_start(int32_t m_tok, double T, int32_t cap_tok,
 /*
  * R24, R25: decode-stage score of every (call, instance).  Interval lists are
  * stored with a fixed stride: instance d owns entries d*stride .. d*stride +
- * iv_count[d] - 1.  t_scale multiplies every decode time (1 for the method
- * itself; the parity tests use it to bracket fp32 rounding of Tdec).
+ * iv_count[d] - 1.  Every decode time is taken as t_scale * Tdec + t_shift
+ * (1 and 0 for the method itself; the parity tests use them to bracket what
+ * fp32 rounding of Tdec and of start + Tdec can decide differently).
  * start, cost: [Q*D] or NULL; best_*: [Q].  Returns -3 on a lock outside
  * [-1, D).
  */
@@ -615,7 +616,7 @@ int hxo_decode_score(const hxo_model *m, int32_t Q, const int32_t *L_in, const i
                      int32_t D, const float *dF, const float *dB, const int32_t *d_used, const int32_t *d_cap,
                      const int32_t *d_batch,
                      int32_t stride, const int32_t *iv_count, const double *iv_start, const double *iv_end,
-                     const int32_t *iv_tok, double t_scale,
+                     const int32_t *iv_tok, double t_scale, double t_shift,
                      double *start, double *cost, int32_t *best_d, double *best_start, double *best_cost)
 {
     if (Q < 0 || D < 0 || stride < 0) return -1;
@@ -628,7 +629,8 @@ int hxo_decode_score(const hxo_model *m, int32_t Q, const int32_t *L_in, const i
             double S = INFINITY, v = INFINITY;
             if (!lock || lock[c] < 0 || lock[c] == d) {
                 double T = t_scale * (double)L_out[c] *
-                           hxo_decode_token_time(m, L_in[c], L_out[c], d_batch[d], d_used[d], (double)dF[d], (double)dB[d]);
+                           hxo_decode_token_time(m, L_in[c], L_out[c], d_batch[d], d_used[d], (double)dF[d], (double)dB[d]) + t_shift;
+                if (T < 0.0) T = 0.0;
                 int64_t need = (int64_t)L_in[c] + (int64_t)L_out[c];
                 int32_t m_tok = need > 2147483647LL ? 2147483647 : (int32_t)need;
                 if (need <= (int64_t)d_cap[d])
@@ -669,7 +671,7 @@ int hxo_decode_plan_greedy(const hxo_model *m, int32_t Q, const int32_t *L_in, c
             int32_t bd;
             double bs, bc;
             rc = hxo_decode_score(m, 1, L_in + c, L_out + c, lock ? lock + c : NULL, D, dF, dB, d_used, d_cap, d_batch,
-                                  stride, iv_count, iv_start, iv_end, iv_tok, 1.0, NULL, NULL, &bd, &bs, &bc);
+                                  stride, iv_count, iv_start, iv_end, iv_tok, 1.0, 0.0, NULL, NULL, &bd, &bs, &bc);
             if (rc) break;
             double r = (elapsed[c] + bc + tail[node[c]]) / horizon[wf[c]];
             if (pick < 0 || r > pick_r) { pick = c; pick_r = r; pick_d = bd; pick_s = bs; pick_cost = bc; }

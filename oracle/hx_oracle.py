@@ -291,7 +291,7 @@ def _intervals(iv, D):
     return stride, cnt, s, e, k
 
 
-def decode_score(model, L_in, L_out, lock, dec, iv, t_scale=1.0, want_all=False) -> DecodeScore:
+def decode_score(model, L_in, L_out, lock, dec, iv, t_scale=1.0, t_shift=0.0, want_all=False) -> DecodeScore:
     """R24/R25 over all (call, decode instance) pairs."""
     L_in, L_out = _i32(L_in), _i32(L_out)
     lock = None if lock is None else _i32(lock)
@@ -303,7 +303,7 @@ def decode_score(model, L_in, L_out, lock, dec, iv, t_scale=1.0, want_all=False)
     co = np.empty((Q, D), np.float64) if want_all else None
     m = _model(model)
     rc = lib().hxo_decode_score(C.byref(m), Q, _p(L_in), _p(L_out), _p(lock), D, _p(dF), _p(dB), _p(dus), _p(dcap), _p(dba),
-                                stride, _p(cnt), _p(s), _p(e), _p(k), C.c_double(float(t_scale)),
+                                stride, _p(cnt), _p(s), _p(e), _p(k), C.c_double(float(t_scale)), C.c_double(float(t_shift)),
                                 _p(st), _p(co), _p(bd), _p(bs), _p(bc))
     if rc:
         raise ValueError(f"hxo_decode_score failed: {rc}")
