@@ -345,7 +345,9 @@ typedef struct {
  *   S(c,d)  = the earliest t >= 0 such that the intervals of d leave room for
  *             L_in + L_out more tokens (Eq. 3) under cap_tok[d] (Eq. 4) at every
  *             instant of [t, t + T); it is 0 or the end of one of d's entries;
- *             +inf when L_in + L_out > cap_tok[d],
+ *             +inf when L_in + L_out > cap_tok[d].  The window is half open and
+ *             t + T is formed and compared in fp32: a call fits exactly between
+ *             two entries when fl(t + T) equals the next entry's start,
  *   cost    = S + T.
  * lock [Q] device or NULL: lock[c] = d restricts call c to instance d (a call
  * locked during prefill planning cannot migrate), -1 leaves it free; any other
