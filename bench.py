@@ -66,12 +66,13 @@ class RoundOnDevice:
         self.drain_p = dev(np.full(P, int(Ls / max(P, 1)), np.int32))
         self.drain_q = dev(np.full(D, int(Os / max(D, 1)), np.int32))
         self.release = dev(np.full(D, int((Ls + Os) / max(D, 1)), np.int32))
+        self.side = None
 
-    def horizons(self):
+    def horizons(self, stream=None):
         r = self.rnd
-        self.ctx.hx_node_cost(r.model, self.L_in, self.L_out, self.tF, self.tB, self.links, self.cost)
+        self.ctx.hx_node_cost(r.model, self.L_in, self.L_out, self.tF, self.tB, self.links, self.cost, stream=stream)
         self.ctx.hx_critical_path(self.row_ptr, self.col, self.cost, self.wf_ptr,
-                                  self.rem, self.tail, self.level, self.hor)
+                                  self.rem, self.tail, self.level, self.hor, stream=stream)
 
     def score(self):
         self.ctx.hx_score_placements(self.rnd.model, self.calls, self.pre, self.dec, self.links,
@@ -82,9 +83,32 @@ class RoundOnDevice:
         self.ctx.hx_commit(self.calls, self.bp, self.bd, self.pre["backlog_tok"], self.dec["used_tok"],
                            self.dec["batch"], self.dec["qd_tok"], self.drain_p, self.drain_q, self.release)
 
+    def search(self):
+        """The search alone: best pair and cost of every call; needs no horizon."""
+        self.ctx.hx_score_placements(self.rnd.model, self.calls, self.pre, self.dec, self.links,
+                                     best_p=self.bp, best_d=self.bd, best_cost=self.bc)
+
+    def urgency(self):
+        self.ctx.hx_urgency(self.calls, self.bc, self.tail, self.hor, self.ratio)
+
     def step(self):
+        """One round, every stage on one stream."""
         self.horizons()
         self.score()
+        self.commit()
+
+    def step_overlapped(self):
+        """One round with the horizon refresh (node cost -> critical path) on a second stream beside the
+        search, which does not need it; the urgency fold joins the two, the commit follows."""
+        import torch
+        main = torch.cuda.current_stream()
+        if self.side is None:
+            self.side = torch.cuda.Stream()          # default priority
+        self.side.wait_stream(main)
+        self.horizons(stream=self.side)
+        self.search()
+        main.wait_stream(self.side)
+        self.urgency()
         self.commit()
 
 
@@ -355,6 +379,9 @@ def main():
     ap.add_argument("--workload", default="large", choices=["large", "mid", "stream"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--eager", action="store_true", help="launch every step from the host instead of replaying a HIP graph")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the horizon refresh on a second stream beside the search (measured: 3-4 us slower per round "
+                         "than one stream, the fork and join cost more than the small kernels they hide)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size reference for HBM byte counters")
@@ -375,9 +402,10 @@ def main():
     n_cand = C * P * D
 
     # the round is launch-bound on the host unless its launches are replayed from a HIP graph
-    rd.step()
+    step = rd.step_overlapped if args.overlap else rd.step
+    step()
     torch.cuda.synchronize()
-    run = rd.step if args.eager else capture(torch, rd.step).replay
+    run = step if args.eager else capture(torch, step).replay
     wall = time_steps(torch, run, args.steps, args.warmup)
     ctx.hx_stream_status()
     ms_per_step = wall / args.steps * 1e3
@@ -396,7 +424,8 @@ def main():
                                 "stream": "streaming round shape: 32768 ready calls x 512 x 512, 8 classes"}[args.workload],
                    "calls": C, "prefill": P, "decode": D, "candidates_per_round": n_cand,
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
-                   "step": "node cost -> critical path -> fused score+argmin+ratio -> commit",
+                   "step": ("[node cost -> critical path] beside [fused score+argmin] on two streams -> urgency fold -> commit"
+                            if args.overlap else "node cost -> critical path -> fused score+argmin+ratio -> commit"),
                    "launch": "eager" if args.eager else "hip graph replay", "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (+ its table-prepare launch)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",

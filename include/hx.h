@@ -277,6 +277,20 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
               const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
               void *stream);
 
+/*
+ * The urgency fold on its own (Eq. (2) with the downstream tail of the call's
+ * node): ratio[c] = (elapsed[c] + best_cost[c] + tail[node[c]]) / horizon[wf[c]],
+ * the same arithmetic as the ratio output of hx_score_placements and hx_select.
+ * For callers that run the search (which needs no horizon) on one stream while
+ * the horizons of the round are still being refreshed on another, and fold
+ * them in afterwards.  calls->node, wf, elapsed, best_cost, ratio: device [C];
+ * a node or workflow outside 0..n_nodes-1 / 0..n_wf-1 gives NaN and raises
+ * HX_ERR_INDEX in the stream status.
+ */
+int hx_urgency(hx_ctx *ctx, const hx_calls *calls, const float *best_cost,
+               const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+               float *ratio, void *stream);
+
 /* ---- (5) the planner around the scoring loop ------------------------------- */
 
 /*

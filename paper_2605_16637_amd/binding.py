@@ -18,7 +18,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
            "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_view",
-           "hx_score_placements", "hx_select", "hx_commit", "hx_rank", "hx_plan_greedy",
+           "hx_score_placements", "hx_select", "hx_urgency", "hx_commit", "hx_rank", "hx_plan_greedy",
            "hx_decode_score", "hx_decode_plan_greedy")
 
 
@@ -264,6 +264,13 @@ class Context:
             C.byref(cs) if cs is not None else None, _ptr(tail, torch.float32), _ptr(horizon, torch.float32),
             n_nodes, n_wf, _ptr(best_p, torch.int32, C_), _ptr(best_d, torch.int32, C_),
             _ptr(best_cost, torch.float32, C_), _ptr(ratio, torch.float32, C_), _stream(stream)))
+
+    def hx_urgency(self, calls, best_cost, tail, horizon, ratio, stream=None):
+        torch = _torch()
+        cs = make_calls(calls)
+        self._check(self.lib.hx_urgency(self._ctx, C.byref(cs), _ptr(best_cost, torch.float32, cs.n),
+                                        _ptr(tail, torch.float32), _ptr(horizon, torch.float32),
+                                        int(tail.numel()), int(horizon.numel()), _ptr(ratio, torch.float32, cs.n), _stream(stream)))
 
     def hx_commit(self, calls, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
                   drain_prefill=None, drain_decode_q=None, release_tok=None,

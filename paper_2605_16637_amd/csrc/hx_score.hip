@@ -311,6 +311,14 @@ __global__ __launch_bounds__(256) void hx_select_kernel(ScoreArgs a)
 }
 
 // fused outputs when the pool is empty: nothing is feasible
+__global__ __launch_bounds__(256) void hx_urgency_kernel(const int32_t *node, const int32_t *wf, const float *elapsed,
+                                                         const float *best_cost, const float *tail, const float *horizon,
+                                                         int n_nodes, int n_wf, int C, float *ratio, int32_t *status)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < C) ratio[c] = hx_projected_ratio(node, wf, elapsed, tail, horizon, n_nodes, n_wf, c, best_cost[c], status);
+}
+
 __global__ void hx_no_pool_kernel(ScoreArgs a)
 {
     int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -483,4 +491,22 @@ extern "C" int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const flo
     const int grid = C < ctx->num_cu * 8 ? C : ctx->num_cu * 8;
     hx_select_kernel<<<grid, 256, 0, stream>>>(a);
     return hx_check_launch(ctx, "hx_select_kernel");
+}
+
+extern "C" int hx_urgency(hx_ctx *ctx, const hx_calls *calls, const float *best_cost,
+                          const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                          float *ratio, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, calls, HX_ERR_INVALID_ARG, "NULL calls");
+    const int C = calls->n;
+    HX_REQUIRE(ctx, C >= 0 && n_nodes >= 0 && n_wf >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, C == 0 || (calls->node && calls->wf && calls->elapsed && best_cost && tail && horizon && ratio),
+               HX_ERR_INVALID_ARG, "the ratio needs node, wf, elapsed, best_cost, tail and horizon");
+    if (C == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hx_urgency_kernel<<<(C + 255) / 256, 256, 0, (hipStream_t)stream_>>>(calls->node, calls->wf, calls->elapsed, best_cost, tail, horizon,
+                                                                       n_nodes, n_wf, C, ratio, ctx->d_status);
+    return hx_check_launch(ctx, "hx_urgency_kernel");
 }

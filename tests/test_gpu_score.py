@@ -271,3 +271,29 @@ def test_materialised_tensor_ragged_and_select_with_ratio(ctx, C, P, D, T):
     with pytest.raises(binding.HxError) as e:
         ctx.hx_stream_status()
     assert e.value.code == -6
+
+
+def test_urgency_entry_point_equals_the_fused_epilogue(ctx):
+    """Eq. (2) folded in afterwards (hx_urgency) is the ratio hx_score_placements writes, bit for bit."""
+    import torch
+    rnd = synth.make_round("mid", 4)
+    calls, pre, dec, links = dev_tables(rnd)
+    d = rnd.dag
+    cost = o.node_cost(rnd.model, d.L_in, d.L_out, rnd.types, rnd.links)
+    rem, tail, level, hor = o.critical_path(d.succ_row_ptr, d.succ_col, cost, d.wf_ptr)
+    t_tail, t_hor = dev(tail.astype(np.float32)), dev(hor.astype(np.float32))
+    gp, gd, gc, gr = fused(ctx, rnd.model, calls, pre, dec, links, tail=t_tail, horizon=t_hor, want_ratio=True)
+    ratio = torch.full((rnd.calls["n"],), -3.0, device="cuda:0")
+    ctx.hx_urgency(calls, dev(gc), t_tail, t_hor, ratio)
+    ctx.hx_stream_status()
+    assert np.array_equal(ratio.cpu().numpy(), gr)
+    want = o.urgency(rnd.calls["elapsed"], gc.astype(np.float64), rnd.calls["node"], rnd.calls["wf"],
+                     tail.astype(np.float32).astype(np.float64), hor.astype(np.float32).astype(np.float64))
+    assert_costs_close(ratio.cpu().numpy(), want, "ratio")
+    # an index outside the arrays is reported, not followed
+    from paper_2605_16637_amd import binding
+    bad = dict(calls); bad["node"] = dev(np.full(rnd.calls["n"], 10**8, np.int32))
+    ctx.hx_urgency(bad, dev(gc), t_tail, t_hor, ratio)
+    with pytest.raises(binding.HxError) as e:
+        ctx.hx_stream_status()
+    assert e.value.code == -6
