@@ -393,7 +393,9 @@ __global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, cons
             if (a.start) a.start[(size_t)c * a.D + d] = s.S;
             if (a.cost) a.cost[(size_t)c * a.D + d] = s.src >= 0 ? v : INFINITY;
             if (s.src >= 0 && v < INFINITY) {
-                atomicMin(&a.key[c], hx_decode_key(v, d, s.src));      // result unused: nothing waits for it
+                // read first: most candidates do not improve on what other instances have already written
+                const u64 mine = hx_decode_key(v, d, s.src);
+                if (__hip_atomic_load(&a.key[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > mine) atomicMin(&a.key[c], mine);
             }
         }
     }
