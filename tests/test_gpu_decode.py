@@ -211,6 +211,20 @@ def test_decode_score_errors(ctx):
     with pytest.raises(binding.HxError) as e:
         run_score(ctx, r.model, L, O, lock, r.dec, widen(iv, 4, 512 - iv["stride"]))
     assert e.value.code == -2
+    import torch
+    Q = len(L)
+    out = [torch.empty(Q, dtype=torch.int32, device="cuda:0"), torch.empty(Q, device="cuda:0"), torch.empty(Q, device="cuda:0")]
+    with pytest.raises(binding.HxError) as e:                      # no output arrays
+        ctx.hx_decode_score(r.model, dev_queue(L, O), None, dev_dec(r.dec), dev_iv(iv), None, None, None)
+    assert e.value.code == -1
+    with pytest.raises(binding.HxError) as e:                      # a ratio without node, workflow, elapsed, tail, horizon
+        ctx.hx_decode_score(r.model, dev_queue(L, O), None, dev_dec(r.dec), dev_iv(iv), *out, ratio=torch.empty(Q, device="cuda:0"))
+    assert e.value.code == -1
+    big = 1025                                                     # a queue the one-workgroup planner does not take
+    with pytest.raises(binding.HxError) as e:
+        run_plan(ctx, r.model, np.full(big, 100), np.full(big, 10), None, np.zeros(big, np.int32), np.zeros(big, np.int32),
+                 np.zeros(big, np.float32), [0.0], [10.0], r.dec, iv)
+    assert e.value.code == -2
     again = run_score(ctx, r.model, L, O, lock, r.dec, iv)
     assert np.array_equal(again["best_d"], good["best_d"]) and np.array_equal(again["cost"], good["cost"])
 
