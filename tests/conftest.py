@@ -25,3 +25,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_is_built():
+    """The tests load the library that is there; they compile it only when there is none."""
+    from paper_2605_16637_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_16637_amd import build
+        build.build()
