@@ -393,6 +393,9 @@ def main():
 
     import torch
     from paper_2605_16637_amd import binding, synth
+    if not os.path.exists(binding.LIB_PATH):        # loads what is built, compiles only when there is nothing
+        from paper_2605_16637_amd import build
+        build.build()
     ctx = binding.Context(0)
     torch.cuda.set_device(0)
 
