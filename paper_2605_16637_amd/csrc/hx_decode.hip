@@ -169,8 +169,8 @@ struct HxSlot {
 // min(+inf, t_i) = t_i; inside a run t_i > rs leaves rs alone); the run is long enough once the next
 // entry's time reaches rs + T, which cannot happen outside a run (rs + T = +inf, and the entry
 // whose successor is "never" always has room: everything has ended by then).  Run starts only
-// grow along the timeline, so the earliest start is the minimum over all hits.  Four entries per
-// step; the loop ends when every lane has its answer or has passed the end of its timeline.
+// grow along the timeline, so the earliest start is the minimum over all hits.  The loop ends when
+// every lane has its answer or has passed the end of its timeline.
 __device__ __forceinline__ HxSlot hx_earliest_start(const int2 *e, const short *src, int n, int thr, float T, bool active)
 {
     const bool open = active && thr >= 0;
@@ -180,19 +180,25 @@ __device__ __forceinline__ HxSlot hx_earliest_start(const int2 *e, const short *
         rs = (occ_) <= thr ? fminf(rs, __int_as_float(cur_)) : INFINITY;          \
         ans = fminf(ans, __int_as_float(nxt_) >= rs + T ? rs : INFINITY);         \
     }
-    for (int i0 = 0;; i0 += 4) {
+    // eight entries per step, the next eight already on their way (lanes that are through read entry 0 on)
+    const int4 *q = reinterpret_cast<const int4 *>(e);
+    int4 c0 = q[0], c1 = q[1], c2 = q[2], c3 = q[3];
+    for (int i0 = 0;; i0 += 8) {
         const bool going = open && i0 < n && !(ans < INFINITY);
         if (__builtin_amdgcn_ballot_w64(going) == 0) break;
-        const int at = going ? i0 : 0;                     // lanes that are through read a harmless place
-        const int4 a = *reinterpret_cast<const int4 *>(e + at);
-        const int4 b = *reinterpret_cast<const int4 *>(e + at + 2);
-        const int t4 = e[at + 4].x;
-        float keep = ans;
-        HX_TL_STEP(a.x, a.y, a.z)
-        HX_TL_STEP(a.z, a.w, b.x)
-        HX_TL_STEP(b.x, b.y, b.z)
-        HX_TL_STEP(b.z, b.w, t4)
+        const int at = going ? (i0 >> 1) + 4 : 0;
+        const int4 n0 = q[at], n1 = q[at + 1], n2 = q[at + 2], n3 = q[at + 3];
+        const float keep = ans;
+        HX_TL_STEP(c0.x, c0.y, c0.z)
+        HX_TL_STEP(c0.z, c0.w, c1.x)
+        HX_TL_STEP(c1.x, c1.y, c1.z)
+        HX_TL_STEP(c1.z, c1.w, c2.x)
+        HX_TL_STEP(c2.x, c2.y, c2.z)
+        HX_TL_STEP(c2.z, c2.w, c3.x)
+        HX_TL_STEP(c3.x, c3.y, c3.z)
+        HX_TL_STEP(c3.z, c3.w, n0.x)
         ans = going ? ans : keep;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
     }
 #undef HX_TL_STEP
     HxSlot r{INFINITY, -1};
@@ -456,7 +462,9 @@ struct DGreedyArgs {
 struct DGreedyLds {
     int ne, nt, D, Q;      // events per instance, stored timeline length, padded sizes
     __host__ __device__ DGreedyLds(int stride, int D_, int Q_)
-        : ne(2 * stride + 1), nt(hx_tl_len(2 * stride + 1)), D((D_ + 3) & ~3), Q((Q_ + 3) & ~3) {}
+        : ne(2 * stride + 1), nt(hx_tl_len(2 * stride + 1) + 2), D((D_ + 3) & ~3), Q((Q_ + 3) & ~3) {}
+    // + 2: the lanes of a wavefront scan different timelines with 16-byte reads; with a timeline length of
+    // 4k + 2 entries neighbouring timelines start 16 bytes apart modulo the banks instead of on the same ones
     __host__ __device__ size_t off_tl() const { return hx_scratch_bytes(ne); }
     __host__ __device__ size_t off_src() const { return off_tl() + hx_align16((size_t)D * nt * 8); }
     __host__ __device__ size_t off_inst() const { return off_src() + hx_align16((size_t)D * ne * 2); }
