@@ -401,3 +401,45 @@ def test_decode_greedy_hand_worked_and_limits(ctx):
     with pytest.raises(binding.HxError) as e:
         run_plan(ctx, ROUND_MODEL, np.array([100, 100]), np.array([10, 10]), None, [0, 1], [0, 0], [1.0, 1.0], [0.0, 0.0], [10.0], decb, ivb)
     assert e.value.code == -2
+
+
+def test_decode_pass_and_ordering_replayed_from_a_hip_graph(ctx):
+    """After one eager call has sized the library's scratch, the decode pass and the ordering (both paths: all
+    pairs and sample sort) are plain kernel launches: captured in a HIP graph, every replay must equal the eager
+    result, with eager work and synchronisation between the replays."""
+    import torch
+    for name, kw in (("decode_mid", {}), ("decode_mid", dict(Q=20000, n_wf=4000))):
+        r, lock, iv = synth.make_decode_round(name, 3, **kw)
+        L, O = r.calls["L_in"], r.calls["L_out"]
+        Q = len(L)
+        q = dev_queue(L, O, r.calls["node"], r.calls["wf"], r.calls["elapsed"])
+        dd, div, d_lock = dev_dec(r.dec), dev_iv(iv), dev(lock)
+        tail = torch.rand(r.dag.n_nodes, device="cuda:0"); hor = torch.rand(r.dag.n_wf, device="cuda:0") * 20 + 5
+        i32 = dict(dtype=torch.int32, device="cuda:0")
+        bd, rk = torch.empty(Q, **i32), torch.empty(Q, **i32)
+        bs, bc, rt = (torch.empty(Q, device="cuda:0") for _ in range(3))
+        outs = (bd, bs, bc, rt, rk)
+
+        def one():
+            ctx.hx_decode_score(r.model, q, d_lock, dd, div, bd, bs, bc, tail=tail, horizon=hor, ratio=rt)
+            ctx.hx_rank(rt, rk)
+
+        def clear():
+            for t in outs:
+                t.fill_(-1)
+
+        clear(); one(); torch.cuda.synchronize()
+        ctx.hx_stream_status()
+        want = [t.cpu().numpy().copy() for t in outs]
+        order = np.argsort(-want[3].astype(np.float64), kind="stable")
+        assert np.array_equal(want[4][order], np.arange(Q))
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            one()
+        for rep in range(3):
+            clear(); torch.cuda.synchronize()
+            g.replay(); torch.cuda.synchronize()
+            for a, b in zip(outs, want):
+                assert np.array_equal(a.cpu().numpy(), b), f"replay {rep} differs from the eager call"
+            ctx.hx_stream_status()
+            one(); torch.cuda.synchronize()            # eager work between replays
