@@ -319,9 +319,11 @@ def robustness_leg(torch, ctx, synth, binding, seed):
     error into the scheduler-visible prefill and decode estimates): every instance's estimates are scaled by
     1 + e or 1 - e, alternating by instance index (its rates divided by that factor); reported are the
     fraction of calls whose pair changes and the true cost of the changed choice relative to the true best."""
-    rnd = synth.make_round("mid", seed)
-    C, P, D = rnd.calls["n"], rnd.pre["n"], rnd.dec["n"]
-    calls, links = binding.to_device(rnd.calls), binding.to_device(rnd.links)
+    rnd = synth.make_round("large", seed)
+    C, P, D = 2048, rnd.pre["n"], rnd.dec["n"]          # the cost tensor of 2048 calls is 512 MB
+    sub = {k: (v[:C] if isinstance(v, np.ndarray) else v) for k, v in rnd.calls.items()}
+    sub["n"] = C
+    calls, links = binding.to_device(sub), binding.to_device(rnd.links)
     pre, dec = binding.to_device(rnd.pre), binding.to_device(rnd.dec)
     i32 = dict(dtype=torch.int32, device="cuda:0")
     cost = torch.empty(C * P * D, device="cuda:0")
@@ -329,7 +331,7 @@ def robustness_leg(torch, ctx, synth, binding, seed):
     ctx.hx_score_placements(synth.MODEL, calls, pre, dec, links, cost=cost, best_p=bp, best_d=bd, best_cost=bc)
     cost = cost.view(C, P * D)
     ok = bp >= 0
-    out = {"workload": "mid round: %d calls x %d x %d" % (C, P, D)}
+    out = {"workload": "large sweep, first %d calls x %d x %d" % (C, P, D)}
     for err in (0.1, 0.2, 0.3):
         fp = torch.where(torch.arange(P, device="cuda:0") % 2 == 0, 1.0 + err, 1.0 - err)
         fd = torch.where(torch.arange(D, device="cuda:0") % 2 == 0, 1.0 + err, 1.0 - err)

@@ -235,9 +235,9 @@ enum : int { ALIVE = 1, DIRTY = 2 };
 
 // One block plans the whole queue: the pool tables, the simulated state and the
 // per-call results live in LDS, there is no launch between iterations.  A call
-// is scored again only if its current pair touches the instance a commit just
-// changed: additions to the state can only raise costs, so every other call
-// keeps its pair and cost exactly.
+// is scored again only if its current pair touches an instance a commit just
+// changed and the pair's cost moved: additions to the state can only raise costs,
+// so every other call keeps its pair and cost exactly.
 template <int KP>
 __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyArgs a, int dp_bound)
 {
@@ -378,8 +378,13 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         // (4) calls whose pair touches a changed instance are scored again
         const int pp = s_pick[1], pd = s_pick[2];
         if (pp >= 0) {
+            // ... unless the cost of that pair came out the same (e.g. the decode instance's availability still
+            // dominates a longer prefill queue): every other pair costs what it did or more, so the pair is still
+            // the lexicographic minimum
             for (int c = tid; c < a.C; c += GREEDY_THREADS)
-                if ((s_flags[c] & ALIVE) && (s_bp[c] == pp || s_bd[c] == pd)) s_flags[c] = ALIVE | DIRTY;
+                if ((s_flags[c] & ALIVE) && (s_bp[c] == pp || s_bd[c] == pd) &&
+                    hx_pair_cost(a.m, pool, a.L_in[c], a.L_out[c], s_bp[c], s_pos[s_bd[c]]) != s_bc[c])
+                    s_flags[c] = ALIVE | DIRTY;
         }
         __syncthreads();
     }

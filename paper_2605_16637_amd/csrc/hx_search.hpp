@@ -157,6 +157,19 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
     return out;
 }
 
+// Cost of one pair (prefill instance p, decode entry e) for a call, by the same functions in the same
+// order as the search above, hence bit-identical to what the search computes for that pair.
+__device__ __forceinline__ float hx_pair_cost(const HxModelF &m, const HxPoolLds &s, int L, int O, int p, int e)
+{
+    constexpr int kT = HX_MAX_TYPES;
+    const HxCallF cf = hx_call_terms(m, L, O);
+    const float done = hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]);
+    const int k = s.ptype[p] * kT + s.dtype[e];
+    const float x = hx_transfer(cf, s.invbw[k], s.lat[k]);
+    const float dec = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
+    return hx_candidate(done + x, s.wait[e], dec);
+}
+
 // projected ratio of a call, Eq. (2) with the downstream tail of the call's
 // node: (elapsed + best + tail[node]) / horizon[wf].  A node or workflow index
 // outside the arrays gives NaN and raises HX_ERR_INDEX.
