@@ -17,7 +17,7 @@
  *    on, owned by the caller, valid until the work enqueued on `stream` has
  *    finished.  "host" pointers are ordinary host memory read during the
  *    call.  The structs hx_model / hx_calls / hx_prefill_tab / hx_decode_tab /
- *    hx_links themselves live in host memory; their pointer members are
+ *    hx_links / hx_intervals themselves live in host memory; their pointer members are
  *    device pointers.  The library never returns memory the caller must free
  *    (hx_dag_view returns borrowed pointers into the context).
  *  - `stream` is a hipStream_t (NULL = the default stream).  Work is enqueued
@@ -30,7 +30,12 @@
  *    for an infeasible pair.  Rates are FLOP/s and B/s, lengths and
  *    capacities are tokens.
  *  - Calls on one context must not overlap in time on different streams: the
- *    context owns scratch that consecutive calls reuse.
+ *    context owns scratch that consecutive calls reuse.  A context is not
+ *    thread-safe.
+ *  - Device memory is allocated by hx_ctx_create and hx_dag_reserve, and by
+ *    hx_decode_score and hx_rank (beyond 16384 calls) the first time they meet
+ *    a larger problem than before; every other call only launches kernels and
+ *    can be captured in a HIP graph.
  */
 #ifndef HX_H
 #define HX_H
