@@ -210,6 +210,20 @@ int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
                   const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
                   const float *new_cost, const int32_t *new_wf, void *stream);
 
+/*
+ * Replaces the cost of n nodes of the context's graph (Sec. 5.1: when true
+ * service times become available the horizon is corrected by replacing
+ * estimates with observed latencies) and recomputes rem, tail and every
+ * horizon from the new costs -- a cost may have gone down, so nothing is kept
+ * but the levels, which do not depend on costs.  Results equal a full
+ * recomputation, bit for bit.
+ *   node_ids device [n], 0 .. nodes appended so far - 1 (others are skipped,
+ *            HX_ERR_INDEX in the stream status); cost device [n] >= 0.
+ * Work grows with the whole graph, not with n: meant for the occasional
+ * correction, not for every round.
+ */
+int hx_dag_set_cost(hx_ctx *ctx, int32_t n, const int32_t *node_ids, const float *cost, void *stream);
+
 /* Borrowed device pointers into the context's graph (valid until the next
  * hx_dag_reserve or hx_ctx_destroy) and the number of nodes appended so far.
  * Any out pointer may be NULL. */

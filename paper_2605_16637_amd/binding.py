@@ -17,7 +17,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
           -5: "HX_ERR_DEVICE", -6: "HX_ERR_INDEX", -7: "HX_ERR_OVERFLOW"}
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
-           "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_view",
+           "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_set_cost", "hx_dag_view",
            "hx_score_placements", "hx_select", "hx_urgency", "hx_commit", "hx_rank", "hx_plan_greedy",
            "hx_decode_score", "hx_decode_plan_greedy")
 
@@ -225,6 +225,11 @@ class Context:
         self._check(self.lib.hx_dag_append(self._ctx, n_new, n_e, _ptr(parent_row_ptr, torch.int32, n_new + 1),
                                            _ptr(parent_col_idx, torch.int32), _ptr(new_cost, torch.float32),
                                            _ptr(new_wf, torch.int32, n_new), _stream(stream)))
+
+    def hx_dag_set_cost(self, node_ids, cost, stream=None):
+        torch = _torch()
+        n = int(node_ids.numel())
+        self._check(self.lib.hx_dag_set_cost(self._ctx, n, _ptr(node_ids, torch.int32), _ptr(cost, torch.float32, n), _stream(stream)))
 
     def hx_dag_view(self, n_wf: int):
         """(rem, tail, level, horizon) of the context's graph as borrowed RawArray

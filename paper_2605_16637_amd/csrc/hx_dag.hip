@@ -508,6 +508,26 @@ __global__ __launch_bounds__(1024) void hx_append_tail_kernel(AppendArgs a, int3
     }
 }
 
+// cost of existing nodes replaced by observed values (an id outside the graph is skipped and reported)
+__global__ __launch_bounds__(256) void hx_set_cost_kernel(int n, const int32_t *ids, const float *value, float *cost, int n_nodes,
+                                                          int32_t *status)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int v = ids[i];
+    if (v < 0 || v >= n_nodes) { hx_raise(status, HX_ERR_INDEX); return; }
+    cost[v] = value[i];
+}
+
+// everything the costs determine back to its starting point: rem = cost, no tail, no horizon
+__global__ __launch_bounds__(256) void hx_refresh_reset_kernel(AppendArgs a, int n_wf)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.n_new) { a.rem[i] = a.cost[i]; a.tail[i] = 0.0f; }
+    if (i < n_wf) a.horizon[i] = 0.0f;
+    if (i < 3) a.counters[i] = 0;
+}
+
 __global__ __launch_bounds__(256) void hx_fill_i32_kernel(int32_t *p, size_t n, int32_t v)
 {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
@@ -676,6 +696,43 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
     g.n_nodes += n_new;
     g.n_edges += n_new_edges;
     return HX_OK;
+}
+
+extern "C" int hx_dag_set_cost(hx_ctx *ctx, int32_t n, const int32_t *node_ids, const float *cost, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HxDagStore &g = ctx->dag;
+    HX_REQUIRE(ctx, g.cost, HX_ERR_INVALID_ARG, "hx_dag_reserve has not been called");
+    HX_REQUIRE(ctx, n >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, n == 0 || (node_ids && cost), HX_ERR_INVALID_ARG, "NULL array");
+    if (n == 0 || g.n_nodes == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    hx_set_cost_kernel<<<(n + 255) / 256, 256, 0, stream>>>(n, node_ids, cost, g.cost, g.n_nodes, ctx->d_status);
+    // a cost may have gone down, so nothing can be kept: every node starts again from rem = cost and walks up
+    // (levels do not depend on costs and stay)
+    AppendArgs a{};
+    a.n_old = 0; a.n_new = g.n_nodes; a.cap_wf = g.cap_wf;
+    a.cost = g.cost; a.rem = g.rem; a.tail = g.tail; a.horizon = g.horizon;
+    a.level = g.level; a.wf = g.wf; a.prow = g.parent_row_ptr; a.pcol = g.parent_col; a.mark = g.mark;
+    a.counters = g.counters; a.status = ctx->d_status;
+    a.cin = 0; a.cout = 1; a.czero = 2; a.epoch = ++g.epoch;
+    a.list_in = g.list[1]; a.list_out = g.list[0];
+    const int m = g.n_nodes > g.cap_wf ? g.n_nodes : g.cap_wf;
+    hx_refresh_reset_kernel<<<(m + 255) / 256, 256, 0, stream>>>(a, g.cap_wf);
+    int grid = (g.n_nodes + 255) / 256;
+    grid = grid > ctx->num_cu * 8 ? ctx->num_cu * 8 : grid;
+    hx_append_relax_kernel<<<grid, 256, 0, stream>>>(a);
+    if (g.max_depth > 0) {
+        a.epoch = g.epoch;
+        hx_append_tail_kernel<<<1, 1024, 0, stream>>>(a, g.list[0], g.list[1], 0, g.max_depth);
+        g.epoch += (uint32_t)g.max_depth;
+    } else {
+        a.cin = 1;
+        hx_append_finish_kernel<<<1, 64, 0, stream>>>(a);
+    }
+    return hx_check_launch(ctx, "hx_dag_set_cost kernels");
 }
 
 extern "C" int hx_dag_view(hx_ctx *ctx, const float **rem, const float **tail, const int32_t **level,

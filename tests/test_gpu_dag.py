@@ -183,6 +183,46 @@ def test_incremental_append_equals_full_recompute(ctx, seed, n_live, rounds):
     assert want[2].max() >= 3
 
 
+def test_observed_costs_replace_estimates(ctx):
+    """Sec. 5.1: estimates are replaced by observed latencies when they become known.  Costs of existing nodes
+    go up and down; rem, tail and horizons must equal a full recomputation, and appending goes on from there."""
+    gen = synth.StreamGen(9, 300, final_lo=5, final_hi=25)
+    rng = np.random.default_rng(9)
+    ctx.hx_dag_reserve(100000, 150000, 20000, 32)
+    prow = np.zeros(1, np.int32); pcol = np.zeros(0, np.int32)
+    cost_all = np.zeros(0, np.float32); wf_all = np.zeros(0, np.int32)
+
+    def check(n_wf):
+        want = o.critical_path_by_parents(prow, pcol, cost_all.astype(np.float64), wf_all, n_wf, round_f32=True)
+        got = view(ctx, cost_all.size, n_wf)
+        assert np.array_equal(got[2], want[2])
+        for k in (0, 1, 3):
+            assert np.array_equal(got[k].astype(np.float64), want[k]), k
+        return want
+
+    for r in range(8):
+        b = gen.next_batch()
+        c32 = rng.uniform(0.2, 4.0, b["n_new"]).astype(np.float32)
+        ctx.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), dev(c32), dev(b["wf"]))
+        prow = np.concatenate([prow, prow[-1] + b["parent_row_ptr"][1:]]).astype(np.int32)
+        pcol = np.concatenate([pcol, b["parent_col"]]); cost_all = np.concatenate([cost_all, c32]); wf_all = np.concatenate([wf_all, b["wf"]])
+        n_wf = b["n_wf_total"]
+        if r in (3, 5, 7):
+            before = check(n_wf)
+            ids = rng.choice(cost_all.size, max(1, cost_all.size // 10), replace=False).astype(np.int32)
+            new = (cost_all[ids] * rng.choice([0.0, 0.3, 1.0, 2.5], ids.size)).astype(np.float32)     # down, same, up
+            ctx.hx_dag_set_cost(dev(ids), dev(new))
+            ctx.hx_stream_status()
+            cost_all[ids] = new
+            after = check(n_wf)
+            assert (after[3] < before[3]).any() and (after[3] > before[3]).any()       # horizons moved both ways
+    from paper_2605_16637_amd import binding
+    ctx.hx_dag_set_cost(dev(np.array([0, 10**7], np.int32)), dev(np.array([1.0, 1.0], np.float32)))
+    with pytest.raises(binding.HxError) as e:
+        ctx.hx_stream_status()
+    assert e.value.code == -6
+
+
 def test_append_errors(ctx):
     from paper_2605_16637_amd import binding
     ctx.hx_dag_reserve(8, 8, 2, 4)
