@@ -235,57 +235,123 @@ __global__ __launch_bounds__(256) void hx_materialise_kernel(ScoreArgs a)
 {
     extern __shared__ __align__(16) float smem[];
     const HxPrepTables *__restrict__ t = a.prep;
-    float *s_done = smem;                       // [P]
-    float *s_dec = s_done + a.P;                // [D]
-    float *s_wait = s_dec + a.D;                // [D]
-    int *s_ptype = (int *)(s_wait + a.D);       // [P]
-    int *s_dtype = s_ptype + a.P;               // [D]
-    float *s_x = (float *)(s_dtype + a.D);      // [kT*kT]
+    const int P4 = (a.P + 3) & ~3, D4 = (a.D + 3) & ~3;      // every array starts on a 16-byte boundary
+    float *s_done = smem;                       // [P]  per call
+    float *s_dec = s_done + P4;                 // [D]  per call
+    float *s_wait = s_dec + D4;                 // [D]
+    int *s_ptype = (int *)(s_wait + D4);        // [P]
+    int *s_dtype = s_ptype + P4;                // [D]
+    float *s_x = (float *)(s_dtype + D4);       // [kT*kT] per call
+    // what does not depend on the call, staged once per workgroup
+    float *s_pw = s_x + kT * kT;                // [P] prefill wait, 1/F, 1/B
+    float *s_pF = s_pw + P4;
+    float *s_pB = s_pF + P4;
+    float *s_c1 = s_pB + P4;                    // [D] decode per-token terms and free tokens, by instance
+    float *s_c2 = s_c1 + D4;
+    float *s_kB = s_c2 + D4;
+    int *s_free = (int *)(s_kB + D4);
+    float *s_lbw = (float *)(s_free + D4);      // [kT*kT] link tables
+    float *s_llat = s_lbw + kT * kT;
     const int tid = threadIdx.x;
+    // rows of the tensor are 16-byte aligned and a whole number of quads long
+    const bool vec4 = (a.D & 3) == 0 && a.D >= 4 && (reinterpret_cast<uintptr_t>(a.cost) & 15) == 0;
+    for (int p = tid; p < a.P; p += blockDim.x) {
+        s_pw[p] = t->pre_wait[p]; s_pF[p] = t->pre_invF[p]; s_pB[p] = t->pre_invB[p]; s_ptype[p] = t->pre_type[p];
+    }
+    for (int d = tid; d < a.D; d += blockDim.x) {
+        const int e = t->dec_pos[d];
+        s_c1[d] = t->dec_c1[e]; s_c2[d] = t->dec_c2[e]; s_kB[d] = t->dec_kB[e]; s_free[d] = t->dec_free[e];
+        s_wait[d] = t->dec_wait[e]; s_dtype[d] = t->dec_type[e];
+    }
+    if (tid < kT * kT) { s_lbw[tid] = t->link_invbw[tid]; s_llat[tid] = t->link_lat[tid]; }
     for (int c = blockIdx.x; c < a.C; c += gridDim.x) {
         const int L = a.L_in[c], O = a.L_out[c];
         const HxCallF cf = hx_call_terms(a.m, L, O);
         __syncthreads();
-        for (int p = tid; p < a.P; p += blockDim.x) {
-            s_done[p] = hx_prefill_done(cf, t->pre_wait[p], t->pre_invF[p], t->pre_invB[p]);
-            s_ptype[p] = t->pre_type[p];
-        }
+        for (int p = tid; p < a.P; p += blockDim.x) s_done[p] = hx_prefill_done(cf, s_pw[p], s_pF[p], s_pB[p]);
         for (int d = tid; d < a.D; d += blockDim.x) {
-            int e = t->dec_pos[d];
-            bool fits = hx_fits(L, O, t->dec_free[e]);
-            s_dec[d] = fits ? hx_decode_time(cf, t->dec_c1[e], t->dec_c2[e], t->dec_kB[e]) : INFINITY;
-            s_wait[d] = t->dec_wait[e];
-            s_dtype[d] = t->dec_type[e];
+            const bool fits = hx_fits(L, O, s_free[d]);
+            s_dec[d] = fits ? hx_decode_time(cf, s_c1[d], s_c2[d], s_kB[d]) : INFINITY;
             if (a.feas) a.feas[(size_t)c * a.D + d] = fits ? 1 : 0;
         }
-        if (tid < kT * kT) s_x[tid] = hx_transfer(cf, t->link_invbw[tid], t->link_lat[tid]);
+        if (tid < kT * kT) s_x[tid] = hx_transfer(cf, s_lbw[tid], s_llat[tid]);
         __syncthreads();
         if (a.cost) {
             float *out = a.cost + (size_t)c * a.P * a.D;
-            const int n = a.P * a.D;
-            for (int i = tid; i < n; i += blockDim.x) {
-                int p = i / a.D, d = i - p * a.D;
-                out[i] = hx_candidate(s_done[p] + s_x[s_ptype[p] * kT + s_dtype[d]], s_wait[d], s_dec[d]);
+            // (p, d) of the elements a thread writes advance without a division: by blockDim positions at a time
+            if (vec4) {
+                // four neighbouring decode instances per step, one 16-byte store
+                const int dq = a.D >> 2;
+                const int step_p = blockDim.x / dq, step_q = blockDim.x % dq;
+                int p = tid / dq, q = tid - p * dq;
+                for (; p < a.P; p += step_p) {
+                    const float done = s_done[p];
+                    const float *xr = s_x + s_ptype[p] * kT;
+                    const float4 w = reinterpret_cast<const float4 *>(s_wait)[q];
+                    const float4 t = reinterpret_cast<const float4 *>(s_dec)[q];
+                    const int4 k = reinterpret_cast<const int4 *>(s_dtype)[q];
+                    float4 v;
+                    v.x = hx_candidate(done + xr[k.x], w.x, t.x);
+                    v.y = hx_candidate(done + xr[k.y], w.y, t.y);
+                    v.z = hx_candidate(done + xr[k.z], w.z, t.z);
+                    v.w = hx_candidate(done + xr[k.w], w.w, t.w);
+                    reinterpret_cast<float4 *>(out + (size_t)p * a.D)[q] = v;
+                    q += step_q;
+                    if (q >= dq) { q -= dq; ++p; }
+                }
+            } else {
+                const int step_p = blockDim.x / a.D, step_d = blockDim.x % a.D;
+                int p = tid / a.D, d = tid - p * a.D;
+                for (; p < a.P; p += step_p) {
+                    out[(size_t)p * a.D + d] = hx_candidate(s_done[p] + s_x[s_ptype[p] * kT + s_dtype[d]], s_wait[d], s_dec[d]);
+                    d += step_d;
+                    if (d >= a.D) { d -= a.D; ++p; }
+                }
             }
         }
     }
 }
-
-// ---- select over a materialised tensor -------------------------------------------------
-
 __global__ __launch_bounds__(256) void hx_select_kernel(ScoreArgs a)
 {
     __shared__ float s_v[4];
     __shared__ int s_i[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = a.P * a.D;
+    const bool vec4 = (n & 3) == 0 && (reinterpret_cast<uintptr_t>(a.cost) & 15) == 0;
     for (int c = blockIdx.x; c < a.C; c += gridDim.x) {
         const float *row = a.cost + (size_t)c * n;
         float bv = INFINITY;
         int bi = 0x7fffffff;
-        for (int i = tid; i < n; i += blockDim.x) {     // i grows: "<" keeps the lowest index of this thread
-            float v = row[i];
-            if (v < bv) { bv = v; bi = i; }
+        if (vec4) {
+            // 16-byte loads, two in flight per thread; indices grow within a quad and from quad to quad
+            const float4 *row4 = reinterpret_cast<const float4 *>(row);
+            const int n4 = n >> 2;
+            int i4 = tid;
+            for (; i4 + (int)blockDim.x < n4; i4 += 2 * blockDim.x) {
+                const float4 x = row4[i4], y = row4[i4 + blockDim.x];
+                const int i = i4 << 2, j = (i4 + blockDim.x) << 2;
+                if (x.x < bv) { bv = x.x; bi = i; }
+                if (x.y < bv) { bv = x.y; bi = i + 1; }
+                if (x.z < bv) { bv = x.z; bi = i + 2; }
+                if (x.w < bv) { bv = x.w; bi = i + 3; }
+                if (y.x < bv) { bv = y.x; bi = j; }
+                if (y.y < bv) { bv = y.y; bi = j + 1; }
+                if (y.z < bv) { bv = y.z; bi = j + 2; }
+                if (y.w < bv) { bv = y.w; bi = j + 3; }
+            }
+            if (i4 < n4) {
+                const float4 x = row4[i4];
+                const int i = i4 << 2;
+                if (x.x < bv) { bv = x.x; bi = i; }
+                if (x.y < bv) { bv = x.y; bi = i + 1; }
+                if (x.z < bv) { bv = x.z; bi = i + 2; }
+                if (x.w < bv) { bv = x.w; bi = i + 3; }
+            }
+        } else {
+            for (int i = tid; i < n; i += blockDim.x) {     // i grows: "<" keeps the lowest index of this thread
+                float v = row[i];
+                if (v < bv) { bv = v; bi = i; }
+            }
         }
 #pragma unroll
         for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
@@ -459,7 +525,7 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         if (int rc = hx_check_launch(ctx, "hx_fused_search_kernel")) return rc;
     }
     if (cost || feas) {
-        const size_t lds = 4 * ((size_t)2 * P + 3 * D + kT * kT);
+        const size_t lds = 4 * ((size_t)5 * ((P + 3) & ~3) + 7 * ((D + 3) & ~3) + 3 * kT * kT);
         const int grid = C < ctx->num_cu * 8 ? C : ctx->num_cu * 8;
         hx_materialise_kernel<<<grid, 256, lds, stream>>>(a);
         if (int rc = hx_check_launch(ctx, "hx_materialise_kernel")) return rc;
