@@ -56,3 +56,14 @@ def test_struct_layouts_match_the_header(tmp_path):
         for field, _ in cls._fields_:
             want.append(f"{name} {field} {getattr(cls, field).offset}")
     assert [g for g in got if g] == want
+
+
+def test_every_entry_point_rejects_a_null_context():
+    """Each call checks its context before anything else (no GPU needed: nothing is launched)."""
+    lib = binding.load()
+    for name in binding.EXPORTS:
+        if name in ("hx_ctx_create", "hx_last_error"):
+            continue
+        fn = getattr(lib, name)
+        # more NULL/zero arguments than any entry point takes; surplus ones are ignored by the C calling convention
+        assert fn(*([None] * 24)) == -1, name
