@@ -23,7 +23,11 @@ import numpy as np
 ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # VALU issue slots the search needs per candidate: max, add, half a 3-input min
 OPS_PER_CANDIDATE = 2.5
-DECODE_OPS_PER_STEP = 7.0    # vector ops per (call, instance, timeline entry) of the decode-stage scan
+# Vector ops of the decode-stage search for one (call, instance) pair.  A free call goes through the instance's
+# first-room table: 6 per step of the bisection for its threshold's rank, 8 per stretch of the timeline, 24 for
+# the call's decode time, threshold and the comparison with its best so far.  A locked call scans its one
+# instance's timeline entry by entry, 7 per entry.
+DECODE_OPS_BISECT_STEP, DECODE_OPS_STRETCH, DECODE_OPS_PAIR, DECODE_OPS_ENTRY = 6.0, 8.0, 24.0, 7.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/
 # (counter x calibration factor of a plain copy); valid for the default workloads only, and to be
@@ -267,22 +271,35 @@ def decode_leg(torch, ctx, synth, binding, seed):
     score_s = time_launches(torch, lambda: ctx.hx_decode_score(synth.MODEL, q, d_lock, dd, div, bd, bs, bc, tail=tail, horizon=hor, ratio=rt), 30)
     both_s = time_launches(torch, one_pass, 30)
     ctx.hx_stream_status()
-    legal = int((lock < 0).sum()) * D + int((lock >= 0).sum())
-    # timeline entries per instance = distinct event times from now on (the past folds onto now)
+    n_free, locked_on = int((lock < 0).sum()), np.bincount(lock[lock >= 0], minlength=D)
+    legal = n_free * D + int((lock >= 0).sum())
+    # per instance: timeline entries = distinct event times from now on (the past folds onto now), and
+    # stretches = 1 + the entries where occupancy rises
     K = iv["stride"]
-    n_tl = np.array([np.unique(np.maximum(np.concatenate([[0.0], iv["start"][d * K:d * K + iv["count"][d]],
-                                                          iv["end"][d * K:d * K + iv["count"][d]]]), 0.0)).size for d in range(D)])
-    per_inst = np.bincount(lock[lock >= 0], minlength=D) + int((lock < 0).sum())
-    steps = float((per_inst * n_tl).sum())                  # (legal pair, timeline entry) steps
-    ops = DECODE_OPS_PER_STEP * steps
+    n_tl, m_tl = np.zeros(D, np.int64), np.zeros(D, np.int64)
+    for d in range(D):
+        k = int(iv["count"][d])
+        st = np.maximum(iv["start"][d * K:d * K + k].astype(np.float64), 0.0)
+        en = np.maximum(iv["end"][d * K:d * K + k].astype(np.float64), 0.0)
+        tk = iv["tok"][d * K:d * K + k].astype(np.int64)
+        t = np.unique(np.concatenate([[0.0], st, en]))
+        occ = np.array([tk[(st <= x) & (x < en)].sum() for x in t])
+        n_tl[d], m_tl[d] = t.size, 1 + int((occ[1:] > occ[:-1]).sum())
+    table = (n_tl <= 512) & (m_tl * (n_tl + 1) <= 4096)
+    per_free = np.where(table, DECODE_OPS_BISECT_STEP * np.ceil(np.log2(n_tl + 1)) + DECODE_OPS_STRETCH * m_tl, DECODE_OPS_ENTRY * n_tl) \
+        + DECODE_OPS_PAIR
+    ops = float(n_free * per_free.sum() + (locked_on * (DECODE_OPS_ENTRY * n_tl + DECODE_OPS_PAIR)).sum())
     out["one pass"] = {"workload": "%d calls x %d instances, %d..%d intervals each, %d%% of the calls locked"
                                    % (Q, D, int(iv["count"].min()), int(iv["count"].max()), round(100 * float((lock >= 0).mean()))),
                        "score_us": score_s * 1e6, "score_and_rank_us": both_s * 1e6,
                        "legal_pairs": legal, "legal_pairs_per_s": legal / score_s,
-                       "timeline_entries_mean": float(n_tl.mean()),
-                       "roofline": {"kernel": "hx_decode_score_kernel (+ timeline and finish launches)", "bound": "alu",
-                                    "ops_per_pair_and_entry": DECODE_OPS_PER_STEP, "achieved": ops / score_s / 1e12,
-                                    "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s", "frac": ops / score_s / 1e12 / ALU_PEAK_TOPS},
+                       "timeline_entries_mean": float(n_tl.mean()), "stretches_mean": float(m_tl.mean()),
+                       "instances_searched_by_table": int(table.sum()),
+                       "roofline": {"kernel": "hx_decode_timeline_kernel + hx_decode_score_kernel + hx_decode_finish_kernel", "bound": "alu",
+                                    "ops_per_free_pair_mean": float(per_free.mean()), "achieved": ops / score_s / 1e12,
+                                    "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s", "frac": ops / score_s / 1e12 / ALU_PEAK_TOPS,
+                                    "entry_by_entry_equivalent_frac": DECODE_OPS_ENTRY * float(((n_free + locked_on) * n_tl).sum())
+                                                                      / score_s / 1e12 / ALU_PEAK_TOPS},
                        "waiting_fraction_of_placed": float(((bs > 0) & (bd >= 0)).float().sum().item() / max(1, int((bd >= 0).sum().item())))}
     rng = np.random.default_rng(seed)
     for name, Qg, Dg, T, res, plan in (("queue 64 x 8 instances, 3 classes", 64, 8, 4, 24, 4), ("queue 256 x 32 instances, 4 classes", 256, 32, 4, 24, 4)):

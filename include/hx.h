@@ -391,10 +391,13 @@ typedef struct {
  * (Eq. 2 at the decode stage; needs the node/wf/elapsed members of `queue`,
  * tail and horizon).  start, cost: device [Q*D] row-major or NULL, every pair
  * (+inf for an instance the lock excludes).  decode->qd_tok and decode->type are
- * not read.  The library keeps scratch for this call (8 bytes per call, and the
- * sorted timeline of every instance, about 20 bytes per interval); a call with
- * a larger Q or D * stride than any before it allocates, after waiting for the
- * device, and is then not capturable in a graph.
+ * not read.  The library keeps scratch for this call: per instance its sorted
+ * timeline and what is derived from it (about 60 bytes per interval, and a
+ * 16 KiB search table), per call a place in the list of free calls and the
+ * best candidate within each of up to 64 groups of instances (12 bytes per
+ * group).  A call with a larger Q, D or D * stride than any before it
+ * allocates, after waiting for the device, and is then not capturable in a
+ * graph.  The selection uses no atomics: results do not depend on timing.
  */
 int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_calls *queue, const int32_t *lock,
                     const hx_decode_tab *decode, const hx_intervals *intervals,

@@ -58,12 +58,14 @@ struct hx_ctx {
     HxPrepTables *d_prep = nullptr;
     int32_t *d_flags = nullptr;        // sweep "changed" flags, [HX_MAX_SWEEP_FLAGS]
     unsigned long long *d_acc = nullptr;   // commit accumulators, [3 * HX_MAX_INSTANCES]
-    unsigned long long *d_dkey = nullptr;  // decode-stage selection keys, [dkey_cap]
-    int32_t dkey_cap = 0;
+    int32_t *d_dpart = nullptr;            // decode-stage free list and per-group partial results, dpart_cap words
+    size_t dpart_cap = 0;
     unsigned long long *d_rkey = nullptr;  // sorted tiles of ordering keys, [rkey_cap]
     size_t rkey_cap = 0;
     void *d_dtl = nullptr;                 // decode-stage timelines (entries, lengths, sources), dtl_cap entries
     size_t dtl_cap = 0;
+    float *d_dtab = nullptr;               // decode-stage first-room tables, dtab_cap instances
+    int dtab_cap = 0;
     int num_cu = 256;
     HxDagStore dag;
 };

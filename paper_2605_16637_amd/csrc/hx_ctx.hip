@@ -172,8 +172,9 @@ extern "C" int hx_ctx_destroy(hx_ctx *ctx)
     if (ctx->d_prep) (void)hipFree(ctx->d_prep);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->d_acc) (void)hipFree(ctx->d_acc);
-    if (ctx->d_dkey) (void)hipFree(ctx->d_dkey);
+    if (ctx->d_dpart) (void)hipFree(ctx->d_dpart);
     if (ctx->d_dtl) (void)hipFree(ctx->d_dtl);
+    if (ctx->d_dtab) (void)hipFree(ctx->d_dtab);
     if (ctx->d_rkey) (void)hipFree(ctx->d_rkey);
     delete ctx;
     return HX_OK;

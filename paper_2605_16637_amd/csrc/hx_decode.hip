@@ -227,7 +227,14 @@ struct DecodeArgs {
     const float *iv_start, *iv_end;
     const int32_t *iv_tok;
     float *start, *cost;
-    u64 *key;
+    // The free calls (valid, not locked) of the queue in queue order: the queue is cut into D slices of `per`
+    // calls, slice d's free calls are free_c[d*per ..], n_free[d] of them.  Unused when there are no locks.
+    int32_t *free_c, *n_free;
+    int per;
+    // Best candidate of every call within each group of gd consecutive instances: [group][Q] each.
+    int gd, n_groups;
+    float *part_cost, *part_start;
+    int32_t *part_d;
     int32_t *status;
 };
 
@@ -252,24 +259,27 @@ __device__ __forceinline__ HxDecodeCand hx_decode_candidate(const HxModelF &m, i
     return c;
 }
 
-// selection key: lexicographic minimum of (cost, instance); the start rides along as the interval it is the end of
-__device__ __forceinline__ u64 hx_decode_key(float cost, int d, int src)
-{
-    return ((u64)__float_as_uint(cost) << 32) | ((u64)(unsigned)d << 16) | (unsigned)src;
-}
+// How the scoring kernel searches an instance's timeline, decided here per instance.
+constexpr int HX_TAB = 4096;          // entries of the first-room table at most
+constexpr int HX_TAB_MAX_N = 512;     // timeline entries at most for the table (their occupancies are ranked all against all)
+constexpr int HX_TAB_FLAG = 1 << 16;  // in tl_m: the table was written
 
-__global__ __launch_bounds__(256) void hx_decode_key_init_kernel(u64 *key, int Q)
-{
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < Q) key[c] = ~0ull;
-}
+struct TlOut {
+    int2 *e;         // [D][nt] timeline entries, padded
+    short *src;      // [D][ne]
+    int *n;          // [D] entries
+    int *seg;        // [D][nt] heads of the stretches, then n
+    int *m;          // [D] stretches, HX_TAB_FLAG added when the arrays below were written
+    int2 *head;      // [D][nt] per stretch: (time of its head, rank of the head's occupancy), padded with (-inf, 0)
+    int *sorted;     // [D][nt] the n occupancies in increasing order
+    float *G;        // [D][HX_TAB] first-room table
+    int *meta;       // [D][8] what the scoring kernel reads first of an instance: n, m (+flag), capacity, used, batch, flops, hbm
+};
 
-// Workgroup d: the timeline of instance d, built in LDS and written to the library's scratch
-// (nt entries per instance, padded); the workgroups also set the selection keys to "nothing yet".
-__global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, int2 *tl_e, short *tl_src, int *tl_n, int nt)
+__global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, TlOut o, int nt)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ int s_n;
+    __shared__ int s_n, s_m;
     const int tid = threadIdx.x;
     const int d = blockIdx.x;
     const int ne = 2 * a.stride + 1;
@@ -282,14 +292,127 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, i
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
         cnt = cnt < 0 ? 0 : a.stride;
     }
+    // this workgroup's slice of the queue (see below): its first calls are asked for now and used after the build
+    const int c_lo = d * a.per, c_hi = min(a.Q, (d + 1) * a.per);
+    const bool pre_in = a.lock && c_lo + tid < c_hi;
+    const int pre_L = pre_in ? a.L_in[c_lo + tid] : 0, pre_O = pre_in ? a.L_out[c_lo + tid] : 0;
+    const int pre_lk = pre_in ? a.lock[c_lo + tid] : -1;
     const size_t at = (size_t)d * a.stride;
     hx_build_timeline<false>(cnt, a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n, a.status);
     const int n = s_n;
-    for (int i = tid; i < hx_tl_len(2 * cnt + 1); i += blockDim.x) tl_e[(size_t)d * nt + i] = tl.e[i];
-    for (int i = tid; i < n; i += blockDim.x) tl_src[(size_t)d * ne + i] = tl.src[i];
-    if (tid == 0) tl_n[d] = n;
-    const int per = (a.Q + a.D - 1) / a.D;
-    for (int c = d * per + tid; c < min(a.Q, (d + 1) * per); c += blockDim.x) a.key[c] = ~0ull;
+    // Everything below is worked out in LDS and registers first and written to memory at the very end: a
+    // barrier waits for the stores before it, and there are several barriers to come.
+
+    // This workgroup's slice of the queue: its free calls, in order.  A thread keeps the place of its call of
+    // the first 256 (few slices are longer) and writes it with the rest.
+    int my_place = -1, n_free = 0;
+    if (a.lock) {
+        __shared__ int s_wave_n[4];
+        const int lane = tid & (HX_WAVE - 1), wave = tid >> 6;
+        for (int base = c_lo; base < c_hi; base += blockDim.x) {
+            const int c = base + tid;
+            const bool in = c < c_hi;
+            const bool first = base == c_lo;
+            const int L = first ? pre_L : (in ? a.L_in[c] : 0), O = first ? pre_O : (in ? a.L_out[c] : 0);
+            const int lk = first ? pre_lk : (in ? a.lock[c] : -1);
+            const bool ok = L >= 0 && O >= 0 && lk >= -1 && lk < a.D;
+            if (!ok) hx_raise(a.status, HX_ERR_INDEX);
+            const bool is_free = in && ok && lk < 0;
+            const u64 mf = __builtin_amdgcn_ballot_w64(is_free);
+            if (lane == 0) s_wave_n[wave] = __popcll(mf);
+            __syncthreads();
+            int before = n_free;
+            for (int w2 = 0; w2 < wave; ++w2) before += s_wave_n[w2];
+            const int place = before + __popcll(mf & ((1ull << lane) - 1ull));
+            if (is_free) {
+                if (first) my_place = place;
+                else a.free_c[d * a.per + place] = c;
+            }
+            n_free += s_wave_n[0] + s_wave_n[1] + s_wave_n[2] + s_wave_n[3];
+            __syncthreads();
+        }
+    }
+
+    // Occupancy rises only where a planned interval starts; between two such entries it never rises.  The
+    // heads of these stretches (entry 0 and every entry above its predecessor), in order, and n as the last one.
+    // The builder's scratch is free again: seg_l, rank and sorted live there.
+    short *seg_l = (short *)w.ds;
+    if (tid < HX_WAVE) {
+        const int per_lane = (n + HX_WAVE - 1) / HX_WAVE;
+        const int lo = min(tid * per_lane, n), hi = min(lo + per_lane, n);
+        int heads = 0;
+        for (int i = lo; i < hi; ++i) heads += i == 0 || tl.e[i].y > tl.e[i - 1].y;
+        int incl = heads;
+#pragma unroll
+        for (int off = 1; off < HX_WAVE; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (tid >= off) incl += up;
+        }
+        int pos = incl - heads;
+        for (int i = lo; i < hi; ++i)
+            if (i == 0 || tl.e[i].y > tl.e[i - 1].y) seg_l[pos++] = (short)i;
+        if (tid == HX_WAVE - 1) { seg_l[incl] = (short)n; s_m = incl; }
+    }
+    // (occupancy, entry) as one key, for the ranks below
+    for (int i = tid; i < n; i += blockDim.x) w.key[i] = ((u64)(unsigned)tl.e[i].y << 16) | (unsigned)i;
+    __syncthreads();
+    const int m = s_m;
+    // Few stretches over a timeline of moderate length: the table below fits and the scoring kernel uses it.
+    const bool table = n <= HX_TAB_MAX_N && m * (n + 1) <= HX_TAB;
+    // Whether an entry leaves room for a call depends only on how the call's threshold ranks among the n
+    // occupancies: with r = the number of occupancies <= threshold, entry i has room exactly when
+    // rank_i = #{j : occ_j <= occ_i} is <= r.  The keys below an entry's own give its place in increasing
+    // order, the keys below (occupancy + 1, 0) its rank.
+    int *rank = w.delta, *sorted = (int *)w.ts;
+    if (table) {
+        for (int i = tid; i < n; i += blockDim.x) {
+            const u64 mine = w.key[i], above = ((mine >> 16) + 1) << 16;
+            int place = 0, le = 0;
+            int j = 0;
+            for (; j + 8 <= n; j += 8) {                   // eight independent reads in flight
+                u64 other[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) other[u] = w.key[j + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { place += other[u] < mine; le += other[u] < above; }
+            }
+            for (; j < n; ++j) { const u64 other = w.key[j]; place += other < mine; le += other < above; }
+            rank[i] = le;
+            sorted[place] = (int)(mine >> 16);
+        }
+        __syncthreads();
+    }
+
+    // ---- the last barrier is behind: everything goes to memory
+    for (int i = tid; i < hx_tl_len(2 * cnt + 1); i += blockDim.x) o.e[(size_t)d * nt + i] = tl.e[i];
+    for (int i = tid; i < n; i += blockDim.x) o.src[(size_t)d * ne + i] = tl.src[i];
+    for (int k = tid; k <= m; k += blockDim.x) o.seg[(size_t)d * nt + k] = (int)seg_l[k];
+    if (my_place >= 0) a.free_c[d * a.per + my_place] = c_lo + tid;
+    if (tid == 0) {
+        o.n[d] = n;
+        o.m[d] = table ? (m | HX_TAB_FLAG) : m;
+        if (a.lock) a.n_free[d] = n_free;
+        int *meta = o.meta + 8 * d;
+        meta[0] = n; meta[1] = table ? (m | HX_TAB_FLAG) : m; meta[2] = a.d_cap[d]; meta[3] = a.d_used[d]; meta[4] = a.d_batch[d];
+        meta[5] = __float_as_int(a.d_flops[d]); meta[6] = __float_as_int(a.d_hbm[d]); meta[7] = 0;
+    }
+    if (!table) return;
+    for (int i = tid; i < n; i += blockDim.x) o.sorted[(size_t)d * nt + i] = sorted[i];
+    for (int k = tid; k < hx_tl_len(m); k += blockDim.x)
+        o.head[(size_t)d * nt + k] = k < m ? make_int2(tl.e[seg_l[k]].x, rank[seg_l[k]]) : make_int2((int)0xff800000u, 0);
+    // G[k][r]: the time of the first entry of stretch k that has room at threshold rank r, +inf if none has.
+    // Ranks never rise inside a stretch, so that entry is found by bisection.
+    const int width = n + 1;
+    for (int idx = tid; idx < m * width; idx += blockDim.x) {
+        const int k = idx / width, r = idx - k * width;
+        const int last = seg_l[k + 1];
+        int lo = seg_l[k], hi = last;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (rank[mid] <= r) hi = mid; else lo = mid + 1;
+        }
+        o.G[(size_t)d * HX_TAB + idx] = lo < last ? __int_as_float(tl.e[lo].x) : INFINITY;
+    }
 }
 
 // The same scan as hx_earliest_start for a timeline every lane of the wavefront shares.  The
@@ -300,8 +423,7 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, i
 typedef int HxTlGroup __attribute__((ext_vector_type(16)));      // eight (time, occupancy) entries
 typedef __attribute__((address_space(4))) const HxTlGroup *hx_tl_group_cp;
 
-__device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restrict__ e, const float *lds_t, const short *lds_src,
-                                                           int n, int thr, float T, bool active)
+__device__ __forceinline__ float hx_earliest_start_shared(const int2 *__restrict__ e, int n, int thr, float T, bool active)
 {
     const bool open = active && thr >= 0;
     float rs = INFINITY, ans = INFINITY;
@@ -327,90 +449,277 @@ __device__ __forceinline__ HxSlot hx_earliest_start_shared(const int2 *__restric
         cur = nxt;
     }
 #undef HX_TL_STEP
-    HxSlot r{INFINITY, -1};
-    if (open && ans < INFINITY) {
-        // which entry the start is: times are strictly increasing, a bisection over the copy in LDS finds it
-        int lo = 0, hi = n - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (lds_t[mid] < ans) lo = mid + 1; else hi = mid;
-        }
-        r.S = ans;
-        r.src = lds_src[lo];
-    }
-    return r;
+    return open ? ans : INFINITY;
 }
 
-// Workgroup (d, part): calls part*chunk .. of the queue against instance d.  The calls that may
-// go to d (free ones and those locked to d) are first gathered in LDS, so that the scan runs with
-// full wavefronts however many calls are locked elsewhere; then one call per lane.
-constexpr int DS_CHUNK = 1024;        // calls per workgroup at most
-
-__global__ __launch_bounds__(256) void hx_decode_score_kernel(DecodeArgs a, const int2 *__restrict__ tl_e,
-                                                              const short *__restrict__ tl_src, const int *__restrict__ tl_n,
-                                                              int nt, int splits, int chunk)
+// The start from the first-room table (see the timeline kernel).  r: the rank of the call's threshold.
+// Stretch by stretch: a run that reaches a head lasted until then, which is where its length is tested
+// (the entry-by-entry scan tests it at every entry, but a run long enough at an entry inside a stretch
+// is still the same run, and long enough, at the next head or at the end); the run survives the head if
+// the head has room; otherwise the next run begins at the stretch's first entry with room, G[k][r].
+// Inside a run that entry is the head itself, later than the run's start, so one minimum serves both
+// cases.  The same comparisons on the same values as the scan: the same start bit for bit.
+// head: per stretch (time, rank) in groups of eight, read as scalars; G, sorted, t, src: LDS.
+__device__ __forceinline__ float hx_earliest_start_table(const int2 *__restrict__ head, const float *G, const int *sorted,
+                                                         int n, int m, int thr, float T, bool active)
 {
-    __shared__ int s_c[DS_CHUNK], s_L[DS_CHUNK], s_O[DS_CHUNK];
-    __shared__ float s_t[2 * HX_MAX_INTERVALS + 2];        // the timeline's times and sources, for the bisection
-    __shared__ short s_src[2 * HX_MAX_INTERVALS + 2];
-    __shared__ int s_count;
-    const int tid = threadIdx.x;
-    const int lane = tid & (HX_WAVE - 1);
-    const int d = blockIdx.x / splits, part = blockIdx.x - d * splits;
-    const int ne = 2 * a.stride + 1;
-    const int2 *__restrict__ e = tl_e + (size_t)d * nt;
-    const short *__restrict__ src = tl_src + (size_t)d * ne;
-    const int n = tl_n[d];
-    const float invF = 1.0f / a.d_flops[d], invB = 1.0f / a.d_hbm[d];
-    const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, invF, invB);
-    const int cap = a.d_cap[d];
-    const int c_lo = part * chunk, c_hi = min(a.Q, c_lo + chunk);
-    if (tid == 0) s_count = 0;
-    for (int i = tid; i < n; i += blockDim.x) { s_t[i] = __int_as_float(e[i].x); s_src[i] = src[i]; }
-    __syncthreads();
-    for (int base = c_lo; base < c_hi; base += blockDim.x) {
-        const int c = base + tid;
-        const bool in = c < c_hi;
-        const int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
-        const int lk = (in && a.lock) ? a.lock[c] : -1;
-        const bool ok = L >= 0 && O >= 0 && lk >= -1 && lk < a.D;
-        if (!ok) hx_raise(a.status, HX_ERR_INDEX);
-        const bool legal = in && ok && (lk < 0 || lk == d);
-        const unsigned long long m = __builtin_amdgcn_ballot_w64(legal);
-        int at = 0;
-        if (lane == 0 && m) at = atomicAdd(&s_count, __popcll(m));
-        at = __builtin_amdgcn_readfirstlane(at) + __popcll(m & ((1ull << lane) - 1ull));
-        if (legal) { s_c[at] = c; s_L[at] = L; s_O[at] = O; }
-        if (in && !legal) {
-            if (a.start) a.start[(size_t)c * a.D + d] = INFINITY;
-            if (a.cost) a.cost[(size_t)c * a.D + d] = INFINITY;
+    const bool open = active && thr >= 0;
+    int r = 0;
+    {
+        int lo = 0, hi = n;                                // first position of sorted[] above thr = #{occ <= thr}
+        while (__builtin_amdgcn_ballot_w64(lo < hi) != 0) {
+            const int mid = (lo + hi) >> 1;
+            const bool le = sorted[min(mid, n - 1)] <= thr;
+            if (lo < hi) { if (le) lo = mid + 1; else hi = mid; }
+        }
+        r = open ? lo : 0;                                 // rank 0: no entry has room
+    }
+    const float *Gr = G + r;
+    const int width = n + 1;
+    float rs = INFINITY, ans = INFINITY;
+    // Eight stretches per step: their heads arrive as scalars, their table entries are read together.  Past the
+    // last stretch the heads are (-inf, rank 0) and the table row is the last one again: no hit, the run
+    // kept, and a minimum with a value that is already in it.
+#define HX_HEAD_STEP(u_)                                                          \
+    {                                                                             \
+        ans = fminf(ans, __int_as_float(cur[2 * (u_)]) >= rs + T ? rs : INFINITY); \
+        rs = cur[2 * (u_) + 1] <= r ? rs : INFINITY;                              \
+        rs = fminf(rs, gv[u_]);                                                   \
+    }
+    const hx_tl_group_cp g = (hx_tl_group_cp)(unsigned long long)head;
+    HxTlGroup cur = g[0];
+    for (int k0 = 0; k0 < m; k0 += 8) {
+        if (__builtin_amdgcn_ballot_w64(open && !(ans < INFINITY)) == 0) break;
+        const HxTlGroup nxt = g[(k0 >> 3) + 1];
+        float gv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) gv[u] = Gr[min(k0 + u, m - 1) * width];
+        HX_HEAD_STEP(0) HX_HEAD_STEP(1) HX_HEAD_STEP(2) HX_HEAD_STEP(3)
+        HX_HEAD_STEP(4) HX_HEAD_STEP(5) HX_HEAD_STEP(6) HX_HEAD_STEP(7)
+        cur = nxt;
+    }
+#undef HX_HEAD_STEP
+    ans = fminf(ans, INFINITY >= rs + T ? rs : INFINITY);  // the last run reaches the end of the timeline
+    return open ? ans : INFINITY;
+}
+
+// The same result by stretches instead of entries.  Inside a stretch occupancy never rises, so the
+// entries with room are its tail, found by bisection; a run that has begun continues through every
+// later stretch whose head still has room and ends at the first head that has not, which is where
+// its length is tested (a run long enough at any earlier entry is long enough there).  All
+// comparisons are the ones the entry-by-entry scan makes, on the same values, so the start is the
+// same bit for bit; the work per (call, instance) is a few operations per stretch plus the
+// bisections instead of seven per entry.  e: the timeline in LDS; seg[0..m]: heads and n.
+__device__ __forceinline__ float hx_earliest_start_stretches(const int2 *e, const int *seg, int n, int m, int thr, float T, bool active)
+{
+    const bool open = active && thr >= 0;
+    float rs = INFINITY, ans = INFINITY;
+    for (int k = 0; k < m; ++k) {
+        if (__builtin_amdgcn_ballot_w64(open && !(ans < INFINITY)) == 0) break;
+        const int first = seg[k], last = seg[k + 1];
+        const int2 head = e[first];
+        const bool head_room = head.y <= thr;
+        // a run that reaches a head lasted until then (rs = +inf outside a run: no hit)
+        ans = fminf(ans, __int_as_float(head.x) >= rs + T ? rs : INFINITY);
+        rs = head_room ? rs : INFINITY;
+        // lanes outside a run take the first entry with room in this stretch, if there is one
+        const bool need = open && !(rs < INFINITY);
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            int lo = first, hi = last;
+            while (__builtin_amdgcn_ballot_w64(need && lo < hi) != 0) {
+                const int mid = (lo + hi) >> 1;
+                const bool room = e[min(mid, n - 1)].y <= thr;
+                if (lo < hi) { if (room) hi = mid; else lo = mid + 1; }
+            }
+            if (need && lo < last) rs = __int_as_float(e[lo].x);
         }
     }
-    __syncthreads();
-    const int n_legal = s_count;
-    for (int base = 0; base < n_legal; base += blockDim.x) {
-        const int i = base + tid;
-        const bool in = i < n_legal;
-        const int c = in ? s_c[i] : 0, L = in ? s_L[i] : 0, O = in ? s_O[i] : 0;
-        const HxDecodeCand k = hx_decode_candidate(a.m, L, O, -1, d, a.D, x, cap, a.status);
-        const HxSlot s = hx_earliest_start_shared(e, s_t, s_src, n, k.thr, k.T, in);
-        const float v = s.S + k.T;                         // +inf when there is no start
-        if (in) {
-            if (a.start) a.start[(size_t)c * a.D + d] = s.S;
-            if (a.cost) a.cost[(size_t)c * a.D + d] = s.src >= 0 ? v : INFINITY;
-            if (s.src >= 0 && v < INFINITY) {
-                // read first: most candidates do not improve on what other instances have already written
-                const u64 mine = hx_decode_key(v, d, s.src);
-                if (__hip_atomic_load(&a.key[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > mine) atomicMin(&a.key[c], mine);
-            }
+    ans = fminf(ans, INFINITY >= rs + T ? rs : INFINITY);  // the last run reaches the end of the timeline
+    return open ? ans : INFINITY;
+}
+
+// What the scoring kernel knows of an instance: one 32-byte record, written by the timeline kernel and read
+// as scalars.
+typedef int HxMetaRec __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(4))) const HxMetaRec *hx_meta_cp;
+
+struct HxInst {
+    int n, m_flag, cap, used, batch;
+    float flops, hbm;
+    __device__ __forceinline__ int m() const { return m_flag & (HX_TAB_FLAG - 1); }
+    // with the table: a few operations per stretch.  Else few long stretches: search them; many short ones
+    // (most entries are starts): the plain scan, straight from memory.
+    __device__ __forceinline__ bool by_table() const { return (m_flag & HX_TAB_FLAG) != 0; }
+    __device__ __forceinline__ bool by_stretch() const { return !by_table() && 4 * m() <= n; }
+};
+
+__device__ __forceinline__ HxInst hx_inst_load(const TlOut &o, int d)
+{
+    const HxMetaRec r = ((hx_meta_cp)(unsigned long long)o.meta)[d];
+    HxInst it;
+    it.n = r[0]; it.m_flag = r[1]; it.cap = r[2]; it.used = r[3]; it.batch = r[4];
+    it.flops = __int_as_float(r[5]); it.hbm = __int_as_float(r[6]);
+    return it;
+}
+
+// An instance's tables, copied to LDS by the whole workgroup.  With the table: its cells, then the sorted
+// occupancies; for the stretch search: the timeline's (time, occupancy) pairs, then the stretch heads.
+constexpr int DS_THREADS = 256;
+constexpr int DS_OFF_SORTED = HX_TAB, DS_OFF_SEG = 2 * (2 * HX_MAX_INTERVALS + 2);   // words into the staging buffer
+constexpr int DS_BUF = HX_TAB + HX_TAB_MAX_N;
+static_assert(DS_BUF >= DS_OFF_SEG + HX_MAX_INTERVALS + 2, "the stretch search's arrays fit in the table's place");
+
+__device__ __forceinline__ void hx_inst_stage(int *buf, const TlOut &o, int d, int nt, const HxInst &it, int tid)
+{
+    const int n = it.n, m = it.m();
+    if (it.by_table()) {
+        const int *G = (const int *)(o.G + (size_t)d * HX_TAB);
+        for (int i = tid; i < m * (n + 1); i += DS_THREADS) buf[i] = G[i];
+        for (int i = tid; i < n; i += DS_THREADS) buf[DS_OFF_SORTED + i] = o.sorted[(size_t)d * nt + i];
+    } else if (it.by_stretch()) {
+        int2 *e = (int2 *)buf;
+        for (int i = tid; i < n; i += DS_THREADS) e[i] = o.e[(size_t)d * nt + i];
+        for (int i = tid; i <= m; i += DS_THREADS) buf[DS_OFF_SEG + i] = o.seg[(size_t)d * nt + i];
+    }
+}
+
+// Selection without atomics: a workgroup takes 256 free calls, one per lane, through a group of gd consecutive
+// instances, one instance after the other, and every lane keeps the best (finish, instance, start) it has
+// seen -- instances ascend, so "strictly smaller" keeps the lowest instance among equal finishes.  The lane's
+// result for the group goes to part_*[group][call]; the finish kernel takes the minimum over the groups in
+// the same order.  (Asking for an instance's tables while the one before it is searched, into a second
+// buffer, was measured and gained nothing: with four workgroups to a compute unit the waits are already
+// covered, and the extra address arithmetic costs what the overlap saves.)
+//
+// The first n_lock workgroups of the grid are for the locked calls instead, one lane per call of the queue
+// (lanes of free calls idle): a locked call has its one instance, so each lane reads that instance's
+// timeline for itself, and its result is the call's result (group 0's place).
+__global__ __launch_bounds__(DS_THREADS) void hx_decode_score_kernel(DecodeArgs a, TlOut o, int nt, int n_lock)
+{
+    __shared__ __align__(16) int s_buf[DS_BUF];
+    int *s_pref = s_buf;                                   // free calls before each slice of the queue: done with before the buffer is filled
+    static_assert(DS_BUF >= HX_MAX_INSTANCES + 1, "the slice prefixes fit in the staging buffer");
+    __shared__ int s_wave_n[DS_THREADS / HX_WAVE];
+    const int tid = threadIdx.x;
+    const int ne = 2 * a.stride + 1;
+    if ((int)blockIdx.x < n_lock) {
+        const int c = (int)blockIdx.x * DS_THREADS + tid;
+        const bool in = c < a.Q;
+        const int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
+        const int lk = in ? a.lock[c] : -1;
+        const bool ok = L >= 0 && O >= 0 && lk >= -1 && lk < a.D;              // an error is already raised
+        const bool legal = in && ok && lk >= 0;
+        const int d = legal ? lk : 0;
+        const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, 1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
+        const HxDecodeCand k = hx_decode_candidate(a.m, legal ? L : 0, legal ? O : 0, -1, d, a.D, x, a.d_cap[d], a.status);
+        const HxSlot s = hx_earliest_start(o.e + (size_t)d * nt, o.src + (size_t)d * ne, o.n[d], k.thr, k.T, legal);
+        const float v = s.S + k.T;
+        const bool placed = legal && s.src >= 0 && v < INFINITY;
+        if (in && !(ok && lk < 0)) {                       // locked or invalid: this lane speaks for the call
+            a.part_cost[c] = placed ? v : INFINITY;
+            a.part_start[c] = placed ? s.S : INFINITY;
+            a.part_d[c] = placed ? d : -1;
+            if (a.start || a.cost)
+                for (int j = 0; j < a.D; ++j) {
+                    const bool here = legal && j == d;
+                    if (a.start) a.start[(size_t)c * a.D + j] = here ? s.S : INFINITY;
+                    if (a.cost) a.cost[(size_t)c * a.D + j] = (here && s.src >= 0) ? v : INFINITY;
+                }
         }
+        return;
+    }
+    const int b = (int)blockIdx.x - n_lock;
+    const int tile = b / a.n_groups, grp = b - tile * a.n_groups;
+    const int lane = tid & (HX_WAVE - 1), wave = tid >> 6;
+    const int d_lo = grp * a.gd, d_hi = min(a.D, (grp + 1) * a.gd);
+    // which call this lane has: position tile*256 + tid of the free calls
+    int c = tile * DS_THREADS + tid;
+    bool in = c < a.Q;
+    if (a.lock) {
+        // free calls before each slice: an inclusive scan of the D slice counts, four per thread
+        int v[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = tid * 4 + j;
+            v[j] = idx < a.D ? a.n_free[idx] : 0;
+            sum += v[j];
+        }
+        int incl = sum;
+#pragma unroll
+        for (int off = 1; off < HX_WAVE; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        if (lane == HX_WAVE - 1) s_wave_n[wave] = incl;
+        __syncthreads();
+        int run = incl - sum;
+        for (int w2 = 0; w2 < wave; ++w2) run += s_wave_n[w2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = tid * 4 + j;
+            if (idx < a.D) s_pref[idx] = run;
+            run += v[j];
+            if (idx == a.D - 1) s_pref[a.D] = run;
+        }
+        __syncthreads();
+        const int n_all = s_pref[a.D];
+        const int p = tile * DS_THREADS + tid;
+        if (tile * DS_THREADS >= n_all) return;            // the whole workgroup: the grid is sized for a queue without locks
+        in = p < n_all;
+        // the last slice that begins at or before position p
+        int lo = 0, hi = a.D - 1;
+        while (__builtin_amdgcn_ballot_w64(lo < hi) != 0) {
+            const int mid = (lo + hi + 1) >> 1;
+            const bool le = s_pref[mid] <= p;
+            if (lo < hi) { if (le) lo = mid; else hi = mid - 1; }
+        }
+        c = in ? a.free_c[lo * a.per + (p - s_pref[lo])] : 0;
+    } else if (tile * DS_THREADS >= a.Q) {
+        return;
+    }
+    const bool has = in;                                   // a call of its own: writes a result, if only "none"
+    int L = in ? a.L_in[c] : 0, O = in ? a.L_out[c] : 0;
+    if (!a.lock && (L < 0 || O < 0)) { hx_raise(a.status, HX_ERR_INDEX); in = false; }
+    if (!in) { L = 0; O = 0; }
+    const HxCallF cf = hx_call_terms(a.m, L, O);
+    const long long need = (long long)L + (long long)O;
+    float best_v = INFINITY, best_S = INFINITY;
+    int best_d = -1;
+    HxInst cur = hx_inst_load(o, d_lo);
+    for (int d = d_lo; d < d_hi; ++d) {
+        const int *buf = s_buf;
+        __syncthreads();                                   // the slice prefixes, or the last instance's tables, are done with
+        hx_inst_stage(s_buf, o, d, nt, cur, tid);
+        const HxInst nxt = hx_inst_load(o, min(d + 1, d_hi - 1));
+        __syncthreads();
+        const HxDecF x = hx_decode_terms(a.m, cur.used, cur.batch, 0, 1.0f / cur.flops, 1.0f / cur.hbm);
+        const float T = hx_decode_time(cf, x.c1, x.c2, x.kB);
+        const long long room = (long long)cur.cap - need;
+        const int thr = room < 0 ? -1 : (room > (long long)INT_MAX ? INT_MAX : (int)room);
+        const int n = cur.n, m = cur.m();
+        const float S = cur.by_table()     ? hx_earliest_start_table(o.head + (size_t)d * nt, (const float *)buf, buf + DS_OFF_SORTED,
+                                                                     n, m, thr, T, in)
+                        : cur.by_stretch() ? hx_earliest_start_stretches((const int2 *)buf, buf + DS_OFF_SEG, n, m, thr, T, in)
+                                           : hx_earliest_start_shared(o.e + (size_t)d * nt, n, thr, T, in);
+        const float v = S + T;                             // +inf when there is no start
+        if (in) {
+            if (a.start) a.start[(size_t)c * a.D + d] = S;
+            if (a.cost) a.cost[(size_t)c * a.D + d] = S < INFINITY ? v : INFINITY;
+            if (S < INFINITY && v < best_v) { best_v = v; best_S = S; best_d = d; }
+        }
+        cur = nxt;
+    }
+    if (has) {
+        const size_t at = (size_t)grp * a.Q + c;
+        a.part_cost[at] = best_v; a.part_start[at] = best_S; a.part_d[at] = best_d;
     }
 }
 
 struct DecodeFinishArgs {
-    int Q, D, stride;
-    const u64 *key;
-    const float *iv_end;
+    int Q, D, n_groups;
+    const int32_t *L_in, *L_out, *lock;
+    const float *part_cost, *part_start;
+    const int32_t *part_d;
     const int32_t *node, *wf;
     const float *elapsed, *tail, *horizon;
     int n_nodes, n_wf;
@@ -419,18 +728,34 @@ struct DecodeFinishArgs {
     int32_t *status;
 };
 
-__global__ __launch_bounds__(256) void hx_decode_finish_kernel(DecodeFinishArgs a)
+// the best of the groups' candidates (one place only for a call that is not free); n_groups = 0: there are no instances
+__global__ __launch_bounds__(64) void hx_decode_finish_kernel(DecodeFinishArgs a)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= a.Q) return;
-    const u64 k = a.key[c];
     int d = -1;
     float S = INFINITY, v = INFINITY;
-    if (k != ~0ull) {
-        d = (int)((k >> 16) & 0xffffu);
-        const int src = (int)(k & 0xffffu);
-        v = __uint_as_float((unsigned)(k >> 32));
-        S = src == 0 ? 0.0f : a.iv_end[(size_t)d * a.stride + (src - 1)];
+    const int lk = a.lock ? a.lock[c] : -1;
+    const bool is_free = a.L_in[c] >= 0 && a.L_out[c] >= 0 && lk == -1;
+    const int groups = is_free ? a.n_groups : min(a.n_groups, 1);
+    // groups ascend in instance: "strictly smaller" keeps the lowest instance among equal finishes
+    int g_best = -1;
+    int g = 0;
+    for (; g + 8 <= groups; g += 8) {
+        float pv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) pv[u] = a.part_cost[(size_t)(g + u) * a.Q + c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (pv[u] < v) { v = pv[u]; g_best = g + u; }
+    }
+    for (; g < groups; ++g) {
+        const float pv = a.part_cost[(size_t)g * a.Q + c];
+        if (pv < v) { v = pv; g_best = g; }
+    }
+    if (g_best >= 0) {
+        S = a.part_start[(size_t)g_best * a.Q + c];
+        d = a.part_d[(size_t)g_best * a.Q + c];
     }
     a.best_d[c] = d; a.best_start[c] = S; a.best_cost[c] = v;
     if (a.ratio)
@@ -670,53 +995,86 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
     hipStream_t stream = (hipStream_t)stream_;
     const int ne = 2 * iv->stride + 1, nt = hx_tl_len(ne);
+    // Groups of instances: enough workgroups (tiles of 256 calls x groups) to fill the chip several times over,
+    // at most 64 groups (the finish kernel reads one partial result per group and call).
+    const int tiles = (Q + 255) / 256;
+    int n_groups = 0, gd = 1;
+    if (D > 0) {
+        n_groups = (8 * ctx->num_cu + tiles - 1) / tiles;
+        if (n_groups > 64) n_groups = 64;
+        if (n_groups > D) n_groups = D;
+        gd = (D + n_groups - 1) / n_groups;
+        n_groups = (D + gd - 1) / gd;
+    }
+    const int per = D > 0 ? (Q + D - 1) / D : Q;
+    // words of scratch per pass: the free list (D slices of `per` places) and three partial results per group and call
+    const size_t part_need = (size_t)(D > 0 ? D : 1) * per + 3 * (size_t)(n_groups > 0 ? n_groups : 1) * Q;
     const size_t tl_need = (size_t)(D > 0 ? D : 1) * nt;
-    if (Q > ctx->dkey_cap || tl_need > ctx->dtl_cap) {
+    if (part_need > ctx->dpart_cap || tl_need > ctx->dtl_cap || D > ctx->dtab_cap) {
         // grown, never shrunk; work queued on the old blocks has to finish before they go
         HX_HIP(ctx, hipDeviceSynchronize());
-        if (Q > ctx->dkey_cap) {
-            if (ctx->d_dkey) { HX_HIP(ctx, hipFree(ctx->d_dkey)); ctx->d_dkey = nullptr; ctx->dkey_cap = 0; }
-            const int want = Q < 4096 ? 4096 : Q;
-            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dkey, (size_t)want * sizeof(u64)));
-            ctx->dkey_cap = want;
+        if (part_need > ctx->dpart_cap) {
+            if (ctx->d_dpart) { HX_HIP(ctx, hipFree(ctx->d_dpart)); ctx->d_dpart = nullptr; ctx->dpart_cap = 0; }
+            const size_t want = part_need < 65536 ? 65536 : part_need;
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dpart, want * sizeof(int32_t)));
+            ctx->dpart_cap = want;
         }
         if (tl_need > ctx->dtl_cap) {
             if (ctx->d_dtl) { HX_HIP(ctx, hipFree(ctx->d_dtl)); ctx->d_dtl = nullptr; ctx->dtl_cap = 0; }
-            // per entry: (time, occupancy) 8 bytes + source 2 bytes; per instance one length
-            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 10 + (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
+            // per entry: (time, occupancy) and (head time, head rank) 8 bytes each, sorted occupancy and stretch head 4
+            // each, source 2; per instance three counts and a record of eight words
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 26 + (3 + 8) * (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
             ctx->dtl_cap = tl_need;
         }
+        if (D > ctx->dtab_cap) {
+            if (ctx->d_dtab) { HX_HIP(ctx, hipFree(ctx->d_dtab)); ctx->d_dtab = nullptr; ctx->dtab_cap = 0; }
+            const int want = D < 64 ? 64 : D;
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtab, (size_t)want * HX_TAB * sizeof(float)));
+            ctx->dtab_cap = want;
+        }
     }
-    int2 *tl_e = (int2 *)ctx->d_dtl;
-    int *tl_n = (int *)((unsigned char *)ctx->d_dtl + ctx->dtl_cap * 8);
-    short *tl_src = (short *)((unsigned char *)ctx->d_dtl + ctx->dtl_cap * 8 + (size_t)HX_MAX_INSTANCES * sizeof(int));
+    TlOut o{};
+    int32_t *n_free = nullptr;
+    {
+        unsigned char *p = (unsigned char *)ctx->d_dtl;
+        const size_t cap = ctx->dtl_cap;                      // a multiple of 8: every block below stays 16-byte aligned
+        o.e = (int2 *)p;        p += cap * 8;
+        o.head = (int2 *)p;     p += cap * 8;
+        o.n = (int *)p;         p += (size_t)HX_MAX_INSTANCES * sizeof(int);
+        o.m = (int *)p;         p += (size_t)HX_MAX_INSTANCES * sizeof(int);
+        n_free = (int32_t *)p;  p += (size_t)HX_MAX_INSTANCES * sizeof(int);
+        o.meta = (int *)p;      p += 8 * (size_t)HX_MAX_INSTANCES * sizeof(int);
+        o.sorted = (int *)p;    p += cap * 4;
+        o.seg = (int *)p;       p += cap * 4;
+        o.src = (short *)p;
+        o.G = ctx->d_dtab;
+    }
+    int32_t *free_c = ctx->d_dpart;
+    float *part_cost = (float *)(ctx->d_dpart + (size_t)(D > 0 ? D : 1) * per);
+    float *part_start = part_cost + (size_t)(n_groups > 0 ? n_groups : 1) * Q;
+    int32_t *part_d = (int32_t *)(part_start + (size_t)(n_groups > 0 ? n_groups : 1) * Q);
     if (D > 0) {
         DecodeArgs a{};
         a.m = to_model(model); a.Q = Q; a.D = D; a.stride = iv->stride;
         a.L_in = queue->L_in; a.L_out = queue->L_out; a.lock = lock;
         a.d_flops = dec->flops; a.d_hbm = dec->hbm_bw; a.d_used = dec->used_tok; a.d_cap = dec->cap_tok; a.d_batch = dec->batch;
         a.iv_count = iv->count; a.iv_start = iv->start; a.iv_end = iv->end; a.iv_tok = iv->tok;
-        a.start = start; a.cost = cost; a.key = ctx->d_dkey; a.status = ctx->d_status;
+        a.start = start; a.cost = cost; a.status = ctx->d_status;
+        a.free_c = free_c; a.n_free = n_free; a.per = per;
+        a.gd = gd; a.n_groups = n_groups; a.part_cost = part_cost; a.part_start = part_start; a.part_d = part_d;
         const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)nt * 8) + hx_align16((size_t)ne * 2);
-        hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, tl_e, tl_src, tl_n, nt);
-        // enough workgroups to fill the chip, each with at least one full pass of calls
-        int splits = (8 * ctx->num_cu + D - 1) / D;
-        const int max_splits = (Q + 255) / 256, min_splits = (Q + DS_CHUNK - 1) / DS_CHUNK;
-        if (splits > max_splits) splits = max_splits;
-        if (splits < min_splits) splits = min_splits;
-        int chunk = (Q + splits - 1) / splits;
-        chunk = (chunk + 255) / 256 * 256;                // <= DS_CHUNK, a multiple of 256 itself
-        splits = (Q + chunk - 1) / chunk;
-        hx_decode_score_kernel<<<D * splits, 256, 0, stream>>>(a, tl_e, tl_src, tl_n, nt, splits, chunk);
-    } else {
-        hx_decode_key_init_kernel<<<(Q + 255) / 256, 256, 0, stream>>>(ctx->d_dkey, Q);
+        hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, o, nt);
+        const int n_lock = lock ? tiles : 0;
+        hx_decode_score_kernel<<<n_lock + tiles * n_groups, 256, 0, stream>>>(a, o, nt, n_lock);
     }
     DecodeFinishArgs f{};
-    f.Q = Q; f.D = D; f.stride = iv->stride; f.key = ctx->d_dkey; f.iv_end = iv->end;
+    f.Q = Q; f.D = D; f.n_groups = n_groups;
+    f.L_in = queue->L_in; f.L_out = queue->L_out; f.lock = lock;
+    f.part_cost = part_cost; f.part_start = part_start; f.part_d = part_d;
     f.node = queue->node; f.wf = queue->wf; f.elapsed = queue->elapsed; f.tail = tail; f.horizon = horizon;
     f.n_nodes = n_nodes; f.n_wf = n_wf;
     f.best_d = best_d; f.best_start = best_start; f.best_cost = best_cost; f.ratio = ratio; f.status = ctx->d_status;
-    hx_decode_finish_kernel<<<(Q + 255) / 256, 256, 0, stream>>>(f);
+    hx_decode_finish_kernel<<<(Q + 63) / 64, 64, 0, stream>>>(f);
     return hx_check_launch(ctx, "hx_decode_score kernels");
 }
 

@@ -15,7 +15,7 @@ constexpr int kT = HX_MAX_TYPES;
 
 // ---- one-pass ordering -----------------------------------------------------------
 
-constexpr int RANK_TILE = 2048;      // calls compared against per block
+constexpr int RANK_TILE = 2048;      // calls compared against per block, at most
 constexpr int RANK_SMALL = 16384;    // queues up to this size are ranked by all-pairs counting
 
 __global__ __launch_bounds__(256) void hx_rank_zero_kernel(int32_t *rank, int C)
@@ -35,12 +35,12 @@ __device__ __forceinline__ unsigned long long hx_rank_key64(float r, int idx)
 
 // rank[c] = number of calls ahead of c: larger ratio, or equal ratio and lower
 // index.  Block (i, j) counts, for 256 calls, those ahead of them among the
-// calls of tile j; the partial counts are added up with integer atomics.
-__global__ __launch_bounds__(256) void hx_rank_count_kernel(const float *ratio, int32_t *rank, int C)
+// `tile` calls of tile j; the partial counts are added up with integer atomics.
+__global__ __launch_bounds__(256) void hx_rank_count_kernel(const float *ratio, int32_t *rank, int C, int tile)
 {
     __shared__ unsigned long long s_key[RANK_TILE];
-    const int k0 = blockIdx.y * RANK_TILE;
-    const int kn = min(RANK_TILE, C - k0);
+    const int k0 = blockIdx.y * tile;
+    const int kn = min(tile, C - k0);
     for (int i = threadIdx.x; i < kn; i += blockDim.x) s_key[i] = hx_rank_key64(ratio[k0 + i], k0 + i);
     __syncthreads();
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
@@ -438,11 +438,17 @@ extern "C" int hx_rank(hx_ctx *ctx, int32_t C, const float *ratio, int32_t *rank
     HxDeviceGuard guard(ctx->device);
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
     hipStream_t stream = (hipStream_t)stream_;
-    const int bx = (C + 255) / 256, by = (C + RANK_TILE - 1) / RANK_TILE;
+    const int bx = (C + 255) / 256;
     if (C <= RANK_SMALL) {
-        // small queues: every call against every call, no scratch
+        // small queues: every call against every call, no scratch.  Tiles short enough for a few thousand
+        // workgroups (a workgroup's time is its tile's length, whatever the queue's), long enough to be worth
+        // their atomics.
+        int tile = (C / 32 + 63) / 64 * 64;
+        if (tile < 64) tile = 64;
+        if (tile > RANK_TILE) tile = RANK_TILE;
+        const int by = (C + tile - 1) / tile;
         hx_rank_zero_kernel<<<bx, 256, 0, stream>>>(rank, C);
-        hx_rank_count_kernel<<<dim3(bx, by), 256, 0, stream>>>(ratio, rank, C);
+        hx_rank_count_kernel<<<dim3(bx, by), 256, 0, stream>>>(ratio, rank, C, tile);
         return hx_check_launch(ctx, "hx_rank kernels");
     }
     const size_t need = (size_t)C + RANK_SPLIT + (RANK_BUCKETS + 1) / 2 + 8;      // keys, splitters, bucket sizes (two ints per word)

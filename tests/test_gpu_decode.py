@@ -125,7 +125,14 @@ def check_score(model, L, O, lock, dec, iv, got, want, pairs=None):
 
 
 @pytest.mark.parametrize("Q,D,stride,res,plan,seed", [(48, 4, 16, 10, 3, 1), (300, 7, 40, 20, 8, 2), (1000, 33, 24, 12, 6, 3),
-                                                        (513, 64, 64, 40, 10, 4), (2049, 5, 30, 1, 12, 5)])
+                                                        (513, 64, 64, 40, 10, 4), (2049, 5, 30, 1, 12, 5),
+                                                        # the kernel searches a timeline in one of three ways, by its shape:
+                                                        # few planned intervals among many resident ones (all cases above),
+                                                        # the same with a timeline too long for its table, mostly planned ones
+                                                        (600, 6, 400, 340, 30, 6), (400, 3, 511, 508, 3, 7), (700, 5, 160, 20, 110, 8),
+                                                        (300, 4, 300, 1, 290, 9),
+                                                        # more instances than groups of them, a queue shorter than a workgroup
+                                                        (100, 300, 8, 4, 2, 10), (257, 1, 12, 6, 3, 11)])
 def test_decode_score_matches_oracle(ctx, Q, D, stride, res, plan, seed):
     r, lock, iv = synth.make_decode_round("decode_tiny", seed, n_wf=max(8, Q // 8), Q=Q, D=D, T=min(4, D), stride=stride,
                                           n_resident=res, n_planned=plan)
@@ -137,7 +144,7 @@ def test_decode_score_matches_oracle(ctx, Q, D, stride, res, plan, seed):
     n_bad = check_score(r.model, L, O, lock, r.dec, iv, got, want)
     assert n_bad <= max(2, Q * D // 2000)
     fin = np.isfinite(want.start)
-    assert (want.start[fin] > 0).any() and (want.start[fin] == 0).any()
+    assert (want.start[fin] > 0).any() and ((want.start[fin] == 0).any() or res < 2)
     # Eq. (2) at the decode stage, from the GPU's own best cost
     el = r.calls["elapsed"].astype(np.float64)
     with np.errstate(all="ignore"):
