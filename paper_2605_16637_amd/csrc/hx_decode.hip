@@ -795,14 +795,21 @@ struct DGreedyLds {
     __host__ __device__ size_t off_inst() const { return off_src() + hx_align16((size_t)D * ne * 2); }
     __host__ __device__ size_t off_call() const { return off_inst() + (size_t)6 * D * 4; }
     __host__ __device__ size_t off_red() const { return off_call() + (size_t)5 * Q * 4; }
-    __host__ __device__ size_t bytes() const { return off_red() + (size_t)(2 * DG_WAVES + 8) * 4; }
+    __host__ __device__ size_t off_mat() const { return hx_align16(off_red() + (size_t)(2 * DG_WAVES + 8) * 4); }
+    __host__ __device__ size_t bytes() const { return off_mat(); }
+    // with the finish of every (instance, call) pair kept: [D][Q] floats more
+    __host__ __device__ size_t bytes_with_matrix() const { return off_mat() + (size_t)D * Q * 4; }
 };
 
 enum : int { DG_ALIVE = 1, DG_DIRTY = 2 };
 
-// A call is scored again only if its instance is the one that just received an interval:
-// an added interval can only delay starts on that instance, every other call keeps its result.
-__global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs a)
+// An added interval can only delay starts on the instance that received it; everything else stands.
+// keep_all (when LDS has room for the finish of every (instance, call) pair): after a step only that
+// instance's column is computed again, one call per lane, all lanes on the same timeline; a call whose best
+// was there takes the minimum of its row again; the start of the call that is picked is found when it is
+// picked.  Otherwise: a call is scored again, on every instance, if its instance is the one that changed.
+// Both ways give the same plan: the same functions on the same timelines, the same (finish, instance) rule.
+__global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs a, int keep_all)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const DGreedyLds lay(a.stride, a.D, a.Q);
@@ -823,6 +830,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     float *s_redv = (float *)(smem + lay.off_red());
     int *s_redi = (int *)(s_redv + DG_WAVES);
     int *s_pick = s_redi + DG_WAVES;
+    float *s_mat = (float *)(smem + lay.off_mat());       // [lay.D][lay.Q] finish of call c on instance d, +inf: none (keep_all)
 
     const int tid = threadIdx.x;
     const int lane = tid & (HX_WAVE - 1);
@@ -845,8 +853,8 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     }
 
     for (int k = 0; k < a.Q; ++k) {
-        // (1) score the calls whose instance changed: one wavefront per call, lanes over instances
-        for (int c = wave; c < a.Q; c += DG_WAVES) {
+        // (1) score the calls whose instance changed (keep_all: every call, once): one wavefront per call, lanes over instances
+        for (int c = wave; c < a.Q && (!keep_all || k == 0); c += DG_WAVES) {
             if (s_flags[c] != (DG_ALIVE | DG_DIRTY)) continue;     // wave-uniform
             const int L = a.L_in[c], O = a.L_out[c];
             const int lk = a.lock ? a.lock[c] : -1;
@@ -862,6 +870,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 const HxSlot s = hx_earliest_start(s_tl + (size_t)dd * lay.nt, s_src + (size_t)dd * lay.ne, s_n[dd],
                                                    q.thr, q.T, in && q.legal);
                 const float v = s.S + q.T;
+                if (keep_all && in) s_mat[(size_t)d * lay.Q + c] = s.src >= 0 ? v : INFINITY;
                 if (in && s.src >= 0 && v < bv) { bv = v; bS = s.S; bd = d; }
             }
             const float best = hx_wave_min(bv);
@@ -905,6 +914,13 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 if (oi != INT_MAX && (ri == INT_MAX || ov > rv || (ov == rv && oi < ri))) { rv = ov; ri = oi; }
             }
             const int c = ri, d = s_bd[c];
+            if (keep_all && k > 0 && d >= 0) {
+                // its best may have moved since its start was last written: the start on the instance it has now
+                HxDecF x;
+                x.wait = 0.0f; x.c1 = s_c1[d]; x.c2 = s_c2[d]; x.kB = s_kB[d];
+                const HxDecodeCand q = hx_decode_candidate(a.m, a.L_in[c], a.L_out[c], -1, d, a.D, x, s_cap[d], a.status);
+                s_bs[c] = hx_earliest_start(s_tl + (size_t)d * lay.nt, s_src + (size_t)d * lay.ne, s_n[d], q.thr, q.T, true).S;
+            }
             a.best_d[c] = d; a.best_start[c] = s_bs[c]; a.best_cost[c] = s_bc[c]; a.ratio[c] = s_ratio[c]; a.rank[c] = k;
             s_flags[c] = 0;
             int changed = -1;
@@ -931,8 +947,37 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
             const size_t at = (size_t)pd * a.stride;
             Tl tl{s_tl + (size_t)pd * lay.nt, s_src + (size_t)pd * lay.ne};
             hx_build_timeline<true>(s_cnt[pd], a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n[pd], a.status);
-            for (int c = tid; c < a.Q; c += DG_THREADS)
-                if ((s_flags[c] & DG_ALIVE) && s_bd[c] == pd) s_flags[c] = DG_ALIVE | DG_DIRTY;
+            if (!keep_all) {
+                for (int c = tid; c < a.Q; c += DG_THREADS)
+                    if ((s_flags[c] & DG_ALIVE) && s_bd[c] == pd) s_flags[c] = DG_ALIVE | DG_DIRTY;
+            } else {
+                HxDecF x;
+                x.wait = 0.0f; x.c1 = s_c1[pd]; x.c2 = s_c2[pd]; x.kB = s_kB[pd];
+                const int cap = s_cap[pd], n = s_n[pd];
+                for (int base = 0; base < a.Q; base += DG_THREADS) {
+                    const int c = base + tid;
+                    const bool live = c < a.Q && (s_flags[c] & DG_ALIVE);
+                    const int L = live ? a.L_in[c] : 0, O = live ? a.L_out[c] : 0;
+                    const int lk = (live && a.lock) ? a.lock[c] : -1;
+                    const HxDecodeCand q = hx_decode_candidate(a.m, L, O, live ? lk : -1, pd, a.D, x, cap, a.status);
+                    const HxSlot s = hx_earliest_start(tl.e, tl.src, n, q.thr, q.T, live && q.legal);
+                    if (live) {
+                        s_mat[(size_t)pd * lay.Q + c] = s.src >= 0 ? s.S + q.T : INFINITY;
+                        if (s_bd[c] == pd) {
+                            // lowest instance among equal finishes: ascending, strictly smaller
+                            float bv = INFINITY;
+                            int bd = -1;
+                            for (int d = 0; d < a.D; ++d) {
+                                const float v = s_mat[(size_t)d * lay.Q + c];
+                                if (v < bv) { bv = v; bd = d; }
+                            }
+                            s_bd[c] = bd;
+                            s_bc[c] = bv;
+                            s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, bv, a.status);
+                        }
+                    }
+                }
+            }
         }
         __syncthreads();
     }
@@ -1110,9 +1155,11 @@ extern "C" int hx_decode_plan_greedy(hx_ctx *ctx, const hx_model *model, const h
     a.iv_count = iv->count; a.iv_start = iv->start; a.iv_end = iv->end; a.iv_tok = iv->tok;
     a.best_d = best_d; a.best_start = best_start; a.best_cost = best_cost; a.ratio = ratio; a.rank = rank;
     a.status = ctx->d_status;
-    if (D == 0)
+    if (D == 0) {
         hx_decode_no_instance_kernel<<<(Q + 255) / 256, 256, 0, stream>>>(a);
-    else
-        hx_decode_plan_kernel<<<1, DG_THREADS, lay.bytes(), stream>>>(a);
+    } else {
+        const bool keep_all = lay.bytes_with_matrix() <= (size_t)160 * 1024;
+        hx_decode_plan_kernel<<<1, DG_THREADS, keep_all ? lay.bytes_with_matrix() : lay.bytes(), stream>>>(a, keep_all ? 1 : 0);
+    }
     return hx_check_launch(ctx, "hx_decode_plan_greedy kernel");
 }

@@ -357,6 +357,8 @@ def check_plan_stepwise(model, L, O, lock, node, wf, elapsed, tail, hor, dec, iv
 
 
 @pytest.mark.parametrize("Q,D,stride,res,plan,lockf,seed", [(3, 2, 4, 2, 1, 0.5, 1), (40, 4, 16, 10, 3, 0.5, 2), (64, 8, 20, 12, 4, 0.0, 3),
+                                                              # (80 x 64 with 96 entries each leaves no local memory for the finish of
+                                                              # every pair: the planner then rescans the calls of the changed instance)
                                                               (100, 16, 30, 20, 6, 1.0, 4), (80, 64, 16, 10, 3, 0.3, 5),
                                                               # two instances and long chains of appended intervals: exact ties of start + decode time
                                                               (69, 2, 2, 1, 1, 0.3726785374341105, 760292)])
