@@ -262,20 +262,22 @@ __device__ __forceinline__ HxDecodeCand hx_decode_candidate(const HxModelF &m, i
 // How the scoring kernel searches an instance's timeline, decided here per instance.
 constexpr int HX_TAB = 4096;          // entries of the first-room table at most
 constexpr int HX_TAB_MAX_N = 512;     // timeline entries at most for the table (their occupancies are ranked all against all)
-constexpr int HX_TAB_FLAG = 1 << 16;  // in tl_m: the table was written
+constexpr int HX_TAB_FLAG = 1 << 16;  // added to the stretch count in an instance's record: the table was written
 
 struct TlOut {
     int2 *e;         // [D][nt] timeline entries, padded
     short *src;      // [D][ne]
     int *n;          // [D] entries
     int *seg;        // [D][nt] heads of the stretches, then n
-    int *m;          // [D] stretches, HX_TAB_FLAG added when the arrays below were written
     int2 *head;      // [D][nt] per stretch: (time of its head, rank of the head's occupancy), padded with (-inf, 0)
     int *sorted;     // [D][nt] the n occupancies in increasing order
     float *G;        // [D][HX_TAB] first-room table
     int *meta;       // [D][8] what the scoring kernel reads first of an instance: n, m (+flag), capacity, used, batch, flops, hbm
 };
 
+// Workgroup d: everything the scoring kernel needs of instance d -- its timeline, built in LDS; the timeline's
+// stretches of non-increasing occupancy; where that is small enough, the first-room table; a record of the
+// instance's sizes and decode terms -- and the free calls among the d-th slice of the queue, in order.
 __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, TlOut o, int nt)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -390,7 +392,6 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
     if (my_place >= 0) a.free_c[d * a.per + my_place] = c_lo + tid;
     if (tid == 0) {
         o.n[d] = n;
-        o.m[d] = table ? (m | HX_TAB_FLAG) : m;
         if (a.lock) a.n_free[d] = n_free;
         int *meta = o.meta + 8 * d;
         meta[0] = n; meta[1] = table ? (m | HX_TAB_FLAG) : m; meta[2] = a.d_cap[d]; meta[3] = a.d_used[d]; meta[4] = a.d_batch[d];
@@ -1067,8 +1068,8 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         if (tl_need > ctx->dtl_cap) {
             if (ctx->d_dtl) { HX_HIP(ctx, hipFree(ctx->d_dtl)); ctx->d_dtl = nullptr; ctx->dtl_cap = 0; }
             // per entry: (time, occupancy) and (head time, head rank) 8 bytes each, sorted occupancy and stretch head 4
-            // each, source 2; per instance three counts and a record of eight words
-            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 26 + (3 + 8) * (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
+            // each, source 2; per instance two counts and a record of eight words
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 26 + (2 + 8) * (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
             ctx->dtl_cap = tl_need;
         }
         if (D > ctx->dtab_cap) {
@@ -1086,7 +1087,6 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         o.e = (int2 *)p;        p += cap * 8;
         o.head = (int2 *)p;     p += cap * 8;
         o.n = (int *)p;         p += (size_t)HX_MAX_INSTANCES * sizeof(int);
-        o.m = (int *)p;         p += (size_t)HX_MAX_INSTANCES * sizeof(int);
         n_free = (int32_t *)p;  p += (size_t)HX_MAX_INSTANCES * sizeof(int);
         o.meta = (int *)p;      p += 8 * (size_t)HX_MAX_INSTANCES * sizeof(int);
         o.sorted = (int *)p;    p += cap * 4;
