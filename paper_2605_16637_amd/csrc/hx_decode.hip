@@ -272,7 +272,7 @@ struct TlOut {
     int2 *head;      // [D][nt] per stretch: (time of its head, rank of the head's occupancy), padded with (-inf, 0)
     int *sorted;     // [D][nt] the n occupancies in increasing order
     float *G;        // [D][HX_TAB] first-room table
-    int *meta;       // [D][8] what the scoring kernel reads first of an instance: n, m (+flag), capacity, used, batch, flops, hbm
+    int *meta;       // [D][8] what the scoring kernel reads first of an instance: n, m (+flag), capacity, decode terms c1, c2, kB
 };
 
 // Workgroup d: everything the scoring kernel needs of instance d -- its timeline, built in LDS; the timeline's
@@ -393,9 +393,11 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
     if (tid == 0) {
         o.n[d] = n;
         if (a.lock) a.n_free[d] = n_free;
+        // the instance's decode terms are the same for every call: worked out here, once
+        const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, 1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
         int *meta = o.meta + 8 * d;
-        meta[0] = n; meta[1] = table ? (m | HX_TAB_FLAG) : m; meta[2] = a.d_cap[d]; meta[3] = a.d_used[d]; meta[4] = a.d_batch[d];
-        meta[5] = __float_as_int(a.d_flops[d]); meta[6] = __float_as_int(a.d_hbm[d]); meta[7] = 0;
+        meta[0] = n; meta[1] = table ? (m | HX_TAB_FLAG) : m; meta[2] = a.d_cap[d];
+        meta[3] = __float_as_int(x.c1); meta[4] = __float_as_int(x.c2); meta[5] = __float_as_int(x.kB); meta[6] = 0; meta[7] = 0;
     }
     if (!table) return;
     for (int i = tid; i < n; i += blockDim.x) o.sorted[(size_t)d * nt + i] = sorted[i];
@@ -545,8 +547,8 @@ typedef int HxMetaRec __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(4))) const HxMetaRec *hx_meta_cp;
 
 struct HxInst {
-    int n, m_flag, cap, used, batch;
-    float flops, hbm;
+    int n, m_flag, cap;
+    float c1, c2, kB;              // the instance's part of the decode time of a call (hx_decode_terms)
     __device__ __forceinline__ int m() const { return m_flag & (HX_TAB_FLAG - 1); }
     // with the table: a few operations per stretch.  Else few long stretches: search them; many short ones
     // (most entries are starts): the plain scan, straight from memory.
@@ -558,8 +560,8 @@ __device__ __forceinline__ HxInst hx_inst_load(const TlOut &o, int d)
 {
     const HxMetaRec r = ((hx_meta_cp)(unsigned long long)o.meta)[d];
     HxInst it;
-    it.n = r[0]; it.m_flag = r[1]; it.cap = r[2]; it.used = r[3]; it.batch = r[4];
-    it.flops = __int_as_float(r[5]); it.hbm = __int_as_float(r[6]);
+    it.n = r[0]; it.m_flag = r[1]; it.cap = r[2];
+    it.c1 = __int_as_float(r[3]); it.c2 = __int_as_float(r[4]); it.kB = __int_as_float(r[5]);
     return it;
 }
 
@@ -693,8 +695,7 @@ __global__ __launch_bounds__(DS_THREADS) void hx_decode_score_kernel(DecodeArgs 
         hx_inst_stage(s_buf, o, d, nt, cur, tid);
         const HxInst nxt = hx_inst_load(o, min(d + 1, d_hi - 1));
         __syncthreads();
-        const HxDecF x = hx_decode_terms(a.m, cur.used, cur.batch, 0, 1.0f / cur.flops, 1.0f / cur.hbm);
-        const float T = hx_decode_time(cf, x.c1, x.c2, x.kB);
+        const float T = hx_decode_time(cf, cur.c1, cur.c2, cur.kB);
         const long long room = (long long)cur.cap - need;
         const int thr = room < 0 ? -1 : (room > (long long)INT_MAX ? INT_MAX : (int)room);
         const int n = cur.n, m = cur.m();
