@@ -229,21 +229,23 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, int d
 
 // ---- materialised tensor ------------------------------------------------------------
 
-// One block per call.  LDS: prefill finish per instance, decode time and
-// availability per instance (original order), class of each side.
-__global__ __launch_bounds__(256) void hx_materialise_kernel(ScoreArgs a)
+// A workgroup takes nc calls at a time (nc = 4 on small pools, where one call's share of the tensor is a few
+// KB and the barriers and the per-call tables would otherwise cost as much as the stores; 1 on large ones).
+// LDS: per call of the batch the prefill finish per instance, the decode time per instance and the class-pair
+// transfer times, each worked out by 256 / nc threads; beside them what does not depend on the call (waits,
+// per-token terms, classes; original instance order), staged once per workgroup.
+__global__ __launch_bounds__(256) void hx_materialise_kernel(ScoreArgs a, int nc)
 {
     extern __shared__ __align__(16) float smem[];
     const HxPrepTables *__restrict__ t = a.prep;
     const int P4 = (a.P + 3) & ~3, D4 = (a.D + 3) & ~3;      // every array starts on a 16-byte boundary
-    float *s_done = smem;                       // [P]  per call
-    float *s_dec = s_done + P4;                 // [D]  per call
-    float *s_wait = s_dec + D4;                 // [D]
+    float *s_done = smem;                       // [nc][P4] per call
+    float *s_dec = s_done + nc * P4;            // [nc][D4] per call
+    float *s_x = s_dec + nc * D4;               // [nc][kT*kT] per call
+    float *s_wait = s_x + nc * kT * kT;         // [D]
     int *s_ptype = (int *)(s_wait + D4);        // [P]
     int *s_dtype = s_ptype + P4;                // [D]
-    float *s_x = (float *)(s_dtype + D4);       // [kT*kT] per call
-    // what does not depend on the call, staged once per workgroup
-    float *s_pw = s_x + kT * kT;                // [P] prefill wait, 1/F, 1/B
+    float *s_pw = (float *)(s_dtype + D4);      // [P] prefill wait, 1/F, 1/B
     float *s_pF = s_pw + P4;
     float *s_pB = s_pF + P4;
     float *s_c1 = s_pB + P4;                    // [D] decode per-token terms and free tokens, by instance
@@ -264,48 +266,59 @@ __global__ __launch_bounds__(256) void hx_materialise_kernel(ScoreArgs a)
         s_wait[d] = t->dec_wait[e]; s_dtype[d] = t->dec_type[e];
     }
     if (tid < kT * kT) { s_lbw[tid] = t->link_invbw[tid]; s_llat[tid] = t->link_lat[tid]; }
-    for (int c = blockIdx.x; c < a.C; c += gridDim.x) {
-        const int L = a.L_in[c], O = a.L_out[c];
+    // the part of the workgroup that works out the tables of one call of the batch
+    const int per_call = blockDim.x / nc;
+    const int slot = tid / per_call, tq = tid - slot * per_call;
+    for (int c0 = blockIdx.x * nc; c0 < a.C; c0 += gridDim.x * nc) {
+        const int cs = c0 + slot;
+        const bool live = cs < a.C;
+        const int L = live ? a.L_in[cs] : 0, O = live ? a.L_out[cs] : 0;
         const HxCallF cf = hx_call_terms(a.m, L, O);
         __syncthreads();
-        for (int p = tid; p < a.P; p += blockDim.x) s_done[p] = hx_prefill_done(cf, s_pw[p], s_pF[p], s_pB[p]);
-        for (int d = tid; d < a.D; d += blockDim.x) {
-            const bool fits = hx_fits(L, O, s_free[d]);
-            s_dec[d] = fits ? hx_decode_time(cf, s_c1[d], s_c2[d], s_kB[d]) : INFINITY;
-            if (a.feas) a.feas[(size_t)c * a.D + d] = fits ? 1 : 0;
+        if (live) {
+            for (int p = tq; p < a.P; p += per_call) s_done[slot * P4 + p] = hx_prefill_done(cf, s_pw[p], s_pF[p], s_pB[p]);
+            for (int d = tq; d < a.D; d += per_call) {
+                const bool fits = hx_fits(L, O, s_free[d]);
+                s_dec[slot * D4 + d] = fits ? hx_decode_time(cf, s_c1[d], s_c2[d], s_kB[d]) : INFINITY;
+                if (a.feas) a.feas[(size_t)cs * a.D + d] = fits ? 1 : 0;
+            }
+            for (int i = tq; i < kT * kT; i += per_call) s_x[slot * kT * kT + i] = hx_transfer(cf, s_lbw[i], s_llat[i]);
         }
-        if (tid < kT * kT) s_x[tid] = hx_transfer(cf, s_lbw[tid], s_llat[tid]);
         __syncthreads();
         if (a.cost) {
-            float *out = a.cost + (size_t)c * a.P * a.D;
-            // (p, d) of the elements a thread writes advance without a division: by blockDim positions at a time
-            if (vec4) {
-                // four neighbouring decode instances per step, one 16-byte store
-                const int dq = a.D >> 2;
-                const int step_p = blockDim.x / dq, step_q = blockDim.x % dq;
-                int p = tid / dq, q = tid - p * dq;
-                for (; p < a.P; p += step_p) {
-                    const float done = s_done[p];
-                    const float *xr = s_x + s_ptype[p] * kT;
-                    const float4 w = reinterpret_cast<const float4 *>(s_wait)[q];
-                    const float4 t = reinterpret_cast<const float4 *>(s_dec)[q];
-                    const int4 k = reinterpret_cast<const int4 *>(s_dtype)[q];
-                    float4 v;
-                    v.x = hx_candidate(done + xr[k.x], w.x, t.x);
-                    v.y = hx_candidate(done + xr[k.y], w.y, t.y);
-                    v.z = hx_candidate(done + xr[k.z], w.z, t.z);
-                    v.w = hx_candidate(done + xr[k.w], w.w, t.w);
-                    reinterpret_cast<float4 *>(out + (size_t)p * a.D)[q] = v;
-                    q += step_q;
-                    if (q >= dq) { q -= dq; ++p; }
-                }
-            } else {
-                const int step_p = blockDim.x / a.D, step_d = blockDim.x % a.D;
-                int p = tid / a.D, d = tid - p * a.D;
-                for (; p < a.P; p += step_p) {
-                    out[(size_t)p * a.D + d] = hx_candidate(s_done[p] + s_x[s_ptype[p] * kT + s_dtype[d]], s_wait[d], s_dec[d]);
-                    d += step_d;
-                    if (d >= a.D) { d -= a.D; ++p; }
+            const int n_here = min(nc, a.C - c0);
+            for (int s = 0; s < n_here; ++s) {
+                float *out = a.cost + (size_t)(c0 + s) * a.P * a.D;
+                const float *done_s = s_done + s * P4, *dec_s = s_dec + s * D4, *x_s = s_x + s * kT * kT;
+                // (p, d) of the elements a thread writes advance without a division: by blockDim positions at a time
+                if (vec4) {
+                    // four neighbouring decode instances per step, one 16-byte store
+                    const int dq = a.D >> 2;
+                    const int step_p = blockDim.x / dq, step_q = blockDim.x % dq;
+                    int p = tid / dq, q = tid - p * dq;
+                    for (; p < a.P; p += step_p) {
+                        const float done = done_s[p];
+                        const float *xr = x_s + s_ptype[p] * kT;
+                        const float4 w = reinterpret_cast<const float4 *>(s_wait)[q];
+                        const float4 tm = reinterpret_cast<const float4 *>(dec_s)[q];
+                        const int4 k = reinterpret_cast<const int4 *>(s_dtype)[q];
+                        float4 v;
+                        v.x = hx_candidate(done + xr[k.x], w.x, tm.x);
+                        v.y = hx_candidate(done + xr[k.y], w.y, tm.y);
+                        v.z = hx_candidate(done + xr[k.z], w.z, tm.z);
+                        v.w = hx_candidate(done + xr[k.w], w.w, tm.w);
+                        reinterpret_cast<float4 *>(out + (size_t)p * a.D)[q] = v;
+                        q += step_q;
+                        if (q >= dq) { q -= dq; ++p; }
+                    }
+                } else {
+                    const int step_p = blockDim.x / a.D, step_d = blockDim.x % a.D;
+                    int p = tid / a.D, d = tid - p * a.D;
+                    for (; p < a.P; p += step_p) {
+                        out[(size_t)p * a.D + d] = hx_candidate(done_s[p] + x_s[s_ptype[p] * kT + s_dtype[d]], s_wait[d], dec_s[d]);
+                        d += step_d;
+                        if (d >= a.D) { d -= a.D; ++p; }
+                    }
                 }
             }
         }
@@ -525,9 +538,12 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         if (int rc = hx_check_launch(ctx, "hx_fused_search_kernel")) return rc;
     }
     if (cost || feas) {
-        const size_t lds = 4 * ((size_t)5 * ((P + 3) & ~3) + 7 * ((D + 3) & ~3) + 3 * kT * kT);
-        const int grid = C < ctx->num_cu * 8 ? C : ctx->num_cu * 8;
-        hx_materialise_kernel<<<grid, 256, lds, stream>>>(a);
+        const int P4 = (P + 3) & ~3, D4 = (D + 3) & ~3;
+        const int nc = (long long)P * D <= 16384 && C >= 4 * ctx->num_cu * 4 ? 4 : 1;      // calls per workgroup at a time
+        const size_t lds = 4 * ((size_t)nc * (P4 + D4 + kT * kT) + 4 * P4 + 6 * D4 + 2 * kT * kT);
+        const int batches = (C + nc - 1) / nc;
+        const int grid = batches < ctx->num_cu * 8 ? batches : ctx->num_cu * 8;
+        hx_materialise_kernel<<<grid, 256, lds, stream>>>(a, nc);
         if (int rc = hx_check_launch(ctx, "hx_materialise_kernel")) return rc;
     }
     return HX_OK;
