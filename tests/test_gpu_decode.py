@@ -381,6 +381,21 @@ def test_decode_greedy_matches_oracle(ctx, Q, D, stride, res, plan, lockf, seed)
     assert (got["best_start"][got["best_d"] >= 0] > 0).any()
 
 
+def test_decode_greedy_at_the_benchmarks_size(ctx):
+    # the queue bench.py times: 256 calls x 32 instances, 24 resident + 4 planned entries each, lists of 140 entries
+    Q, D = 256, 32
+    r, lock, iv = synth.make_decode_round("decode_tiny", 2, n_wf=64, Q=Q, D=D, T=4, stride=28, n_resident=24, n_planned=4)
+    L, O = r.calls["L_in"], r.calls["L_out"]
+    rng = np.random.default_rng(1)
+    node = np.arange(Q, dtype=np.int32); wf = (np.arange(Q) % 8).astype(np.int32)
+    tail = rng.uniform(0, 5, Q).astype(np.float32); hor = rng.uniform(10, 60, 8).astype(np.float32)
+    elapsed = rng.uniform(0, 30, Q).astype(np.float32)
+    big = widen(iv, D, 140 - 28)
+    got = run_plan(ctx, r.model, L, O, lock, node, wf, elapsed, tail, hor, r.dec, big)
+    check_plan_stepwise(r.model, L, O, lock, node, wf, elapsed, tail, hor, r.dec, big, got)
+    assert sorted(got["rank"]) == list(range(Q)) and (got["best_d"] >= 0).mean() > 0.9
+
+
 def test_decode_greedy_hand_worked_and_limits(ctx):
     from paper_2605_16637_amd import binding
     from helpers import ROUND_MODEL
