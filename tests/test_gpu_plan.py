@@ -102,7 +102,9 @@ def check_plan_stepwise(model, L, O, elapsed, node, wf, tail, hor, pre, dec, lin
 
 
 @pytest.mark.parametrize("C,P,D,T,seed", [(3, 2, 2, 2, 1), (24, 8, 8, 3, 2), (64, 8, 10, 3, 3), (40, 64, 64, 4, 4),
-                                          (130, 20, 33, 8, 5), (16, 256, 256, 8, 6)])
+                                          (130, 20, 33, 8, 5), (16, 256, 256, 8, 6),
+                                          # the queue and pool bench.py times
+                                          (256, 64, 64, 4, 7)])
 def test_greedy_plan_matches_oracle(ctx, C, P, D, T, seed):
     rng = np.random.default_rng(70 + seed)
     model = synth.MODEL
