@@ -227,7 +227,7 @@ struct GreedyLds {
              + P + 7 * (size_t)D                               // simulated state and what is needed to re-derive an entry
              + 5 * (size_t)C                                   // per call: pair, cost, ratio, flags
              + 4 * GREEDY_WAVES                                // reduction scratch
-             + (size_t)GREEDY_WAVES * (2 * Dp + kT * kT);      // per-wave search buffers
+             + (size_t)GREEDY_WAVES * (2 * Dp + kT * kT + kT); // per-wave search buffers
     }
 };
 
@@ -280,8 +280,9 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     const int tid = threadIdx.x;
     const int lane = tid & (HX_WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    float2 *wbuf = (float2 *)(s_wave + (size_t)wave * (2 * lay.Dp + kT * kT));
+    float2 *wbuf = (float2 *)(s_wave + (size_t)wave * (2 * lay.Dp + kT * kT + kT));
     float *xbuf = (float *)(wbuf + lay.Dp);
+    float *rbuf = xbuf + kT * kT;
 
     for (int e = tid; e < Dp; e += GREEDY_THREADS) {
         s_wait[e] = t->dec_wait[e]; s_c1[e] = t->dec_c1[e]; s_c2[e] = t->dec_c2[e]; s_kB[e] = t->dec_kB[e];
@@ -315,7 +316,11 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         // (1) score the calls whose pair may have changed, on the simulated state
         for (int c = wave; c < a.C; c += GREEDY_WAVES) {
             if (s_flags[c] != (ALIVE | DIRTY)) continue;           // wave-uniform: c depends on the wave only
-            const HxBest b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
+            // large pools: class by class (KP = 0); small ones: pair by pair, whose inner loop costs less than the
+            // class search's reductions up to about 64 x 64 pairs
+            HxBest b;
+            if constexpr (KP == 0) b = hx_search_call_by_class<true>(a.m, pool, wbuf, xbuf, rbuf, a.L_in[c], a.L_out[c], lane);
+            else b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
             if (lane == 0) {
                 s_bp[c] = b.p; s_bd[c] = b.d; s_bc[c] = b.cost;
                 s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf,
@@ -418,7 +423,10 @@ __global__ __launch_bounds__(256) void hx_copy_i32_kernel(const int32_t *src, in
 int hx_plan_init()
 {
     const int lds = 160 * 1024;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<1>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<0>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<1>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_plan_greedy_kernel<2>),
@@ -524,7 +532,8 @@ extern "C" int hx_plan_greedy(hx_ctx *ctx, const hx_model *model, const hx_calls
     const GreedyLds lay(dp_bound, P, D, C);
     const size_t lds = 4 * lay.words();
     HX_REQUIRE(ctx, lds <= 160 * 1024, HX_ERR_SHAPE, "queue and pool need %zu B of LDS", lds);
-    if (P <= 64) hx_plan_greedy_kernel<1><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
+    if ((long long)P * D > 64 * 64) hx_plan_greedy_kernel<0><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
+    else if (P <= 64) hx_plan_greedy_kernel<1><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
     else if (P <= 128) hx_plan_greedy_kernel<2><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
     else hx_plan_greedy_kernel<4><<<1, GREEDY_THREADS, lds, stream>>>(a, dp_bound);
     return hx_check_launch(ctx, "hx_plan_greedy_kernel");

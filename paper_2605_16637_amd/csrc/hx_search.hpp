@@ -157,6 +157,96 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
     return out;
 }
 
+// The same result -- the lexicographic minimum of (cost, p, d) over the whole pool, bit for bit -- found
+// class by class instead of pair by pair (for planners, which need the result, not the P x D costs).
+// A candidate's cost is max(done_p + x[class_p][class_d], avail_d) + dec_d, non-decreasing in its first
+// operand, and that operand depends on the decode instance through its class only: so the minimum over p
+// for a decode entry is max(r[class_d], avail_d) + dec_d with r[k] = min over p of done_p + x[class_p][k],
+// exactly (max and min round nothing, and the one addition is applied to the same operands).  P x T
+// additions for r, D candidates, and for the (usually one) entry that attains the minimum a pass over p to
+// find the lowest prefill instance that attains it there.
+// wbuf, xbuf as in hx_search_call; rbuf: the wave's [HX_MAX_TYPES] floats.
+template <bool REFRESH_WAIT>
+__device__ __forceinline__ HxBest hx_search_call_by_class(const HxModelF &m, const HxPoolLds &s, float2 *wbuf, float *xbuf,
+                                                          float *rbuf, int L, int O, int lane)
+{
+    constexpr int kT = HX_MAX_TYPES;
+    const HxCallF cf = hx_call_terms(m, L, O);
+    const int Dp = s.Dp;
+    for (int e = lane; e < Dp; e += HX_WAVE) {
+        if (REFRESH_WAIT) wbuf[e].x = s.wait[e];
+        wbuf[e].y = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
+    }
+    xbuf[lane] = hx_transfer(cf, s.invbw[lane], s.lat[lane]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // r[k]: the earliest the call's KV can be at an instance of decode class k
+    float r[kT];
+#pragma unroll
+    for (int k = 0; k < kT; ++k) r[k] = INFINITY;
+    for (int chunk = 0; chunk < s.P; chunk += HX_WAVE) {
+        const int p = min(chunk + lane, s.Pp - 1);
+        const float done = chunk + lane < s.P ? hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]) : INFINITY;
+        const float *xr = xbuf + s.ptype[p] * kT;
+#pragma unroll
+        for (int k = 0; k < kT; ++k) r[k] = fminf(r[k], done + xr[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < kT; ++k) r[k] = hx_wave_min(r[k]);
+    if (lane < kT) {
+        float mine = r[0];
+#pragma unroll
+        for (int k = 1; k < kT; ++k) mine = lane == k ? r[k] : mine;
+        rbuf[lane] = mine;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    float bv = INFINITY;
+    for (int e = lane; e < Dp; e += HX_WAVE) {
+        const float2 q = wbuf[e];
+        bv = fminf(bv, hx_candidate(rbuf[s.dtype[e] & (kT - 1)], q.x, q.y));
+    }
+    bv = hx_wave_min(bv);
+    HxBest out{bv, -1, -1};
+    if (bv < INFINITY) {
+        int best_p = 0x7fffffff, best_d = 0x7fffffff;
+        for (int e0 = 0; e0 < Dp; e0 += HX_WAVE) {
+            const int e = e0 + lane;
+            bool hit = false;
+            if (e < Dp) {
+                const float2 q = wbuf[e];
+                hit = s.orig[e] >= 0 && hx_candidate(rbuf[s.dtype[e] & (kT - 1)], q.x, q.y) == bv;
+            }
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(hit);
+            while (todo) {
+                const int ee = e0 + __builtin_ctzll(todo);          // an entry that attains the minimum (wave-uniform)
+                todo &= todo - 1;
+                const float2 q = wbuf[ee];
+                const int k = s.dtype[ee] & (kT - 1);
+                int p_low = 0x7fffffff;
+                for (int chunk = 0; chunk < s.P; chunk += HX_WAVE) {
+                    const int p = min(chunk + lane, s.Pp - 1);
+                    const float done = hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]);
+                    const float v = hx_candidate(done + xbuf[s.ptype[p] * kT + k], q.x, q.y);
+                    if (chunk + lane < s.P && v == bv) p_low = min(p_low, chunk + lane);
+                }
+                p_low = hx_wave_min(p_low);
+                const int d = s.orig[ee];
+                if (p_low < best_p || (p_low == best_p && d < best_d)) { best_p = p_low; best_d = d; }
+            }
+        }
+        out.p = best_p; out.d = best_d;
+    }
+    // the next call of this wave rewrites the buffers: order its writes after these reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return out;
+}
+
 // Cost of one pair (prefill instance p, decode entry e) for a call, by the same functions in the same
 // order as the search above, hence bit-identical to what the search computes for that pair.
 __device__ __forceinline__ float hx_pair_cost(const HxModelF &m, const HxPoolLds &s, int L, int O, int p, int e)

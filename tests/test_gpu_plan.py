@@ -104,7 +104,9 @@ def check_plan_stepwise(model, L, O, elapsed, node, wf, tail, hor, pre, dec, lin
 @pytest.mark.parametrize("C,P,D,T,seed", [(3, 2, 2, 2, 1), (24, 8, 8, 3, 2), (64, 8, 10, 3, 3), (40, 64, 64, 4, 4),
                                           (130, 20, 33, 8, 5), (16, 256, 256, 8, 6),
                                           # the queue and pool bench.py times
-                                          (256, 64, 64, 4, 7)])
+                                          (256, 64, 64, 4, 7),
+                                          # pools searched class by class (more than 64 x 64 pairs)
+                                          (60, 100, 90, 5, 8), (48, 70, 256, 3, 9)])
 def test_greedy_plan_matches_oracle(ctx, C, P, D, T, seed):
     rng = np.random.default_rng(70 + seed)
     model = synth.MODEL
@@ -141,6 +143,33 @@ def test_greedy_hand_worked_conflict_on_gpu(ctx):
     assert gc[1] == pytest.approx(G["greedy_A_cost"], rel=REL) and gc[0] == pytest.approx(G["greedy_B_cost"], rel=REL)
     assert gr[1] == pytest.approx(G["greedy_A_ratio"], rel=REL) and gr[0] == pytest.approx(G["greedy_B_ratio"], rel=REL)
     assert list(bl) == [1000, 1000] and list(us) == [2200] and list(qd) == [200] and list(ba) == [2]
+
+
+@pytest.mark.parametrize("P,D", [(6, 5), (96, 80)])
+def test_greedy_breaks_exact_ties_by_lowest_index(ctx, P, D):
+    # identical instances on both sides (two classes, all of a class in the same state): every call sees exact ties
+    # over many pairs; the plan has to be the oracle's pair for pair, the lowest (p, d) among equals at every step --
+    # on a small pool (searched pair by pair) and on a large one (searched class by class)
+    rng = np.random.default_rng(P)
+    C = 40
+    tp, td = (np.arange(P) % 2).astype(np.int32), (np.arange(D) % 2).astype(np.int32)
+    F, B = np.array([4e14, 1e15], np.float32), np.array([2e12, 3.3e12], np.float32)
+    pre = dict(flops=F[tp], hbm_bw=B[tp], backlog_tok=np.zeros(P, np.int32), type=tp)
+    dec = dict(flops=F[td], hbm_bw=B[td], used_tok=np.full(D, 4096, np.int32), cap_tok=np.full(D, 10**6, np.int32),
+               batch=np.full(D, 2, np.int32), qd_tok=np.zeros(D, np.int32), type=td)
+    links = dict(n_types=2, bw=np.array([[5e10, 2.5e10], [2.5e10, 1e11]], np.float32), latency=np.zeros((2, 2), np.float32))
+    L, O = synth.gen_lengths(rng, C)
+    elapsed = rng.uniform(0, 20, C).astype(np.float32)
+    node = np.arange(C, dtype=np.int32); wf = (np.arange(C) % 4).astype(np.int32)
+    tail = rng.uniform(0, 5, C).astype(np.float32); hor = rng.uniform(5, 50, 4).astype(np.float32)
+    got = run_greedy(ctx, synth.MODEL, L, O, elapsed, node, wf, tail, hor, pre, dec, links)
+    want = o.plan_greedy(synth.MODEL, L, O, elapsed, node, wf, tail, hor, pre, dec, links)
+    assert np.array_equal(got[4], want.rank)
+    assert np.array_equal(got[0], want.best_p) and np.array_equal(got[1], want.best_d)
+    assert_costs_close(got[2], want.best_cost, "plan cost")
+    # the first call placed had the whole pool to choose from, all instances of a class equal: it took the first of its classes
+    first = int(np.argmin(got[4]))
+    assert got[0][first] < 2 and got[1][first] < 2
 
 
 def test_planner_limits_and_empty_inputs(ctx):
