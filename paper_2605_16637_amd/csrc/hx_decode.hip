@@ -796,7 +796,7 @@ struct DGreedyLds {
     __host__ __device__ size_t off_src() const { return off_tl() + hx_align16((size_t)D * nt * 8); }
     __host__ __device__ size_t off_inst() const { return off_src() + hx_align16((size_t)D * ne * 2); }
     __host__ __device__ size_t off_call() const { return off_inst() + (size_t)6 * D * 4; }
-    __host__ __device__ size_t off_red() const { return off_call() + (size_t)5 * Q * 4; }
+    __host__ __device__ size_t off_red() const { return off_call() + (size_t)11 * Q * 4; }
     __host__ __device__ size_t off_mat() const { return hx_align16(off_red() + (size_t)(2 * DG_WAVES + 8) * 4); }
     __host__ __device__ size_t bytes() const { return off_mat(); }
     // with the finish of every (instance, call) pair kept: [D][Q] floats more
@@ -829,6 +829,12 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     float *s_bc = s_bs + lay.Q;
     float *s_ratio = s_bc + lay.Q;
     int *s_flags = (int *)(s_ratio + lay.Q);
+    int *s_L = s_flags + lay.Q;                            // what the queue says of a call, read once
+    int *s_O = s_L + lay.Q;
+    int *s_lk = s_O + lay.Q;
+    float *s_el = (float *)(s_lk + lay.Q);
+    float *s_tail = s_el + lay.Q;                          // tail of its node, horizon of its workflow (NaN: index out of range)
+    float *s_hz = s_tail + lay.Q;
     float *s_redv = (float *)(smem + lay.off_red());
     int *s_redi = (int *)(s_redv + DG_WAVES);
     int *s_pick = s_redi + DG_WAVES;
@@ -846,7 +852,15 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, 1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
         s_c1[d] = x.c1; s_c2[d] = x.c2; s_kB[d] = x.kB;
     }
-    for (int c = tid; c < a.Q; c += DG_THREADS) s_flags[c] = DG_ALIVE | DG_DIRTY;
+    for (int c = tid; c < a.Q; c += DG_THREADS) {
+        s_flags[c] = DG_ALIVE | DG_DIRTY;
+        s_L[c] = a.L_in[c]; s_O[c] = a.L_out[c]; s_lk[c] = a.lock ? a.lock[c] : -1; s_el[c] = a.elapsed[c];
+        const int nd = a.node[c], w = a.wf[c];
+        const bool ok = nd >= 0 && nd < a.n_nodes && w >= 0 && w < a.n_wf;
+        if (!ok) hx_raise(a.status, HX_ERR_INDEX);
+        s_tail[c] = ok ? a.tail[nd] : __uint_as_float(0x7fc00000u);
+        s_hz[c] = ok ? a.horizon[w] : __uint_as_float(0x7fc00000u);
+    }
     __syncthreads();
     for (int d = 0; d < a.D; ++d) {
         const size_t at = (size_t)d * a.stride;
@@ -858,8 +872,8 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         // (1) score the calls whose instance changed (keep_all: every call, once): one wavefront per call, lanes over instances
         for (int c = wave; c < a.Q && (!keep_all || k == 0); c += DG_WAVES) {
             if (s_flags[c] != (DG_ALIVE | DG_DIRTY)) continue;     // wave-uniform
-            const int L = a.L_in[c], O = a.L_out[c];
-            const int lk = a.lock ? a.lock[c] : -1;
+            const int L = s_L[c], O = s_O[c];
+            const int lk = s_lk[c];
             float bv = INFINITY, bS = INFINITY;
             int bd = INT_MAX;
             for (int d0 = 0; d0 < a.D; d0 += HX_WAVE) {
@@ -883,8 +897,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 s_bd[c] = any ? best_d : -1;
                 s_bs[c] = any ? best_S : INFINITY;
                 s_bc[c] = any ? best : INFINITY;
-                s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c,
-                                                any ? best : INFINITY, a.status);
+                s_ratio[c] = ((s_el[c] + (any ? best : INFINITY)) + s_tail[c]) / s_hz[c];       // Eq. (2), as hx_projected_ratio forms it
                 s_flags[c] = DG_ALIVE;
             }
         }
@@ -920,7 +933,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 // its best may have moved since its start was last written: the start on the instance it has now
                 HxDecF x;
                 x.wait = 0.0f; x.c1 = s_c1[d]; x.c2 = s_c2[d]; x.kB = s_kB[d];
-                const HxDecodeCand q = hx_decode_candidate(a.m, a.L_in[c], a.L_out[c], -1, d, a.D, x, s_cap[d], a.status);
+                const HxDecodeCand q = hx_decode_candidate(a.m, s_L[c], s_O[c], -1, d, a.D, x, s_cap[d], a.status);
                 s_bs[c] = hx_earliest_start(s_tl + (size_t)d * lay.nt, s_src + (size_t)d * lay.ne, s_n[d], q.thr, q.T, true).S;
             }
             a.best_d[c] = d; a.best_start[c] = s_bs[c]; a.best_cost[c] = s_bc[c]; a.ratio[c] = s_ratio[c]; a.rank[c] = k;
@@ -931,7 +944,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                     hx_raise(a.status, HX_ERR_CAPACITY);
                 } else {
                     const size_t at = (size_t)d * a.stride + s_cnt[d];
-                    const long long need = (long long)a.L_in[c] + (long long)a.L_out[c];
+                    const long long need = (long long)s_L[c] + (long long)s_O[c];
                     a.iv_start[at] = s_bs[c];
                     a.iv_end[at] = s_bc[c];
                     a.iv_tok[at] = need > (long long)INT_MAX ? INT_MAX : (int)need;
@@ -959,8 +972,8 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 for (int base = 0; base < a.Q; base += DG_THREADS) {
                     const int c = base + tid;
                     const bool live = c < a.Q && (s_flags[c] & DG_ALIVE);
-                    const int L = live ? a.L_in[c] : 0, O = live ? a.L_out[c] : 0;
-                    const int lk = (live && a.lock) ? a.lock[c] : -1;
+                    const int L = live ? s_L[c] : 0, O = live ? s_O[c] : 0;
+                    const int lk = live ? s_lk[c] : -1;
                     const HxDecodeCand q = hx_decode_candidate(a.m, L, O, live ? lk : -1, pd, a.D, x, cap, a.status);
                     const HxSlot s = hx_earliest_start(tl.e, tl.src, n, q.thr, q.T, live && q.legal);
                     if (live) {
@@ -975,7 +988,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                             }
                             s_bd[c] = bd;
                             s_bc[c] = bv;
-                            s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, bv, a.status);
+                            s_ratio[c] = ((s_el[c] + bv) + s_tail[c]) / s_hz[c];
                         }
                     }
                 }

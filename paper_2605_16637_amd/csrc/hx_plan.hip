@@ -225,7 +225,7 @@ struct GreedyLds {
     {
         return (size_t)7 * Dp + 4 * Pp + 2 * kT * kT + 16     // pool view, as in the fused search
              + P + 7 * (size_t)D                               // simulated state and what is needed to re-derive an entry
-             + 5 * (size_t)C                                   // per call: pair, cost, ratio, flags
+             + 10 * (size_t)C                                  // per call: pair, cost, ratio, flags; lengths, elapsed, tail, horizon
              + 4 * GREEDY_WAVES                                // reduction scratch
              + (size_t)GREEDY_WAVES * (2 * Dp + kT * kT + kT); // per-wave search buffers
     }
@@ -272,7 +272,12 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     float *s_bc = (float *)(s_bd + lay.C);
     float *s_ratio = s_bc + lay.C;
     int *s_flags = (int *)(s_ratio + lay.C);
-    float *s_redv = (float *)(s_flags + lay.C);        // reduction scratch, then the pick
+    int *s_L = s_flags + lay.C;                        // what the queue says of a call, read once
+    int *s_O = s_L + lay.C;
+    float *s_el = (float *)(s_O + lay.C);
+    float *s_tl = s_el + lay.C;                        // tail of its node, horizon of its workflow (NaN: index out of range)
+    float *s_hz = s_tl + lay.C;
+    float *s_redv = (float *)(s_hz + lay.C);           // reduction scratch, then the pick
     int *s_redi = (int *)(s_redv + GREEDY_WAVES);
     int *s_pick = s_redi + GREEDY_WAVES;               // [0] call, [1] p, [2] d
     float *s_wave = (float *)(s_pick + 2 * GREEDY_WAVES);
@@ -303,7 +308,15 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     }
     if (tid < kT * kT) { s_invbw[tid] = t->link_invbw[tid]; s_lat[tid] = t->link_lat[tid]; }
     if (tid <= kT) s_seg[tid] = t->seg[tid];
-    for (int c = tid; c < a.C; c += GREEDY_THREADS) s_flags[c] = ALIVE | DIRTY;
+    for (int c = tid; c < a.C; c += GREEDY_THREADS) {
+        s_flags[c] = ALIVE | DIRTY;
+        s_L[c] = a.L_in[c]; s_O[c] = a.L_out[c]; s_el[c] = a.elapsed[c];
+        const int nd = a.node[c], w = a.wf[c];
+        const bool ok = nd >= 0 && nd < a.n_nodes && w >= 0 && w < a.n_wf;
+        if (!ok) hx_raise(a.status, HX_ERR_INDEX);
+        s_tl[c] = ok ? a.tail[nd] : __uint_as_float(0x7fc00000u);
+        s_hz[c] = ok ? a.horizon[w] : __uint_as_float(0x7fc00000u);
+    }
     __syncthreads();
 
     int seg[kT + 1];
@@ -319,12 +332,11 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             // large pools: class by class (KP = 0); small ones: pair by pair, whose inner loop costs less than the
             // class search's reductions up to about 64 x 64 pairs
             HxBest b;
-            if constexpr (KP == 0) b = hx_search_call_by_class<true>(a.m, pool, wbuf, xbuf, rbuf, a.L_in[c], a.L_out[c], lane);
-            else b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
+            if constexpr (KP == 0) b = hx_search_call_by_class<true>(a.m, pool, wbuf, xbuf, rbuf, s_L[c], s_O[c], lane);
+            else b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, s_L[c], s_O[c], lane);
             if (lane == 0) {
                 s_bp[c] = b.p; s_bd[c] = b.d; s_bc[c] = b.cost;
-                s_ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf,
-                                                c, b.cost, a.status);
+                s_ratio[c] = ((s_el[c] + b.cost) + s_tl[c]) / s_hz[c];       // Eq. (2), as hx_projected_ratio forms it
                 s_flags[c] = ALIVE;
             }
         }
@@ -360,7 +372,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             s_flags[c] = 0;
             s_pick[0] = c; s_pick[1] = p; s_pick[2] = d;
             if (p >= 0) {
-                const int L = a.L_in[c], O = a.L_out[c];
+                const int L = s_L[c], O = s_O[c];
                 long long bl = (long long)s_backlog[p] + L, qd = (long long)s_qd[d] + O, us = (long long)s_used[d] + L + O;
                 if (L < 0 || O < 0) { hx_raise(a.status, HX_ERR_INDEX); bl = s_backlog[p]; qd = s_qd[d]; us = s_used[d]; }
                 if (bl > 2147483647LL || qd > 2147483647LL || us > 2147483647LL) {
@@ -388,7 +400,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             // the lexicographic minimum
             for (int c = tid; c < a.C; c += GREEDY_THREADS)
                 if ((s_flags[c] & ALIVE) && (s_bp[c] == pp || s_bd[c] == pd) &&
-                    hx_pair_cost(a.m, pool, a.L_in[c], a.L_out[c], s_bp[c], s_pos[s_bd[c]]) != s_bc[c])
+                    hx_pair_cost(a.m, pool, s_L[c], s_O[c], s_bp[c], s_pos[s_bd[c]]) != s_bc[c])
                     s_flags[c] = ALIVE | DIRTY;
         }
         __syncthreads();
