@@ -45,35 +45,36 @@ struct PrepArgs {
     int32_t *status;
 };
 
+// One workgroup of 1024 threads, one thread per instance of either side (at most HX_MAX_INSTANCES each).
+// Everything is read at the top and written at the bottom: the three barriers in between (class counts,
+// class segments) then wait for neither loads nor stores.
 __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
 {
     __shared__ int s_cnt[kT], s_seg[kT + 1];
+    __shared__ int s_wcnt[HX_MAX_INSTANCES / HX_WAVE][kT];
     const int tid = threadIdx.x;
+    const int lane = tid & (HX_WAVE - 1), wv = tid >> 6;
     HxPrepTables *o = a.out;
 
-    if (tid < kT * kT) {
-        int tp = tid / kT, td = tid % kT;
-        bool in = tp < a.T && td < a.T;
-        o->link_invbw[tid] = in ? 1.0f / a.bw[tp * a.T + td] : 0.0f;
-        o->link_lat[tid] = (in && a.lat) ? a.lat[tp * a.T + td] : 0.0f;
-    }
-    for (int p = tid; p < a.P; p += blockDim.x) {
-        int t = a.p_type[p];
-        if (t < 0 || t >= a.T) { hx_raise(a.status, HX_ERR_INDEX); t = 0; }
-        float invF = 1.0f / a.p_flops[p];
-        o->pre_invF[p] = invF;
-        o->pre_invB[p] = 1.0f / a.p_hbm[p];
-        o->pre_wait[p] = hx_prefill_wait(a.m, a.p_backlog[p], invF);
-        o->pre_type[p] = t;
-    }
-    // class of each decode instance, per-wave class counts (ballots), class segments
-    __shared__ int s_wcnt[HX_MAX_INSTANCES / HX_WAVE][kT];
-    const int lane = tid & (HX_WAVE - 1), wv = tid >> 6;
-    int my_t = -1;
-    if (tid < a.D) {
-        my_t = a.d_type[tid];
-        if (my_t < 0 || my_t >= a.T) { hx_raise(a.status, HX_ERR_INDEX); my_t = 0; }
-    }
+    // ---- reads
+    const bool has_link = tid < kT * kT;
+    const int tp = tid / kT, td = tid % kT;
+    const bool link_in = has_link && tp < a.T && td < a.T;
+    const float l_bw = link_in ? a.bw[tp * a.T + td] : 1.0f;
+    const float l_lat = (link_in && a.lat) ? a.lat[tp * a.T + td] : 0.0f;
+    const bool has_p = tid < a.P;
+    int p_t = has_p ? a.p_type[tid] : 0;
+    const float p_flops = has_p ? a.p_flops[tid] : 1.0f, p_hbm = has_p ? a.p_hbm[tid] : 1.0f;
+    const int p_backlog = has_p ? a.p_backlog[tid] : 0;
+    const bool has_d = tid < a.D;
+    int my_t = has_d ? a.d_type[tid] : -1;
+    const int d_used = has_d ? a.d_used[tid] : 0, d_batch = has_d ? a.d_batch[tid] : 0, d_qd = has_d ? a.d_qd[tid] : 0;
+    const int d_cap = has_d ? a.d_cap[tid] : 0;
+    const float d_flops = has_d ? a.d_flops[tid] : 1.0f, d_hbm = has_d ? a.d_hbm[tid] : 1.0f;
+    if (has_p && (p_t < 0 || p_t >= a.T)) { hx_raise(a.status, HX_ERR_INDEX); p_t = 0; }
+    if (has_d && (my_t < 0 || my_t >= a.T)) { hx_raise(a.status, HX_ERR_INDEX); my_t = 0; }
+
+    // ---- decode instances ranked by class: per-wave class counts (ballots), class sizes, class segments
     int my_rank = 0;                     // instances of my class before me in my wave
 #pragma unroll
     for (int t = 0; t < kT; ++t) {
@@ -100,12 +101,25 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
             e += (s_cnt[t] + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP;
         }
         s_seg[kT] = e;
-        for (int t = 0; t <= kT; ++t) o->seg[t] = s_seg[t];
-        o->n_entries = e;
     }
     __syncthreads();
+
+    // ---- writes
+    if (has_link) {
+        o->link_invbw[tid] = link_in ? 1.0f / l_bw : 0.0f;
+        o->link_lat[tid] = l_lat;
+    }
+    if (has_p) {
+        const float invF = 1.0f / p_flops;
+        o->pre_invF[tid] = invF;
+        o->pre_invB[tid] = 1.0f / p_hbm;
+        o->pre_wait[tid] = hx_prefill_wait(a.m, p_backlog, invF);
+        o->pre_type[tid] = p_t;
+    }
+    if (tid <= kT) o->seg[tid] = s_seg[tid];
     const int n_entries = s_seg[kT];
-    // pads first, real entries overwrite them below (disjoint indices)
+    if (tid == 0) o->n_entries = n_entries;
+    // pads (real entries below: disjoint indices)
     for (int e = tid; e < n_entries; e += blockDim.x) {
         int t = 0;
         while (t + 1 < kT && e >= s_seg[t + 1]) ++t;
@@ -114,13 +128,12 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
             o->dec_free[e] = -1; o->dec_orig[e] = -1; o->dec_type[e] = t;
         }
     }
-    if (tid < a.D) {
+    if (has_d) {
         const int d = tid, t = my_t;
         int e = s_seg[t] + s_wcnt[wv][t] + my_rank;
-        HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], a.d_qd[d],
-                                   1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
+        HxDecF x = hx_decode_terms(a.m, d_used, d_batch, d_qd, 1.0f / d_flops, 1.0f / d_hbm);
         o->dec_wait[e] = x.wait; o->dec_c1[e] = x.c1; o->dec_c2[e] = x.c2; o->dec_kB[e] = x.kB;
-        long long fr = (long long)a.d_cap[d] - (long long)a.d_used[d];
+        long long fr = (long long)d_cap - (long long)d_used;
         o->dec_free[e] = fr < -1 ? -1 : (fr > 2147483647LL ? 2147483647 : (int)fr);
         o->dec_orig[e] = d; o->dec_type[e] = t; o->dec_pos[d] = e;
     }
