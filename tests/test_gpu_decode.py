@@ -159,6 +159,19 @@ def test_decode_score_matches_oracle(ctx, Q, D, stride, res, plan, seed):
     assert_costs_close(got2["best_cost"][same], want2.best_cost[same], "best cost of free calls")
 
 
+def test_decode_score_is_the_same_every_time(ctx):
+    # no atomics, no dependence on which workgroup runs first: two passes over the same input agree bit for bit,
+    # also with another pass of another shape in between (the scratch is reused)
+    r, lock, iv = synth.make_decode_round("decode_mid", 5)
+    L, O = r.calls["L_in"], r.calls["L_out"]
+    first = run_score(ctx, r.model, L, O, lock, r.dec, iv)
+    r2, lock2, iv2 = synth.make_decode_round("decode_tiny", 6)
+    run_score(ctx, r2.model, r2.calls["L_in"], r2.calls["L_out"], lock2, r2.dec, iv2)
+    again = run_score(ctx, r.model, L, O, lock, r.dec, iv)
+    for key in first:
+        assert np.array_equal(first[key], again[key]), key
+
+
 def test_decode_score_edge_cases(ctx):
     import torch
     model = synth.MODEL
