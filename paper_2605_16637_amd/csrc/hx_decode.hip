@@ -463,8 +463,9 @@ __device__ __forceinline__ float hx_earliest_start_shared(const int2 *__restrict
 // Inside a run that entry is the head itself, later than the run's start, so one minimum serves both
 // cases.  The same comparisons on the same values as the scan: the same start bit for bit.
 // head: per stretch (time, rank) in groups of eight, read as scalars; G, sorted, t, src: LDS.
-__device__ __forceinline__ float hx_earliest_start_table(const int2 *__restrict__ head, const float *G, const int *sorted,
-                                                         int n, int m, int thr, float T, bool active)
+// first: the first eight heads, which the caller asked for ahead of time.
+__device__ __forceinline__ float hx_earliest_start_table(const int2 *__restrict__ head, HxTlGroup first, const float *G,
+                                                         const int *sorted, int n, int m, int thr, float T, bool active)
 {
     const bool open = active && thr >= 0;
     int r = 0;
@@ -490,7 +491,7 @@ __device__ __forceinline__ float hx_earliest_start_table(const int2 *__restrict_
         rs = fminf(rs, gv[u_]);                                                   \
     }
     const hx_tl_group_cp g = (hx_tl_group_cp)(unsigned long long)head;
-    HxTlGroup cur = g[0];
+    HxTlGroup cur = first;
     for (int k0 = 0; k0 < m; k0 += 8) {
         if (__builtin_amdgcn_ballot_w64(open && !(ans < INFINITY)) == 0) break;
         const HxTlGroup nxt = g[(k0 >> 3) + 1];
@@ -572,19 +573,48 @@ constexpr int DS_OFF_SORTED = HX_TAB, DS_OFF_SEG = 2 * (2 * HX_MAX_INTERVALS + 2
 constexpr int DS_BUF = HX_TAB + HX_TAB_MAX_N;
 static_assert(DS_BUF >= DS_OFF_SEG + HX_MAX_INTERVALS + 2, "the stretch search's arrays fit in the table's place");
 
+// n words from memory to LDS by the whole workgroup, eight loads per thread asked for before the first is
+// stored (one memory round trip per 2048 words); from[0] must be readable
+__device__ __forceinline__ void hx_copy_words(int *to, const int *__restrict__ from, int n, int tid)
+{
+    for (int base = 0; base < n; base += 8 * DS_THREADS) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * DS_THREADS + tid;
+            v[u] = from[i < n ? i : 0];                    // past the end: the first word again, not stored
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * DS_THREADS + tid;
+            if (i < n) to[i] = v[u];
+        }
+    }
+}
+
 __device__ __forceinline__ void hx_inst_stage(int *buf, const TlOut &o, int d, int nt, const HxInst &it, int tid)
 {
     const int n = it.n, m = it.m();
     if (it.by_table()) {
-        const int *G = (const int *)(o.G + (size_t)d * HX_TAB);
-        for (int i = tid; i < m * (n + 1); i += DS_THREADS) buf[i] = G[i];
-        for (int i = tid; i < n; i += DS_THREADS) buf[DS_OFF_SORTED + i] = o.sorted[(size_t)d * nt + i];
+        // the sorted occupancies (at most two per thread) ride with the table's first 2048 cells: one round trip
+        const int *G = (const int *)(o.G + (size_t)d * HX_TAB), *sorted = o.sorted + (size_t)d * nt;
+        const int cells = m * (n + 1);
+        int v[8], s2[2];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int i = u * DS_THREADS + tid; v[u] = G[i < cells ? i : 0]; }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) { const int i = u * DS_THREADS + tid; s2[u] = sorted[i < n ? i : 0]; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int i = u * DS_THREADS + tid; if (i < cells) buf[i] = v[u]; }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) { const int i = u * DS_THREADS + tid; if (i < n) buf[DS_OFF_SORTED + i] = s2[u]; }
+        if (cells > 8 * DS_THREADS) hx_copy_words(buf + 8 * DS_THREADS, G + 8 * DS_THREADS, cells - 8 * DS_THREADS, tid);
     } else if (it.by_stretch()) {
-        int2 *e = (int2 *)buf;
-        for (int i = tid; i < n; i += DS_THREADS) e[i] = o.e[(size_t)d * nt + i];
-        for (int i = tid; i <= m; i += DS_THREADS) buf[DS_OFF_SEG + i] = o.seg[(size_t)d * nt + i];
+        hx_copy_words(buf, (const int *)(o.e + (size_t)d * nt), 2 * n, tid);
+        hx_copy_words(buf + DS_OFF_SEG, o.seg + (size_t)d * nt, m + 1, tid);
     }
 }
+static_assert(HX_TAB_MAX_N <= 2 * DS_THREADS, "two sorted occupancies per thread");
 
 // Selection without atomics: a workgroup takes 256 free calls, one per lane, through a group of gd consecutive
 // instances, one instance after the other, and every lane keeps the best (finish, instance, start) it has
@@ -693,13 +723,15 @@ __global__ __launch_bounds__(DS_THREADS) void hx_decode_score_kernel(DecodeArgs 
         const int *buf = s_buf;
         __syncthreads();                                   // the slice prefixes, or the last instance's tables, are done with
         hx_inst_stage(s_buf, o, d, nt, cur, tid);
+        // (scalars, on their way while the tables land: the first heads of this instance, the next instance's record)
+        const HxTlGroup heads = *(hx_tl_group_cp)(unsigned long long)(o.head + (size_t)d * nt);
         const HxInst nxt = hx_inst_load(o, min(d + 1, d_hi - 1));
         __syncthreads();
         const float T = hx_decode_time(cf, cur.c1, cur.c2, cur.kB);
         const long long room = (long long)cur.cap - need;
         const int thr = room < 0 ? -1 : (room > (long long)INT_MAX ? INT_MAX : (int)room);
         const int n = cur.n, m = cur.m();
-        const float S = cur.by_table()     ? hx_earliest_start_table(o.head + (size_t)d * nt, (const float *)buf, buf + DS_OFF_SORTED,
+        const float S = cur.by_table()     ? hx_earliest_start_table(o.head + (size_t)d * nt, heads, (const float *)buf, buf + DS_OFF_SORTED,
                                                                      n, m, thr, T, in)
                         : cur.by_stretch() ? hx_earliest_start_stretches((const int2 *)buf, buf + DS_OFF_SEG, n, m, thr, T, in)
                                            : hx_earliest_start_shared(o.e + (size_t)d * nt, n, thr, T, in);
