@@ -90,46 +90,49 @@ struct CpArgs {
 
 constexpr int CP_THREADS = 256;      // threads per block
 constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking lane each
-constexpr int CP_NMAX = 1700;        // nodes staged per block
-constexpr int CP_EMAX = 3000;        // edges staged per block
-constexpr int CP_NPT = (CP_NMAX + 1 + CP_THREADS - 1) / CP_THREADS;
-constexpr int CP_EPT = (CP_EMAX + CP_THREADS - 1) / CP_THREADS;
+constexpr int CP_NMAX = 1400;        // nodes staged per block
+constexpr int CP_NPT = (CP_NMAX + CP_THREADS - 1) / CP_THREADS;
 constexpr int CP_DEG = 4;            // successors a walking lane combines per step
-constexpr int CP_NONE = 0xffff;
 
-struct __align__(8) CpRec { float rem; int lvl; };   // (cost, -) until the node is final, then (rem, level)
+// A node in LDS.  Before the walk reaches it: (cost, 0); after: (rem, level).
+// s01/s23 hold its CP_DEG successors as 16-bit byte offsets of their records in
+// the block's array, 0 for an empty slot: record 0 is (0, -1), what a node
+// without successors takes its maximum over.
+struct __align__(16) CpNode { int rem_bits; int lvl; unsigned s01, s23; };
+static_assert((CP_NMAX + 1) * sizeof(CpNode) <= 65536, "successor offsets are 16 bits");
 
-// One block takes `wpb` consecutive workflows; their nodes and edges are two
-// contiguous slices of the CSR arrays.
-//  stage  cost, row offsets and successor ids are read flat and coalesced, all
-//         loads issued before the first is used (enough bytes in flight to
-//         cover HBM latency), and parked in LDS: row offsets and successor ids
-//         as 16-bit offsets into the slices (10 B + 2 B per edge for a node).
+// One block takes `wpb` consecutive workflows; their nodes are a contiguous
+// slice of the node arrays.
+//  stage  one thread per node (a few nodes each, strided so that neighbouring
+//         lanes read neighbouring words): cost and both ends of the node's row,
+//         then its successor ids, every load of a stage issued before the first
+//         is used.  The thread checks each edge as far as it can without
+//         knowing the node's workflow (successor later than the node, inside the
+//         block's slice) and parks the node in LDS as one 16-byte record.
 //  walk   one lane per workflow (the lanes of one wave, a different wave in
 //         consecutive blocks so that the walkers of a CU spread over its
-//         SIMDs) walks the nodes from the last to the first.  A step costs one
-//         LDS round trip: the successor ids of the next node and the row
-//         offset of the one after are fetched in the same batch as the
-//         gathers of the current node.  Edges are checked here (successor
-//         later than the node, inside the workflow).  tail goes straight to
-//         global memory from the walking lane.
-//  store  every thread writes rem and level of a few nodes, coalesced.
-// A slice that does not fit -- more than CP_NMAX nodes or CP_EMAX edges, a
-// node with more than CP_DEG successors -- is walked in global memory, one
-// lane per workflow.
+//         SIMDs) walks the nodes from the last to the first.  A step is one
+//         16-byte read (cost and successors of the next node, asked for one
+//         step ahead), four 8-byte gathers, two three-way maxima each for rem
+//         and level on integer bit patterns (max(0, .) of fp32 values that are
+//         not NaN is the signed integer maximum of their bits with 0), and one
+//         12-byte write.  What staging could not check -- a successor in a later
+//         workflow of the same block -- shows in the largest offset the lane
+//         has followed.  tail takes the place of the node's first successors.
+//  store  every thread writes rem, level and tail of a few nodes, coalesced.
+// A slice of more than CP_NMAX nodes, or with a node of more than CP_DEG
+// successors, is walked in global memory, one lane per workflow.
 __global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
 void hx_cp_local_kernel(CpArgs a, int wpb)
 {
-    __shared__ CpRec s_rec[CP_NMAX + 1];      // [CP_NMAX] = (0, -1): what an empty successor slot reads
-    __shared__ uint16_t s_row[CP_NMAX + 2];   // first edge of each node, relative to the slice
-    __shared__ uint16_t s_col[CP_EMAX + CP_DEG];
-    __shared__ int s_flag;                    // 2: slice does not fit
+    __shared__ CpNode s_node[CP_NMAX + 1];
+    __shared__ int s_flag;                    // 2: walked in global memory
 
     const int tid = threadIdx.x;
     const int w0 = blockIdx.x * wpb;
     const int w1 = min(w0 + wpb, a.n_wf);
     int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
-    if (tid == 0) { s_flag = 0; s_rec[CP_NMAX] = CpRec{0.0f, -1}; }
+    if (tid == 0) { s_flag = 0; s_node[0] = CpNode{0, -1, 0u, 0u}; }
     // the slice of the block: malformed -> nothing is read, the error is reported
     if (n0 < 0 || n1 > a.n_nodes || n0 > n1) {
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
@@ -146,111 +149,107 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
     if (ws < n0 || we > n1 || ws > we) { bad_index = true; ws = we = n0; }   // this workflow is skipped
     float hmax = 0.0f;
 
-    bool fits = nn <= CP_NMAX;
-    int e0 = 0, e1 = 0;
-    if (fits) {
+    // a graph with fewer than CP_DEG edges in all is not worth a second way of reading successors
+    bool in_lds = nn <= CP_NMAX && a.n_edges >= CP_DEG;
+    if (in_lds && nn > 0) {
         float c[CP_NPT];
-        int r[CP_NPT];
+        int ra[CP_NPT], rb[CP_NPT];
+#pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            const int i = min(k * CP_THREADS + tid, nn - 1);   // a thread past the end repeats the last node
+            c[k] = a.cost[n0 + i];
+            ra[k] = a.row_ptr[n0 + i];
+            rb[k] = a.row_ptr[n0 + i + 1];
+        }
+        // the first CP_DEG ids of each row in one 16-byte load (a row that starts within the last
+        // CP_DEG - 1 ids of the array reads the last CP_DEG and shifts)
+        int ed[CP_NPT][CP_DEG];
+        const int e_last4 = a.n_edges - CP_DEG;
+#pragma unroll
+        for (int k = 0; k < CP_NPT; ++k) {
+            if (ra[k] < 0 || rb[k] > a.n_edges || ra[k] > rb[k]) { bad_index = true; ra[k] = rb[k] = 0; }
+            __builtin_memcpy(ed[k], a.col + min(ra[k], e_last4), sizeof(int) * CP_DEG);
+        }
+        // the costs are parked while the ids are on their way
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
             const int i = k * CP_THREADS + tid;
-            c[k] = i < nn ? a.cost[n0 + i] : 0.0f;
-            r[k] = i <= nn ? a.row_ptr[n0 + i] : 0;
+            if (i < nn) *(int2 *)&s_node[i + 1] = make_int2(__float_as_int(c[k]), 0);
         }
-        e0 = a.row_ptr[n0]; e1 = a.row_ptr[n1];
-        if (e0 < 0 || e1 > a.n_edges || e0 > e1) { bad_index = true; e0 = e1 = 0; }
-        const int ne = e1 - e0;
-        fits = ne <= CP_EMAX;
-        int ed[CP_EPT];
 #pragma unroll
-        for (int k = 0; k < CP_EPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            ed[k] = (fits && i < ne) ? a.col[e0 + i] : -1;
+        for (int k = 0; k < CP_NPT; ++k) {
+            if (ra[k] > e_last4 && rb[k] > ra[k]) {          // at most CP_DEG - 1 rows of the whole graph
+#pragma unroll
+                for (int j = 0; j < CP_DEG; ++j) ed[k][j] = a.col[min(ra[k] + j, a.n_edges - 1)];
+            }
         }
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
             const int i = k * CP_THREADS + tid;
-            if (i < nn) s_rec[i] = CpRec{c[k], 0};
-            if (i <= nn) s_row[i] = (uint16_t)min(max(r[k] - e0, 0), ne);   // a non-monotone row_ptr cannot leave the slice
-        }
+            const int ic = min(i, nn - 1);
+            const int deg = rb[k] - ra[k];
+            // a legal successor is one of ic+1 .. nn-1: one unsigned compare of its distance beyond ic+1
+            const int first = n0 + ic + 1;
+            const unsigned span = (unsigned)(nn - 1 - ic);
+            const unsigned off = (unsigned)(ic + 2) * (unsigned)sizeof(CpNode);
+            unsigned slot[CP_DEG];
+            int n_ok = 0;
 #pragma unroll
-        for (int k = 0; k < CP_EPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            const int rel = ed[k] - n0;
-            if (fits && i < ne) s_col[i] = (rel >= 0 && rel < nn) ? (uint16_t)rel : (uint16_t)CP_NONE;
+            for (int j = 0; j < CP_DEG; ++j) {
+                const unsigned t = (unsigned)(ed[k][j] - first);
+                const bool ok = t < (deg > j ? span : 0u);   // a slot past the end of the row has no legal id
+                n_ok += ok;
+                slot[j] = ok ? t * (unsigned)sizeof(CpNode) + off : 0u;
+            }
+            if (deg > CP_DEG) in_lds = false;
+            else if (n_ok != deg) not_dag = true;            // an edge backwards or out of the block's slice
+            if (i < nn) *(uint2 *)&s_node[i + 1].s01 = make_uint2(slot[0] | (slot[1] << 16), slot[2] | (slot[3] << 16));
         }
-        if (!fits) s_flag = 2;
-    } else if (tid == 0) {
-        s_flag = 2;
     }
+    if (!in_lds) s_flag = 2;
     __syncthreads();
 
     if (s_flag == 0) {
         if (we > ws) {                                  // a walking lane with a non-empty workflow
-            const int lo = ws - n0, hi = we - n0;
-            // software pipeline: at the step of node v the lane holds the successors of v and the
-            // first edge of v-1, and fetches the successors of v-1 and the first edge of v-2
-            int r1 = s_row[hi];
-            int r0 = s_row[hi - 1];
-            int rp = s_row[max(hi - 2, lo)];            // first edge of v-1
-            int u[CP_DEG];
-#pragma unroll
-            for (int j = 0; j < CP_DEG; ++j) u[j] = s_col[r0 + j];
-            bool wide = false;
-            int n_ok = 0, n_edges_seen = 0;
-            float *tail_out = a.tail + n0;
-            for (int v = hi - 1; v >= lo; --v) {
-                const int deg = r1 - r0;
-                wide = wide || deg > CP_DEG;
-                // fetches for the next two steps
-                const int rpp = s_row[max(v - 2, lo)];
-                int un[CP_DEG];
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) un[j] = s_col[rp + j];
-                const float cv = s_rec[v].rem;
-                // gathers of this step; a slot that is empty or breaks the order reads the (0, -1) entry
-                CpRec g[CP_DEG];
-                const unsigned span = (unsigned)(hi - v - 1);      // ids v+1 .. hi-1 are the legal successors
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) {
-                    const bool ok = j < deg && (unsigned)(u[j] - v - 1) < span;
-                    n_ok += ok;
-                    g[j] = s_rec[ok ? u[j] : CP_NMAX];
-                }
-                n_edges_seen += min(deg, CP_DEG);
-                float tl = 0.0f;
-                int lv = -1;
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) {
-                    tl = fmaxf(tl, g[j].rem);
-                    lv = max(lv, g[j].lvl);
-                }
-                const float rv = cv + tl;
-                s_rec[v] = CpRec{rv, lv + 1};
-                tail_out[v] = tl;
-                hmax = fmaxf(hmax, rv);
-                r1 = r0; r0 = rp; rp = rpp;
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) u[j] = un[j];
+            char *base = (char *)s_node;
+            const unsigned lo = (unsigned)(ws - n0 + 1) * (unsigned)sizeof(CpNode);
+            const unsigned hi = (unsigned)(we - n0 + 1) * (unsigned)sizeof(CpNode);
+            int hbits = 0;
+            unsigned umax = 0;
+            uint4 cur = *(const uint4 *)(base + hi - sizeof(CpNode));
+            for (unsigned p = hi - (unsigned)sizeof(CpNode); p >= lo; p -= (unsigned)sizeof(CpNode)) {
+                // the node before this one (record 0 before the block's first: read, not used)
+                const uint4 nxt = *(const uint4 *)(base + p - sizeof(CpNode));
+                const unsigned u0 = cur.z & 0xffffu, u1 = cur.z >> 16, u2 = cur.w & 0xffffu, u3 = cur.w >> 16;
+                const int2 g0 = *(const int2 *)(base + u0), g1 = *(const int2 *)(base + u1);
+                const int2 g2 = *(const int2 *)(base + u2), g3 = *(const int2 *)(base + u3);
+                umax = max(max(umax, u0), max(max(u1, u2), u3));
+                const int tb = max(max(g0.x, g1.x), max(g2.x, g3.x));
+                const int lv = max(max(g0.y, g1.y), max(g2.y, g3.y));
+                const float rv = __int_as_float((int)cur.x) + __int_as_float(tb);
+                // (rem, level, tail): the successors of a finished node are not read again
+                *(int2 *)(base + p) = make_int2(__float_as_int(rv), lv + 1);
+                *(int *)(base + p + 8) = tb;
+                hbits = max(hbits, __float_as_int(rv));
+                cur = nxt;
             }
-            not_dag = not_dag || n_ok != n_edges_seen;     // an edge left its workflow or pointed backwards
-            if (wide) s_flag = 3;                       // a node with more successors than a step combines
+            hmax = __int_as_float(hbits);
+            not_dag = not_dag || umax >= hi;            // an edge into a later workflow of the block
         }
         __syncthreads();
-    }
-    if (s_flag == 0) {
 #pragma unroll
         for (int k = 0; k < CP_NPT; ++k) {
             const int i = k * CP_THREADS + tid;
             if (i < nn) {
-                const CpRec me = s_rec[i];
-                a.rem[n0 + i] = me.rem;
-                a.level[n0 + i] = me.lvl;
+                const int4 me = *(const int4 *)&s_node[i + 1];
+                a.rem[n0 + i] = __int_as_float(me.x);
+                a.level[n0 + i] = me.y;
+                a.tail[n0 + i] = __int_as_float(me.z);
             }
         }
     } else {
-        // walked in global memory (also after a staged walk met a node that is too wide: everything is redone)
-        hmax = 0.0f;
+        // walked in global memory
+        not_dag = false;                                // found again below, edge by edge
         for (int v = we - 1; v >= ws; --v) {
             int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
             if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
@@ -267,7 +266,12 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
             hmax = fmaxf(hmax, rv);
         }
     }
-    if (walker) a.horizon[w0 + wl] = hmax;
+    if (walker) {
+        // the lane's workflow, worked out again from the thread index rather than kept in a register all along
+        int t2 = tid;
+        asm volatile("" : "+v"(t2));
+        a.horizon[w0 + t2 - ((int)(blockIdx.x & 3) << 6)] = hmax;
+    }
     if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
     if (bad_index) hx_raise(a.status, HX_ERR_INDEX);
 }
@@ -599,7 +603,7 @@ extern "C" int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
              ctx->d_status};
     if (max_sweeps == 0) {
         // workflows per block: as many as fit the staged slice at the average workflow size
-        long long fit = n_nodes > 0 ? (long long)(CP_NMAX * 2 / 3) * n_wf / n_nodes : CP_WPB;
+        long long fit = n_nodes > 0 ? (long long)(CP_NMAX * 41 / 50) * n_wf / n_nodes : CP_WPB;
         const int wpb = (int)(fit < 1 ? 1 : (fit > CP_WPB ? CP_WPB : fit));
         const int grid = (n_wf + wpb - 1) / wpb;
         hx_cp_local_kernel<<<grid, CP_THREADS, 0, stream>>>(a, wpb);

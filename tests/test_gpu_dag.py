@@ -137,6 +137,34 @@ def test_sweeps_accept_any_numbering_and_report_cycles(ctx):
         ctx.hx_stream_status()
 
 
+@pytest.mark.parametrize("edge,code", [((1, 4), -3),     # into a later workflow that shares the block
+                                       ((4, 1), -3),     # backwards, into an earlier workflow
+                                       ((2, 2), -3),     # onto itself
+                                       ((1, 9), -3),     # past the last node
+                                       (None, 0)])
+def test_single_pass_reports_edges_that_leave_their_workflow(ctx, edge, code):
+    from paper_2605_16637_amd import binding
+    # two chains of three nodes, 0-1-2 and 3-4-5, plus one extra edge
+    succ = {0: [1], 1: [2], 2: [], 3: [4], 4: [5], 5: []}
+    if edge:
+        succ[edge[0]] = succ[edge[0]] + [edge[1]]
+    row_ptr = np.cumsum([0] + [len(succ[v]) for v in range(6)]).astype(np.int32)
+    col = np.array([u for v in range(6) for u in succ[v]], np.int32)
+    cost32 = np.arange(1, 7, dtype=np.float32)
+    got = gpu_cp(ctx, row_ptr, col, cost32, [0, 3, 6], check=False)
+    if code == 0:
+        ctx.hx_stream_status()
+        assert list(got[0]) == [6.0, 5.0, 3.0, 15.0, 11.0, 6.0] and list(got[3]) == [6.0, 15.0]
+        assert list(got[2]) == [2, 1, 0, 2, 1, 0]
+    else:
+        with pytest.raises(binding.HxError) as e:
+            ctx.hx_stream_status()
+        assert e.value.code == code
+        # the workflow the bad edge does not start in is untouched by it
+        other = slice(3, 6) if edge[0] < 3 else slice(0, 3)
+        assert list(got[0][other]) == ([15.0, 11.0, 6.0] if edge[0] < 3 else [6.0, 5.0, 3.0])
+
+
 def fetch(raw):
     """Copy a borrowed device array of the context to the host (device-to-device copy into a tensor first)."""
     import ctypes
