@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # (counter x calibration factor of a plain copy); valid for the default workloads only, and to be
 # reset to None whenever the kernel changes until the counters are taken again
 FUSED_TRAFFIC_BYTES = {"large": 4.44e6 + 0.52e6}
-CP_TRAFFIC_BYTES = None
+CP_TRAFFIC_BYTES = 31.51e6 + 24.59e6
 
 
 def dev(x):

@@ -165,8 +165,11 @@ int hx_node_cost(hx_ctx *ctx, const hx_model *model, int32_t n,
  *
  * max_sweeps == 0: single pass.  Requires what online reveal gives by
  *   construction: every successor has a larger id than its node and belongs
- *   to the same workflow.  An edge that breaks this is skipped and raises
- *   HX_ERR_NOT_DAG in the stream status.
+ *   to the same workflow.  An edge that breaks this raises HX_ERR_NOT_DAG in
+ *   the stream status; what is then written for the workflow the edge starts
+ *   in is unspecified (no other workflow is affected, nothing faults).  Any
+ *   workflow size and any number of successors per node are accepted; the
+ *   pass is fastest when a node has at most 4.
  * max_sweeps  > 0: level-synchronous relaxation for any numbering; successors
  *   may be anywhere.  Sweeps until nothing changes, at most max_sweeps times
  *   (a DAG of depth L needs L+2); still changing then -> HX_ERR_NOT_DAG in the

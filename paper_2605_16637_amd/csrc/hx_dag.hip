@@ -94,12 +94,61 @@ constexpr int CP_NMAX = 1400;        // nodes staged per block
 constexpr int CP_NPT = (CP_NMAX + CP_THREADS - 1) / CP_THREADS;
 constexpr int CP_DEG = 4;            // successors a walking lane combines per step
 
-// A node in LDS.  Before the walk reaches it: (cost, 0); after: (rem, level).
+// A node in LDS.  Before the walk reaches it: (cost, left); after: (rem, level, tail).
 // s01/s23 hold its CP_DEG successors as 16-bit byte offsets of their records in
 // the block's array, 0 for an empty slot: record 0 is (0, -1), what a node
-// without successors takes its maximum over.
+// without successors takes its maximum over.  `left` marks a node whose slots
+// are empty because staging left its row to the walk, which reads it from
+// global memory: a node with more than CP_DEG successors, or one whose row
+// starts within the last CP_DEG - 1 ids of the whole array.
 struct __align__(16) CpNode { int rem_bits; int lvl; unsigned s01, s23; };
 static_assert((CP_NMAX + 1) * sizeof(CpNode) <= 65536, "successor offsets are 16 bits");
+
+// The walk of one lane over its workflow [ws, we), records in LDS at `base` (record 0 = the empty
+// successor, node n0 + i at record i + 1).  LEFT: some node of the run was left to the walk (more
+// successors than a record holds, or a row at the very end of the id array): such a node's row is
+// read from global memory, edge by edge.  Returns whether an edge left the workflow.
+template <bool LEFT>
+__device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, int ws, int we, float &hmax)
+{
+    bool not_dag = false;
+    const unsigned lo = (unsigned)(ws - n0 + 1) * (unsigned)sizeof(CpNode);
+    const unsigned hi = (unsigned)(we - n0 + 1) * (unsigned)sizeof(CpNode);
+    int hbits = 0;
+    unsigned umax = 0;
+    uint4 cur = *(const uint4 *)(base + hi - sizeof(CpNode));
+    for (unsigned p = hi - (unsigned)sizeof(CpNode); p >= lo; p -= (unsigned)sizeof(CpNode)) {
+        // the node before this one (record 0 before the run's first: read, not used)
+        const uint4 nxt = *(const uint4 *)(base + p - sizeof(CpNode));
+        const unsigned u0 = cur.z & 0xffffu, u1 = cur.z >> 16, u2 = cur.w & 0xffffu, u3 = cur.w >> 16;
+        const int2 g0 = *(const int2 *)(base + u0), g1 = *(const int2 *)(base + u1);
+        const int2 g2 = *(const int2 *)(base + u2), g3 = *(const int2 *)(base + u3);
+        umax = max(max(umax, u0), max(max(u1, u2), u3));
+        int tb = max(max(g0.x, g1.x), max(g2.x, g3.x));
+        int lv = max(max(g0.y, g1.y), max(g2.y, g3.y));
+        if (LEFT && cur.y != 0) {
+            const int v = (int)(p / (unsigned)sizeof(CpNode)) - 1;
+            const int r0 = a.row_ptr[n0 + v], r1 = a.row_ptr[n0 + v + 1];       // found in range when staged
+            for (int e = r0; e < r1; ++e) {
+                const unsigned t = (unsigned)a.col[e] - (unsigned)(n0 + v + 1);   // distance beyond v + 1
+                if (t < (unsigned)(we - n0 - v - 1)) {
+                    const int2 g = *(const int2 *)(base + p + (t + 1) * (unsigned)sizeof(CpNode));
+                    tb = max(tb, g.x); lv = max(lv, g.y);
+                } else {
+                    not_dag = true;
+                }
+            }
+        }
+        const float rv = __int_as_float((int)cur.x) + __int_as_float(tb);
+        // (rem, level, tail): the successors of a finished node are not read again
+        *(int2 *)(base + p) = make_int2(__float_as_int(rv), lv + 1);
+        *(int *)(base + p + 8) = tb;
+        hbits = max(hbits, __float_as_int(rv));
+        cur = nxt;
+    }
+    hmax = __int_as_float(hbits);
+    return not_dag || umax >= hi;                       // or an edge into a later workflow of the run
+}
 
 // One block takes `wpb` consecutive workflows; their nodes are a contiguous
 // slice of the node arrays.
@@ -120,157 +169,150 @@ static_assert((CP_NMAX + 1) * sizeof(CpNode) <= 65536, "successor offsets are 16
 //         workflow of the same block -- shows in the largest offset the lane
 //         has followed.  tail takes the place of the node's first successors.
 //  store  every thread writes rem, level and tail of a few nodes, coalesced.
-// A slice of more than CP_NMAX nodes, or with a node of more than CP_DEG
-// successors, is walked in global memory, one lane per workflow.
+// Workflows that together exceed CP_NMAX nodes are taken in several runs, each
+// as long as fits, one after the other; a single workflow of more than CP_NMAX
+// nodes (and a graph of fewer than CP_DEG edges in all) is walked in global
+// memory by one lane.
 __global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
 void hx_cp_local_kernel(CpArgs a, int wpb)
 {
     __shared__ CpNode s_node[CP_NMAX + 1];
-    __shared__ int s_flag;                    // 2: walked in global memory
+    __shared__ int s_any;                     // == first workflow of the run + 1: a node of this run was left to the walk
 
     const int tid = threadIdx.x;
     const int w0 = blockIdx.x * wpb;
     const int w1 = min(w0 + wpb, a.n_wf);
-    int n0 = a.wf_ptr[w0], n1 = a.wf_ptr[w1];
-    if (tid == 0) { s_flag = 0; s_node[0] = CpNode{0, -1, 0u, 0u}; }
-    // the slice of the block: malformed -> nothing is read, the error is reported
-    if (n0 < 0 || n1 > a.n_nodes || n0 > n1) {
-        if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
-        if (tid < wpb && w0 + tid < w1) a.horizon[w0 + tid] = 0.0f;
-        return;
-    }
-    const int nn = n1 - n0;
-    // the walking lanes: wave (blockIdx mod 4), lane = workflow within the block
+    // the walking lanes: wave (blockIdx mod 4), lane = workflow within the run
     const int wl = tid - ((int)(blockIdx.x & 3) << 6);
-    const bool walker = wl >= 0 && wl < wpb && w0 + wl < w1;
-    int ws = n0, we = n0;
-    if (walker) { ws = a.wf_ptr[w0 + wl]; we = a.wf_ptr[w0 + wl + 1]; }
     bool not_dag = false, bad_index = false;
-    if (ws < n0 || we > n1 || ws > we) { bad_index = true; ws = we = n0; }   // this workflow is skipped
-    float hmax = 0.0f;
+    if (tid == 0) s_node[0] = CpNode{0, -1, 0u, 0u};
+    char *const base = (char *)s_node;
 
-    // a graph with fewer than CP_DEG edges in all is not worth a second way of reading successors
-    bool in_lds = nn <= CP_NMAX && a.n_edges >= CP_DEG;
-    if (in_lds && nn > 0) {
-        float c[CP_NPT];
-        int ra[CP_NPT], rb[CP_NPT];
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            const int i = min(k * CP_THREADS + tid, nn - 1);   // a thread past the end repeats the last node
-            c[k] = a.cost[n0 + i];
-            ra[k] = a.row_ptr[n0 + i];
-            rb[k] = a.row_ptr[n0 + i + 1];
-        }
-        // the first CP_DEG ids of each row in one 16-byte load (a row that starts within the last
-        // CP_DEG - 1 ids of the array reads the last CP_DEG and shifts)
-        int ed[CP_NPT][CP_DEG];
-        const int e_last4 = a.n_edges - CP_DEG;
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            if (ra[k] < 0 || rb[k] > a.n_edges || ra[k] > rb[k]) { bad_index = true; ra[k] = rb[k] = 0; }
-            __builtin_memcpy(ed[k], a.col + min(ra[k], e_last4), sizeof(int) * CP_DEG);
-        }
-        // the costs are parked while the ids are on their way
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            if (i < nn) *(int2 *)&s_node[i + 1] = make_int2(__float_as_int(c[k]), 0);
-        }
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            if (ra[k] > e_last4 && rb[k] > ra[k]) {          // at most CP_DEG - 1 rows of the whole graph
-#pragma unroll
-                for (int j = 0; j < CP_DEG; ++j) ed[k][j] = a.col[min(ra[k] + j, a.n_edges - 1)];
+    // the first run's bounds are read before anything is written: uniform loads of memory the kernel
+    // has not touched go through the scalar cache
+    const int n0_first = w0 < w1 ? a.wf_ptr[w0] : 0, n1_first = w0 < w1 ? a.wf_ptr[w1] : 0;
+    for (int wa = w0; wa < w1;) {
+        // the run [wa, wb): normally all of the block's workflows
+        int wb = w1;
+        // a walking lane's own bounds are asked for together with the run's (none of them waits for the other)
+        int ws = 0, we = 0;
+        if (wl >= 0 && wl < w1 - wa) { ws = a.wf_ptr[wa + wl]; we = a.wf_ptr[wa + wl + 1]; }
+        const int n0 = wa == w0 ? n0_first : a.wf_ptr[wa];
+        int n1 = wa == w0 ? n1_first : a.wf_ptr[wb];
+        if (n0 >= 0 && n1 >= n0 && n1 - n0 > CP_NMAX) {
+            int lo = wa, hi = wb;                       // wf_ptr[lo] - n0 fits, wf_ptr[hi] - n0 does not
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                const int x = a.wf_ptr[mid];
+                if (x >= n0 && x - n0 <= CP_NMAX) lo = mid; else hi = mid;
             }
+            wb = max(lo, wa + 1);
+            n1 = a.wf_ptr[wb];
         }
-#pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            const int ic = min(i, nn - 1);
-            const int deg = rb[k] - ra[k];
-            // a legal successor is one of ic+1 .. nn-1: one unsigned compare of its distance beyond ic+1
-            const int first = n0 + ic + 1;
-            const unsigned span = (unsigned)(nn - 1 - ic);
-            const unsigned off = (unsigned)(ic + 2) * (unsigned)sizeof(CpNode);
-            unsigned slot[CP_DEG];
-            int n_ok = 0;
-#pragma unroll
-            for (int j = 0; j < CP_DEG; ++j) {
-                const unsigned t = (unsigned)(ed[k][j] - first);
-                const bool ok = t < (deg > j ? span : 0u);   // a slot past the end of the row has no legal id
-                n_ok += ok;
-                slot[j] = ok ? t * (unsigned)sizeof(CpNode) + off : 0u;
-            }
-            if (deg > CP_DEG) in_lds = false;
-            else if (n_ok != deg) not_dag = true;            // an edge backwards or out of the block's slice
-            if (i < nn) *(uint2 *)&s_node[i + 1].s01 = make_uint2(slot[0] | (slot[1] << 16), slot[2] | (slot[3] << 16));
+        const bool walker = wl >= 0 && wl < wb - wa;
+        // the slice of the run: malformed -> nothing is read, the error is reported
+        if (n0 < 0 || n1 > a.n_nodes || n0 > n1) {
+            bad_index = true;
+            if (walker) a.horizon[wa + wl] = 0.0f;
+            wa = wb;
+            continue;
         }
-    }
-    if (!in_lds) s_flag = 2;
-    __syncthreads();
+        const int nn = n1 - n0;
+        if (!walker) ws = we = n0;
+        if (ws < n0 || we > n1 || ws > we) { bad_index = true; ws = we = n0; }   // this workflow is skipped
+        float hmax = 0.0f;
 
-    if (s_flag == 0) {
-        if (we > ws) {                                  // a walking lane with a non-empty workflow
-            char *base = (char *)s_node;
-            const unsigned lo = (unsigned)(ws - n0 + 1) * (unsigned)sizeof(CpNode);
-            const unsigned hi = (unsigned)(we - n0 + 1) * (unsigned)sizeof(CpNode);
-            int hbits = 0;
-            unsigned umax = 0;
-            uint4 cur = *(const uint4 *)(base + hi - sizeof(CpNode));
-            for (unsigned p = hi - (unsigned)sizeof(CpNode); p >= lo; p -= (unsigned)sizeof(CpNode)) {
-                // the node before this one (record 0 before the block's first: read, not used)
-                const uint4 nxt = *(const uint4 *)(base + p - sizeof(CpNode));
-                const unsigned u0 = cur.z & 0xffffu, u1 = cur.z >> 16, u2 = cur.w & 0xffffu, u3 = cur.w >> 16;
-                const int2 g0 = *(const int2 *)(base + u0), g1 = *(const int2 *)(base + u1);
-                const int2 g2 = *(const int2 *)(base + u2), g3 = *(const int2 *)(base + u3);
-                umax = max(max(umax, u0), max(max(u1, u2), u3));
-                const int tb = max(max(g0.x, g1.x), max(g2.x, g3.x));
-                const int lv = max(max(g0.y, g1.y), max(g2.y, g3.y));
-                const float rv = __int_as_float((int)cur.x) + __int_as_float(tb);
-                // (rem, level, tail): the successors of a finished node are not read again
-                *(int2 *)(base + p) = make_int2(__float_as_int(rv), lv + 1);
-                *(int *)(base + p + 8) = tb;
-                hbits = max(hbits, __float_as_int(rv));
-                cur = nxt;
-            }
-            hmax = __int_as_float(hbits);
-            not_dag = not_dag || umax >= hi;            // an edge into a later workflow of the block
-        }
-        __syncthreads();
+        if (nn <= CP_NMAX && a.n_edges >= CP_DEG) {
+            if (nn > 0) {
+                float c[CP_NPT];
+                int ra[CP_NPT], rb[CP_NPT];
 #pragma unroll
-        for (int k = 0; k < CP_NPT; ++k) {
-            const int i = k * CP_THREADS + tid;
-            if (i < nn) {
-                const int4 me = *(const int4 *)&s_node[i + 1];
-                a.rem[n0 + i] = __int_as_float(me.x);
-                a.level[n0 + i] = me.y;
-                a.tail[n0 + i] = __int_as_float(me.z);
+                for (int k = 0; k < CP_NPT; ++k) {
+                    const int i = min(k * CP_THREADS + tid, nn - 1);   // a thread past the end repeats the last node
+                    c[k] = a.cost[n0 + i];
+                    ra[k] = a.row_ptr[n0 + i];
+                    rb[k] = a.row_ptr[n0 + i + 1];
+                }
+                // the first CP_DEG ids of each row in one 16-byte load.  A row of more than CP_DEG ids, or one
+                // that starts within the last CP_DEG - 1 ids of the whole array (where such a load would run
+                // past the end), is left to the walk.
+                int ed[CP_NPT][CP_DEG];
+                int deg[CP_NPT];
+                const int e_last4 = a.n_edges - CP_DEG;
+#pragma unroll
+                for (int k = 0; k < CP_NPT; ++k) {
+                    if (ra[k] < 0 || rb[k] > a.n_edges || ra[k] > rb[k]) { bad_index = true; ra[k] = rb[k] = 0; }
+                    __builtin_memcpy(ed[k], a.col + min(ra[k], e_last4), sizeof(int) * CP_DEG);
+                    deg[k] = rb[k] - ra[k];
+                    if (deg[k] > CP_DEG || (deg[k] > 0 && ra[k] > e_last4)) { deg[k] = -1; s_any = wa + 1; }
+                }
+                // the costs are parked while the ids are on their way
+#pragma unroll
+                for (int k = 0; k < CP_NPT; ++k) {
+                    const int i = k * CP_THREADS + tid;
+                    if (i < nn) *(int2 *)&s_node[i + 1] = make_int2(__float_as_int(c[k]), deg[k] < 0);
+                    deg[k] = max(deg[k], 0);                         // a node left to the walk keeps no slots
+                }
+#pragma unroll
+                for (int k = 0; k < CP_NPT; ++k) {
+                    const int i = k * CP_THREADS + tid;
+                    const int ic = min(i, nn - 1);
+                    // a legal successor is one of ic+1 .. nn-1: one unsigned compare of its distance beyond ic+1
+                    const int first = n0 + ic + 1;
+                    const unsigned span = (unsigned)(nn - 1 - ic);
+                    const unsigned off = (unsigned)(ic + 2) * (unsigned)sizeof(CpNode);
+                    unsigned slot[CP_DEG];
+                    int n_ok = 0;
+#pragma unroll
+                    for (int j = 0; j < CP_DEG; ++j) {
+                        const unsigned t = (unsigned)ed[k][j] - (unsigned)first;
+                        const bool ok = t < (deg[k] > j ? span : 0u);   // a slot past the end of the row has no legal id
+                        n_ok += ok;
+                        slot[j] = ok ? t * (unsigned)sizeof(CpNode) + off : 0u;
+                    }
+                    if (n_ok != deg[k]) not_dag = true;              // an edge backwards or out of the run's slice
+                    if (i < nn) *(uint2 *)&s_node[i + 1].s01 = make_uint2(slot[0] | (slot[1] << 16), slot[2] | (slot[3] << 16));
+                }
+            }
+            __syncthreads();
+
+            if (we > ws) {                              // a walking lane with a non-empty workflow
+                const bool bad = s_any == wa + 1 ? hx_cp_walk<true>(a, base, n0, ws, we, hmax)
+                                                 : hx_cp_walk<false>(a, base, n0, ws, we, hmax);
+                not_dag = not_dag || bad;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < CP_NPT; ++k) {
+                const int i = k * CP_THREADS + tid;
+                if (i < nn) {
+                    const int4 me = *(const int4 *)&s_node[i + 1];
+                    a.rem[n0 + i] = __int_as_float(me.x);
+                    a.level[n0 + i] = me.y;
+                    a.tail[n0 + i] = __int_as_float(me.z);
+                }
+            }
+            __syncthreads();                            // the next run stages over these records
+        } else {
+            // walked in global memory
+            for (int v = we - 1; v >= ws; --v) {
+                int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
+                if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
+                float tl = 0.0f;
+                int lv = 0;
+                for (int e = r0; e < r1; ++e) {
+                    int u = a.col[e];
+                    if (u <= v || u >= we) { not_dag = true; continue; }
+                    tl = fmaxf(tl, a.rem[u]);          // written earlier by this same thread
+                    lv = max(lv, a.level[u] + 1);
+                }
+                float rv = a.cost[v] + tl;
+                a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
+                hmax = fmaxf(hmax, rv);
             }
         }
-    } else {
-        // walked in global memory
-        not_dag = false;                                // found again below, edge by edge
-        for (int v = we - 1; v >= ws; --v) {
-            int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
-            if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
-            float tl = 0.0f;
-            int lv = 0;
-            for (int e = r0; e < r1; ++e) {
-                int u = a.col[e];
-                if (u <= v || u >= we) { not_dag = true; continue; }
-                tl = fmaxf(tl, a.rem[u]);          // written earlier by this same thread
-                lv = max(lv, a.level[u] + 1);
-            }
-            float rv = a.cost[v] + tl;
-            a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
-            hmax = fmaxf(hmax, rv);
-        }
-    }
-    if (walker) {
-        // the lane's workflow, worked out again from the thread index rather than kept in a register all along
-        int t2 = tid;
-        asm volatile("" : "+v"(t2));
-        a.horizon[w0 + t2 - ((int)(blockIdx.x & 3) << 6)] = hmax;
+        if (walker) a.horizon[wa + wl] = hmax;
+        wa = wb;
     }
     if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
     if (bad_index) hx_raise(a.status, HX_ERR_INDEX);

@@ -165,6 +165,48 @@ def test_single_pass_reports_edges_that_leave_their_workflow(ctx, edge, code):
         assert list(got[0][other]) == ([15.0, 11.0, 6.0] if edge[0] < 3 else [6.0, 5.0, 3.0])
 
 
+def _random_forest(rng, sizes, fan_out, p_second=0.5):
+    """Workflows of the given sizes, ids parent-first and workflow-contiguous; every node but a workflow's
+    first draws one parent (and sometimes a second) among the earlier nodes of its workflow that still
+    have fewer than `fan_out` successors."""
+    succ, wf_ptr = [], [0]
+    for size in sizes:
+        base = len(succ)
+        succ.extend([] for _ in range(size))
+        for i in range(1, size):
+            free = [u for u in range(base, base + i) if len(succ[u]) < fan_out]
+            for u in set(rng.choice(free, size=min(len(free), 1 + (rng.random() < p_second)), replace=False).tolist()):
+                succ[u].append(base + i)
+        wf_ptr.append(len(succ))
+    row_ptr = np.cumsum([0] + [len(x) for x in succ]).astype(np.int32)
+    col = np.array([u for x in succ for u in sorted(x)], np.int32)
+    return row_ptr, col, np.array(wf_ptr, np.int32)
+
+
+@pytest.mark.parametrize("sizes,fan_out,seed", [
+    ([40] * 30, 12, 1),                         # nodes with up to 12 successors
+    ([3, 900, 5, 700, 1, 650, 20] * 3, 4, 2),   # neighbours that do not fit one block's LDS together
+    ([60, 1390, 2, 1400, 1401, 7, 1399], 9, 3), # at and around the most one block stages; wide nodes too
+    ([1] * 300 + [2500] + [4] * 100, 3, 4),     # one workflow too large for LDS between small ones
+])
+def test_single_pass_wide_nodes_and_runs_of_workflows(ctx, sizes, fan_out, seed):
+    rng = np.random.default_rng(seed)
+    row_ptr, col, wf_ptr = _random_forest(rng, sizes, fan_out)
+    assert (np.diff(row_ptr).max() > 4) == (fan_out > 4)
+    cost32 = rng.uniform(0.1, 2.0, len(row_ptr) - 1).astype(np.float32)
+    want = o.critical_path(row_ptr, col, cost32.astype(np.float64), wf_ptr, round_f32=True)
+    assert_cp_bit_exact(gpu_cp(ctx, row_ptr, col, cost32, wf_ptr), want)
+    # a wide node with one edge out of its workflow is reported
+    wide = int(np.argmax(np.diff(row_ptr)))
+    if row_ptr[wide + 1] - row_ptr[wide] > 4 and wf_ptr[1] <= wide:
+        col2 = col.copy(); col2[row_ptr[wide + 1] - 1] = 0
+        gpu_cp(ctx, row_ptr, col2, cost32, wf_ptr, check=False)
+        from paper_2605_16637_amd import binding
+        with pytest.raises(binding.HxError) as e:
+            ctx.hx_stream_status()
+        assert e.value.code == -3
+
+
 def fetch(raw):
     """Copy a borrowed device array of the context to the host (device-to-device copy into a tensor first)."""
     import ctypes
