@@ -124,7 +124,7 @@ __device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, 
         const int2 g0 = *(const int2 *)(base + u0), g1 = *(const int2 *)(base + u1);
         const int2 g2 = *(const int2 *)(base + u2), g3 = *(const int2 *)(base + u3);
         umax = max(max(umax, u0), max(max(u1, u2), u3));
-        int tb = max(max(g0.x, g1.x), max(g2.x, g3.x));
+        int tb = max(max(g0.x, g1.x), max(max(g2.x, g3.x), 0));      // 0: the tail is never negative, whatever the costs
         int lv = max(max(g0.y, g1.y), max(g2.y, g3.y));
         if (LEFT && cur.y != 0) {
             const int v = (int)(p / (unsigned)sizeof(CpNode)) - 1;
