@@ -74,9 +74,9 @@ class RoundOnDevice:
 
     def horizons(self, stream=None):
         r = self.rnd
-        self.ctx.hx_node_cost(r.model, self.L_in, self.L_out, self.tF, self.tB, self.links, self.cost, stream=stream)
-        self.ctx.hx_critical_path(self.row_ptr, self.col, self.cost, self.wf_ptr,
-                                  self.rem, self.tail, self.level, self.hor, stream=stream)
+        # node cost and critical path in one launch
+        self.ctx.hx_horizons(r.model, self.row_ptr, self.col, self.L_in, self.L_out, self.tF, self.tB, self.links,
+                             self.wf_ptr, self.cost, self.rem, self.tail, self.level, self.hor, stream=stream)
 
     def score(self):
         self.ctx.hx_score_placements(self.rnd.model, self.calls, self.pre, self.dec, self.links,
@@ -446,8 +446,8 @@ def main():
                                 "stream": "streaming round shape: 32768 ready calls x 512 x 512, 8 classes"}[args.workload],
                    "calls": C, "prefill": P, "decode": D, "candidates_per_round": n_cand,
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
-                   "step": ("[node cost -> critical path] beside [fused score+argmin] on two streams -> urgency fold -> commit"
-                            if args.overlap else "node cost -> critical path -> fused score+argmin+ratio -> commit"),
+                   "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
+                            if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
                    "launch": "eager" if args.eager else "hip graph replay", "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (+ its table-prepare launch)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",

@@ -183,6 +183,23 @@ int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
                      float *rem, float *tail, int32_t *level, float *horizon, void *stream);
 
 /*
+ * hx_node_cost followed by hx_critical_path (max_sweeps = 0) in one launch:
+ * the standalone cost of every node is worked out from its lengths while the
+ * pass stages the node, written to node_cost (device [n_nodes], out) and used
+ * at once.  Same arguments, same requirements on the numbering, same results
+ * bit for bit, same error reporting as the two calls.  Meant for the graphs
+ * of a scheduling round, where a launch saved counts; on graphs of millions
+ * of nodes the two separate calls are faster (the cost evaluation needs
+ * registers that the pass alone gives to more resident workgroups).
+ */
+int hx_horizons(hx_ctx *ctx, const hx_model *model, int32_t n_nodes, int32_t n_edges,
+                const int32_t *succ_row_ptr, const int32_t *succ_col_idx,
+                const int32_t *L_in, const int32_t *L_out,
+                int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
+                int32_t n_wf, const int32_t *wf_ptr,
+                float *node_cost, float *rem, float *tail, int32_t *level, float *horizon, void *stream);
+
+/*
  * Incremental form for DAGs revealed at run time (Sec. 4.1, online reveal;
  * Sec. 5.1, the horizon is refreshed at every reveal).  The graph lives
  * in the context.  hx_dag_reserve sizes it (allocates; not for the hot loop)

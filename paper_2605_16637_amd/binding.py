@@ -17,7 +17,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
           -5: "HX_ERR_DEVICE", -6: "HX_ERR_INDEX", -7: "HX_ERR_OVERFLOW"}
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
-           "hx_critical_path", "hx_dag_reserve", "hx_dag_append", "hx_dag_set_cost", "hx_dag_view",
+           "hx_critical_path", "hx_horizons", "hx_dag_reserve", "hx_dag_append", "hx_dag_set_cost", "hx_dag_view",
            "hx_score_placements", "hx_select", "hx_urgency", "hx_commit", "hx_rank", "hx_plan_greedy",
            "hx_decode_score", "hx_decode_plan_greedy")
 
@@ -214,6 +214,19 @@ class Context:
             _ptr(node_cost, torch.float32, n), n_wf, _ptr(wf_ptr, torch.int32), int(max_sweeps),
             _ptr(rem, torch.float32, n), _ptr(tail, torch.float32, n), _ptr(level, torch.int32, n),
             _ptr(horizon, torch.float32, n_wf), _stream(stream)))
+
+    def hx_horizons(self, model, succ_row_ptr, succ_col_idx, L_in, L_out, type_flops, type_hbm_bw, links, wf_ptr,
+                    node_cost, rem, tail, level, horizon, stream=None):
+        torch = _torch()
+        n, n_wf, n_edges = int(succ_row_ptr.numel()) - 1, int(wf_ptr.numel()) - 1, int(succ_col_idx.numel())
+        T = int(type_flops.numel())
+        m, lk = make_model(model), make_links(links)
+        self._check(self.lib.hx_horizons(
+            self._ctx, C.byref(m), n, n_edges, _ptr(succ_row_ptr, torch.int32), _ptr(succ_col_idx, torch.int32),
+            _ptr(L_in, torch.int32, n), _ptr(L_out, torch.int32, n), T, _ptr(type_flops, torch.float32),
+            _ptr(type_hbm_bw, torch.float32, T), C.byref(lk), n_wf, _ptr(wf_ptr, torch.int32),
+            _ptr(node_cost, torch.float32, n), _ptr(rem, torch.float32, n), _ptr(tail, torch.float32, n),
+            _ptr(level, torch.int32, n), _ptr(horizon, torch.float32, n_wf), _stream(stream)))
 
     def hx_dag_reserve(self, max_nodes, max_edges, max_wf, max_depth, stream=None):
         self._check(self.lib.hx_dag_reserve(self._ctx, int(max_nodes), int(max_edges), int(max_wf),

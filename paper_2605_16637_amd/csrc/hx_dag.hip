@@ -29,51 +29,67 @@ struct NodeCostArgs {
     float *cost;
 };
 
-// cost[v] = min over class pairs of prefill + transfer + decode on an idle pool.
-// The class tables are padded to kT x kT in LDS (a pair with a class that does
-// not exist has infinite transfer latency), so the pair loop unrolls completely
-// and its table reads are LDS broadcasts.
-__global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
+// Per-class tables of the standalone cost, padded to kT x kT (a pair with a class
+// that does not exist has infinite transfer latency), so that the pair loop
+// unrolls completely and its table reads are LDS broadcasts.
+struct CostTables {
+    float invF[kT], invB[kT], c1[kT], c2[kT], kB[kT];
+    float invbw[kT * kT], lat[kT * kT];
+};
+
+// filled by the first kT * kT threads of the block; a barrier follows at the caller's
+__device__ __forceinline__ void hx_cost_tables_fill(CostTables &t, const NodeCostArgs &a, int tid)
 {
-    __shared__ float s_invF[kT], s_invB[kT], s_c1[kT], s_kB[kT], s_c2[kT];
-    __shared__ __align__(16) float s_invbw[kT * kT], s_lat[kT * kT];
-    const int tid = threadIdx.x;
-    // the first node's lengths are on their way while the class tables are set up
-    const int v0 = blockIdx.x * blockDim.x + tid;
-    int L = v0 < a.n ? a.L_in[v0] : 0, O = v0 < a.n ? a.L_out[v0] : 0;
     if (tid < kT) {
         const bool in = tid < a.T;
         float invF = in ? 1.0f / a.tF[tid] : 0.0f, invB = in ? 1.0f / a.tB[tid] : 0.0f;
         HxDecF d = hx_decode_terms(a.m, 0, 0, 0, invF, invB);
-        s_invF[tid] = invF; s_invB[tid] = invB;
+        t.invF[tid] = invF; t.invB[tid] = invB;
         // a padded class is excluded by an infinite link latency below; its own terms stay finite (0)
-        s_c1[tid] = in ? d.c1 : 0.0f; s_c2[tid] = in ? d.c2 : 0.0f; s_kB[tid] = in ? d.kB : 0.0f;
+        t.c1[tid] = in ? d.c1 : 0.0f; t.c2[tid] = in ? d.c2 : 0.0f; t.kB[tid] = in ? d.kB : 0.0f;
     }
     if (tid < kT * kT) {
         const int tp = tid / kT, td = tid % kT;
         const bool in = tp < a.T && td < a.T;
-        s_invbw[tid] = in ? 1.0f / a.bw[tp * a.T + td] : 0.0f;
-        s_lat[tid] = in ? (a.lat ? a.lat[tp * a.T + td] : 0.0f) : INFINITY;
+        t.invbw[tid] = in ? 1.0f / a.bw[tp * a.T + td] : 0.0f;
+        t.lat[tid] = in ? (a.lat ? a.lat[tp * a.T + td] : 0.0f) : INFINITY;
     }
+}
+
+// min over class pairs of prefill + transfer + decode on an idle pool
+__device__ __forceinline__ float hx_node_cost_eval(const HxModelF &m, const CostTables &t, int L, int O)
+{
+    const HxCallF cf = hx_call_terms(m, L, O);
+    float dec[kT];
+#pragma unroll
+    for (int td = 0; td < kT; ++td) dec[td] = hx_decode_time(cf, t.c1[td], t.c2[td], t.kB[td]);
+    float best = INFINITY;
+#pragma unroll
+    for (int tp = 0; tp < kT; ++tp) {
+        const float done = hx_prefill_done(cf, 0.0f, t.invF[tp], t.invB[tp]);
+#pragma unroll
+        for (int td = 0; td < kT; ++td) {
+            const float x = hx_transfer(cf, t.invbw[tp * kT + td], t.lat[tp * kT + td]);
+            best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
+        }
+    }
+    return best;
+}
+
+__global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
+{
+    __shared__ CostTables s_tab;
+    const int tid = threadIdx.x;
+    // the first node's lengths are on their way while the class tables are set up
+    const int v0 = blockIdx.x * blockDim.x + tid;
+    int L = v0 < a.n ? a.L_in[v0] : 0, O = v0 < a.n ? a.L_out[v0] : 0;
+    hx_cost_tables_fill(s_tab, a, tid);
     __syncthreads();
     for (int v = v0; v < a.n; v += gridDim.x * blockDim.x) {
-        const HxCallF cf = hx_call_terms(a.m, L, O);
+        const int Lv = L, Ov = O;
         const int vn = v + gridDim.x * blockDim.x;
         if (vn < a.n) { L = a.L_in[vn]; O = a.L_out[vn]; }
-        float dec[kT];
-#pragma unroll
-        for (int td = 0; td < kT; ++td) dec[td] = hx_decode_time(cf, s_c1[td], s_c2[td], s_kB[td]);
-        float best = INFINITY;
-#pragma unroll
-        for (int tp = 0; tp < kT; ++tp) {
-            const float done = hx_prefill_done(cf, 0.0f, s_invF[tp], s_invB[tp]);
-#pragma unroll
-            for (int td = 0; td < kT; ++td) {
-                const float x = hx_transfer(cf, s_invbw[tp * kT + td], s_lat[tp * kT + td]);
-                best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
-            }
-        }
-        a.cost[v] = best;
+        a.cost[v] = hx_node_cost_eval(a.m, s_tab, Lv, Ov);
     }
 }
 
@@ -91,7 +107,7 @@ struct CpArgs {
 constexpr int CP_THREADS = 256;      // threads per block
 constexpr int CP_WPB = 64;           // at most this many workflows per block, one walking lane each
 constexpr int CP_NMAX = 1400;        // nodes staged per block
-constexpr int CP_NPT = (CP_NMAX + CP_THREADS - 1) / CP_THREADS;
+constexpr int CP_NMAX_COST = 1344;   // the same where the block also holds the class tables of the node cost
 constexpr int CP_DEG = 4;            // successors a walking lane combines per step
 
 // A node in LDS.  Before the walk reaches it: (cost, left); after: (rem, level, tail).
@@ -173,12 +189,14 @@ __device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, 
 // as long as fits, one after the other; a single workflow of more than CP_NMAX
 // nodes (and a graph of fewer than CP_DEG edges in all) is walked in global
 // memory by one lane.
-__global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
-void hx_cp_local_kernel(CpArgs a, int wpb)
+// COST: the node costs are not read but worked out here from the nodes' lengths (and written out as
+// well), `nc` and `tab` being the arguments and the class tables of the standalone cost.
+template <int NMAX, bool COST>
+__device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNode *s_node, int &s_any,
+                                                 const NodeCostArgs *nc, const CostTables *tab)
 {
-    __shared__ CpNode s_node[CP_NMAX + 1];
-    __shared__ int s_any;                     // == first workflow of the run + 1: a node of this run was left to the walk
-
+    constexpr int CP_NMAX = NMAX;             // nodes staged per run
+    constexpr int CP_NPT = (NMAX + CP_THREADS - 1) / CP_THREADS;
     const int tid = threadIdx.x;
     const int w0 = blockIdx.x * wpb;
     const int w1 = min(w0 + wpb, a.n_wf);
@@ -225,11 +243,13 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
         if (nn <= CP_NMAX && a.n_edges >= CP_DEG) {
             if (nn > 0) {
                 float c[CP_NPT];
+                int len_in[COST ? CP_NPT : 1], len_out[COST ? CP_NPT : 1];
                 int ra[CP_NPT], rb[CP_NPT];
 #pragma unroll
                 for (int k = 0; k < CP_NPT; ++k) {
                     const int i = min(k * CP_THREADS + tid, nn - 1);   // a thread past the end repeats the last node
-                    c[k] = a.cost[n0 + i];
+                    if constexpr (COST) { len_in[k] = nc->L_in[n0 + i]; len_out[k] = nc->L_out[n0 + i]; }
+                    else c[k] = a.cost[n0 + i];
                     ra[k] = a.row_ptr[n0 + i];
                     rb[k] = a.row_ptr[n0 + i + 1];
                 }
@@ -246,10 +266,14 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
                     deg[k] = rb[k] - ra[k];
                     if (deg[k] > CP_DEG || (deg[k] > 0 && ra[k] > e_last4)) { deg[k] = -1; s_any = wa + 1; }
                 }
-                // the costs are parked while the ids are on their way
+                // the costs are worked out (COST) and parked while the ids are on their way
 #pragma unroll
                 for (int k = 0; k < CP_NPT; ++k) {
                     const int i = k * CP_THREADS + tid;
+                    if constexpr (COST) if (i < nn) {
+                        c[k] = hx_node_cost_eval(nc->m, *tab, len_in[k], len_out[k]);
+                        nc->cost[n0 + i] = c[k];
+                    }
                     if (i < nn) *(int2 *)&s_node[i + 1] = make_int2(__float_as_int(c[k]), deg[k] < 0);
                     deg[k] = max(deg[k], 0);                         // a node left to the walk keeps no slots
                 }
@@ -306,7 +330,10 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
                     tl = fmaxf(tl, a.rem[u]);          // written earlier by this same thread
                     lv = max(lv, a.level[u] + 1);
                 }
-                float rv = a.cost[v] + tl;
+                float cv;
+                if constexpr (COST) { cv = hx_node_cost_eval(nc->m, *tab, nc->L_in[v], nc->L_out[v]); nc->cost[v] = cv; }
+                else cv = a.cost[v];
+                float rv = cv + tl;
                 a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
                 hmax = fmaxf(hmax, rv);
             }
@@ -316,6 +343,31 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
     }
     if (not_dag) hx_raise(a.status, HX_ERR_NOT_DAG);
     if (bad_index) hx_raise(a.status, HX_ERR_INDEX);
+}
+
+// seven blocks of 22.4 KB per compute unit, 72 vector registers
+__global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
+void hx_cp_local_kernel(CpArgs a, int wpb)
+{
+    __shared__ CpNode s_node[CP_NMAX + 1];
+    __shared__ int s_any;                     // == first workflow of the run + 1: a node of this run was left to the walk
+    hx_cp_local_body<CP_NMAX, false>(a, wpb, s_node, s_any, nullptr, nullptr);
+}
+
+// The same pass with the standalone node cost worked out while staging instead of being read:
+// one launch for what hx_node_cost_kernel and hx_cp_local_kernel do one after the other.  The
+// evaluation of 64 class pairs per node wants more registers than seven blocks per compute unit
+// leave; the launch is meant for the graphs of a scheduling round (tens of thousands of nodes,
+// spread over all compute units), where the latency of a launch counts and residency does not.
+__global__ __launch_bounds__(CP_THREADS)
+void hx_cp_cost_kernel(CpArgs a, NodeCostArgs nc, int wpb)
+{
+    __shared__ CpNode s_node[CP_NMAX_COST + 1];
+    __shared__ int s_any;
+    __shared__ CostTables s_tab;
+    hx_cost_tables_fill(s_tab, nc, threadIdx.x);
+    __syncthreads();
+    hx_cp_local_body<CP_NMAX_COST, true>(a, wpb, s_node, s_any, &nc, &s_tab);
 }
 
 // ---- critical path, level-synchronous sweeps ------------------------------------------
@@ -662,6 +714,43 @@ extern "C" int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
     }
     hx_cp_finish_kernel<<<(n_wf + 255) / 256 + 1, 256, 0, stream>>>(a, ctx->d_flags, max_sweeps);
     return hx_check_launch(ctx, "hx_cp_finish_kernel");
+}
+
+extern "C" int hx_horizons(hx_ctx *ctx, const hx_model *model, int32_t n_nodes, int32_t n_edges,
+                           const int32_t *succ_row_ptr, const int32_t *succ_col_idx,
+                           const int32_t *L_in, const int32_t *L_out,
+                           int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
+                           int32_t n_wf, const int32_t *wf_ptr,
+                           float *node_cost, float *rem, float *tail, int32_t *level, float *horizon, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, model && links && links->bw && type_flops && type_hbm_bw, HX_ERR_INVALID_ARG, "NULL table");
+    HX_REQUIRE(ctx, n_nodes >= 0 && n_edges >= 0 && n_wf >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, n_types >= 1 && n_types <= HX_MAX_TYPES && links->n_types == n_types, HX_ERR_SHAPE,
+               "n_types %d (links %d) outside 1..%d", n_types, links->n_types, HX_MAX_TYPES);
+    HX_REQUIRE(ctx, succ_row_ptr && wf_ptr, HX_ERR_INVALID_ARG, "NULL row_ptr or wf_ptr");
+    HX_REQUIRE(ctx, n_edges == 0 || succ_col_idx, HX_ERR_INVALID_ARG, "NULL col_idx");
+    HX_REQUIRE(ctx, n_nodes == 0 || (L_in && L_out && node_cost && rem && tail && level), HX_ERR_INVALID_ARG, "NULL node array");
+    HX_REQUIRE(ctx, n_wf == 0 || horizon, HX_ERR_INVALID_ARG, "NULL horizon");
+    if (n_wf == 0) return HX_OK;
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    CpArgs a{n_nodes, n_edges, n_wf, succ_row_ptr, succ_col_idx, wf_ptr, node_cost, rem, tail, horizon, level,
+             ctx->d_status};
+    NodeCostArgs nc{};
+    nc.m = HxModelF{model->kv_bytes_per_token, model->flops_per_token, model->attn_flops_per_token2,
+                    model->weight_bytes, model->nominal_batch};
+    nc.n = n_nodes; nc.T = n_types; nc.L_in = L_in; nc.L_out = L_out; nc.tF = type_flops; nc.tB = type_hbm_bw;
+    nc.bw = links->bw; nc.lat = links->latency; nc.cost = node_cost;
+    // workflows per block: as many as fit the staged slice at the average workflow size, but no more
+    // than it takes to give every compute unit a block (a thread evaluates the cost of each of its nodes)
+    long long fit = n_nodes > 0 ? (long long)(CP_NMAX_COST * 41 / 50) * n_wf / n_nodes : CP_WPB;
+    const long long spread = n_wf / ctx->num_cu;
+    fit = fit > spread ? (spread < 1 ? 1 : spread) : fit;
+    const int wpb = (int)(fit < 1 ? 1 : (fit > CP_WPB ? CP_WPB : fit));
+    const int grid = (n_wf + wpb - 1) / wpb;
+    hx_cp_cost_kernel<<<grid, CP_THREADS, 0, (hipStream_t)stream_>>>(a, nc, wpb);
+    return hx_check_launch(ctx, "hx_cp_cost_kernel");
 }
 
 extern "C" int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges, int32_t max_wf,

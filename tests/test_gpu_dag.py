@@ -207,6 +207,58 @@ def test_single_pass_wide_nodes_and_runs_of_workflows(ctx, sizes, fan_out, seed)
         assert e.value.code == -3
 
 
+def gpu_horizons(ctx, rnd, row_ptr, col, L_in, L_out, wf_ptr, check=True):
+    import torch
+    from paper_2605_16637_amd import binding
+    n, n_wf = len(row_ptr) - 1, len(wf_ptr) - 1
+    f = lambda v: torch.full((n,), v, device="cuda:0")
+    cost, rem, tail = f(-1.0), f(-1.0), f(-1.0)
+    level = torch.full((n,), -1, dtype=torch.int32, device="cuda:0")
+    hor = torch.full((n_wf,), -1.0, device="cuda:0")
+    ctx.hx_horizons(rnd.model, dev(np.asarray(row_ptr, np.int32)), dev(np.asarray(col, np.int32)),
+                    dev(np.asarray(L_in, np.int32)), dev(np.asarray(L_out, np.int32)),
+                    dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"]), binding.to_device(rnd.links),
+                    dev(np.asarray(wf_ptr, np.int32)), cost, rem, tail, level, hor)
+    if check:
+        ctx.hx_stream_status()
+    return cost.cpu().numpy(), (rem.cpu().numpy(), tail.cpu().numpy(), level.cpu().numpy(), hor.cpu().numpy())
+
+
+@pytest.mark.parametrize("name,seed", [("tiny", 1), ("mid", 3), ("large", 1)])
+def test_horizons_in_one_launch(ctx, name, seed):
+    """Node cost and critical path in one launch: the cost within tolerance of the oracle's and bit for
+    bit what hx_node_cost gives; the pass bit for bit the oracle's fp32 pass on those costs."""
+    import torch
+    from paper_2605_16637_amd import binding
+    rnd = synth.make_round(name, seed)
+    d = rnd.dag
+    gcost, got = gpu_horizons(ctx, rnd, d.succ_row_ptr, d.succ_col, d.L_in, d.L_out, d.wf_ptr)
+    assert_costs_close(gcost, o.node_cost(rnd.model, d.L_in, d.L_out, rnd.types, rnd.links), "node cost")
+    two = torch.empty(d.n_nodes, device="cuda:0")
+    ctx.hx_node_cost(rnd.model, dev(d.L_in), dev(d.L_out), dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"]),
+                     binding.to_device(rnd.links), two)
+    assert np.array_equal(gcost, two.cpu().numpy())
+    want = o.critical_path(d.succ_row_ptr, d.succ_col, gcost.astype(np.float64), d.wf_ptr, round_f32=True)
+    assert_cp_bit_exact(got, want)
+
+
+@pytest.mark.parametrize("sizes,fan_out,seed", [
+    ([40] * 30, 12, 1), ([3, 900, 5, 700, 1, 650, 20] * 3, 4, 2), ([1] * 300 + [2500] + [4] * 100, 3, 4), ([], 3, 5), ([0, 1, 0], 3, 6)])
+def test_horizons_in_one_launch_wide_nodes_and_runs(ctx, sizes, fan_out, seed):
+    rng = np.random.default_rng(seed)
+    rnd = synth.make_round("tiny", 1)
+    row_ptr, col, wf_ptr = _random_forest(rng, sizes, fan_out)
+    n = len(row_ptr) - 1
+    L_in, L_out = rng.integers(64, 8000, n).astype(np.int32), rng.integers(16, 2000, n).astype(np.int32)
+    gcost, got = gpu_horizons(ctx, rnd, row_ptr, col, L_in, L_out, wf_ptr)
+    if n == 0:
+        assert all(x.size == 0 for x in got[:3]) and list(got[3]) == [0.0] * (len(wf_ptr) - 1)
+        return
+    assert_costs_close(gcost, o.node_cost(rnd.model, L_in, L_out, rnd.types, rnd.links), "node cost")
+    want = o.critical_path(row_ptr, col, gcost.astype(np.float64), wf_ptr, round_f32=True)
+    assert_cp_bit_exact(got, want)
+
+
 def fetch(raw):
     """Copy a borrowed device array of the context to the host (device-to-device copy into a tensor first)."""
     import ctypes
