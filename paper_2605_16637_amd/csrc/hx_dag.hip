@@ -187,8 +187,8 @@ __device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, 
 //  store  every thread writes rem, level and tail of a few nodes, coalesced.
 // Workflows that together exceed CP_NMAX nodes are taken in several runs, each
 // as long as fits, one after the other; a single workflow of more than CP_NMAX
-// nodes (and a graph of fewer than CP_DEG edges in all) is walked in global
-// memory by one lane.
+// nodes is walked in global memory by one lane (and so is every workflow, a
+// lane each, of a graph with fewer than CP_DEG edges in all).
 // COST: the node costs are not read but worked out here from the nodes' lengths (and written out as
 // well), `nc` and `tab` being the arguments and the class tables of the standalone cost.
 template <int NMAX, bool COST>
