@@ -187,7 +187,8 @@ int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
  * the standalone cost of every node is worked out from its lengths while the
  * pass stages the node, written to node_cost (device [n_nodes], out) and used
  * at once.  Same arguments, same requirements on the numbering, same results
- * bit for bit, same error reporting as the two calls.  Meant for the graphs
+ * bit for bit, same error reporting as the two calls; a node that no workflow
+ * of wf_ptr covers gets no cost (the pass does not visit it).  Meant for the graphs
  * of a scheduling round, where a launch saved counts; on graphs of millions
  * of nodes the two separate calls are faster (the cost evaluation needs
  * registers that the pass alone gives to more resident workgroups).
