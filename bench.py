@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/
 # (counter x calibration factor of a plain copy); valid for the default workloads only, and to be
 # reset to None whenever the kernel changes until the counters are taken again
-FUSED_TRAFFIC_BYTES = {"large": 4.44e6 + 0.52e6}
+FUSED_TRAFFIC_BYTES = {"large": 4.55e6 + 0.52e6}
 CP_TRAFFIC_BYTES = 31.51e6 + 24.59e6
 
 
@@ -449,7 +449,7 @@ def main():
                    "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
                             if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
                    "launch": "eager" if args.eager else "hip graph replay", "seed": args.seed},
-        "roofline": {"kernel": "hx_fused_search_kernel (+ its table-prepare launch)", "bound": "alu",
+        "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                      "frac": achieved / ALU_PEAK_TOPS, "traffic": FUSED_TRAFFIC_BYTES.get(args.workload),
                      "ops_per_candidate": OPS_PER_CANDIDATE, "launch_ms": score_s * 1e3,

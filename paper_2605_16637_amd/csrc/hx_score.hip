@@ -139,6 +139,129 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
     }
 }
 
+// The same tables, built by a workgroup of 256 threads straight into its own LDS arrays (the fused search
+// does this itself instead of reading what hx_prepare_kernel wrote: a launch less per round, for a few
+// barriers more per workgroup).  Entry order is the one above: classes ascending, instances of a class
+// ascending.  s_scratch: [(HX_MAX_INSTANCES / HX_WAVE) * kT + kT] ints.  Ends with a barrier.
+struct PrepLds {
+    float *wait, *c1, *c2, *kB;
+    int *free, *orig, *dtype;
+    float *pw, *pinvF, *pinvB;
+    int *ptype;
+    float *invbw, *lat;
+    int *seg;            // [kT + 1]
+    int *scratch;
+    int Pp;
+};
+
+__device__ __forceinline__ void hx_prepare_into_lds(const PrepArgs &a, const PrepLds &o)
+{
+    constexpr int NCH = HX_MAX_INSTANCES / 256;          // chunks of 256 instances
+    const int tid = threadIdx.x;
+    const int lane = tid & (HX_WAVE - 1), wv = tid >> 6;
+    int *s_wcnt = o.scratch;                             // [NCH * 4 waves][kT]
+    int *s_cnt = o.scratch + NCH * 4 * kT;               // [kT]
+
+    // ---- reads (all of them before the first barrier)
+    const bool has_link = tid < kT * kT;
+    const int tp = tid / kT, td = tid % kT;
+    const bool link_in = has_link && tp < a.T && td < a.T;
+    const float l_bw = link_in ? a.bw[tp * a.T + td] : 1.0f;
+    const float l_lat = (link_in && a.lat) ? a.lat[tp * a.T + td] : 0.0f;
+    int my_t[NCH], d_used[NCH], d_batch[NCH], d_qd[NCH], d_cap[NCH];
+    float d_flops[NCH], d_hbm[NCH];
+    bool bad = false;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+        const int d = j * 256 + tid;
+        const bool has_d = d < a.D;
+        my_t[j] = has_d ? a.d_type[d] : -1;
+        d_used[j] = has_d ? a.d_used[d] : 0; d_batch[j] = has_d ? a.d_batch[d] : 0; d_qd[j] = has_d ? a.d_qd[d] : 0;
+        d_cap[j] = has_d ? a.d_cap[d] : 0;
+        d_flops[j] = has_d ? a.d_flops[d] : 1.0f; d_hbm[j] = has_d ? a.d_hbm[d] : 1.0f;
+        if (has_d && (my_t[j] < 0 || my_t[j] >= a.T)) { bad = true; my_t[j] = 0; }
+    }
+    for (int p = tid; p < o.Pp; p += 256) {
+        const bool in = p < a.P;
+        int p_t = in ? a.p_type[p] : 0;
+        if (in && (p_t < 0 || p_t >= a.T)) { bad = true; p_t = 0; }
+        const float invF = in ? 1.0f / a.p_flops[p] : 0.0f;
+        o.pinvF[p] = invF;
+        o.pinvB[p] = in ? 1.0f / a.p_hbm[p] : 0.0f;
+        o.pw[p] = in ? hx_prefill_wait(a.m, a.p_backlog[p], invF) : INFINITY;    // lanes beyond P never win
+        o.ptype[p] = p_t;
+    }
+    if (bad) hx_raise(a.status, HX_ERR_INDEX);
+    if (has_link) {
+        o.invbw[tid] = link_in ? 1.0f / l_bw : 0.0f;
+        o.lat[tid] = l_lat;
+    }
+
+    // ---- decode instances ranked by class: per-wave class counts (ballots), class sizes, class segments
+    int my_rank[NCH];
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+        my_rank[j] = 0;
+        if (j * 256 < a.D) {
+#pragma unroll
+            for (int t = 0; t < kT; ++t) {
+                const unsigned long long b = __ballot(my_t[j] == t);
+                if (lane == 0) s_wcnt[(j * 4 + wv) * kT + t] = __popcll(b);
+                if (my_t[j] == t) my_rank[j] = __popcll(b & ((1ull << lane) - 1ull));
+            }
+        }
+    }
+    __syncthreads();
+    const int n_slots = (a.D + HX_WAVE - 1) / HX_WAVE;   // waves of instances, in instance order
+    if (tid < HX_WAVE) {                                 // the first wave: lane t < kT owns class t
+        int n = 0;
+        if (tid < kT) {
+            for (int k = 0; k < n_slots; ++k) {
+                const int here = s_wcnt[k * kT + tid];
+                s_wcnt[k * kT + tid] = n;                // instances of the class in earlier waves
+                n += here;
+            }
+            s_cnt[tid] = n;
+        }
+        // class segments: running sum of the padded class sizes over the lanes
+        const int padded = tid < kT ? (n + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP : 0;
+        int incl = padded;
+#pragma unroll
+        for (int off = 1; off < kT; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        if (tid < kT) o.seg[tid] = incl - padded;
+        if (tid == kT - 1) o.seg[kT] = incl;
+    }
+    __syncthreads();
+
+    // ---- entries: pads, then the instances (disjoint indices)
+    const int n_entries = o.seg[kT];
+    for (int e = tid; e < n_entries; e += 256) {
+        int t = 0;
+        while (t + 1 < kT && e >= o.seg[t + 1]) ++t;
+        if (e >= o.seg[t] + s_cnt[t]) {
+            o.wait[e] = 0.0f; o.c1[e] = 0.0f; o.c2[e] = 0.0f; o.kB[e] = 0.0f;
+            o.free[e] = -1; o.orig[e] = -1; o.dtype[e] = t;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+        const int d = j * 256 + tid;
+        if (d < a.D) {
+            const int t = my_t[j];
+            const int e = o.seg[t] + s_wcnt[(j * 4 + wv) * kT + t] + my_rank[j];
+            const HxDecF x = hx_decode_terms(a.m, d_used[j], d_batch[j], d_qd[j], 1.0f / d_flops[j], 1.0f / d_hbm[j]);
+            o.wait[e] = x.wait; o.c1[e] = x.c1; o.c2[e] = x.c2; o.kB[e] = x.kB;
+            const long long fr = (long long)d_cap[j] - (long long)d_used[j];
+            o.free[e] = fr < -1 ? -1 : (fr > 2147483647LL ? 2147483647 : (int)fr);
+            o.orig[e] = d; o.dtype[e] = t;
+        }
+    }
+    __syncthreads();
+}
+
 // ---- common argument block of the scoring kernels ------------------------------
 
 struct ScoreArgs {
@@ -174,11 +297,9 @@ struct FusedLds {
 };
 
 template <int KP>
-__global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, int dp_bound)
+__global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound)
 {
     extern __shared__ __align__(16) float smem[];
-    const HxPrepTables *__restrict__ t = a.prep;
-    const int Dp = t->n_entries;           // <= dp_bound by construction
     const FusedLds lay(dp_bound, a.P);
     float *s_wait = smem;                  // 7 decode arrays of dp_bound entries
     float *s_c1 = s_wait + lay.Dp;
@@ -203,20 +324,12 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, int d
     float2 *wbuf = (float2 *)(s_wave + (size_t)wave * lay.wave_floats());   // (avail, decode time) per entry
     float *xbuf = (float *)(wbuf + lay.Dp);                                  // transfer per class pair
 
-    for (int e = tid; e < Dp; e += blockDim.x) {
-        s_wait[e] = t->dec_wait[e]; s_c1[e] = t->dec_c1[e]; s_c2[e] = t->dec_c2[e]; s_kB[e] = t->dec_kB[e];
-        s_free[e] = t->dec_free[e]; s_orig[e] = t->dec_orig[e]; s_dtype[e] = t->dec_type[e];
-    }
-    for (int p = tid; p < lay.Pp; p += blockDim.x) {
-        bool in = p < a.P;
-        s_pw[p] = in ? t->pre_wait[p] : INFINITY;     // lanes beyond P never win
-        s_pinvF[p] = in ? t->pre_invF[p] : 0.0f;
-        s_pinvB[p] = in ? t->pre_invB[p] : 0.0f;
-        s_ptype[p] = in ? t->pre_type[p] : 0;
-    }
-    if (tid < kT * kT) { s_invbw[tid] = t->link_invbw[tid]; s_lat[tid] = t->link_lat[tid]; }
-    if (tid <= kT) s_seg[tid] = t->seg[tid];
-    __syncthreads();
+    // the per-round tables of the pool, derived here; the class counts of the derivation borrow the
+    // waves' buffers, which nothing has used yet
+    const PrepLds out{s_wait, s_c1, s_c2, s_kB, s_free, s_orig, s_dtype, s_pw, s_pinvF, s_pinvB, s_ptype,
+                      s_invbw, s_lat, s_seg, (int *)s_wave, lay.Pp};
+    hx_prepare_into_lds(pa, out);
+    const int Dp = s_seg[kT];              // <= dp_bound by construction
     for (int e = lane; e < Dp; e += HX_WAVE) wbuf[e].x = s_wait[e];
 
     int seg[kT + 1];
@@ -425,6 +538,19 @@ HxModelF to_model(const hx_model *m)
                     m->weight_bytes, m->nominal_batch};
 }
 
+// the pool tables as the table derivation reads them (pointers checked by the caller)
+PrepArgs make_prep_args(hx_ctx *ctx, const hx_model *model, const hx_prefill_tab *pre, const hx_decode_tab *dec,
+                        const hx_links *links)
+{
+    PrepArgs pa{};
+    pa.m = to_model(model); pa.P = pre->n; pa.D = dec->n; pa.T = links->n_types;
+    pa.p_flops = pre->flops; pa.p_hbm = pre->hbm_bw; pa.p_backlog = pre->backlog_tok; pa.p_type = pre->type;
+    pa.d_flops = dec->flops; pa.d_hbm = dec->hbm_bw; pa.d_used = dec->used_tok; pa.d_cap = dec->cap_tok;
+    pa.d_batch = dec->batch; pa.d_qd = dec->qd_tok; pa.d_type = dec->type;
+    pa.bw = links->bw; pa.lat = links->latency; pa.out = ctx->d_prep; pa.status = ctx->d_status;
+    return pa;
+}
+
 int check_ratio_inputs(hx_ctx *ctx, const hx_calls *calls, const float *tail, const float *horizon,
                        int32_t n_nodes, int32_t n_wf, const float *ratio)
 {
@@ -453,12 +579,7 @@ int hx_prepare_pool(hx_ctx *ctx, const hx_model *model, const hx_prefill_tab *pr
     HX_REQUIRE(ctx, D == 0 || (dec->flops && dec->hbm_bw && dec->used_tok && dec->cap_tok && dec->batch &&
                                dec->qd_tok && dec->type), HX_ERR_INVALID_ARG, "NULL member in decode table");
     HX_REQUIRE(ctx, links->bw, HX_ERR_INVALID_ARG, "links.bw is NULL");
-    PrepArgs pa{};
-    pa.m = to_model(model); pa.P = P; pa.D = D; pa.T = T;
-    pa.p_flops = pre->flops; pa.p_hbm = pre->hbm_bw; pa.p_backlog = pre->backlog_tok; pa.p_type = pre->type;
-    pa.d_flops = dec->flops; pa.d_hbm = dec->hbm_bw; pa.d_used = dec->used_tok; pa.d_cap = dec->cap_tok;
-    pa.d_batch = dec->batch; pa.d_qd = dec->qd_tok; pa.d_type = dec->type;
-    pa.bw = links->bw; pa.lat = links->latency; pa.out = ctx->d_prep; pa.status = ctx->d_status;
+    const PrepArgs pa = make_prep_args(ctx, model, pre, dec, links);
     hx_prepare_kernel<<<1, 1024, 0, stream>>>(pa);
     return hx_check_launch(ctx, "hx_prepare_kernel");
 }
@@ -530,9 +651,9 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         return HX_OK;
     }
 
-    if (int rc = hx_prepare_pool(ctx, model, pre, dec, links, stream)) return rc;
-
     if (fused) {
+        // the search derives the per-round tables of the pool in its own workgroups: no launch of its own for them
+        const PrepArgs pa = make_prep_args(ctx, model, pre, dec, links);
         // upper bound of the padded decode entries, known on the host without reading the device
         const int dp_bound = (D + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP + (T - 1) * HX_DGROUP;
         const int waves = 4;
@@ -544,13 +665,14 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         int grid = ctx->num_cu * blocks_per_cu;
         const int need = (C + waves - 1) / waves;
         grid = grid > need ? need : grid;
-        auto launch = [&](auto kern) { kern<<<grid, waves * HX_WAVE, lds, stream>>>(a, dp_bound); };
+        auto launch = [&](auto kern) { kern<<<grid, waves * HX_WAVE, lds, stream>>>(a, pa, dp_bound); };
         if (P <= 64) launch(hx_fused_search_kernel<1>);
         else if (P <= 128) launch(hx_fused_search_kernel<2>);
         else launch(hx_fused_search_kernel<4>);
         if (int rc = hx_check_launch(ctx, "hx_fused_search_kernel")) return rc;
     }
     if (cost || feas) {
+        if (int rc = hx_prepare_pool(ctx, model, pre, dec, links, stream)) return rc;
         const int P4 = (P + 3) & ~3, D4 = (D + 3) & ~3;
         const int nc = (long long)P * D <= 16384 && C >= 4 * ctx->num_cu * 4 ? 4 : 1;      // calls per workgroup at a time
         const size_t lds = 4 * ((size_t)nc * (P4 + D4 + kT * kT) + 4 * P4 + 6 * D4 + 2 * kT * kT);
