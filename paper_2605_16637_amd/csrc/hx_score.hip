@@ -215,14 +215,9 @@ __device__ __forceinline__ void hx_prepare_into_lds(const PrepArgs &a, const Pre
     const int n_slots = (a.D + HX_WAVE - 1) / HX_WAVE;   // waves of instances, in instance order
     if (tid < HX_WAVE) {                                 // the first wave: lane t < kT owns class t
         int n = 0;
-        if (tid < kT) {
-            for (int k = 0; k < n_slots; ++k) {
-                const int here = s_wcnt[k * kT + tid];
-                s_wcnt[k * kT + tid] = n;                // instances of the class in earlier waves
-                n += here;
-            }
-            s_cnt[tid] = n;
-        }
+        if (tid < kT)
+            for (int k = 0; k < n_slots; ++k) n += s_wcnt[k * kT + tid];     // independent reads
+        if (tid < kT) s_cnt[tid] = n;
         // class segments: running sum of the padded class sizes over the lanes
         const int padded = tid < kT ? (n + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP : 0;
         int incl = padded;
@@ -237,11 +232,18 @@ __device__ __forceinline__ void hx_prepare_into_lds(const PrepArgs &a, const Pre
     __syncthreads();
 
     // ---- entries: pads, then the instances (disjoint indices)
-    const int n_entries = o.seg[kT];
+    int seg[kT + 1], cnt[kT];
+#pragma unroll
+    for (int t = 0; t <= kT; ++t) seg[t] = o.seg[t];
+#pragma unroll
+    for (int t = 0; t < kT; ++t) cnt[t] = s_cnt[t];
+    const int n_entries = seg[kT];
     for (int e = tid; e < n_entries; e += 256) {
-        int t = 0;
-        while (t + 1 < kT && e >= o.seg[t + 1]) ++t;
-        if (e >= o.seg[t] + s_cnt[t]) {
+        int t = 0, first = 0, used = cnt[0];
+#pragma unroll
+        for (int k = 1; k < kT; ++k)
+            if (e >= seg[k]) { t = k; first = seg[k]; used = cnt[k]; }
+        if (e >= first + used) {
             o.wait[e] = 0.0f; o.c1[e] = 0.0f; o.c2[e] = 0.0f; o.kB[e] = 0.0f;
             o.free[e] = -1; o.orig[e] = -1; o.dtype[e] = t;
         }
@@ -251,7 +253,8 @@ __device__ __forceinline__ void hx_prepare_into_lds(const PrepArgs &a, const Pre
         const int d = j * 256 + tid;
         if (d < a.D) {
             const int t = my_t[j];
-            const int e = o.seg[t] + s_wcnt[(j * 4 + wv) * kT + t] + my_rank[j];
+            int e = o.seg[t] + my_rank[j];
+            for (int k = 0; k < j * 4 + wv; ++k) e += s_wcnt[k * kT + t];        // instances of the class in earlier waves
             const HxDecF x = hx_decode_terms(a.m, d_used[j], d_batch[j], d_qd[j], 1.0f / d_flops[j], 1.0f / d_hbm[j]);
             o.wait[e] = x.wait; o.c1[e] = x.c1; o.c2[e] = x.c2; o.kB[e] = x.kB;
             const long long fr = (long long)d_cap[j] - (long long)d_used[j];
