@@ -397,7 +397,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="large", choices=["large", "mid", "stream"])
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--eager", action="store_true", help="launch every step from the host instead of replaying a HIP graph")
+    ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph"],
+                    help="how the timed steps are launched: from the host, one launch after the other (eager), or as "
+                         "replays of a HIP graph; auto = eager for the large and streaming rounds, whose four launches the "
+                         "host enqueues faster than the GPU runs them, graph for the mid round, which is launch-bound")
+    ap.add_argument("--eager", action="store_true", help="same as --launch eager")
     ap.add_argument("--overlap", action="store_true",
                     help="run the horizon refresh on a second stream beside the search (measured: 3-4 us slower per round "
                          "than one stream, the fork and join cost more than the small kernels they hide)")
@@ -423,11 +427,17 @@ def main():
     C, P, D = rnd.calls["n"], rnd.pre["n"], rnd.dec["n"]
     n_cand = C * P * D
 
-    # the round is launch-bound on the host unless its launches are replayed from a HIP graph
+    # A short round is launch-bound on the host unless its launches are replayed from a HIP graph.  A long one
+    # is not, and in a replayed graph the second kernel starts a few microseconds after the first has ended
+    # (seen in the kernel trace whenever the first kernel is shorter than about 7 us): eager launches, which
+    # the host enqueues ahead of the GPU, then give the higher rate.
+    launch = "eager" if args.eager else args.launch
+    if launch == "auto":
+        launch = "graph" if args.workload == "mid" else "eager"
     step = rd.step_overlapped if args.overlap else rd.step
     step()
     torch.cuda.synchronize()
-    run = step if args.eager else capture(torch, step).replay
+    run = step if launch == "eager" else capture(torch, step).replay
     wall = time_steps(torch, run, args.steps, args.warmup)
     ctx.hx_stream_status()
     ms_per_step = wall / args.steps * 1e3
@@ -448,7 +458,7 @@ def main():
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
                    "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
                             if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
-                   "launch": "eager" if args.eager else "hip graph replay", "seed": args.seed},
+                   "launch": "eager, the host enqueues ahead of the GPU" if launch == "eager" else "hip graph replay", "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                      "frac": achieved / ALU_PEAK_TOPS, "traffic": FUSED_TRAFFIC_BYTES.get(args.workload),
@@ -462,7 +472,7 @@ def main():
         rm = RoundOnDevice(ctx, mid)
         rm.step()
         torch.cuda.synchronize()
-        run_mid = rm.step if args.eager else capture(torch, rm.step).replay
+        run_mid = rm.step if (args.eager or args.launch == "eager") else capture(torch, rm.step).replay   # one round at a time: launch-bound
         lat = []
         for i in range(520):
             torch.cuda.synchronize()
