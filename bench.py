@@ -399,8 +399,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph"],
                     help="how the timed steps are launched: from the host, one launch after the other (eager), or as "
-                         "replays of a HIP graph; auto = eager for the large and streaming rounds, whose four launches the "
-                         "host enqueues faster than the GPU runs them, graph for the mid round, which is launch-bound")
+                         "replays of a HIP graph; auto = the faster of the two in a short untimed trial (eager where the "
+                         "host enqueues a step faster than the GPU runs it, graph where the round is launch-bound)")
     ap.add_argument("--eager", action="store_true", help="same as --launch eager")
     ap.add_argument("--overlap", action="store_true",
                     help="run the horizon refresh on a second stream beside the search (measured: 3-4 us slower per round "
@@ -432,12 +432,17 @@ def main():
     # (seen in the kernel trace whenever the first kernel is shorter than about 7 us): eager launches, which
     # the host enqueues ahead of the GPU, then give the higher rate.
     launch = "eager" if args.eager else args.launch
-    if launch == "auto":
-        launch = "graph" if args.workload == "mid" else "eager"
     step = rd.step_overlapped if args.overlap else rd.step
     step()
     torch.cuda.synchronize()
-    run = step if launch == "eager" else capture(torch, step).replay
+    if launch == "auto":
+        # whichever is faster on this host, from a short untimed trial of each (a slow host makes eager launch-bound)
+        replay = capture(torch, step).replay
+        trial = {"eager": time_steps(torch, step, 30, 5), "graph": time_steps(torch, replay, 30, 5)}
+        launch = min(trial, key=trial.get)
+        run = step if launch == "eager" else replay
+    else:
+        run = step if launch == "eager" else capture(torch, step).replay
     wall = time_steps(torch, run, args.steps, args.warmup)
     ctx.hx_stream_status()
     ms_per_step = wall / args.steps * 1e3
