@@ -224,7 +224,7 @@ def gpu_horizons(ctx, rnd, row_ptr, col, L_in, L_out, wf_ptr, check=True):
     return cost.cpu().numpy(), (rem.cpu().numpy(), tail.cpu().numpy(), level.cpu().numpy(), hor.cpu().numpy())
 
 
-@pytest.mark.parametrize("name,seed", [("tiny", 1), ("mid", 3), ("large", 1)])
+@pytest.mark.parametrize("name,seed", [("tiny", 1), ("mid", 3), ("large", 1), ("cp", 2)])
 def test_horizons_in_one_launch(ctx, name, seed):
     """Node cost and critical path in one launch: the cost within tolerance of the oracle's and bit for
     bit what hx_node_cost gives; the pass bit for bit the oracle's fp32 pass on those costs."""
