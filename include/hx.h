@@ -125,7 +125,7 @@ int hx_ctx_create(hx_ctx **out, int device);
 int hx_ctx_destroy(hx_ctx *ctx);
 
 /* Text of the last error of this context (static storage, never NULL); with
- * ctx == NULL, why the last hx_ctx_create of this process failed. */
+ * ctx == NULL, why the last hx_ctx_create or hx_commit_static of this process failed. */
 const char *hx_last_error(const hx_ctx *ctx);
 
 /* Synchronises `stream`, returns the sticky device status (HX_OK or the first
@@ -316,6 +316,30 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
               const int32_t *drain_prefill, const int32_t *drain_decode_q,
               const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
               void *stream);
+
+/*
+ * hx_commit for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Takes
+ * no context and allocates nothing, now or earlier: the per-round accumulators
+ * (one 64-bit word per backlog, used and queue counter, 24 KB) are a static
+ * device array inside the library, one copy per GPU, held until the process
+ * ends.  Same arguments, arithmetic and results as hx_commit, on the current
+ * HIP device; P and D at most HX_MAX_INSTANCES (HX_ERR_SHAPE beyond, nothing
+ * launched).  status: device int32 or NULL; takes the first HX_ERR_INDEX /
+ * HX_ERR_OVERFLOW a kernel raises if it holds 0 (the caller clears and reads
+ * it); with NULL such conditions go unreported (the elements are still
+ * skipped or saturated).  Launches three kernels on `stream` (the first clears
+ * the accumulators: they keep what the last call left) and no memset or copy.
+ * All calls on one GPU share the one array: calls that overlap in time on that
+ * GPU (two streams, two threads) race; calls in stream order do not.  The text
+ * of a failure is returned by hx_last_error(NULL).
+ */
+int hx_commit_static(const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
+                     int32_t P, int32_t *backlog_tok,
+                     int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
+                     const int32_t *drain_prefill, const int32_t *drain_decode_q,
+                     const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
+                     int32_t *status, void *stream);
 
 /*
  * The urgency fold on its own (Eq. (2) with the downstream tail of the call's

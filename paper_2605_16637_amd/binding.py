@@ -18,7 +18,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
            "hx_critical_path", "hx_horizons", "hx_dag_reserve", "hx_dag_append", "hx_dag_set_cost", "hx_dag_view",
-           "hx_score_placements", "hx_select", "hx_urgency", "hx_commit", "hx_rank", "hx_plan_greedy",
+           "hx_score_placements", "hx_select", "hx_urgency", "hx_commit", "hx_commit_static", "hx_rank", "hx_plan_greedy",
            "hx_decode_score", "hx_decode_plan_greedy")
 
 
@@ -352,6 +352,24 @@ class Context:
             _ptr(tail, f32), _ptr(horizon, f32), int(tail.numel()), int(horizon.numel()),
             _ptr(best_d, i32, cs.n), _ptr(best_start, f32, cs.n), _ptr(best_cost, f32, cs.n), _ptr(ratio, f32, cs.n),
             _ptr(rank, i32, cs.n), _stream(stream)))
+
+
+def hx_commit_static(calls, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
+                     drain_prefill=None, drain_decode_q=None, release_tok=None,
+                     tokens_per_seq=2048, max_batch=256, status=None, stream=None):
+    """The commit that needs no context and allocates nothing (static scratch inside the library)."""
+    torch = _torch()
+    lib = load()
+    cs = make_calls(calls)
+    P, D = int(backlog_tok.numel()), int(used_tok.numel())
+    i32 = torch.int32
+    rc = lib.hx_commit_static(
+        C.byref(cs), _ptr(best_p, i32, cs.n), _ptr(best_d, i32, cs.n),
+        P, _ptr(backlog_tok, i32), D, _ptr(used_tok, i32), _ptr(batch, i32, D), _ptr(qd_tok, i32, D),
+        _ptr(drain_prefill, i32, P), _ptr(drain_decode_q, i32, D), _ptr(release_tok, i32, D),
+        int(tokens_per_seq), int(max_batch), _ptr(status, i32, 1), _stream(stream))
+    if rc != HX_OK:
+        raise HxError(rc, lib.hx_last_error(None).decode())
 
 
 def to_device(d: dict, device="cuda:0") -> dict:

@@ -120,6 +120,43 @@ __global__ __launch_bounds__(256) void hx_commit_drain_kernel(CommitArgs a)
     }
 }
 
+// Scratch of hx_commit_static, the commit for callers that cannot allocate: the
+// accumulators of one round, [P] backlog, [D] used, [D] qd additions, then a
+// spare word that takes the status of a caller who passes none.  Each GPU the
+// library runs on holds its own copy (25 KB) until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get
+// the address that call returned for the current device.
+constexpr int HX_STATIC_ACC = 3 * HX_MAX_INSTANCES;
+static __device__ __align__(256) unsigned long long scratch[HX_STATIC_ACC + 32];
+
+constexpr int HX_MAX_DEVICES = 64;
+unsigned long long *g_scratch_ptr[HX_MAX_DEVICES];   // device address of `scratch`, per device; NULL = not asked yet
+
+// address of `scratch` on `device`, which must be the current device
+hipError_t hx_static_scratch(int device, unsigned long long **out)
+{
+    unsigned long long *p = __atomic_load_n(&g_scratch_ptr[device], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void *sym = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!sym) return hipErrorInvalidSymbol;
+        p = (unsigned long long *)sym;
+        __atomic_store_n(&g_scratch_ptr[device], p, __ATOMIC_RELEASE);   // every thread gets the same answer
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+int static_fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_create_err, sizeof(g_create_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
 }  // namespace
 
 extern "C" int hx_ctx_create(hx_ctx **out, int device)
@@ -144,6 +181,11 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (e == hipSuccess) { what = "hipMalloc(tables)"; e = hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)); }
     if (e == hipSuccess) { what = "hipMalloc(flags)"; e = hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)); }
     if (e == hipSuccess) { what = "hipMalloc(accumulators)"; e = hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)); }
+    if (e == hipSuccess && device < HX_MAX_DEVICES) {     // set-up for hx_commit_static on this device
+        what = "hipGetSymbolAddress(scratch)";
+        unsigned long long *p = nullptr;
+        e = hx_static_scratch(device, &p);
+    }
     if (e == hipSuccess && (hx_score_init() != HX_OK || hx_plan_init() != HX_OK || hx_decode_init() != HX_OK)) { what = "hipFuncSetAttribute(LDS size)"; e = hipErrorInvalidValue; }
     if (e == hipSuccess) {
         what = "launch of hx_clear_status_kernel";
@@ -237,4 +279,48 @@ extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best
     const int n_inst = P > D ? P : D;
     hx_commit_drain_kernel<<<(n_inst + 255) / 256, 256, 0, stream>>>(a);
     return hx_check_launch(ctx, "hx_commit kernels");
+}
+
+extern "C" int hx_commit_static(const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
+                                int32_t P, int32_t *backlog_tok,
+                                int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
+                                const int32_t *drain_prefill, const int32_t *drain_decode_q,
+                                const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
+                                int32_t *status, void *stream_)
+{
+    if (!calls) return static_fail(HX_ERR_INVALID_ARG, "hx_commit_static: NULL calls");
+    const int C = calls->n;
+    if (C < 0 || P < 0 || D < 0) return static_fail(HX_ERR_INVALID_ARG, "hx_commit_static: negative size");
+    if (P > HX_MAX_INSTANCES || D > HX_MAX_INSTANCES)
+        return static_fail(HX_ERR_SHAPE, "hx_commit_static: pool %d x %d beyond the %d instances per side its static scratch holds",
+                           P, D, HX_MAX_INSTANCES);
+    if (tokens_per_seq <= 0 || max_batch < 0) return static_fail(HX_ERR_INVALID_ARG, "hx_commit_static: tokens_per_seq must be positive");
+    if (C > 0 && !(calls->L_in && calls->L_out && best_p && best_d)) return static_fail(HX_ERR_INVALID_ARG, "hx_commit_static: NULL call array");
+    if (P > 0 && !backlog_tok) return static_fail(HX_ERR_INVALID_ARG, "hx_commit_static: NULL backlog_tok");
+    if (D > 0 && !(used_tok && batch && qd_tok)) return static_fail(HX_ERR_INVALID_ARG, "hx_commit_static: NULL decode array");
+    if (P + D == 0) return HX_OK;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return static_fail(HX_ERR_DEVICE, "hx_commit_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (device < 0 || device >= HX_MAX_DEVICES) return static_fail(HX_ERR_SHAPE, "hx_commit_static: device %d beyond the %d it keeps scratch for", device, HX_MAX_DEVICES);
+    unsigned long long *acc = nullptr;
+    e = hx_static_scratch(device, &acc);
+    if (e != hipSuccess) return static_fail(HX_ERR_DEVICE, "hx_commit_static: hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    hipStream_t stream = (hipStream_t)stream_;
+    CommitArgs a{C, P, D, calls->L_in, calls->L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
+                 drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, acc,
+                 status ? status : (int32_t *)(acc + HX_STATIC_ACC)};
+    // the array keeps what the last call left: start from zero whatever that was
+    // (a fill kernel, so that the call can be captured in a graph)
+    hx_commit_clear_kernel<<<(P + 2 * D + 255) / 256, 256, 0, stream>>>(a);
+    if (C > 0) {
+        int grid = (C + 255) / 256;
+        grid = grid > 256 ? 256 : grid;
+        hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a);
+    }
+    const int n_inst = P > D ? P : D;
+    hx_commit_drain_kernel<<<(n_inst + 255) / 256, 256, 0, stream>>>(a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return static_fail(HX_ERR_DEVICE, "hx_commit_static: launch: %s", hipGetErrorString(e));
+    return HX_OK;
 }
