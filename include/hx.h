@@ -267,7 +267,7 @@ int hx_dag_view(hx_ctx *ctx, const float **rem, const float **tail, const int32_
  * (Eq. (2) with the downstream tail of the call's node; needs tail [n_nodes],
  * horizon [n_wf] and the node/wf/elapsed members of `calls`; a node or
  * workflow index outside those lengths gives NaN and raises HX_ERR_INDEX in
- * the stream status).  best_p, best_d, best_cost are
+ * the stream status; a workflow whose horizon is 0 gives +infinity).  best_p, best_d, best_cost are
  * all NULL or all non-NULL; ratio may be NULL on its own.
  * Materialised outputs, each may be NULL: cost [C*P*D] row-major (c,p,d) --
  * bit-identical to what the fused search compares; feas [C*D] 1/0.
@@ -349,7 +349,8 @@ int hx_commit_static(const hx_calls *calls, const int32_t *best_p, const int32_t
  * the horizons of the round are still being refreshed on another, and fold
  * them in afterwards.  calls->node, wf, elapsed, best_cost, ratio: device [C];
  * a node or workflow outside 0..n_nodes-1 / 0..n_wf-1 gives NaN and raises
- * HX_ERR_INDEX in the stream status.
+ * HX_ERR_INDEX in the stream status; a horizon of 0 gives +infinity (Eq. (2)
+ * is undefined there: such a call counts as most urgent).
  */
 int hx_urgency(hx_ctx *ctx, const hx_calls *calls, const float *best_cost,
                const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,

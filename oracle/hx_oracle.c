@@ -66,7 +66,7 @@
  *                        rem(v) = cost(v) + tail(v),
  *                        level(v) = 0 without successors, else
  *                        1 + max level(u);  H(w) = max_{v in w} rem(v)
- *  R11 urgency           R(c) = (elapsed_c + Delta*_c + tail(node_c)) / H(wf_c)
+ *  R11 urgency           R(c) = (elapsed_c + Delta*_c + tail(node_c)) / H(wf_c); +inf where H(wf_c) = 0
  *                        = Eq. (2) whenever the call is a leaf of the
  *                        revealed DAG (tail = 0)
  *  R12 commit and drain  integer bookkeeping of chosen placements, see
@@ -425,13 +425,60 @@ int hxo_horizon_by_id(int32_t n, const double *rem, const int32_t *wf_of_node,
     return 0;
 }
 
-/* R11: Eq. (2) with the downstream tail of the call's node added. */
+/* R10 on a graph in reveal order (Sec. 4.1: a call is revealed after its
+ * parents, so every parent has a smaller id than its child), given as parent
+ * lists with a per-node workflow id: the same definition as hxo_critical_path,
+ * evaluated by one pass from the last node to the first.  When node v is
+ * reached every successor of v (a larger id) is final and has already offered
+ * its rem and level to v, so tail[v] and level[v] are complete; rem[v] is then
+ * one addition and v offers it to its own parents.  For long-lived graphs of
+ * tens of millions of nodes, where the depth-first form's transposition of the
+ * parent lists is what costs.
+ * Returns 0; -1 bad argument (a parent id not below its child's, a workflow id
+ * out of range). */
+int hxo_critical_path_revealed(int32_t n, const int32_t *parent_row_ptr, const int32_t *parent_col,
+                               const double *cost, const int32_t *wf_of_node, int32_t n_wf, int round_f32,
+                               double *rem, double *tail, int32_t *level, double *horizon)
+{
+    if (n < 0 || n_wf < 0) return -1;
+    for (int32_t v = 0; v < n; ++v) {
+        if (parent_row_ptr[v] > parent_row_ptr[v + 1] || parent_row_ptr[v] < 0) return -1;
+        for (int32_t e = parent_row_ptr[v]; e < parent_row_ptr[v + 1]; ++e)
+            if (parent_col[e] < 0 || parent_col[e] >= v) return -1;
+        if (wf_of_node[v] < 0 || wf_of_node[v] >= n_wf) return -1;
+        tail[v] = 0.0; level[v] = 0;
+    }
+    for (int32_t w = 0; w < n_wf; ++w) horizon[w] = 0.0;
+    for (int32_t v = n - 1; v >= 0; --v) {
+        double r = cost[v] + tail[v];
+        if (round_f32) r = (double)(float)r;
+        rem[v] = r;
+        if (r > horizon[wf_of_node[v]]) horizon[wf_of_node[v]] = r;
+        for (int32_t e = parent_row_ptr[v]; e < parent_row_ptr[v + 1]; ++e) {
+            int32_t u = parent_col[e];
+            if (r > tail[u]) tail[u] = r;
+            if (level[v] + 1 > level[u]) level[u] = level[v] + 1;
+        }
+    }
+    return 0;
+}
+
+/* R11: Eq. (2) with the downstream tail of the call's node added.  Eq. (2)
+ * divides by the workflow's horizon and says nothing of a horizon of zero (a
+ * workflow whose revealed calls all cost nothing); the reading taken here: such
+ * a call is as urgent as can be, R = +infinity, whatever the numerator. */
+static double ratio_r11(double elapsed, double cost, double tail, double horizon)
+{
+    if (!(horizon > 0.0)) return INFINITY;
+    return (elapsed + cost + tail) / horizon;
+}
+
 int hxo_urgency(int32_t C, const double *elapsed, const double *best_cost,
                 const int32_t *node, const int32_t *wf,
                 const double *tail, const double *horizon, double *ratio)
 {
     for (int32_t c = 0; c < C; ++c)
-        ratio[c] = (elapsed[c] + best_cost[c] + tail[node[c]]) / horizon[wf[c]];
+        ratio[c] = ratio_r11(elapsed[c], best_cost[c], tail[node[c]], horizon[wf[c]]);
     return 0;
 }
 
@@ -546,7 +593,7 @@ int hxo_plan_greedy(const hxo_model *m,
                                                   (double)link_bw[tp * T + td], lat);
                     if (v < bc) { bc = v; bp = p; bd = d; }
                 }
-            double r = (elapsed[c] + bc + tail[node[c]]) / horizon[wf[c]];
+            double r = ratio_r11(elapsed[c], bc, tail[node[c]], horizon[wf[c]]);
             if (pick < 0 || r > pick_r) { pick = c; pick_r = r; pick_cost = bc; pick_p = bp; pick_d = bd; }
         }
         done[pick] = 1;
@@ -606,18 +653,56 @@ double hxo_decode_start(int32_t m_tok, double T, int32_t cap_tok,
 /*
  * R24, R25: decode-stage score of every (call, instance).  Interval lists are
  * stored with a fixed stride: instance d owns entries d*stride .. d*stride +
- * iv_count[d] - 1.  Every decode time is taken as t_scale * Tdec + t_shift
- * (1 and 0 for the method itself; the parity tests use them to bracket what
- * fp32 rounding of Tdec and of start + Tdec can decide differently).
- * start, cost: [Q*D] or NULL; best_*: [Q].  Returns -3 on a lock outside
- * [-1, D).
+ * iv_count[d] - 1.  start, cost: [Q*D] or NULL; best_*: [Q].  Returns -3 on a
+ * lock outside [-1, D).
  */
 int hxo_decode_score(const hxo_model *m, int32_t Q, const int32_t *L_in, const int32_t *L_out, const int32_t *lock,
                      int32_t D, const float *dF, const float *dB, const int32_t *d_used, const int32_t *d_cap,
                      const int32_t *d_batch,
                      int32_t stride, const int32_t *iv_count, const double *iv_start, const double *iv_end,
-                     const int32_t *iv_tok, double t_scale, double t_shift,
+                     const int32_t *iv_tok,
                      double *start, double *cost, int32_t *best_d, double *best_start, double *best_cost)
+{
+    if (Q < 0 || D < 0 || stride < 0) return -1;
+    for (int32_t c = 0; c < Q; ++c)
+        if (lock && (lock[c] < -1 || lock[c] >= D)) return -3;
+    for (int32_t c = 0; c < Q; ++c) {
+        double bc = INFINITY, bs = INFINITY;
+        int32_t bd = -1;
+        for (int32_t d = 0; d < D; ++d) {
+            double S = INFINITY, v = INFINITY;
+            if (!lock || lock[c] < 0 || lock[c] == d) {
+                double T = (double)L_out[c] *
+                           hxo_decode_token_time(m, L_in[c], L_out[c], d_batch[d], d_used[d], (double)dF[d], (double)dB[d]);
+                int64_t need = (int64_t)L_in[c] + (int64_t)L_out[c];
+                int32_t m_tok = need > 2147483647LL ? 2147483647 : (int32_t)need;
+                if (need <= (int64_t)d_cap[d])
+                    S = hxo_decode_start(m_tok, T, d_cap[d], iv_count[d], iv_start + (size_t)d * stride,
+                                         iv_end + (size_t)d * stride, iv_tok + (size_t)d * stride);
+                v = S + T;
+            }
+            if (start) start[(size_t)c * D + d] = S;
+            if (cost) cost[(size_t)c * D + d] = v;
+            if (v < bc) { bc = v; bs = S; bd = d; }
+        }
+        best_d[c] = bd; best_start[c] = bs; best_cost[c] = bc;
+    }
+    return 0;
+}
+
+/*
+ * Not part of the method: hxo_decode_score with every decode time replaced by
+ * max(0, t_scale * Tdec + t_shift), for the parity tests of a finished plan,
+ * which bracket what fp32 rounding of Tdec and of start + Tdec can decide
+ * differently (a plan creates exact ties: a call placed where another of the
+ * same decode time ended).  At (1, 0) it returns what hxo_decode_score returns.
+ */
+int hxo_decode_score_bracket(const hxo_model *m, int32_t Q, const int32_t *L_in, const int32_t *L_out, const int32_t *lock,
+                             int32_t D, const float *dF, const float *dB, const int32_t *d_used, const int32_t *d_cap,
+                             const int32_t *d_batch,
+                             int32_t stride, const int32_t *iv_count, const double *iv_start, const double *iv_end,
+                             const int32_t *iv_tok, double t_scale, double t_shift,
+                             double *start, double *cost, int32_t *best_d, double *best_start, double *best_cost)
 {
     if (Q < 0 || D < 0 || stride < 0) return -1;
     for (int32_t c = 0; c < Q; ++c)
@@ -671,9 +756,9 @@ int hxo_decode_plan_greedy(const hxo_model *m, int32_t Q, const int32_t *L_in, c
             int32_t bd;
             double bs, bc;
             rc = hxo_decode_score(m, 1, L_in + c, L_out + c, lock ? lock + c : NULL, D, dF, dB, d_used, d_cap, d_batch,
-                                  stride, iv_count, iv_start, iv_end, iv_tok, 1.0, 0.0, NULL, NULL, &bd, &bs, &bc);
+                                  stride, iv_count, iv_start, iv_end, iv_tok, NULL, NULL, &bd, &bs, &bc);
             if (rc) break;
-            double r = (elapsed[c] + bc + tail[node[c]]) / horizon[wf[c]];
+            double r = ratio_r11(elapsed[c], bc, tail[node[c]], horizon[wf[c]]);
             if (pick < 0 || r > pick_r) { pick = c; pick_r = r; pick_d = bd; pick_s = bs; pick_cost = bc; }
         }
         if (rc) break;

@@ -198,6 +198,29 @@ def critical_path_by_parents(parent_row_ptr, parent_col, cost, wf_of_node, n_wf,
     return rem, tail, level, hor
 
 
+def critical_path_revealed(parent_row_ptr, parent_col, cost, wf_of_node, n_wf, round_f32=True, out=None):
+    """R10 on a graph in reveal order (every parent id below its child's), one
+    pass from the last node to the first; same results as critical_path_by_parents.
+    out: optional (rem f64, tail f64, level i32, horizon f64) buffers at least as
+    long as needed, reused by callers that repeat the pass on a growing graph
+    (the results are views of their heads)."""
+    prow, pcol, wf = _i32(parent_row_ptr), _i32(parent_col), _i32(wf_of_node)
+    cost = _f64(cost)
+    n = cost.size
+    if out is None:
+        rem = np.empty(n, np.float64); tail = np.empty(n, np.float64)
+        level = np.empty(n, np.int32); hor = np.empty(n_wf, np.float64)
+    else:
+        rem, tail, level, hor = out[0][:n], out[1][:n], out[2][:n], out[3][:n_wf]
+        assert rem.dtype == np.float64 and tail.dtype == np.float64 and level.dtype == np.int32 and hor.dtype == np.float64
+        assert rem.size == n and tail.size == n and level.size == n and hor.size == n_wf
+    rc = lib().hxo_critical_path_revealed(n, _p(prow), _p(pcol), _p(cost), _p(wf), int(n_wf),
+                                          1 if round_f32 else 0, _p(rem), _p(tail), _p(level), _p(hor))
+    if rc:
+        raise ValueError("not in reveal order, or a workflow id out of range")
+    return rem, tail, level, hor
+
+
 def urgency(elapsed, best_cost, node, wf, tail, horizon):
     """R11 / Eq. (2)."""
     elapsed, best_cost, tail, horizon = _f64(elapsed), _f64(best_cost), _f64(tail), _f64(horizon)
@@ -291,8 +314,7 @@ def _intervals(iv, D):
     return stride, cnt, s, e, k
 
 
-def decode_score(model, L_in, L_out, lock, dec, iv, t_scale=1.0, t_shift=0.0, want_all=False) -> DecodeScore:
-    """R24/R25 over all (call, decode instance) pairs."""
+def _decode_score(fn, extra, model, L_in, L_out, lock, dec, iv, want_all):
     L_in, L_out = _i32(L_in), _i32(L_out)
     lock = None if lock is None else _i32(lock)
     dF, dB, dus, dcap, dba = _f32(dec["flops"]), _f32(dec["hbm_bw"]), _i32(dec["used_tok"]), _i32(dec["cap_tok"]), _i32(dec["batch"])
@@ -302,12 +324,23 @@ def decode_score(model, L_in, L_out, lock, dec, iv, t_scale=1.0, t_shift=0.0, wa
     st = np.empty((Q, D), np.float64) if want_all else None
     co = np.empty((Q, D), np.float64) if want_all else None
     m = _model(model)
-    rc = lib().hxo_decode_score(C.byref(m), Q, _p(L_in), _p(L_out), _p(lock), D, _p(dF), _p(dB), _p(dus), _p(dcap), _p(dba),
-                                stride, _p(cnt), _p(s), _p(e), _p(k), C.c_double(float(t_scale)), C.c_double(float(t_shift)),
-                                _p(st), _p(co), _p(bd), _p(bs), _p(bc))
+    rc = fn(C.byref(m), Q, _p(L_in), _p(L_out), _p(lock), D, _p(dF), _p(dB), _p(dus), _p(dcap), _p(dba),
+            stride, _p(cnt), _p(s), _p(e), _p(k), *extra, _p(st), _p(co), _p(bd), _p(bs), _p(bc))
     if rc:
-        raise ValueError(f"hxo_decode_score failed: {rc}")
+        raise ValueError(f"decode score failed: {rc}")
     return DecodeScore(bd, bs, bc, st, co)
+
+
+def decode_score(model, L_in, L_out, lock, dec, iv, want_all=False) -> DecodeScore:
+    """R24/R25 over all (call, decode instance) pairs."""
+    return _decode_score(lib().hxo_decode_score, (), model, L_in, L_out, lock, dec, iv, want_all)
+
+
+def decode_score_bracket(model, L_in, L_out, lock, dec, iv, t_scale, t_shift, want_all=False) -> DecodeScore:
+    """Not the method: decode_score with every decode time replaced by
+    max(0, t_scale * T + t_shift); only the parity test of a finished decode plan uses it."""
+    return _decode_score(lib().hxo_decode_score_bracket, (C.c_double(float(t_scale)), C.c_double(float(t_shift))),
+                         model, L_in, L_out, lock, dec, iv, want_all)
 
 
 @dataclass

@@ -793,7 +793,7 @@ __global__ __launch_bounds__(64) void hx_decode_finish_kernel(DecodeFinishArgs a
     }
     a.best_d[c] = d; a.best_start[c] = S; a.best_cost[c] = v;
     if (a.ratio)
-        a.ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, v, a.status);
+        hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, v, a.status, a.ratio);
 }
 
 // ---- recomputing greedy of the decode stage, one workgroup -----------------------------
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     int *s_O = s_L + lay.Q;
     int *s_lk = s_O + lay.Q;
     float *s_el = (float *)(s_lk + lay.Q);
-    float *s_tail = s_el + lay.Q;                          // tail of its node, horizon of its workflow (NaN: index out of range)
+    float *s_tail = s_el + lay.Q;                          // tail of its node, horizon of its workflow (-1: index out of range)
     float *s_hz = s_tail + lay.Q;
     float *s_redv = (float *)(smem + lay.off_red());
     int *s_redi = (int *)(s_redv + DG_WAVES);
@@ -890,8 +890,8 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         const int nd = a.node[c], w = a.wf[c];
         const bool ok = nd >= 0 && nd < a.n_nodes && w >= 0 && w < a.n_wf;
         if (!ok) hx_raise(a.status, HX_ERR_INDEX);
-        s_tail[c] = ok ? a.tail[nd] : __uint_as_float(0x7fc00000u);
-        s_hz[c] = ok ? a.horizon[w] : __uint_as_float(0x7fc00000u);
+        s_tail[c] = ok ? a.tail[nd] : 0.0f;
+        s_hz[c] = ok ? fmaxf(a.horizon[w], 0.0f) : -1.0f;
     }
     __syncthreads();
     for (int d = 0; d < a.D; ++d) {
@@ -929,7 +929,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 s_bd[c] = any ? best_d : -1;
                 s_bs[c] = any ? best_S : INFINITY;
                 s_bc[c] = any ? best : INFINITY;
-                s_ratio[c] = ((s_el[c] + (any ? best : INFINITY)) + s_tail[c]) / s_hz[c];       // Eq. (2), as hx_projected_ratio forms it
+                hx_store_bits(s_ratio, c, hx_ratio_bits(s_el[c], any ? best : INFINITY, s_tail[c], s_hz[c], s_hz[c] >= 0.0f));   // Eq. (2)
                 s_flags[c] = DG_ALIVE;
             }
         }
@@ -968,7 +968,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 const HxDecodeCand q = hx_decode_candidate(a.m, s_L[c], s_O[c], -1, d, a.D, x, s_cap[d], a.status);
                 s_bs[c] = hx_earliest_start(s_tl + (size_t)d * lay.nt, s_src + (size_t)d * lay.ne, s_n[d], q.thr, q.T, true).S;
             }
-            a.best_d[c] = d; a.best_start[c] = s_bs[c]; a.best_cost[c] = s_bc[c]; a.ratio[c] = s_ratio[c]; a.rank[c] = k;
+            a.best_d[c] = d; a.best_start[c] = s_bs[c]; a.best_cost[c] = s_bc[c]; hx_store_bits(a.ratio, c, __float_as_uint(s_ratio[c])); a.rank[c] = k;
             s_flags[c] = 0;
             int changed = -1;
             if (d >= 0) {
@@ -1037,7 +1037,7 @@ __global__ __launch_bounds__(256) void hx_decode_no_instance_kernel(DGreedyArgs 
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= a.Q) return;
     a.best_d[c] = -1; a.best_start[c] = INFINITY; a.best_cost[c] = INFINITY; a.rank[c] = c;
-    a.ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, INFINITY, a.status);
+    hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, INFINITY, a.status, a.ratio);
 }
 
 HxModelF to_model(const hx_model *m)

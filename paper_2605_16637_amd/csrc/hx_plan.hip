@@ -236,8 +236,10 @@ enum : int { ALIVE = 1, DIRTY = 2 };
 // One block plans the whole queue: the pool tables, the simulated state and the
 // per-call results live in LDS, there is no launch between iterations.  A call
 // is scored again only if its current pair touches an instance a commit just
-// changed and the pair's cost moved: additions to the state can only raise costs,
-// so every other call keeps its pair and cost exactly.
+// changed and the pair's cost moved: while commits only add load they can only
+// raise costs, so every other call keeps its pair and cost exactly.  A commit
+// that lowers a term of its decode instance (a snapshot batch above the batch
+// rule's value) has every remaining call scored again.
 template <int KP>
 __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyArgs a, int dp_bound)
 {
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     int *s_L = s_flags + lay.C;                        // what the queue says of a call, read once
     int *s_O = s_L + lay.C;
     float *s_el = (float *)(s_O + lay.C);
-    float *s_tl = s_el + lay.C;                        // tail of its node, horizon of its workflow (NaN: index out of range)
+    float *s_tl = s_el + lay.C;                        // tail of its node, horizon of its workflow (-1: index out of range)
     float *s_hz = s_tl + lay.C;
     float *s_redv = (float *)(s_hz + lay.C);           // reduction scratch, then the pick
     int *s_redi = (int *)(s_redv + GREEDY_WAVES);
@@ -314,8 +316,8 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         const int nd = a.node[c], w = a.wf[c];
         const bool ok = nd >= 0 && nd < a.n_nodes && w >= 0 && w < a.n_wf;
         if (!ok) hx_raise(a.status, HX_ERR_INDEX);
-        s_tl[c] = ok ? a.tail[nd] : __uint_as_float(0x7fc00000u);
-        s_hz[c] = ok ? a.horizon[w] : __uint_as_float(0x7fc00000u);
+        s_tl[c] = ok ? a.tail[nd] : 0.0f;
+        s_hz[c] = ok ? fmaxf(a.horizon[w], 0.0f) : -1.0f;
     }
     __syncthreads();
 
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             else b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, s_L[c], s_O[c], lane);
             if (lane == 0) {
                 s_bp[c] = b.p; s_bd[c] = b.d; s_bc[c] = b.cost;
-                s_ratio[c] = ((s_el[c] + b.cost) + s_tl[c]) / s_hz[c];       // Eq. (2), as hx_projected_ratio forms it
+                hx_store_bits(s_ratio, c, hx_ratio_bits(s_el[c], b.cost, s_tl[c], s_hz[c], s_hz[c] >= 0.0f));       // Eq. (2)
                 s_flags[c] = ALIVE;
             }
         }
@@ -368,7 +370,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
                 if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
             }
             const int c = bi, p = s_bp[c], d = s_bd[c];
-            a.best_p[c] = p; a.best_d[c] = d; a.best_cost[c] = s_bc[c]; a.ratio[c] = s_ratio[c]; a.rank[c] = k;
+            a.best_p[c] = p; a.best_d[c] = d; a.best_cost[c] = s_bc[c]; hx_store_bits(a.ratio, c, __float_as_uint(s_ratio[c])); a.rank[c] = k;
             s_flags[c] = 0;
             s_pick[0] = c; s_pick[1] = p; s_pick[2] = d;
             if (p >= 0) {
@@ -386,18 +388,27 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
                 s_pw[p] = hx_prefill_wait(a.m, s_backlog[p], s_pinvF[p]);
                 const HxDecF x = hx_decode_terms(a.m, s_used[d], s_batch[d], s_qd[d], s_dinvF[d], s_dinvB[d]);
                 const int e = s_pos[d];
-                s_wait[e] = x.wait; s_c1[e] = x.c1; s_c2[e] = x.c2; s_kB[e] = x.kB;
                 const long long fr = (long long)s_cap[d] - us;
-                s_free[e] = fr < -1 ? -1 : (int)fr;
+                const int nfree = fr < -1 ? -1 : (int)fr;
+                // A commit normally only adds load.  It lowers a term when the snapshot's batch stood above what
+                // the batch rule gives for the new occupancy (the caller's batch is only required to be >= 0):
+                // then pairs on d get cheaper and any call may prefer d now.
+                s_pick[3] = (x.wait < s_wait[e] || x.c1 < s_c1[e] || x.c2 < s_c2[e] || nfree > s_free[e]) ? 1 : 0;
+                s_wait[e] = x.wait; s_c1[e] = x.c1; s_c2[e] = x.c2; s_kB[e] = x.kB;
+                s_free[e] = nfree;
             }
         }
         __syncthreads();
-        // (4) calls whose pair touches a changed instance are scored again
+        // (4) which calls are scored again
         const int pp = s_pick[1], pd = s_pick[2];
-        if (pp >= 0) {
-            // ... unless the cost of that pair came out the same (e.g. the decode instance's availability still
-            // dominates a longer prefill queue): every other pair costs what it did or more, so the pair is still
-            // the lexicographic minimum
+        if (pp >= 0 && s_pick[3]) {
+            // a term of the decode instance fell: nothing can be kept
+            for (int c = tid; c < a.C; c += GREEDY_THREADS)
+                if (s_flags[c] & ALIVE) s_flags[c] = ALIVE | DIRTY;
+        } else if (pp >= 0) {
+            // load was only added: every pair costs what it did or more, so only calls whose pair touches one of
+            // the two instances can lose their minimum -- and not even those if the cost of their pair came out
+            // the same (e.g. the decode instance's availability still dominates a longer prefill queue)
             for (int c = tid; c < a.C; c += GREEDY_THREADS)
                 if ((s_flags[c] & ALIVE) && (s_bp[c] == pp || s_bd[c] == pd) &&
                     hx_pair_cost(a.m, pool, s_L[c], s_O[c], s_bp[c], s_pos[s_bd[c]]) != s_bc[c])
@@ -420,7 +431,7 @@ __global__ __launch_bounds__(256) void hx_plan_no_pool_kernel(GreedyArgs a)
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= a.C) return;
     a.best_p[c] = -1; a.best_d[c] = -1; a.best_cost[c] = INFINITY; a.rank[c] = c;
-    a.ratio[c] = hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, INFINITY, a.status);
+    hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, INFINITY, a.status, a.ratio);
 }
 
 __global__ __launch_bounds__(256) void hx_copy_i32_kernel(const int32_t *src, int32_t *dst, int n)

@@ -282,9 +282,9 @@ struct ScoreArgs {
 };
 
 // projected ratio, Eq. (2), with the downstream tail of the call's node
-__device__ __forceinline__ float hx_ratio(const ScoreArgs &a, int c, float best)
+__device__ __forceinline__ void hx_ratio(const ScoreArgs &a, int c, float best)
 {
-    return hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, best, a.status);
+    hx_projected_ratio(a.node, a.wf, a.elapsed, a.tail, a.horizon, a.n_nodes, a.n_wf, c, best, a.status, a.ratio);
 }
 
 // ---- fused search ----------------------------------------------------------------
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, PrepA
             a.best_p[c] = pstar;
             a.best_d[c] = dstar;
             a.best_cost[c] = bestv;
-            if (a.ratio) a.ratio[c] = hx_ratio(a, c, bestv);
+            if (a.ratio) hx_ratio(a, c, bestv);
         }
     }
 }
@@ -513,26 +513,27 @@ __global__ __launch_bounds__(256) void hx_select_kernel(ScoreArgs a)
             a.best_p[c] = any ? bi / a.D : -1;
             a.best_d[c] = any ? bi % a.D : -1;
             a.best_cost[c] = bv;
-            if (a.ratio) a.ratio[c] = hx_ratio(a, c, bv);
+            if (a.ratio) hx_ratio(a, c, bv);
         }
     }
 }
 
-// fused outputs when the pool is empty: nothing is feasible
+// the urgency fold on its own: Eq. (2) from best costs found earlier
 __global__ __launch_bounds__(256) void hx_urgency_kernel(const int32_t *node, const int32_t *wf, const float *elapsed,
                                                          const float *best_cost, const float *tail, const float *horizon,
                                                          int n_nodes, int n_wf, int C, float *ratio, int32_t *status)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < C) ratio[c] = hx_projected_ratio(node, wf, elapsed, tail, horizon, n_nodes, n_wf, c, best_cost[c], status);
+    if (c < C) hx_projected_ratio(node, wf, elapsed, tail, horizon, n_nodes, n_wf, c, best_cost[c], status, ratio);
 }
 
+// fused outputs when the pool is empty: nothing is feasible
 __global__ void hx_no_pool_kernel(ScoreArgs a)
 {
     int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= a.C) return;
     a.best_p[c] = -1; a.best_d[c] = -1; a.best_cost[c] = INFINITY;
-    if (a.ratio) a.ratio[c] = hx_ratio(a, c, INFINITY);
+    if (a.ratio) hx_ratio(a, c, INFINITY);
 }
 
 HxModelF to_model(const hx_model *m)

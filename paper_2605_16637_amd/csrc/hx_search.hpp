@@ -260,23 +260,36 @@ __device__ __forceinline__ float hx_pair_cost(const HxModelF &m, const HxPoolLds
     return hx_candidate(done + x, s.wait[e], dec);
 }
 
-// projected ratio of a call, Eq. (2) with the downstream tail of the call's
-// node: (elapsed + best + tail[node]) / horizon[wf].  A node or workflow index
+// The library is built on the assumption that no arithmetic ever sees a NaN, so
+// the NaN that marks a bad index is chosen among integers and stored as bits.
+constexpr unsigned HX_QNAN_BITS = 0x7fc00000u;
+
+// Eq. (2) with the downstream tail of the call's node, as bits: (elapsed + best
+// + tail) / horizon; a workflow without a horizon (0: nothing it has revealed
+// costs anything) makes its calls as urgent as can be, +inf; !ok gives the NaN.
+__device__ __forceinline__ unsigned hx_ratio_bits(float elapsed, float best, float tail, float horizon, bool ok)
+{
+    const float r = horizon > 0.0f ? ((elapsed + best) + tail) / horizon : INFINITY;
+    return ok ? __float_as_uint(r) : HX_QNAN_BITS;
+}
+
+__device__ __forceinline__ void hx_store_bits(float *out, int i, unsigned bits) { ((unsigned *)out)[i] = bits; }
+
+// projected ratio of call c, stored to ratio[c].  A node or workflow index
 // outside the arrays gives NaN and raises HX_ERR_INDEX.
-__device__ __forceinline__ float hx_projected_ratio(const int32_t *node, const int32_t *wf, const float *elapsed,
-                                                    const float *tail, const float *horizon, int n_nodes, int n_wf,
-                                                    int c, float best, int32_t *status)
+__device__ __forceinline__ void hx_projected_ratio(const int32_t *node, const int32_t *wf, const float *elapsed,
+                                                   const float *tail, const float *horizon, int n_nodes, int n_wf,
+                                                   int c, float best, int32_t *status, float *ratio)
 {
     const int nd = node[c], w = wf[c];
-    if (nd < 0 || nd >= n_nodes || w < 0 || w >= n_wf) {
-        hx_raise(status, HX_ERR_INDEX);
-        return __uint_as_float(0x7fc00000u);   // quiet NaN
-    }
-    return ((elapsed[c] + best) + tail[nd]) / horizon[w];
+    const bool ok = nd >= 0 && nd < n_nodes && w >= 0 && w < n_wf;
+    if (!ok) hx_raise(status, HX_ERR_INDEX);
+    hx_store_bits(ratio, c, hx_ratio_bits(elapsed[c], best, ok ? tail[nd] : 0.0f, ok ? horizon[w] : 1.0f, ok));
 }
 
 // ordering key of a ratio: a NaN (raised elsewhere as a bad index) sorts with +inf
 __device__ __forceinline__ float hx_rank_key(float r)
 {
-    return (__float_as_uint(r) & 0x7fffffffu) > 0x7f800000u ? INFINITY : r;
+    const unsigned b = __float_as_uint(r);                       // chosen among integers: r may be the NaN
+    return __uint_as_float((b & 0x7fffffffu) > 0x7f800000u ? 0x7f800000u : b);
 }

@@ -337,8 +337,8 @@ def check_plan_stepwise(model, L, O, lock, node, wf, elapsed, tail, hor, dec, iv
         # urgent as every call's most optimistic score.
         lk = None if lock_a is None else lock_a[alive]
         shift = 2.5e-7 * (1.0 + float(np.max(st["end"], initial=0.0)))
-        s = o.decode_score(model, L[alive], O[alive], lk, dec, cur, t_scale=1 + REL, t_shift=shift)        # pessimistic
-        s_lo = o.decode_score(model, L[alive], O[alive], lk, dec, cur, t_scale=1 - REL, t_shift=-shift)   # optimistic
+        s = o.decode_score_bracket(model, L[alive], O[alive], lk, dec, cur, t_scale=1 + REL, t_shift=shift)        # pessimistic
+        s_lo = o.decode_score_bracket(model, L[alive], O[alive], lk, dec, cur, t_scale=1 - REL, t_shift=-shift)   # optimistic
         with np.errstate(all="ignore"):
             R = (el[alive] + s_lo.best_cost + tl[np.asarray(node)[alive]]) / hz[np.asarray(wf)[alive]]
         i = alive.index(c)

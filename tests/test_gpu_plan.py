@@ -195,3 +195,36 @@ def test_planner_limits_and_empty_inputs(ctx):
         ctx.hx_plan_greedy(synth.MODEL, big, binding.to_device(pre), binding.to_device(dec), binding.to_device(links),
                            dev(np.zeros(1, np.float32)), dev(np.ones(1, np.float32)), *out)
     assert e.value.code == -2
+
+
+def test_greedy_rescans_everything_when_a_commit_lowers_a_term(ctx):
+    # The snapshot's batch of a decode instance may stand above what the batch rule gives for its occupancy (the
+    # interface only asks for batch >= 0).  The first commit on that instance then lowers its per-token time, pairs
+    # on it get cheaper, and calls whose current pair is elsewhere must move there: the plan is Algorithm 1's full
+    # recomputation only if those calls are scored again.  Compute-bound decode (large FLOP per token) makes the
+    # batch term the one that counts; two decode classes, the fast instance starting with the inflated batch.
+    rng = np.random.default_rng(91)
+    model = dict(synth.MODEL); model["flops_per_token"] = 4e11
+    P, D, C = 6, 2, 24
+    tp = (np.arange(P) % 2).astype(np.int32); td = np.array([1, 0], np.int32)
+    F, B = np.array([4e14, 1e15], np.float32), np.array([2e12, 3.3e12], np.float32)
+    pre = dict(flops=F[tp], hbm_bw=B[tp], backlog_tok=rng.integers(0, 3000, P).astype(np.int32), type=tp)
+    L, O = synth.gen_lengths(rng, C)
+    dec = dict(flops=F[td], hbm_bw=B[td], used_tok=np.array([20000, 20000], np.int32),
+               cap_tok=np.array([10**6, 20000 + int(np.median(L + O)) * 6], np.int32),
+               batch=np.array([150, 12], np.int32), qd_tok=np.array([500, 500], np.int32), type=td)
+    links = dict(n_types=2, bw=np.array([[5e10, 2.5e10], [2.5e10, 1e11]], np.float32), latency=np.zeros((2, 2), np.float32))
+    elapsed = rng.uniform(0, 20, C).astype(np.float32)
+    node = np.arange(C, dtype=np.int32); wf = (np.arange(C) % 4).astype(np.int32)
+    tail = rng.uniform(0, 5, C).astype(np.float32); hor = rng.uniform(5, 50, 4).astype(np.float32)
+    want = o.plan_greedy(model, L, O, elapsed, node, wf, tail, hor, pre, dec, links)
+    # the case is what it is meant to be: on the snapshot every call prefers instance 1; once a call has gone to
+    # instance 0 its batch falls from 150 and most of the remaining calls follow
+    snap = o.score(model, L, O, pre, dec, links)
+    assert (snap.best_d == 1).all() and want.batch[0] < 150 and (want.best_d == 0).sum() > C // 2
+    got = run_greedy(ctx, model, L, O, elapsed, node, wf, tail, hor, pre, dec, links)
+    check_plan_stepwise(model, L, O, elapsed, node, wf, tail, hor, pre, dec, links, got)
+    assert np.array_equal(got[4], want.rank)
+    assert np.array_equal(got[0], want.best_p) and np.array_equal(got[1], want.best_d)
+    assert_costs_close(got[2], want.best_cost, "plan cost")
+    assert np.array_equal(got[7], want.batch) and np.array_equal(got[6], want.used_tok)

@@ -134,22 +134,53 @@ def test_projected_ratio(ctx):
     assert np.allclose(gr, eq2, rtol=1e-6)
 
 
-def test_large_sweep_sampled(ctx):
+def test_ratio_of_a_workflow_without_horizon_and_of_a_bad_index(ctx):
+    # Eq. (2) divides by the horizon: a horizon of 0 gives +inf whatever the numerator (the oracle's reading), an
+    # index outside the arrays gives NaN and is reported -- through hx_score_placements and through hx_urgency
+    import torch
+    from paper_2605_16637_amd import binding
+    rnd = synth.make_round("tiny", 2)
+    n = rnd.calls["n"]
+    c = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in rnd.calls.items()}
+    c["node"][:] = np.arange(n) % 5; c["wf"][:] = np.arange(n) % 3
+    c["elapsed"][1] = 0.0
+    tail = np.array([0.0, 1.0, 2.0, 0.5, 0.0], np.float32); hor = np.array([8.0, 0.0, 3.0], np.float32)
+    ores = oracle_round(rnd)
+    want = o.urgency(c["elapsed"], ores.best_cost, c["node"], c["wf"], tail, hor)
+    assert np.isposinf(want[1::3]).all() and np.isfinite(want[0::3]).all()
+    calls = binding.to_device(c)
+    _, pre, dec, links = dev_tables(rnd)
+    gp, gd, gc, gr = fused(ctx, rnd.model, calls, pre, dec, links, tail=dev(tail), horizon=dev(hor), want_ratio=True)
+    assert_costs_close(gr, want, "ratio")
+    r2 = torch.empty(n, device="cuda:0")
+    ctx.hx_urgency(calls, dev(gc), dev(tail), dev(hor), r2)
+    ctx.hx_stream_status()
+    assert np.array_equal(r2.cpu().numpy(), gr)
+    c["wf"][4] = 3; c["node"][7] = -1
+    calls = binding.to_device(c)
+    ctx.hx_urgency(calls, dev(gc), dev(tail), dev(hor), r2)
+    with pytest.raises(binding.HxError) as e:
+        ctx.hx_stream_status()
+    assert e.value.code == -6
+    got = r2.cpu().numpy()
+    bad = np.zeros(n, bool); bad[[4, 7]] = True
+    assert np.isnan(got[bad]).all() and np.array_equal(got[~bad], gr[~bad])
+
+
+def test_large_sweep_every_call_by_enumeration(ctx):
     # the full 16384 x 256 x 256 round in the launch configuration the benchmark
-    # times; the oracle checks a sample of calls one by one, properties hold for all
+    # times: the oracle enumerates all 256 x 256 pairs of every one of the 16384 calls
     rnd = synth.make_round("large", 1)
     calls, pre, dec, links = dev_tables(rnd)
     gp, gd, gc = fused(ctx, rnd.model, calls, pre, dec, links)
-    C = rnd.calls["n"]
-    rng = np.random.default_rng(7)
-    rows = np.sort(rng.choice(C, 384, replace=False))
     L, O = rnd.calls["L_in"], rnd.calls["L_out"]
-    ores = o.score(rnd.model, L[rows], O[rows], rnd.pre, rnd.dec, rnd.links)
-    assert_search_matches(rnd.model, L, O, rnd.pre, rnd.dec, rnd.links, ores, gp[rows], gd[rows], gc[rows], rows=rows)
+    ores = o.score(rnd.model, L, O, rnd.pre, rnd.dec, rnd.links)
+    n_diff = assert_search_matches(rnd.model, L, O, rnd.pre, rnd.dec, rnd.links, ores, gp, gd, gc)
+    assert n_diff <= rnd.calls["n"] // 200                      # fp32 near-ties are rare
     need = L.astype(np.int64) + O
     free = rnd.dec["cap_tok"].astype(np.int64) - rnd.dec["used_tok"]
     infeasible = (need[:, None] > free[None, :]).mean()
-    assert 0.05 < infeasible < 0.15
+    assert 0.09 < infeasible < 0.11                              # one (call, decode) pair in ten does not fit
     ok = gd >= 0
     assert (need[ok] <= free[gd[ok]]).all()                     # infeasible never chosen
     assert np.array_equal(~ok, need > free.max())               # "none" exactly when nothing fits

@@ -94,70 +94,6 @@ def test_streaming_rounds(ctx, seed, n_live, rounds, P, D):
     assert (ores.best_p < 0).mean() < 0.9       # the pool did not drift into "nothing fits"
 
 
-def test_streaming_rounds_full_scale(ctx):
-    """The benchmark's streaming configuration (20000 live workflows, 32768 ready calls x 512 x 512) for a few
-    rounds.  The graph (incremental append against a full recomputation) and the committed integer state are
-    checked in full every round; the search is checked on a sample of calls, priced by the oracle on the state
-    the round started from."""
-    import torch
-    from paper_2605_16637_amd import binding
-    model = synth.MODEL
-    n_live, C, P, D, rounds = 20000, 32768, 512, 512, 3
-    gen = synth.StreamGen(1, n_live)
-    rng = np.random.default_rng(1)
-    L0, O0 = synth.gen_lengths(rng, 50000)
-    types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
-    d_links, d_pre, d_dec = binding.to_device(links), binding.to_device(pre), binding.to_device(dec)
-    tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
-    ctx.hx_dag_reserve(400000, 700000, 100000, 32)
-    o_pre = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in pre.items()}
-    o_dec = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in dec.items()}
-    prow = np.zeros(1, np.int32); pcol = np.zeros(0, np.int32)
-    cost_all = np.zeros(0, np.float32); wf_all = np.zeros(0, np.int32)
-    for r in range(rounds):
-        b = gen.next_batch()
-        n_new, n_wf = b["n_new"], b["n_wf_total"]
-        g_cost = torch.empty(n_new, device="cuda:0")
-        ctx.hx_node_cost(model, dev(b["L_in"]), dev(b["L_out"]), tF, tB, d_links, g_cost)
-        ctx.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), g_cost, dev(b["wf"]))
-        g_rem, g_tail, g_level, g_hor, n_nodes = ctx.hx_dag_view(n_wf)
-        pick = np.sort(rng.choice(n_new, min(C, n_new), replace=False)).astype(np.int32)
-        Lc, Oc = b["L_in"][pick], b["L_out"][pick]
-        elapsed = rng.uniform(0, 30, pick.size).astype(np.float32)
-        calls = dict(n=int(pick.size), L_in=dev(Lc), L_out=dev(Oc), node=dev(b["ids"][pick]), wf=dev(b["wf"][pick]), elapsed=dev(elapsed))
-        i32 = dict(dtype=torch.int32, device="cuda:0")
-        bp, bd = torch.empty(pick.size, **i32), torch.empty(pick.size, **i32)
-        bc, ratio = torch.empty(pick.size, device="cuda:0"), torch.empty(pick.size, device="cuda:0")
-        ctx.hx_score_placements(model, calls, d_pre, d_dec, d_links, tail=g_tail, horizon=g_hor, best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
-        Ls, Os = int(Lc.sum()), int(Oc.sum())
-        dp = np.full(P, Ls // P, np.int32); dq = np.full(D, Os // D, np.int32); rl = np.full(D, (Ls + Os) // D, np.int32)
-        ctx.hx_commit(calls, bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"], dev(dp), dev(dq), dev(rl))
-        ctx.hx_stream_status()
-        # graph: the GPU's own fp32 node costs, full recomputation with one rounding per node -> bit for bit
-        prow = np.concatenate([prow, prow[-1] + b["parent_row_ptr"][1:]]).astype(np.int32)
-        pcol = np.concatenate([pcol, b["parent_col"]]); cost_all = np.concatenate([cost_all, g_cost.cpu().numpy()])
-        wf_all = np.concatenate([wf_all, b["wf"]])
-        rem, tail, level, hor = o.critical_path_by_parents(prow, pcol, cost_all.astype(np.float64), wf_all, n_wf, round_f32=True)
-        assert n_nodes == cost_all.size
-        assert np.array_equal(fetch(g_level), level)
-        assert np.array_equal(fetch(g_rem).astype(np.float64), rem) and np.array_equal(fetch(g_hor).astype(np.float64), hor)
-        assert_costs_close(cost_all[-n_new:], o.node_cost(model, b["L_in"], b["L_out"], types, links), "node cost")
-        # search: a sample of the round's calls on the state the round started from
-        gp, gd, gc, gr = bp.cpu().numpy(), bd.cpu().numpy(), bc.cpu().numpy(), ratio.cpu().numpy()
-        rows = np.sort(rng.choice(pick.size, 256, replace=False))
-        ores = o.score(model, Lc[rows], Oc[rows], o_pre, o_dec, links)
-        assert_search_matches(model, Lc, Oc, o_pre, o_dec, links, ores, gp[rows], gd[rows], gc[rows], rows=rows)
-        want_ratio = (elapsed.astype(np.float64) + gc + tail[b["ids"][pick]]) / hor[b["wf"][pick]]
-        assert_costs_close(gr, want_ratio, "ratio")
-        # commit: all calls, the GPU's pairs, integer state exact
-        bl, us, ba, qd, rc = o.commit(Lc, Oc, gp, gd, o_pre["backlog_tok"], o_dec["used_tok"], o_dec["batch"], o_dec["qd_tok"], dp, dq, rl)
-        assert rc == 0
-        o_pre["backlog_tok"], o_dec["used_tok"], o_dec["batch"], o_dec["qd_tok"] = bl, us, ba, qd
-        assert np.array_equal(d_pre["backlog_tok"].cpu().numpy(), bl) and np.array_equal(d_dec["used_tok"].cpu().numpy(), us)
-        assert np.array_equal(d_dec["batch"].cpu().numpy(), ba) and np.array_equal(d_dec["qd_tok"].cpu().numpy(), qd)
-        assert (gp >= 0).mean() > 0.5
-
-
 def test_round_replayed_from_a_hip_graph(ctx):
     # the benchmark replays a captured round; every replay must equal the eager
     # result, with eager work and synchronisation between replays

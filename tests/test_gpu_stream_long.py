@@ -1,0 +1,204 @@
+"""The streaming configuration at its stated length: 1000 consecutive scheduling
+rounds with carried pool and graph state (Sec. 4.1 online reveal; Sec. 5.1 the
+horizon is refreshed at every reveal; Algorithm 1, simulated-state update).
+
+Every round reveals new calls (hx_node_cost -> hx_dag_append into the graph the
+context keeps), scores the ready calls with their projected ratio
+(hx_score_placements) and commits the chosen pairs (hx_commit).
+
+  reduced scale (2048 calls x 64 x 64): the oracle replays every round in full on
+    its own state -- its own fp64 node costs and horizon pass over the whole graph,
+    every call scored by enumeration, its own commit;
+  full scale (20000 live workflows, 32768 calls x 512 x 512): every round the
+    oracle commits the GPU's pairs on its own integer tables (tables compared
+    exactly, and through a running 64-bit checksum); at rounds 0-9 and every 50th
+    the oracle is handed the device's state of that moment: the pool tables the
+    round started from (read back from the device) and the GPU's fp32 node costs,
+    from which it recomputes the whole graph bit for bit, scores all 32768 calls by
+    enumeration and recomputes every ratio.
+
+The 1000 rounds are cut into consecutive tests so that each reports within a
+minute; a test run on its own first runs (and checks) the rounds before it."""
+import hashlib
+
+import numpy as np
+import pytest
+
+from oracle import hx_oracle as o
+from paper_2605_16637_amd import synth
+from gpu_helpers import assert_costs_close, assert_search_matches, dev
+from test_gpu_dag import fetch
+
+pytestmark = pytest.mark.gpu
+
+ROUNDS = 1000
+
+
+def checksum(h, tables):
+    m = hashlib.blake2b(digest_size=8)
+    m.update(h)
+    for t in tables:
+        m.update(np.ascontiguousarray(t, np.int32).tobytes())
+    return m.digest()
+
+
+class Stream:
+    def __init__(self, seed, n_live, C, P, D, own_costs, check_rounds):
+        import torch
+        from paper_2605_16637_amd import binding
+        self.torch, self.binding = torch, binding
+        self.ctx = binding.Context(0)
+        self.C, self.P, self.D, self.own_costs, self.check_rounds = C, P, D, own_costs, check_rounds
+        self.gen = synth.StreamGen(seed, n_live)
+        self.rng = np.random.default_rng(1000 + seed)
+        L0, O0 = synth.gen_lengths(self.rng, 50000)
+        self.types, self.links, pre, dec = synth.gen_pool(self.rng, P, D, 8, L0, O0, near_capacity=True)
+        self.d_links, self.d_pre, self.d_dec = binding.to_device(self.links), binding.to_device(pre), binding.to_device(dec)
+        self.tF, self.tB = dev(self.types["flops"]), dev(self.types["hbm_bw"])
+        self.o_pre = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in pre.items()}
+        self.o_dec = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in dec.items()}
+        # the whole run's graph: at most 4 new calls per live workflow and round on average
+        cap_n = int(ROUNDS * n_live * 4.1) + 64 * n_live
+        cap_e, cap_w = int(cap_n * 1.35), n_live + cap_n // 10 + 1024
+        self.ctx.hx_dag_reserve(cap_n, cap_e, cap_w, 32)
+        self.prow = np.zeros(cap_n + 1, np.int32); self.pcol = np.zeros(cap_e, np.int32)
+        self.cost = np.zeros(cap_n, np.float64); self.wf = np.zeros(cap_n, np.int32)
+        self.buf = (np.empty(cap_n, np.float64), np.empty(cap_n, np.float64), np.empty(cap_n, np.int32), np.empty(cap_w, np.float64))
+        self.n = self.e = 0
+        self.round = 0
+        self.h_gpu = self.h_ora = b""
+        self.n_diff = self.n_scored = self.n_placed = self.n_calls = 0
+        self.max_level = 0
+
+    def close(self):
+        self.ctx.close()
+
+    def advance_to(self, end):
+        while self.round < end:
+            self.one_round()
+
+    def one_round(self):
+        torch, ctx, model = self.torch, self.ctx, synth.MODEL
+        r, P, D = self.round, self.P, self.D
+        check = r in self.check_rounds
+        b = self.gen.next_batch()
+        n_new, n_wf, m = b["n_new"], b["n_wf_total"], int(b["parent_col"].size)
+        before = [self.d_pre["backlog_tok"].clone(), self.d_dec["used_tok"].clone(), self.d_dec["batch"].clone(),
+                  self.d_dec["qd_tok"].clone()] if check else None
+        # reveal
+        d_L, d_O = dev(b["L_in"]), dev(b["L_out"])
+        g_cost = torch.empty(n_new, device="cuda:0")
+        ctx.hx_node_cost(model, d_L, d_O, self.tF, self.tB, self.d_links, g_cost)
+        ctx.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), g_cost, dev(b["wf"]))
+        g_rem, g_tail, g_level, g_hor, n_nodes = ctx.hx_dag_view(n_wf)
+        # the ready calls of the round: up to C of the calls just revealed
+        pick = np.sort(self.rng.choice(n_new, min(self.C, n_new), replace=False)).astype(np.int32)
+        Lc, Oc = b["L_in"][pick], b["L_out"][pick]
+        elapsed = self.rng.uniform(0, 30, pick.size).astype(np.float32)
+        calls = dict(n=int(pick.size), L_in=dev(Lc), L_out=dev(Oc), node=dev(b["ids"][pick]), wf=dev(b["wf"][pick]), elapsed=dev(elapsed))
+        i32 = dict(dtype=torch.int32, device="cuda:0")
+        bp, bd = torch.empty(pick.size, **i32), torch.empty(pick.size, **i32)
+        bc, ratio = torch.empty(pick.size, device="cuda:0"), torch.empty(pick.size, device="cuda:0")
+        ctx.hx_score_placements(model, calls, self.d_pre, self.d_dec, self.d_links, tail=g_tail, horizon=g_hor,
+                                best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+        # drains sized to what the round adds, so the pool stays in its regime
+        Ls, Os = int(Lc.sum()), int(Oc.sum())
+        dp = np.full(P, Ls // P, np.int32); dq = np.full(D, Os // D, np.int32); rl = np.full(D, (Ls + Os) // D, np.int32)
+        ctx.hx_commit(calls, bp, bd, self.d_pre["backlog_tok"], self.d_dec["used_tok"], self.d_dec["batch"], self.d_dec["qd_tok"],
+                      dev(dp), dev(dq), dev(rl))
+        ctx.hx_stream_status()
+        assert n_nodes == self.n + n_new
+
+        # ---- the oracle's side of the round ----
+        o_cost = o.node_cost(model, b["L_in"], b["L_out"], self.types, self.links)
+        cost32 = g_cost.cpu().numpy()
+        assert_costs_close(cost32, o_cost, "node cost")
+        n0, e0 = self.n, self.e
+        self.prow[n0 + 1:n0 + n_new + 1] = e0 + b["parent_row_ptr"][1:]
+        self.pcol[e0:e0 + m] = b["parent_col"]
+        self.wf[n0:n0 + n_new] = b["wf"]
+        self.cost[n0:n0 + n_new] = o_cost if self.own_costs else cost32
+        self.n, self.e = n0 + n_new, e0 + m
+        gp, gd = bp.cpu().numpy(), bd.cpu().numpy()
+        if check:
+            # the state the round started from, as the device held it
+            start = [t.cpu().numpy() for t in before]
+            for got, want in zip(start, (self.o_pre["backlog_tok"], self.o_dec["used_tok"], self.o_dec["batch"], self.o_dec["qd_tok"])):
+                assert np.array_equal(got, want)
+            t_pre = dict(self.o_pre, backlog_tok=start[0])
+            t_dec = dict(self.o_dec, used_tok=start[1], batch=start[2], qd_tok=start[3])
+            # graph: the whole of it, recomputed from scratch
+            rem, tail, level, hor = o.critical_path_revealed(self.prow[:self.n + 1], self.pcol[:self.e], self.cost[:self.n],
+                                                             self.wf[:self.n], n_wf, round_f32=not self.own_costs, out=self.buf)
+            assert np.array_equal(fetch(g_level), level), f"round {r}: levels"
+            if self.own_costs:
+                assert_costs_close(fetch(g_rem), rem, "rem"); assert_costs_close(fetch(g_tail), tail, "tail")
+                assert_costs_close(fetch(g_hor), hor, "horizon")
+            else:
+                assert np.array_equal(fetch(g_rem).astype(np.float64), rem), f"round {r}: rem"
+                assert np.array_equal(fetch(g_tail).astype(np.float64), tail), f"round {r}: tail"
+                assert np.array_equal(fetch(g_hor).astype(np.float64), hor), f"round {r}: horizon"
+            self.max_level = max(self.max_level, int(level.max()))
+            # search: every call of the round, by enumeration
+            ores = o.score(model, Lc, Oc, t_pre, t_dec, self.links)
+            gc = bc.cpu().numpy()
+            self.n_diff += assert_search_matches(model, Lc, Oc, t_pre, t_dec, self.links, ores, gp, gd, gc)
+            self.n_scored += pick.size
+            want_ratio = o.urgency(elapsed, ores.best_cost, b["ids"][pick], b["wf"][pick], tail, hor)
+            assert_costs_close(ratio.cpu().numpy(), want_ratio, "ratio")
+        # commit of the GPU's pairs on the oracle's tables: integer state exact, every round
+        bl, us, ba, qd, rc = o.commit(Lc, Oc, gp, gd, self.o_pre["backlog_tok"], self.o_dec["used_tok"], self.o_dec["batch"],
+                                      self.o_dec["qd_tok"], dp, dq, rl)
+        assert rc == 0
+        self.o_pre["backlog_tok"], self.o_dec["used_tok"], self.o_dec["batch"], self.o_dec["qd_tok"] = bl, us, ba, qd
+        got = [self.d_pre["backlog_tok"].cpu().numpy(), self.d_dec["used_tok"].cpu().numpy(), self.d_dec["batch"].cpu().numpy(),
+               self.d_dec["qd_tok"].cpu().numpy()]
+        self.h_gpu, self.h_ora = checksum(self.h_gpu, got), checksum(self.h_ora, (bl, us, ba, qd))
+        assert self.h_gpu == self.h_ora, f"round {r}: state checksum"
+        for a, w in zip(got, (bl, us, ba, qd)):
+            assert np.array_equal(a, w), f"round {r}: committed state"
+        self.n_placed += int((gp >= 0).sum()); self.n_calls += int(pick.size)
+        self.last_placed = float((gp >= 0).mean())
+        self.round += 1
+
+
+_runs = {}
+
+
+def _get(name):
+    if name not in _runs:
+        for other in list(_runs):           # one long run holds the graph store at a time
+            _runs.pop(other).close()
+        if name == "reduced":
+            _runs[name] = Stream(seed=3, n_live=640, C=2048, P=64, D=64, own_costs=True, check_rounds=range(ROUNDS))
+        else:
+            _runs[name] = Stream(seed=1, n_live=20000, C=32768, P=512, D=512, own_costs=False,
+                                 check_rounds=set(range(10)) | set(range(50, ROUNDS, 50)) | {ROUNDS - 1})
+    return _runs[name]
+
+
+def _finish(s):
+    assert s.n_diff <= max(3, s.n_scored // 200)            # near-ties in fp32 are rare
+    assert s.n_placed / s.n_calls > 0.5 and s.last_placed > 0.5   # the pool did not drift into "nothing fits"
+    assert s.max_level >= 6
+    print("rounds %d nodes %d edges %d workflows %d calls scored by the oracle %d (near-ties %d) placed %.3f checksum %s"
+          % (s.round, s.n, s.e, s.gen.n_wf, s.n_scored, s.n_diff, s.n_placed / s.n_calls, s.h_gpu.hex()))
+
+
+@pytest.mark.parametrize("end", [250, 500, 750, 1000])
+def test_1000_rounds_reduced_scale_replayed_in_full(end):
+    s = _get("reduced")
+    s.advance_to(end)
+    if end == ROUNDS:
+        _finish(s)
+        _runs.pop("reduced").close()
+
+
+@pytest.mark.parametrize("end", [5, 10] + list(range(100, ROUNDS + 1, 100)))
+def test_1000_rounds_full_scale_teacher_forced(end):
+    s = _get("full")
+    s.advance_to(end)
+    if end == ROUNDS:
+        assert s.n > 60_000_000
+        _finish(s)
+        _runs.pop("full").close()

@@ -155,3 +155,40 @@ def test_cycle_is_reported():
         o.critical_path([0, 1, 2, 3], [1, 2, 0], [1.0, 1.0, 1.0], [0, 3])
     with pytest.raises(ValueError, match="not a DAG"):
         o.critical_path([0, 1], [0], [1.0], [0, 1])
+
+
+def test_reveal_order_pass_against_path_enumeration_and_the_depth_first_form():
+    # the one-pass form used on long-lived graphs: same values as enumerating every path (<= 12 nodes),
+    # same bits as the depth-first form on streamed graphs, fp64 and fp32-rounding modes
+    rng = np.random.default_rng(35)
+    for trial in range(40):
+        n = int(rng.integers(1, 13))
+        row_ptr, col = small_dag(rng, n, rng.uniform(0.1, 0.5))          # edges i -> j with i < j: reveal order
+        cost = rng.uniform(0.1, 5.0, n)
+        src = np.repeat(np.arange(n), np.diff(row_ptr))
+        order = np.lexsort((src, col))
+        prow = np.zeros(n + 1, np.int32); prow[1:] = np.cumsum(np.bincount(col, minlength=n)) if col.size else 0
+        pcol = src[order].astype(np.int32)
+        wf = rng.integers(0, 3, n).astype(np.int32)
+        rem, tail, level, hor = o.critical_path_revealed(prow, pcol, cost, wf, 3, round_f32=False)
+        brem, blevel = brute_force(n, row_ptr, col, cost)
+        assert np.allclose(rem, brem, rtol=1e-13) and np.array_equal(level, blevel)
+        assert np.allclose(tail, brem - cost, rtol=1e-12, atol=1e-12)
+        for w in range(3):
+            assert hor[w] == pytest.approx(brem[wf == w].max() if (wf == w).any() else 0.0, rel=1e-13)
+    gen = synth.StreamGen(3, 200, final_lo=6, final_hi=20)
+    prow = np.zeros(1, np.int32); pcol = np.zeros(0, np.int32); wf = np.zeros(0, np.int32)
+    for r in range(12):
+        b = gen.next_batch()
+        prow = np.concatenate([prow, prow[-1] + b["parent_row_ptr"][1:]]).astype(np.int32)
+        pcol = np.concatenate([pcol, b["parent_col"]]); wf = np.concatenate([wf, b["wf"]])
+    cost = rng.uniform(0.05, 9.0, wf.size).astype(np.float32).astype(np.float64)
+    for mode in (True, False):
+        a = o.critical_path_by_parents(prow, pcol, cost, wf, gen.n_wf, round_f32=mode)
+        b = o.critical_path_revealed(prow, pcol, cost, wf, gen.n_wf, round_f32=mode)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    assert a[2].max() >= 5                                  # deep enough to mean something
+    # a parent that is not older than its child is refused
+    with pytest.raises(ValueError):
+        o.critical_path_revealed([0, 1, 1], [1], [1.0, 1.0], [0, 0], 1)

@@ -212,3 +212,16 @@ def test_greedy_infeasible_and_full_list():
     iv1 = dict(stride=1, count=[0], start=np.zeros(1), end=np.zeros(1), tok=np.zeros(1, np.int32))
     with pytest.raises(ValueError):
         o.decode_plan_greedy(ROUND_MODEL, [100, 100], [10, 10], None, [1.0, 1.0], [0, 1], [0, 0], [0.0, 0.0], [10.0], dec, iv1)
+
+
+def test_bracketing_variant_is_the_method_at_scale_one_shift_zero():
+    # the parity test of a finished plan calls a variant that scales and shifts decode times; it is kept apart from
+    # the method's own function and must be that function at (1, 0); away from it, starts can only move later/earlier
+    r, lock, iv = synth.make_decode_round("decode_tiny", seed=3)
+    a = o.decode_score(r.model, r.calls["L_in"], r.calls["L_out"], lock, r.dec, iv, want_all=True)
+    b = o.decode_score_bracket(r.model, r.calls["L_in"], r.calls["L_out"], lock, r.dec, iv, 1.0, 0.0, want_all=True)
+    for x, y in ((a.best_d, b.best_d), (a.best_start, b.best_start), (a.best_cost, b.best_cost), (a.start, b.start), (a.cost, b.cost)):
+        assert np.array_equal(x, y)
+    hi = o.decode_score_bracket(r.model, r.calls["L_in"], r.calls["L_out"], lock, r.dec, iv, 1.01, 0.001, want_all=True)
+    lo = o.decode_score_bracket(r.model, r.calls["L_in"], r.calls["L_out"], lock, r.dec, iv, 0.99, -0.001, want_all=True)
+    assert (hi.start >= a.start).all() and (lo.start <= a.start).all()

@@ -148,6 +148,11 @@ def test_urgency_round():
     # node and workflow indices are not swapped
     r = o.urgency([0.0], [1.0], [1], [0], [10.0, 20.0], [7.0, 1e9])
     assert r[0] == pytest.approx(21.0 / 7.0, rel=TOL)
+    # a workflow without a horizon (Eq. (2) is undefined there): as urgent as can be, also for a zero numerator
+    r = o.urgency([2.0, 0.0], [3.0, 0.0], [0, 0], [0, 0], [0.0], [0.0])
+    assert np.isposinf(r).all()
+    # nothing feasible: +inf over any horizon
+    assert np.isposinf(o.urgency([2.0], [np.inf], [0], [0], [0.0], [4.0])[0])
 
 
 @pytest.mark.parametrize("field,side", [("backlog_tok", "pre"), ("qd_tok", "dec"), ("used_tok", "dec"), ("batch", "dec")])

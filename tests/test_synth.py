@@ -49,7 +49,7 @@ def test_near_capacity_pool_and_calls():
     r = synth.make_round("large", 1)
     need = r.calls["L_in"].astype(np.int64) + r.calls["L_out"]
     free = r.dec["cap_tok"].astype(np.int64) - r.dec["used_tok"]
-    assert 0.05 < (need[:, None] > free[None, :]).mean() < 0.15
+    assert 0.09 < (need[:, None] > free[None, :]).mean() < 0.11     # free = a U(0.8, 1) quantile of demand: 0.10 expected
     assert (r.dec["used_tok"] >= 0).all() and (r.dec["used_tok"] <= r.dec["cap_tok"]).all()
     assert np.array_equal(r.pre["type"], np.arange(r.pre["n"]) % 8)
     for t in range(8):
