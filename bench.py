@@ -19,21 +19,52 @@ if ROOT not in sys.path:
 
 import numpy as np
 
-# non-packed, non-FMA fp32 VALU issue peak: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
+# The roofline of the search.  A SIMD of a compute unit issues one wave-wide fp32 vector instruction per 4 cycles
+# on its main pipe (16 lanes per clock): 256 CU x 4 SIMD x 16 lanes x 2.4 GHz = 39.32 T lane-ops/s.  Additions,
+# multiplications and fused multiply-adds can issue on a second fp32 pipe at the same time as an instruction of
+# another wavefront on the main one (measured in calibration_leg: a stream of v_add_f32, or of v_add_f32
+# alternating with v_max_f32, runs at twice the rate of a stream of v_max_f32 or v_min3_f32); the advertised
+# 157.3 TFLOP/s is both pipes busy with fused multiply-adds.  Comparisons, maxima and minima have the main pipe
+# only.  Per candidate the search needs one maximum, one addition and half a three-input minimum: 2.5 instructions,
+# of which 1.5 are bound to the main pipe -- the resource that limits it.  achieved = candidates/s x 1.5 against
+# 39.32 T main-pipe lane-ops/s; the same loop on registers alone is measured beside it.
 ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
-# VALU issue slots the search needs per candidate: max, add, half a 3-input min
-OPS_PER_CANDIDATE = 2.5
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+MAIN_PIPE_OPS_PER_CANDIDATE = 1.5      # v_max_f32 + half a v_min3_f32
+OPS_PER_CANDIDATE = 2.5                # with the v_add_f32
 # Vector ops of the decode-stage search for one (call, instance) pair.  A free call goes through the instance's
 # first-room table: 6 per step of the bisection for its threshold's rank, 8 per stretch of the timeline, 24 for
 # the call's decode time, threshold and the comparison with its best so far.  A locked call scans its one
 # instance's timeline entry by entry, 7 per entry.
 DECODE_OPS_BISECT_STEP, DECODE_OPS_STRETCH, DECODE_OPS_PAIR, DECODE_OPS_ENTRY = 6.0, 8.0, 24.0, 7.0
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/
-# (counter x calibration factor of a plain copy); valid for the default workloads only, and to be
-# reset to None whenever the kernel changes until the counters are taken again
-FUSED_TRAFFIC_BYTES = {"large": 4.55e6 + 0.52e6}
-CP_TRAFFIC_BYTES = 31.51e6 + 24.59e6
+
+
+def source_sha():
+    """sha256 over the library's kernel sources: a counter summary under profiles/ names the sources it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2605_16637_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".hpp")) and f != "hx_calib.hip":
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()
+
+
+def profiled_traffic(summary, key="traffic_bytes_per_launch"):
+    """HBM bytes per launch as the rocprofv3 counter runs summarised in profiles/<summary> found them, or None when
+    there is no such line or the kernel sources have changed since (the summary records their sha256)."""
+    path = os.path.join(ROOT, "profiles", summary)
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if ":" in line:
+            k, v = line.split(":", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("source_sha256") != source_sha() or key not in vals:
+        return None
+    return float(vals[key].split()[0])
 
 
 def dev(x):
@@ -151,35 +182,41 @@ def time_launches(torch, fn, reps, warmup=5):
 
 
 def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=32768, P=512, D=512):
-    """Rounds of a live system: reveal (node cost + append), score the ready calls
-    with their projected ratio, commit.  Every batch is resident before the clock starts."""
+    """Rounds of a live system, the streaming configuration at its stated length: reveal (node cost + append to the
+    graph the context keeps), score the ready calls with their projected ratio, commit; pool and graph state carried
+    from round to round.  Every batch is resident in HBM before its clock starts.  Two ways of enqueueing a round are
+    timed on alternating rounds of the same run (they give the same results, so the state evolves as one sequence):
+    everything on one stream, and the reveal on a second stream beside the search (which needs no horizon), the
+    urgency fold joining the two before the commit."""
     rng = np.random.default_rng(seed)
     gen = synth.StreamGen(seed, n_live)
     L0, O0 = synth.gen_lengths(rng, 50000)
     types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
     d_links, d_pre, d_dec = binding.to_device(links), binding.to_device(pre), binding.to_device(dec)
     tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
-    warm = 3
-    batches, n_nodes, n_edges = [], 0, 0
-    for _ in range(rounds + warm):
+    warm = 4
+    # the run's whole graph stays in the context's store: at most 4 new calls per live workflow and round on average
+    cap_n = int((rounds + warm) * n_live * 4.1) + 64 * n_live
+    ctx.hx_dag_reserve(cap_n, int(cap_n * 1.35), n_live + cap_n // 10 + 1024, 32)
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    bp, bd = torch.empty(C, **i32), torch.empty(C, **i32)
+    bc, ratio = torch.empty(C, device="cuda:0"), torch.empty(C, device="cuda:0")
+    side = torch.cuda.Stream()            # default priority
+
+    def next_batch():
         b = gen.next_batch()
         n = b["n_new"]
         pick = np.sort(rng.choice(n, min(C, n), replace=False)).astype(np.int32)
         Ls, Os = int(b["L_in"][pick].sum()), int(b["L_out"][pick].sum())
-        batches.append(dict(
+        return dict(
             n_new=n, n_wf=b["n_wf_total"], prow=dev(b["parent_row_ptr"]), pcol=dev(b["parent_col"]), wf=dev(b["wf"]),
             L_in=dev(b["L_in"]), L_out=dev(b["L_out"]), cost=torch.empty(n, device="cuda:0"),
             calls=dict(n=int(pick.size), L_in=dev(b["L_in"][pick]), L_out=dev(b["L_out"][pick]), node=dev(b["ids"][pick]),
                        wf=dev(b["wf"][pick]), elapsed=dev(rng.uniform(0, 30, pick.size).astype(np.float32))),
             drain_p=dev(np.full(P, Ls // P, np.int32)), drain_q=dev(np.full(D, Os // D, np.int32)),
-            release=dev(np.full(D, (Ls + Os) // D, np.int32))))
-        n_nodes += n; n_edges += int(b["parent_col"].size)
-    ctx.hx_dag_reserve(n_nodes + 16, n_edges + 16, gen.n_wf + 16, 32)
-    i32 = dict(dtype=torch.int32, device="cuda:0")
-    bp, bd = torch.empty(C, **i32), torch.empty(C, **i32)
-    bc, ratio = torch.empty(C, device="cuda:0"), torch.empty(C, device="cuda:0")
+            release=dev(np.full(D, (Ls + Os) // D, np.int32)))
 
-    def one(b):
+    def one_stream(b):
         ctx.hx_node_cost(synth.MODEL, b["L_in"], b["L_out"], tF, tB, d_links, b["cost"])
         ctx.hx_dag_append(b["prow"], b["pcol"], b["cost"], b["wf"])
         _, tail, _, hor, _ = ctx.hx_dag_view(b["n_wf"])
@@ -188,26 +225,49 @@ def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=3276
         ctx.hx_commit(b["calls"], bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"],
                       b["drain_p"], b["drain_q"], b["release"])
 
-    for b in batches[:warm]:
-        one(b)
-    torch.cuda.synchronize()
-    lat, cand = [], 0
-    t_all = time.perf_counter()
-    for b in batches[warm:]:
-        t0 = time.perf_counter()
-        one(b)
+    def two_streams(b):
+        main = torch.cuda.current_stream()
+        side.wait_stream(main)
+        ctx.hx_node_cost(synth.MODEL, b["L_in"], b["L_out"], tF, tB, d_links, b["cost"], stream=side)
+        ctx.hx_dag_append(b["prow"], b["pcol"], b["cost"], b["wf"], stream=side)
+        ctx.hx_score_placements(synth.MODEL, b["calls"], d_pre, d_dec, d_links, best_p=bp, best_d=bd, best_cost=bc)
+        main.wait_stream(side)
+        _, tail, _, hor, _ = ctx.hx_dag_view(b["n_wf"])
+        ctx.hx_urgency(b["calls"], bc, tail, hor, ratio)
+        ctx.hx_commit(b["calls"], bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"],
+                      b["drain_p"], b["drain_q"], b["release"])
+
+    modes = (("one stream", one_stream), ("reveal beside the search", two_streams))
+    lat = {name: [] for name, _ in modes}
+    cand = {name: 0 for name, _ in modes}
+    n_nodes = placed = 0
+    for r in range(rounds + warm):
+        b = next_batch()
+        name, fn = modes[r % 2]
         torch.cuda.synchronize()
-        lat.append((time.perf_counter() - t0) * 1e6)
-        cand += b["calls"]["n"] * P * D
-    wall = time.perf_counter() - t_all
+        t0 = time.perf_counter()
+        fn(b)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        n_nodes += b["n_new"]
+        if r >= warm:
+            lat[name].append(dt * 1e6)
+            cand[name] += b["calls"]["n"] * P * D
+            placed += int((bp[:b["calls"]["n"]] >= 0).sum().item())
     ctx.hx_stream_status()
-    placed = float((bp >= 0).float().mean().item())
-    lat = np.array(lat)
+    res = {}
+    for name, _ in modes:
+        x = np.array(lat[name])
+        res[name] = {"rounds": int(x.size), "p50_us": float(np.percentile(x, 50)), "p99_us": float(np.percentile(x, 99)),
+                     "candidates_per_s": cand[name] / (x.sum() * 1e-6)}
+    best = min(res, key=lambda k: res[k]["p50_us"])
     return {"workload": "streaming rounds: %d live workflows, +0..8 calls per workflow per round, %d ready calls x %d x %d, 8 classes"
                         % (n_live, C, P, D),
             "rounds": rounds, "candidates_per_round": C * P * D, "new_nodes_per_round": n_nodes / (rounds + warm),
-            "p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
-            "candidates_per_s": cand / wall, "placed_fraction_last_round": placed, "launch": "eager, synchronised every round"}
+            "graph_nodes_at_the_end": n_nodes,
+            "p50_us": res[best]["p50_us"], "p99_us": res[best]["p99_us"], "candidates_per_s": res[best]["candidates_per_s"],
+            "order": best, "by_order": res, "placed_fraction": placed / max(1, sum(cand.values()) // (P * D)),
+            "launch": "eager, synchronised every round; the two orders on alternating rounds of one run"}
 
 
 def planner_leg(torch, ctx, synth, binding, seed):
@@ -297,9 +357,7 @@ def decode_leg(torch, ctx, synth, binding, seed):
                        "instances_searched_by_table": int(table.sum()),
                        "roofline": {"kernel": "hx_decode_timeline_kernel + hx_decode_score_kernel + hx_decode_finish_kernel", "bound": "alu",
                                     "ops_per_free_pair_mean": float(per_free.mean()), "achieved": ops / score_s / 1e12,
-                                    "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s", "frac": ops / score_s / 1e12 / ALU_PEAK_TOPS,
-                                    "entry_by_entry_equivalent_frac": DECODE_OPS_ENTRY * float(((n_free + locked_on) * n_tl).sum())
-                                                                      / score_s / 1e12 / ALU_PEAK_TOPS},
+                                    "peak": ALU_PEAK_TOPS, "unit": "T lane-ops/s", "frac": ops / score_s / 1e12 / ALU_PEAK_TOPS},
                        "waiting_fraction_of_placed": float(((bs > 0) & (bd >= 0)).float().sum().item() / max(1, int((bd >= 0).sum().item())))}
     rng = np.random.default_rng(seed)
     for name, Qg, Dg, T, res, plan in (("queue 64 x 8 instances, 3 classes", 64, 8, 4, 24, 4), ("queue 256 x 32 instances, 4 classes", 256, 32, 4, 24, 4)):
@@ -368,26 +426,113 @@ def robustness_leg(torch, ctx, synth, binding, seed):
     return out
 
 
-def cpu_baseline(rnd, target_s=12.0):
-    """The oracle, as it stands, on a bounded sample of the same round."""
+def cpu_baseline(rnd, target_s=9.0):
+    """The oracle, as it stands, on bounded samples of the same round: on all the host threads this process may use,
+    and on one."""
     from oracle import hx_oracle as o
-    threads = min(os.cpu_count() or 1, 16)
+    host_cpus = os.cpu_count() or 1
+    try:
+        share = len(os.sched_getaffinity(0))
+    except AttributeError:
+        share = host_cpus
+    threads = int(os.environ.get("OMP_NUM_THREADS") or min(share, 16))
     L, O = rnd.calls["L_in"], rnd.calls["L_out"]
     per = rnd.pre["n"] * rnd.dec["n"]
-    n0 = max(1, min(len(L), 2_000_000 // per * threads))
-    t0 = time.perf_counter()
-    o.score(rnd.model, L[:n0], O[:n0], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
-    dt = time.perf_counter() - t0
-    n1 = int(max(n0, min(len(L), n0 * target_s / max(dt, 1e-6))))
-    # when the whole round takes less than the target, it is scored several times over
-    passes = int(max(1, min(20, round(target_s * n0 / max(dt, 1e-6) / n1)))) if n1 == len(L) else 1
-    t0 = time.perf_counter()
-    for _ in range(passes):
-        o.score(rnd.model, L[:n1], O[:n1], rnd.pre, rnd.dec, rnd.links, nthreads=threads)
-    dt = time.perf_counter() - t0
-    return dict(value=passes * n1 * per / dt, unit="candidates/s", cores=threads, kind="oracle",
-                sample="%d pass(es) over the first %d of %d calls x %d x %d candidates, fp64, %.1f s" %
-                       (passes, n1, len(L), rnd.pre["n"], rnd.dec["n"], dt))
+
+    def timed(nthreads, budget):
+        n0 = max(1, min(len(L), 2_000_000 // per * nthreads))
+        t0 = time.perf_counter()
+        o.score(rnd.model, L[:n0], O[:n0], rnd.pre, rnd.dec, rnd.links, nthreads=nthreads)
+        dt = time.perf_counter() - t0
+        n1 = int(max(n0, min(len(L), n0 * budget / max(dt, 1e-6))))
+        # when the whole round takes less than the budget, it is scored several times over
+        passes = int(max(1, min(20, round(budget * n0 / max(dt, 1e-6) / n1)))) if n1 == len(L) else 1
+        t0 = time.perf_counter()
+        for _ in range(passes):
+            o.score(rnd.model, L[:n1], O[:n1], rnd.pre, rnd.dec, rnd.links, nthreads=nthreads)
+        dt = time.perf_counter() - t0
+        return passes * n1 * per / dt, "%d pass(es) over the first %d of %d calls x %d x %d candidates, fp64, %.1f s" % (
+            passes, n1, len(L), rnd.pre["n"], rnd.dec["n"], dt)
+
+    v_all, s_all = timed(threads, target_s)
+    v_one, s_one = timed(1, target_s * 0.6)
+    return dict(value=v_all, unit="candidates/s", cores=threads, kind="oracle", sample=s_all,
+                single_thread=dict(value=v_one, unit="candidates/s", cores=1, sample=s_one),
+                host_cpus=host_cpus, cpus_this_process_may_use=share)
+
+
+def calibration_leg(torch):
+    """What the chip does on known work, in this run: the rate at which it issues plain fp32 vector instructions of
+    each kind (v_max_f32 alone, v_add_f32 alone, the two alternating; 16 independent registers per lane, eight
+    wavefronts per SIMD, no memory), the arithmetic of the search's inner loop on registers alone, and a plain
+    256 MiB device copy."""
+    import ctypes
+    from paper_2605_16637_amd import build as hx_build
+    if not os.path.exists(hx_build.CALIB_LIB):
+        hx_build.build()
+    lib = ctypes.CDLL(hx_build.CALIB_LIB)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    blocks, iters = cus * 8, 1000
+    sink = torch.empty(blocks * 256, device="cuda:0")
+    ptr = ctypes.c_void_p(sink.data_ptr())
+    stream = lambda: ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    out = {"compute_units": cus}
+    for mix, name in ((0, "v_max_f32"), (1, "v_add_f32"), (2, "v_max_f32 and v_add_f32 alternating")):
+        def fn():
+            assert lib.hx_calib_valu(blocks, iters, mix, ptr, stream()) == 0
+        sec = time_launches(torch, fn, 10, warmup=3)
+        out[name] = {"lane_ops_per_s": blocks * 256 * iters * 32 / sec, "launch_ms": sec * 1e3}
+
+    def search():
+        assert lib.hx_calib_search(blocks, iters, ptr, stream()) == 0
+    sec = time_launches(torch, search, 10, warmup=3)
+    cand = blocks * 256 * iters * 32 / sec
+    out["search loop on registers"] = {"candidates_per_s": cand, "main_pipe_lane_ops_per_s": cand * MAIN_PIPE_OPS_PER_CANDIDATE,
+                                       "all_lane_ops_per_s": cand * OPS_PER_CANDIDATE, "launch_ms": sec * 1e3}
+    n16 = 256 * 1024 * 1024 // 16
+    src = torch.empty(n16 * 4, dtype=torch.float32, device="cuda:0").fill_(1.0)
+    dst = torch.empty_like(src)
+
+    def copy():
+        assert lib.hx_calib_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), ctypes.c_size_t(n16),
+                                 cus * 16, stream()) == 0
+    sec = time_launches(torch, copy, 10, warmup=3)
+    out["plain copy of 256 MiB"] = {"bytes_read": n16 * 16, "bytes_written": n16 * 16, "launch_ms": sec * 1e3,
+                                    "GB_per_s": 2 * n16 * 16 / sec / 1e9, "frac_of_hbm_peak": 2 * n16 * 16 / sec / 1e9 / HBM_PEAK_GBS}
+    out["published"] = {"main_pipe_lane_ops_per_s": ALU_PEAK_TOPS * 1e12, "clock_ghz": 2.4, "fp32_vector_tflops": FP32_VECTOR_PEAK_TFLOPS}
+    return out
+
+
+def round_latency(torch, ctx, synth, name, seed, eager, rounds=500):
+    """p50 / p99 of one scheduling round, host clock from "round handed over" to "indices ready" (stream
+    synchronised), and the share of calls whose projected ratio exceeds 1.5 when elapsed = U(0,1) x horizon (the
+    deadline alpha x H_w of Eq. (1) with alpha = 1.5)."""
+    rnd = synth.make_round(name, seed)
+    rd = RoundOnDevice(ctx, rnd)
+    rd.horizons()
+    u = torch.rand(rnd.calls["n"], device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(seed))
+    rd.calls["elapsed"].copy_(u * rd.hor[rd.calls["wf"].long()])
+    rd.score()
+    torch.cuda.synchronize()
+    late = float((rd.ratio > 1.5).float().mean().item())
+    rd.step()
+    torch.cuda.synchronize()
+    run = rd.step if eager else capture(torch, rd.step).replay       # one round at a time: launch-bound
+    lat = []
+    for i in range(rounds + 20):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run()
+        torch.cuda.synchronize()
+        if i >= 20:
+            lat.append((time.perf_counter() - t0) * 1e6)
+    lat = np.array(lat)
+    ctx.hx_stream_status()
+    return {"workload": "%s round: %d calls x %d x %d, %d workflows / %d nodes" % (name, rnd.calls["n"], rnd.pre["n"], rnd.dec["n"],
+                                                                                  rnd.dag.n_wf, rnd.dag.n_nodes),
+            "p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)), "rounds": int(lat.size),
+            "candidates_per_s_at_p50": rnd.n_candidates / (np.percentile(lat, 50) * 1e-6),
+            "calls_with_ratio_above_1.5": late, "launch": "eager" if eager else "hip graph replay"}
 
 
 def main():
@@ -406,6 +551,8 @@ def main():
                     help="run the horizon refresh on a second stream beside the search (measured: 3-4 us slower per round "
                          "than one stream, the fork and join cost more than the small kernels they hide)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-calibration", action="store_true", help="skip the measurement of the chip's vector issue rate")
+    ap.add_argument("--stream-rounds", type=int, default=1000, help="consecutive rounds of the streaming leg")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 256 MiB device copies, the known-size reference for HBM byte counters")
     ap.add_argument("--no-extras", action="store_true", help="skip the mid-round latency and critical-path legs")
@@ -449,7 +596,7 @@ def main():
     value = n_cand * args.steps / wall
     # the dominant kernel on its own: table prepare + fused search, HIP events on the launch stream
     score_s = time_launches(torch, rd.score, max(20, min(args.steps, 200)))
-    achieved = n_cand * OPS_PER_CANDIDATE / score_s / 1e12
+    achieved = n_cand * MAIN_PIPE_OPS_PER_CANDIDATE / score_s / 1e12
     out = {
         "metric": "placement candidates scored/sec",
         "value": value, "unit": "candidates/s",
@@ -465,32 +612,25 @@ def main():
                             if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
                    "launch": "eager, the host enqueues ahead of the GPU" if launch == "eager" else "hip graph replay", "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups)", "bound": "alu",
-                     "achieved": achieved, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
-                     "frac": achieved / ALU_PEAK_TOPS, "traffic": FUSED_TRAFFIC_BYTES.get(args.workload),
-                     "ops_per_candidate": OPS_PER_CANDIDATE, "launch_ms": score_s * 1e3,
-                     "candidates_per_s_kernel": n_cand / score_s},
+                     "achieved": achieved, "peak": ALU_PEAK_TOPS,
+                     "unit": "T lane-ops/s on the SIMDs' main fp32 pipe (v_max_f32, v_min3_f32: 1.5 per candidate; the v_add_f32 pairs with them on the second pipe)",
+                     "frac": achieved / ALU_PEAK_TOPS,
+                     "traffic": profiled_traffic("fused_search_large_sweep.txt") if args.workload == "large" else None,
+                     "main_pipe_ops_per_candidate": MAIN_PIPE_OPS_PER_CANDIDATE, "ops_per_candidate": OPS_PER_CANDIDATE,
+                     "launch_ms": score_s * 1e3, "candidates_per_s_kernel": n_cand / score_s,
+                     "frac_of_fp32_vector_peak_157.3_tflops": n_cand * OPS_PER_CANDIDATE / score_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS},
     }
+    if not args.no_calibration:
+        cal = calibration_leg(torch)
+        out["calibration"] = cal
+        measured = cal["search loop on registers"]["main_pipe_lane_ops_per_s"] / 1e12
+        out["roofline"]["peak_measured"] = measured
+        out["roofline"]["frac_of_measured"] = achieved / measured
 
     if not args.no_extras:
-        # p50 scheduling-round latency on the mid round: host clock from "round handed over" to "indices ready"
-        mid = synth.make_round("mid", args.seed)
-        rm = RoundOnDevice(ctx, mid)
-        rm.step()
-        torch.cuda.synchronize()
-        run_mid = rm.step if (args.eager or args.launch == "eager") else capture(torch, rm.step).replay   # one round at a time: launch-bound
-        lat = []
-        for i in range(520):
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            run_mid()
-            torch.cuda.synchronize()
-            if i >= 20:
-                lat.append((time.perf_counter() - t0) * 1e6)
-        lat = np.array(lat)
-        out["round_latency"] = {"workload": "mid round: 4096 calls x 64 x 64, 1000 workflows / %d nodes" % mid.dag.n_nodes,
-                                "p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
-                                "rounds": int(lat.size),
-                                "candidates_per_s_at_p50": mid.n_candidates / (np.percentile(lat, 50) * 1e-6)}
+        eager = args.eager or args.launch == "eager"
+        out["round_latency"] = round_latency(torch, ctx, synth, "mid", args.seed, eager)
+        out["round_latency"]["tiny"] = round_latency(torch, ctx, synth, "tiny", args.seed, eager)
         # critical-path stress: 100 000 workflows, 2.0 M nodes; rotating copies so the
         # pass does not run out of the 256 MB last-level cache
         cp = synth.make_round("cp", args.seed)
@@ -532,7 +672,7 @@ def main():
         out["critical_path"] = {"workload": "critical-path stress: %d workflows, %d nodes, %d edges" % (d.n_wf, d.n_nodes, d.n_edges),
                                 "kernel": "hx_cp_local_kernel", "bound": "hbm", "launch_ms": cp_ms,
                                 "algorithmic_bytes": cp_bytes, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                "frac": gbs / HBM_PEAK_GBS, "traffic": CP_TRAFFIC_BYTES, "rotating_copies": n_copies,
+                                "frac": gbs / HBM_PEAK_GBS, "traffic": profiled_traffic("cp_local_critical_path_stress.txt"), "rotating_copies": n_copies,
                                 "plain_copy_same_bytes_ms": copy_ms}
         del sets
         # the same kernel on eight copies of the graph side by side (16 M nodes, 435 MB per pass, more than the
@@ -569,7 +709,7 @@ def main():
             "unit": "GB/s", "frac": big_bytes / (big_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "plain_copy_same_bytes_ms": copy8_ms}
 
     if not args.no_extras:
-        out["streaming"] = streaming_leg(torch, ctx, synth, binding, args.seed, rounds=30)
+        out["streaming"] = streaming_leg(torch, ctx, synth, binding, args.seed, rounds=args.stream_rounds)
         out["planner"] = planner_leg(torch, ctx, synth, binding, args.seed)
         out["decode_stage"] = decode_leg(torch, ctx, synth, binding, args.seed)
         out["estimate_error"] = robustness_leg(torch, ctx, synth, binding, args.seed)

@@ -281,6 +281,36 @@ int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *call
                         int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
                         void *stream);
 
+/*
+ * Debug entry point: element-by-element check of a round's inputs.  The
+ * scoring calls check sizes and pointers only and tolerate out-of-range
+ * elements without faulting (their results for such elements are
+ * unspecified); this call counts them.  report: host [HX_VALIDATE_FIELDS] out,
+ * the number of offending elements per category below.  calls->node, wf and
+ * elapsed, and links->latency, are checked when not NULL.  Synchronises
+ * `stream`.  Returns HX_OK when every count is zero, else HX_ERR_INVALID_ARG
+ * with hx_last_error naming the first non-empty category.  Not for the hot
+ * loop: it reads every input array once and waits for the result.
+ */
+enum {
+    HX_BAD_L_IN = 0,          /* L_in < 0                                             */
+    HX_BAD_L_OUT,             /* L_out < 0                                            */
+    HX_BAD_NODE,              /* node outside 0..n_nodes-1                            */
+    HX_BAD_WF,                /* wf outside 0..n_wf-1                                 */
+    HX_BAD_ELAPSED,           /* elapsed negative, infinite or NaN                    */
+    HX_BAD_PREFILL_RATE,      /* prefill flops or hbm_bw not finite and > 0           */
+    HX_BAD_PREFILL_BACKLOG,   /* backlog_tok < 0                                      */
+    HX_BAD_PREFILL_TYPE,      /* prefill type outside 0..n_types-1                    */
+    HX_BAD_DECODE_RATE,       /* decode flops or hbm_bw not finite and > 0            */
+    HX_BAD_DECODE_STATE,      /* used_tok, cap_tok, batch or qd_tok < 0               */
+    HX_BAD_DECODE_TYPE,       /* decode type outside 0..n_types-1                     */
+    HX_BAD_LINK,              /* bw not finite and > 0, latency negative or not finite */
+    HX_VALIDATE_FIELDS
+};
+int hx_validate_round(hx_ctx *ctx, const hx_calls *calls, const hx_prefill_tab *prefill,
+                      const hx_decode_tab *decode, const hx_links *links,
+                      int32_t n_nodes, int32_t n_wf, int32_t *report, void *stream);
+
 /* ---- (3) select: per-call argmin over a materialised tensor --------------- */
 
 /*

@@ -31,6 +31,17 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer, every
+    finding fatal (for a test that runs the pins against it; load it by
+    putting its path in HXO_LIB with libasan preloaded)."""
+    subprocess.check_call(
+        ["gcc", "-O1", "-g", "-std=c99", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
+         "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+         "-o", out, _SRC, "-lm"])
+    return out
+
+
 class _Model(C.Structure):
     _fields_ = [("kv_bytes_per_token", C.c_double), ("flops_per_token", C.c_double),
                 ("attn_flops_per_token2", C.c_double), ("weight_bytes", C.c_double),
@@ -43,7 +54,7 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(os.environ.get("HXO_LIB") or build())      # HXO_LIB: a build of the same source to use instead
         _lib.hxo_score_one.restype = C.c_double
         _lib.hxo_candidate_cost.restype = C.c_double
         for name in ("hxo_prefill_wait", "hxo_prefill_time", "hxo_transfer_time",

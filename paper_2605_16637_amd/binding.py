@@ -18,7 +18,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
            "hx_critical_path", "hx_horizons", "hx_dag_reserve", "hx_dag_append", "hx_dag_set_cost", "hx_dag_view",
-           "hx_score_placements", "hx_select", "hx_urgency", "hx_commit", "hx_commit_static", "hx_rank", "hx_plan_greedy",
+           "hx_score_placements", "hx_validate_round", "hx_select", "hx_urgency", "hx_commit", "hx_commit_static", "hx_rank", "hx_plan_greedy",
            "hx_decode_score", "hx_decode_plan_greedy")
 
 
@@ -270,6 +270,23 @@ class Context:
             _ptr(cost, torch.float32, Cn * P * D), _ptr(feas, torch.uint8, Cn * D),
             _ptr(best_p, torch.int32, Cn), _ptr(best_d, torch.int32, Cn), _ptr(best_cost, torch.float32, Cn),
             _ptr(ratio, torch.float32, Cn), _stream(stream)))
+
+    VALIDATE_FIELDS = ("L_in", "L_out", "node", "wf", "elapsed", "prefill_rate", "prefill_backlog", "prefill_type",
+                       "decode_rate", "decode_state", "decode_type", "link")
+
+    def hx_validate_round(self, calls, prefill, decode, links, n_nodes=0, n_wf=0, stream=None):
+        """Counts of out-of-range input elements per category (a dict); raises HxError if any is non-zero
+        unless the caller reads the counts from the exception's ``report``."""
+        cs, pt, dt, lk = make_calls(calls), make_prefill(prefill), make_decode(decode), make_links(links)
+        report = (C.c_int32 * len(self.VALIDATE_FIELDS))()
+        rc = self.lib.hx_validate_round(self._ctx, C.byref(cs), C.byref(pt), C.byref(dt), C.byref(lk),
+                                        int(n_nodes), int(n_wf), report, _stream(stream))
+        counts = dict(zip(self.VALIDATE_FIELDS, list(report)))
+        if rc != HX_OK:
+            err = HxError(rc, self.lib.hx_last_error(self._ctx).decode())
+            err.report = counts
+            raise err
+        return counts
 
     def hx_select(self, C_, P, D, cost, best_p, best_d, best_cost, calls=None, tail=None, horizon=None,
                   ratio=None, stream=None):

@@ -1,4 +1,5 @@
-"""Builds the C-ABI library ``libhx.so`` from the HIP sources, in-tree, for gfx950."""
+"""Builds the C-ABI library ``libhx.so`` (and the benchmark's calibration kernels,
+``libhx_calib.so``) from the HIP sources, in-tree, for gfx950."""
 from __future__ import annotations
 
 import os
@@ -7,6 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhx.so")
+CALIB_LIB = os.path.join(HERE, "libhx_calib.so")      # the benchmark's calibration kernels, a library of their own
 SOURCES = ["hx_ctx.hip", "hx_score.hip", "hx_dag.hip", "hx_plan.hip", "hx_decode.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -21,8 +23,19 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *FLAGS, "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+# host-side AddressSanitizer + UndefinedBehaviorSanitizer (device code cannot be sanitized here): each option
+# directly after -Xarch_host
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build(verbose: bool = False, out: str = LIB, extra_flags=()) -> str:
+    if out == LIB:
+        _compile(["hipcc", *FLAGS, "-o", CALIB_LIB, os.path.join(CSRC, "hx_calib.hip")], verbose)
+    return _compile(["hipcc", *FLAGS, *extra_flags, "-o", out, *[os.path.join(CSRC, s) for s in SOURCES]], verbose, out)
+
+
+def _compile(cmd, verbose, out=None) -> str:
     if verbose:
         print(" ".join(cmd))
     run = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -36,7 +49,7 @@ def build(verbose: bool = False) -> str:
               % (len(lines) - len(rest)))
     if run.returncode:
         raise subprocess.CalledProcessError(run.returncode, cmd)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -120,6 +120,71 @@ __global__ __launch_bounds__(256) void hx_commit_drain_kernel(CommitArgs a)
     }
 }
 
+// ---- element-by-element check of a round's inputs (debug entry point) ----
+
+struct ValidateArgs {
+    int C, P, D, T, n_nodes, n_wf;
+    const int32_t *L_in, *L_out, *node, *wf;
+    const float *elapsed;
+    const float *p_flops, *p_hbm;
+    const int32_t *p_backlog, *p_type;
+    const float *d_flops, *d_hbm;
+    const int32_t *d_used, *d_cap, *d_batch, *d_qd, *d_type;
+    const float *bw, *lat;
+    int32_t *count;          // [HX_VALIDATE_FIELDS]
+};
+
+// classification on the bit pattern: the build assumes that no arithmetic sees a NaN
+__device__ __forceinline__ bool hx_is_rate(float x)          // finite and > 0
+{
+    const unsigned b = __float_as_uint(x);
+    return b > 0u && b < 0x7f800000u;
+}
+__device__ __forceinline__ bool hx_is_span(float x)          // finite and >= 0
+{
+    const unsigned b = __float_as_uint(x);
+    return b < 0x7f800000u || b == 0x80000000u;
+}
+
+__global__ __launch_bounds__(256) void hx_validate_clear_kernel(int32_t *count)
+{
+    if (threadIdx.x < HX_VALIDATE_FIELDS) count[threadIdx.x] = 0;
+}
+
+__global__ __launch_bounds__(256) void hx_validate_kernel(ValidateArgs a)
+{
+    int bad[HX_VALIDATE_FIELDS];
+#pragma unroll
+    for (int k = 0; k < HX_VALIDATE_FIELDS; ++k) bad[k] = 0;
+    const int stride = gridDim.x * blockDim.x;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.C; i += stride) {
+        bad[HX_BAD_L_IN] += a.L_in[i] < 0;
+        bad[HX_BAD_L_OUT] += a.L_out[i] < 0;
+        if (a.node) bad[HX_BAD_NODE] += a.node[i] < 0 || a.node[i] >= a.n_nodes;
+        if (a.wf) bad[HX_BAD_WF] += a.wf[i] < 0 || a.wf[i] >= a.n_wf;
+        if (a.elapsed) bad[HX_BAD_ELAPSED] += !hx_is_span(a.elapsed[i]);
+    }
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.P; i += stride) {
+        bad[HX_BAD_PREFILL_RATE] += !hx_is_rate(a.p_flops[i]) || !hx_is_rate(a.p_hbm[i]);
+        bad[HX_BAD_PREFILL_BACKLOG] += a.p_backlog[i] < 0;
+        bad[HX_BAD_PREFILL_TYPE] += a.p_type[i] < 0 || a.p_type[i] >= a.T;
+    }
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.D; i += stride) {
+        bad[HX_BAD_DECODE_RATE] += !hx_is_rate(a.d_flops[i]) || !hx_is_rate(a.d_hbm[i]);
+        bad[HX_BAD_DECODE_STATE] += a.d_used[i] < 0 || a.d_cap[i] < 0 || a.d_batch[i] < 0 || a.d_qd[i] < 0;
+        bad[HX_BAD_DECODE_TYPE] += a.d_type[i] < 0 || a.d_type[i] >= a.T;
+    }
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.T * a.T; i += stride)
+        bad[HX_BAD_LINK] += !hx_is_rate(a.bw[i]) || (a.lat && !hx_is_span(a.lat[i]));
+#pragma unroll
+    for (int k = 0; k < HX_VALIDATE_FIELDS; ++k) {
+        int v = bad[k];
+#pragma unroll
+        for (int off = HX_WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off);
+        if ((threadIdx.x & (HX_WAVE - 1)) == 0 && v) atomicAdd(&a.count[k], v);
+    }
+}
+
 // Scratch of hx_commit_static, the commit for callers that cannot allocate: the
 // accumulators of one round, [P] backlog, [D] used, [D] qd additions, then a
 // spare word that takes the status of a caller who passes none.  Each GPU the
@@ -322,5 +387,46 @@ extern "C" int hx_commit_static(const hx_calls *calls, const int32_t *best_p, co
     hx_commit_drain_kernel<<<(n_inst + 255) / 256, 256, 0, stream>>>(a);
     e = hipGetLastError();
     if (e != hipSuccess) return static_fail(HX_ERR_DEVICE, "hx_commit_static: launch: %s", hipGetErrorString(e));
+    return HX_OK;
+}
+
+extern "C" int hx_validate_round(hx_ctx *ctx, const hx_calls *calls, const hx_prefill_tab *pre, const hx_decode_tab *dec,
+                                 const hx_links *links, int32_t n_nodes, int32_t n_wf, int32_t *report, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, calls && pre && dec && links && report, HX_ERR_INVALID_ARG, "NULL table or report");
+    const int C = calls->n, P = pre->n, D = dec->n, T = links->n_types;
+    HX_REQUIRE(ctx, C >= 0 && P >= 0 && D >= 0 && n_nodes >= 0 && n_wf >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, T >= 1 && T <= HX_MAX_TYPES, HX_ERR_SHAPE, "n_types %d outside 1..%d", T, HX_MAX_TYPES);
+    HX_REQUIRE(ctx, C == 0 || (calls->L_in && calls->L_out), HX_ERR_INVALID_ARG, "NULL call array");
+    HX_REQUIRE(ctx, P == 0 || (pre->flops && pre->hbm_bw && pre->backlog_tok && pre->type), HX_ERR_INVALID_ARG,
+               "NULL member in prefill table");
+    HX_REQUIRE(ctx, D == 0 || (dec->flops && dec->hbm_bw && dec->used_tok && dec->cap_tok && dec->batch && dec->qd_tok && dec->type),
+               HX_ERR_INVALID_ARG, "NULL member in decode table");
+    HX_REQUIRE(ctx, links->bw, HX_ERR_INVALID_ARG, "links.bw is NULL");
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    ValidateArgs a{C, P, D, T, n_nodes, n_wf, calls->L_in, calls->L_out, calls->node, calls->wf, calls->elapsed,
+                   pre->flops, pre->hbm_bw, pre->backlog_tok, pre->type,
+                   dec->flops, dec->hbm_bw, dec->used_tok, dec->cap_tok, dec->batch, dec->qd_tok, dec->type,
+                   links->bw, links->latency, ctx->d_flags};
+    int n = C > P ? C : P;
+    n = n > D ? n : D;
+    n = n > T * T ? n : T * T;
+    int grid = (n + 255) / 256;
+    grid = grid > ctx->num_cu * 4 ? ctx->num_cu * 4 : grid;
+    hx_validate_clear_kernel<<<1, 256, 0, stream>>>(ctx->d_flags);
+    hx_validate_kernel<<<grid, 256, 0, stream>>>(a);
+    if (int rc = hx_check_launch(ctx, "hx_validate_kernel")) return rc;
+    HX_HIP(ctx, hipMemcpyAsync(report, ctx->d_flags, HX_VALIDATE_FIELDS * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    HX_HIP(ctx, hipStreamSynchronize(stream));
+    static const char *const what[HX_VALIDATE_FIELDS] = {
+        "negative L_in", "negative L_out", "node outside 0..n_nodes-1", "wf outside 0..n_wf-1", "elapsed negative or not finite",
+        "prefill flops or hbm_bw not a positive finite number", "negative backlog_tok", "prefill type outside 0..n_types-1",
+        "decode flops or hbm_bw not a positive finite number", "negative used_tok, cap_tok, batch or qd_tok",
+        "decode type outside 0..n_types-1", "link bandwidth not positive and finite, or latency negative or not finite"};
+    for (int k = 0; k < HX_VALIDATE_FIELDS; ++k)
+        if (report[k]) return hx_fail(ctx, HX_ERR_INVALID_ARG, "%d element(s): %s", report[k], what[k]);
     return HX_OK;
 }

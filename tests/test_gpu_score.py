@@ -328,3 +328,30 @@ def test_urgency_entry_point_equals_the_fused_epilogue(ctx):
     with pytest.raises(binding.HxError) as e:
         ctx.hx_stream_status()
     assert e.value.code == -6
+
+
+def test_debug_validation_counts_bad_elements(ctx):
+    # the scoring calls check sizes and pointers only; the debug entry point counts out-of-range elements per category
+    from paper_2605_16637_amd import binding
+    rnd = synth.make_round("mid", 2)
+    calls, pre, dec, links = dev_tables(rnd)
+    ok = ctx.hx_validate_round(calls, pre, dec, links, n_nodes=rnd.dag.n_nodes, n_wf=rnd.dag.n_wf)
+    assert set(ok) == set(binding.Context.VALIDATE_FIELDS) and not any(ok.values())
+    c = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in rnd.calls.items()}
+    p = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in rnd.pre.items()}
+    d = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in rnd.dec.items()}
+    l = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in rnd.links.items()}
+    c["L_in"][[3, 9]] = -1; c["L_out"][5] = -7; c["node"][0] = rnd.dag.n_nodes; c["wf"][[1, 2, 4000]] = -1
+    c["elapsed"][[10, 11, 12]] = [np.nan, np.inf, -1.0]
+    p["flops"][1] = 0.0; p["hbm_bw"][2] = np.nan; p["backlog_tok"][[7, 8]] = -5; p["type"][63] = 4
+    d["flops"][0] = -1e12; d["cap_tok"][3] = -1; d["qd_tok"][3] = -1; d["batch"][9] = -2; d["type"][[5, 6]] = [-1, 99]
+    l["bw"] = np.array(l["bw"], np.float32).copy(); l["bw"].reshape(-1)[5] = np.inf
+    with pytest.raises(binding.HxError) as e:
+        ctx.hx_validate_round(binding.to_device(c), binding.to_device(p), binding.to_device(d), binding.to_device(l),
+                              n_nodes=rnd.dag.n_nodes, n_wf=rnd.dag.n_wf)
+    assert e.value.code == -1 and "L_in" in str(e.value)
+    assert e.value.report == dict(L_in=2, L_out=1, node=1, wf=3, elapsed=3, prefill_rate=2, prefill_backlog=2, prefill_type=1,
+                                  decode_rate=1, decode_state=2, decode_type=2, link=1)
+    # an empty round and an empty pool are fine
+    none = dict(calls, n=0)
+    assert not any(ctx.hx_validate_round(none, dict(pre, n=0), dict(dec, n=0), links).values())
