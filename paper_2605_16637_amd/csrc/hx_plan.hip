@@ -227,7 +227,7 @@ struct GreedyLds {
              + P + 7 * (size_t)D                               // simulated state and what is needed to re-derive an entry
              + 10 * (size_t)C                                  // per call: pair, cost, ratio, flags; lengths, elapsed, tail, horizon
              + 4 * GREEDY_WAVES                                // reduction scratch
-             + (size_t)GREEDY_WAVES * (2 * Dp + kT * kT + kT); // per-wave search buffers
+             + (size_t)GREEDY_WAVES * (Dp + kT * kT + kT);     // per-wave search buffers
     }
 };
 
@@ -287,8 +287,8 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     const int tid = threadIdx.x;
     const int lane = tid & (HX_WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    float2 *wbuf = (float2 *)(s_wave + (size_t)wave * (2 * lay.Dp + kT * kT + kT));
-    float *xbuf = (float *)(wbuf + lay.Dp);
+    float *dbuf = s_wave + (size_t)wave * (lay.Dp + kT * kT + kT);
+    float *xbuf = dbuf + lay.Dp;
     float *rbuf = xbuf + kT * kT;
 
     for (int e = tid; e < Dp; e += GREEDY_THREADS) {
@@ -334,8 +334,8 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             // large pools: class by class (KP = 0); small ones: pair by pair, whose inner loop costs less than the
             // class search's reductions up to about 64 x 64 pairs
             HxBest b;
-            if constexpr (KP == 0) b = hx_search_call_by_class<true>(a.m, pool, wbuf, xbuf, rbuf, s_L[c], s_O[c], lane);
-            else b = hx_search_call<KP, true>(a.m, pool, seg, wbuf, xbuf, s_L[c], s_O[c], lane);
+            if constexpr (KP == 0) b = hx_search_call_by_class(a.m, pool, dbuf, xbuf, rbuf, s_L[c], s_O[c], lane);
+            else b = hx_search_call<KP>(a.m, pool, seg, dbuf, xbuf, s_L[c], s_O[c], lane);
             if (lane == 0) {
                 s_bp[c] = b.p; s_bd[c] = b.d; s_bc[c] = b.cost;
                 hx_store_bits(s_ratio, c, hx_ratio_bits(s_el[c], b.cost, s_tl[c], s_hz[c], s_hz[c] >= 0.0f));       // Eq. (2)

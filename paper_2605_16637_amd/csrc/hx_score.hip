@@ -139,7 +139,7 @@ __global__ __launch_bounds__(1024) void hx_prepare_kernel(PrepArgs a)
     }
 }
 
-// The same tables, built by a workgroup of 256 threads straight into its own LDS arrays (the fused search
+// The same tables, built by the first 256 threads of a workgroup straight into its own LDS arrays (the fused search
 // does this itself instead of reading what hx_prepare_kernel wrote: a launch less per round, for a few
 // barriers more per workgroup).  Entry order is the one above: classes ascending, instances of a class
 // ascending.  s_scratch: [(HX_MAX_INSTANCES / HX_WAVE) * kT + kT] ints.  Ends with a barrier.
@@ -157,8 +157,10 @@ struct PrepLds {
 __device__ __forceinline__ void hx_prepare_into_lds(const PrepArgs &a, const PrepLds &o)
 {
     constexpr int NCH = HX_MAX_INSTANCES / 256;          // chunks of 256 instances
-    const int tid = threadIdx.x;
-    const int lane = tid & (HX_WAVE - 1), wv = tid >> 6;
+    // the first 256 threads of the workgroup do the work; wavefronts beyond them only keep the barriers company
+    const bool worker = threadIdx.x < 256;
+    const int tid = worker ? (int)threadIdx.x : (1 << 24);      // beyond every size: all the tests below fail
+    const int lane = threadIdx.x & (HX_WAVE - 1), wv = (threadIdx.x >> 6) & 3;
     int *s_wcnt = o.scratch;                             // [NCH * 4 waves][kT]
     int *s_cnt = o.scratch + NCH * 4 * kT;               // [kT]
 
@@ -206,7 +208,7 @@ __device__ __forceinline__ void hx_prepare_into_lds(const PrepArgs &a, const Pre
 #pragma unroll
             for (int t = 0; t < kT; ++t) {
                 const unsigned long long b = __ballot(my_t[j] == t);
-                if (lane == 0) s_wcnt[(j * 4 + wv) * kT + t] = __popcll(b);
+                if (lane == 0 && worker) s_wcnt[(j * 4 + wv) * kT + t] = __popcll(b);
                 if (my_t[j] == t) my_rank[j] = __popcll(b & ((1ull << lane) - 1ull));
             }
         }
@@ -295,12 +297,12 @@ struct FusedLds {
     __host__ __device__ FusedLds(int n_entries_bound, int P)
         : Dp(n_entries_bound), Pp((P + HX_WAVE - 1) / HX_WAVE * HX_WAVE) {}
     __host__ __device__ size_t block_floats() const { return (size_t)7 * Dp + (size_t)4 * Pp + 2 * kT * kT + 16; }
-    __host__ __device__ size_t wave_floats() const { return (size_t)2 * Dp + kT * kT; }
+    __host__ __device__ size_t wave_floats() const { return (size_t)Dp + kT * kT; }
     __host__ __device__ size_t bytes(int waves) const { return 4 * (block_floats() + waves * wave_floats()); }
 };
 
 template <int KP>
-__global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound)
+__global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound)
 {
     extern __shared__ __align__(16) float smem[];
     const FusedLds lay(dp_bound, a.P);
@@ -324,8 +326,8 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, PrepA
     const int lane = tid & (HX_WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int waves_per_block = blockDim.x >> 6;
-    float2 *wbuf = (float2 *)(s_wave + (size_t)wave * lay.wave_floats());   // (avail, decode time) per entry
-    float *xbuf = (float *)(wbuf + lay.Dp);                                  // transfer per class pair
+    float *dbuf = s_wave + (size_t)wave * lay.wave_floats();    // the call's decode time per entry
+    float *xbuf = dbuf + lay.Dp;                                // transfer per class pair
 
     // the per-round tables of the pool, derived here; the class counts of the derivation borrow the
     // waves' buffers, which nothing has used yet
@@ -333,7 +335,6 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, PrepA
                       s_invbw, s_lat, s_seg, (int *)s_wave, lay.Pp};
     hx_prepare_into_lds(pa, out);
     const int Dp = s_seg[kT];              // <= dp_bound by construction
-    for (int e = lane; e < Dp; e += HX_WAVE) wbuf[e].x = s_wait[e];
 
     int seg[kT + 1];
 #pragma unroll
@@ -344,7 +345,7 @@ __global__ __launch_bounds__(256) void hx_fused_search_kernel(ScoreArgs a, PrepA
     const int gw = blockIdx.x * waves_per_block + wave;
     const int nw = gridDim.x * waves_per_block;
     for (int c = gw; c < a.C; c += nw) {
-        const HxBest b = hx_search_call<KP, false>(a.m, pool, seg, wbuf, xbuf, a.L_in[c], a.L_out[c], lane);
+        const HxBest b = hx_search_call<KP>(a.m, pool, seg, dbuf, xbuf, a.L_in[c], a.L_out[c], lane);
         const float bestv = b.cost;
         const int pstar = b.p, dstar = b.d;
         if (lane == 0) {
@@ -660,12 +661,22 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         const PrepArgs pa = make_prep_args(ctx, model, pre, dec, links);
         // upper bound of the padded decode entries, known on the host without reading the device
         const int dp_bound = (D + HX_DGROUP - 1) / HX_DGROUP * HX_DGROUP + (T - 1) * HX_DGROUP;
-        const int waves = 4;
+        // Workgroups of 4 or 8 wavefronts (one or two per SIMD), as many per compute unit as local memory allows up
+        // to 6 wavefronts per SIMD (registers would allow 7; measured no faster, and 6 divides into either
+        // workgroup size): the pool tables are per workgroup, a wavefront adds its decode-time and transfer
+        // buffers.  Whichever size puts more wavefronts on a SIMD.
         const FusedLds lay(dp_bound, P);
+        const int reg_limit = 6 * 4;                               // wavefronts per compute unit
+        int waves = 4, blocks_per_cu = 1, best_on_cu = 0;
+        for (int w = 4; w <= 8; w += 4) {
+            const size_t need_lds = lay.bytes(w);
+            if (need_lds > 160 * 1024) continue;
+            int b = (int)((160 * 1024) / need_lds);
+            b = b > reg_limit / w ? reg_limit / w : b;
+            if (b * w > best_on_cu) { best_on_cu = b * w; waves = w; blocks_per_cu = b; }
+        }
         const size_t lds = lay.bytes(waves);
-        HX_REQUIRE(ctx, lds <= 160 * 1024, HX_ERR_SHAPE, "pool needs %zu B of LDS", lds);
-        int blocks_per_cu = (int)((160 * 1024) / lds);
-        blocks_per_cu = blocks_per_cu > 4 ? 4 : (blocks_per_cu < 1 ? 1 : blocks_per_cu);
+        HX_REQUIRE(ctx, best_on_cu > 0, HX_ERR_SHAPE, "pool needs %zu B of LDS", lds);
         int grid = ctx->num_cu * blocks_per_cu;
         const int need = (C + waves - 1) / waves;
         grid = grid > need ? need : grid;

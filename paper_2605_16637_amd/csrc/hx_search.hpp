@@ -3,10 +3,11 @@
 // that both compare exactly the same fp32 costs.
 //
 // Lanes are prefill instances (KP per lane, in chunks of 64*KP beyond that).
-// Everything that depends on the decode instance only -- its availability hint
-// and the call's decode time there (+inf where the call does not fit) -- is
-// written once per call into the wave's LDS buffer and read back as
-// broadcasts; decode entries are grouped by GPU class, so the transfer time
+// What depends on the decode instance only is the same for all 64 lanes and is
+// read from LDS as broadcasts: the instance's availability hint (from the
+// workgroup's pool tables, it does not depend on the call) and the call's
+// decode time there (+inf where the call does not fit), written once per call
+// into the wave's own buffer; decode entries are grouped by GPU class, so the transfer time
 // leaves the inner loop, which is  t = max(ready, avail_d) + dec_d ;
 // best = min(best, t)  with no index bookkeeping.  The index is recovered
 // afterwards: the wave minimum fixes the winning prefill instance (lowest p
@@ -70,24 +71,59 @@ struct HxBest {
     int p, d;      // -1, -1 then
 };
 
-// wbuf: the wave's [Dp] (avail, decode time) pairs; with REFRESH_WAIT the avail
-// halves are rewritten from the pool view first (the caller changes the pool
-// between calls), otherwise the caller has filled them once.
-// xbuf: the wave's [kT*kT] transfer times.  seg: class segments, wave-uniform.
-template <int KP, bool REFRESH_WAIT>
+// One instruction each, in the order written (the compiler keeps volatile statements in order): the fold below
+// fixes its instruction sequence by hand.  Same operations as hx_candidate and fminf, hence the same bits.
+#define HX_VMAX(d, a, b) asm volatile("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b))
+#define HX_VADD(d, a, b) asm volatile("v_add_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b))
+#define HX_VMIN3(d, a, b, c) asm volatile("v_min3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c))
+
+// Folds the eight candidates of one group of decode entries, availability in a0, a1, decode time in d0, d1, into the
+// running minimum of each of the lane's KP prefill instances: t = max(ready, avail) + dec, three-input minima.
+// A SIMD's main pipe issues the maxima and minima (one per 4 cycles); an addition can issue at the same time
+// on the second fp32 pipe, for another wavefront.  The three kinds are therefore mixed finely -- the additions
+// and minima of a slot between the maxima of the next -- so that whatever point of the sequence the other
+// wavefronts of the SIMD are at, one of them is likely to offer an instruction of the other kind.
+template <int KP>
+__device__ __forceinline__ void hx_fold_group(const float (&r)[KP], float (&best)[KP],
+                                              const float4 &a0, const float4 &a1, const float4 &d0, const float4 &d1)
+{
+    const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+    const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+    float t[KP][8], m1[KP], m2[KP];
+#pragma unroll
+    for (int j = 0; j < KP; ++j) {
+        HX_VMAX(t[j][0], r[j], av[0]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (e + 1 < 8) HX_VMAX(t[j][e + 1], r[j], av[e + 1]);
+            HX_VADD(t[j][e], t[j][e], dv[e]);
+            if (j > 0 && e == 1) HX_VMIN3(best[j - 1], best[j - 1], t[j - 1][0], t[j - 1][1]);
+            if (j > 0 && e == 3) HX_VMIN3(m1[j - 1], t[j - 1][2], t[j - 1][3], t[j - 1][4]);
+            if (j > 0 && e == 5) HX_VMIN3(m2[j - 1], t[j - 1][5], t[j - 1][6], t[j - 1][7]);
+            if (j > 0 && e == 7) HX_VMIN3(best[j - 1], best[j - 1], m1[j - 1], m2[j - 1]);
+        }
+    }
+    HX_VMIN3(best[KP - 1], best[KP - 1], t[KP - 1][0], t[KP - 1][1]);
+    HX_VMIN3(m1[KP - 1], t[KP - 1][2], t[KP - 1][3], t[KP - 1][4]);
+    HX_VMIN3(m2[KP - 1], t[KP - 1][5], t[KP - 1][6], t[KP - 1][7]);
+    HX_VMIN3(best[KP - 1], best[KP - 1], m1[KP - 1], m2[KP - 1]);
+}
+
+// dbuf: the wave's [Dp] decode times of the call (16-byte aligned); xbuf: the wave's [kT*kT] transfer times.
+// s.wait (availability per decode entry) is read as it stands in the pool view: a caller that changes the
+// pool between calls changes it there.  seg: class segments, wave-uniform.
+template <int KP>
 __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPoolLds &s,
                                                  const int (&seg)[HX_MAX_TYPES + 1],
-                                                 float2 *wbuf, float *xbuf, int L, int O, int lane)
+                                                 float *dbuf, float *xbuf, int L, int O, int lane)
 {
     constexpr int kT = HX_MAX_TYPES;
     const HxCallF cf = hx_call_terms(m, L, O);
     const int Dp = s.Dp;
 
     // decode time of this call on every decode entry (+inf where it does not fit)
-    for (int e = lane; e < Dp; e += HX_WAVE) {
-        if (REFRESH_WAIT) wbuf[e].x = s.wait[e];
-        wbuf[e].y = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
-    }
+    for (int e = lane; e < Dp; e += HX_WAVE)
+        dbuf[e] = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
     xbuf[lane] = hx_transfer(cf, s.invbw[lane], s.lat[lane]);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -96,37 +132,29 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
     float bestv = INFINITY;
     int bestp = -1;
     for (int chunk = 0; chunk < s.P; chunk += HX_WAVE * KP) {
-        float R[KP][kT], bj[KP];
+        // per prefill instance of the lane: its finish time, and where its row of transfer times starts
+        float done[KP], bj[KP];
+        const float *xr[KP];
 #pragma unroll
         for (int j = 0; j < KP; ++j) {
             int p = chunk + j * HX_WAVE + lane;
             p = p < s.Pp ? p : s.Pp - 1;            // stays inside the staged (padded) table
             const bool in = chunk + j * HX_WAVE + lane < s.P;
-            const float done = in ? hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]) : INFINITY;
-            const float *xr = xbuf + s.ptype[p] * kT;
-#pragma unroll
-            for (int k = 0; k < kT; ++k) R[j][k] = done + xr[k];
+            done[j] = in ? hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]) : INFINITY;
+            xr[j] = xbuf + s.ptype[p] * kT;
             bj[j] = INFINITY;
         }
 #pragma unroll
         for (int k = 0; k < kT; ++k) {
-            const float4 *q = (const float4 *)(wbuf + seg[k]);
+            const float4 *qa = (const float4 *)(s.wait + seg[k]);
+            const float4 *qd = (const float4 *)(dbuf + seg[k]);
             const int ngroups = (seg[k + 1] - seg[k]) / HX_DGROUP;
-            for (int g = 0; g < ngroups; ++g, q += HX_DGROUP / 2) {
-                const float4 q0 = q[0], q1 = q[1], q2 = q[2], q3 = q[3];
+            // ready time at an instance of decode class k: prefill finish + transfer (formed per class rather than
+            // kept for all classes: registers are what limits the wavefronts per SIMD)
+            float rk[KP];
 #pragma unroll
-                for (int j = 0; j < KP; ++j) {
-                    const float r = R[j][k];
-                    const float t0 = hx_candidate(r, q0.x, q0.y), t1 = hx_candidate(r, q0.z, q0.w);
-                    const float t2 = hx_candidate(r, q1.x, q1.y), t3 = hx_candidate(r, q1.z, q1.w);
-                    const float t4 = hx_candidate(r, q2.x, q2.y), t5 = hx_candidate(r, q2.z, q2.w);
-                    const float t6 = hx_candidate(r, q3.x, q3.y), t7 = hx_candidate(r, q3.z, q3.w);
-                    const float m0 = fminf(fminf(bj[j], t0), t1);
-                    const float m1 = fminf(fminf(t2, t3), t4);
-                    const float m2 = fminf(fminf(t5, t6), t7);
-                    bj[j] = fminf(fminf(m0, m1), m2);
-                }
-            }
+            for (int j = 0; j < KP; ++j) rk[j] = done[j] + xr[j][k];
+            for (int g = 0; g < ngroups; ++g, qa += 2, qd += 2) hx_fold_group<KP>(rk, bj, qa[0], qa[1], qd[0], qd[1]);
         }
 #pragma unroll
         for (int j = 0; j < KP; ++j) {
@@ -146,7 +174,7 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
         const float *xr = xbuf + s.ptype[bestp] * kT;
         int dmin = 0x7fffffff;
         for (int e = lane; e < Dp; e += HX_WAVE) {
-            const float v = hx_candidate(done + xr[s.dtype[e]], wbuf[e].x, wbuf[e].y);
+            const float v = hx_candidate(done + xr[s.dtype[e]], s.wait[e], dbuf[e]);
             if (v == bestv) dmin = min(dmin, s.orig[e]);
         }
         out.d = hx_wave_min(dmin);
@@ -165,18 +193,15 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
 // exactly (max and min round nothing, and the one addition is applied to the same operands).  P x T
 // additions for r, D candidates, and for the (usually one) entry that attains the minimum a pass over p to
 // find the lowest prefill instance that attains it there.
-// wbuf, xbuf as in hx_search_call; rbuf: the wave's [HX_MAX_TYPES] floats.
-template <bool REFRESH_WAIT>
-__device__ __forceinline__ HxBest hx_search_call_by_class(const HxModelF &m, const HxPoolLds &s, float2 *wbuf, float *xbuf,
+// dbuf, xbuf as in hx_search_call; rbuf: the wave's [HX_MAX_TYPES] floats.
+__device__ __forceinline__ HxBest hx_search_call_by_class(const HxModelF &m, const HxPoolLds &s, float *dbuf, float *xbuf,
                                                           float *rbuf, int L, int O, int lane)
 {
     constexpr int kT = HX_MAX_TYPES;
     const HxCallF cf = hx_call_terms(m, L, O);
     const int Dp = s.Dp;
-    for (int e = lane; e < Dp; e += HX_WAVE) {
-        if (REFRESH_WAIT) wbuf[e].x = s.wait[e];
-        wbuf[e].y = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
-    }
+    for (int e = lane; e < Dp; e += HX_WAVE)
+        dbuf[e] = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
     xbuf[lane] = hx_transfer(cf, s.invbw[lane], s.lat[lane]);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -206,10 +231,8 @@ __device__ __forceinline__ HxBest hx_search_call_by_class(const HxModelF &m, con
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     float bv = INFINITY;
-    for (int e = lane; e < Dp; e += HX_WAVE) {
-        const float2 q = wbuf[e];
-        bv = fminf(bv, hx_candidate(rbuf[s.dtype[e] & (kT - 1)], q.x, q.y));
-    }
+    for (int e = lane; e < Dp; e += HX_WAVE)
+        bv = fminf(bv, hx_candidate(rbuf[s.dtype[e] & (kT - 1)], s.wait[e], dbuf[e]));
     bv = hx_wave_min(bv);
     HxBest out{bv, -1, -1};
     if (bv < INFINITY) {
@@ -217,21 +240,18 @@ __device__ __forceinline__ HxBest hx_search_call_by_class(const HxModelF &m, con
         for (int e0 = 0; e0 < Dp; e0 += HX_WAVE) {
             const int e = e0 + lane;
             bool hit = false;
-            if (e < Dp) {
-                const float2 q = wbuf[e];
-                hit = s.orig[e] >= 0 && hx_candidate(rbuf[s.dtype[e] & (kT - 1)], q.x, q.y) == bv;
-            }
+            if (e < Dp) hit = s.orig[e] >= 0 && hx_candidate(rbuf[s.dtype[e] & (kT - 1)], s.wait[e], dbuf[e]) == bv;
             unsigned long long todo = __builtin_amdgcn_ballot_w64(hit);
             while (todo) {
                 const int ee = e0 + __builtin_ctzll(todo);          // an entry that attains the minimum (wave-uniform)
                 todo &= todo - 1;
-                const float2 q = wbuf[ee];
+                const float q_wait = s.wait[ee], q_dec = dbuf[ee];
                 const int k = s.dtype[ee] & (kT - 1);
                 int p_low = 0x7fffffff;
                 for (int chunk = 0; chunk < s.P; chunk += HX_WAVE) {
                     const int p = min(chunk + lane, s.Pp - 1);
                     const float done = hx_prefill_done(cf, s.pw[p], s.pinvF[p], s.pinvB[p]);
-                    const float v = hx_candidate(done + xbuf[s.ptype[p] * kT + k], q.x, q.y);
+                    const float v = hx_candidate(done + xbuf[s.ptype[p] * kT + k], q_wait, q_dec);
                     if (chunk + lane < s.P && v == bv) p_low = min(p_low, chunk + lane);
                 }
                 p_low = hx_wave_min(p_low);
