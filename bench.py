@@ -515,23 +515,33 @@ def round_latency(torch, ctx, synth, name, seed, eager, rounds=500):
     rd.score()
     torch.cuda.synchronize()
     late = float((rd.ratio > 1.5).float().mean().item())
-    rd.step()
-    torch.cuda.synchronize()
-    run = rd.step if eager else capture(torch, rd.step).replay       # one round at a time: launch-bound
-    lat = []
-    for i in range(rounds + 20):
+    # the round is enqueued two ways -- everything on one stream, and the horizon refresh on a second stream beside the
+    # search with the urgency fold joining them -- and timed both ways on alternating rounds of one run; both give
+    # the same results, so the pool state evolves as one sequence.  One round at a time is launch-bound: each order
+    # is replayed from a HIP graph unless eager launches were asked for.
+    orders = {"one stream": rd.step, "horizons beside the search": rd.step_overlapped}
+    runs = {}
+    for name_o, fn in orders.items():
+        fn()
+        torch.cuda.synchronize()
+        runs[name_o] = fn if eager else capture(torch, fn).replay
+    lat = {k: [] for k in runs}
+    names = list(runs)
+    for i in range(2 * rounds + 40):
+        k = names[i % 2]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        run()
+        runs[k]()
         torch.cuda.synchronize()
-        if i >= 20:
-            lat.append((time.perf_counter() - t0) * 1e6)
-    lat = np.array(lat)
+        if i >= 40:
+            lat[k].append((time.perf_counter() - t0) * 1e6)
     ctx.hx_stream_status()
+    by = {k: {"p50_us": float(np.percentile(v, 50)), "p99_us": float(np.percentile(v, 99)), "rounds": len(v)} for k, v in lat.items()}
+    best = min(by, key=lambda k: by[k]["p50_us"])
     return {"workload": "%s round: %d calls x %d x %d, %d workflows / %d nodes" % (name, rnd.calls["n"], rnd.pre["n"], rnd.dec["n"],
                                                                                   rnd.dag.n_wf, rnd.dag.n_nodes),
-            "p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)), "rounds": int(lat.size),
-            "candidates_per_s_at_p50": rnd.n_candidates / (np.percentile(lat, 50) * 1e-6),
+            "p50_us": by[best]["p50_us"], "p99_us": by[best]["p99_us"], "rounds": by[best]["rounds"], "order": best, "by_order": by,
+            "candidates_per_s_at_p50": rnd.n_candidates / (by[best]["p50_us"] * 1e-6),
             "calls_with_ratio_above_1.5": late, "launch": "eager" if eager else "hip graph replay"}
 
 

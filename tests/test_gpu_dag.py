@@ -403,7 +403,7 @@ def test_append_walks_that_hand_over_to_the_sweeps(ctx):
     assert e.value.code == -4
 
 
-@pytest.mark.parametrize("C", [5000, 200000])       # one-block and multi-block paths
+@pytest.mark.parametrize("C", [900, 5000, 200000])      # one launch (small rounds); two launches, few and many workgroups
 def test_commit_matches_oracle(ctx, C):
     import torch
     from paper_2605_16637_amd import binding
