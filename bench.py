@@ -515,34 +515,38 @@ def round_latency(torch, ctx, synth, name, seed, eager, rounds=500):
     rd.score()
     torch.cuda.synchronize()
     late = float((rd.ratio > 1.5).float().mean().item())
-    # the round is enqueued two ways -- everything on one stream, and the horizon refresh on a second stream beside the
-    # search with the urgency fold joining them -- and timed both ways on alternating rounds of one run; both give
-    # the same results, so the pool state evolves as one sequence.  One round at a time is launch-bound: each order
-    # is replayed from a HIP graph unless eager launches were asked for.
-    orders = {"one stream": rd.step, "horizons beside the search": rd.step_overlapped}
-    runs = {}
-    for name_o, fn in orders.items():
-        fn()
-        torch.cuda.synchronize()
-        runs[name_o] = fn if eager else capture(torch, fn).replay
+    # The round is enqueued in several ways, timed on alternating rounds of one run (all give the same results, so
+    # the pool state evolves as one sequence): replayed from a HIP graph; launched eagerly with the arguments of
+    # its library calls marshalled beforehand (binding.Context.prepare: a replayed graph costs the host more than
+    # three plain launches do); and as a graph with the horizon refresh on a second stream beside the search,
+    # the urgency fold joining them.  With --eager the calls are marshalled at every round.
+    rd.step()
+    rd.step_overlapped()
+    torch.cuda.synchronize()
+    if eager:
+        runs = {"eager, one stream": rd.step, "eager, horizons beside the search": rd.step_overlapped}
+    else:
+        runs = {"hip graph replay, one stream": capture(torch, rd.step).replay,
+                "hip graph replay, horizons beside the search": capture(torch, rd.step_overlapped).replay,
+                "prepared launches, one stream": ctx.prepare(rd.step)}
     lat = {k: [] for k in runs}
     names = list(runs)
-    for i in range(2 * rounds + 40):
-        k = names[i % 2]
+    for i in range(len(names) * (rounds + 20)):
+        k = names[i % len(names)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         runs[k]()
         torch.cuda.synchronize()
-        if i >= 40:
+        if i >= len(names) * 20:
             lat[k].append((time.perf_counter() - t0) * 1e6)
     ctx.hx_stream_status()
     by = {k: {"p50_us": float(np.percentile(v, 50)), "p99_us": float(np.percentile(v, 99)), "rounds": len(v)} for k, v in lat.items()}
     best = min(by, key=lambda k: by[k]["p50_us"])
     return {"workload": "%s round: %d calls x %d x %d, %d workflows / %d nodes" % (name, rnd.calls["n"], rnd.pre["n"], rnd.dec["n"],
                                                                                   rnd.dag.n_wf, rnd.dag.n_nodes),
-            "p50_us": by[best]["p50_us"], "p99_us": by[best]["p99_us"], "rounds": by[best]["rounds"], "order": best, "by_order": by,
+            "p50_us": by[best]["p50_us"], "p99_us": by[best]["p99_us"], "rounds": by[best]["rounds"], "launch": best, "by_launch": by,
             "candidates_per_s_at_p50": rnd.n_candidates / (by[best]["p50_us"] * 1e-6),
-            "calls_with_ratio_above_1.5": late, "launch": "eager" if eager else "hip graph replay"}
+            "calls_with_ratio_above_1.5": late}
 
 
 def main():
@@ -552,7 +556,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="large", choices=["large", "mid", "stream"])
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph"],
+    ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph", "prepared"],
                     help="how the timed steps are launched: from the host, one launch after the other (eager), or as "
                          "replays of a HIP graph; auto = the faster of the two in a short untimed trial (eager where the "
                          "host enqueues a step faster than the GPU runs it, graph where the round is launch-bound)")
@@ -592,14 +596,20 @@ def main():
     step = rd.step_overlapped if args.overlap else rd.step
     step()
     torch.cuda.synchronize()
+    modes = {"eager": lambda: step, "graph": lambda: capture(torch, step).replay,
+             # the same launches with the arguments of the library calls marshalled once (not with --overlap: the
+             # waits between the two streams are not library calls)
+             "prepared": lambda: ctx.prepare(step)}
+    if args.overlap:
+        del modes["prepared"]
     if launch == "auto":
-        # whichever is faster on this host, from a short untimed trial of each (a slow host makes eager launch-bound)
-        replay = capture(torch, step).replay
-        trial = {"eager": time_steps(torch, step, 30, 5), "graph": time_steps(torch, replay, 30, 5)}
+        # whichever is fastest on this host, from a short untimed trial of each (a slow host makes eager launch-bound)
+        made = {k: f() for k, f in modes.items()}
+        trial = {k: time_steps(torch, f, 30, 5) for k, f in made.items()}
         launch = min(trial, key=trial.get)
-        run = step if launch == "eager" else replay
+        run = made[launch]
     else:
-        run = step if launch == "eager" else capture(torch, step).replay
+        run = modes[launch]()
     wall = time_steps(torch, run, args.steps, args.warmup)
     ctx.hx_stream_status()
     ms_per_step = wall / args.steps * 1e3
@@ -620,7 +630,9 @@ def main():
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
                    "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
                             if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
-                   "launch": "eager, the host enqueues ahead of the GPU" if launch == "eager" else "hip graph replay", "seed": args.seed},
+                   "launch": {"eager": "eager, the host enqueues ahead of the GPU", "graph": "hip graph replay",
+                              "prepared": "eager launches with pre-marshalled arguments, the host enqueues ahead of the GPU"}[launch],
+                   "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS,
                      "unit": "T lane-ops/s on the SIMDs' main fp32 pipe (v_max_f32, v_min3_f32: 1.5 per candidate; the v_add_f32 pairs with them on the second pipe)",

@@ -178,6 +178,7 @@ class Context:
         if rc != HX_OK:
             raise HxError(rc, self.lib.hx_last_error(None).decode())
         self.device = device
+        self._recording = None
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx.value:
@@ -194,26 +195,56 @@ class Context:
         if rc != HX_OK:
             raise HxError(rc, self.lib.hx_last_error(self._ctx).decode())
 
+    def _invoke(self, fn, *args):
+        """Calls an entry point with marshalled arguments -- or, inside prepare(), only notes the call."""
+        if self._recording is not None:
+            self._recording.append((fn, args))
+        else:
+            self._check(fn(*args))
+
+    def prepare(self, fn):
+        """Runs ``fn`` (any sequence of this context's calls) without calling the library and returns a
+        callable that makes exactly those library calls with the arguments marshalled now: for loops where
+        the same calls recur on the same buffers (a scheduling round replayed every few tens of microseconds)
+        and the marshalling would cost more than the launches.  The tensors passed must stay alive and in
+        place; the stream is the one current at prepare time.  Calls that return values (hx_dag_view,
+        hx_validate_round) are made as usual."""
+        self._recording = []
+        try:
+            fn()
+            calls = self._recording
+        finally:
+            self._recording = None
+        ctx, last_error = self._ctx, self.lib.hx_last_error
+
+        def replay():
+            for f, a in calls:
+                rc = f(*a)
+                if rc != HX_OK:
+                    raise HxError(rc, last_error(ctx).decode())
+        replay.n_calls = len(calls)
+        return replay
+
     def hx_stream_status(self, stream=None):
-        self._check(self.lib.hx_stream_status(self._ctx, _stream(stream)))
+        self._invoke(self.lib.hx_stream_status, self._ctx, _stream(stream))
 
     def hx_node_cost(self, model, L_in, L_out, type_flops, type_hbm_bw, links, cost, stream=None):
         torch = _torch()
         n, T = int(L_in.numel()), int(type_flops.numel())
         m, lk = make_model(model), make_links(links)
-        self._check(self.lib.hx_node_cost(self._ctx, C.byref(m), n, _ptr(L_in, torch.int32), _ptr(L_out, torch.int32, n),
+        self._invoke(self.lib.hx_node_cost, self._ctx, C.byref(m), n, _ptr(L_in, torch.int32), _ptr(L_out, torch.int32, n),
                                           T, _ptr(type_flops, torch.float32), _ptr(type_hbm_bw, torch.float32, T),
-                                          C.byref(lk), _ptr(cost, torch.float32, n), _stream(stream)))
+                                          C.byref(lk), _ptr(cost, torch.float32, n), _stream(stream))
 
     def hx_critical_path(self, succ_row_ptr, succ_col_idx, node_cost, wf_ptr, rem, tail, level, horizon,
                          max_sweeps=0, stream=None):
         torch = _torch()
         n, n_wf, n_edges = int(succ_row_ptr.numel()) - 1, int(wf_ptr.numel()) - 1, int(succ_col_idx.numel())
-        self._check(self.lib.hx_critical_path(
+        self._invoke(self.lib.hx_critical_path, 
             self._ctx, n, n_edges, _ptr(succ_row_ptr, torch.int32), _ptr(succ_col_idx, torch.int32),
             _ptr(node_cost, torch.float32, n), n_wf, _ptr(wf_ptr, torch.int32), int(max_sweeps),
             _ptr(rem, torch.float32, n), _ptr(tail, torch.float32, n), _ptr(level, torch.int32, n),
-            _ptr(horizon, torch.float32, n_wf), _stream(stream)))
+            _ptr(horizon, torch.float32, n_wf), _stream(stream))
 
     def hx_horizons(self, model, succ_row_ptr, succ_col_idx, L_in, L_out, type_flops, type_hbm_bw, links, wf_ptr,
                     node_cost, rem, tail, level, horizon, stream=None):
@@ -221,28 +252,28 @@ class Context:
         n, n_wf, n_edges = int(succ_row_ptr.numel()) - 1, int(wf_ptr.numel()) - 1, int(succ_col_idx.numel())
         T = int(type_flops.numel())
         m, lk = make_model(model), make_links(links)
-        self._check(self.lib.hx_horizons(
+        self._invoke(self.lib.hx_horizons, 
             self._ctx, C.byref(m), n, n_edges, _ptr(succ_row_ptr, torch.int32), _ptr(succ_col_idx, torch.int32),
             _ptr(L_in, torch.int32, n), _ptr(L_out, torch.int32, n), T, _ptr(type_flops, torch.float32),
             _ptr(type_hbm_bw, torch.float32, T), C.byref(lk), n_wf, _ptr(wf_ptr, torch.int32),
             _ptr(node_cost, torch.float32, n), _ptr(rem, torch.float32, n), _ptr(tail, torch.float32, n),
-            _ptr(level, torch.int32, n), _ptr(horizon, torch.float32, n_wf), _stream(stream)))
+            _ptr(level, torch.int32, n), _ptr(horizon, torch.float32, n_wf), _stream(stream))
 
     def hx_dag_reserve(self, max_nodes, max_edges, max_wf, max_depth, stream=None):
-        self._check(self.lib.hx_dag_reserve(self._ctx, int(max_nodes), int(max_edges), int(max_wf),
-                                            int(max_depth), _stream(stream)))
+        self._invoke(self.lib.hx_dag_reserve, self._ctx, int(max_nodes), int(max_edges), int(max_wf),
+                                            int(max_depth), _stream(stream))
 
     def hx_dag_append(self, parent_row_ptr, parent_col_idx, new_cost, new_wf, stream=None):
         torch = _torch()
         n_new, n_e = int(new_cost.numel()), int(parent_col_idx.numel())
-        self._check(self.lib.hx_dag_append(self._ctx, n_new, n_e, _ptr(parent_row_ptr, torch.int32, n_new + 1),
+        self._invoke(self.lib.hx_dag_append, self._ctx, n_new, n_e, _ptr(parent_row_ptr, torch.int32, n_new + 1),
                                            _ptr(parent_col_idx, torch.int32), _ptr(new_cost, torch.float32),
-                                           _ptr(new_wf, torch.int32, n_new), _stream(stream)))
+                                           _ptr(new_wf, torch.int32, n_new), _stream(stream))
 
     def hx_dag_set_cost(self, node_ids, cost, stream=None):
         torch = _torch()
         n = int(node_ids.numel())
-        self._check(self.lib.hx_dag_set_cost(self._ctx, n, _ptr(node_ids, torch.int32), _ptr(cost, torch.float32, n), _stream(stream)))
+        self._invoke(self.lib.hx_dag_set_cost, self._ctx, n, _ptr(node_ids, torch.int32), _ptr(cost, torch.float32, n), _stream(stream))
 
     def hx_dag_view(self, n_wf: int):
         """(rem, tail, level, horizon) of the context's graph as borrowed RawArray
@@ -264,12 +295,12 @@ class Context:
         Cn, P, D = cs.n, pt.n, dt.n
         n_nodes = 0 if tail is None else int(tail.numel())
         n_wf = 0 if horizon is None else int(horizon.numel())
-        self._check(self.lib.hx_score_placements(
+        self._invoke(self.lib.hx_score_placements, 
             self._ctx, C.byref(m), C.byref(cs), C.byref(pt), C.byref(dt), C.byref(lk),
             _ptr(tail, torch.float32), _ptr(horizon, torch.float32), n_nodes, n_wf,
             _ptr(cost, torch.float32, Cn * P * D), _ptr(feas, torch.uint8, Cn * D),
             _ptr(best_p, torch.int32, Cn), _ptr(best_d, torch.int32, Cn), _ptr(best_cost, torch.float32, Cn),
-            _ptr(ratio, torch.float32, Cn), _stream(stream)))
+            _ptr(ratio, torch.float32, Cn), _stream(stream))
 
     VALIDATE_FIELDS = ("L_in", "L_out", "node", "wf", "elapsed", "prefill_rate", "prefill_backlog", "prefill_type",
                        "decode_rate", "decode_state", "decode_type", "link")
@@ -294,18 +325,18 @@ class Context:
         cs = make_calls(calls) if calls is not None else None
         n_nodes = 0 if tail is None else int(tail.numel())
         n_wf = 0 if horizon is None else int(horizon.numel())
-        self._check(self.lib.hx_select(
+        self._invoke(self.lib.hx_select, 
             self._ctx, int(C_), int(P), int(D), _ptr(cost, torch.float32, C_ * P * D),
             C.byref(cs) if cs is not None else None, _ptr(tail, torch.float32), _ptr(horizon, torch.float32),
             n_nodes, n_wf, _ptr(best_p, torch.int32, C_), _ptr(best_d, torch.int32, C_),
-            _ptr(best_cost, torch.float32, C_), _ptr(ratio, torch.float32, C_), _stream(stream)))
+            _ptr(best_cost, torch.float32, C_), _ptr(ratio, torch.float32, C_), _stream(stream))
 
     def hx_urgency(self, calls, best_cost, tail, horizon, ratio, stream=None):
         torch = _torch()
         cs = make_calls(calls)
-        self._check(self.lib.hx_urgency(self._ctx, C.byref(cs), _ptr(best_cost, torch.float32, cs.n),
+        self._invoke(self.lib.hx_urgency, self._ctx, C.byref(cs), _ptr(best_cost, torch.float32, cs.n),
                                         _ptr(tail, torch.float32), _ptr(horizon, torch.float32),
-                                        int(tail.numel()), int(horizon.numel()), _ptr(ratio, torch.float32, cs.n), _stream(stream)))
+                                        int(tail.numel()), int(horizon.numel()), _ptr(ratio, torch.float32, cs.n), _stream(stream))
 
     def hx_commit(self, calls, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
                   drain_prefill=None, drain_decode_q=None, release_tok=None,
@@ -314,17 +345,17 @@ class Context:
         cs = make_calls(calls)
         P, D = int(backlog_tok.numel()), int(used_tok.numel())
         i32 = torch.int32
-        self._check(self.lib.hx_commit(
+        self._invoke(self.lib.hx_commit, 
             self._ctx, C.byref(cs), _ptr(best_p, i32, cs.n), _ptr(best_d, i32, cs.n),
             P, _ptr(backlog_tok, i32), D, _ptr(used_tok, i32), _ptr(batch, i32, D), _ptr(qd_tok, i32, D),
             _ptr(drain_prefill, i32, P), _ptr(drain_decode_q, i32, D), _ptr(release_tok, i32, D),
-            int(tokens_per_seq), int(max_batch), _stream(stream)))
+            int(tokens_per_seq), int(max_batch), _stream(stream))
 
 
     def hx_rank(self, ratio, rank, stream=None):
         torch = _torch()
         n = int(ratio.numel())
-        self._check(self.lib.hx_rank(self._ctx, n, _ptr(ratio, torch.float32), _ptr(rank, torch.int32, n), _stream(stream)))
+        self._invoke(self.lib.hx_rank, self._ctx, n, _ptr(ratio, torch.float32), _ptr(rank, torch.int32, n), _stream(stream))
 
     def hx_plan_greedy(self, model, calls, prefill, decode, links, tail, horizon,
                        best_p, best_d, best_cost, ratio, rank,
@@ -333,14 +364,14 @@ class Context:
         torch = _torch()
         m, cs, pt, dt, lk = make_model(model), make_calls(calls), make_prefill(prefill), make_decode(decode), make_links(links)
         i32 = torch.int32
-        self._check(self.lib.hx_plan_greedy(
+        self._invoke(self.lib.hx_plan_greedy, 
             self._ctx, C.byref(m), C.byref(cs), C.byref(pt), C.byref(dt), C.byref(lk),
             _ptr(tail, torch.float32), _ptr(horizon, torch.float32), int(tail.numel()), int(horizon.numel()),
             int(tokens_per_seq), int(max_batch),
             _ptr(best_p, i32, cs.n), _ptr(best_d, i32, cs.n), _ptr(best_cost, torch.float32, cs.n),
             _ptr(ratio, torch.float32, cs.n), _ptr(rank, i32, cs.n),
             _ptr(backlog_tok_out, i32, pt.n), _ptr(used_tok_out, i32, dt.n), _ptr(batch_out, i32, dt.n),
-            _ptr(qd_tok_out, i32, dt.n), _stream(stream)))
+            _ptr(qd_tok_out, i32, dt.n), _stream(stream))
 
 
     def hx_decode_score(self, model, queue, lock, decode, intervals, best_d, best_start, best_cost,
@@ -351,12 +382,12 @@ class Context:
         n_nodes = 0 if tail is None else int(tail.numel())
         n_wf = 0 if horizon is None else int(horizon.numel())
         f32, i32 = torch.float32, torch.int32
-        self._check(self.lib.hx_decode_score(
+        self._invoke(self.lib.hx_decode_score, 
             self._ctx, C.byref(m), C.byref(cs), _ptr(lock, i32, cs.n), C.byref(dt), C.byref(iv),
             _ptr(tail, f32), _ptr(horizon, f32), n_nodes, n_wf,
             _ptr(start, f32, cs.n * dt.n), _ptr(cost, f32, cs.n * dt.n),
             _ptr(best_d, i32, cs.n), _ptr(best_start, f32, cs.n), _ptr(best_cost, f32, cs.n), _ptr(ratio, f32, cs.n),
-            _stream(stream)))
+            _stream(stream))
 
     def hx_decode_plan_greedy(self, model, queue, lock, decode, intervals, tail, horizon,
                               best_d, best_start, best_cost, ratio, rank, stream=None):
@@ -364,11 +395,11 @@ class Context:
         m, cs, dt = make_model(model), make_calls(queue), make_decode(decode)
         iv = make_intervals(intervals, dt.n)
         f32, i32 = torch.float32, torch.int32
-        self._check(self.lib.hx_decode_plan_greedy(
+        self._invoke(self.lib.hx_decode_plan_greedy, 
             self._ctx, C.byref(m), C.byref(cs), _ptr(lock, i32, cs.n), C.byref(dt), C.byref(iv),
             _ptr(tail, f32), _ptr(horizon, f32), int(tail.numel()), int(horizon.numel()),
             _ptr(best_d, i32, cs.n), _ptr(best_start, f32, cs.n), _ptr(best_cost, f32, cs.n), _ptr(ratio, f32, cs.n),
-            _ptr(rank, i32, cs.n), _stream(stream)))
+            _ptr(rank, i32, cs.n), _stream(stream))
 
 
 def hx_commit_static(calls, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,

@@ -58,6 +58,7 @@ struct hx_ctx {
     HxPrepTables *d_prep = nullptr;
     int32_t *d_flags = nullptr;        // sweep "changed" flags, [HX_MAX_SWEEP_FLAGS]
     unsigned long long *d_acc = nullptr;   // commit accumulators, [3 * HX_MAX_INSTANCES]
+    int32_t *d_ticket = nullptr;           // commit: workgroups that have delivered their sums; 0 between launches
     int32_t *d_dpart = nullptr;            // decode-stage free list and per-group partial results, dpart_cap words
     size_t dpart_cap = 0;
     unsigned long long *d_rkey = nullptr;  // sorted tiles of ordering keys, [rkey_cap]

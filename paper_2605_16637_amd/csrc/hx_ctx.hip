@@ -26,6 +26,7 @@ struct CommitArgs {
     int tokens_per_seq, max_batch;
     unsigned long long *acc;    // [P] backlog, [D] used, [D] qd additions of this round
     int32_t *status;
+    int32_t *ticket;            // workgroups of the adding kernel that have delivered their sums (0 between launches); NULL: a drain launch follows
 };
 
 __global__ __launch_bounds__(256) void hx_commit_clear_kernel(CommitArgs a)
@@ -64,6 +65,14 @@ __device__ __forceinline__ void hx_add_by_key(unsigned long long *acc, bool vali
     }
 }
 
+__device__ __forceinline__ int hx_add_sat_drain(int cur, unsigned long long add, int drain, int32_t *status)
+{
+    unsigned long long total = (unsigned long long)(cur < 0 ? 0 : cur) + add;
+    if (total > 2147483647ull) { hx_raise(status, HX_ERR_OVERFLOW); total = 2147483647ull; }
+    long long left = (long long)total - (long long)drain;
+    return left < 0 ? 0 : (left > 2147483647LL ? 2147483647 : (int)left);
+}
+
 // The state update of Algorithm 1 for all calls of the round at once: integer
 // additions commute, so the result does not depend on call order.  Every wave
 // first combines its calls per instance, every block sums into an LDS copy of
@@ -89,16 +98,35 @@ __global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
     }
     if (bad) hx_raise(a.status, HX_ERR_INDEX);
     __syncthreads();
+    unsigned long long seen = 0ull;
     for (int i = threadIdx.x; i < n_acc; i += blockDim.x)
-        if (s_acc[i]) atomicAdd(&a.acc[i], s_acc[i]);
-}
-
-__device__ __forceinline__ int hx_add_sat_drain(int cur, unsigned long long add, int drain, int32_t *status)
-{
-    unsigned long long total = (unsigned long long)(cur < 0 ? 0 : cur) + add;
-    if (total > 2147483647ull) { hx_raise(status, HX_ERR_OVERFLOW); total = 2147483647ull; }
-    long long left = (long long)total - (long long)drain;
-    return left < 0 ? 0 : (left > 2147483647LL ? 2147483647 : (int)left);
+        if (s_acc[i]) seen ^= atomicAdd(&a.acc[i], s_acc[i]);
+    if (!a.ticket) return;
+    // The workgroup that delivers last applies the drains: no second launch.  Everything the workgroups
+    // exchange goes through device-scope atomics (the sums above, the ticket, and the accumulators read back with
+    // an exchange that also leaves them at zero), so no cache has to be written back in between.  A workgroup
+    // takes its ticket only after every one of its additions has returned its old value, i.e. has been
+    // performed: the empty statement below needs those values, and the barrier follows it.
+    asm volatile("" ::"v"((unsigned)(seen ^ (seen >> 32))) : "memory");
+    __shared__ int s_last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int t = atomicAdd(a.ticket, 1);
+        s_last = t == (int)gridDim.x - 1;
+        if (s_last) __hip_atomic_store(a.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    for (int i = threadIdx.x; i < (a.P > a.D ? a.P : a.D); i += blockDim.x) {
+        if (i < a.P) a.backlog[i] = hx_add_sat_drain(a.backlog[i], atomicExch(&a.acc[i], 0ull), a.drain_p ? a.drain_p[i] : 0, a.status);
+        if (i < a.D) {
+            a.qd[i] = hx_add_sat_drain(a.qd[i], atomicExch(&a.acc[a.P + a.D + i], 0ull), a.drain_q ? a.drain_q[i] : 0, a.status);
+            const int used = hx_add_sat_drain(a.used[i], atomicExch(&a.acc[a.P + i], 0ull), a.release ? a.release[i] : 0, a.status);
+            a.used[i] = used;
+            long long b = ((long long)used + a.tokens_per_seq - 1) / a.tokens_per_seq;
+            a.batch[i] = (int)(b > a.max_batch ? a.max_batch : b);
+        }
+    }
 }
 
 // Both steps in one workgroup, for rounds small enough that one compute unit adds them up as fast as a launch
@@ -286,6 +314,7 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
     if (e == hipSuccess) { what = "hipHostMalloc(status)"; e = hipHostMalloc((void **)&ctx->h_status, sizeof(int32_t), hipHostMallocDefault); }
     if (e == hipSuccess) { what = "hipMalloc(tables)"; e = hipMalloc((void **)&ctx->d_prep, sizeof(HxPrepTables)); }
     if (e == hipSuccess) { what = "hipMalloc(flags)"; e = hipMalloc((void **)&ctx->d_flags, HX_MAX_SWEEP_FLAGS * sizeof(int32_t)); }
+    if (e == hipSuccess) { what = "hipMalloc(ticket)"; e = hipMalloc((void **)&ctx->d_ticket, sizeof(int32_t)); }
     if (e == hipSuccess) { what = "hipMalloc(accumulators)"; e = hipMalloc((void **)&ctx->d_acc, 3 * HX_MAX_INSTANCES * sizeof(unsigned long long)); }
     if (e == hipSuccess && device < HX_MAX_DEVICES) {     // set-up for hx_commit_static on this device
         what = "hipGetSymbolAddress(scratch)";
@@ -299,6 +328,7 @@ extern "C" int hx_ctx_create(hx_ctx **out, int device)
         z.P = HX_MAX_INSTANCES; z.D = HX_MAX_INSTANCES; z.acc = ctx->d_acc;
         hx_commit_clear_kernel<<<(3 * HX_MAX_INSTANCES + 255) / 256, 256, 0, nullptr>>>(z);
         hx_clear_status_kernel<<<1, 1, 0, nullptr>>>(ctx->d_status);
+        hx_clear_status_kernel<<<1, 1, 0, nullptr>>>(ctx->d_ticket);
         e = hipGetLastError();
     }
     if (e == hipSuccess) { what = "hipStreamSynchronize"; e = hipStreamSynchronize(nullptr); }
@@ -319,6 +349,7 @@ extern "C" int hx_ctx_destroy(hx_ctx *ctx)
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     if (ctx->d_prep) (void)hipFree(ctx->d_prep);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
+    if (ctx->d_ticket) (void)hipFree(ctx->d_ticket);
     if (ctx->d_acc) (void)hipFree(ctx->d_acc);
     if (ctx->d_dpart) (void)hipFree(ctx->d_dpart);
     if (ctx->d_dtl) (void)hipFree(ctx->d_dtl);
@@ -383,10 +414,9 @@ extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best
     }
     int grid = (C + 255) / 256;
     grid = grid > ctx->num_cu ? ctx->num_cu : grid;
+    a.ticket = ctx->d_ticket;                  // the workgroup that finishes last applies the drains
     hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a);
-    const int n_inst = P > D ? P : D;
-    hx_commit_drain_kernel<<<(n_inst + 255) / 256, 256, 0, stream>>>(a);
-    return hx_check_launch(ctx, "hx_commit kernels");
+    return hx_check_launch(ctx, "hx_commit_add_kernel");
 }
 
 extern "C" int hx_commit_static(const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,

@@ -329,6 +329,20 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
     float *dbuf = s_wave + (size_t)wave * lay.wave_floats();    // the call's decode time per entry
     float *xbuf = dbuf + lay.Dp;                                // transfer per class pair
 
+    // What the wave's first call says of itself is asked for before the pool's tables are derived, and every
+    // later call's while the call before it is searched: the loads are wave-uniform (scalar), and none of the
+    // kernel's chains of dependent memory round trips waits for them on its own.
+    const int gw = blockIdx.x * waves_per_block + wave;
+    const int nw = gridDim.x * waves_per_block;
+    const bool want_ratio = a.ratio != nullptr;
+    int c = gw;
+    int L = 0, O = 0, nd = 0, w = 0;
+    float el = 0.0f;
+    if (c < a.C) {
+        L = a.L_in[c]; O = a.L_out[c];
+        if (want_ratio) { nd = a.node[c]; w = a.wf[c]; el = a.elapsed[c]; }
+    }
+
     // the per-round tables of the pool, derived here; the class counts of the derivation borrow the
     // waves' buffers, which nothing has used yet
     const PrepLds out{s_wait, s_c1, s_c2, s_kB, s_free, s_orig, s_dtype, s_pw, s_pinvF, s_pinvB, s_ptype,
@@ -342,18 +356,29 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
     const HxPoolLds pool{s_wait, s_c1, s_c2, s_kB, s_free, s_orig, s_dtype, s_pw, s_pinvF, s_pinvB, s_ptype,
                          s_invbw, s_lat, Dp, a.P, lay.Pp};
 
-    const int gw = blockIdx.x * waves_per_block + wave;
-    const int nw = gridDim.x * waves_per_block;
-    for (int c = gw; c < a.C; c += nw) {
-        const HxBest b = hx_search_call<KP>(a.m, pool, seg, dbuf, xbuf, a.L_in[c], a.L_out[c], lane);
-        const float bestv = b.cost;
-        const int pstar = b.p, dstar = b.d;
-        if (lane == 0) {
-            a.best_p[c] = pstar;
-            a.best_d[c] = dstar;
-            a.best_cost[c] = bestv;
-            if (a.ratio) hx_ratio(a, c, bestv);
+    while (c < a.C) {
+        // the downstream tail and the horizon of the call's workflow travel while the call is searched
+        const bool ok = !want_ratio || (nd >= 0 && nd < a.n_nodes && w >= 0 && w < a.n_wf);
+        float tl = 0.0f, hz = 1.0f;
+        if (want_ratio && ok) { tl = a.tail[nd]; hz = a.horizon[w]; }
+        const int cn = c + nw;
+        int Ln = 0, On = 0, ndn = 0, wn = 0;
+        float eln = 0.0f;
+        if (cn < a.C) {
+            Ln = a.L_in[cn]; On = a.L_out[cn];
+            if (want_ratio) { ndn = a.node[cn]; wn = a.wf[cn]; eln = a.elapsed[cn]; }
         }
+        const HxBest b = hx_search_call<KP>(a.m, pool, seg, dbuf, xbuf, L, O, lane);
+        if (lane == 0) {
+            a.best_p[c] = b.p;
+            a.best_d[c] = b.d;
+            a.best_cost[c] = b.cost;
+            if (want_ratio) {
+                if (!ok) hx_raise(a.status, HX_ERR_INDEX);
+                hx_store_bits(a.ratio, c, hx_ratio_bits(el, b.cost, tl, hz, ok));      // Eq. (2), as hx_projected_ratio forms it
+            }
+        }
+        c = cn; L = Ln; O = On; nd = ndn; w = wn; el = eln;
     }
 }
 

@@ -153,3 +153,54 @@ def test_round_replayed_from_a_hip_graph(ctx):
         # eager work of the program between replays
         one_round()
         torch.cuda.synchronize()
+
+
+def test_prepared_calls_equal_the_calls_they_were_prepared_from(ctx):
+    # binding.Context.prepare: the same library calls with their arguments marshalled once; several rounds in a
+    # row (the second sees the state the first committed), against the same rounds made call by call
+    import torch
+    rnd = synth.make_round("tiny", 7)
+    d = rnd.dag
+    calls, pre, dec, links = dev_tables(rnd)
+    tF, tB = dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"])
+    L_in, L_out = dev(d.L_in), dev(d.L_out)
+    rp, col, wp = dev(d.succ_row_ptr), dev(d.succ_col), dev(d.wf_ptr)
+    f32 = dict(dtype=torch.float32, device="cuda:0"); i32 = dict(dtype=torch.int32, device="cuda:0")
+    cost = torch.empty(d.n_nodes, **f32); rem = torch.empty(d.n_nodes, **f32); tail = torch.empty(d.n_nodes, **f32)
+    level = torch.empty(d.n_nodes, **i32); hor = torch.empty(d.n_wf, **f32)
+    n = rnd.calls["n"]
+    bp = torch.empty(n, **i32); bd = torch.empty(n, **i32); bc = torch.empty(n, **f32); ratio = torch.empty(n, **f32)
+    state = (pre["backlog_tok"], dec["used_tok"], dec["batch"], dec["qd_tok"])
+    state0 = [t.clone() for t in state]
+    drain = torch.full((rnd.pre["n"],), 3000, **i32), torch.full((rnd.dec["n"],), 500, **i32), torch.full((rnd.dec["n"],), 4000, **i32)
+
+    def one_round():
+        ctx.hx_horizons(rnd.model, rp, col, L_in, L_out, tF, tB, links, wp, cost, rem, tail, level, hor)
+        ctx.hx_score_placements(rnd.model, calls, pre, dec, links, tail=tail, horizon=hor,
+                                best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+        ctx.hx_commit(calls, bp, bd, *state, *drain)
+
+    def reset():
+        for t, s0 in zip(state, state0):
+            t.copy_(s0)
+        for t in (cost, rem, tail, hor, bc, ratio):
+            t.fill_(-1.0)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.cpu().numpy().copy() for t in (cost, rem, tail, level, hor, bp, bd, bc, ratio, *state)]
+
+    reset(); one_round(); one_round(); one_round()
+    want = snapshot()
+    ctx.hx_stream_status()
+    reset()
+    torch.cuda.synchronize()
+    before = snapshot()
+    prepared = ctx.prepare(one_round)
+    assert prepared.n_calls == 3
+    for a, b in zip(snapshot(), before):
+        assert np.array_equal(a, b)                      # preparing calls nothing
+    prepared(); prepared(); prepared()
+    for a, b in zip(snapshot(), want):
+        assert np.array_equal(a, b)
+    ctx.hx_stream_status()
