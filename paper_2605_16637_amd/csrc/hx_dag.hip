@@ -56,21 +56,26 @@ __device__ __forceinline__ void hx_cost_tables_fill(CostTables &t, const NodeCos
     }
 }
 
-// min over class pairs of prefill + transfer + decode on an idle pool
-__device__ __forceinline__ float hx_node_cost_eval(const HxModelF &m, const CostTables &t, int L, int O)
+// min over class pairs of prefill + transfer + decode on an idle pool.  T: classes in use (wave-uniform); the
+// pairs beyond them would lose anyway (infinite latency in the padded tables) and are not evaluated.
+__device__ __forceinline__ float hx_node_cost_eval(const HxModelF &m, const CostTables &t, int T, int L, int O)
 {
     const HxCallF cf = hx_call_terms(m, L, O);
     float dec[kT];
 #pragma unroll
-    for (int td = 0; td < kT; ++td) dec[td] = hx_decode_time(cf, t.c1[td], t.c2[td], t.kB[td]);
+    for (int td = 0; td < kT; ++td) dec[td] = td < T ? hx_decode_time(cf, t.c1[td], t.c2[td], t.kB[td]) : INFINITY;
     float best = INFINITY;
 #pragma unroll
     for (int tp = 0; tp < kT; ++tp) {
-        const float done = hx_prefill_done(cf, 0.0f, t.invF[tp], t.invB[tp]);
+        if (tp < T) {
+            const float done = hx_prefill_done(cf, 0.0f, t.invF[tp], t.invB[tp]);
 #pragma unroll
-        for (int td = 0; td < kT; ++td) {
-            const float x = hx_transfer(cf, t.invbw[tp * kT + td], t.lat[tp * kT + td]);
-            best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
+            for (int td = 0; td < kT; ++td) {
+                if (td < T) {
+                    const float x = hx_transfer(cf, t.invbw[tp * kT + td], t.lat[tp * kT + td]);
+                    best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
+                }
+            }
         }
     }
     return best;
@@ -89,7 +94,7 @@ __global__ __launch_bounds__(256) void hx_node_cost_kernel(NodeCostArgs a)
         const int Lv = L, Ov = O;
         const int vn = v + gridDim.x * blockDim.x;
         if (vn < a.n) { L = a.L_in[vn]; O = a.L_out[vn]; }
-        a.cost[v] = hx_node_cost_eval(a.m, s_tab, Lv, Ov);
+        a.cost[v] = hx_node_cost_eval(a.m, s_tab, a.T, Lv, Ov);
     }
 }
 
@@ -271,7 +276,7 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
                 for (int k = 0; k < CP_NPT; ++k) {
                     const int i = k * CP_THREADS + tid;
                     if constexpr (COST) if (i < nn) {
-                        c[k] = hx_node_cost_eval(nc->m, *tab, len_in[k], len_out[k]);
+                        c[k] = hx_node_cost_eval(nc->m, *tab, nc->T, len_in[k], len_out[k]);
                         nc->cost[n0 + i] = c[k];
                     }
                     if (i < nn) *(int2 *)&s_node[i + 1] = make_int2(__float_as_int(c[k]), deg[k] < 0);
@@ -331,7 +336,7 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
                     lv = max(lv, a.level[u] + 1);
                 }
                 float cv;
-                if constexpr (COST) { cv = hx_node_cost_eval(nc->m, *tab, nc->L_in[v], nc->L_out[v]); nc->cost[v] = cv; }
+                if constexpr (COST) { cv = hx_node_cost_eval(nc->m, *tab, nc->T, nc->L_in[v], nc->L_out[v]); nc->cost[v] = cv; }
                 else cv = a.cost[v];
                 float rv = cv + tl;
                 a.rem[v] = rv; a.tail[v] = tl; a.level[v] = lv;
