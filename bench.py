@@ -40,20 +40,22 @@ DECODE_OPS_BISECT_STEP, DECODE_OPS_STRETCH, DECODE_OPS_PAIR, DECODE_OPS_ENTRY = 
 HBM_PEAK_GBS = 8000.0
 
 
-def source_sha():
-    """sha256 over the library's kernel sources: a counter summary under profiles/ names the sources it was taken on."""
+def source_sha(files):
+    """sha256 over the named kernel sources: a counter summary under profiles/ names the sources it was taken on."""
     import hashlib
     h = hashlib.sha256()
-    d = os.path.join(ROOT, "paper_2605_16637_amd", "csrc")
-    for f in sorted(os.listdir(d)):
-        if f.endswith((".hip", ".hpp")) and f != "hx_calib.hip":
-            h.update(open(os.path.join(d, f), "rb").read())
+    for f in files:
+        h.update(open(os.path.join(ROOT, "paper_2605_16637_amd", "csrc", f), "rb").read())
     return h.hexdigest()
 
 
-def profiled_traffic(summary, key="traffic_bytes_per_launch"):
+FUSED_SOURCES = ("hx_score.hip", "hx_search.hpp", "hx_terms.hpp", "hx_common.hpp")
+CP_SOURCES = ("hx_dag.hip", "hx_terms.hpp", "hx_common.hpp")
+
+
+def profiled_traffic(summary, sources, key="traffic_bytes_per_launch"):
     """HBM bytes per launch as the rocprofv3 counter runs summarised in profiles/<summary> found them, or None when
-    there is no such line or the kernel sources have changed since (the summary records their sha256)."""
+    there is no such line or the kernel's sources have changed since (the summary records their sha256)."""
     path = os.path.join(ROOT, "profiles", summary)
     if not os.path.exists(path):
         return None
@@ -62,7 +64,7 @@ def profiled_traffic(summary, key="traffic_bytes_per_launch"):
         if ":" in line:
             k, v = line.split(":", 1)
             vals[k.strip()] = v.strip()
-    if vals.get("source_sha256") != source_sha() or key not in vals:
+    if vals.get("source_sha256") != source_sha(sources) or key not in vals:
         return None
     return float(vals[key].split()[0])
 
@@ -637,7 +639,7 @@ def main():
                      "achieved": achieved, "peak": ALU_PEAK_TOPS,
                      "unit": "T lane-ops/s on the SIMDs' main fp32 pipe (v_max_f32, v_min3_f32: 1.5 per candidate; the v_add_f32 pairs with them on the second pipe)",
                      "frac": achieved / ALU_PEAK_TOPS,
-                     "traffic": profiled_traffic("fused_search_large_sweep.txt") if args.workload == "large" else None,
+                     "traffic": profiled_traffic("fused_search_large_sweep.txt", FUSED_SOURCES) if args.workload == "large" else None,
                      "main_pipe_ops_per_candidate": MAIN_PIPE_OPS_PER_CANDIDATE, "ops_per_candidate": OPS_PER_CANDIDATE,
                      "launch_ms": score_s * 1e3, "candidates_per_s_kernel": n_cand / score_s,
                      "frac_of_fp32_vector_peak_157.3_tflops": n_cand * OPS_PER_CANDIDATE / score_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS},
@@ -694,7 +696,7 @@ def main():
         out["critical_path"] = {"workload": "critical-path stress: %d workflows, %d nodes, %d edges" % (d.n_wf, d.n_nodes, d.n_edges),
                                 "kernel": "hx_cp_local_kernel", "bound": "hbm", "launch_ms": cp_ms,
                                 "algorithmic_bytes": cp_bytes, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                "frac": gbs / HBM_PEAK_GBS, "traffic": profiled_traffic("cp_local_critical_path_stress.txt"), "rotating_copies": n_copies,
+                                "frac": gbs / HBM_PEAK_GBS, "traffic": profiled_traffic("cp_local_critical_path_stress.txt", CP_SOURCES), "rotating_copies": n_copies,
                                 "plain_copy_same_bytes_ms": copy_ms}
         del sets
         # the same kernel on eight copies of the graph side by side (16 M nodes, 435 MB per pass, more than the
