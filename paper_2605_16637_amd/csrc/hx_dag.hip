@@ -196,7 +196,8 @@ __device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, 
 // lane each, of a graph with fewer than CP_DEG edges in all).
 // COST: the node costs are not read but worked out here from the nodes' lengths (and written out as
 // well), `nc` and `tab` being the arguments and the class tables of the standalone cost.
-template <int NMAX, bool COST>
+// STREAM: rem, level and tail leave with stores that do not claim cache lines (see the store phase).
+template <int NMAX, bool COST, bool STREAM>
 __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNode *s_node, int &s_any,
                                                  const NodeCostArgs *nc, const CostTables *tab)
 {
@@ -316,9 +317,19 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
                 const int i = k * CP_THREADS + tid;
                 if (i < nn) {
                     const int4 me = *(const int4 *)&s_node[i + 1];
-                    a.rem[n0 + i] = __int_as_float(me.x);
-                    a.level[n0 + i] = me.y;
-                    a.tail[n0 + i] = __int_as_float(me.z);
+                    if constexpr (STREAM) {
+                        // a graph far larger than the caches: stores that do not claim cache lines (measured on the
+                        // 2 M-node stress graph: 17.2 -> 14.4 us per launch; the same hint on the loads of a stage
+                        // costs 2-5 us).  A round's graph of 10^4 - 10^5 nodes is read again by the next kernel of
+                        // the round and is better left in the caches.
+                        __builtin_nontemporal_store(__int_as_float(me.x), &a.rem[n0 + i]);
+                        __builtin_nontemporal_store(me.y, &a.level[n0 + i]);
+                        __builtin_nontemporal_store(__int_as_float(me.z), &a.tail[n0 + i]);
+                    } else {
+                        a.rem[n0 + i] = __int_as_float(me.x);
+                        a.level[n0 + i] = me.y;
+                        a.tail[n0 + i] = __int_as_float(me.z);
+                    }
                 }
             }
             __syncthreads();                            // the next run stages over these records
@@ -351,12 +362,13 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
 }
 
 // seven blocks of 22.4 KB per compute unit, 72 vector registers
+template <bool STREAM>
 __global__ __launch_bounds__(CP_THREADS) __attribute__((amdgpu_waves_per_eu(7, 8)))
 void hx_cp_local_kernel(CpArgs a, int wpb)
 {
     __shared__ CpNode s_node[CP_NMAX + 1];
     __shared__ int s_any;                     // == first workflow of the run + 1: a node of this run was left to the walk
-    hx_cp_local_body<CP_NMAX, false>(a, wpb, s_node, s_any, nullptr, nullptr);
+    hx_cp_local_body<CP_NMAX, false, STREAM>(a, wpb, s_node, s_any, nullptr, nullptr);
 }
 
 // The same pass with the standalone node cost worked out while staging instead of being read:
@@ -372,7 +384,7 @@ void hx_cp_cost_kernel(CpArgs a, NodeCostArgs nc, int wpb)
     __shared__ CostTables s_tab;
     hx_cost_tables_fill(s_tab, nc, threadIdx.x);
     __syncthreads();
-    hx_cp_local_body<CP_NMAX_COST, true>(a, wpb, s_node, s_any, &nc, &s_tab);
+    hx_cp_local_body<CP_NMAX_COST, true, false>(a, wpb, s_node, s_any, &nc, &s_tab);
 }
 
 // ---- critical path, level-synchronous sweeps ------------------------------------------
@@ -705,7 +717,9 @@ extern "C" int hx_critical_path(hx_ctx *ctx, int32_t n_nodes, int32_t n_edges,
         long long fit = n_nodes > 0 ? (long long)(CP_NMAX * 41 / 50) * n_wf / n_nodes : CP_WPB;
         const int wpb = (int)(fit < 1 ? 1 : (fit > CP_WPB ? CP_WPB : fit));
         const int grid = (n_wf + wpb - 1) / wpb;
-        hx_cp_local_kernel<<<grid, CP_THREADS, 0, stream>>>(a, wpb);
+        // results of 12 MB and more are streamed out past the caches
+        if (n_nodes >= (1 << 20)) hx_cp_local_kernel<true><<<grid, CP_THREADS, 0, stream>>>(a, wpb);
+        else hx_cp_local_kernel<false><<<grid, CP_THREADS, 0, stream>>>(a, wpb);
         return hx_check_launch(ctx, "hx_cp_local_kernel");
     }
     const int nmax = n_nodes > max_sweeps + 1 ? n_nodes : max_sweeps + 1;
