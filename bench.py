@@ -186,10 +186,10 @@ def time_launches(torch, fn, reps, warmup=5):
 def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=32768, P=512, D=512):
     """Rounds of a live system, the streaming configuration at its stated length: reveal (node cost + append to the
     graph the context keeps), score the ready calls with their projected ratio, commit; pool and graph state carried
-    from round to round.  Every batch is resident in HBM before its clock starts.  Two ways of enqueueing a round are
+    from round to round.  Every batch is resident in HBM before its clock starts.  Three ways of enqueueing a round are
     timed on alternating rounds of the same run (they give the same results, so the state evolves as one sequence):
-    everything on one stream, and the reveal on a second stream beside the search (which needs no horizon), the
-    urgency fold joining the two before the commit."""
+    its four library calls on one stream; the reveal on a second stream beside the search (which needs no horizon),
+    the urgency fold joining the two before the commit; and the whole round as one library call (hx_round)."""
     rng = np.random.default_rng(seed)
     gen = synth.StreamGen(seed, n_live)
     L0, O0 = synth.gen_lengths(rng, 50000)
@@ -239,13 +239,19 @@ def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=3276
         ctx.hx_commit(b["calls"], bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"],
                       b["drain_p"], b["drain_q"], b["release"])
 
-    modes = (("one stream", one_stream), ("reveal beside the search", two_streams))
+    def one_call(b):
+        ctx.hx_round(synth.MODEL, b["calls"], d_pre, d_dec, d_links, bp, bd, bc, ratio=ratio, n_wf=b["n_wf"],
+                     parent_row_ptr=b["prow"], parent_col_idx=b["pcol"], new_L_in=b["L_in"], new_L_out=b["L_out"],
+                     new_wf=b["wf"], new_cost=b["cost"], type_flops=tF, type_hbm_bw=tB,
+                     drain_prefill=b["drain_p"], drain_decode_q=b["drain_q"], release_tok=b["release"])
+
+    modes = (("one stream", one_stream), ("reveal beside the search", two_streams), ("one library call per round (hx_round)", one_call))
     lat = {name: [] for name, _ in modes}
     cand = {name: 0 for name, _ in modes}
     n_nodes = placed = 0
     for r in range(rounds + warm):
         b = next_batch()
-        name, fn = modes[r % 2]
+        name, fn = modes[r % len(modes)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         fn(b)
@@ -269,7 +275,7 @@ def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=3276
             "graph_nodes_at_the_end": n_nodes,
             "p50_us": res[best]["p50_us"], "p99_us": res[best]["p99_us"], "candidates_per_s": res[best]["candidates_per_s"],
             "order": best, "by_order": res, "placed_fraction": placed / max(1, sum(cand.values()) // (P * D)),
-            "launch": "eager, synchronised every round; the two orders on alternating rounds of one run"}
+            "launch": "eager, synchronised every round; the three orders on alternating rounds of one run"}
 
 
 def planner_leg(torch, ctx, synth, binding, seed):

@@ -348,6 +348,54 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
               void *stream);
 
 /*
+ * One scheduling invocation of Algorithm 1 in one call, for callers that pay for
+ * every crossing of this boundary: the calls revealed since the last
+ * invocation are priced and appended to the context's graph (horizons of the
+ * affected workflows refreshed: Sec. 4.1, 5.1), every ready call is projected
+ * onto its best feasible (prefill, decode) pair with its ratio (Sec. 5.3, 5.4,
+ * Eq. (2)), and the chosen pairs are committed to the pool snapshot (the
+ * simulated-state update, once for the round).  Exactly
+ *   hx_node_cost(new_L_in, new_L_out -> new_cost); hx_dag_append(new nodes);
+ *   hx_score_placements(fused outputs, tail and horizon = the context's graph);
+ *   hx_commit(calls, best_p, best_d, the snapshot's counters, the drains)
+ * enqueued on `stream` in that order, with the same argument meaning, results
+ * and error reporting as those calls (the first one that fails ends the call;
+ * what was enqueued before it stays enqueued).  n_new may be 0 (nothing is
+ * revealed), calls.n may be 0.  hx_dag_reserve must have been called.  The
+ * counters of `prefill` and `decode` that the commit updates are passed once
+ * more as writable pointers (they may be the same memory as the tables' own
+ * backlog_tok, used_tok, batch, qd_tok: the search has read them by then).
+ */
+typedef struct {
+    /* reveal */
+    int32_t n_new, n_new_edges;
+    const int32_t *parent_row_ptr;   /* device [n_new+1]                        */
+    const int32_t *parent_col_idx;   /* device [n_new_edges]                    */
+    const int32_t *new_L_in;         /* device [n_new]                          */
+    const int32_t *new_L_out;        /* device [n_new]                          */
+    const int32_t *new_wf;           /* device [n_new]                          */
+    float         *new_cost;         /* device [n_new] out: standalone costs    */
+    int32_t n_types;                 /* classes of type_flops / type_hbm_bw     */
+    const float   *type_flops;       /* device [n_types]                        */
+    const float   *type_hbm_bw;      /* device [n_types]                        */
+    int32_t n_wf;                    /* workflows numbered so far (horizon length used for the ratio) */
+    /* search */
+    hx_calls        calls;           /* node, wf, elapsed required when ratio != NULL */
+    hx_prefill_tab  prefill;
+    hx_decode_tab   decode;
+    hx_links        links;
+    int32_t *best_p, *best_d;        /* device [calls.n] out                    */
+    float   *best_cost, *ratio;      /* device [calls.n] out; ratio may be NULL */
+    /* commit */
+    int32_t *backlog_tok;            /* device [prefill.n], updated in place    */
+    int32_t *used_tok, *batch, *qd_tok;   /* device [decode.n], updated in place */
+    const int32_t *drain_prefill, *drain_decode_q, *release_tok;   /* device or NULL */
+    int32_t tokens_per_seq, max_batch;
+} hx_round_args;
+
+int hx_round(hx_ctx *ctx, const hx_model *model, const hx_round_args *round, void *stream);
+
+/*
  * hx_commit for callers that cannot allocate device memory: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Takes
  * no context and allocates nothing, now or earlier: the per-round accumulators

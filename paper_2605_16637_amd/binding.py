@@ -18,7 +18,7 @@ ERRORS = {-1: "HX_ERR_INVALID_ARG", -2: "HX_ERR_SHAPE", -3: "HX_ERR_NOT_DAG", -4
 
 EXPORTS = ("hx_ctx_create", "hx_ctx_destroy", "hx_last_error", "hx_stream_status", "hx_node_cost",
            "hx_critical_path", "hx_horizons", "hx_dag_reserve", "hx_dag_append", "hx_dag_set_cost", "hx_dag_view",
-           "hx_score_placements", "hx_validate_round", "hx_select", "hx_urgency", "hx_commit", "hx_commit_static", "hx_rank", "hx_plan_greedy",
+           "hx_score_placements", "hx_validate_round", "hx_select", "hx_urgency", "hx_commit", "hx_commit_static", "hx_round", "hx_rank", "hx_plan_greedy",
            "hx_decode_score", "hx_decode_plan_greedy")
 
 
@@ -56,6 +56,17 @@ class hx_links(C.Structure):
 class hx_intervals(C.Structure):
     _fields_ = [("stride", C.c_int32), ("count", C.c_void_p), ("start", C.c_void_p), ("end", C.c_void_p),
                 ("tok", C.c_void_p)]
+
+
+class hx_round_args(C.Structure):
+    _fields_ = [("n_new", C.c_int32), ("n_new_edges", C.c_int32), ("parent_row_ptr", C.c_void_p), ("parent_col_idx", C.c_void_p),
+                ("new_L_in", C.c_void_p), ("new_L_out", C.c_void_p), ("new_wf", C.c_void_p), ("new_cost", C.c_void_p),
+                ("n_types", C.c_int32), ("type_flops", C.c_void_p), ("type_hbm_bw", C.c_void_p), ("n_wf", C.c_int32),
+                ("calls", hx_calls), ("prefill", hx_prefill_tab), ("decode", hx_decode_tab), ("links", hx_links),
+                ("best_p", C.c_void_p), ("best_d", C.c_void_p), ("best_cost", C.c_void_p), ("ratio", C.c_void_p),
+                ("backlog_tok", C.c_void_p), ("used_tok", C.c_void_p), ("batch", C.c_void_p), ("qd_tok", C.c_void_p),
+                ("drain_prefill", C.c_void_p), ("drain_decode_q", C.c_void_p), ("release_tok", C.c_void_p),
+                ("tokens_per_seq", C.c_int32), ("max_batch", C.c_int32)]
 
 
 _lib = None
@@ -351,6 +362,33 @@ class Context:
             _ptr(drain_prefill, i32, P), _ptr(drain_decode_q, i32, D), _ptr(release_tok, i32, D),
             int(tokens_per_seq), int(max_batch), _stream(stream))
 
+
+    def hx_round(self, model, calls, prefill, decode, links, best_p, best_d, best_cost, ratio=None, n_wf=0,
+                 parent_row_ptr=None, parent_col_idx=None, new_L_in=None, new_L_out=None, new_wf=None, new_cost=None,
+                 type_flops=None, type_hbm_bw=None, drain_prefill=None, drain_decode_q=None, release_tok=None,
+                 tokens_per_seq=2048, max_batch=256, stream=None):
+        """One scheduling invocation in one library call: reveal (node cost + append), fused search with the
+        ratio, commit into the pool's own counters."""
+        torch = _torch()
+        i32, f32 = torch.int32, torch.float32
+        m = make_model(model)
+        r = hx_round_args()
+        n_new = 0 if new_L_in is None else int(new_L_in.numel())
+        r.n_new, r.n_new_edges = n_new, 0 if parent_col_idx is None else int(parent_col_idx.numel())
+        r.parent_row_ptr, r.parent_col_idx = _ptr(parent_row_ptr, i32, n_new + 1 if n_new else None), _ptr(parent_col_idx, i32)
+        r.new_L_in, r.new_L_out, r.new_wf = _ptr(new_L_in, i32), _ptr(new_L_out, i32, n_new), _ptr(new_wf, i32, n_new)
+        r.new_cost = _ptr(new_cost, f32, n_new)
+        r.n_types = 0 if type_flops is None else int(type_flops.numel())
+        r.type_flops, r.type_hbm_bw = _ptr(type_flops, f32), _ptr(type_hbm_bw, f32, r.n_types)
+        r.n_wf = int(n_wf)
+        r.calls, r.prefill, r.decode, r.links = make_calls(calls), make_prefill(prefill), make_decode(decode), make_links(links)
+        n = r.calls.n
+        r.best_p, r.best_d, r.best_cost, r.ratio = _ptr(best_p, i32, n), _ptr(best_d, i32, n), _ptr(best_cost, f32, n), _ptr(ratio, f32, n)
+        r.backlog_tok = _ptr(prefill["backlog_tok"], i32, r.prefill.n)
+        r.used_tok, r.batch, r.qd_tok = (_ptr(decode[k], i32, r.decode.n) for k in ("used_tok", "batch", "qd_tok"))
+        r.drain_prefill, r.drain_decode_q, r.release_tok = _ptr(drain_prefill, i32, r.prefill.n), _ptr(drain_decode_q, i32, r.decode.n), _ptr(release_tok, i32, r.decode.n)
+        r.tokens_per_seq, r.max_batch = int(tokens_per_seq), int(max_batch)
+        self._invoke(self.lib.hx_round, self._ctx, C.byref(m), C.byref(r), _stream(stream))
 
     def hx_rank(self, ratio, rank, stream=None):
         torch = _torch()

@@ -503,3 +503,29 @@ extern "C" int hx_validate_round(hx_ctx *ctx, const hx_calls *calls, const hx_pr
         if (report[k]) return hx_fail(ctx, HX_ERR_INVALID_ARG, "%d element(s): %s", report[k], what[k]);
     return HX_OK;
 }
+
+extern "C" int hx_round(hx_ctx *ctx, const hx_model *model, const hx_round_args *r, void *stream)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    HX_REQUIRE(ctx, model && r, HX_ERR_INVALID_ARG, "NULL model or round");
+    HX_REQUIRE(ctx, r->n_new >= 0 && r->n_wf >= 0, HX_ERR_INVALID_ARG, "negative size");
+    int rc = HX_OK;
+    if (r->n_new > 0) {
+        rc = hx_node_cost(ctx, model, r->n_new, r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw,
+                          &r->links, r->new_cost, stream);
+        if (rc != HX_OK) return rc;
+        rc = hx_dag_append(ctx, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx, r->new_cost, r->new_wf, stream);
+        if (rc != HX_OK) return rc;
+    }
+    const float *tail = nullptr, *horizon = nullptr;
+    int32_t n_nodes = 0;
+    if (r->ratio) {
+        rc = hx_dag_view(ctx, nullptr, &tail, nullptr, &horizon, &n_nodes);
+        if (rc != HX_OK) return rc;
+    }
+    rc = hx_score_placements(ctx, model, &r->calls, &r->prefill, &r->decode, &r->links, tail, horizon, n_nodes, r->n_wf,
+                             nullptr, nullptr, r->best_p, r->best_d, r->best_cost, r->ratio, stream);
+    if (rc != HX_OK) return rc;
+    return hx_commit(ctx, &r->calls, r->best_p, r->best_d, r->prefill.n, r->backlog_tok, r->decode.n, r->used_tok, r->batch,
+                     r->qd_tok, r->drain_prefill, r->drain_decode_q, r->release_tok, r->tokens_per_seq, r->max_batch, stream);
+}

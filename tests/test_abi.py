@@ -38,7 +38,8 @@ def test_struct_layouts_match_the_header(tmp_path):
     """The ctypes structures of the binding against what a C compiler makes of hx.h."""
     import subprocess
     structs = {"hx_model": binding.hx_model, "hx_calls": binding.hx_calls, "hx_prefill_tab": binding.hx_prefill_tab,
-               "hx_decode_tab": binding.hx_decode_tab, "hx_links": binding.hx_links, "hx_intervals": binding.hx_intervals}
+               "hx_decode_tab": binding.hx_decode_tab, "hx_links": binding.hx_links, "hx_intervals": binding.hx_intervals,
+               "hx_round_args": binding.hx_round_args}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hx.h"', 'int main(void) {']
     for name, cls in structs.items():
         lines.append(f'printf("{name} size %zu\\n", sizeof({name}));')

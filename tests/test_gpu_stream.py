@@ -204,3 +204,63 @@ def test_prepared_calls_equal_the_calls_they_were_prepared_from(ctx):
     for a, b in zip(snapshot(), want):
         assert np.array_equal(a, b)
     ctx.hx_stream_status()
+
+
+def test_round_in_one_call_equals_its_four_calls(ctx):
+    # hx_round = hx_node_cost -> hx_dag_append -> hx_score_placements (fused, with the ratio) -> hx_commit, enqueued by
+    # one library call: a few streaming rounds made both ways on two contexts' graphs and two copies of the pool, bit for bit
+    import torch
+    from paper_2605_16637_amd import binding
+    model = synth.MODEL
+    rng = np.random.default_rng(5)
+    L0, O0 = synth.gen_lengths(rng, 4000)
+    P, D = 48, 40
+    types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
+    d_links = binding.to_device(links)
+    tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
+    other = binding.Context(0)
+    try:
+        pools = [(binding.to_device(pre), binding.to_device(dec)) for _ in range(2)]
+        for c in (ctx, other):
+            c.hx_dag_reserve(200000, 300000, 50000, 24)
+        gens = [synth.StreamGen(9, 150, final_lo=6, final_hi=20) for _ in range(2)]
+        i32 = dict(dtype=torch.int32, device="cuda:0")
+        for r in range(6):
+            outs = []
+            for which, (c, gen, (d_pre, d_dec)) in enumerate(zip((ctx, other), gens, pools)):
+                b = gen.next_batch()
+                n_new, n_wf = b["n_new"], b["n_wf_total"]
+                el = np.random.default_rng(100 + r).uniform(0, 30, n_new).astype(np.float32)
+                calls = dict(n=n_new, L_in=dev(b["L_in"]), L_out=dev(b["L_out"]), node=dev(b["ids"]), wf=dev(b["wf"]), elapsed=dev(el))
+                bp, bd = torch.empty(n_new, **i32), torch.empty(n_new, **i32)
+                bc, ratio = torch.empty(n_new, device="cuda:0"), torch.empty(n_new, device="cuda:0")
+                cost = torch.empty(n_new, device="cuda:0")
+                dr = [dev(np.full(P, 900, np.int32)), dev(np.full(D, 300, np.int32)), dev(np.full(D, 1500, np.int32))]
+                if which == 0:
+                    c.hx_round(model, calls, d_pre, d_dec, d_links, bp, bd, bc, ratio=ratio, n_wf=n_wf,
+                               parent_row_ptr=dev(b["parent_row_ptr"]), parent_col_idx=dev(b["parent_col"]),
+                               new_L_in=calls["L_in"], new_L_out=calls["L_out"], new_wf=calls["wf"], new_cost=cost,
+                               type_flops=tF, type_hbm_bw=tB, drain_prefill=dr[0], drain_decode_q=dr[1], release_tok=dr[2])
+                else:
+                    c.hx_node_cost(model, calls["L_in"], calls["L_out"], tF, tB, d_links, cost)
+                    c.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), cost, calls["wf"])
+                    _, g_tail, _, g_hor, _ = c.hx_dag_view(n_wf)
+                    c.hx_score_placements(model, calls, d_pre, d_dec, d_links, tail=g_tail, horizon=g_hor,
+                                          best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+                    c.hx_commit(calls, bp, bd, d_pre["backlog_tok"], d_dec["used_tok"], d_dec["batch"], d_dec["qd_tok"], *dr)
+                c.hx_stream_status()
+                g_rem, g_tail, g_level, g_hor, n_nodes = c.hx_dag_view(n_wf)
+                outs.append([x.cpu().numpy() for x in (cost, bp, bd, bc, ratio, d_pre["backlog_tok"], d_dec["used_tok"],
+                                                       d_dec["batch"], d_dec["qd_tok"])] + [fetch(g_rem), fetch(g_level), fetch(g_hor)])
+            for a, b2 in zip(*outs):
+                assert np.array_equal(a, b2), f"round {r}"
+            assert (outs[0][1] >= 0).any()
+        # a round that reveals nothing and one without calls
+        d_pre, d_dec = pools[0]
+        empty = dict(n=0, L_in=dev(np.zeros(1, np.int32)), L_out=dev(np.zeros(1, np.int32)))
+        before = d_dec["used_tok"].clone()
+        ctx.hx_round(model, empty, d_pre, d_dec, d_links, torch.empty(1, **i32), torch.empty(1, **i32), torch.empty(1, device="cuda:0"))
+        ctx.hx_stream_status()
+        assert torch.equal(before, d_dec["used_tok"])
+    finally:
+        other.close()
