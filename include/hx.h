@@ -30,12 +30,18 @@
  *    for an infeasible pair.  Rates are FLOP/s and B/s, lengths and
  *    capacities are tokens.
  *  - Calls on one context must not overlap in time on different streams: the
- *    context owns scratch that consecutive calls reuse.  A context is not
+ *    context owns scratch that consecutive calls reuse.  One exception, for
+ *    rounds that refresh horizons beside the search: hx_node_cost,
+ *    hx_critical_path (single pass), hx_horizons, hx_dag_append and
+ *    hx_dag_set_cost may run on one stream while hx_score_placements with
+ *    fused outputs only, or hx_urgency, runs on another (they share nothing
+ *    but the status word, which kernels update atomically).  A context is not
  *    thread-safe.
  *  - Device memory is allocated by hx_ctx_create and hx_dag_reserve, and by
  *    hx_decode_score and hx_rank (beyond 16384 calls) the first time they meet
  *    a larger problem than before; every other call only launches kernels and
- *    can be captured in a HIP graph.
+ *    can be captured in a HIP graph (hx_validate_round and hx_stream_status
+ *    wait for the stream and cannot).
  */
 #ifndef HX_H
 #define HX_H
