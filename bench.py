@@ -186,19 +186,27 @@ def time_launches(torch, fn, reps, warmup=5):
 def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=32768, P=512, D=512):
     """Rounds of a live system, the streaming configuration at its stated length: reveal (node cost + append to the
     graph the context keeps), score the ready calls with their projected ratio, commit; pool and graph state carried
-    from round to round.  Every batch is resident in HBM before its clock starts.  Three ways of enqueueing a round are
+    from round to round.  Every batch is resident in HBM before its clock starts.  Four ways of enqueueing a round are
     timed on alternating rounds of the same run (they give the same results, so the state evolves as one sequence):
     its four library calls on one stream; the reveal on a second stream beside the search (which needs no horizon),
-    the urgency fold joining the two before the commit; and the whole round as one library call (hx_round)."""
+    the urgency fold joining the two before the commit; the whole round as one library call (hx_round); and that
+    call with its argument block built before the clock starts, as a caller written in C has it (through the
+    binding the block costs tens of microseconds of Python during which the GPU waits).
+    The batches are generated a chunk of rounds ahead, so that the rounds of a chunk follow each other without a
+    pause; the first two rounds after each pause for generation are run (the state is one sequence) but not timed.
+    A GPU left idle for milliseconds lowers its clocks, and the round after such a pause takes longer: that figure is
+    measured apart, on further rounds each preceded by 10 ms of sleep."""
     rng = np.random.default_rng(seed)
     gen = synth.StreamGen(seed, n_live)
     L0, O0 = synth.gen_lengths(rng, 50000)
     types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
     d_links, d_pre, d_dec = binding.to_device(links), binding.to_device(pre), binding.to_device(dec)
     tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
-    warm = 4
+    chunk, skip, n_idle = 50, 2, 24
+    n_chunks = (rounds + chunk - skip - 1) // (chunk - skip)
+    total = rounds + skip * n_chunks + skip + n_idle
     # the run's whole graph stays in the context's store: at most 4 new calls per live workflow and round on average
-    cap_n = int((rounds + warm) * n_live * 4.1) + 64 * n_live
+    cap_n = int(total * n_live * 4.1) + 64 * n_live
     ctx.hx_dag_reserve(cap_n, int(cap_n * 1.35), n_live + cap_n // 10 + 1024, 32)
     i32 = dict(dtype=torch.int32, device="cuda:0")
     bp, bd = torch.empty(C, **i32), torch.empty(C, **i32)
@@ -245,37 +253,63 @@ def streaming_leg(torch, ctx, synth, binding, seed, rounds, n_live=20000, C=3276
                      new_wf=b["wf"], new_cost=b["cost"], type_flops=tF, type_hbm_bw=tB,
                      drain_prefill=b["drain_p"], drain_decode_q=b["drain_q"], release_tok=b["release"])
 
-    modes = (("one stream", one_stream), ("reveal beside the search", two_streams), ("one library call per round (hx_round)", one_call))
-    lat = {name: [] for name, _ in modes}
-    cand = {name: 0 for name, _ in modes}
-    n_nodes = placed = 0
-    for r in range(rounds + warm):
-        b = next_batch()
-        name, fn = modes[r % len(modes)]
+    # (name, order, arguments marshalled before the clock starts: what a caller written in C sees)
+    modes = (("one stream", one_stream, False), ("reveal beside the search", two_streams, False),
+             ("one library call per round (hx_round)", one_call, False),
+             ("hx_round, arguments marshalled ahead", one_call, True))
+    lat = {name: [] for name, _, _ in modes}
+    cand = {name: 0 for name, _, _ in modes}
+    state = {"nodes": 0, "placed": 0, "calls": 0, "rounds": 0}
+
+    def timed(b, fn, ahead, pause_s=0.0):
+        go = ctx.prepare(lambda: fn(b)) if ahead else (lambda: fn(b))
         torch.cuda.synchronize()
+        if pause_s:
+            time.sleep(pause_s)
         t0 = time.perf_counter()
-        fn(b)
+        go()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        n_nodes += b["n_new"]
-        if r >= warm:
-            lat[name].append(dt * 1e6)
-            cand[name] += b["calls"]["n"] * P * D
-            placed += int((bp[:b["calls"]["n"]] >= 0).sum().item())
+        state["nodes"] += b["n_new"]; state["rounds"] += 1; state["calls"] += b["calls"]["n"]
+        state["placed"] += int((bp[:b["calls"]["n"]] >= 0).sum().item())
+        return dt * 1e6
+
+    done = 0
+    while done < rounds:
+        n = min(chunk, rounds - done + skip)
+        batches = [next_batch() for _ in range(n)]
+        for k, b in enumerate(batches):
+            name, fn, ahead = modes[done % len(modes)]
+            us = timed(b, fn, ahead)
+            if k >= skip:
+                lat[name].append(us)
+                cand[name] += b["calls"]["n"] * P * D
+                done += 1
+    # after a pause: the same round on a GPU that has been idle for 10 ms
+    idle = []
+    batches = [next_batch() for _ in range(skip + n_idle)]
+    for k, b in enumerate(batches):
+        us = timed(b, one_call, True, pause_s=0.010 if k >= skip else 0.0)
+        if k >= skip:
+            idle.append(us)
     ctx.hx_stream_status()
     res = {}
-    for name, _ in modes:
+    for name, _, _ in modes:
         x = np.array(lat[name])
         res[name] = {"rounds": int(x.size), "p50_us": float(np.percentile(x, 50)), "p99_us": float(np.percentile(x, 99)),
                      "candidates_per_s": cand[name] / (x.sum() * 1e-6)}
     best = min(res, key=lambda k: res[k]["p50_us"])
     return {"workload": "streaming rounds: %d live workflows, +0..8 calls per workflow per round, %d ready calls x %d x %d, 8 classes"
                         % (n_live, C, P, D),
-            "rounds": rounds, "candidates_per_round": C * P * D, "new_nodes_per_round": n_nodes / (rounds + warm),
-            "graph_nodes_at_the_end": n_nodes,
+            "rounds": rounds, "candidates_per_round": C * P * D, "new_nodes_per_round": state["nodes"] / state["rounds"],
+            "graph_nodes_at_the_end": state["nodes"],
             "p50_us": res[best]["p50_us"], "p99_us": res[best]["p99_us"], "candidates_per_s": res[best]["candidates_per_s"],
-            "order": best, "by_order": res, "placed_fraction": placed / max(1, sum(cand.values()) // (P * D)),
-            "launch": "eager, synchronised every round; the three orders on alternating rounds of one run"}
+            "order": best, "by_order": res,
+            "after_10ms_idle": {"order": "hx_round, arguments marshalled ahead", "rounds": len(idle),
+                                "p50_us": float(np.percentile(idle, 50)), "p99_us": float(np.percentile(idle, 99))},
+            "placed_fraction": state["placed"] / max(1, state["calls"]),
+            "launch": "eager, synchronised every round, rounds back to back in chunks of %d generated ahead (the first %d "
+                      "of a chunk untimed); the four orders on alternating rounds of one run" % (chunk, skip)}
 
 
 def planner_leg(torch, ctx, synth, binding, seed):

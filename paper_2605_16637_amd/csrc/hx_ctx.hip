@@ -2,6 +2,11 @@
 #include "hx_common.hpp"
 
 void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
+int hx_dag_append_with_cost(hx_ctx *ctx, const hx_model *model, int32_t n_new, int32_t n_new_edges,
+                            const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                            const int32_t *new_L_in, const int32_t *new_L_out,
+                            int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
+                            float *new_cost, const int32_t *new_wf, void *stream);   // hx_dag.hip
 int hx_score_init();                // hx_score.hip
 int hx_plan_init();                 // hx_plan.hip
 int hx_decode_init();               // hx_decode.hip
@@ -511,10 +516,9 @@ extern "C" int hx_round(hx_ctx *ctx, const hx_model *model, const hx_round_args 
     HX_REQUIRE(ctx, r->n_new >= 0 && r->n_wf >= 0, HX_ERR_INVALID_ARG, "negative size");
     int rc = HX_OK;
     if (r->n_new > 0) {
-        rc = hx_node_cost(ctx, model, r->n_new, r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw,
-                          &r->links, r->new_cost, stream);
-        if (rc != HX_OK) return rc;
-        rc = hx_dag_append(ctx, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx, r->new_cost, r->new_wf, stream);
+        rc = hx_dag_append_with_cost(ctx, model, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx,
+                                     r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw, &r->links,
+                                     r->new_cost, r->new_wf, stream);
         if (rc != HX_OK) return rc;
     }
     const float *tail = nullptr, *horizon = nullptr;

@@ -502,17 +502,30 @@ __device__ __forceinline__ void hx_push_parent_scoped(const AppendArgs &a, int u
     hx_push_parent_t<true>(a, u, rem_v, level_v);
 }
 
-__global__ void hx_append_reset_kernel(int32_t *counters)
+// First phase of an append: the new nodes' own entries.  The two list counters the append needs at zero (the
+// one the walks append to, the one the first sweep after them clears) are cleared here: the walks are a launch
+// of their own after this one, so no launch is spent on the counters.
+// COST: the nodes' standalone costs are not read but worked out here from their lengths, exactly as
+// hx_node_cost_kernel does, and written to the caller's array as well (one launch less in front of the walks, where
+// every launch of a round still waits for the host).
+template <bool COST>
+__global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a, NodeCostArgs nc)
 {
-    if (threadIdx.x < 3) counters[threadIdx.x] = 0;
-}
-
-__global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a)
-{
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.counters[a.czero] = 0;
+    __shared__ CostTables s_tab;
+    if constexpr (COST) {
+        hx_cost_tables_fill(s_tab, nc, threadIdx.x);
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) { a.counters[a.czero] = 0; a.counters[a.cout] = 0; }
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.n_new; i += gridDim.x * blockDim.x) {
         const int v = a.n_old + i;
-        float c = a.new_cost[i];
+        float c;
+        if constexpr (COST) {
+            c = hx_node_cost_eval(nc.m, s_tab, nc.T, nc.L_in[i], nc.L_out[i]);
+            nc.cost[i] = c;
+        } else {
+            c = a.new_cost[i];
+        }
         int w = a.new_wf[i];
         int r0 = a.new_row_ptr[i], r1 = a.new_row_ptr[i + 1];
         if (r0 < 0 || r1 > a.n_new_edges || r0 > r1) { hx_raise(a.status, HX_ERR_INDEX); r0 = r1 = min(max(r0, 0), a.n_new_edges); }
@@ -668,25 +681,40 @@ void dag_free(HxDagStore &g)
 
 void hx_dag_release(hx_ctx *ctx) { dag_free(ctx->dag); }
 
+namespace {
+
+// the argument checks of the standalone cost, and its kernel arguments
+int node_cost_args(hx_ctx *ctx, const hx_model *model, int32_t n, const int32_t *L_in, const int32_t *L_out,
+                   int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links, float *cost,
+                   NodeCostArgs *out)
+{
+    HX_REQUIRE(ctx, model && links && links->bw && type_flops && type_hbm_bw, HX_ERR_INVALID_ARG, "NULL table");
+    HX_REQUIRE(ctx, n >= 0, HX_ERR_INVALID_ARG, "negative n");
+    HX_REQUIRE(ctx, n_types >= 1 && n_types <= HX_MAX_TYPES && links->n_types == n_types, HX_ERR_SHAPE,
+               "n_types %d (links %d) outside 1..%d", n_types, links->n_types, HX_MAX_TYPES);
+    HX_REQUIRE(ctx, n == 0 || (L_in && L_out && cost), HX_ERR_INVALID_ARG, "NULL array");
+    NodeCostArgs a{};
+    a.m = HxModelF{model->kv_bytes_per_token, model->flops_per_token, model->attn_flops_per_token2,
+                   model->weight_bytes, model->nominal_batch};
+    a.n = n; a.T = n_types; a.L_in = L_in; a.L_out = L_out; a.tF = type_flops; a.tB = type_hbm_bw;
+    a.bw = links->bw; a.lat = links->latency; a.cost = cost;
+    *out = a;
+    return HX_OK;
+}
+
+}  // namespace
+
 extern "C" int hx_node_cost(hx_ctx *ctx, const hx_model *model, int32_t n,
                             const int32_t *L_in, const int32_t *L_out,
                             int32_t n_types, const float *type_flops, const float *type_hbm_bw,
                             const hx_links *links, float *cost, void *stream_)
 {
     if (!ctx) return HX_ERR_INVALID_ARG;
-    HX_REQUIRE(ctx, model && links && links->bw && type_flops && type_hbm_bw, HX_ERR_INVALID_ARG, "NULL table");
-    HX_REQUIRE(ctx, n >= 0, HX_ERR_INVALID_ARG, "negative n");
-    HX_REQUIRE(ctx, n_types >= 1 && n_types <= HX_MAX_TYPES && links->n_types == n_types, HX_ERR_SHAPE,
-               "n_types %d (links %d) outside 1..%d", n_types, links->n_types, HX_MAX_TYPES);
-    HX_REQUIRE(ctx, n == 0 || (L_in && L_out && cost), HX_ERR_INVALID_ARG, "NULL array");
+    NodeCostArgs a{};
+    if (int rc = node_cost_args(ctx, model, n, L_in, L_out, n_types, type_flops, type_hbm_bw, links, cost, &a)) return rc;
     if (n == 0) return HX_OK;
     HxDeviceGuard guard(ctx->device);
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
-    NodeCostArgs a{};
-    a.m = HxModelF{model->kv_bytes_per_token, model->flops_per_token, model->attn_flops_per_token2,
-                   model->weight_bytes, model->nominal_batch};
-    a.n = n; a.T = n_types; a.L_in = L_in; a.L_out = L_out; a.tF = type_flops; a.tB = type_hbm_bw;
-    a.bw = links->bw; a.lat = links->latency; a.cost = cost;
     int grid = (n + 255) / 256;
     grid = grid > ctx->num_cu * 8 ? ctx->num_cu * 8 : grid;
     hx_node_cost_kernel<<<grid, 256, 0, (hipStream_t)stream_>>>(a);
@@ -803,11 +831,13 @@ extern "C" int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges,
     return hx_check_launch(ctx, "hx_fill_i32_kernel");
 }
 
-extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
-                             const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
-                             const float *new_cost, const int32_t *new_wf, void *stream_)
+namespace {
+
+// nc: NULL, or the arguments of the standalone cost of the new nodes, which the first kernel then works out itself
+// (new_cost is nc->cost then, written as well as used)
+int dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+               const float *new_cost, const int32_t *new_wf, const NodeCostArgs *nc, hipStream_t stream)
 {
-    if (!ctx) return HX_ERR_INVALID_ARG;
     HxDagStore &g = ctx->dag;
     HX_REQUIRE(ctx, g.cost, HX_ERR_INVALID_ARG, "hx_dag_reserve has not been called");
     HX_REQUIRE(ctx, n_new >= 0 && n_new_edges >= 0, HX_ERR_INVALID_ARG, "negative size");
@@ -820,7 +850,6 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
     if (n_new == 0) return HX_OK;
     HxDeviceGuard guard(ctx->device);
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
-    hipStream_t stream = (hipStream_t)stream_;
 
     AppendArgs a{};
     a.n_old = g.n_nodes; a.n_new = n_new; a.e_old = g.n_edges; a.n_new_edges = n_new_edges; a.cap_wf = g.cap_wf;
@@ -831,10 +860,10 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
 
     int grid = (n_new + 255) / 256;
     grid = grid > ctx->num_cu * 8 ? ctx->num_cu * 8 : grid;
-    hx_append_reset_kernel<<<1, 64, 0, stream>>>(g.counters);
     a.cin = 0; a.cout = 1; a.czero = 2; a.epoch = ++g.epoch;
     a.list_in = g.list[1]; a.list_out = g.list[0];
-    hx_append_init_kernel<<<grid, 256, 0, stream>>>(a);
+    if (nc) hx_append_init_kernel<true><<<grid, 256, 0, stream>>>(a, *nc);
+    else hx_append_init_kernel<false><<<grid, 256, 0, stream>>>(a, NodeCostArgs{});
     hx_append_relax_kernel<<<grid, 256, 0, stream>>>(a);
     // what the walks handed over (normally nothing) is finished level by level in one workgroup:
     // sweep k reads the list sweep k-1 wrote, max_depth sweeps reach every ancestor
@@ -850,6 +879,30 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
     g.n_nodes += n_new;
     g.n_edges += n_new_edges;
     return HX_OK;
+}
+
+}  // namespace
+
+extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
+                             const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                             const float *new_cost, const int32_t *new_wf, void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    return dag_append(ctx, n_new, n_new_edges, parent_row_ptr, parent_col_idx, new_cost, new_wf, nullptr, (hipStream_t)stream_);
+}
+
+// hx_node_cost of the new nodes followed by hx_dag_append, the cost worked out by the append's first kernel: the
+// same checks and the same results as the two calls, one launch less (for hx_round)
+int hx_dag_append_with_cost(hx_ctx *ctx, const hx_model *model, int32_t n_new, int32_t n_new_edges,
+                            const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                            const int32_t *new_L_in, const int32_t *new_L_out,
+                            int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
+                            float *new_cost, const int32_t *new_wf, void *stream_)
+{
+    NodeCostArgs nc{};
+    if (int rc = node_cost_args(ctx, model, n_new, new_L_in, new_L_out, n_types, type_flops, type_hbm_bw, links, new_cost, &nc))
+        return rc;
+    return dag_append(ctx, n_new, n_new_edges, parent_row_ptr, parent_col_idx, new_cost, new_wf, &nc, (hipStream_t)stream_);
 }
 
 extern "C" int hx_dag_set_cost(hx_ctx *ctx, int32_t n, const int32_t *node_ids, const float *cost, void *stream_)

@@ -1089,7 +1089,7 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
     const int ne = 2 * iv->stride + 1, nt = hx_tl_len(ne);
     // Groups of instances: enough workgroups (tiles of 256 calls x groups) to fill the chip several times over,
     // at most 64 groups (the finish kernel reads one partial result per group and call).
-    const int tiles = (Q + 255) / 256;
+    const int tiles = (Q + DS_THREADS - 1) / DS_THREADS;
     int n_groups = 0, gd = 1;
     if (D > 0) {
         n_groups = (8 * ctx->num_cu + tiles - 1) / tiles;
@@ -1156,7 +1156,7 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)nt * 8) + hx_align16((size_t)ne * 2);
         hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, o, nt);
         const int n_lock = lock ? tiles : 0;
-        hx_decode_score_kernel<<<n_lock + tiles * n_groups, 256, 0, stream>>>(a, o, nt, n_lock);
+        hx_decode_score_kernel<<<n_lock + tiles * n_groups, DS_THREADS, 0, stream>>>(a, o, nt, n_lock);
     }
     DecodeFinishArgs f{};
     f.Q = Q; f.D = D; f.n_groups = n_groups;
