@@ -45,6 +45,7 @@ struct HxDagStore {
     int32_t n_nodes = 0, n_edges = 0;
     float *cost = nullptr, *rem = nullptr, *tail = nullptr, *horizon = nullptr;
     int32_t *level = nullptr, *wf = nullptr, *parent_row_ptr = nullptr, *parent_col = nullptr;
+    int32_t *parent0 = nullptr;        // [cap_nodes] a node's first parent (-1: none), beside its row of parent_col
     int32_t *mark = nullptr, *list[2] = {nullptr, nullptr};
     int32_t *counters = nullptr;       // [4]: list sizes (3, rotating) + epoch
     uint32_t epoch = 0;

@@ -446,7 +446,7 @@ struct AppendArgs {
     const int32_t *new_row_ptr, *new_col, *new_wf;
     const float *new_cost;
     float *cost, *rem, *tail, *horizon;
-    int32_t *level, *wf, *prow, *pcol, *mark;
+    int32_t *level, *wf, *prow, *pcol, *parent0, *mark;
     int32_t *list_in, *list_out;
     int32_t *counters;      // [0..2] rotating list sizes
     int cin, cout, czero;   // which counter is read, appended to, cleared
@@ -534,11 +534,14 @@ __global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a, NodeC
         if (w < 0 || w >= a.cap_wf) { hx_raise(a.status, HX_ERR_INDEX); w = -1; }
         a.wf[v] = w;
         if (w >= 0) hx_raise_max_f32(&a.horizon[w], c);
+        int first = -1;
         for (int e = r0; e < r1; ++e) {
             int u = a.new_col[e];
             if (u < 0 || u >= v) { hx_raise(a.status, HX_ERR_NOT_DAG); u = -1; }
             a.pcol[a.e_old + e] = u;
+            if (e == r0) first = u;
         }
+        a.parent0[v] = first;
     }
 }
 
@@ -546,13 +549,31 @@ __global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a, NodeC
 // also new finds that parent initialised).  Asynchronous propagation: every new node walks up from itself, one thread per new node.  A visit
 // of node u recomputes rem[u] from the tail u has now, raises its workflow's horizon, and raises the
 // tail and level of u's parents; a parent that grew is visited next (further grown parents wait on a
-// small stack).  Whoever raises a node visits it afterwards and reads the value current by then, so
+// small stack).  Whoever raises a node visits it afterwards with a tail at least as large as the one it left there, so
 // every increase is carried upwards by someone, and a thread whose value did not raise anything
 // stops: the fixed point is the same as that of the level-by-level sweeps, maxima are exact, and no
 // launch or barrier separates the levels.  A walk that outgrows its stack or its step budget hands
 // the remaining nodes to the worklist, which the sweeps after this kernel finish.
+//
+// A walk is a chain of memory round trips, and most of it goes up through first parents.  One round trip per
+// level on that path: a node's first parent is kept beside its row of parents, so it is known when the node is
+// reached; the two atomics that raise the parent return what it held before, which together with the raised value
+// is what it holds now; and everything else the visit of the parent needs (cost, workflow, its own row and first
+// parent -- nothing an append changes) is asked for together with those atomics.  Further parents, and nodes
+// taken from the stack, pay the extra trips.
 constexpr int RELAX_STACK = 16;
 constexpr int RELAX_STEPS = 1024;
+
+struct HxVisit {
+    float cost, tl;
+    int lv, w, e0, e1, q0;
+};
+
+// what a visit needs of node u that no append changes
+__device__ __forceinline__ void hx_visit_fixed(const AppendArgs &a, int u, HxVisit &x)
+{
+    x.cost = a.cost[u]; x.w = a.wf[u]; x.e0 = a.prow[u]; x.e1 = a.prow[u + 1]; x.q0 = a.parent0[u];
+}
 
 __global__ __launch_bounds__(256) void hx_append_relax_kernel(AppendArgs a)
 {
@@ -560,16 +581,39 @@ __global__ __launch_bounds__(256) void hx_append_relax_kernel(AppendArgs a)
         int stack[RELAX_STACK];
         int sp = 0, steps = 0;
         int u = a.n_old + i;
+        HxVisit x;
+        bool have = false;                   // x already describes u (reached through its child's first-parent slot)
         while (u >= 0) {
-            const float tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float r = a.cost[u] + tl;
+            if (!have) {
+                x.tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                x.lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                hx_visit_fixed(a, u, x);
+            }
+            const float r = x.cost + x.tl;
+            const int lv = x.lv;
             hx_raise_max_f32(&a.rem[u], r);
-            const int w = a.wf[u];
-            if (w >= 0) hx_raise_max_f32(&a.horizon[w], r);
+            if (x.w >= 0) hx_raise_max_f32(&a.horizon[x.w], r);
             ++steps;
             int next = -1;
-            for (int e = a.prow[u]; e < a.prow[u + 1]; ++e) {
+            have = false;
+            const int e0 = x.e0, e1 = x.e1, q0 = x.q0;
+            if (e1 > e0 && q0 >= 0) {
+                // the first parent: raised, and its own visit prepared, in one round trip
+                const unsigned old_t = atomicMax((unsigned *)&a.tail[q0], __float_as_uint(r));
+                const int old_l = atomicMax(&a.level[q0], lv + 1);
+                HxVisit y;
+                hx_visit_fixed(a, q0, y);
+                if (__float_as_uint(r) > old_t || lv + 1 > old_l) {
+                    if (steps >= RELAX_STEPS) {
+                        hx_enqueue(a, q0);
+                    } else {
+                        y.tl = __uint_as_float(max(old_t, __float_as_uint(r)));
+                        y.lv = max(old_l, lv + 1);
+                        x = y; next = q0; have = true;
+                    }
+                }
+            }
+            for (int e = e0 + 1; e < e1; ++e) {
                 const int q = a.pcol[e];
                 if (q < 0) continue;
                 bool grew = hx_raise_max_f32(&a.tail[q], r);
@@ -671,7 +715,7 @@ int dev_alloc(hx_ctx *ctx, T **p, size_t n)
 
 void dag_free(HxDagStore &g)
 {
-    void *ptrs[] = {g.cost, g.rem, g.tail, g.horizon, g.level, g.wf, g.parent_row_ptr, g.parent_col,
+    void *ptrs[] = {g.cost, g.rem, g.tail, g.horizon, g.level, g.wf, g.parent_row_ptr, g.parent_col, g.parent0,
                     g.mark, g.list[0], g.list[1], g.counters};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     g = HxDagStore{};
@@ -817,7 +861,7 @@ extern "C" int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges,
     if ((rc = dev_alloc(ctx, &g.cost, N)) || (rc = dev_alloc(ctx, &g.rem, N)) || (rc = dev_alloc(ctx, &g.tail, N)) ||
         (rc = dev_alloc(ctx, &g.horizon, W)) || (rc = dev_alloc(ctx, &g.level, N)) || (rc = dev_alloc(ctx, &g.wf, N)) ||
         (rc = dev_alloc(ctx, &g.parent_row_ptr, N + 1)) || (rc = dev_alloc(ctx, &g.parent_col, E)) ||
-        (rc = dev_alloc(ctx, &g.mark, N)) || (rc = dev_alloc(ctx, &g.list[0], N)) ||
+        (rc = dev_alloc(ctx, &g.parent0, N)) || (rc = dev_alloc(ctx, &g.mark, N)) || (rc = dev_alloc(ctx, &g.list[0], N)) ||
         (rc = dev_alloc(ctx, &g.list[1], N)) || (rc = dev_alloc(ctx, &g.counters, (size_t)4))) {
         dag_free(g);
         return rc;
@@ -855,7 +899,7 @@ int dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *p
     a.n_old = g.n_nodes; a.n_new = n_new; a.e_old = g.n_edges; a.n_new_edges = n_new_edges; a.cap_wf = g.cap_wf;
     a.new_row_ptr = parent_row_ptr; a.new_col = parent_col_idx; a.new_wf = new_wf; a.new_cost = new_cost;
     a.cost = g.cost; a.rem = g.rem; a.tail = g.tail; a.horizon = g.horizon;
-    a.level = g.level; a.wf = g.wf; a.prow = g.parent_row_ptr; a.pcol = g.parent_col; a.mark = g.mark;
+    a.level = g.level; a.wf = g.wf; a.prow = g.parent_row_ptr; a.pcol = g.parent_col; a.parent0 = g.parent0; a.mark = g.mark;
     a.counters = g.counters; a.status = ctx->d_status;
 
     int grid = (n_new + 255) / 256;
@@ -922,7 +966,7 @@ extern "C" int hx_dag_set_cost(hx_ctx *ctx, int32_t n, const int32_t *node_ids, 
     AppendArgs a{};
     a.n_old = 0; a.n_new = g.n_nodes; a.cap_wf = g.cap_wf;
     a.cost = g.cost; a.rem = g.rem; a.tail = g.tail; a.horizon = g.horizon;
-    a.level = g.level; a.wf = g.wf; a.prow = g.parent_row_ptr; a.pcol = g.parent_col; a.mark = g.mark;
+    a.level = g.level; a.wf = g.wf; a.prow = g.parent_row_ptr; a.pcol = g.parent_col; a.parent0 = g.parent0; a.mark = g.mark;
     a.counters = g.counters; a.status = ctx->d_status;
     a.cin = 0; a.cout = 1; a.czero = 2; a.epoch = ++g.epoch;
     a.list_in = g.list[1]; a.list_out = g.list[0];
