@@ -134,6 +134,14 @@ class RoundOnDevice:
         self.score()
         self.commit()
 
+    def round_call(self):
+        """One round as one library call (hx_round with the round's whole graph)."""
+        g = dict(succ_row_ptr=self.row_ptr, succ_col_idx=self.col, wf_ptr=self.wf_ptr, L_in=self.L_in, L_out=self.L_out,
+                 node_cost=self.cost, rem=self.rem, tail=self.tail, level=self.level, horizon=self.hor)
+        self.ctx.hx_round(self.rnd.model, self.calls, self.pre, self.dec, self.links, self.bp, self.bd, self.bc,
+                          ratio=self.ratio, type_flops=self.tF, type_hbm_bw=self.tB, drain_prefill=self.drain_p,
+                          drain_decode_q=self.drain_q, release_tok=self.release, graph=g)
+
     def step_overlapped(self):
         """One round with the horizon refresh (node cost -> critical path) on a second stream beside the
         search, which does not need it; the urgency fold joins the two, the commit follows."""
@@ -564,13 +572,16 @@ def round_latency(torch, ctx, synth, name, seed, eager, rounds=500):
     # the urgency fold joining them.  With --eager the calls are marshalled at every round.
     rd.step()
     rd.step_overlapped()
+    rd.round_call()
     torch.cuda.synchronize()
     if eager:
-        runs = {"eager, one stream": rd.step, "eager, horizons beside the search": rd.step_overlapped}
+        runs = {"eager, one stream": rd.step, "eager, horizons beside the search": rd.step_overlapped,
+                "eager, hx_round": rd.round_call}
     else:
         runs = {"hip graph replay, one stream": capture(torch, rd.step).replay,
                 "hip graph replay, horizons beside the search": capture(torch, rd.step_overlapped).replay,
-                "prepared launches, one stream": ctx.prepare(rd.step)}
+                "prepared launches, one stream": ctx.prepare(rd.step),
+                "hx_round, arguments marshalled ahead": ctx.prepare(rd.round_call)}
     lat = {k: [] for k in runs}
     names = list(runs)
     for i in range(len(names) * (rounds + 20)):
@@ -598,10 +609,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="large", choices=["large", "mid", "stream"])
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph", "prepared"],
-                    help="how the timed steps are launched: from the host, one launch after the other (eager), or as "
-                         "replays of a HIP graph; auto = the faster of the two in a short untimed trial (eager where the "
-                         "host enqueues a step faster than the GPU runs it, graph where the round is launch-bound)")
+    ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph", "prepared", "round"],
+                    help="how the timed steps are launched: the round's three library calls from the host, one launch after "
+                         "the other (eager; prepared = their arguments marshalled once), as replays of a HIP graph, or as "
+                         "one hx_round call (arguments marshalled once); auto = the fastest of them in a short untimed trial")
     ap.add_argument("--eager", action="store_true", help="same as --launch eager")
     ap.add_argument("--overlap", action="store_true",
                     help="run the horizon refresh on a second stream beside the search (measured: 3-4 us slower per round "
@@ -641,9 +652,11 @@ def main():
     modes = {"eager": lambda: step, "graph": lambda: capture(torch, step).replay,
              # the same launches with the arguments of the library calls marshalled once (not with --overlap: the
              # waits between the two streams are not library calls)
-             "prepared": lambda: ctx.prepare(step)}
+             "prepared": lambda: ctx.prepare(step),
+             # the whole round as one library call
+             "round": lambda: ctx.prepare(rd.round_call)}
     if args.overlap:
-        del modes["prepared"]
+        del modes["prepared"], modes["round"]
     if launch == "auto":
         # whichever is fastest on this host, from a short untimed trial of each (a slow host makes eager launch-bound)
         made = {k: f() for k, f in modes.items()}
@@ -673,7 +686,8 @@ def main():
                    "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
                             if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
                    "launch": {"eager": "eager, the host enqueues ahead of the GPU", "graph": "hip graph replay",
-                              "prepared": "eager launches with pre-marshalled arguments, the host enqueues ahead of the GPU"}[launch],
+                              "prepared": "eager launches with pre-marshalled arguments, the host enqueues ahead of the GPU",
+                              "round": "one hx_round call per step, arguments marshalled once, the host enqueues ahead of the GPU"}[launch],
                    "seed": args.seed},
         "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups)", "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS,

@@ -355,22 +355,28 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
 
 /*
  * One scheduling invocation of Algorithm 1 in one call, for callers that pay for
- * every crossing of this boundary: the calls revealed since the last
- * invocation are priced and appended to the context's graph (horizons of the
- * affected workflows refreshed: Sec. 4.1, 5.1), every ready call is projected
- * onto its best feasible (prefill, decode) pair with its ratio (Sec. 5.3, 5.4,
- * Eq. (2)), and the chosen pairs are committed to the pool snapshot (the
- * simulated-state update, once for the round).  Exactly
+ * every crossing of this boundary: the calls revealed since
+ * the last invocation are priced and appended to the context's graph (horizons
+ * of the affected workflows refreshed: Sec. 4.1, 5.1), every ready call is
+ * projected onto its best feasible (prefill, decode) pair with its ratio
+ * (Sec. 5.3, 5.4, Eq. (2)), and the chosen pairs are committed to the pool
+ * snapshot (the simulated-state update, once for the round).  The results,
+ * argument meaning and error reporting are exactly those of
  *   hx_node_cost(new_L_in, new_L_out -> new_cost); hx_dag_append(new nodes);
  *   hx_score_placements(fused outputs, tail and horizon = the context's graph);
  *   hx_commit(calls, best_p, best_d, the snapshot's counters, the drains)
- * enqueued on `stream` in that order, with the same argument meaning, results
- * and error reporting as those calls (the first one that fails ends the call;
- * what was enqueued before it stays enqueued).  n_new may be 0 (nothing is
- * revealed), calls.n may be 0.  hx_dag_reserve must have been called.  The
- * counters of `prefill` and `decode` that the commit updates are passed once
- * more as writable pointers (they may be the same memory as the tables' own
- * backlog_tok, used_tok, batch, qd_tok: the search has read them by then).
+ * made on `stream` in that order (the first one that fails ends the call; what
+ * was enqueued before it stays enqueued), one launch fewer: the new nodes'
+ * costs are worked out by the append's first kernel.  n_new may be 0 (nothing
+ * is revealed), calls.n may be 0.  The counters of `prefill` and `decode` that
+ * the commit updates are passed once more as writable pointers (they may be
+ * the same memory as the tables' own backlog_tok, used_tok, batch, qd_tok: the
+ * search has read them by then).
+ * A round may instead bring its whole graph (n_nodes > 0, n_new = 0; a
+ * scheduler that rebuilds the ready workflows' DAGs per invocation): then the
+ * reveal is hx_horizons on the arrays given (same requirements on the
+ * numbering, same outputs) and the ratio uses their tail and horizon;
+ * hx_dag_reserve is needed for the first form only.
  */
 typedef struct {
     /* reveal */
@@ -385,6 +391,16 @@ typedef struct {
     const float   *type_flops;       /* device [n_types]                        */
     const float   *type_hbm_bw;      /* device [n_types]                        */
     int32_t n_wf;                    /* workflows numbered so far (horizon length used for the ratio) */
+    /* reveal, the other form: the whole graph of the round, arguments as hx_horizons (n_nodes > 0 selects it) */
+    int32_t n_nodes, n_edges;
+    const int32_t *succ_row_ptr;     /* device [n_nodes+1]                      */
+    const int32_t *succ_col_idx;     /* device [n_edges]                        */
+    const int32_t *wf_ptr;           /* device [n_wf+1]                         */
+    const int32_t *node_L_in;        /* device [n_nodes]                        */
+    const int32_t *node_L_out;       /* device [n_nodes]                        */
+    float   *node_cost, *rem, *tail; /* device [n_nodes] out                    */
+    int32_t *level;                  /* device [n_nodes] out                    */
+    float   *horizon;                /* device [n_wf] out                       */
     /* search */
     hx_calls        calls;           /* node, wf, elapsed required when ratio != NULL */
     hx_prefill_tab  prefill;

@@ -62,6 +62,9 @@ class hx_round_args(C.Structure):
     _fields_ = [("n_new", C.c_int32), ("n_new_edges", C.c_int32), ("parent_row_ptr", C.c_void_p), ("parent_col_idx", C.c_void_p),
                 ("new_L_in", C.c_void_p), ("new_L_out", C.c_void_p), ("new_wf", C.c_void_p), ("new_cost", C.c_void_p),
                 ("n_types", C.c_int32), ("type_flops", C.c_void_p), ("type_hbm_bw", C.c_void_p), ("n_wf", C.c_int32),
+                ("n_nodes", C.c_int32), ("n_edges", C.c_int32), ("succ_row_ptr", C.c_void_p), ("succ_col_idx", C.c_void_p),
+                ("wf_ptr", C.c_void_p), ("node_L_in", C.c_void_p), ("node_L_out", C.c_void_p),
+                ("node_cost", C.c_void_p), ("rem", C.c_void_p), ("tail", C.c_void_p), ("level", C.c_void_p), ("horizon", C.c_void_p),
                 ("calls", hx_calls), ("prefill", hx_prefill_tab), ("decode", hx_decode_tab), ("links", hx_links),
                 ("best_p", C.c_void_p), ("best_d", C.c_void_p), ("best_cost", C.c_void_p), ("ratio", C.c_void_p),
                 ("backlog_tok", C.c_void_p), ("used_tok", C.c_void_p), ("batch", C.c_void_p), ("qd_tok", C.c_void_p),
@@ -366,9 +369,10 @@ class Context:
     def hx_round(self, model, calls, prefill, decode, links, best_p, best_d, best_cost, ratio=None, n_wf=0,
                  parent_row_ptr=None, parent_col_idx=None, new_L_in=None, new_L_out=None, new_wf=None, new_cost=None,
                  type_flops=None, type_hbm_bw=None, drain_prefill=None, drain_decode_q=None, release_tok=None,
-                 tokens_per_seq=2048, max_batch=256, stream=None):
-        """One scheduling invocation in one library call: reveal (node cost + append), fused search with the
-        ratio, commit into the pool's own counters."""
+                 tokens_per_seq=2048, max_batch=256, graph=None, stream=None):
+        """One scheduling invocation in one library call: reveal (node cost + append, or -- ``graph``: a dict with
+        succ_row_ptr, succ_col_idx, wf_ptr, L_in, L_out and the outputs node_cost, rem, tail, level, horizon --
+        the whole graph's horizons), fused search with the ratio, commit into the pool's own counters."""
         torch = _torch()
         i32, f32 = torch.int32, torch.float32
         m = make_model(model)
@@ -381,6 +385,14 @@ class Context:
         r.n_types = 0 if type_flops is None else int(type_flops.numel())
         r.type_flops, r.type_hbm_bw = _ptr(type_flops, f32), _ptr(type_hbm_bw, f32, r.n_types)
         r.n_wf = int(n_wf)
+        if graph is not None:
+            g = graph
+            n, nw = int(g["succ_row_ptr"].numel()) - 1, int(g["wf_ptr"].numel()) - 1
+            r.n_nodes, r.n_edges, r.n_wf = n, int(g["succ_col_idx"].numel()), nw
+            r.succ_row_ptr, r.succ_col_idx, r.wf_ptr = _ptr(g["succ_row_ptr"], i32), _ptr(g["succ_col_idx"], i32), _ptr(g["wf_ptr"], i32)
+            r.node_L_in, r.node_L_out = _ptr(g["L_in"], i32, n), _ptr(g["L_out"], i32, n)
+            r.node_cost, r.rem, r.tail = _ptr(g["node_cost"], f32, n), _ptr(g["rem"], f32, n), _ptr(g["tail"], f32, n)
+            r.level, r.horizon = _ptr(g["level"], i32, n), _ptr(g["horizon"], f32, nw)
         r.calls, r.prefill, r.decode, r.links = make_calls(calls), make_prefill(prefill), make_decode(decode), make_links(links)
         n = r.calls.n
         r.best_p, r.best_d, r.best_cost, r.ratio = _ptr(best_p, i32, n), _ptr(best_d, i32, n), _ptr(best_cost, f32, n), _ptr(ratio, f32, n)

@@ -513,19 +513,29 @@ extern "C" int hx_round(hx_ctx *ctx, const hx_model *model, const hx_round_args 
 {
     if (!ctx) return HX_ERR_INVALID_ARG;
     HX_REQUIRE(ctx, model && r, HX_ERR_INVALID_ARG, "NULL model or round");
-    HX_REQUIRE(ctx, r->n_new >= 0 && r->n_wf >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, r->n_new >= 0 && r->n_wf >= 0 && r->n_nodes >= 0, HX_ERR_INVALID_ARG, "negative size");
+    HX_REQUIRE(ctx, r->n_new == 0 || r->n_nodes == 0, HX_ERR_INVALID_ARG,
+               "a round reveals new nodes (n_new) or brings its whole graph (n_nodes), not both");
     int rc = HX_OK;
-    if (r->n_new > 0) {
-        rc = hx_dag_append_with_cost(ctx, model, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx,
-                                     r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw, &r->links,
-                                     r->new_cost, r->new_wf, stream);
-        if (rc != HX_OK) return rc;
-    }
     const float *tail = nullptr, *horizon = nullptr;
     int32_t n_nodes = 0;
-    if (r->ratio) {
-        rc = hx_dag_view(ctx, nullptr, &tail, nullptr, &horizon, &n_nodes);
+    if (r->n_nodes > 0) {
+        rc = hx_horizons(ctx, model, r->n_nodes, r->n_edges, r->succ_row_ptr, r->succ_col_idx, r->node_L_in, r->node_L_out,
+                         r->n_types, r->type_flops, r->type_hbm_bw, &r->links, r->n_wf, r->wf_ptr,
+                         r->node_cost, r->rem, r->tail, r->level, r->horizon, stream);
         if (rc != HX_OK) return rc;
+        if (r->ratio) { tail = r->tail; horizon = r->horizon; n_nodes = r->n_nodes; }
+    } else {
+        if (r->n_new > 0) {
+            rc = hx_dag_append_with_cost(ctx, model, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx,
+                                         r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw, &r->links,
+                                         r->new_cost, r->new_wf, stream);
+            if (rc != HX_OK) return rc;
+        }
+        if (r->ratio) {
+            rc = hx_dag_view(ctx, nullptr, &tail, nullptr, &horizon, &n_nodes);
+            if (rc != HX_OK) return rc;
+        }
     }
     rc = hx_score_placements(ctx, model, &r->calls, &r->prefill, &r->decode, &r->links, tail, horizon, n_nodes, r->n_wf,
                              nullptr, nullptr, r->best_p, r->best_d, r->best_cost, r->ratio, stream);

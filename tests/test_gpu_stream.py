@@ -264,3 +264,83 @@ def test_round_in_one_call_equals_its_four_calls(ctx):
         assert torch.equal(before, d_dec["used_tok"])
     finally:
         other.close()
+
+
+def _round_buffers(torch, binding, rnd, seed):
+    """Device copies of one synthetic round: inputs, the outputs of the reveal and of the search, drains."""
+    d = rnd.dag
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    n, P, D = rnd.calls["n"], rnd.pre["n"], rnd.dec["n"]
+    rng = np.random.default_rng(seed)
+    return dict(
+        calls=binding.to_device(rnd.calls), pre=binding.to_device(rnd.pre), dec=binding.to_device(rnd.dec),
+        graph=dict(succ_row_ptr=dev(d.succ_row_ptr), succ_col_idx=dev(d.succ_col), wf_ptr=dev(d.wf_ptr),
+                   L_in=dev(d.L_in), L_out=dev(d.L_out),
+                   node_cost=torch.empty(d.n_nodes, **f32), rem=torch.empty(d.n_nodes, **f32),
+                   tail=torch.empty(d.n_nodes, **f32), level=torch.empty(d.n_nodes, **i32), horizon=torch.empty(d.n_wf, **f32)),
+        bp=torch.empty(n, **i32), bd=torch.empty(n, **i32), bc=torch.empty(n, **f32), ratio=torch.empty(n, **f32),
+        drains=[dev(rng.integers(0, 4000, P).astype(np.int32)), dev(rng.integers(0, 1500, D).astype(np.int32)),
+                dev(rng.integers(0, 6000, D).astype(np.int32))])
+
+
+def _round_state(b):
+    g = b["graph"]
+    return [x.cpu().numpy() for x in (g["node_cost"], g["rem"], g["tail"], g["level"], g["horizon"], b["bp"], b["bd"], b["bc"],
+                                      b["ratio"], b["pre"]["backlog_tok"], b["dec"]["used_tok"], b["dec"]["batch"], b["dec"]["qd_tok"])]
+
+
+@pytest.mark.parametrize("name,override", [
+    ("tiny", {}),
+    ("mid", {}),                                           # one prefill instance per lane
+    ("mid", dict(C=3000, P=100, D=70, T=3)),               # two per lane, ragged
+    ("mid", dict(C=9000, P=300, D=260, T=8)),              # four per lane, several calls per wavefront
+    ("mid", dict(C=700, P=5, D=600, T=2)),
+])
+def test_round_with_its_whole_graph_equals_its_three_calls(ctx, name, override):
+    # hx_round with the round's whole graph = hx_horizons -> hx_score_placements (fused, ratio) -> hx_commit:
+    # three consecutive rounds on two copies of the pool, everything bit for bit; then a plain hx_commit on both
+    import torch
+    from paper_2605_16637_amd import binding
+    rnd = synth.make_round(name, 3, **override)
+    links = binding.to_device(rnd.links)
+    tF, tB = dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"])
+    a, b = _round_buffers(torch, binding, rnd, 7), _round_buffers(torch, binding, rnd, 7)
+    for r in range(3):
+        g = a["graph"]
+        ctx.hx_horizons(rnd.model, g["succ_row_ptr"], g["succ_col_idx"], g["L_in"], g["L_out"], tF, tB, links, g["wf_ptr"],
+                        g["node_cost"], g["rem"], g["tail"], g["level"], g["horizon"])
+        ctx.hx_score_placements(rnd.model, a["calls"], a["pre"], a["dec"], links, tail=g["tail"], horizon=g["horizon"],
+                                best_p=a["bp"], best_d=a["bd"], best_cost=a["bc"], ratio=a["ratio"])
+        ctx.hx_commit(a["calls"], a["bp"], a["bd"], a["pre"]["backlog_tok"], a["dec"]["used_tok"], a["dec"]["batch"],
+                      a["dec"]["qd_tok"], *a["drains"])
+        ctx.hx_round(rnd.model, b["calls"], b["pre"], b["dec"], links, b["bp"], b["bd"], b["bc"], ratio=b["ratio"],
+                     type_flops=tF, type_hbm_bw=tB, drain_prefill=b["drains"][0], drain_decode_q=b["drains"][1],
+                     release_tok=b["drains"][2], graph=b["graph"])
+        ctx.hx_stream_status()
+        for x, y in zip(_round_state(a), _round_state(b)):
+            assert np.array_equal(x, y, equal_nan=True), f"round {r}"
+        assert (a["bp"] >= 0).any()
+    for s in (a, b):
+        ctx.hx_commit(s["calls"], s["bp"], s["bd"], s["pre"]["backlog_tok"], s["dec"]["used_tok"], s["dec"]["batch"],
+                      s["dec"]["qd_tok"], *s["drains"])
+    ctx.hx_stream_status()
+    for x, y in zip(_round_state(a), _round_state(b)):
+        assert np.array_equal(x, y, equal_nan=True)
+    # without the ratio, and with counters at the edge of int32: the same saturation, the same report
+    for s in (a, b):
+        s["pre"]["backlog_tok"].fill_(2147483000)
+    ctx.hx_score_placements(rnd.model, a["calls"], a["pre"], a["dec"], links, best_p=a["bp"], best_d=a["bd"], best_cost=a["bc"])
+    ctx.hx_commit(a["calls"], a["bp"], a["bd"], a["pre"]["backlog_tok"], a["dec"]["used_tok"], a["dec"]["batch"],
+                  a["dec"]["qd_tok"])
+    assert (a["bp"] >= 0).any()
+    with pytest.raises(binding.HxError) as e1:
+        ctx.hx_stream_status()
+    assert e1.value.code == -7     # HX_ERR_OVERFLOW
+    ctx.hx_round(rnd.model, b["calls"], b["pre"], b["dec"], links, b["bp"], b["bd"], b["bc"],
+                 type_flops=tF, type_hbm_bw=tB, graph=b["graph"])
+    with pytest.raises(binding.HxError) as e2:
+        ctx.hx_stream_status()
+    assert e2.value.code == -7
+    for x, y in zip(_round_state(a)[5:8] + _round_state(a)[9:], _round_state(b)[5:8] + _round_state(b)[9:]):
+        assert np.array_equal(x, y)
