@@ -199,8 +199,11 @@ __device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, 
 // STREAM: rem, level and tail leave with stores that do not claim cache lines (see the store phase).
 template <int NMAX, bool COST, bool STREAM>
 __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNode *s_node, int &s_any,
-                                                 const NodeCostArgs *nc, const CostTables *tab)
+                                                 const NodeCostArgs *nc, CostTables *tab)
 {
+    // COST: the class tables are filled once, by the block's first run, after that run's own loads have been asked
+    // for (the tables' loads and divisions then run under those instead of in front of them); block-uniform
+    bool tab_ready = !COST;
     constexpr int CP_NMAX = NMAX;             // nodes staged per run
     constexpr int CP_NPT = (NMAX + CP_THREADS - 1) / CP_THREADS;
     const int tid = threadIdx.x;
@@ -272,6 +275,11 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
                     deg[k] = rb[k] - ra[k];
                     if (deg[k] > CP_DEG || (deg[k] > 0 && ra[k] > e_last4)) { deg[k] = -1; s_any = wa + 1; }
                 }
+                if constexpr (COST) if (!tab_ready) {
+                    hx_cost_tables_fill(*tab, *nc, tid);
+                    __syncthreads();
+                    tab_ready = true;
+                }
                 // the costs are worked out (COST) and parked while the ids are on their way
 #pragma unroll
                 for (int k = 0; k < CP_NPT; ++k) {
@@ -335,6 +343,11 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
             __syncthreads();                            // the next run stages over these records
         } else {
             // walked in global memory
+            if constexpr (COST) if (!tab_ready) {
+                hx_cost_tables_fill(*tab, *nc, tid);
+                __syncthreads();
+                tab_ready = true;
+            }
             for (int v = we - 1; v >= ws; --v) {
                 int r0 = a.row_ptr[v], r1 = a.row_ptr[v + 1];
                 if (r0 < 0 || r1 > a.n_edges || r0 > r1) { bad_index = true; r0 = r1 = 0; }
@@ -382,8 +395,6 @@ void hx_cp_cost_kernel(CpArgs a, NodeCostArgs nc, int wpb)
     __shared__ CpNode s_node[CP_NMAX_COST + 1];
     __shared__ int s_any;
     __shared__ CostTables s_tab;
-    hx_cost_tables_fill(s_tab, nc, threadIdx.x);
-    __syncthreads();
     hx_cp_local_body<CP_NMAX_COST, true, false>(a, wpb, s_node, s_any, &nc, &s_tab);
 }
 
