@@ -344,3 +344,23 @@ def test_round_with_its_whole_graph_equals_its_three_calls(ctx, name, override):
     assert e2.value.code == -7
     for x, y in zip(_round_state(a)[5:8] + _round_state(a)[9:], _round_state(b)[5:8] + _round_state(b)[9:]):
         assert np.array_equal(x, y)
+
+
+def test_round_takes_one_form_of_reveal(ctx):
+    # new nodes for the context's graph, or the round's whole graph: both at once is refused before anything is enqueued
+    import torch
+    from paper_2605_16637_amd import binding
+    rnd = synth.make_round("tiny", 1)
+    links = binding.to_device(rnd.links)
+    tF, tB = dev(rnd.types["flops"]), dev(rnd.types["hbm_bw"])
+    b = _round_buffers(torch, binding, rnd, 1)
+    before = [x.clone() for x in (b["pre"]["backlog_tok"], b["dec"]["used_tok"])]
+    one = dev(np.zeros(1, np.int32))
+    with pytest.raises(binding.HxError) as e:
+        ctx.hx_round(rnd.model, b["calls"], b["pre"], b["dec"], links, b["bp"], b["bd"], b["bc"], ratio=b["ratio"],
+                     parent_row_ptr=dev(np.zeros(2, np.int32)), parent_col_idx=None, new_L_in=one, new_L_out=one, new_wf=one,
+                     new_cost=torch.empty(1, device="cuda:0"), type_flops=tF, type_hbm_bw=tB, graph=b["graph"])
+    assert e.value.code == -1      # HX_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.equal(before[0], b["pre"]["backlog_tok"]) and torch.equal(before[1], b["dec"]["used_tok"])
+    ctx.hx_stream_status()
