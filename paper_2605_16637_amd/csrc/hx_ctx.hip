@@ -412,7 +412,7 @@ extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best
     HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
     hipStream_t stream = (hipStream_t)stream_;
     CommitArgs a{C, P, D, calls->L_in, calls->L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
-                 drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, ctx->d_acc, ctx->d_status};
+                 drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, ctx->d_acc, ctx->d_status, nullptr};
     if (C <= HX_COMMIT_ONE_LAUNCH) {
         hx_commit_one_kernel<<<1, COMMIT_ONE_THREADS, 0, stream>>>(a);
         return hx_check_launch(ctx, "hx_commit_one_kernel");
@@ -452,7 +452,7 @@ extern "C" int hx_commit_static(const hx_calls *calls, const int32_t *best_p, co
     hipStream_t stream = (hipStream_t)stream_;
     CommitArgs a{C, P, D, calls->L_in, calls->L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
                  drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, acc,
-                 status ? status : (int32_t *)(acc + HX_STATIC_ACC)};
+                 status ? status : (int32_t *)(acc + HX_STATIC_ACC), nullptr};
     // the array keeps what the last call left: start from zero whatever that was
     // (a fill kernel, so that the call can be captured in a graph)
     hx_commit_clear_kernel<<<(P + 2 * D + 255) / 256, 256, 0, stream>>>(a);
