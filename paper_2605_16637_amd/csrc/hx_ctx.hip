@@ -1,5 +1,7 @@
 // Context life cycle, stream status and the commit-and-drain step.
 #include "hx_common.hpp"
+#include "hx_search.hpp"
+#include "hx_cp.hpp"
 
 void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
 int hx_dag_append_with_cost(hx_ctx *ctx, const hx_model *model, int32_t n_new, int32_t n_new_edges,
@@ -8,6 +10,11 @@ int hx_dag_append_with_cost(hx_ctx *ctx, const hx_model *model, int32_t n_new, i
                             int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
                             float *new_cost, const int32_t *new_wf, void *stream);   // hx_dag.hip
 int hx_score_init();                // hx_score.hip
+int hx_reveal_search(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                     const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
+                     const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                     int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                     const HxHorizonsPlan *reveal, bool *revealed, void *stream);   // hx_score.hip
 int hx_plan_init();                 // hx_plan.hip
 int hx_decode_init();               // hx_decode.hip
 
@@ -32,6 +39,15 @@ struct CommitArgs {
     unsigned long long *acc;    // [P] backlog, [D] used, [D] qd additions of this round
     int32_t *status;
     int32_t *ticket;            // workgroups of the adding kernel that have delivered their sums (0 between launches); NULL: a drain launch follows
+};
+
+// The urgency fold of the same calls (Eq. (2)), for a round whose search ran before its horizons were there: the
+// commit kernels form it as they pass over the calls.  ratio == NULL: no fold.
+struct RatioArgs {
+    const int32_t *node, *wf;
+    const float *elapsed, *tail, *horizon, *best_cost;
+    int n_nodes, n_wf;
+    float *ratio;
 };
 
 __global__ __launch_bounds__(256) void hx_commit_clear_kernel(CommitArgs a)
@@ -82,7 +98,7 @@ __device__ __forceinline__ int hx_add_sat_drain(int cur, unsigned long long add,
 // additions commute, so the result does not depend on call order.  Every wave
 // first combines its calls per instance, every block sums into an LDS copy of
 // the counters, and only the non-zero sums reach the global accumulators.
-__global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
+__global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a, RatioArgs rt)
 {
     __shared__ unsigned long long s_acc[3 * HX_MAX_INSTANCES];
     const int n_acc = a.P + 2 * a.D;
@@ -95,6 +111,8 @@ __global__ __launch_bounds__(256) void hx_commit_add_kernel(CommitArgs a)
         const int c = it * stride + blockIdx.x * blockDim.x + threadIdx.x;
         int p = -1, d = -1, L = 0, O = 0;
         if (c < a.C) { p = a.best_p[c]; d = a.best_d[c]; L = a.L_in[c]; O = a.L_out[c]; }
+        if (rt.ratio && c < a.C)
+            hx_projected_ratio(rt.node, rt.wf, rt.elapsed, rt.tail, rt.horizon, rt.n_nodes, rt.n_wf, c, rt.best_cost[c], a.status, rt.ratio);
         bool valid = p >= 0 && d >= 0;                      // otherwise the call stays queued
         if (valid && (p >= a.P || d >= a.D || L < 0 || O < 0)) { bad = true; valid = false; }
         hx_add_by_key(s_acc, valid, p, (unsigned long long)L, nullptr, 0ull);
@@ -142,7 +160,7 @@ constexpr int COMMIT_ONE_THREADS = 1024;
 // round).  Measured: 4096 calls already take it 2 us longer than the two launches (chosen placements concentrate
 // on few instances, and lanes that meet on a counter wait for each other), 16384 calls 30 us longer.
 constexpr int HX_COMMIT_ONE_LAUNCH = 1024;
-__global__ __launch_bounds__(COMMIT_ONE_THREADS) void hx_commit_one_kernel(CommitArgs a)
+__global__ __launch_bounds__(COMMIT_ONE_THREADS) void hx_commit_one_kernel(CommitArgs a, RatioArgs rt)
 {
     __shared__ unsigned long long s_acc[3 * HX_MAX_INSTANCES];
     const int n_acc = a.P + 2 * a.D;
@@ -154,6 +172,8 @@ __global__ __launch_bounds__(COMMIT_ONE_THREADS) void hx_commit_one_kernel(Commi
         const int c = it * COMMIT_ONE_THREADS + threadIdx.x;
         int p = -1, d = -1, L = 0, O = 0;
         if (c < a.C) { p = a.best_p[c]; d = a.best_d[c]; L = a.L_in[c]; O = a.L_out[c]; }
+        if (rt.ratio && c < a.C)
+            hx_projected_ratio(rt.node, rt.wf, rt.elapsed, rt.tail, rt.horizon, rt.n_nodes, rt.n_wf, c, rt.best_cost[c], a.status, rt.ratio);
         bool valid = p >= 0 && d >= 0;
         if (valid && (p >= a.P || d >= a.D || L < 0 || O < 0)) { bad = true; valid = false; }
         if (valid) {       // LDS atomics: lanes that meet on a counter are serialised there, nowhere else
@@ -390,14 +410,16 @@ extern "C" int hx_stream_status(hx_ctx *ctx, void *stream_)
     return HX_OK;
 }
 
-extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
-                         int32_t P, int32_t *backlog_tok,
-                         int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
-                         const int32_t *drain_prefill, const int32_t *drain_decode_q,
-                         const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
-                         void *stream_)
+namespace {
+
+// hx_commit, with the urgency fold of the same calls in the same launch when rt.ratio is given
+int commit_round(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
+                 int32_t P, int32_t *backlog_tok,
+                 int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
+                 const int32_t *drain_prefill, const int32_t *drain_decode_q,
+                 const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
+                 const RatioArgs &rt, void *stream_)
 {
-    if (!ctx) return HX_ERR_INVALID_ARG;
     HX_REQUIRE(ctx, calls, HX_ERR_INVALID_ARG, "NULL calls");
     const int C = calls->n;
     HX_REQUIRE(ctx, C >= 0 && P >= 0 && D >= 0, HX_ERR_INVALID_ARG, "negative size");
@@ -414,14 +436,28 @@ extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best
     CommitArgs a{C, P, D, calls->L_in, calls->L_out, best_p, best_d, backlog_tok, used_tok, batch, qd_tok,
                  drain_prefill, drain_decode_q, release_tok, tokens_per_seq, max_batch, ctx->d_acc, ctx->d_status, nullptr};
     if (C <= HX_COMMIT_ONE_LAUNCH) {
-        hx_commit_one_kernel<<<1, COMMIT_ONE_THREADS, 0, stream>>>(a);
+        hx_commit_one_kernel<<<1, COMMIT_ONE_THREADS, 0, stream>>>(a, rt);
         return hx_check_launch(ctx, "hx_commit_one_kernel");
     }
     int grid = (C + 255) / 256;
     grid = grid > ctx->num_cu ? ctx->num_cu : grid;
     a.ticket = ctx->d_ticket;                  // the workgroup that finishes last applies the drains
-    hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a);
+    hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a, rt);
     return hx_check_launch(ctx, "hx_commit_add_kernel");
+}
+
+}  // namespace
+
+extern "C" int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
+                         int32_t P, int32_t *backlog_tok,
+                         int32_t D, int32_t *used_tok, int32_t *batch, int32_t *qd_tok,
+                         const int32_t *drain_prefill, const int32_t *drain_decode_q,
+                         const int32_t *release_tok, int32_t tokens_per_seq, int32_t max_batch,
+                         void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    return commit_round(ctx, calls, best_p, best_d, P, backlog_tok, D, used_tok, batch, qd_tok, drain_prefill, drain_decode_q,
+                        release_tok, tokens_per_seq, max_batch, RatioArgs{}, stream_);
 }
 
 extern "C" int hx_commit_static(const hx_calls *calls, const int32_t *best_p, const int32_t *best_d,
@@ -459,7 +495,7 @@ extern "C" int hx_commit_static(const hx_calls *calls, const int32_t *best_p, co
     if (C > 0) {
         int grid = (C + 255) / 256;
         grid = grid > 256 ? 256 : grid;
-        hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a);
+        hx_commit_add_kernel<<<grid, 256, 0, stream>>>(a, RatioArgs{});
     }
     const int n_inst = P > D ? P : D;
     hx_commit_drain_kernel<<<(n_inst + 255) / 256, 256, 0, stream>>>(a);
@@ -520,6 +556,27 @@ extern "C" int hx_round(hx_ctx *ctx, const hx_model *model, const hx_round_args 
     const float *tail = nullptr, *horizon = nullptr;
     int32_t n_nodes = 0;
     if (r->n_nodes > 0) {
+        // A small round's horizon refresh rides in the search's launch and its ratio in the commit's: two launches
+        // instead of three, the two chains of memory round trips side by side.  Only where every argument check of
+        // the three calls passes and the round fits (else nothing has been launched and the calls follow one
+        // after the other, each reporting what it finds).
+        HxHorizonsPlan plan;
+        const int P = r->prefill.n, D = r->decode.n;
+        const bool commit_ok = r->calls.n > 0 && P > 0 && D > 0 && P <= HX_MAX_INSTANCES && D <= HX_MAX_INSTANCES &&
+                               r->tokens_per_seq > 0 && r->max_batch >= 0 && r->backlog_tok && r->used_tok && r->batch && r->qd_tok;
+        bool revealed = false;
+        if (commit_ok &&
+            hx_horizons_plan(ctx, model, r->n_nodes, r->n_edges, r->succ_row_ptr, r->succ_col_idx, r->node_L_in, r->node_L_out,
+                             r->n_types, r->type_flops, r->type_hbm_bw, &r->links, r->n_wf, r->wf_ptr,
+                             r->node_cost, r->rem, r->tail, r->level, r->horizon, &plan) == HX_OK &&
+            hx_reveal_search(ctx, model, &r->calls, &r->prefill, &r->decode, &r->links, r->tail, r->horizon, r->n_nodes, r->n_wf,
+                             r->best_p, r->best_d, r->best_cost, r->ratio, &plan, &revealed, stream) == HX_OK &&
+            revealed) {
+            const RatioArgs rt{r->calls.node, r->calls.wf, r->calls.elapsed, r->tail, r->horizon, r->best_cost,
+                               r->n_nodes, r->n_wf, r->ratio};
+            return commit_round(ctx, &r->calls, r->best_p, r->best_d, P, r->backlog_tok, D, r->used_tok, r->batch, r->qd_tok,
+                                r->drain_prefill, r->drain_decode_q, r->release_tok, r->tokens_per_seq, r->max_batch, rt, stream);
+        }
         rc = hx_horizons(ctx, model, r->n_nodes, r->n_edges, r->succ_row_ptr, r->succ_col_idx, r->node_L_in, r->node_L_out,
                          r->n_types, r->type_flops, r->type_hbm_bw, &r->links, r->n_wf, r->wf_ptr,
                          r->node_cost, r->rem, r->tail, r->level, r->horizon, stream);

@@ -23,13 +23,12 @@
 #include "hx_common.hpp"
 #include "hx_terms.hpp"
 #include "hx_search.hpp"
+#include "hx_cp.hpp"
 
 #include <cfloat>
 #include <cmath>
 
 namespace {
-
-constexpr int kT = HX_MAX_TYPES;
 
 // ---- prepare ------------------------------------------------------------------
 
@@ -301,10 +300,11 @@ struct FusedLds {
     __host__ __device__ size_t bytes(int waves) const { return 4 * (block_floats() + waves * wave_floats()); }
 };
 
+// block, n_blocks: the workgroup's place among those that search (the launch may hold other workgroups too)
 template <int KP>
-__global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound)
+__device__ __forceinline__ void hx_fused_search_body(const ScoreArgs &a, const PrepArgs &pa, int dp_bound, float *smem,
+                                                     int block, int n_blocks)
 {
-    extern __shared__ __align__(16) float smem[];
     const FusedLds lay(dp_bound, a.P);
     float *s_wait = smem;                  // 7 decode arrays of dp_bound entries
     float *s_c1 = s_wait + lay.Dp;
@@ -332,8 +332,8 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
     // What the wave's first call says of itself is asked for before the pool's tables are derived, and every
     // later call's while the call before it is searched: the loads are wave-uniform (scalar), and none of the
     // kernel's chains of dependent memory round trips waits for them on its own.
-    const int gw = blockIdx.x * waves_per_block + wave;
-    const int nw = gridDim.x * waves_per_block;
+    const int gw = block * waves_per_block + wave;
+    const int nw = n_blocks * waves_per_block;
     const bool want_ratio = a.ratio != nullptr;
     int c = gw;
     int L = 0, O = 0, nd = 0, w = 0;
@@ -380,6 +380,43 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
         }
         c = cn; L = Ln; O = On; nd = ndn; w = wn; el = eln;
     }
+}
+
+template <int KP>
+__global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound)
+{
+    extern __shared__ __align__(16) float smem[];
+    hx_fused_search_body<KP>(a, pa, dp_bound, smem, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// ---- the first kernel of a small scheduling round: reveal and search in one launch ------------------
+//
+// A round whose search is short (every wavefront has at most one call, all workgroups resident at once) spends
+// its time in the latencies of its launches and of their chains of memory round trips, not in arithmetic.  The
+// horizon refresh (node cost + critical path, what hx_cp_cost_kernel does) and the search do not depend on each
+// other -- only the ratio needs both, and it is formed by the commit kernel that follows -- so they share a launch:
+// the first n_reveal workgroups take workflows exactly as hx_cp_cost_kernel's do (same body, the cost's class pairs
+// one after the other to stay within the search's registers), the others search.  Same results as the two
+// kernels, one launch and the gap before it less, and the two latency chains run side by side.
+constexpr int RV_NMAX = 256;             // nodes staged per run of a reveal workgroup
+
+struct RevealLds {
+    CpNode node[RV_NMAX + 1];
+    CostTables tab;
+    int any;
+};
+
+template <int KP>
+__global__ __launch_bounds__(CP_THREADS) void hx_reveal_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound, CpArgs cp,
+                                                                      NodeCostArgs nc, int wpb, int n_reveal)
+{
+    extern __shared__ __align__(16) float smem[];
+    if ((int)blockIdx.x < n_reveal) {
+        RevealLds *l = (RevealLds *)smem;
+        hx_cp_local_body<RV_NMAX, true, false, true>(cp, wpb, l->node, l->any, &nc, &l->tab);
+        return;
+    }
+    hx_fused_search_body<KP>(a, pa, dp_bound, smem, (int)blockIdx.x - n_reveal, (int)gridDim.x - n_reveal);
 }
 
 // ---- materialised tensor ------------------------------------------------------------
@@ -618,26 +655,29 @@ int hx_prepare_pool(hx_ctx *ctx, const hx_model *model, const hx_prefill_tab *pr
 int hx_score_init()
 {
     const int lds = 160 * 1024;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_fused_search_kernel<1>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_fused_search_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(hx_fused_search_kernel<4>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    const void *kernels[] = {
+        reinterpret_cast<const void *>(hx_fused_search_kernel<1>), reinterpret_cast<const void *>(hx_fused_search_kernel<2>),
+        reinterpret_cast<const void *>(hx_fused_search_kernel<4>), reinterpret_cast<const void *>(hx_reveal_search_kernel<1>),
+        reinterpret_cast<const void *>(hx_reveal_search_kernel<2>), reinterpret_cast<const void *>(hx_reveal_search_kernel<4>)};
+    hipError_t e = hipSuccess;
+    for (const void *k : kernels)
+        if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return e == hipSuccess ? HX_OK : HX_ERR_DEVICE;
 }
 
-extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
-                                   const hx_prefill_tab *pre, const hx_decode_tab *dec,
-                                   const hx_links *links,
-                                   const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
-                                   float *cost, uint8_t *feas,
-                                   int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
-                                   void *stream_)
+namespace {
+
+// reveal: NULL, or the horizon refresh of the same round (hx_horizons_plan), to ride in the search's launch if the
+// round is small enough for that: *revealed says whether it did.  With a reveal the ratio is only checked, not
+// written -- the horizons are not there yet; the caller forms it afterwards -- and nothing but the fused search is
+// launched: if the reveal does not fit, nothing at all is, and the caller makes the calls one after the other.
+int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                     const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
+                     const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                     float *cost, uint8_t *feas,
+                     int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                     const HxHorizonsPlan *reveal, bool *revealed, void *stream_)
 {
-    if (!ctx) return HX_ERR_INVALID_ARG;
     HX_REQUIRE(ctx, model && calls && pre && dec && links, HX_ERR_INVALID_ARG, "NULL table");
     const int C = calls->n, P = pre->n, D = dec->n, T = links->n_types;
     HX_REQUIRE(ctx, C >= 0 && P >= 0 && D >= 0, HX_ERR_INVALID_ARG, "negative size");
@@ -670,9 +710,10 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
     a.L_in = calls->L_in; a.L_out = calls->L_out; a.node = calls->node; a.wf = calls->wf;
     a.elapsed = calls->elapsed; a.tail = tail; a.horizon = horizon; a.n_nodes = n_nodes; a.n_wf = n_wf;
     a.prep = ctx->d_prep;
-    a.best_p = best_p; a.best_d = best_d; a.best_cost = best_cost; a.ratio = ratio;
+    a.best_p = best_p; a.best_d = best_d; a.best_cost = best_cost; a.ratio = reveal ? nullptr : ratio;
     a.cost = cost; a.feas = feas; a.status = ctx->d_status;
 
+    if (reveal && (P == 0 || D == 0 || !fused || cost || feas || reveal->grid == 0)) return HX_OK;      // not this way
     if (P == 0 || D == 0) {
         if (fused) {
             hx_no_pool_kernel<<<(C + 255) / 256, 256, 0, stream>>>(a);
@@ -691,6 +732,25 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         // workgroup size): the pool tables are per workgroup, a wavefront adds its decode-time and transfer
         // buffers.  Whichever size puts more wavefronts on a SIMD.
         const FusedLds lay(dp_bound, P);
+        if (reveal) {
+            // workgroups of four wavefronts, a call per wavefront, everything resident at once: else not this way
+            const size_t lds4 = lay.bytes(4) > sizeof(RevealLds) ? lay.bytes(4) : sizeof(RevealLds);
+            const long long per_cu = (long long)(160 * 1024) / (long long)lds4 < 6 ? (long long)(160 * 1024) / (long long)lds4 : 6;
+            const int n_search = (C + 3) / 4;
+            const long long nodes_per_unit = (long long)reveal->a.n_nodes * reveal->wpb / (reveal->a.n_wf > 0 ? reveal->a.n_wf : 1);
+            if (lds4 > 160 * 1024 || (long long)n_search + reveal->grid > per_cu * ctx->num_cu || nodes_per_unit > RV_NMAX / 2)
+                return HX_OK;
+            auto launch = [&](auto kern) {
+                kern<<<reveal->grid + n_search, CP_THREADS, lds4, stream>>>(a, pa, dp_bound, reveal->a, reveal->nc, reveal->wpb,
+                                                                            reveal->grid);
+            };
+            if (P <= 64) launch(hx_reveal_search_kernel<1>);
+            else if (P <= 128) launch(hx_reveal_search_kernel<2>);
+            else launch(hx_reveal_search_kernel<4>);
+            if (int rc = hx_check_launch(ctx, "hx_reveal_search_kernel")) return rc;
+            *revealed = true;
+            return HX_OK;
+        }
         const int reg_limit = 6 * 4;                               // wavefronts per compute unit
         int waves = 4, blocks_per_cu = 1, best_on_cu = 0;
         for (int w = 4; w <= 8; w += 4) {
@@ -722,6 +782,35 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
         if (int rc = hx_check_launch(ctx, "hx_materialise_kernel")) return rc;
     }
     return HX_OK;
+}
+
+}  // namespace
+
+extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                                   const hx_prefill_tab *pre, const hx_decode_tab *dec,
+                                   const hx_links *links,
+                                   const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                                   float *cost, uint8_t *feas,
+                                   int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                                   void *stream_)
+{
+    if (!ctx) return HX_ERR_INVALID_ARG;
+    return score_placements(ctx, model, calls, pre, dec, links, tail, horizon, n_nodes, n_wf, cost, feas,
+                            best_p, best_d, best_cost, ratio, nullptr, nullptr, stream_);
+}
+
+// The horizon refresh `reveal` and hx_score_placements (fused outputs) in one launch, where the round is small
+// enough (*revealed; otherwise nothing has been launched).  ratio is checked like hx_score_placements' but not
+// written: the caller forms it once the launch has produced the horizons (the commit kernel does).
+int hx_reveal_search(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                     const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
+                     const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                     int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                     const HxHorizonsPlan *reveal, bool *revealed, void *stream_)
+{
+    *revealed = false;
+    return score_placements(ctx, model, calls, pre, dec, links, tail, horizon, n_nodes, n_wf, nullptr, nullptr,
+                            best_p, best_d, best_cost, ratio, reveal, revealed, stream_);
 }
 
 extern "C" int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const float *cost,
