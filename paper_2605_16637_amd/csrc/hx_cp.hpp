@@ -73,21 +73,25 @@ __device__ __forceinline__ float hx_node_cost_eval(const HxModelF &m, const Cost
 }
 
 
-// The same minimum with the class pairs taken one after the other instead of all at once: a dozen registers
-// instead of two hundred, for kernels whose other work sets the register budget.  Every pair's cost is formed by
-// the same functions on the same values, and a minimum does not depend on the order: the same bits.
+// The same minimum with the prefill classes taken one after the other instead of all pairs at once: some twenty
+// registers instead of two hundred, for kernels whose other work sets the register budget.  Every pair's cost is
+// formed by the same functions on the same values, and a minimum does not depend on the order: the same bits.
 __device__ __forceinline__ float hx_node_cost_eval_rolled(const HxModelF &m, const CostTables &t, int T, int L, int O)
 {
     const HxCallF cf = hx_call_terms(m, L, O);
+    float dec[kT];
+#pragma unroll
+    for (int td = 0; td < kT; ++td) dec[td] = td < T ? hx_decode_time(cf, t.c1[td], t.c2[td], t.kB[td]) : INFINITY;
     float best = INFINITY;
 #pragma unroll 1
     for (int tp = 0; tp < T; ++tp) {
         const float done = hx_prefill_done(cf, 0.0f, t.invF[tp], t.invB[tp]);
-#pragma unroll 1
-        for (int td = 0; td < T; ++td) {
-            const float dec = hx_decode_time(cf, t.c1[td], t.c2[td], t.kB[td]);
-            const float x = hx_transfer(cf, t.invbw[tp * kT + td], t.lat[tp * kT + td]);
-            best = fminf(best, hx_candidate(done + x, 0.0f, dec));
+#pragma unroll
+        for (int td = 0; td < kT; ++td) {
+            if (td < T) {
+                const float x = hx_transfer(cf, t.invbw[tp * kT + td], t.lat[tp * kT + td]);
+                best = fminf(best, hx_candidate(done + x, 0.0f, dec[td]));
+            }
         }
     }
     return best;

@@ -398,7 +398,7 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
 // the first n_reveal workgroups take workflows exactly as hx_cp_cost_kernel's do (same body, the cost's class pairs
 // one after the other to stay within the search's registers), the others search.  Same results as the two
 // kernels, one launch and the gap before it less, and the two latency chains run side by side.
-constexpr int RV_NMAX = 256;             // nodes staged per run of a reveal workgroup
+constexpr int RV_NMAX = 512;             // nodes staged per run of a reveal workgroup
 
 struct RevealLds {
     CpNode node[RV_NMAX + 1];
@@ -733,13 +733,21 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
         // buffers.  Whichever size puts more wavefronts on a SIMD.
         const FusedLds lay(dp_bound, P);
         if (reveal) {
-            // workgroups of four wavefronts, a call per wavefront, everything resident at once: else not this way
+            // Workgroups of four wavefronts, as many searching ones as are resident at once (six per compute unit, or
+            // what local memory allows) or as the calls need, whichever is less; the reveal's workgroups come first in
+            // the grid and run first.  Where the searching workgroups alone fill the chip, the last of them start when
+            // the reveal's have gone -- and those are the ones whose wavefronts have the fewest calls (calls are dealt
+            // c, c + n, ...), so they still end before the others.  Not this way if the reveal's units are too large
+            // for its staging area or its workgroups more than a third of the searching ones.
             const size_t lds4 = lay.bytes(4) > sizeof(RevealLds) ? lay.bytes(4) : sizeof(RevealLds);
-            const long long per_cu = (long long)(160 * 1024) / (long long)lds4 < 6 ? (long long)(160 * 1024) / (long long)lds4 : 6;
-            const int n_search = (C + 3) / 4;
+            if (lds4 > 160 * 1024) return HX_OK;
+            const long long by_lds = (long long)(160 * 1024) / (long long)lds4;
+            const long long resident = (by_lds < 6 ? by_lds : 6) * ctx->num_cu;
+            const long long need4 = (C + 3) / 4;
+            const int n_search = (int)(need4 < resident ? need4 : resident);
             const long long nodes_per_unit = (long long)reveal->a.n_nodes * reveal->wpb / (reveal->a.n_wf > 0 ? reveal->a.n_wf : 1);
-            if (lds4 > 160 * 1024 || (long long)n_search + reveal->grid > per_cu * ctx->num_cu || nodes_per_unit > RV_NMAX / 2)
-                return HX_OK;
+            const bool all_resident = need4 + reveal->grid <= resident;
+            if (nodes_per_unit > RV_NMAX * 7 / 10 || !(all_resident || 3LL * reveal->grid <= n_search)) return HX_OK;
             auto launch = [&](auto kern) {
                 kern<<<reveal->grid + n_search, CP_THREADS, lds4, stream>>>(a, pa, dp_bound, reveal->a, reveal->nc, reveal->wpb,
                                                                             reveal->grid);
