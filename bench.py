@@ -135,7 +135,8 @@ class RoundOnDevice:
         self.commit()
 
     def round_call(self):
-        """One round as one library call (hx_round with the round's whole graph)."""
+        """One round as one library call (hx_round with the round's whole graph): two launches where the round
+        fits -- the horizon refresh in the search's launch, the ratio in the commit's."""
         g = dict(succ_row_ptr=self.row_ptr, succ_col_idx=self.col, wf_ptr=self.wf_ptr, L_in=self.L_in, L_out=self.L_out,
                  node_cost=self.cost, rem=self.rem, tail=self.tail, level=self.level, horizon=self.hor)
         self.ctx.hx_round(self.rnd.model, self.calls, self.pre, self.dec, self.links, self.bp, self.bd, self.bc,
@@ -581,7 +582,7 @@ def round_latency(torch, ctx, synth, name, seed, eager, rounds=500):
         runs = {"hip graph replay, one stream": capture(torch, rd.step).replay,
                 "hip graph replay, horizons beside the search": capture(torch, rd.step_overlapped).replay,
                 "prepared launches, one stream": ctx.prepare(rd.step),
-                "hx_round, arguments marshalled ahead": ctx.prepare(rd.round_call)}
+                "hx_round (two launches), arguments marshalled ahead": ctx.prepare(rd.round_call)}
     lat = {k: [] for k in runs}
     names = list(runs)
     for i in range(len(names) * (rounds + 20)):
@@ -618,7 +619,8 @@ def main():
     ap.add_argument("--launch", default="auto", choices=["auto", "eager", "graph", "prepared", "round"],
                     help="how the timed steps are launched: the round's three library calls from the host, one launch after "
                          "the other (eager; prepared = their arguments marshalled once), as replays of a HIP graph, or as "
-                         "one hx_round call (arguments marshalled once); auto = the fastest of them in a short untimed trial")
+                         "one hx_round call (two launches: the horizon refresh rides in the search's, the ratio in the "
+                         "commit's; arguments marshalled once); auto = the fastest of them in a short untimed trial")
     ap.add_argument("--eager", action="store_true", help="same as --launch eager")
     ap.add_argument("--overlap", action="store_true",
                     help="run the horizon refresh on a second stream beside the search (measured: 3-4 us slower per round "
@@ -690,12 +692,16 @@ def main():
                    "calls": C, "prefill": P, "decode": D, "candidates_per_round": n_cand,
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
                    "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
-                            if args.overlap else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
+                            if args.overlap else
+                            "hx_round: [node cost + critical path] and [fused score+argmin] in one launch -> commit with the ratio (one launch)"
+                            if launch == "round" else "node cost + critical path (one launch) -> fused score+argmin+ratio -> commit"),
                    "launch": {"eager": "eager, the host enqueues ahead of the GPU", "graph": "hip graph replay",
                               "prepared": "eager launches with pre-marshalled arguments, the host enqueues ahead of the GPU",
-                              "round": "one hx_round call per step, arguments marshalled once, the host enqueues ahead of the GPU"}[launch],
+                              "round": "one hx_round call per step (two launches), arguments marshalled once, the host enqueues ahead of the GPU"}[launch],
                    "seed": args.seed},
-        "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups)", "bound": "alu",
+        "roofline": {"kernel": "hx_fused_search_kernel (derives the pool's per-round tables in its own workgroups); in an hx_round step the "
+                               "same search runs as hx_reveal_search_kernel, with the horizon refresh's workgroups in the same launch",
+                     "bound": "alu",
                      "achieved": achieved, "peak": ALU_PEAK_TOPS,
                      "unit": "T lane-ops/s on the SIMDs' main fp32 pipe (v_max_f32, v_min3_f32: 1.5 per candidate; the v_add_f32 pairs with them on the second pipe)",
                      "frac": achieved / ALU_PEAK_TOPS,

@@ -376,7 +376,13 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
  * scheduler that rebuilds the ready workflows' DAGs per invocation): then the
  * reveal is hx_horizons on the arrays given (same requirements on the
  * numbering, same outputs) and the ratio uses their tail and horizon;
- * hx_dag_reserve is needed for the first form only.
+ * hx_dag_reserve is needed for the first form only.  Such a round is made in
+ * two launches instead of three where every argument check of the three calls
+ * passes and the graph's workflows are small enough to be staged 512 nodes at
+ * a time: the horizon refresh and the search, which do not depend on each
+ * other, share a launch, and the ratio is formed by the commit's launch.  The
+ * results are the same bit for bit; in any other case the three calls are made
+ * one after the other.
  */
 typedef struct {
     /* reveal */
