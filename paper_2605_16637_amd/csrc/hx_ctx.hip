@@ -2,19 +2,20 @@
 #include "hx_common.hpp"
 #include "hx_search.hpp"
 #include "hx_cp.hpp"
+#include "hx_append.hpp"
 
 void hx_dag_release(hx_ctx *ctx);   // hx_dag.hip
-int hx_dag_append_with_cost(hx_ctx *ctx, const hx_model *model, int32_t n_new, int32_t n_new_edges,
-                            const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
-                            const int32_t *new_L_in, const int32_t *new_L_out,
-                            int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
-                            float *new_cost, const int32_t *new_wf, void *stream);   // hx_dag.hip
 int hx_score_init();                // hx_score.hip
 int hx_reveal_search(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
                      const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
                      const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
                      int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
                      const HxHorizonsPlan *reveal, bool *revealed, void *stream);   // hx_score.hip
+int hx_relax_search(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                    const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
+                    const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                    int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                    const HxAppendPlan *walks, bool *merged, void *stream);         // hx_score.hip
 int hx_plan_init();                 // hx_plan.hip
 int hx_decode_init();               // hx_decode.hip
 
@@ -583,11 +584,40 @@ extern "C" int hx_round(hx_ctx *ctx, const hx_model *model, const hx_round_args 
         if (rc != HX_OK) return rc;
         if (r->ratio) { tail = r->tail; horizon = r->horizon; n_nodes = r->n_nodes; }
     } else {
+        // The append's walks ride in the search's launch, and the ratio in the commit's, where every argument check
+        // passes and the search is large enough beside them: four launches instead of five, the walks' chain of
+        // memory round trips under the search.  Else the walks are a launch of their own and the calls follow.
+        HxAppendPlan ap{};
+        bool merged = false;
         if (r->n_new > 0) {
-            rc = hx_dag_append_with_cost(ctx, model, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx,
-                                         r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw, &r->links,
-                                         r->new_cost, r->new_wf, stream);
+            rc = hx_dag_append_begin(ctx, model, r->n_new, r->n_new_edges, r->parent_row_ptr, r->parent_col_idx,
+                                     r->new_L_in, r->new_L_out, r->n_types, r->type_flops, r->type_hbm_bw, &r->links,
+                                     r->new_cost, r->new_wf, &ap, stream);
             if (rc != HX_OK) return rc;
+        }
+        if (ap.grid > 0) {
+            const int P = r->prefill.n, D = r->decode.n;
+            const bool commit_ok = r->calls.n > 0 && P > 0 && D > 0 && P <= HX_MAX_INSTANCES && D <= HX_MAX_INSTANCES &&
+                                   r->tokens_per_seq > 0 && r->max_batch >= 0 && r->backlog_tok && r->used_tok && r->batch && r->qd_tok;
+            const float *g_tail = nullptr, *g_hor = nullptr;
+            int32_t g_nodes = 0;
+            if (commit_ok && hx_dag_view(ctx, nullptr, &g_tail, nullptr, &g_hor, &g_nodes) == HX_OK &&
+                hx_relax_search(ctx, model, &r->calls, &r->prefill, &r->decode, &r->links, g_tail, g_hor, g_nodes + r->n_new, r->n_wf,
+                                r->best_p, r->best_d, r->best_cost, r->ratio, &ap, &merged, stream) != HX_OK)
+                merged = false;
+            if (!merged) {
+                rc = hx_dag_append_walks(ctx, &ap, stream);
+                if (rc != HX_OK) return rc;
+            }
+            rc = hx_dag_append_end(ctx, &ap, stream);
+            if (rc != HX_OK) return rc;
+            if (merged) {
+                rc = hx_dag_view(ctx, nullptr, &g_tail, nullptr, &g_hor, &g_nodes);
+                if (rc != HX_OK) return rc;
+                const RatioArgs rt{r->calls.node, r->calls.wf, r->calls.elapsed, g_tail, g_hor, r->best_cost, g_nodes, r->n_wf, r->ratio};
+                return commit_round(ctx, &r->calls, r->best_p, r->best_d, P, r->backlog_tok, D, r->used_tok, r->batch, r->qd_tok,
+                                    r->drain_prefill, r->drain_decode_q, r->release_tok, r->tokens_per_seq, r->max_batch, rt, stream);
+            }
         }
         if (r->ratio) {
             rc = hx_dag_view(ctx, nullptr, &tail, nullptr, &horizon, &n_nodes);

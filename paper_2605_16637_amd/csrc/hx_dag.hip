@@ -13,6 +13,7 @@
 #include "hx_common.hpp"
 #include "hx_terms.hpp"
 #include "hx_cp.hpp"
+#include "hx_append.hpp"
 
 #include <cmath>
 
@@ -117,67 +118,6 @@ __global__ __launch_bounds__(256) void hx_cp_finish_kernel(CpArgs a, const int32
 
 // ---- incremental append ------------------------------------------------------------------
 
-struct AppendArgs {
-    int n_old, n_new, e_old, n_new_edges, cap_wf;
-    const int32_t *new_row_ptr, *new_col, *new_wf;
-    const float *new_cost;
-    float *cost, *rem, *tail, *horizon;
-    int32_t *level, *wf, *prow, *pcol, *parent0, *mark;
-    int32_t *list_in, *list_out;
-    int32_t *counters;      // [0..2] rotating list sizes
-    int cin, cout, czero;   // which counter is read, appended to, cleared
-    uint32_t epoch;
-    int32_t *status;
-};
-
-// non-negative fp32 values order like their bit patterns
-__device__ __forceinline__ bool hx_raise_max_f32(float *addr, float v)
-{
-    unsigned old = atomicMax((unsigned *)addr, __float_as_uint(v));
-    return __float_as_uint(v) > old;
-}
-
-// push the (new) rem and level of node v to its parent u; enqueue u if it grew.  The lanes of a
-// wavefront that enqueue at the same moment take their list slots with one atomic between them
-// (the list counter is a single address: one atomic per lane would serialise the whole sweep).
-// SCOPED: the list entry is written with a device-scope store (for the single-workgroup loop,
-// whose later steps read the list back).
-template <bool SCOPED>
-__device__ __forceinline__ void hx_push_parent_t(const AppendArgs &a, int u, float rem_v, int level_v)
-{
-    bool grew = hx_raise_max_f32(&a.tail[u], rem_v);
-    int old = atomicMax(&a.level[u], level_v + 1);
-    grew = grew || (level_v + 1 > old);
-    const bool want = grew && (uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch;
-    const unsigned long long m = __builtin_amdgcn_ballot_w64(want);      // of the lanes active here
-    if (m) {
-        const int lane = (int)(threadIdx.x & (HX_WAVE - 1));
-        const int leader = __ffsll((long long)m) - 1;
-        int base = 0;
-        if (lane == leader) base = atomicAdd(&a.counters[a.cout], __popcll(m));
-        base = __shfl(base, leader);
-        if (want) {
-            const int slot = base + __popcll(m & ((1ull << lane) - 1ull));   // at most one entry per node and sweep:
-            if (SCOPED) __hip_atomic_store(&a.list_out[slot], u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else a.list_out[slot] = u;                                        // never beyond cap_nodes
-        }
-    }
-}
-
-// node u onto the worklist of the next sweep, once per sweep (rare path: one atomic per entry)
-__device__ __forceinline__ void hx_enqueue(const AppendArgs &a, int u)
-{
-    if ((uint32_t)atomicExch(&a.mark[u], (int)a.epoch) != a.epoch) {
-        const int slot = atomicAdd(&a.counters[a.cout], 1);
-        a.list_out[slot] = u;
-    }
-}
-
-__device__ __forceinline__ void hx_push_parent_scoped(const AppendArgs &a, int u, float rem_v, int level_v)
-{
-    hx_push_parent_t<true>(a, u, rem_v, level_v);
-}
-
 // First phase of an append: the new nodes' own entries.  The two list counters the append needs at zero (the
 // one the walks append to, the one the first sweep after them clears) are cleared here: the walks are a launch
 // of their own after this one, so no launch is spent on the counters.
@@ -221,89 +161,9 @@ __global__ __launch_bounds__(256) void hx_append_init_kernel(AppendArgs a, NodeC
     }
 }
 
-// Second phase of an append (a kernel boundary after init, so that a new node whose parent is
-// also new finds that parent initialised).  Asynchronous propagation: every new node walks up from itself, one thread per new node.  A visit
-// of node u recomputes rem[u] from the tail u has now, raises its workflow's horizon, and raises the
-// tail and level of u's parents; a parent that grew is visited next (further grown parents wait on a
-// small stack).  Whoever raises a node visits it afterwards with a tail at least as large as the one it left there, so
-// every increase is carried upwards by someone, and a thread whose value did not raise anything
-// stops: the fixed point is the same as that of the level-by-level sweeps, maxima are exact, and no
-// launch or barrier separates the levels.  A walk that outgrows its stack or its step budget hands
-// the remaining nodes to the worklist, which the sweeps after this kernel finish.
-//
-// A walk is a chain of memory round trips, and most of it goes up through first parents.  One round trip per
-// level on that path: a node's first parent is kept beside its row of parents, so it is known when the node is
-// reached; the two atomics that raise the parent return what it held before, which together with the raised value
-// is what it holds now; and everything else the visit of the parent needs (cost, workflow, its own row and first
-// parent -- nothing an append changes) is asked for together with those atomics.  Further parents, and nodes
-// taken from the stack, pay the extra trips.
-constexpr int RELAX_STACK = 16;
-constexpr int RELAX_STEPS = 1024;
-
-struct HxVisit {
-    float cost, tl;
-    int lv, w, e0, e1, q0;
-};
-
-// what a visit needs of node u that no append changes
-__device__ __forceinline__ void hx_visit_fixed(const AppendArgs &a, int u, HxVisit &x)
-{
-    x.cost = a.cost[u]; x.w = a.wf[u]; x.e0 = a.prow[u]; x.e1 = a.prow[u + 1]; x.q0 = a.parent0[u];
-}
-
 __global__ __launch_bounds__(256) void hx_append_relax_kernel(AppendArgs a)
 {
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.n_new; i += gridDim.x * blockDim.x) {
-        int stack[RELAX_STACK];
-        int sp = 0, steps = 0;
-        int u = a.n_old + i;
-        HxVisit x;
-        bool have = false;                   // x already describes u (reached through its child's first-parent slot)
-        while (u >= 0) {
-            if (!have) {
-                x.tl = __hip_atomic_load(&a.tail[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                x.lv = __hip_atomic_load(&a.level[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                hx_visit_fixed(a, u, x);
-            }
-            const float r = x.cost + x.tl;
-            const int lv = x.lv;
-            hx_raise_max_f32(&a.rem[u], r);
-            if (x.w >= 0) hx_raise_max_f32(&a.horizon[x.w], r);
-            ++steps;
-            int next = -1;
-            have = false;
-            const int e0 = x.e0, e1 = x.e1, q0 = x.q0;
-            if (e1 > e0 && q0 >= 0) {
-                // the first parent: raised, and its own visit prepared, in one round trip
-                const unsigned old_t = atomicMax((unsigned *)&a.tail[q0], __float_as_uint(r));
-                const int old_l = atomicMax(&a.level[q0], lv + 1);
-                HxVisit y;
-                hx_visit_fixed(a, q0, y);
-                if (__float_as_uint(r) > old_t || lv + 1 > old_l) {
-                    if (steps >= RELAX_STEPS) {
-                        hx_enqueue(a, q0);
-                    } else {
-                        y.tl = __uint_as_float(max(old_t, __float_as_uint(r)));
-                        y.lv = max(old_l, lv + 1);
-                        x = y; next = q0; have = true;
-                    }
-                }
-            }
-            for (int e = e0 + 1; e < e1; ++e) {
-                const int q = a.pcol[e];
-                if (q < 0) continue;
-                bool grew = hx_raise_max_f32(&a.tail[q], r);
-                const int old = atomicMax(&a.level[q], lv + 1);
-                grew = grew || (lv + 1 > old);
-                if (!grew) continue;
-                if (steps >= RELAX_STEPS) hx_enqueue(a, q);
-                else if (next < 0) next = q;
-                else if (sp < RELAX_STACK) stack[sp++] = q;
-                else hx_enqueue(a, q);
-            }
-            u = next >= 0 ? next : (sp > 0 ? stack[--sp] : -1);
-        }
-    }
+    hx_append_relax_body(a, (int)blockIdx.x, (int)gridDim.x);
 }
 
 __global__ void hx_append_finish_kernel(AppendArgs a)
@@ -570,11 +430,12 @@ extern "C" int hx_dag_reserve(hx_ctx *ctx, int32_t max_nodes, int32_t max_edges,
 
 namespace {
 
-// nc: NULL, or the arguments of the standalone cost of the new nodes, which the first kernel then works out itself
-// (new_cost is nc->cost then, written as well as used)
-int dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
-               const float *new_cost, const int32_t *new_wf, const NodeCostArgs *nc, hipStream_t stream)
+// The append's first kernel.  nc: NULL, or the arguments of the standalone cost of the new nodes, which that kernel
+// then works out itself (new_cost is nc->cost then, written as well as used).  plan->grid == 0: nothing to append.
+int dag_append_begin(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                     const float *new_cost, const int32_t *new_wf, const NodeCostArgs *nc, HxAppendPlan *plan, hipStream_t stream)
 {
+    *plan = HxAppendPlan{};
     HxDagStore &g = ctx->dag;
     HX_REQUIRE(ctx, g.cost, HX_ERR_INVALID_ARG, "hx_dag_reserve has not been called");
     HX_REQUIRE(ctx, n_new >= 0 && n_new_edges >= 0, HX_ERR_INVALID_ARG, "negative size");
@@ -601,9 +462,41 @@ int dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *p
     a.list_in = g.list[1]; a.list_out = g.list[0];
     if (nc) hx_append_init_kernel<true><<<grid, 256, 0, stream>>>(a, *nc);
     else hx_append_init_kernel<false><<<grid, 256, 0, stream>>>(a, NodeCostArgs{});
-    hx_append_relax_kernel<<<grid, 256, 0, stream>>>(a);
-    // what the walks handed over (normally nothing) is finished level by level in one workgroup:
-    // sweep k reads the list sweep k-1 wrote, max_depth sweeps reach every ancestor
+    if (int rc = hx_check_launch(ctx, "hx_append_init_kernel")) return rc;
+    plan->a = a; plan->grid = grid; plan->n_new = n_new; plan->n_new_edges = n_new_edges;
+    return HX_OK;
+}
+
+int dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+               const float *new_cost, const int32_t *new_wf, const NodeCostArgs *nc, hipStream_t stream)
+{
+    HxAppendPlan plan;
+    if (int rc = dag_append_begin(ctx, n_new, n_new_edges, parent_row_ptr, parent_col_idx, new_cost, new_wf, nc, &plan, stream)) return rc;
+    if (plan.grid == 0) return HX_OK;
+    if (int rc = hx_dag_append_walks(ctx, &plan, stream)) return rc;
+    return hx_dag_append_end(ctx, &plan, stream);
+}
+
+}  // namespace
+
+// the walks of an append that has begun, as a launch of their own
+int hx_dag_append_walks(hx_ctx *ctx, const HxAppendPlan *plan, void *stream)
+{
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hx_append_relax_kernel<<<plan->grid, 256, 0, (hipStream_t)stream>>>(plan->a);
+    return hx_check_launch(ctx, "hx_append_relax_kernel");
+}
+
+// what follows the walks: what they handed over (normally nothing) is finished level by level in one workgroup --
+// sweep k reads the list sweep k-1 wrote, max_depth sweeps reach every ancestor -- and the graph has grown
+int hx_dag_append_end(hx_ctx *ctx, const HxAppendPlan *plan, void *stream_)
+{
+    HxDeviceGuard guard(ctx->device);
+    HX_REQUIRE(ctx, guard.ok, HX_ERR_DEVICE, "cannot select device %d", ctx->device);
+    hipStream_t stream = (hipStream_t)stream_;
+    HxDagStore &g = ctx->dag;
+    AppendArgs a = plan->a;
     if (g.max_depth > 0) {
         a.epoch = g.epoch;                       // the loop advances it once per step
         hx_append_tail_kernel<<<1, 1024, 0, stream>>>(a, g.list[0], g.list[1], 0, g.max_depth);
@@ -613,12 +506,10 @@ int dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges, const int32_t *p
         hx_append_finish_kernel<<<1, 64, 0, stream>>>(a);
     }
     if (int rc = hx_check_launch(ctx, "hx_dag_append kernels")) return rc;
-    g.n_nodes += n_new;
-    g.n_edges += n_new_edges;
+    g.n_nodes += plan->n_new;
+    g.n_edges += plan->n_new_edges;
     return HX_OK;
 }
-
-}  // namespace
 
 extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
                              const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
@@ -628,18 +519,20 @@ extern "C" int hx_dag_append(hx_ctx *ctx, int32_t n_new, int32_t n_new_edges,
     return dag_append(ctx, n_new, n_new_edges, parent_row_ptr, parent_col_idx, new_cost, new_wf, nullptr, (hipStream_t)stream_);
 }
 
-// hx_node_cost of the new nodes followed by hx_dag_append, the cost worked out by the append's first kernel: the
-// same checks and the same results as the two calls, one launch less (for hx_round)
-int hx_dag_append_with_cost(hx_ctx *ctx, const hx_model *model, int32_t n_new, int32_t n_new_edges,
-                            const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
-                            const int32_t *new_L_in, const int32_t *new_L_out,
-                            int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
-                            float *new_cost, const int32_t *new_wf, void *stream_)
+// hx_node_cost of the new nodes followed by the first kernel of hx_dag_append, the cost worked out by that kernel: the
+// same checks and the same results as the two calls, one launch less (for hx_round, which goes on with
+// hx_dag_append_walks -- or takes the walks into its search's launch -- and hx_dag_append_end)
+int hx_dag_append_begin(hx_ctx *ctx, const hx_model *model, int32_t n_new, int32_t n_new_edges,
+                        const int32_t *parent_row_ptr, const int32_t *parent_col_idx,
+                        const int32_t *new_L_in, const int32_t *new_L_out,
+                        int32_t n_types, const float *type_flops, const float *type_hbm_bw, const hx_links *links,
+                        float *new_cost, const int32_t *new_wf, HxAppendPlan *plan, void *stream_)
 {
+    *plan = HxAppendPlan{};
     NodeCostArgs nc{};
     if (int rc = node_cost_args(ctx, model, n_new, new_L_in, new_L_out, n_types, type_flops, type_hbm_bw, links, new_cost, &nc))
         return rc;
-    return dag_append(ctx, n_new, n_new_edges, parent_row_ptr, parent_col_idx, new_cost, new_wf, &nc, (hipStream_t)stream_);
+    return dag_append_begin(ctx, n_new, n_new_edges, parent_row_ptr, parent_col_idx, new_cost, new_wf, &nc, plan, (hipStream_t)stream_);
 }
 
 extern "C" int hx_dag_set_cost(hx_ctx *ctx, int32_t n, const int32_t *node_ids, const float *cost, void *stream_)

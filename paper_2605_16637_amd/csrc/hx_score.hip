@@ -24,6 +24,7 @@
 #include "hx_terms.hpp"
 #include "hx_search.hpp"
 #include "hx_cp.hpp"
+#include "hx_append.hpp"
 
 #include <cfloat>
 #include <cmath>
@@ -419,6 +420,21 @@ __global__ __launch_bounds__(CP_THREADS) void hx_reveal_search_kernel(ScoreArgs 
     hx_fused_search_body<KP>(a, pa, dp_bound, smem, (int)blockIdx.x - n_reveal, (int)gridDim.x - n_reveal);
 }
 
+// The same for a round that appends to the context's graph: the append's walks (hx_append_relax_kernel's work: one
+// thread per new node, a chain of device-scope atomics up its ancestors) take the first n_lead workgroups of the
+// search's launch.  They are all latency and no arithmetic, and where the search fills the chip the workgroups they
+// displace are again the ones with the fewest calls.
+template <int KP>
+__global__ __launch_bounds__(512) void hx_relax_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound, AppendArgs ap, int n_lead)
+{
+    extern __shared__ __align__(16) float smem[];
+    if ((int)blockIdx.x < n_lead) {
+        hx_append_relax_body(ap, (int)blockIdx.x, n_lead);
+        return;
+    }
+    hx_fused_search_body<KP>(a, pa, dp_bound, smem, (int)blockIdx.x - n_lead, (int)gridDim.x - n_lead);
+}
+
 // ---- materialised tensor ------------------------------------------------------------
 
 // A workgroup takes nc calls at a time (nc = 4 on small pools, where one call's share of the tensor is a few
@@ -658,7 +674,9 @@ int hx_score_init()
     const void *kernels[] = {
         reinterpret_cast<const void *>(hx_fused_search_kernel<1>), reinterpret_cast<const void *>(hx_fused_search_kernel<2>),
         reinterpret_cast<const void *>(hx_fused_search_kernel<4>), reinterpret_cast<const void *>(hx_reveal_search_kernel<1>),
-        reinterpret_cast<const void *>(hx_reveal_search_kernel<2>), reinterpret_cast<const void *>(hx_reveal_search_kernel<4>)};
+        reinterpret_cast<const void *>(hx_reveal_search_kernel<2>), reinterpret_cast<const void *>(hx_reveal_search_kernel<4>),
+        reinterpret_cast<const void *>(hx_relax_search_kernel<1>), reinterpret_cast<const void *>(hx_relax_search_kernel<2>),
+        reinterpret_cast<const void *>(hx_relax_search_kernel<4>)};
     hipError_t e = hipSuccess;
     for (const void *k : kernels)
         if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -668,7 +686,8 @@ int hx_score_init()
 namespace {
 
 // reveal: NULL, or the horizon refresh of the same round (hx_horizons_plan), to ride in the search's launch if the
-// round is small enough for that: *revealed says whether it did.  With a reveal the ratio is only checked, not
+// round is small enough for that: *revealed says whether it did.  walks: NULL, or an append of the same round that
+// has begun (hx_dag_append_begin), whose walks are to ride in the search's launch likewise.  With a reveal the ratio is only checked, not
 // written -- the horizons are not there yet; the caller forms it afterwards -- and nothing but the fused search is
 // launched: if the reveal does not fit, nothing at all is, and the caller makes the calls one after the other.
 int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
@@ -676,7 +695,7 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
                      const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
                      float *cost, uint8_t *feas,
                      int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
-                     const HxHorizonsPlan *reveal, bool *revealed, void *stream_)
+                     const HxHorizonsPlan *reveal, const HxAppendPlan *walks, bool *revealed, void *stream_)
 {
     HX_REQUIRE(ctx, model && calls && pre && dec && links, HX_ERR_INVALID_ARG, "NULL table");
     const int C = calls->n, P = pre->n, D = dec->n, T = links->n_types;
@@ -710,10 +729,11 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
     a.L_in = calls->L_in; a.L_out = calls->L_out; a.node = calls->node; a.wf = calls->wf;
     a.elapsed = calls->elapsed; a.tail = tail; a.horizon = horizon; a.n_nodes = n_nodes; a.n_wf = n_wf;
     a.prep = ctx->d_prep;
-    a.best_p = best_p; a.best_d = best_d; a.best_cost = best_cost; a.ratio = reveal ? nullptr : ratio;
+    a.best_p = best_p; a.best_d = best_d; a.best_cost = best_cost; a.ratio = (reveal || walks) ? nullptr : ratio;
     a.cost = cost; a.feas = feas; a.status = ctx->d_status;
 
     if (reveal && (P == 0 || D == 0 || !fused || cost || feas || reveal->grid == 0)) return HX_OK;      // not this way
+    if (walks && (P == 0 || D == 0 || !fused || cost || feas || walks->grid == 0)) return HX_OK;
     if (P == 0 || D == 0) {
         if (fused) {
             hx_no_pool_kernel<<<(C + 255) / 256, 256, 0, stream>>>(a);
@@ -773,6 +793,20 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
         int grid = ctx->num_cu * blocks_per_cu;
         const int need = (C + waves - 1) / waves;
         grid = grid > need ? need : grid;
+        if (walks) {
+            // the walks' threads take several new nodes each if need be; not this way if they would be more than a
+            // third of the launch (a small search behind a large append: the two launches are then the better way)
+            const int threads = waves * HX_WAVE;
+            const int n_lead = (walks->a.n_new + threads - 1) / threads;
+            if (3LL * n_lead > grid) return HX_OK;
+            auto launch_w = [&](auto kern) { kern<<<n_lead + grid, threads, lds, stream>>>(a, pa, dp_bound, walks->a, n_lead); };
+            if (P <= 64) launch_w(hx_relax_search_kernel<1>);
+            else if (P <= 128) launch_w(hx_relax_search_kernel<2>);
+            else launch_w(hx_relax_search_kernel<4>);
+            if (int rc = hx_check_launch(ctx, "hx_relax_search_kernel")) return rc;
+            *revealed = true;
+            return HX_OK;
+        }
         auto launch = [&](auto kern) { kern<<<grid, waves * HX_WAVE, lds, stream>>>(a, pa, dp_bound); };
         if (P <= 64) launch(hx_fused_search_kernel<1>);
         else if (P <= 128) launch(hx_fused_search_kernel<2>);
@@ -804,7 +838,7 @@ extern "C" int hx_score_placements(hx_ctx *ctx, const hx_model *model, const hx_
 {
     if (!ctx) return HX_ERR_INVALID_ARG;
     return score_placements(ctx, model, calls, pre, dec, links, tail, horizon, n_nodes, n_wf, cost, feas,
-                            best_p, best_d, best_cost, ratio, nullptr, nullptr, stream_);
+                            best_p, best_d, best_cost, ratio, nullptr, nullptr, nullptr, stream_);
 }
 
 // The horizon refresh `reveal` and hx_score_placements (fused outputs) in one launch, where the round is small
@@ -818,7 +852,20 @@ int hx_reveal_search(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
 {
     *revealed = false;
     return score_placements(ctx, model, calls, pre, dec, links, tail, horizon, n_nodes, n_wf, nullptr, nullptr,
-                            best_p, best_d, best_cost, ratio, reveal, revealed, stream_);
+                            best_p, best_d, best_cost, ratio, reveal, nullptr, revealed, stream_);
+}
+
+// The walks of an append that has begun and hx_score_placements (fused outputs) in one launch, where the search is
+// large enough beside them (*merged; otherwise nothing has been launched).  ratio: checked, not written, as above.
+int hx_relax_search(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
+                    const hx_prefill_tab *pre, const hx_decode_tab *dec, const hx_links *links,
+                    const float *tail, const float *horizon, int32_t n_nodes, int32_t n_wf,
+                    int32_t *best_p, int32_t *best_d, float *best_cost, float *ratio,
+                    const HxAppendPlan *walks, bool *merged, void *stream_)
+{
+    *merged = false;
+    return score_placements(ctx, model, calls, pre, dec, links, tail, horizon, n_nodes, n_wf, nullptr, nullptr,
+                            best_p, best_d, best_cost, ratio, nullptr, walks, merged, stream_);
 }
 
 extern "C" int hx_select(hx_ctx *ctx, int32_t C, int32_t P, int32_t D, const float *cost,

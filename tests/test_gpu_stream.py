@@ -206,15 +206,21 @@ def test_prepared_calls_equal_the_calls_they_were_prepared_from(ctx):
     ctx.hx_stream_status()
 
 
-def test_round_in_one_call_equals_its_four_calls(ctx):
+@pytest.mark.parametrize("P,D,n_live,rounds,cap", [
+    (48, 40, 150, 6, 200000),           # a small search: one prefill instance per lane
+    (512, 512, 20000, 3, 700000),       # the streaming configuration's shape: the search fills the chip, four per lane
+    (100, 300, 3000, 3, 300000),        # two per lane, ragged
+])
+def test_round_in_one_call_equals_its_four_calls(ctx, P, D, n_live, rounds, cap):
     # hx_round = hx_node_cost -> hx_dag_append -> hx_score_placements (fused, with the ratio) -> hx_commit, enqueued by
-    # one library call: a few streaming rounds made both ways on two contexts' graphs and two copies of the pool, bit for bit
+    # one library call (in fewer launches: the cost in the append's first kernel, the walks in the search's launch, the
+    # ratio in the commit's): a few streaming rounds made both ways on two contexts' graphs and two copies of the pool,
+    # bit for bit
     import torch
     from paper_2605_16637_amd import binding
     model = synth.MODEL
     rng = np.random.default_rng(5)
     L0, O0 = synth.gen_lengths(rng, 4000)
-    P, D = 48, 40
     types, links, pre, dec = synth.gen_pool(rng, P, D, 8, L0, O0, near_capacity=True)
     d_links = binding.to_device(links)
     tF, tB = dev(types["flops"]), dev(types["hbm_bw"])
@@ -222,10 +228,10 @@ def test_round_in_one_call_equals_its_four_calls(ctx):
     try:
         pools = [(binding.to_device(pre), binding.to_device(dec)) for _ in range(2)]
         for c in (ctx, other):
-            c.hx_dag_reserve(200000, 300000, 50000, 24)
-        gens = [synth.StreamGen(9, 150, final_lo=6, final_hi=20) for _ in range(2)]
+            c.hx_dag_reserve(cap, cap * 3 // 2, cap // 4 + n_live, 24)
+        gens = [synth.StreamGen(9, n_live, final_lo=6, final_hi=20) for _ in range(2)]
         i32 = dict(dtype=torch.int32, device="cuda:0")
-        for r in range(6):
+        for r in range(rounds):
             outs = []
             for which, (c, gen, (d_pre, d_dec)) in enumerate(zip((ctx, other), gens, pools)):
                 b = gen.next_batch()
