@@ -366,9 +366,13 @@ int hx_commit(hx_ctx *ctx, const hx_calls *calls, const int32_t *best_p, const i
  *   hx_score_placements(fused outputs, tail and horizon = the context's graph);
  *   hx_commit(calls, best_p, best_d, the snapshot's counters, the drains)
  * made on `stream` in that order (the first one that fails ends the call; what
- * was enqueued before it stays enqueued), one launch fewer: the new nodes'
- * costs are worked out by the append's first kernel.  n_new may be 0 (nothing
- * is revealed), calls.n may be 0.  The counters of `prefill` and `decode` that
+ * was enqueued before it stays enqueued), in fewer launches: the new nodes'
+ * costs are worked out by the append's first kernel, and -- where every
+ * argument check of the calls passes and the search is large enough beside
+ * the append -- the append's walks up the graph share the search's launch (the
+ * search does not depend on them; only the ratio does) and the ratio is formed
+ * by the commit's launch.  n_new may be 0 (nothing is revealed), calls.n may
+ * be 0.  The counters of `prefill` and `decode` that
  * the commit updates are passed once more as writable pointers (they may be
  * the same memory as the tables' own backlog_tok, used_tok, batch, qd_tok: the
  * search has read them by then).
