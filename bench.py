@@ -49,8 +49,8 @@ def source_sha(files):
     return h.hexdigest()
 
 
-FUSED_SOURCES = ("hx_score.hip", "hx_search.hpp", "hx_terms.hpp", "hx_common.hpp")
-CP_SOURCES = ("hx_dag.hip", "hx_terms.hpp", "hx_common.hpp")
+FUSED_SOURCES = ("hx_score.hip", "hx_search.hpp", "hx_terms.hpp", "hx_common.hpp", "hx_cp.hpp", "hx_append.hpp")
+CP_SOURCES = ("hx_dag.hip", "hx_cp.hpp", "hx_append.hpp", "hx_terms.hpp", "hx_common.hpp")
 
 
 def profiled_traffic(summary, sources, key="traffic_bytes_per_launch"):
