@@ -4,7 +4,9 @@ horizon is refreshed at every reveal; Algorithm 1, simulated-state update).
 
 Every round reveals new calls (hx_node_cost -> hx_dag_append into the graph the
 context keeps), scores the ready calls with their projected ratio
-(hx_score_placements) and commits the chosen pairs (hx_commit).
+(hx_score_placements) and commits the chosen pairs (hx_commit) -- even rounds
+as those four library calls, odd rounds as one hx_round call, which makes the
+same round in fewer launches.
 
   reduced scale (2048 calls x 64 x 64): the oracle replays every round in full on
     its own state -- its own fp64 node costs and horizon pass over the whole graph,
@@ -85,13 +87,9 @@ class Stream:
         n_new, n_wf, m = b["n_new"], b["n_wf_total"], int(b["parent_col"].size)
         before = [self.d_pre["backlog_tok"].clone(), self.d_dec["used_tok"].clone(), self.d_dec["batch"].clone(),
                   self.d_dec["qd_tok"].clone()] if check else None
-        # reveal
+        # the ready calls of the round: up to C of the calls just revealed
         d_L, d_O = dev(b["L_in"]), dev(b["L_out"])
         g_cost = torch.empty(n_new, device="cuda:0")
-        ctx.hx_node_cost(model, d_L, d_O, self.tF, self.tB, self.d_links, g_cost)
-        ctx.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), g_cost, dev(b["wf"]))
-        g_rem, g_tail, g_level, g_hor, n_nodes = ctx.hx_dag_view(n_wf)
-        # the ready calls of the round: up to C of the calls just revealed
         pick = np.sort(self.rng.choice(n_new, min(self.C, n_new), replace=False)).astype(np.int32)
         Lc, Oc = b["L_in"][pick], b["L_out"][pick]
         elapsed = self.rng.uniform(0, 30, pick.size).astype(np.float32)
@@ -99,13 +97,25 @@ class Stream:
         i32 = dict(dtype=torch.int32, device="cuda:0")
         bp, bd = torch.empty(pick.size, **i32), torch.empty(pick.size, **i32)
         bc, ratio = torch.empty(pick.size, device="cuda:0"), torch.empty(pick.size, device="cuda:0")
-        ctx.hx_score_placements(model, calls, self.d_pre, self.d_dec, self.d_links, tail=g_tail, horizon=g_hor,
-                                best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
         # drains sized to what the round adds, so the pool stays in its regime
         Ls, Os = int(Lc.sum()), int(Oc.sum())
         dp = np.full(P, Ls // P, np.int32); dq = np.full(D, Os // D, np.int32); rl = np.full(D, (Ls + Os) // D, np.int32)
-        ctx.hx_commit(calls, bp, bd, self.d_pre["backlog_tok"], self.d_dec["used_tok"], self.d_dec["batch"], self.d_dec["qd_tok"],
-                      dev(dp), dev(dq), dev(rl))
+        if r % 2 == 0:
+            # reveal, score, commit: the four library calls
+            ctx.hx_node_cost(model, d_L, d_O, self.tF, self.tB, self.d_links, g_cost)
+            ctx.hx_dag_append(dev(b["parent_row_ptr"]), dev(b["parent_col"]), g_cost, dev(b["wf"]))
+            g_rem, g_tail, g_level, g_hor, n_nodes = ctx.hx_dag_view(n_wf)
+            ctx.hx_score_placements(model, calls, self.d_pre, self.d_dec, self.d_links, tail=g_tail, horizon=g_hor,
+                                    best_p=bp, best_d=bd, best_cost=bc, ratio=ratio)
+            ctx.hx_commit(calls, bp, bd, self.d_pre["backlog_tok"], self.d_dec["used_tok"], self.d_dec["batch"], self.d_dec["qd_tok"],
+                          dev(dp), dev(dq), dev(rl))
+        else:
+            # the same round as one call (fewer launches: the walks in the search's, the ratio in the commit's)
+            ctx.hx_round(model, calls, self.d_pre, self.d_dec, self.d_links, bp, bd, bc, ratio=ratio, n_wf=n_wf,
+                         parent_row_ptr=dev(b["parent_row_ptr"]), parent_col_idx=dev(b["parent_col"]), new_L_in=d_L, new_L_out=d_O,
+                         new_wf=dev(b["wf"]), new_cost=g_cost, type_flops=self.tF, type_hbm_bw=self.tB,
+                         drain_prefill=dev(dp), drain_decode_q=dev(dq), release_tok=dev(rl))
+            g_rem, g_tail, g_level, g_hor, n_nodes = ctx.hx_dag_view(n_wf)
         ctx.hx_stream_status()
         assert n_nodes == self.n + n_new
 
