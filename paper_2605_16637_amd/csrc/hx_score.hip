@@ -390,15 +390,16 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
     hx_fused_search_body<KP>(a, pa, dp_bound, smem, (int)blockIdx.x, (int)gridDim.x);
 }
 
-// ---- the first kernel of a small scheduling round: reveal and search in one launch ------------------
+// ---- the first kernel of a scheduling round that brings its whole graph: reveal and search in one launch ----
 //
-// A round whose search is short (every wavefront has at most one call, all workgroups resident at once) spends
-// its time in the latencies of its launches and of their chains of memory round trips, not in arithmetic.  The
-// horizon refresh (node cost + critical path, what hx_cp_cost_kernel does) and the search do not depend on each
+// The horizon refresh (node cost + critical path, what hx_cp_cost_kernel does) and the search do not depend on each
 // other -- only the ratio needs both, and it is formed by the commit kernel that follows -- so they share a launch:
-// the first n_reveal workgroups take workflows exactly as hx_cp_cost_kernel's do (same body, the cost's class pairs
-// one after the other to stay within the search's registers), the others search.  Same results as the two
-// kernels, one launch and the gap before it less, and the two latency chains run side by side.
+// the first n_reveal workgroups take workflows exactly as hx_cp_cost_kernel's do (same body, the cost's prefill
+// classes one after the other to stay within the search's registers), the others search.  Same results as the
+// two kernels, one launch and the gap before it less.  On a small round (every wavefront has at most one call,
+// all workgroups resident at once) both halves are chains of memory round trips, which now run side by side; on a
+// large one the reveal's workgroups hold their places for some ten microseconds while the rest of the chip
+// searches, and the searching workgroups that start after them are the ones with the fewest calls.
 constexpr int RV_NMAX = 512;             // nodes staged per run of a reveal workgroup
 
 struct RevealLds {

@@ -153,6 +153,28 @@ def test_round_replayed_from_a_hip_graph(ctx):
         # eager work of the program between replays
         one_round()
         torch.cuda.synchronize()
+    # the same round as one hx_round call (two launches: the reveal in the search's, the ratio in the commit's), captured
+    graph_args = dict(succ_row_ptr=rp, succ_col_idx=col, wf_ptr=wp, L_in=L_in, L_out=L_out,
+                      node_cost=cost, rem=rem, tail=tail, level=level, horizon=hor)
+
+    def one_call():
+        ctx.hx_round(rnd.model, calls, pre, dec, links, bp, bd, bc, ratio=ratio, type_flops=tF, type_hbm_bw=tB,
+                     drain_prefill=drain_p, drain_decode_q=drain_q, release_tok=release, graph=graph_args)
+
+    reset(); one_call()                              # loads what the capture must not load for the first time
+    g2 = torch.cuda.CUDAGraph()
+    reset()
+    with torch.cuda.graph(g2):
+        one_call()
+    for rep in range(3):
+        reset()
+        torch.cuda.synchronize()
+        g2.replay(); g2.replay()
+        for a, b in zip(snapshot(), want):
+            assert np.array_equal(a, b), f"replay {rep} of the one-call round differs from the eager rounds"
+        ctx.hx_stream_status()
+        one_round()
+        torch.cuda.synchronize()
 
 
 def test_prepared_calls_equal_the_calls_they_were_prepared_from(ctx):
