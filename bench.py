@@ -691,6 +691,10 @@ def main():
                                 "stream": "streaming round shape: 32768 ready calls x 512 x 512, 8 classes"}[args.workload],
                    "calls": C, "prefill": P, "decode": D, "candidates_per_round": n_cand,
                    "dag_nodes": rnd.dag.n_nodes, "dag_edges": rnd.dag.n_edges, "workflows": rnd.dag.n_wf,
+                   # share of (call, decode instance) pairs whose KV does not fit the instance's free tokens (inputs only)
+                   "infeasible_pair_fraction": float(np.mean(
+                       (rnd.calls["L_in"].astype(np.int64) + rnd.calls["L_out"])[:, None]
+                       > (rnd.dec["cap_tok"].astype(np.int64) - rnd.dec["used_tok"])[None, :])),
                    "step": ("[node cost + critical path (one launch)] beside [fused score+argmin] on two streams -> urgency fold -> commit"
                             if args.overlap else
                             "hx_round: [node cost + critical path] and [fused score+argmin] in one launch -> commit with the ratio (one launch)"
