@@ -324,6 +324,9 @@ def _round_state(b):
     ("mid", dict(C=3000, P=100, D=70, T=3)),               # two per lane, ragged
     ("mid", dict(C=9000, P=300, D=260, T=8)),              # four per lane, several calls per wavefront
     ("mid", dict(C=700, P=5, D=600, T=2)),
+    # workflows of up to 600 nodes: more than the reveal's workgroups stage at a time (several runs per workgroup,
+    # single workflows walked in global memory), wide fan-out
+    ("mid", dict(n_wf=300, size_lo=4, size_hi=600, fanout_max=6, depth_max=40, C=2000)),
 ])
 def test_round_with_its_whole_graph_equals_its_three_calls(ctx, name, override):
     # hx_round with the round's whole graph = hx_horizons -> hx_score_placements (fused, ratio) -> hx_commit:
