@@ -225,7 +225,7 @@ struct GreedyLds {
     {
         return (size_t)7 * Dp + 4 * Pp + 2 * kT * kT + 16     // pool view, as in the fused search
              + P + 7 * (size_t)D                               // simulated state and what is needed to re-derive an entry
-             + 10 * (size_t)C                                  // per call: pair, cost, ratio, flags; lengths, elapsed, tail, horizon
+             + 11 * (size_t)C                                  // per call: pair, cost, ratio, flags; lengths, elapsed, tail, horizon; the list of calls to score again
              + 4 * GREEDY_WAVES                                // reduction scratch
              + (size_t)GREEDY_WAVES * (Dp + kT * kT + kT);     // per-wave search buffers
     }
@@ -279,7 +279,8 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     float *s_el = (float *)(s_O + lay.C);
     float *s_tl = s_el + lay.C;                        // tail of its node, horizon of its workflow (-1: index out of range)
     float *s_hz = s_tl + lay.C;
-    float *s_redv = (float *)(s_hz + lay.C);           // reduction scratch, then the pick
+    int *s_list = (int *)(s_hz + lay.C);               // the calls to score again, in any order: dealt to the wavefronts evenly
+    float *s_redv = (float *)(s_list + lay.C);         // reduction scratch, then the pick
     int *s_redi = (int *)(s_redv + GREEDY_WAVES);
     int *s_pick = s_redi + GREEDY_WAVES;               // [0] call, [1] p, [2] d
     float *s_wave = (float *)(s_pick + 2 * GREEDY_WAVES);
@@ -312,6 +313,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     if (tid <= kT) s_seg[tid] = t->seg[tid];
     for (int c = tid; c < a.C; c += GREEDY_THREADS) {
         s_flags[c] = ALIVE | DIRTY;
+        s_list[c] = c;
         s_L[c] = a.L_in[c]; s_O[c] = a.L_out[c]; s_el[c] = a.elapsed[c];
         const int nd = a.node[c], w = a.wf[c];
         const bool ok = nd >= 0 && nd < a.n_nodes && w >= 0 && w < a.n_wf;
@@ -327,9 +329,12 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
     const HxPoolLds pool{s_wait, s_c1, s_c2, s_kB, s_free, s_orig, s_dtype, s_pw, s_pinvF, s_pinvB, s_ptype,
                          s_invbw, s_lat, Dp, a.P, lay.Pp};
 
+    int n_dirty = a.C;                                 // every call at first (uniform; s_pick[4] carries it from step to step)
     for (int k = 0; k < a.C; ++k) {
-        // (1) score the calls whose pair may have changed, on the simulated state
-        for (int c = wave; c < a.C; c += GREEDY_WAVES) {
+        // (1) score the calls whose pair may have changed, on the simulated state: the list deals them to the
+        // wavefronts evenly (by call index, a wavefront could find all of its calls dirty and its neighbour none)
+        for (int i = wave; i < n_dirty; i += GREEDY_WAVES) {
+            const int c = s_list[i];
             if (s_flags[c] != (ALIVE | DIRTY)) continue;           // wave-uniform: c depends on the wave only
             // large pools: class by class (KP = 0); small ones: pair by pair, whose inner loop costs less than the
             // class search's reductions up to about 64 x 64 pairs
@@ -372,7 +377,8 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             const int c = bi, p = s_bp[c], d = s_bd[c];
             a.best_p[c] = p; a.best_d[c] = d; a.best_cost[c] = s_bc[c]; hx_store_bits(a.ratio, c, __float_as_uint(s_ratio[c])); a.rank[c] = k;
             s_flags[c] = 0;
-            s_pick[0] = c; s_pick[1] = p; s_pick[2] = d;
+            s_pick[0] = c; s_pick[1] = p; s_pick[2] = d; s_pick[3] = 0;
+            s_pick[4] = 0;                                  // the next step's list starts empty
             if (p >= 0) {
                 const int L = s_L[c], O = s_O[c];
                 long long bl = (long long)s_backlog[p] + L, qd = (long long)s_qd[d] + O, us = (long long)s_used[d] + L + O;
@@ -404,17 +410,20 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         if (pp >= 0 && s_pick[3]) {
             // a term of the decode instance fell: nothing can be kept
             for (int c = tid; c < a.C; c += GREEDY_THREADS)
-                if (s_flags[c] & ALIVE) s_flags[c] = ALIVE | DIRTY;
+                if (s_flags[c] & ALIVE) { s_flags[c] = ALIVE | DIRTY; s_list[atomicAdd(&s_pick[4], 1)] = c; }
         } else if (pp >= 0) {
             // load was only added: every pair costs what it did or more, so only calls whose pair touches one of
             // the two instances can lose their minimum -- and not even those if the cost of their pair came out
             // the same (e.g. the decode instance's availability still dominates a longer prefill queue)
             for (int c = tid; c < a.C; c += GREEDY_THREADS)
                 if ((s_flags[c] & ALIVE) && (s_bp[c] == pp || s_bd[c] == pd) &&
-                    hx_pair_cost(a.m, pool, s_L[c], s_O[c], s_bp[c], s_pos[s_bd[c]]) != s_bc[c])
+                    hx_pair_cost(a.m, pool, s_L[c], s_O[c], s_bp[c], s_pos[s_bd[c]]) != s_bc[c]) {
                     s_flags[c] = ALIVE | DIRTY;
+                    s_list[atomicAdd(&s_pick[4], 1)] = c;
+                }
         }
         __syncthreads();
+        n_dirty = s_pick[4];
     }
     // the simulated state the plan leaves
     for (int p = tid; p < a.P; p += GREEDY_THREADS) if (a.backlog_out) a.backlog_out[p] = s_backlog[p];
