@@ -367,13 +367,21 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         }
         if (lane == 0) { s_redv[wave] = bv; s_redi[wave] = bi; }
         __syncthreads();
-        // (3) one thread records the pick and adds it to the simulated state
-        if (tid == 0) {
-            for (int w = 1; w < GREEDY_WAVES; ++w) {
-                const float ov = s_redv[w];
-                const int oi = s_redi[w];
-                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+        // (3) the first wavefront takes the best of the wavefronts' candidates (one per lane, the same rule), and its
+        // first lane records the pick and adds it to the simulated state
+        if (wave == 0) {
+            bv = lane < GREEDY_WAVES ? s_redv[lane] : -INFINITY;
+            bi = lane < GREEDY_WAVES ? s_redi[lane] : 0x7fffffff;
+#pragma unroll
+            for (int off = GREEDY_WAVES / 2; off > 0; off >>= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+                bv = take ? ov : bv;
+                bi = take ? oi : bi;
             }
+        }
+        if (tid == 0) {
             const int c = bi, p = s_bp[c], d = s_bd[c];
             a.best_p[c] = p; a.best_d[c] = d; a.best_cost[c] = s_bc[c]; hx_store_bits(a.ratio, c, __float_as_uint(s_ratio[c])); a.rank[c] = k;
             s_flags[c] = 0;
