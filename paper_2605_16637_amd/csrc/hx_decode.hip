@@ -953,13 +953,21 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         }
         if (lane == 0) { s_redv[wave] = rv; s_redi[wave] = ri; }
         __syncthreads();
-        // (3) one thread records the pick and appends its interval
-        if (tid == 0) {
-            for (int wv = 1; wv < DG_WAVES; ++wv) {
-                const float ov = s_redv[wv];
-                const int oi = s_redi[wv];
-                if (oi != INT_MAX && (ri == INT_MAX || ov > rv || (ov == rv && oi < ri))) { rv = ov; ri = oi; }
+        // (3) the first wavefront takes the best of the wavefronts' candidates (one per lane, the same rule), and its
+        // first lane records the pick and appends its interval
+        if (wave == 0) {
+            rv = lane < DG_WAVES ? s_redv[lane] : -INFINITY;
+            ri = lane < DG_WAVES ? s_redi[lane] : INT_MAX;
+#pragma unroll
+            for (int off = DG_WAVES / 2; off > 0; off >>= 1) {
+                const float ov = __shfl_xor(rv, off);
+                const int oi = __shfl_xor(ri, off);
+                const bool take = oi != INT_MAX && (ri == INT_MAX || ov > rv || (ov == rv && oi < ri));
+                rv = take ? ov : rv;
+                ri = take ? oi : ri;
             }
+        }
+        if (tid == 0) {
             const int c = ri, d = s_bd[c];
             if (keep_all && k > 0 && d >= 0) {
                 // its best may have moved since its start was last written: the start on the instance it has now
@@ -1020,7 +1028,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                             }
                             s_bd[c] = bd;
                             s_bc[c] = bv;
-                            s_ratio[c] = ((s_el[c] + bv) + s_tail[c]) / s_hz[c];
+                            hx_store_bits(s_ratio, c, hx_ratio_bits(s_el[c], bv, s_tail[c], s_hz[c], s_hz[c] >= 0.0f));   // Eq. (2)
                         }
                     }
                 }
