@@ -347,8 +347,11 @@ def check_plan_stepwise(model, L, O, lock, node, wf, elapsed, tail, hor, dec, iv
         assert (np.isinf(top) and np.isinf(R[i])) or mine >= top * (1 - 2 * REL), f"step {k}: call {c} ratio {mine} vs {top}"
         d = int(got["best_d"][c])
         if np.isinf(R[i]):
-            assert d == -1 and np.isinf(got["best_cost"][c]) and np.isinf(got["best_start"][c]) and np.isinf(got["ratio"][c])
+            # nothing feasible, or a workflow without horizon: infinitely urgent either way, lowest index first
+            assert np.isinf(got["ratio"][c])
             assert c == min(a for a, r in zip(alive, R) if np.isinf(r))
+        if np.isinf(s_lo.best_cost[i]):
+            assert d == -1 and np.isinf(got["best_cost"][c]) and np.isinf(got["best_start"][c])
         else:
             assert d >= 0 and (lock_a is None or lock_a[c] < 0 or lock_a[c] == d)
             S = float(got["best_start"][c])
@@ -356,8 +359,9 @@ def check_plan_stepwise(model, L, O, lock, node, wf, elapsed, tail, hor, dec, iv
             alt = S + decode_time(model, L[c], O[c], dec, d)
             assert alt <= s.best_cost[i] * (1 + REL), f"step {k}: instance of call {c}"
             assert abs(got["best_cost"][c] - alt) <= REL * alt
-            want_r = (el[c] + alt + tl[node[c]]) / hz[wf[c]]
-            assert abs(got["ratio"][c] - want_r) <= REL * want_r
+            if hz[wf[c]] > 0:
+                want_r = (el[c] + alt + tl[node[c]]) / hz[wf[c]]
+                assert abs(got["ratio"][c] - want_r) <= REL * want_r
             at = d * K + cnt[d]
             st["start"][at] = got["best_start"][c]; st["end"][at] = got["best_cost"][c]; st["tok"][at] = L[c] + O[c]
             cnt[d] += 1
@@ -392,6 +396,29 @@ def test_decode_greedy_matches_oracle(ctx, Q, D, stride, res, plan, lockf, seed)
         assert_costs_close(got["best_cost"], want.best_cost, "plan cost"); assert_costs_close(got["ratio"], want.ratio, "plan ratio")
         assert np.array_equal(got["count"], want.count)
     assert (got["best_start"][got["best_d"] >= 0] > 0).any()
+
+
+@pytest.mark.parametrize("Q,D,stride,res,plan", [(40, 4, 16, 10, 3), (80, 64, 16, 10, 3)])      # finish of every pair kept; not kept
+def test_decode_greedy_with_workflows_without_horizon(ctx, Q, D, stride, res, plan):
+    # a workflow whose horizon is 0 makes its calls infinitely urgent: they are planned first, lowest index first, and
+    # placed like any other call; their ratio stays +inf when their best instance moves
+    r, lock, iv = synth.make_decode_round("decode_tiny", 31, n_wf=max(8, Q // 4), Q=Q, D=D, T=min(4, D), stride=stride,
+                                          n_resident=res, n_planned=plan, lock_fraction=0.2)
+    L, O = r.calls["L_in"], r.calls["L_out"]
+    rng = np.random.default_rng(7)
+    n_nodes, n_wf = Q + 5, 4
+    node = rng.permutation(n_nodes)[:Q].astype(np.int32); wf = rng.integers(0, n_wf, Q).astype(np.int32)
+    elapsed = rng.uniform(0, 20, Q).astype(np.float32)
+    tail = rng.uniform(0, 5, n_nodes).astype(np.float32); hor = rng.uniform(5, 50, n_wf).astype(np.float32)
+    hor[1] = 0.0
+    big = widen(iv, D, Q)
+    got = run_plan(ctx, r.model, L, O, lock, node, wf, elapsed, tail, hor, r.dec, big)
+    check_plan_stepwise(r.model, L, O, lock, node, wf, elapsed, tail, hor, r.dec, big, got)
+    urgent = np.nonzero(wf == 1)[0]
+    assert urgent.size > 2 and np.isinf(got["ratio"][urgent]).all()
+    assert np.array_equal(np.sort(got["rank"][urgent]), np.arange(urgent.size))            # before every other call
+    assert np.array_equal(np.argsort(got["rank"][urgent]), np.arange(urgent.size))           # in index order
+    assert (got["best_d"][urgent] >= 0).any()
 
 
 def test_decode_greedy_at_the_benchmarks_size(ctx):
