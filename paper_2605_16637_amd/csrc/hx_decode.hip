@@ -943,14 +943,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 if (ri == INT_MAX || r > rv) { rv = r; ri = c; }
             }
         }
-#pragma unroll
-        for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(rv, off);
-            const int oi = __shfl_xor(ri, off);
-            const bool take = oi != INT_MAX && (ri == INT_MAX || ov > rv || (ov == rv && oi < ri));
-            rv = take ? ov : rv;
-            ri = take ? oi : ri;
-        }
+        hx_wave_argmax(rv, ri);
         if (lane == 0) { s_redv[wave] = rv; s_redi[wave] = ri; }
         __syncthreads();
         // (3) the first wavefront takes the best of the wavefronts' candidates (one per lane, the same rule), and its
@@ -958,14 +951,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         if (wave == 0) {
             rv = lane < DG_WAVES ? s_redv[lane] : -INFINITY;
             ri = lane < DG_WAVES ? s_redi[lane] : INT_MAX;
-#pragma unroll
-            for (int off = DG_WAVES / 2; off > 0; off >>= 1) {
-                const float ov = __shfl_xor(rv, off);
-                const int oi = __shfl_xor(ri, off);
-                const bool take = oi != INT_MAX && (ri == INT_MAX || ov > rv || (ov == rv && oi < ri));
-                rv = take ? ov : rv;
-                ri = take ? oi : ri;
-            }
+            hx_wave_argmax(rv, ri);
         }
         if (tid == 0) {
             const int c = ri, d = s_bd[c];

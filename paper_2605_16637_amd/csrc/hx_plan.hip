@@ -357,14 +357,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
                 if (bi == 0x7fffffff || r > bv) { bv = r; bi = c; }
             }
         }
-#pragma unroll
-        for (int off = HX_WAVE / 2; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(bv, off);
-            const int oi = __shfl_xor(bi, off);
-            const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-            bv = take ? ov : bv;
-            bi = take ? oi : bi;
-        }
+        hx_wave_argmax(bv, bi);
         if (lane == 0) { s_redv[wave] = bv; s_redi[wave] = bi; }
         __syncthreads();
         // (3) the first wavefront takes the best of the wavefronts' candidates (one per lane, the same rule), and its
@@ -372,14 +365,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         if (wave == 0) {
             bv = lane < GREEDY_WAVES ? s_redv[lane] : -INFINITY;
             bi = lane < GREEDY_WAVES ? s_redi[lane] : 0x7fffffff;
-#pragma unroll
-            for (int off = GREEDY_WAVES / 2; off > 0; off >>= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oi = __shfl_xor(bi, off);
-                const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-                bv = take ? ov : bv;
-                bi = take ? oi : bi;
-            }
+            hx_wave_argmax(bv, bi);
         }
         if (tid == 0) {
             const int c = bi, p = s_bp[c], d = s_bd[c];

@@ -24,36 +24,48 @@
 // Minimum over the 64 lanes of a wavefront with data-parallel-primitive lane
 // moves (no LDS traffic): two quad swaps and two row mirrors leave every row
 // of 16 lanes holding its minimum, two row broadcasts carry it to lane 63,
-// which is read back as a wave-uniform value.
-#define HX_DPP_MIN_STEP(T_, MINF, ctrl, row_mask)                                                        \
-    x = MINF(x, hx_from_bits<T_>(__builtin_amdgcn_update_dpp(hx_to_bits(x), hx_to_bits(x), ctrl, row_mask, 0xf, false)))
-
-template <typename T> __device__ __forceinline__ T hx_from_bits(int b);
-template <> __device__ __forceinline__ float hx_from_bits<float>(int b) { return __int_as_float(b); }
-template <> __device__ __forceinline__ int hx_from_bits<int>(int b) { return b; }
-__device__ __forceinline__ int hx_to_bits(float x) { return __float_as_int(x); }
-__device__ __forceinline__ int hx_to_bits(int x) { return x; }
+// which is read back as a wave-uniform value.  Each step is one instruction,
+// the minimum itself taking its first operand through the lane move (lanes
+// a row mask leaves out keep their value: the destination is the operand).
+// A lane move may read a register two cycles after a vector instruction wrote
+// it at the earliest, and five after one wrote the execution mask; the
+// compiler does not see inside these statements, so they carry their own waits
+// (and one at the end, before the lane read that follows).
+#define HX_DPP_MIN_CHAIN(OP)                                                                  \
+    "s_nop 4\n\t" OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"        \
+    "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"        \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"            \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"                 \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"               \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"               \
+    "s_nop 1"
 
 __device__ __forceinline__ float hx_wave_min(float x)
 {
-    HX_DPP_MIN_STEP(float, fminf, 0xB1, 0xf);     // quad_perm [1,0,3,2]
-    HX_DPP_MIN_STEP(float, fminf, 0x4E, 0xf);     // quad_perm [2,3,0,1]
-    HX_DPP_MIN_STEP(float, fminf, 0x141, 0xf);    // row_half_mirror
-    HX_DPP_MIN_STEP(float, fminf, 0x140, 0xf);    // row_mirror
-    HX_DPP_MIN_STEP(float, fminf, 0x142, 0xa);    // row_bcast15 into rows 1 and 3
-    HX_DPP_MIN_STEP(float, fminf, 0x143, 0xc);    // row_bcast31 into rows 2 and 3
+    asm volatile(HX_DPP_MIN_CHAIN("v_min_f32_dpp") : "+v"(x));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
 __device__ __forceinline__ int hx_wave_min(int x)
 {
-    HX_DPP_MIN_STEP(int, min, 0xB1, 0xf);
-    HX_DPP_MIN_STEP(int, min, 0x4E, 0xf);
-    HX_DPP_MIN_STEP(int, min, 0x141, 0xf);
-    HX_DPP_MIN_STEP(int, min, 0x140, 0xf);
-    HX_DPP_MIN_STEP(int, min, 0x142, 0xa);
-    HX_DPP_MIN_STEP(int, min, 0x143, 0xc);
+    asm volatile(HX_DPP_MIN_CHAIN("v_min_i32_dpp") : "+v"(x));
     return __builtin_amdgcn_readlane(x, 63);
+}
+
+__device__ __forceinline__ float hx_wave_max(float x)
+{
+    asm volatile(HX_DPP_MIN_CHAIN("v_max_f32_dpp") : "+v"(x));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// The wavefront's largest value and the lowest index that has it, in every lane.  A lane without a
+// candidate passes (-inf, INT_MAX): it loses to every candidate, also to one whose value is -inf.
+// Every lane of the wavefront must be active.
+__device__ __forceinline__ void hx_wave_argmax(float &v, int &i)
+{
+    const float top = hx_wave_max(v);
+    i = hx_wave_min(v == top ? i : 0x7fffffff);
+    v = top;
 }
 
 // views of the pool tables staged in LDS
@@ -121,9 +133,18 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
     const HxCallF cf = hx_call_terms(m, L, O);
     const int Dp = s.Dp;
 
-    // decode time of this call on every decode entry (+inf where it does not fit)
-    for (int e = lane; e < Dp; e += HX_WAVE)
-        dbuf[e] = hx_fits(L, O, s.free[e]) ? hx_decode_time(cf, s.c1[e], s.c2[e], s.kB[e]) : INFINITY;
+    // decode time of this call on every decode entry (+inf where it does not fit), four entries per lane and
+    // step (Dp is a multiple of the group size, the tables are 16-byte aligned)
+    for (int e = 4 * lane; e < Dp; e += 4 * HX_WAVE) {
+        const int4 fr = *(const int4 *)(s.free + e);
+        const float4 c1 = *(const float4 *)(s.c1 + e), c2 = *(const float4 *)(s.c2 + e), kB = *(const float4 *)(s.kB + e);
+        float4 t;
+        t.x = hx_fits(L, O, fr.x) ? hx_decode_time(cf, c1.x, c2.x, kB.x) : INFINITY;
+        t.y = hx_fits(L, O, fr.y) ? hx_decode_time(cf, c1.y, c2.y, kB.y) : INFINITY;
+        t.z = hx_fits(L, O, fr.z) ? hx_decode_time(cf, c1.z, c2.z, kB.z) : INFINITY;
+        t.w = hx_fits(L, O, fr.w) ? hx_decode_time(cf, c1.w, c2.w, kB.w) : INFINITY;
+        *(float4 *)(dbuf + e) = t;
+    }
     xbuf[lane] = hx_transfer(cf, s.invbw[lane], s.lat[lane]);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -173,9 +194,15 @@ __device__ __forceinline__ HxBest hx_search_call(const HxModelF &m, const HxPool
         const float done = hx_prefill_done(cf, s.pw[bestp], s.pinvF[bestp], s.pinvB[bestp]);
         const float *xr = xbuf + s.ptype[bestp] * kT;
         int dmin = 0x7fffffff;
-        for (int e = lane; e < Dp; e += HX_WAVE) {
-            const float v = hx_candidate(done + xr[s.dtype[e]], s.wait[e], dbuf[e]);
-            if (v == bestv) dmin = min(dmin, s.orig[e]);
+        // four entries per lane and step: a group of entries is of one class (pads have no decode time and never match)
+        for (int e = 4 * lane; e < Dp; e += 4 * HX_WAVE) {
+            const float ready = done + xr[s.dtype[e]];
+            const float4 w = *(const float4 *)(s.wait + e), t = *(const float4 *)(dbuf + e);
+            const int4 og = *(const int4 *)(s.orig + e);
+            if (hx_candidate(ready, w.x, t.x) == bestv) dmin = min(dmin, og.x);
+            if (hx_candidate(ready, w.y, t.y) == bestv) dmin = min(dmin, og.y);
+            if (hx_candidate(ready, w.z, t.z) == bestv) dmin = min(dmin, og.z);
+            if (hx_candidate(ready, w.w, t.w) == bestv) dmin = min(dmin, og.w);
         }
         out.d = hx_wave_min(dmin);
     }
