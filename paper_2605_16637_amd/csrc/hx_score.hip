@@ -751,7 +751,8 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
         // Workgroups of 4 or 8 wavefronts (one or two per SIMD), as many per compute unit as local memory allows up
         // to 6 wavefronts per SIMD (registers would allow 7; measured no faster, and 6 divides into either
         // workgroup size): the pool tables are per workgroup, a wavefront adds its decode-time and transfer
-        // buffers.  Whichever size puts more wavefronts on a SIMD.
+        // buffers.  Whichever size puts more wavefronts on a SIMD, the larger on a tie (half as many workgroups derive
+        // the pool's tables).
         const FusedLds lay(dp_bound, P);
         if (reveal) {
             // Workgroups of four wavefronts, as many searching ones as are resident at once (six per compute unit, or
@@ -787,7 +788,7 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
             if (need_lds > 160 * 1024) continue;
             int b = (int)((160 * 1024) / need_lds);
             b = b > reg_limit / w ? reg_limit / w : b;
-            if (b * w > best_on_cu) { best_on_cu = b * w; waves = w; blocks_per_cu = b; }
+            if (b * w >= best_on_cu) { best_on_cu = b * w; waves = w; blocks_per_cu = b; }
         }
         const size_t lds = lay.bytes(waves);
         HX_REQUIRE(ctx, best_on_cu > 0, HX_ERR_SHAPE, "pool needs %zu B of LDS", lds);
