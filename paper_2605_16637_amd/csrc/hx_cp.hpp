@@ -199,7 +199,7 @@ __device__ __forceinline__ bool hx_cp_walk(const CpArgs &a, char *base, int n0, 
 // ROLLED: the cost's class pairs one after the other (hx_node_cost_eval_rolled), for a kernel with few registers to spare.
 template <int NMAX, bool COST, bool STREAM, bool ROLLED = false>
 __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNode *s_node, int &s_any,
-                                                 const NodeCostArgs *nc, CostTables *tab)
+                                                 const NodeCostArgs *nc, CostTables *tab, int block)
 {
     // COST: the class tables are filled once, by the block's first run, after that run's own loads have been asked
     // for (the tables' loads and divisions then run under those instead of in front of them); block-uniform
@@ -207,10 +207,10 @@ __device__ __forceinline__ void hx_cp_local_body(const CpArgs &a, int wpb, CpNod
     constexpr int CP_NMAX = NMAX;             // nodes staged per run
     constexpr int CP_NPT = (NMAX + CP_THREADS - 1) / CP_THREADS;
     const int tid = threadIdx.x;
-    const int w0 = blockIdx.x * wpb;
+    const int w0 = block * wpb;
     const int w1 = min(w0 + wpb, a.n_wf);
-    // the walking lanes: wave (blockIdx mod 4), lane = workflow within the run
-    const int wl = tid - ((int)(blockIdx.x & 3) << 6);
+    // the walking lanes: wave (block mod 4), lane = workflow within the run
+    const int wl = tid - ((block & 3) << 6);
     bool not_dag = false, bad_index = false;
     if (tid == 0) s_node[0] = CpNode{0, -1, 0u, 0u};
     char *const base = (char *)s_node;

@@ -47,7 +47,7 @@ void hx_cp_local_kernel(CpArgs a, int wpb)
 {
     __shared__ CpNode s_node[CP_NMAX + 1];
     __shared__ int s_any;                     // == first workflow of the run + 1: a node of this run was left to the walk
-    hx_cp_local_body<CP_NMAX, false, STREAM>(a, wpb, s_node, s_any, nullptr, nullptr);
+    hx_cp_local_body<CP_NMAX, false, STREAM>(a, wpb, s_node, s_any, nullptr, nullptr, (int)blockIdx.x);
 }
 
 // The same pass with the standalone node cost worked out while staging instead of being read:
@@ -61,7 +61,7 @@ void hx_cp_cost_kernel(CpArgs a, NodeCostArgs nc, int wpb)
     __shared__ CpNode s_node[CP_NMAX_COST + 1];
     __shared__ int s_any;
     __shared__ CostTables s_tab;
-    hx_cp_local_body<CP_NMAX_COST, true, false>(a, wpb, s_node, s_any, &nc, &s_tab);
+    hx_cp_local_body<CP_NMAX_COST, true, false>(a, wpb, s_node, s_any, &nc, &s_tab, (int)blockIdx.x);
 }
 
 // ---- critical path, level-synchronous sweeps ------------------------------------------

@@ -394,12 +394,12 @@ __global__ __launch_bounds__(512) void hx_fused_search_kernel(ScoreArgs a, PrepA
 //
 // The horizon refresh (node cost + critical path, what hx_cp_cost_kernel does) and the search do not depend on each
 // other -- only the ratio needs both, and it is formed by the commit kernel that follows -- so they share a launch:
-// the first n_reveal workgroups take workflows exactly as hx_cp_cost_kernel's do (same body, the cost's prefill
-// classes one after the other to stay within the search's registers), the others search.  Same results as the
-// two kernels, one launch and the gap before it less.  On a small round (every wavefront has at most one call,
-// all workgroups resident at once) both halves are chains of memory round trips, which now run side by side; on a
-// large one the reveal's workgroups hold their places for some ten microseconds while the rest of the chip
-// searches, and the searching workgroups that start after them are the ones with the fewest calls.
+// n_reveal workgroups take workflows exactly as hx_cp_cost_kernel's do (same body, the cost's prefill classes one
+// after the other to stay within the search's registers), the others search.  Same results as the two kernels,
+// one launch and the gap before it less.  On a small round (every wavefront has at most one call, all workgroups
+// resident at once) both halves are chains of memory round trips, which now run side by side; on a large one the
+// reveal's workgroups, the last of the grid then, take the places of the searching workgroups that end first
+// (those whose wavefronts were dealt one call fewer) while the rest of the chip goes on searching.
 constexpr int RV_NMAX = 512;             // nodes staged per run of a reveal workgroup
 
 struct RevealLds {
@@ -408,17 +408,21 @@ struct RevealLds {
     int any;
 };
 
-template <int KP>
+// FIRST: the reveal's workgroups are the first n_reveal of the grid (else the last)
+template <int KP, bool FIRST>
 __global__ __launch_bounds__(CP_THREADS) void hx_reveal_search_kernel(ScoreArgs a, PrepArgs pa, int dp_bound, CpArgs cp,
                                                                       NodeCostArgs nc, int wpb, int n_reveal)
 {
     extern __shared__ __align__(16) float smem[];
-    if ((int)blockIdx.x < n_reveal) {
+    const int n_search = (int)gridDim.x - n_reveal;
+    const int block = FIRST ? (int)blockIdx.x - n_reveal : (int)blockIdx.x;              // among the searching ones
+    if (FIRST ? block < 0 : block >= n_search) {
         RevealLds *l = (RevealLds *)smem;
-        hx_cp_local_body<RV_NMAX, true, false, true>(cp, wpb, l->node, l->any, &nc, &l->tab);
+        hx_cp_local_body<RV_NMAX, true, false, true>(cp, wpb, l->node, l->any, &nc, &l->tab,
+                                                     FIRST ? (int)blockIdx.x : block - n_search);
         return;
     }
-    hx_fused_search_body<KP>(a, pa, dp_bound, smem, (int)blockIdx.x - n_reveal, (int)gridDim.x - n_reveal);
+    hx_fused_search_body<KP>(a, pa, dp_bound, smem, block, n_search);
 }
 
 // The same for a round that appends to the context's graph: the append's walks (hx_append_relax_kernel's work: one
@@ -674,8 +678,11 @@ int hx_score_init()
     const int lds = 160 * 1024;
     const void *kernels[] = {
         reinterpret_cast<const void *>(hx_fused_search_kernel<1>), reinterpret_cast<const void *>(hx_fused_search_kernel<2>),
-        reinterpret_cast<const void *>(hx_fused_search_kernel<4>), reinterpret_cast<const void *>(hx_reveal_search_kernel<1>),
-        reinterpret_cast<const void *>(hx_reveal_search_kernel<2>), reinterpret_cast<const void *>(hx_reveal_search_kernel<4>),
+        reinterpret_cast<const void *>(hx_fused_search_kernel<4>),
+        reinterpret_cast<const void *>(hx_reveal_search_kernel<1, true>), reinterpret_cast<const void *>(hx_reveal_search_kernel<2, true>),
+        reinterpret_cast<const void *>(hx_reveal_search_kernel<4, true>),
+        reinterpret_cast<const void *>(hx_reveal_search_kernel<1, false>), reinterpret_cast<const void *>(hx_reveal_search_kernel<2, false>),
+        reinterpret_cast<const void *>(hx_reveal_search_kernel<4, false>),
         reinterpret_cast<const void *>(hx_relax_search_kernel<1>), reinterpret_cast<const void *>(hx_relax_search_kernel<2>),
         reinterpret_cast<const void *>(hx_relax_search_kernel<4>)};
     hipError_t e = hipSuccess;
@@ -756,11 +763,14 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
         const FusedLds lay(dp_bound, P);
         if (reveal) {
             // Workgroups of four wavefronts, as many searching ones as are resident at once (six per compute unit, or
-            // what local memory allows) or as the calls need, whichever is less; the reveal's workgroups come first in
-            // the grid and run first.  Where the searching workgroups alone fill the chip, the last of them start when
-            // the reveal's have gone -- and those are the ones whose wavefronts have the fewest calls (calls are dealt
-            // c, c + n, ...), so they still end before the others.  Not this way if the reveal's units are too large
-            // for its staging area or its workgroups more than a third of the searching ones.
+            // what local memory allows) or as the calls need, whichever is less.  Where all of the launch is resident
+            // at once the reveal's workgroups are the first of the grid.  Where the searching workgroups alone fill
+            // the chip they are the last: they start as the first searching workgroups end -- those whose wavefronts
+            // have the fewest calls (calls are dealt c, c + n, ...) -- in places that would stand empty for the rest of
+            // the launch, and are done before the wavefronts with one call more (in front of the grid they held up
+            // that many searching workgroups from the start: 73 us against 71 for the large round's launch).  Not this
+            // way if the reveal's units are too large for its staging area or its workgroups more than a third of
+            // the searching ones.
             const size_t lds4 = lay.bytes(4) > sizeof(RevealLds) ? lay.bytes(4) : sizeof(RevealLds);
             if (lds4 > 160 * 1024) return HX_OK;
             const long long by_lds = (long long)(160 * 1024) / (long long)lds4;
@@ -774,9 +784,15 @@ int score_placements(hx_ctx *ctx, const hx_model *model, const hx_calls *calls,
                 kern<<<reveal->grid + n_search, CP_THREADS, lds4, stream>>>(a, pa, dp_bound, reveal->a, reveal->nc, reveal->wpb,
                                                                             reveal->grid);
             };
-            if (P <= 64) launch(hx_reveal_search_kernel<1>);
-            else if (P <= 128) launch(hx_reveal_search_kernel<2>);
-            else launch(hx_reveal_search_kernel<4>);
+            if (all_resident) {
+                if (P <= 64) launch(hx_reveal_search_kernel<1, true>);
+                else if (P <= 128) launch(hx_reveal_search_kernel<2, true>);
+                else launch(hx_reveal_search_kernel<4, true>);
+            } else {
+                if (P <= 64) launch(hx_reveal_search_kernel<1, false>);
+                else if (P <= 128) launch(hx_reveal_search_kernel<2, false>);
+                else launch(hx_reveal_search_kernel<4, false>);
+            }
             if (int rc = hx_check_launch(ctx, "hx_reveal_search_kernel")) return rc;
             *revealed = true;
             return HX_OK;
