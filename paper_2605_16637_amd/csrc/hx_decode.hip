@@ -977,6 +977,15 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                     s_cnt[d] += 1;
                     changed = d;
                     __threadfence();
+                    // The usual case -- the interval holds something, starts now or later, ends at a finite time, and
+                    // the timeline has at most one entry per thread -- is inserted into the timeline below;
+                    // anything else has the timeline built again from the instance's intervals.
+                    const float S = s_bs[c], E = s_bc[c];
+                    s_pick[1] = (S >= 0.0f && S < E && E < INFINITY && need > 0 && s_n[d] <= DG_THREADS) ? 1 : 0;
+                    s_pick[2] = s_n[d]; s_pick[3] = s_n[d];          // entries before S, before E: all, unless an entry says otherwise
+                    s_pick[4] = __float_as_int(S > 0.0f ? S : 0.0f); s_pick[5] = __float_as_int(E);
+                    s_pick[6] = need > (long long)INT_MAX ? INT_MAX : (int)need;
+                    s_pick[7] = s_cnt[d];                            // 1 + the interval's index
                 }
             }
             s_pick[0] = changed;
@@ -987,7 +996,57 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         if (pd >= 0) {
             const size_t at = (size_t)pd * a.stride;
             Tl tl{s_tl + (size_t)pd * lay.nt, s_src + (size_t)pd * lay.ne};
-            hx_build_timeline<true>(s_cnt[pd], a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n[pd], a.status);
+            if (s_pick[1]) {
+                // The compact timeline is a function of the instance's events, so adding the two events of the new
+                // interval (S, E, tok) to it gives what building it again would: entries from S up to E hold tok
+                // more; S and E become entries of their own unless the timeline already has an entry at that time
+                // (S: the occupancy before it plus tok; E: the occupancy that stood before E); the entry at E is
+                // the end of the new interval (of all events at one time the end with the highest index counts).
+                const int n = s_n[pd];
+                const float S = __int_as_float(s_pick[4]), E = __int_as_float(s_pick[5]);
+                const int tok = s_pick[6];
+                const bool in = tid < n;
+                const int2 me = in ? tl.e[tid] : make_int2(0x7f800000, 0);
+                const short my_src = in ? tl.src[tid] : (short)0;
+                const float t = __int_as_float(me.x);
+                const float before = (in && tid > 0) ? __int_as_float(tl.e[tid - 1].x) : -1.0f;
+                if (in && t >= S && before < S) s_pick[2] = tid;
+                if (in && t >= E && before < E) s_pick[3] = tid;
+                __syncthreads();
+                const int pos_s = s_pick[2], pos_e = s_pick[3];                   // pos_e >= 1: entry 0 is now, and E > 0
+                const bool has_s = pos_s < n && __int_as_float(tl.e[pos_s].x) == S;
+                const bool has_e = pos_e < n && __int_as_float(tl.e[pos_e].x) == E;
+                const int occ_before_s = tl.e[pos_s > 0 ? pos_s - 1 : 0].y, occ_before_e = tl.e[pos_e - 1].y;
+                const int old_len = hx_tl_len(2 * s_cnt[pd] - 1), new_len = hx_tl_len(2 * s_cnt[pd] + 1);
+                __syncthreads();                                                  // every old entry has been read
+                const int n_new = n + (has_s ? 0 : 1) + (has_e ? 0 : 1);
+                if (in) {
+                    const int at_new = tid + ((!has_s && tid >= pos_s) ? 1 : 0) + ((!has_e && tid >= pos_e) ? 1 : 0);
+                    long long occ = me.y;
+                    if (tid >= pos_s && tid < pos_e) occ += tok;
+                    if (occ > (long long)INT_MAX) { hx_raise(a.status, HX_ERR_OVERFLOW); occ = INT_MAX; }
+                    tl.e[at_new] = make_int2(me.x, (int)occ);
+                    tl.src[at_new] = (has_e && tid == pos_e) ? (short)s_pick[7] : my_src;
+                }
+                if (tid == 0 && !has_s) {
+                    long long occ = (long long)occ_before_s + tok;
+                    if (occ > (long long)INT_MAX) { hx_raise(a.status, HX_ERR_OVERFLOW); occ = INT_MAX; }
+                    tl.e[pos_s] = make_int2(s_pick[4], (int)occ);
+                    tl.src[pos_s] = 0;
+                }
+                if (tid == HX_WAVE && !has_e) {
+                    const int at_e = pos_e + (has_s ? 0 : 1);
+                    tl.e[at_e] = make_int2(s_pick[5], occ_before_e);
+                    tl.src[at_e] = (short)s_pick[7];
+                }
+                // the filler behind the entries reaches as far as a timeline of two more events may be read
+                for (int i = old_len + tid; i < new_len; i += DG_THREADS)
+                    if (i >= n_new) tl.e[i] = make_int2(0x7f800000, 0);
+                if (tid == 2 * HX_WAVE) s_n[pd] = n_new;
+                __syncthreads();
+            } else {
+                hx_build_timeline<true>(s_cnt[pd], a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n[pd], a.status);
+            }
             if (!keep_all) {
                 for (int c = tid; c < a.Q; c += DG_THREADS)
                     if ((s_flags[c] & DG_ALIVE) && s_bd[c] == pd) s_flags[c] = DG_ALIVE | DG_DIRTY;

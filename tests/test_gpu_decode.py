@@ -421,6 +421,27 @@ def test_decode_greedy_with_workflows_without_horizon(ctx, Q, D, stride, res, pl
     assert (got["best_d"][urgent] >= 0).any()
 
 
+@pytest.mark.parametrize("Q,D,stride,res,plan", [(40, 4, 16, 10, 3), (80, 64, 16, 10, 3)])      # finish of every pair kept; not kept
+def test_decode_greedy_with_calls_that_decode_nothing(ctx, Q, D, stride, res, plan):
+    # a call without output tokens finishes when it starts: its interval holds nothing and the instance's timeline
+    # stays as it is (the planner then builds the timeline again instead of inserting the interval)
+    r, lock, iv = synth.make_decode_round("decode_tiny", 37, n_wf=max(8, Q // 4), Q=Q, D=D, T=min(4, D), stride=stride,
+                                          n_resident=res, n_planned=plan, lock_fraction=0.2)
+    L, O = r.calls["L_in"].copy(), r.calls["L_out"].copy()
+    O[::3] = 0
+    rng = np.random.default_rng(11)
+    n_nodes, n_wf = Q + 5, 4
+    node = rng.permutation(n_nodes)[:Q].astype(np.int32); wf = rng.integers(0, n_wf, Q).astype(np.int32)
+    elapsed = rng.uniform(0, 20, Q).astype(np.float32)
+    tail = rng.uniform(0, 5, n_nodes).astype(np.float32); hor = rng.uniform(5, 50, n_wf).astype(np.float32)
+    big = widen(iv, D, Q)
+    got = run_plan(ctx, r.model, L, O, lock, node, wf, elapsed, tail, hor, r.dec, big)
+    check_plan_stepwise(r.model, L, O, lock, node, wf, elapsed, tail, hor, r.dec, big, got)
+    placed = got["best_d"] >= 0
+    assert (placed & (O == 0)).sum() > 3 and (placed & (O > 0)).sum() > 3
+    assert np.array_equal(got["best_start"][placed & (O == 0)], got["best_cost"][placed & (O == 0)])
+
+
 def test_decode_greedy_at_the_benchmarks_size(ctx):
     # the queue bench.py times: 256 calls x 32 instances, 24 resident + 4 planned entries each, lists of 140 entries
     Q, D = 256, 32
