@@ -64,7 +64,7 @@ struct hx_ctx {
     size_t dpart_cap = 0;
     unsigned long long *d_rkey = nullptr;  // sorted tiles of ordering keys, [rkey_cap]
     size_t rkey_cap = 0;
-    void *d_dtl = nullptr;                 // decode-stage timelines (entries, lengths, sources), dtl_cap entries
+    void *d_dtl = nullptr;                 // decode-stage timelines (entries, lengths, stretches, sorted occupancies), dtl_cap entries
     size_t dtl_cap = 0;
     float *d_dtab = nullptr;               // decode-stage first-room tables, dtab_cap instances
     int dtab_cap = 0;

@@ -31,13 +31,11 @@ struct TlScratch {
     int *delta;      // +tok at a start, -tok at an end
     float *ts;       // sorted: time
     int *ds;         //         delta
-    short *su, *ss;  // unsorted / sorted: 1 + index of the interval that ends here, 0 = now
 };
 
 // compact timeline: entry i covers [t_i, t_{i+1}) (the last one has no end) with occupancy occ_i
 struct Tl {
     int2 *e;         // (time bits, occupancy)
-    short *src;      // which interval's end t_i is (1 + index), 0 = now
 };
 
 __host__ __device__ inline size_t hx_align16(size_t x) { return (x + 15) & ~(size_t)15; }
@@ -52,14 +50,12 @@ __device__ inline TlScratch hx_carve_scratch(unsigned char *p, int ne)
     w.key = (u64 *)p;                 p += hx_align16((size_t)ne * 8);
     w.delta = (int *)p;               p += hx_align16((size_t)ne * 4);
     w.ts = (float *)p;                p += hx_align16((size_t)ne * 4);
-    w.ds = (int *)p;                  p += hx_align16((size_t)ne * 4);
-    w.su = (short *)p;                p += hx_align16((size_t)ne * 2);
-    w.ss = (short *)p;
+    w.ds = (int *)p;
     return w;
 }
 __host__ __device__ inline size_t hx_scratch_bytes(int ne)
 {
-    return hx_align16((size_t)ne * 8) + 3 * hx_align16((size_t)ne * 4) + 2 * hx_align16((size_t)ne * 2);
+    return hx_align16((size_t)ne * 8) + 3 * hx_align16((size_t)ne * 4);
 }
 
 template <bool COHERENT, typename T> __device__ __forceinline__ T hx_ld(const T *p)
@@ -79,7 +75,7 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
     const int n_ev = 2 * cnt + 1;
     for (int i = tid; i < n_ev; i += nthreads) {
         float time = 0.0f;
-        int delta = 0, src = 0;
+        int delta = 0;
         unsigned is_end = 1;                               // event 0 is "now"
         if (i > 0) {
             const int j = (i - 1) >> 1;
@@ -90,13 +86,11 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
                 const float x = is_end ? e : s;
                 time = x > 0.0f ? x : 0.0f;                // the past is folded onto now
                 delta = is_end ? -k : k;
-                src = (is_end && e > 0.0f) ? j + 1 : 0;
             }
         }
         // at equal times starts sort before ends, so the last event of a time is an end if there is one
         w.key[i] = ((u64)__float_as_uint(time) << 32) | ((u64)is_end << 31) | (unsigned)i;
         w.delta[i] = delta;
-        w.su[i] = (short)src;
     }
     __syncthreads();
     // position of every event = number of smaller keys (keys are unique)
@@ -114,7 +108,6 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
         for (; j < n_ev; ++j) r += w.key[j] < ki;
         w.ts[r] = __uint_as_float((unsigned)(ki >> 32));
         w.ds[r] = w.delta[i];
-        w.ss[r] = w.su[i];
     }
     __syncthreads();
     // one wavefront: running occupancy, and one entry per distinct time (the last event of that time)
@@ -143,7 +136,6 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
                 if (run > (long long)INT_MAX) hx_raise(status, HX_ERR_OVERFLOW);
                 const int occ = run > (long long)INT_MAX ? INT_MAX : (int)run;
                 out.e[pos] = make_int2(__float_as_int(w.ts[i]), occ);
-                out.src[pos] = w.ss[i];
                 ++pos;
             }
         }
@@ -158,7 +150,7 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
 
 struct HxSlot {
     float S;     // start, +inf if none
-    int src;     // 1 + index of the interval whose end S is, 0 = now, -1 if none
+    bool found;
 };
 
 // thr = tokens the call may find occupied (capacity - demand), < 0: never fits.  T = decode time.
@@ -171,7 +163,7 @@ struct HxSlot {
 // whose successor is "never" always has room: everything has ended by then).  Run starts only
 // grow along the timeline, so the earliest start is the minimum over all hits.  The loop ends when
 // every lane has its answer or has passed the end of its timeline.
-__device__ __forceinline__ HxSlot hx_earliest_start(const int2 *e, const short *src, int n, int thr, float T, bool active)
+__device__ __forceinline__ HxSlot hx_earliest_start(const int2 *e, int n, int thr, float T, bool active)
 {
     const bool open = active && thr >= 0;
     float rs = INFINITY, ans = INFINITY;
@@ -201,18 +193,8 @@ __device__ __forceinline__ HxSlot hx_earliest_start(const int2 *e, const short *
         c0 = n0; c1 = n1; c2 = n2; c3 = n3;
     }
 #undef HX_TL_STEP
-    HxSlot r{INFINITY, -1};
-    if (open && ans < INFINITY) {
-        // which entry the start is: times are strictly increasing, so a bisection finds it
-        int lo = 0, hi = n - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (__int_as_float(e[mid].x) < ans) lo = mid + 1; else hi = mid;
-        }
-        r.S = ans;
-        r.src = src[lo];
-    }
-    return r;
+    const bool found = open && ans < INFINITY;
+    return HxSlot{found ? ans : INFINITY, found};
 }
 
 // ---- one scoring pass over (queue x instances) -----------------------------------------
@@ -266,7 +248,6 @@ constexpr int HX_TAB_FLAG = 1 << 16;  // added to the stretch count in an instan
 
 struct TlOut {
     int2 *e;         // [D][nt] timeline entries, padded
-    short *src;      // [D][ne]
     int *n;          // [D] entries
     int *seg;        // [D][nt] heads of the stretches, then n
     int2 *head;      // [D][nt] per stretch: (time of its head, rank of the head's occupancy), padded with (-inf, 0)
@@ -288,7 +269,6 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
     TlScratch w = hx_carve_scratch(smem, ne);
     Tl tl;
     tl.e = (int2 *)(smem + hx_scratch_bytes(ne));
-    tl.src = (short *)(smem + hx_scratch_bytes(ne) + hx_align16((size_t)hx_tl_len(ne) * 8));
     int cnt = a.iv_count[d];
     if (cnt < 0 || cnt > a.stride) {
         if (tid == 0) hx_raise(a.status, HX_ERR_INDEX);
@@ -387,7 +367,6 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
 
     // ---- the last barrier is behind: everything goes to memory
     for (int i = tid; i < hx_tl_len(2 * cnt + 1); i += blockDim.x) o.e[(size_t)d * nt + i] = tl.e[i];
-    for (int i = tid; i < n; i += blockDim.x) o.src[(size_t)d * ne + i] = tl.src[i];
     for (int k = tid; k <= m; k += blockDim.x) o.seg[(size_t)d * nt + k] = (int)seg_l[k];
     if (my_place >= 0) a.free_c[d * a.per + my_place] = c_lo + tid;
     if (tid == 0) {
@@ -462,7 +441,7 @@ __device__ __forceinline__ float hx_earliest_start_shared(const int2 *__restrict
 // the head has room; otherwise the next run begins at the stretch's first entry with room, G[k][r].
 // Inside a run that entry is the head itself, later than the run's start, so one minimum serves both
 // cases.  The same comparisons on the same values as the scan: the same start bit for bit.
-// head: per stretch (time, rank) in groups of eight, read as scalars; G, sorted, t, src: LDS.
+// head: per stretch (time, rank) in groups of eight, read as scalars; G, sorted: LDS.
 // first: the first eight heads, which the caller asked for ahead of time.
 __device__ __forceinline__ float hx_earliest_start_table(const int2 *__restrict__ head, HxTlGroup first, const float *G,
                                                          const int *sorted, int n, int m, int thr, float T, bool active)
@@ -634,7 +613,6 @@ __global__ __launch_bounds__(DS_THREADS) void hx_decode_score_kernel(DecodeArgs 
     static_assert(DS_BUF >= HX_MAX_INSTANCES + 1, "the slice prefixes fit in the staging buffer");
     __shared__ int s_wave_n[DS_THREADS / HX_WAVE];
     const int tid = threadIdx.x;
-    const int ne = 2 * a.stride + 1;
     if ((int)blockIdx.x < n_lock) {
         const int c = (int)blockIdx.x * DS_THREADS + tid;
         const bool in = c < a.Q;
@@ -645,9 +623,9 @@ __global__ __launch_bounds__(DS_THREADS) void hx_decode_score_kernel(DecodeArgs 
         const int d = legal ? lk : 0;
         const HxDecF x = hx_decode_terms(a.m, a.d_used[d], a.d_batch[d], 0, 1.0f / a.d_flops[d], 1.0f / a.d_hbm[d]);
         const HxDecodeCand k = hx_decode_candidate(a.m, legal ? L : 0, legal ? O : 0, -1, d, a.D, x, a.d_cap[d], a.status);
-        const HxSlot s = hx_earliest_start(o.e + (size_t)d * nt, o.src + (size_t)d * ne, o.n[d], k.thr, k.T, legal);
+        const HxSlot s = hx_earliest_start(o.e + (size_t)d * nt, o.n[d], k.thr, k.T, legal);
         const float v = s.S + k.T;
-        const bool placed = legal && s.src >= 0 && v < INFINITY;
+        const bool placed = legal && s.found && v < INFINITY;
         if (in && !(ok && lk < 0)) {                       // locked or invalid: this lane speaks for the call
             a.part_cost[c] = placed ? v : INFINITY;
             a.part_start[c] = placed ? s.S : INFINITY;
@@ -656,7 +634,7 @@ __global__ __launch_bounds__(DS_THREADS) void hx_decode_score_kernel(DecodeArgs 
                 for (int j = 0; j < a.D; ++j) {
                     const bool here = legal && j == d;
                     if (a.start) a.start[(size_t)c * a.D + j] = here ? s.S : INFINITY;
-                    if (a.cost) a.cost[(size_t)c * a.D + j] = (here && s.src >= 0) ? v : INFINITY;
+                    if (a.cost) a.cost[(size_t)c * a.D + j] = (here && s.found) ? v : INFINITY;
                 }
         }
         return;
@@ -825,23 +803,22 @@ struct DGreedyLds {
     // + 2: the lanes of a wavefront scan different timelines with 16-byte reads; with a timeline length of
     // 4k + 2 entries neighbouring timelines start 16 bytes apart modulo the banks instead of on the same ones
     __host__ __device__ size_t off_tl() const { return hx_scratch_bytes(ne); }
-    __host__ __device__ size_t off_src() const { return off_tl() + hx_align16((size_t)D * nt * 8); }
-    __host__ __device__ size_t off_inst() const { return off_src() + hx_align16((size_t)D * ne * 2); }
+    __host__ __device__ size_t off_inst() const { return off_tl() + hx_align16((size_t)D * nt * 8); }
     __host__ __device__ size_t off_call() const { return off_inst() + (size_t)6 * D * 4; }
     __host__ __device__ size_t off_red() const { return off_call() + (size_t)11 * Q * 4; }
     __host__ __device__ size_t off_mat() const { return hx_align16(off_red() + (size_t)(2 * DG_WAVES + 8) * 4); }
     __host__ __device__ size_t bytes() const { return off_mat(); }
-    // with the finish of every (instance, call) pair kept: [D][Q] floats more
+    // with the start of every (instance, call) pair kept: [D][Q] floats more
     __host__ __device__ size_t bytes_with_matrix() const { return off_mat() + (size_t)D * Q * 4; }
 };
 
 enum : int { DG_ALIVE = 1, DG_DIRTY = 2 };
 
 // An added interval can only delay starts on the instance that received it; everything else stands.
-// keep_all (when LDS has room for the finish of every (instance, call) pair): after a step only that
+// keep_all (when LDS has room for the start of every (instance, call) pair): after a step only that
 // instance's column is computed again, one call per lane, all lanes on the same timeline; a call whose best
-// was there takes the minimum of its row again; the start of the call that is picked is found when it is
-// picked.  Otherwise: a call is scored again, on every instance, if its instance is the one that changed.
+// was there takes the minimum of its row again (start + the call's decode time on the instance, the sum its
+// finish was when the pair was scored); the start of the call that is picked is read from its row.  Otherwise: a call is scored again, on every instance, if its instance is the one that changed.
 // Both ways give the same plan: the same functions on the same timelines, the same (finish, instance) rule.
 __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs a, int keep_all)
 {
@@ -849,7 +826,6 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     const DGreedyLds lay(a.stride, a.D, a.Q);
     TlScratch w = hx_carve_scratch(smem, lay.ne);
     int2 *s_tl = (int2 *)(smem + lay.off_tl());
-    short *s_src = (short *)(smem + lay.off_src());
     int *s_n = (int *)(smem + lay.off_inst());
     int *s_cnt = s_n + lay.D;
     int *s_cap = s_cnt + lay.D;
@@ -870,7 +846,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     float *s_redv = (float *)(smem + lay.off_red());
     int *s_redi = (int *)(s_redv + DG_WAVES);
     int *s_pick = s_redi + DG_WAVES;
-    float *s_mat = (float *)(smem + lay.off_mat());       // [lay.D][lay.Q] finish of call c on instance d, +inf: none (keep_all)
+    float *s_mat = (float *)(smem + lay.off_mat());       // [lay.D][lay.Q] start of call c on instance d, +inf: none (keep_all)
 
     const int tid = threadIdx.x;
     const int lane = tid & (HX_WAVE - 1);
@@ -896,7 +872,7 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
     __syncthreads();
     for (int d = 0; d < a.D; ++d) {
         const size_t at = (size_t)d * a.stride;
-        Tl tl{s_tl + (size_t)d * lay.nt, s_src + (size_t)d * lay.ne};
+        Tl tl{s_tl + (size_t)d * lay.nt};
         hx_build_timeline<false>(s_cnt[d], a.iv_start + at, a.iv_end + at, a.iv_tok + at, w, tl, &s_n[d], a.status);
     }
 
@@ -915,11 +891,11 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                 HxDecF x;
                 x.wait = 0.0f; x.c1 = s_c1[dd]; x.c2 = s_c2[dd]; x.kB = s_kB[dd];
                 const HxDecodeCand q = hx_decode_candidate(a.m, L, O, lk, dd, a.D, x, s_cap[dd], a.status);
-                const HxSlot s = hx_earliest_start(s_tl + (size_t)dd * lay.nt, s_src + (size_t)dd * lay.ne, s_n[dd],
+                const HxSlot s = hx_earliest_start(s_tl + (size_t)dd * lay.nt, s_n[dd],
                                                    q.thr, q.T, in && q.legal);
                 const float v = s.S + q.T;
-                if (keep_all && in) s_mat[(size_t)d * lay.Q + c] = s.src >= 0 ? v : INFINITY;
-                if (in && s.src >= 0 && v < bv) { bv = v; bS = s.S; bd = d; }
+                if (keep_all && in) s_mat[(size_t)d * lay.Q + c] = s.found ? s.S : INFINITY;
+                if (in && s.found && v < bv) { bv = v; bS = s.S; bd = d; }
             }
             const float best = hx_wave_min(bv);
             const int best_d = hx_wave_min(bv == best && best < INFINITY ? bd : INT_MAX);
@@ -955,13 +931,8 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         }
         if (tid == 0) {
             const int c = ri, d = s_bd[c];
-            if (keep_all && k > 0 && d >= 0) {
-                // its best may have moved since its start was last written: the start on the instance it has now
-                HxDecF x;
-                x.wait = 0.0f; x.c1 = s_c1[d]; x.c2 = s_c2[d]; x.kB = s_kB[d];
-                const HxDecodeCand q = hx_decode_candidate(a.m, s_L[c], s_O[c], -1, d, a.D, x, s_cap[d], a.status);
-                s_bs[c] = hx_earliest_start(s_tl + (size_t)d * lay.nt, s_src + (size_t)d * lay.ne, s_n[d], q.thr, q.T, true).S;
-            }
+            // its best may have moved since its start was last written: the start on the instance it has now
+            if (keep_all && d >= 0) s_bs[c] = s_mat[(size_t)d * lay.Q + c];
             a.best_d[c] = d; a.best_start[c] = s_bs[c]; a.best_cost[c] = s_bc[c]; hx_store_bits(a.ratio, c, __float_as_uint(s_ratio[c])); a.rank[c] = k;
             s_flags[c] = 0;
             int changed = -1;
@@ -976,16 +947,15 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                     a.iv_tok[at] = need > (long long)INT_MAX ? INT_MAX : (int)need;
                     s_cnt[d] += 1;
                     changed = d;
-                    __threadfence();
                     // The usual case -- the interval holds something, starts now or later, ends at a finite time, and
                     // the timeline has at most one entry per thread -- is inserted into the timeline below;
                     // anything else has the timeline built again from the instance's intervals.
                     const float S = s_bs[c], E = s_bc[c];
                     s_pick[1] = (S >= 0.0f && S < E && E < INFINITY && need > 0 && s_n[d] <= DG_THREADS) ? 1 : 0;
+                    if (!s_pick[1]) __threadfence();                 // the other threads are about to read the interval from memory
                     s_pick[2] = s_n[d]; s_pick[3] = s_n[d];          // entries before S, before E: all, unless an entry says otherwise
                     s_pick[4] = __float_as_int(S > 0.0f ? S : 0.0f); s_pick[5] = __float_as_int(E);
                     s_pick[6] = need > (long long)INT_MAX ? INT_MAX : (int)need;
-                    s_pick[7] = s_cnt[d];                            // 1 + the interval's index
                 }
             }
             s_pick[0] = changed;
@@ -995,19 +965,17 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
         const int pd = s_pick[0];
         if (pd >= 0) {
             const size_t at = (size_t)pd * a.stride;
-            Tl tl{s_tl + (size_t)pd * lay.nt, s_src + (size_t)pd * lay.ne};
+            Tl tl{s_tl + (size_t)pd * lay.nt};
             if (s_pick[1]) {
                 // The compact timeline is a function of the instance's events, so adding the two events of the new
                 // interval (S, E, tok) to it gives what building it again would: entries from S up to E hold tok
                 // more; S and E become entries of their own unless the timeline already has an entry at that time
-                // (S: the occupancy before it plus tok; E: the occupancy that stood before E); the entry at E is
-                // the end of the new interval (of all events at one time the end with the highest index counts).
+                // (S: the occupancy before it plus tok; E: the occupancy that stood before E).
                 const int n = s_n[pd];
                 const float S = __int_as_float(s_pick[4]), E = __int_as_float(s_pick[5]);
                 const int tok = s_pick[6];
                 const bool in = tid < n;
                 const int2 me = in ? tl.e[tid] : make_int2(0x7f800000, 0);
-                const short my_src = in ? tl.src[tid] : (short)0;
                 const float t = __int_as_float(me.x);
                 const float before = (in && tid > 0) ? __int_as_float(tl.e[tid - 1].x) : -1.0f;
                 if (in && t >= S && before < S) s_pick[2] = tid;
@@ -1026,18 +994,15 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                     if (tid >= pos_s && tid < pos_e) occ += tok;
                     if (occ > (long long)INT_MAX) { hx_raise(a.status, HX_ERR_OVERFLOW); occ = INT_MAX; }
                     tl.e[at_new] = make_int2(me.x, (int)occ);
-                    tl.src[at_new] = (has_e && tid == pos_e) ? (short)s_pick[7] : my_src;
                 }
                 if (tid == 0 && !has_s) {
                     long long occ = (long long)occ_before_s + tok;
                     if (occ > (long long)INT_MAX) { hx_raise(a.status, HX_ERR_OVERFLOW); occ = INT_MAX; }
                     tl.e[pos_s] = make_int2(s_pick[4], (int)occ);
-                    tl.src[pos_s] = 0;
                 }
                 if (tid == HX_WAVE && !has_e) {
                     const int at_e = pos_e + (has_s ? 0 : 1);
                     tl.e[at_e] = make_int2(s_pick[5], occ_before_e);
-                    tl.src[at_e] = (short)s_pick[7];
                 }
                 // the filler behind the entries reaches as far as a timeline of two more events may be read
                 for (int i = old_len + tid; i < new_len; i += DG_THREADS)
@@ -1060,15 +1025,31 @@ __global__ __launch_bounds__(DG_THREADS) void hx_decode_plan_kernel(DGreedyArgs 
                     const int L = live ? s_L[c] : 0, O = live ? s_O[c] : 0;
                     const int lk = live ? s_lk[c] : -1;
                     const HxDecodeCand q = hx_decode_candidate(a.m, L, O, live ? lk : -1, pd, a.D, x, cap, a.status);
-                    const HxSlot s = hx_earliest_start(tl.e, tl.src, n, q.thr, q.T, live && q.legal);
+                    const HxSlot s = hx_earliest_start(tl.e, n, q.thr, q.T, live && q.legal);
                     if (live) {
-                        s_mat[(size_t)pd * lay.Q + c] = s.src >= 0 ? s.S + q.T : INFINITY;
+                        s_mat[(size_t)pd * lay.Q + c] = s.found ? s.S : INFINITY;
                         if (s_bd[c] == pd) {
-                            // lowest instance among equal finishes: ascending, strictly smaller
+                            // lowest instance among equal finishes: ascending, strictly smaller (the finish is the kept
+                            // start plus the call's decode time there, the same sum as when the pair was scored)
+                            const HxCallF cf = hx_call_terms(a.m, L, O);
                             float bv = INFINITY;
                             int bd = -1;
-                            for (int d = 0; d < a.D; ++d) {
-                                const float v = s_mat[(size_t)d * lay.Q + c];
+                            int d = 0;
+                            for (; d + 8 <= a.D; d += 8) {                    // eight instances' reads in flight
+                                float S8[8], c1[8], c2[8], kB[8];
+#pragma unroll
+                                for (int u = 0; u < 8; ++u) {
+                                    S8[u] = s_mat[(size_t)(d + u) * lay.Q + c];
+                                    c1[u] = s_c1[d + u]; c2[u] = s_c2[d + u]; kB[u] = s_kB[d + u];
+                                }
+#pragma unroll
+                                for (int u = 0; u < 8; ++u) {
+                                    const float v = S8[u] + hx_decode_time(cf, c1[u], c2[u], kB[u]);
+                                    if (v < bv) { bv = v; bd = d + u; }
+                                }
+                            }
+                            for (; d < a.D; ++d) {
+                                const float v = s_mat[(size_t)d * lay.Q + c] + hx_decode_time(cf, s_c1[d], s_c2[d], s_kB[d]);
                                 if (v < bv) { bv = v; bd = d; }
                             }
                             s_bd[c] = bd;
@@ -1168,7 +1149,7 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
             if (ctx->d_dtl) { HX_HIP(ctx, hipFree(ctx->d_dtl)); ctx->d_dtl = nullptr; ctx->dtl_cap = 0; }
             // per entry: (time, occupancy) and (head time, head rank) 8 bytes each, sorted occupancy and stretch head 4
             // each, source 2; per instance two counts and a record of eight words
-            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 26 + (2 + 8) * (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
+            HX_HIP(ctx, hipMalloc((void **)&ctx->d_dtl, tl_need * 24 + (2 + 8) * (size_t)HX_MAX_INSTANCES * sizeof(int) + 64));
             ctx->dtl_cap = tl_need;
         }
         if (D > ctx->dtab_cap) {
@@ -1190,7 +1171,6 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         o.meta = (int *)p;      p += 8 * (size_t)HX_MAX_INSTANCES * sizeof(int);
         o.sorted = (int *)p;    p += cap * 4;
         o.seg = (int *)p;       p += cap * 4;
-        o.src = (short *)p;
         o.G = ctx->d_dtab;
     }
     int32_t *free_c = ctx->d_dpart;
@@ -1206,7 +1186,7 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         a.start = start; a.cost = cost; a.status = ctx->d_status;
         a.free_c = free_c; a.n_free = n_free; a.per = per;
         a.gd = gd; a.n_groups = n_groups; a.part_cost = part_cost; a.part_start = part_start; a.part_d = part_d;
-        const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)nt * 8) + hx_align16((size_t)ne * 2);
+        const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)nt * 8);
         hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, o, nt);
         const int n_lock = lock ? tiles : 0;
         hx_decode_score_kernel<<<n_lock + tiles * n_groups, DS_THREADS, 0, stream>>>(a, o, nt, n_lock);
