@@ -360,9 +360,10 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
         hx_wave_argmax(bv, bi);
         if (lane == 0) { s_redv[wave] = bv; s_redi[wave] = bi; }
         __syncthreads();
-        // (3) the first wavefront takes the best of the wavefronts' candidates (one per lane, the same rule), and its
-        // first lane records the pick and adds it to the simulated state
-        if (wave == 0) {
+        // (3) the first two wavefronts take the best of the wavefronts' candidates (one per lane, the same rule); the
+        // first lane of one records the pick and adds it to the prefill side of the simulated state, the first lane
+        // of the other to the decode side (two chains of dependent LDS reads side by side)
+        if (wave < 2) {
             bv = lane < GREEDY_WAVES ? s_redv[lane] : -INFINITY;
             bi = lane < GREEDY_WAVES ? s_redi[lane] : 0x7fffffff;
             hx_wave_argmax(bv, bi);
@@ -371,21 +372,35 @@ __global__ __launch_bounds__(GREEDY_THREADS) void hx_plan_greedy_kernel(GreedyAr
             const int c = bi, p = s_bp[c], d = s_bd[c];
             a.best_p[c] = p; a.best_d[c] = d; a.best_cost[c] = s_bc[c]; hx_store_bits(a.ratio, c, __float_as_uint(s_ratio[c])); a.rank[c] = k;
             s_flags[c] = 0;
-            s_pick[0] = c; s_pick[1] = p; s_pick[2] = d; s_pick[3] = 0;
+            s_pick[0] = c; s_pick[1] = p; s_pick[2] = d;
             s_pick[4] = 0;                                  // the next step's list starts empty
             if (p >= 0) {
-                const int L = s_L[c], O = s_O[c];
-                long long bl = (long long)s_backlog[p] + L, qd = (long long)s_qd[d] + O, us = (long long)s_used[d] + L + O;
-                if (L < 0 || O < 0) { hx_raise(a.status, HX_ERR_INDEX); bl = s_backlog[p]; qd = s_qd[d]; us = s_used[d]; }
-                if (bl > 2147483647LL || qd > 2147483647LL || us > 2147483647LL) {
-                    hx_raise(a.status, HX_ERR_OVERFLOW);
-                    bl = min(bl, 2147483647LL); qd = min(qd, 2147483647LL); us = min(us, 2147483647LL);
-                }
-                s_backlog[p] = (int)bl; s_qd[d] = (int)qd; s_used[d] = (int)us;
-                const long long nb = (us + a.tokens_per_seq - 1) / a.tokens_per_seq;
-                s_batch[d] = (int)(nb > a.max_batch ? a.max_batch : nb);
-                // the derived tables of the two instances, by the functions the per-round prepare uses
+                const int L = s_L[c];
+                long long bl = (long long)s_backlog[p] + L;
+                if (L < 0 || s_O[c] < 0) bl = s_backlog[p];            // raised by the other lane
+                if (bl > 2147483647LL) { hx_raise(a.status, HX_ERR_OVERFLOW); bl = 2147483647LL; }
+                s_backlog[p] = (int)bl;
+                // the derived table entry of the prefill instance, by the function the per-round prepare uses
                 s_pw[p] = hx_prefill_wait(a.m, s_backlog[p], s_pinvF[p]);
+            }
+        }
+        if (tid == HX_WAVE) {
+            const int c = bi, p = s_bp[c], d = s_bd[c];
+            s_pick[3] = 0;
+            if (p >= 0) {
+                const int L = s_L[c], O = s_O[c];
+                long long qd = (long long)s_qd[d] + O, us = (long long)s_used[d] + L + O;
+                if (L < 0 || O < 0) { hx_raise(a.status, HX_ERR_INDEX); qd = s_qd[d]; us = s_used[d]; }
+                if (qd > 2147483647LL || us > 2147483647LL) {
+                    hx_raise(a.status, HX_ERR_OVERFLOW);
+                    qd = min(qd, 2147483647LL); us = min(us, 2147483647LL);
+                }
+                s_qd[d] = (int)qd; s_used[d] = (int)us;
+                // us >= 0 and tokens_per_seq are below 2^31, their sum fits 32 unsigned bits: no 64-bit division
+                const long long nb = us >= 0 ? (long long)(((unsigned)us + (unsigned)a.tokens_per_seq - 1u) / (unsigned)a.tokens_per_seq)
+                                             : (us + a.tokens_per_seq - 1) / a.tokens_per_seq;
+                s_batch[d] = (int)(nb > a.max_batch ? a.max_batch : nb);
+                // the derived table entry of the decode instance, by the function the per-round prepare uses
                 const HxDecF x = hx_decode_terms(a.m, s_used[d], s_batch[d], s_qd[d], s_dinvF[d], s_dinvB[d]);
                 const int e = s_pos[d];
                 const long long fr = (long long)s_cap[d] - us;
