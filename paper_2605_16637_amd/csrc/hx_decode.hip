@@ -65,6 +65,18 @@ template <bool COHERENT, typename T> __device__ __forceinline__ T hx_ld(const T 
     return *p;
 }
 
+// Counting against all of n keys, one key per group of `parts` neighbouring lanes: 4 or 2 lanes per key where the
+// workgroup has that many threads to spare (a power of two, so a group lies inside a quad of lanes).
+__device__ __forceinline__ int hx_count_parts(int n, int nthreads) { return 4 * n <= nthreads ? 4 : (2 * n <= nthreads ? 2 : 1); }
+
+// the sum over the lanes of a group (lane moves inside the quad; every lane of the group is active)
+__device__ __forceinline__ int hx_parts_sum(int r, int parts)
+{
+    if (parts >= 2) r += __builtin_amdgcn_update_dpp(0, r, 0xB1, 0xf, 0xf, false);      // quad_perm [1,0,3,2]
+    if (parts >= 4) r += __builtin_amdgcn_update_dpp(0, r, 0x4E, 0xf, 0xf, false);      // quad_perm [2,3,0,1]
+    return r;
+}
+
 // All threads of the workgroup call this.  cnt entries of one instance -> compact timeline in
 // `out`, its length in *n_out (LDS).  Ends the call with a barrier.
 template <bool COHERENT>
@@ -93,21 +105,28 @@ __device__ void hx_build_timeline(int cnt, const float *st, const float *en, con
         w.delta[i] = delta;
     }
     __syncthreads();
-    // position of every event = number of smaller keys (keys are unique)
-    for (int i = tid; i < n_ev; i += nthreads) {
+    // position of every event = number of smaller keys (keys are unique); with threads to spare, the 2 or 4
+    // neighbouring lanes of an event count a part of the keys each
+    const int parts = hx_count_parts(n_ev, nthreads);
+    const int share = ((n_ev + parts - 1) / parts + 7) & ~7;
+    for (int i = tid / parts; i < n_ev; i += nthreads / parts) {
         const u64 ki = w.key[i];
+        const int j_lo = min((tid & (parts - 1)) * share, n_ev), j_hi = min(j_lo + share, n_ev);
         int r = 0;
-        int j = 0;
-        for (; j + 8 <= n_ev; j += 8) {                   // eight independent reads in flight
+        int j = j_lo;
+        for (; j + 8 <= j_hi; j += 8) {                   // eight independent reads in flight
             u64 kk[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) kk[u] = w.key[j + u];
 #pragma unroll
             for (int u = 0; u < 8; ++u) r += kk[u] < ki;
         }
-        for (; j < n_ev; ++j) r += w.key[j] < ki;
-        w.ts[r] = __uint_as_float((unsigned)(ki >> 32));
-        w.ds[r] = w.delta[i];
+        for (; j < j_hi; ++j) r += w.key[j] < ki;
+        r = hx_parts_sum(r, parts);
+        if ((tid & (parts - 1)) == 0) {
+            w.ts[r] = __uint_as_float((unsigned)(ki >> 32));
+            w.ds[r] = w.delta[i];
+        }
     }
     __syncthreads();
     // one wavefront: running occupancy, and one entry per distinct time (the last event of that time)
@@ -259,7 +278,8 @@ struct TlOut {
 // Workgroup d: everything the scoring kernel needs of instance d -- its timeline, built in LDS; the timeline's
 // stretches of non-increasing occupancy; where that is small enough, the first-room table; a record of the
 // instance's sizes and decode terms -- and the free calls among the d-th slice of the queue, in order.
-__global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, TlOut o, int nt)
+constexpr int TL_THREADS = 512;
+__global__ __launch_bounds__(TL_THREADS) void hx_decode_timeline_kernel(DecodeArgs a, TlOut o, int nt)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_n, s_m;
@@ -286,10 +306,10 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
     // barrier waits for the stores before it, and there are several barriers to come.
 
     // This workgroup's slice of the queue: its free calls, in order.  A thread keeps the place of its call of
-    // the first 256 (few slices are longer) and writes it with the rest.
+    // the first 512 (few slices are longer) and writes it with the rest.
     int my_place = -1, n_free = 0;
     if (a.lock) {
-        __shared__ int s_wave_n[4];
+        __shared__ int s_wave_n[TL_THREADS / HX_WAVE];
         const int lane = tid & (HX_WAVE - 1), wave = tid >> 6;
         for (int base = c_lo; base < c_hi; base += blockDim.x) {
             const int c = base + tid;
@@ -310,7 +330,7 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
                 if (first) my_place = place;
                 else a.free_c[d * a.per + place] = c;
             }
-            n_free += s_wave_n[0] + s_wave_n[1] + s_wave_n[2] + s_wave_n[3];
+            for (int w2 = 0; w2 < TL_THREADS / HX_WAVE; ++w2) n_free += s_wave_n[w2];
             __syncthreads();
         }
     }
@@ -347,20 +367,26 @@ __global__ __launch_bounds__(256) void hx_decode_timeline_kernel(DecodeArgs a, T
     // order, the keys below (occupancy + 1, 0) its rank.
     int *rank = w.delta, *sorted = (int *)w.ts;
     if (table) {
-        for (int i = tid; i < n; i += blockDim.x) {
+        const int parts = hx_count_parts(n, TL_THREADS);
+        const int share = ((n + parts - 1) / parts + 7) & ~7;
+        for (int i = tid / parts; i < n; i += TL_THREADS / parts) {
             const u64 mine = w.key[i], above = ((mine >> 16) + 1) << 16;
+            const int j_lo = min((tid & (parts - 1)) * share, n), j_hi = min(j_lo + share, n);
             int place = 0, le = 0;
-            int j = 0;
-            for (; j + 8 <= n; j += 8) {                   // eight independent reads in flight
+            int j = j_lo;
+            for (; j + 8 <= j_hi; j += 8) {                // eight independent reads in flight
                 u64 other[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) other[u] = w.key[j + u];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) { place += other[u] < mine; le += other[u] < above; }
             }
-            for (; j < n; ++j) { const u64 other = w.key[j]; place += other < mine; le += other < above; }
-            rank[i] = le;
-            sorted[place] = (int)(mine >> 16);
+            for (; j < j_hi; ++j) { const u64 other = w.key[j]; place += other < mine; le += other < above; }
+            place = hx_parts_sum(place, parts); le = hx_parts_sum(le, parts);
+            if ((tid & (parts - 1)) == 0) {
+                rank[i] = le;
+                sorted[place] = (int)(mine >> 16);
+            }
         }
         __syncthreads();
     }
@@ -1187,7 +1213,7 @@ extern "C" int hx_decode_score(hx_ctx *ctx, const hx_model *model, const hx_call
         a.free_c = free_c; a.n_free = n_free; a.per = per;
         a.gd = gd; a.n_groups = n_groups; a.part_cost = part_cost; a.part_start = part_start; a.part_d = part_d;
         const size_t lds = hx_scratch_bytes(ne) + hx_align16((size_t)nt * 8);
-        hx_decode_timeline_kernel<<<D, 256, lds, stream>>>(a, o, nt);
+        hx_decode_timeline_kernel<<<D, TL_THREADS, lds, stream>>>(a, o, nt);
         const int n_lock = lock ? tiles : 0;
         hx_decode_score_kernel<<<n_lock + tiles * n_groups, DS_THREADS, 0, stream>>>(a, o, nt, n_lock);
     }
